@@ -1,0 +1,108 @@
+/*
+ * fwa.h -- C ABI of the Flash Window Attention library for AMD MI355X (gfx950).
+ *
+ * The library computes fused, batched short-sequence attention over
+ * window-partitioned tensors (paper Section 2.1, eq. 1-4):
+ *
+ *     O[n, :, head h] = softmax(scale * Q_nh K_nh^T + B[h] + M[n mod nW]) V_nh
+ *
+ * with the whole L x L score/probability tile kept on chip and Q, K, V, O
+ * crossing device memory exactly once (paper Algorithm 1), and its backward
+ * (paper Algorithm 2) which recomputes P on chip and needs nothing saved from
+ * the forward.  The paper's equations carry no scale, bias or mask; they are
+ * additive extensions: scale multiplies QK^T before B and M are added.
+ *
+ * Conventions shared by every entry point
+ * ---------------------------------------
+ *  - Every pointer is a DEVICE pointer owned by the caller.  The library
+ *    never allocates, frees or synchronises; it enqueues kernels on `stream`
+ *    (a hipStream_t passed as void*; NULL = the default stream) and returns.
+ *  - Tensors are contiguous, row-major.  Q, K, V, O, dO, dQ, dK, dV are
+ *    [N, L, C]; head h owns channels [h*d, (h+1)*d) with d = C / heads.
+ *    Supported: d == 32, 1 <= L <= 256, N >= 0 (N == 0 is a no-op).
+ *  - dtype is FWA_F32 (fp32 data, fp32 arithmetic) or FWA_BF16 (bf16 data,
+ *    bf16 matrix-core products with fp32 accumulation, fp32 softmax, one final
+ *    round-to-nearest-even to bf16).
+ *  - bias, mask, dbias are always fp32.
+ *  - Base pointers must be 16-byte aligned.  Outputs must not alias inputs.
+ *  - The return value is FWA_OK or an error code; on error nothing has been
+ *    launched.  No global state; calls are thread-safe.
+ */
+#ifndef FWA_H
+#define FWA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum { FWA_F32 = 0, FWA_BF16 = 1 };
+
+enum {
+    FWA_OK = 0,
+    FWA_ERR_NULL = 1,        /* a required pointer is NULL                          */
+    FWA_ERR_SHAPE = 2,       /* negative N, L < 1, C % heads != 0, N % nW != 0, ... */
+    FWA_ERR_UNSUPPORTED = 3, /* head dim != 32, L > 256, unknown dtype              */
+    FWA_ERR_ALIGN = 4,       /* a base pointer is not 16-byte aligned               */
+    FWA_ERR_WORKSPACE = 5,   /* workspace missing or smaller than required          */
+    FWA_ERR_LAUNCH = 6       /* the HIP runtime refused the launch                  */
+};
+
+/*
+ * Forward pass (paper Algorithm 1; eq. 2-4).
+ *   q, k, v : in,  [N, L, C], dtype
+ *   o       : out, [N, L, C], dtype, fully overwritten
+ *   bias    : NULL, or in [heads, L, L] fp32 (already gathered per token pair)
+ *   mask    : NULL, or in [nW, L, L] fp32, added to the scores of window n as
+ *             mask[n % nW]; requires nW >= 1 and N % nW == 0.  nW is ignored
+ *             when mask is NULL.
+ */
+int fwa_forward(const void* q, const void* k, const void* v, void* o,
+                int64_t N, int L, int C, int heads, float scale,
+                const float* bias, const float* mask, int nW,
+                int dtype, void* stream);
+
+/*
+ * Backward pass (paper Algorithm 2).  Inputs are Q, K, V and dO only.
+ *   d_o        : in,  [N, L, C], dtype
+ *   dq, dk, dv : out, [N, L, C], dtype, fully overwritten
+ *   dbias      : NULL, or out [heads, L, L] fp32 = sum over all N windows of
+ *                dS; overwritten, not accumulated.  The mask gets no gradient.
+ *   workspace  : device scratch of at least fwa_backward_workspace_bytes(...)
+ *                bytes, 16-byte aligned; may be NULL when that size is 0.
+ *                Contents on entry are ignored and undefined on exit.
+ * Results are bit-reproducible from run to run for fixed arguments.
+ */
+int fwa_backward(const void* q, const void* k, const void* v, const void* d_o,
+                 void* dq, void* dk, void* dv, float* dbias,
+                 int64_t N, int L, int C, int heads, float scale,
+                 const float* bias, const float* mask, int nW,
+                 int dtype, void* workspace, size_t workspace_bytes, void* stream);
+
+/* Bytes of workspace fwa_backward needs for these arguments (0 if none).
+ * Returns 0 for arguments fwa_backward would reject. */
+size_t fwa_backward_workspace_bytes(int64_t N, int L, int C, int heads, int dtype, int want_dbias);
+
+/*
+ * Relative-position bias helpers for k x k windows (L = k*k).  Token i sits
+ * at (i / k, i % k); pair (i, j) maps to table column
+ * (y_i - y_j + k - 1) * (2k - 1) + (x_i - x_j + k - 1).  The paper only says
+ * its baseline follows Swin Transformer; this is that published indexing.
+ *   fwa_bias_gather : table [heads, (2k-1)^2] -> bias [heads, L, L]
+ *   fwa_bias_scatter: dbias [heads, L, L] -> dtable [heads, (2k-1)^2]
+ *                     (adjoint of the gather; overwritten; fixed summation
+ *                     order, bit-reproducible)
+ * All fp32 device pointers.  Requires heads >= 1 and 1 <= k <= 16.
+ */
+int fwa_bias_gather(const float* table, float* bias, int heads, int k, void* stream);
+int fwa_bias_scatter(const float* dbias, float* dtable, int heads, int k, void* stream);
+
+/* Static, NUL-terminated description of an error code. */
+const char* fwa_status_string(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FWA_H */

@@ -1,0 +1,190 @@
+"""ctypes binding of the C-ABI library declared in ``include/fwa.h``.
+
+Argument marshalling only: every step of the attention path runs in the HIP
+kernels of ``libfwa.so``.  torch supplies device memory and the stream.  There
+is no CPU fallback: when the library has not been built, or a call is made
+without a GPU tensor, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+FWA_F32 = 0
+FWA_BF16 = 1
+
+FWA_OK = 0
+FWA_ERR_NULL = 1
+FWA_ERR_SHAPE = 2
+FWA_ERR_UNSUPPORTED = 3
+FWA_ERR_ALIGN = 4
+FWA_ERR_WORKSPACE = 5
+FWA_ERR_LAUNCH = 6
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libfwa.so")
+_lib = None
+
+EXPORTS = ("fwa_forward", "fwa_backward", "fwa_backward_workspace_bytes", "fwa_bias_gather",
+           "fwa_bias_scatter", "fwa_status_string")
+
+
+class FwaError(RuntimeError):
+    def __init__(self, code: int, what: str):
+        super().__init__(f"{what}: {fwa_status_string(code)} (code {code})")
+        self.code = code
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Load ``libfwa.so`` (built in-tree by ``paper_2501_06480_amd.build``)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise RuntimeError(
+            f"{_LIB_PATH} is missing: build it with `python -m paper_2501_06480_amd.build` "
+            "(hipcc, gfx950). There is no fallback path.")
+    lib = ctypes.CDLL(_LIB_PATH)
+    vp, i64, ci, cf, sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_float, ctypes.c_size_t
+    lib.fwa_forward.restype = ci
+    lib.fwa_forward.argtypes = [vp, vp, vp, vp, i64, ci, ci, ci, cf, vp, vp, ci, ci, vp]
+    lib.fwa_backward.restype = ci
+    lib.fwa_backward.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i64, ci, ci, ci, cf, vp, vp, ci, ci,
+                                 vp, sz, vp]
+    lib.fwa_backward_workspace_bytes.restype = sz
+    lib.fwa_backward_workspace_bytes.argtypes = [i64, ci, ci, ci, ci, ci]
+    lib.fwa_bias_gather.restype = ci
+    lib.fwa_bias_gather.argtypes = [vp, vp, ci, ci, vp]
+    lib.fwa_bias_scatter.restype = ci
+    lib.fwa_bias_scatter.argtypes = [vp, vp, ci, ci, vp]
+    lib.fwa_status_string.restype = ctypes.c_char_p
+    lib.fwa_status_string.argtypes = [ci]
+    _lib = lib
+    return lib
+
+
+def fwa_status_string(code: int) -> str:
+    return load_library().fwa_status_string(int(code)).decode()
+
+
+def _dtype_code(t) -> int:
+    import torch
+    if t.dtype == torch.float32:
+        return FWA_F32
+    if t.dtype == torch.bfloat16:
+        return FWA_BF16
+    raise TypeError(f"unsupported tensor dtype {t.dtype}")
+
+
+def _dev_ptr(t, name: str, like=None, f32: bool = False) -> Optional[int]:
+    import torch
+    if t is None:
+        return None
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise TypeError(f"{name} must be a GPU tensor (there is no CPU path)")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    if f32 and t.dtype != torch.float32:
+        raise TypeError(f"{name} must be float32")
+    if like is not None and (t.shape != like.shape or t.dtype != like.dtype or t.device != like.device):
+        raise ValueError(f"{name} must match q in shape, dtype and device")
+    return t.data_ptr()
+
+
+def _stream_handle(stream, device) -> int:
+    import torch
+    if stream is None:
+        stream = torch.cuda.current_stream(device)
+    return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+
+
+def fwa_forward(q, k, v, heads: int, scale: float, bias=None, mask=None, out=None, stream=None):
+    """O = softmax(scale*QK^T + B + M) V (paper Algorithm 1).  Tensors are [N, L, C] on the GPU."""
+    import torch
+    lib = load_library()
+    N, L, C = q.shape
+    o = torch.empty_like(q) if out is None else out
+    nW = 0 if mask is None else int(mask.shape[0])
+    if bias is not None and tuple(bias.shape) != (heads, L, L):
+        raise ValueError("bias must be [heads, L, L]")
+    if mask is not None and tuple(mask.shape) != (nW, L, L):
+        raise ValueError("mask must be [nW, L, L]")
+    with torch.cuda.device(q.device):
+        rc = lib.fwa_forward(_dev_ptr(q, "q"), _dev_ptr(k, "k", q), _dev_ptr(v, "v", q),
+                             _dev_ptr(o, "out", q), N, L, C, int(heads), float(scale),
+                             _dev_ptr(bias, "bias", f32=True), _dev_ptr(mask, "mask", f32=True), nW,
+                             _dtype_code(q), _stream_handle(stream, q.device))
+    if rc != FWA_OK:
+        raise FwaError(rc, "fwa_forward")
+    return o
+
+
+def fwa_backward_workspace_bytes(N: int, L: int, C: int, heads: int, dtype: int, want_dbias: bool) -> int:
+    return int(load_library().fwa_backward_workspace_bytes(N, L, C, heads, dtype, int(bool(want_dbias))))
+
+
+def fwa_backward(q, k, v, d_o, heads: int, scale: float, bias=None, mask=None, want_dbias: bool = False,
+                 workspace=None, stream=None):
+    """(dQ, dK, dV, dBias) from Q, K, V, dO (paper Algorithm 2).  dBias is None unless asked for."""
+    import torch
+    lib = load_library()
+    N, L, C = q.shape
+    dq, dk, dv = torch.empty_like(q), torch.empty_like(q), torch.empty_like(q)
+    dbias = torch.empty((heads, L, L), dtype=torch.float32, device=q.device) if want_dbias else None
+    nW = 0 if mask is None else int(mask.shape[0])
+    if bias is not None and tuple(bias.shape) != (heads, L, L):
+        raise ValueError("bias must be [heads, L, L]")
+    if mask is not None and tuple(mask.shape) != (nW, L, L):
+        raise ValueError("mask must be [nW, L, L]")
+    need = fwa_backward_workspace_bytes(N, L, C, heads, _dtype_code(q), want_dbias)
+    if workspace is None and need:
+        workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    with torch.cuda.device(q.device):
+        rc = lib.fwa_backward(_dev_ptr(q, "q"), _dev_ptr(k, "k", q), _dev_ptr(v, "v", q),
+                              _dev_ptr(d_o, "d_o", q), dq.data_ptr(), dk.data_ptr(), dv.data_ptr(),
+                              None if dbias is None else dbias.data_ptr(), N, L, C, int(heads),
+                              float(scale), _dev_ptr(bias, "bias", f32=True),
+                              _dev_ptr(mask, "mask", f32=True), nW, _dtype_code(q),
+                              None if workspace is None else workspace.data_ptr(), ws_bytes,
+                              _stream_handle(stream, q.device))
+    if rc != FWA_OK:
+        raise FwaError(rc, "fwa_backward")
+    return dq, dk, dv, dbias
+
+
+def fwa_bias_gather(table, k: int, stream=None):
+    """[heads, (2k-1)^2] fp32 table -> [heads, k*k, k*k] fp32 bias, on the GPU."""
+    import torch
+    lib = load_library()
+    heads = int(table.shape[0])
+    if tuple(table.shape) != (heads, (2 * k - 1) ** 2):
+        raise ValueError("table must be [heads, (2k-1)^2]")
+    bias = torch.empty((heads, k * k, k * k), dtype=torch.float32, device=table.device)
+    with torch.cuda.device(table.device):
+        rc = lib.fwa_bias_gather(_dev_ptr(table, "table", f32=True), bias.data_ptr(), heads, int(k),
+                                 _stream_handle(stream, table.device))
+    if rc != FWA_OK:
+        raise FwaError(rc, "fwa_bias_gather")
+    return bias
+
+
+def fwa_bias_scatter(dbias, k: int, stream=None):
+    """[heads, k*k, k*k] fp32 bias gradient -> [heads, (2k-1)^2] table gradient."""
+    import torch
+    lib = load_library()
+    heads = int(dbias.shape[0])
+    if tuple(dbias.shape) != (heads, k * k, k * k):
+        raise ValueError("dbias must be [heads, k*k, k*k]")
+    dtable = torch.empty((heads, (2 * k - 1) ** 2), dtype=torch.float32, device=dbias.device)
+    with torch.cuda.device(dbias.device):
+        rc = lib.fwa_bias_scatter(_dev_ptr(dbias, "dbias", f32=True), dtable.data_ptr(), heads, int(k),
+                                  _stream_handle(stream, dbias.device))
+    if rc != FWA_OK:
+        raise FwaError(rc, "fwa_bias_scatter")
+    return dtable
