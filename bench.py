@@ -1,0 +1,139 @@
+#!/usr/bin/env python3
+"""Benchmark of the Flash Window Attention forward on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W]
+
+A step is one pass of the whole forward hot path (load Q/K/V, scores, softmax,
+PV, store O -- one kernel launch through the C ABI) over one Swin-T stage-1
+batch: 128 images of 56x56 tokens, 7x7 windows -> N = 8192 windows, L = 49,
+C = 96 = 3 heads x 32, bf16 data, fp32 accumulation, synthetic N(0,1) inputs
+already resident in HBM.  The step cycles through several distinct Q/K/V/O
+buffer sets whose total size exceeds twice the 256 MB last-level cache, so every
+step streams from HBM.
+
+Prints ONE JSON line: whole-job window-heads/s, plus the roofline object of the
+forward kernel (HIP-event time per launch against the 8 TB/s HBM peak) and the
+fp64 CPU oracle timed on this machine's host cores as a baseline.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E bandwidth
+LLC_BYTES = 256 * 2 ** 20       # Infinity Cache
+# HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE for this
+# workload (see profiles/); None until measured.
+MEASURED_TRAFFIC_BYTES = None
+
+
+def ensure_built():
+    from paper_2501_06480_amd import binding
+    if not os.path.exists(binding.library_path()):
+        from paper_2501_06480_amd import build
+        build.build(verbose=False)
+
+
+def cpu_baseline(workload):
+    """The fp64 oracle, as it stands, on the host cores, over the same batch shape."""
+    import numpy as np
+    import torch
+    import oracle
+    g = torch.Generator().manual_seed(workload.seed)
+    q, k, v = (torch.randn((workload.N, workload.L, workload.C), generator=g).bfloat16().double().numpy()
+               for _ in range(3))
+    oracle.load()
+    t0 = time.perf_counter()
+    o = oracle.forward(q, k, v, workload.heads, workload.scale)
+    dt = time.perf_counter() - t0
+    assert np.isfinite(o).all()
+    return {"value": workload.N * workload.heads / dt, "unit": "window-heads/s",
+            "cores": oracle.threads_used(), "kind": "oracle",
+            "sample": f"whole batch once: {workload.N} windows x {workload.heads} heads, fp64, {dt:.2f} s wall"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=2000)
+    ap.add_argument("--warmup", type=int, default=200)
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (profiling runs)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (the workload is data-parallel "
+              "over windows; see DESIGN.md). Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    ensure_built()
+    import paper_2501_06480_amd as fwa
+    from paper_2501_06480_amd import synth
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU: there is no CPU path.", file=sys.stderr)
+        sys.exit(3)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    w = synth.config2()
+    shape = (w.N, w.L, w.C)
+    set_bytes = 4 * w.N * w.L * w.C * 2
+    nsets = max(2, -(-2 * LLC_BYTES // set_bytes) + 1)
+    g = torch.Generator(device=dev).manual_seed(w.seed)
+    sets = []
+    for _ in range(nsets):
+        q, k, v = (torch.randn(shape, device=dev, dtype=torch.float32, generator=g).to(torch.bfloat16)
+                   for _ in range(3))
+        sets.append((q, k, v, torch.empty(shape, device=dev, dtype=torch.bfloat16)))
+
+    def step(i):
+        q, k, v, o = sets[i % nsets]
+        fwa.fwa_forward(q, k, v, w.heads, w.scale, out=o)
+
+    for i in range(args.warmup):
+        step(i)
+    starts = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
+    stops = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        starts[i].record()
+        step(i)
+        stops[i].record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    kernel_ms = sum(a.elapsed_time(b) for a, b in zip(starts, stops)) / args.steps
+    assert all(torch.isfinite(s[3].float()).all().item() for s in sets)
+
+    wh = w.N * w.heads
+    algo_bytes = 4 * w.L * 32 * 2 * wh           # Q, K, V in and O out, once each, bf16
+    achieved = algo_bytes / (kernel_ms * 1e-3) / 1e9
+    line = {
+        "metric": "fwd window-heads/sec, Swin-T stage-1 shapes bf16",
+        "value": wh * args.steps / wall,
+        "unit": "window-heads/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": wall / args.steps * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "swin_t_stage1_fwd: N=8192 windows, L=49, C=96, heads=3, head_dim=32, "
+                               "no bias/mask, batch 128 of 56x56", "buffer_sets": nsets,
+                   "window_heads_per_step": wh},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBPS, "traffic": MEASURED_TRAFFIC_BYTES,
+                     "kernel": "fwd_bf16_kernel<4,false>", "kernel_ms": kernel_ms,
+                     "algorithmic_bytes_per_launch": algo_bytes},
+    }
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(w)
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

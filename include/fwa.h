@@ -47,7 +47,8 @@ enum {
     FWA_ERR_UNSUPPORTED = 3, /* head dim != 32, L > 256, unknown dtype              */
     FWA_ERR_ALIGN = 4,       /* a base pointer is not 16-byte aligned               */
     FWA_ERR_WORKSPACE = 5,   /* workspace missing or smaller than required          */
-    FWA_ERR_LAUNCH = 6       /* the HIP runtime refused the launch                  */
+    FWA_ERR_LAUNCH = 6,      /* the HIP runtime refused the launch                  */
+    FWA_ERR_ALIAS = 7        /* an output pointer equals another argument           */
 };
 
 /*

@@ -21,6 +21,7 @@ FWA_ERR_UNSUPPORTED = 3
 FWA_ERR_ALIGN = 4
 FWA_ERR_WORKSPACE = 5
 FWA_ERR_LAUNCH = 6
+FWA_ERR_ALIAS = 7
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libfwa.so")
@@ -114,11 +115,11 @@ def fwa_forward(q, k, v, heads: int, scale: float, bias=None, mask=None, out=Non
         raise ValueError("bias must be [heads, L, L]")
     if mask is not None and tuple(mask.shape) != (nW, L, L):
         raise ValueError("mask must be [nW, L, L]")
+    args = (_dev_ptr(q, "q"), _dev_ptr(k, "k", q), _dev_ptr(v, "v", q), _dev_ptr(o, "out", q), N, L, C,
+            int(heads), float(scale), _dev_ptr(bias, "bias", f32=True), _dev_ptr(mask, "mask", f32=True), nW,
+            _dtype_code(q), _stream_handle(stream, q.device))
     with torch.cuda.device(q.device):
-        rc = lib.fwa_forward(_dev_ptr(q, "q"), _dev_ptr(k, "k", q), _dev_ptr(v, "v", q),
-                             _dev_ptr(o, "out", q), N, L, C, int(heads), float(scale),
-                             _dev_ptr(bias, "bias", f32=True), _dev_ptr(mask, "mask", f32=True), nW,
-                             _dtype_code(q), _stream_handle(stream, q.device))
+        rc = lib.fwa_forward(*args)
     if rc != FWA_OK:
         raise FwaError(rc, "fwa_forward")
     return o
@@ -134,6 +135,7 @@ def fwa_backward(q, k, v, d_o, heads: int, scale: float, bias=None, mask=None, w
     import torch
     lib = load_library()
     N, L, C = q.shape
+    ptrs = (_dev_ptr(q, "q"), _dev_ptr(k, "k", q), _dev_ptr(v, "v", q), _dev_ptr(d_o, "d_o", q))
     dq, dk, dv = torch.empty_like(q), torch.empty_like(q), torch.empty_like(q)
     dbias = torch.empty((heads, L, L), dtype=torch.float32, device=q.device) if want_dbias else None
     nW = 0 if mask is None else int(mask.shape[0])
@@ -146,8 +148,7 @@ def fwa_backward(q, k, v, d_o, heads: int, scale: float, bias=None, mask=None, w
         workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     with torch.cuda.device(q.device):
-        rc = lib.fwa_backward(_dev_ptr(q, "q"), _dev_ptr(k, "k", q), _dev_ptr(v, "v", q),
-                              _dev_ptr(d_o, "d_o", q), dq.data_ptr(), dk.data_ptr(), dv.data_ptr(),
+        rc = lib.fwa_backward(*ptrs, dq.data_ptr(), dk.data_ptr(), dv.data_ptr(),
                               None if dbias is None else dbias.data_ptr(), N, L, C, int(heads),
                               float(scale), _dev_ptr(bias, "bias", f32=True),
                               _dev_ptr(mask, "mask", f32=True), nW, _dtype_code(q),
@@ -165,9 +166,10 @@ def fwa_bias_gather(table, k: int, stream=None):
     heads = int(table.shape[0])
     if tuple(table.shape) != (heads, (2 * k - 1) ** 2):
         raise ValueError("table must be [heads, (2k-1)^2]")
+    tp = _dev_ptr(table, "table", f32=True)
     bias = torch.empty((heads, k * k, k * k), dtype=torch.float32, device=table.device)
     with torch.cuda.device(table.device):
-        rc = lib.fwa_bias_gather(_dev_ptr(table, "table", f32=True), bias.data_ptr(), heads, int(k),
+        rc = lib.fwa_bias_gather(tp, bias.data_ptr(), heads, int(k),
                                  _stream_handle(stream, table.device))
     if rc != FWA_OK:
         raise FwaError(rc, "fwa_bias_gather")
@@ -181,9 +183,10 @@ def fwa_bias_scatter(dbias, k: int, stream=None):
     heads = int(dbias.shape[0])
     if tuple(dbias.shape) != (heads, k * k, k * k):
         raise ValueError("dbias must be [heads, k*k, k*k]")
+    dp = _dev_ptr(dbias, "dbias", f32=True)
     dtable = torch.empty((heads, (2 * k - 1) ** 2), dtype=torch.float32, device=dbias.device)
     with torch.cuda.device(dbias.device):
-        rc = lib.fwa_bias_scatter(_dev_ptr(dbias, "dbias", f32=True), dtable.data_ptr(), heads, int(k),
+        rc = lib.fwa_bias_scatter(dp, dtable.data_ptr(), heads, int(k),
                                   _stream_handle(stream, dbias.device))
     if rc != FWA_OK:
         raise FwaError(rc, "fwa_bias_scatter")

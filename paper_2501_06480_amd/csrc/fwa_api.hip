@@ -1,0 +1,133 @@
+// extern "C" entry points of libfwa: argument validation and dispatch.
+// Every check happens before any HIP call, so an error never launches work.
+#include "../../include/fwa.h"
+#include "fwa_internal.h"
+
+namespace {
+
+inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+
+// Shape checks shared by forward, backward and the workspace query.
+int check_shape(int64_t N, int L, int C, int heads, int dtype) {
+    if (N < 0 || L < 1 || C < 1 || heads < 1) return FWA_ERR_SHAPE;
+    if (C % heads != 0) return FWA_ERR_SHAPE;
+    if (dtype != FWA_F32 && dtype != FWA_BF16) return FWA_ERR_UNSUPPORTED;
+    if (C / heads != fwa::kHeadDim) return FWA_ERR_UNSUPPORTED;
+    if (L > fwa::kMaxL) return FWA_ERR_UNSUPPORTED;
+    // one launch: the number of wave tasks (at most 4 per window-head) must fit a 32-bit grid
+    if ((double)N * heads * 4.0 > 2.0e9) return FWA_ERR_UNSUPPORTED;
+    return FWA_OK;
+}
+
+int check_mask(int64_t N, const float* mask, int nW) {
+    if (mask == nullptr) return FWA_OK;
+    if (nW < 1 || N % nW != 0) return FWA_ERR_SHAPE;
+    return FWA_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* fwa_status_string(int code) {
+    switch (code) {
+        case FWA_OK: return "ok";
+        case FWA_ERR_NULL: return "a required pointer is NULL";
+        case FWA_ERR_SHAPE: return "inconsistent shape arguments";
+        case FWA_ERR_UNSUPPORTED: return "unsupported head dim, window length or dtype";
+        case FWA_ERR_ALIGN: return "a base pointer is not 16-byte aligned";
+        case FWA_ERR_WORKSPACE: return "workspace missing or too small";
+        case FWA_ERR_LAUNCH: return "the HIP runtime refused the launch";
+        case FWA_ERR_ALIAS: return "an output aliases another argument";
+        default: return "unknown status code";
+    }
+}
+
+int fwa_forward(const void* q, const void* k, const void* v, void* o, int64_t N, int L, int C, int heads,
+                float scale, const float* bias, const float* mask, int nW, int dtype, void* stream) {
+    int rc = check_shape(N, L, C, heads, dtype);
+    if (rc != FWA_OK) return rc;
+    rc = check_mask(N, mask, nW);
+    if (rc != FWA_OK) return rc;
+    if (N == 0) return FWA_OK;
+    if (!q || !k || !v || !o) return FWA_ERR_NULL;
+    if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(o) || misaligned(bias) || misaligned(mask))
+        return FWA_ERR_ALIGN;
+    if (o == q || o == k || o == v) return FWA_ERR_ALIAS;
+    fwa::FwdArgs a;
+    a.q = q; a.k = k; a.v = v; a.o = o;
+    a.bias = bias; a.mask = mask;
+    a.N = N; a.L = L; a.C = C; a.heads = heads; a.nW = mask ? nW : 1; a.scale = scale;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const hipError_t e = dtype == FWA_BF16 ? fwa::launch_forward_bf16(a, st) : fwa::launch_forward_f32(a, st);
+    return e == hipSuccess ? FWA_OK : FWA_ERR_LAUNCH;
+}
+
+size_t fwa_backward_workspace_bytes(int64_t N, int L, int C, int heads, int dtype, int want_dbias) {
+    if (check_shape(N, L, C, heads, dtype) != FWA_OK) return 0;
+    if (!want_dbias || N == 0) return 0;
+    return (size_t)fwa::backward_slots(N, heads) * heads * L * L * sizeof(float);
+}
+
+int fwa_backward(const void* q, const void* k, const void* v, const void* d_o, void* dq, void* dk, void* dv,
+                 float* dbias, int64_t N, int L, int C, int heads, float scale, const float* bias,
+                 const float* mask, int nW, int dtype, void* workspace, size_t workspace_bytes, void* stream) {
+    int rc = check_shape(N, L, C, heads, dtype);
+    if (rc != FWA_OK) return rc;
+    rc = check_mask(N, mask, nW);
+    if (rc != FWA_OK) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (N == 0) {
+        // the sum over zero windows: dbias is still "overwritten"
+        if (dbias) {
+            if (misaligned(dbias)) return FWA_ERR_ALIGN;
+            if (fwa::launch_zero_f32(dbias, (size_t)heads * L * L, st) != hipSuccess) return FWA_ERR_LAUNCH;
+        }
+        return FWA_OK;
+    }
+    if (!q || !k || !v || !d_o || !dq || !dk || !dv) return FWA_ERR_NULL;
+    if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(d_o) || misaligned(dq) || misaligned(dk) ||
+        misaligned(dv) || misaligned(dbias) || misaligned(bias) || misaligned(mask) || misaligned(workspace))
+        return FWA_ERR_ALIGN;
+    const void* ins[4] = {q, k, v, d_o};
+    void* outs[3] = {dq, dk, dv};
+    for (int a = 0; a < 3; ++a) {
+        for (int b = 0; b < 4; ++b)
+            if (outs[a] == ins[b]) return FWA_ERR_ALIAS;
+        for (int b = a + 1; b < 3; ++b)
+            if (outs[a] == outs[b]) return FWA_ERR_ALIAS;
+    }
+    const size_t need = fwa_backward_workspace_bytes(N, L, C, heads, dtype, dbias != nullptr);
+    if (need > 0 && (workspace == nullptr || workspace_bytes < need)) return FWA_ERR_WORKSPACE;
+    fwa::BwdArgs a;
+    a.q = q; a.k = k; a.v = v; a.d_o = d_o;
+    a.dq = dq; a.dk = dk; a.dv = dv; a.dbias = dbias;
+    a.partial = dbias ? static_cast<float*>(workspace) : nullptr;
+    a.bias = bias; a.mask = mask;
+    a.N = N; a.L = L; a.C = C; a.heads = heads; a.nW = mask ? nW : 1; a.scale = scale;
+    a.slots = fwa::backward_slots(N, heads);
+    const hipError_t e = dtype == FWA_BF16 ? fwa::launch_backward_bf16(a, st) : fwa::launch_backward_f32(a, st);
+    return e == hipSuccess ? FWA_OK : FWA_ERR_LAUNCH;
+}
+
+int fwa_bias_gather(const float* table, float* bias, int heads, int k, void* stream) {
+    if (heads < 1 || k < 1) return FWA_ERR_SHAPE;
+    if (k > 16) return FWA_ERR_UNSUPPORTED;
+    if (!table || !bias) return FWA_ERR_NULL;
+    if (misaligned(table) || misaligned(bias)) return FWA_ERR_ALIGN;
+    if (table == bias) return FWA_ERR_ALIAS;
+    return fwa::launch_bias_gather(table, bias, heads, k, static_cast<hipStream_t>(stream)) == hipSuccess
+               ? FWA_OK : FWA_ERR_LAUNCH;
+}
+
+int fwa_bias_scatter(const float* dbias, float* dtable, int heads, int k, void* stream) {
+    if (heads < 1 || k < 1) return FWA_ERR_SHAPE;
+    if (k > 16) return FWA_ERR_UNSUPPORTED;
+    if (!dbias || !dtable) return FWA_ERR_NULL;
+    if (misaligned(dbias) || misaligned(dtable)) return FWA_ERR_ALIGN;
+    if (dbias == dtable) return FWA_ERR_ALIAS;
+    return fwa::launch_bias_scatter(dbias, dtable, heads, k, static_cast<hipStream_t>(stream)) == hipSuccess
+               ? FWA_OK : FWA_ERR_LAUNCH;
+}
+
+}  // extern "C"

@@ -1,0 +1,61 @@
+// Internal declarations shared by the HIP translation units of libfwa.
+// Nothing here is part of the public ABI (see include/fwa.h for that).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace fwa {
+
+constexpr int kHeadDim = 32;   // the only supported head width
+constexpr int kMaxL = 256;     // 16 key blocks of 16 rows
+constexpr int kWavesPerBlock = 4;
+
+struct FwdArgs {
+    const void* q;
+    const void* k;
+    const void* v;
+    void* o;
+    const float* bias;   // [heads, L, L] or nullptr
+    const float* mask;   // [nW, L, L] or nullptr
+    long long N;
+    int L;
+    int C;
+    int heads;
+    int nW;
+    float scale;
+};
+
+struct BwdArgs {
+    const void* q;
+    const void* k;
+    const void* v;
+    const void* d_o;
+    void* dq;
+    void* dk;
+    void* dv;
+    float* dbias;        // [heads, L, L] or nullptr
+    float* partial;      // workspace for per-slot dS sums, or nullptr
+    const float* bias;
+    const float* mask;
+    long long N;
+    int L;
+    int C;
+    int heads;
+    int nW;
+    float scale;
+    int slots;           // number of partial-sum slots per head in `partial`
+};
+
+// Each returns a hipError_t from the launch (hipSuccess when enqueued).
+hipError_t launch_forward_bf16(const FwdArgs& a, hipStream_t s);
+hipError_t launch_forward_f32(const FwdArgs& a, hipStream_t s);
+hipError_t launch_backward_bf16(const BwdArgs& a, hipStream_t s);
+hipError_t launch_backward_f32(const BwdArgs& a, hipStream_t s);
+int backward_slots(long long N, int heads);
+hipError_t launch_zero_f32(float* dst, size_t count, hipStream_t s);
+hipError_t launch_bias_gather(const float* table, float* bias, int heads, int k, hipStream_t s);
+hipError_t launch_bias_scatter(const float* dbias, float* dtable, int heads, int k, hipStream_t s);
+
+}  // namespace fwa

@@ -34,12 +34,14 @@ def bf16_round(x: np.ndarray):
     """Round fp32 -> bf16 (nearest even).  Returns (values as fp32, raw uint16 bits)."""
     x = np.ascontiguousarray(x, dtype=np.float32)
     u = x.view(np.uint32)
-    lsb = (u >> np.uint32(16)) & np.uint32(1)
-    rounded = (u + np.uint32(0x7FFF) + lsb) >> np.uint32(16)
-    # NaN never occurs in these inputs; inf stays inf under the add above.
-    bits = rounded.astype(np.uint16)
-    vals = (bits.astype(np.uint32) << np.uint32(16)).view(np.float32)
-    return vals, bits
+    r = u >> np.uint32(16)
+    r &= np.uint32(1)
+    r += np.uint32(0x7FFF)
+    r += u                      # NaN never occurs in these inputs; inf stays inf under this add
+    r >>= np.uint32(16)
+    bits = r.astype(np.uint16)
+    r <<= np.uint32(16)
+    return r.view(np.float32), bits
 
 
 def bf16_bits_to_f32(bits: np.ndarray) -> np.ndarray:
@@ -47,7 +49,10 @@ def bf16_bits_to_f32(bits: np.ndarray) -> np.ndarray:
 
 
 def normal(shape, seed: int, std: float = 1.0) -> np.ndarray:
-    return (rng(seed).standard_normal(shape, dtype=np.float32) * np.float32(std)).astype(np.float32)
+    x = rng(seed).standard_normal(shape, dtype=np.float32)
+    if std != 1.0:
+        x *= np.float32(std)
+    return x
 
 
 def bias_table(heads: int, k: int, seed: int, std: float = 0.02) -> np.ndarray:

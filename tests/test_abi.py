@@ -1,0 +1,117 @@
+"""Host-side tests of the C ABI: the library loads, exports what the header declares,
+and rejects bad arguments before touching the GPU (so these run without one)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2501_06480_amd import binding
+    if not os.path.exists(binding.library_path()):
+        from paper_2501_06480_amd import build
+        build.build(verbose=False)
+    return binding.load_library()
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "fwa.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(fwa_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol(lib):
+    from paper_2501_06480_amd import binding
+    names = declared_functions()
+    assert sorted(binding.EXPORTS) == names
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_status_strings(lib):
+    seen = set()
+    for code in range(8):
+        s = lib.fwa_status_string(code).decode()
+        assert s and s != "unknown status code"
+        seen.add(s)
+    assert len(seen) == 8
+    assert lib.fwa_status_string(99).decode() == "unknown status code"
+
+
+P = 0x10000  # a fake, 16-byte aligned, non-NULL "device pointer"; never dereferenced on error paths
+
+
+def fwd(lib, q=P, k=P + 0x1000, v=P + 0x2000, o=P + 0x3000, N=4, L=49, C=96, heads=3, scale=0.1, bias=None,
+        mask=None, nW=0, dtype=1):
+    return lib.fwa_forward(q, k, v, o, N, L, C, heads, scale, bias, mask, nW, dtype, None)
+
+
+def bwd(lib, q=P, k=P + 0x1000, v=P + 0x2000, g=P + 0x3000, dq=P + 0x4000, dk=P + 0x5000, dv=P + 0x6000,
+        dbias=None, N=4, L=49, C=96, heads=3, scale=0.1, bias=None, mask=None, nW=0, dtype=1, ws=None,
+        ws_bytes=0):
+    return lib.fwa_backward(q, k, v, g, dq, dk, dv, dbias, N, L, C, heads, scale, bias, mask, nW, dtype, ws,
+                            ws_bytes, None)
+
+
+def test_forward_rejects_bad_arguments(lib):
+    from paper_2501_06480_amd import binding as b
+    assert fwd(lib, N=-1) == b.FWA_ERR_SHAPE
+    assert fwd(lib, L=0) == b.FWA_ERR_SHAPE
+    assert fwd(lib, heads=0) == b.FWA_ERR_SHAPE
+    assert fwd(lib, C=100, heads=3) == b.FWA_ERR_SHAPE
+    assert fwd(lib, C=192, heads=3) == b.FWA_ERR_UNSUPPORTED      # head dim 64
+    assert fwd(lib, L=257) == b.FWA_ERR_UNSUPPORTED
+    assert fwd(lib, dtype=2) == b.FWA_ERR_UNSUPPORTED
+    assert fwd(lib, mask=P + 0x9000, nW=0) == b.FWA_ERR_SHAPE
+    assert fwd(lib, mask=P + 0x9000, nW=3) == b.FWA_ERR_SHAPE     # 4 % 3 != 0
+    assert fwd(lib, q=None) == b.FWA_ERR_NULL
+    assert fwd(lib, o=None) == b.FWA_ERR_NULL
+    assert fwd(lib, k=P + 8) == b.FWA_ERR_ALIGN
+    assert fwd(lib, bias=P + 4) == b.FWA_ERR_ALIGN
+    assert fwd(lib, o=P) == b.FWA_ERR_ALIAS
+    assert fwd(lib, N=0, q=None, k=None, v=None, o=None) == b.FWA_OK   # empty batch: no-op
+
+
+def test_backward_rejects_bad_arguments(lib):
+    from paper_2501_06480_amd import binding as b
+    assert bwd(lib, N=-1) == b.FWA_ERR_SHAPE
+    assert bwd(lib, C=128, heads=2) == b.FWA_ERR_UNSUPPORTED
+    assert bwd(lib, L=300) == b.FWA_ERR_UNSUPPORTED
+    assert bwd(lib, g=None) == b.FWA_ERR_NULL
+    assert bwd(lib, dv=None) == b.FWA_ERR_NULL
+    assert bwd(lib, dq=P + 2) == b.FWA_ERR_ALIGN
+    assert bwd(lib, dq=P) == b.FWA_ERR_ALIAS
+    assert bwd(lib, dk=P + 0x4000) == b.FWA_ERR_ALIAS              # dk == dq
+    assert bwd(lib, mask=P + 0x9000, nW=8) == b.FWA_ERR_SHAPE
+    need = lib.fwa_backward_workspace_bytes(4, 49, 96, 3, 1, 1)
+    assert need >= 3 * 49 * 49 * 4
+    assert bwd(lib, dbias=P + 0x7000) == b.FWA_ERR_WORKSPACE
+    assert bwd(lib, dbias=P + 0x7000, ws=P + 0x8000, ws_bytes=need - 1) == b.FWA_ERR_WORKSPACE
+    assert lib.fwa_backward_workspace_bytes(4, 49, 96, 3, 1, 0) == 0
+    assert lib.fwa_backward_workspace_bytes(4, 49, 100, 3, 1, 1) == 0
+    assert lib.fwa_backward_workspace_bytes(0, 49, 96, 3, 1, 1) == 0
+    assert bwd(lib, N=0) == b.FWA_OK
+
+
+def test_bias_helpers_reject_bad_arguments(lib):
+    from paper_2501_06480_amd import binding as b
+    assert lib.fwa_bias_gather(P, P + 0x1000, 0, 7, None) == b.FWA_ERR_SHAPE
+    assert lib.fwa_bias_gather(P, P + 0x1000, 3, 0, None) == b.FWA_ERR_SHAPE
+    assert lib.fwa_bias_gather(P, P + 0x1000, 3, 17, None) == b.FWA_ERR_UNSUPPORTED
+    assert lib.fwa_bias_gather(None, P, 3, 7, None) == b.FWA_ERR_NULL
+    assert lib.fwa_bias_gather(P, P + 4, 3, 7, None) == b.FWA_ERR_ALIGN
+    assert lib.fwa_bias_gather(P, P, 3, 7, None) == b.FWA_ERR_ALIAS
+    assert lib.fwa_bias_scatter(P, None, 3, 7, None) == b.FWA_ERR_NULL
+    assert lib.fwa_bias_scatter(P, P + 0x1000, 3, 20, None) == b.FWA_ERR_UNSUPPORTED
+
+
+def test_binding_refuses_cpu_tensors():
+    import torch
+    import paper_2501_06480_amd as fwa
+    q = torch.zeros((2, 49, 96), dtype=torch.bfloat16)
+    with pytest.raises((TypeError, RuntimeError, AssertionError)):
+        fwa.fwa_forward(q, q, q, 3, 0.1)
