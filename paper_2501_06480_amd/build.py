@@ -12,8 +12,10 @@ OUT = os.path.join(HERE, "libfwa.so")
 OBJ_DIR = os.path.join(HERE, "_build")
 SOURCES = ["fwa_api.hip", "fwa_forward.hip", "fwa_backward.hip", "fwa_bias.hip"]
 # packed fp32 VALU ops are switched off on purpose: the compiler must not form them
+# and matrix-core results go to ordinary VGPRs (no accumulator-register copies).
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wextra",
-               "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+               "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+               "-mllvm", "-amdgpu-mfma-vgpr-form"]
 
 
 def _hipcc() -> str:

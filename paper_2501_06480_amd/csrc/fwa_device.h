@@ -19,6 +19,7 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr float kLog2e = 1.4426950408889634f;
 
@@ -37,17 +38,84 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
 }
 
 __device__ __forceinline__ bf16x8 as_bf16x8(uint4 u) { return __builtin_bit_cast(bf16x8, u); }
+__device__ __forceinline__ bf16x8 as_bf16x8(u32x4 u) { return __builtin_bit_cast(bf16x8, u); }
 
-// max / sum over the 4 lanes (g = 0..3) that share the same n
+// Raw buffer descriptor over `bytes` bytes at `base`.  Loads whose offset lies
+// beyond `bytes` return zero and such stores are dropped by the hardware, which
+// is how rows past the end of a tile are padded without branches.  Every access
+// made through it is either entirely inside or entirely outside the range.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, uint32_t bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, 0x00020000);
+}
+
+// NOTE: never write __builtin_bit_cast(T, vec[i]) on a vector element: this
+// compiler reads element 0 whatever i is.  Cast whole vectors, or copy the
+// element into a scalar first.
+__device__ __forceinline__ f32x4 load_f32x4(__amdgpu_buffer_rsrc_t r, uint32_t voffset) {
+    return __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(r, voffset, 0, 0));
+}
+__device__ __forceinline__ void store_f32x4(f32x4 v, __amdgpu_buffer_rsrc_t r, uint32_t voffset) {
+    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v), r, voffset, 0, 0);
+}
+__device__ __forceinline__ float load_f32(__amdgpu_buffer_rsrc_t r, uint32_t voffset) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r, voffset, 0, 0));
+}
+
+// Unsigned division by a runtime constant with a host-made multiplier
+// (round-up method): n / d == (mulhi(n, mul) + n) >> shift for n < 2^31.
+struct FastDiv {
+    uint32_t mul, shift, d;
+};
+__host__ inline FastDiv make_fastdiv(uint32_t d) {
+    FastDiv f;
+    f.d = d;
+    uint32_t l = 0;
+    while ((1u << l) < d) ++l;
+    f.shift = l;
+    f.mul = (uint32_t)((((uint64_t)1 << 32) * (((uint64_t)1 << l) - d)) / d + 1);
+    return f;
+}
+__device__ __forceinline__ uint32_t fastdiv(uint32_t n, const FastDiv& f) {
+    return (uint32_t)(((uint64_t)__umulhi(n, f.mul) + n) >> f.shift);
+}
+
+// Workgroups are handed to the 8 XCDs (each with its own L2) round-robin by
+// index.  This maps the hardware index to a logical one such that logical
+// neighbours run on the same XCD: XCD x owns the contiguous logical range
+// [x*q + min(x, r), ...) where q, r = nblocks / 8, nblocks % 8.
+__device__ __forceinline__ uint32_t xcd_logical_block(uint32_t bid, uint32_t q, uint32_t r) {
+    const uint32_t x = bid & 7u, idx = bid >> 3;
+    return x * q + (x < r ? x : r) + idx;
+}
+
+// max / sum over the 4 lanes (g = 0..3) that share the same n.  The gfx950
+// lane-swap instructions exchange 16-lane rows between two registers
+// (v_permlane16_swap: odd rows of the first with even rows of the second;
+// v_permlane32_swap: upper half of the first with lower half of the second).
+// Fed two copies of x, one swap leaves (x of rows 0,0,2,2 | x of rows 1,1,3,3)
+// resp. (x of the low half | x of the high half) in the two registers, so a
+// swap plus one max/add per step reduces across rows without the LDS crossbar.
 __device__ __forceinline__ float max_over_g(float x) {
-    x = fmaxf(x, __shfl_xor(x, 16));
-    x = fmaxf(x, __shfl_xor(x, 32));
-    return x;
+    uint32_t u = __builtin_bit_cast(uint32_t, x);
+    auto s16 = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+    uint32_t a = s16[0], b = s16[1];
+    x = fmaxf(__builtin_bit_cast(float, a), __builtin_bit_cast(float, b));
+    u = __builtin_bit_cast(uint32_t, x);
+    auto s32 = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    a = s32[0];
+    b = s32[1];
+    return fmaxf(__builtin_bit_cast(float, a), __builtin_bit_cast(float, b));
 }
 __device__ __forceinline__ float sum_over_g(float x) {
-    x += __shfl_xor(x, 16);
-    x += __shfl_xor(x, 32);
-    return x;
+    uint32_t u = __builtin_bit_cast(uint32_t, x);
+    auto s16 = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+    uint32_t a = s16[0], b = s16[1];
+    x = __builtin_bit_cast(float, a) + __builtin_bit_cast(float, b);
+    u = __builtin_bit_cast(uint32_t, x);
+    auto s32 = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    a = s32[0];
+    b = s32[1];
+    return __builtin_bit_cast(float, a) + __builtin_bit_cast(float, b);
 }
 // sum over the 16 lanes (n = 0..15) that share the same g
 __device__ __forceinline__ float sum_over_n(float x) {

@@ -12,186 +12,259 @@
 //         lane (g, n), tile jb, slot r  <->  S[i = n][j = 16 jb + 4 g + r];
 //     a query row is spread over the 4 lanes sharing n, so max and sum need
 //     two cross-row shuffles each and no LDS;
-//   * in that layout the probabilities of a lane are already the A operand of
-//     P V (its k-slots are keys 4g..4g+3 of two neighbouring tiles); V is
-//     loaded as dwords (channel pair 2n, 2n+1 of those same keys) and split
-//     into an even-channel and an odd-channel B operand, so the two output
-//     accumulators of a lane are neighbouring channels and are stored as one
-//     packed dword;
-//   * rows/columns beyond L (L is padded to a multiple of 16 on chip only)
-//     load as zero, padded score columns are set to -inf, padded rows are
-//     never stored.  Nothing is read or written outside [N, L, C].
+//   * in that layout the probabilities of a lane are already a B operand of
+//     O^T = V^T P^T (its k-slots are keys 4g..4g+3 of two neighbouring tiles);
+//     V is loaded as dwords (channel pair 2m, 2m+1 of those same keys) and
+//     split into an even-channel and an odd-channel A operand.  The two
+//     accumulators of lane (g, n) then hold channels 8g..8g+7 of query row n:
+//     the row's softmax sum is in the same lane and the result leaves as one
+//     16-byte store, mirroring the Q load;
+//   * all global traffic goes through raw buffer descriptors sized to the tile:
+//     rows beyond L (L is padded to a multiple of 16 on chip only) load as
+//     zero and their stores are dropped by the address range check, so there
+//     are no branches and nothing is touched outside [N, L, C]; padded score
+//     columns are set to -inf.  The range check covers the vector offset and
+//     the immediate only, NOT the scalar offset operand, so every offset goes
+//     into the vector operand and the scalar one stays 0.
 #include "fwa_device.h"
 #include "fwa_internal.h"
 
 namespace fwa {
 namespace {
 
+// How a launch is cut into workgroups and waves (all wave-uniform).
+struct FwdGeom {
+    FastDiv groups;        // workgroups per window
+    uint32_t heads_per_block;
+    uint32_t qsplit_log2;  // waves sharing the query blocks of one tile = 1 << qsplit_log2
+    uint32_t xcd_q, xcd_r; // nblocks / 8, nblocks % 8 for the XCD-aware block order
+};
+
+template <int NB>
+struct Tiling {
+    static constexpr int kQSplitLog2 = NB <= 4 ? 0 : (NB <= 8 ? 1 : 2);
+    static constexpr int kQSplit = 1 << kQSplitLog2;
+    static constexpr int kQPerWave = (NB + kQSplit - 1) / kQSplit;  // query blocks per wave
+};
+
+struct TileCoord {
+    uint32_t w, h, qs;
+    bool valid;
+};
+__device__ __forceinline__ TileCoord tile_of_wave(const FwdGeom& gm, int heads) {
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const uint32_t lb = xcd_logical_block(blockIdx.x, gm.xcd_q, gm.xcd_r);
+    TileCoord t;
+    t.w = fastdiv(lb, gm.groups);
+    const uint32_t hg = lb - t.w * gm.groups.d;
+    t.h = hg * gm.heads_per_block + (wave >> gm.qsplit_log2);
+    t.qs = wave & ((1u << gm.qsplit_log2) - 1u);
+    t.valid = t.h < (uint32_t)heads;
+    return t;
+}
+
 // ---------------------------------------------------------------- bf16 ----
 // NB = ceil(L / 16) key/query blocks; BM = a bias and/or mask is present.
 template <int NB, bool BM>
-__global__ void __launch_bounds__(64 * kWavesPerBlock)
-fwd_bf16_kernel(FwdArgs p, int qsplit, int qb_per_split, long long ntasks) {
+__global__ void __launch_bounds__(64 * kWavesPerBlock) fwd_bf16_kernel(FwdArgs p, FwdGeom gm) {
     constexpr int NB2 = (NB + 1) / 2;
+    constexpr int QPW = Tiling<NB>::kQPerWave;
     const int lane = threadIdx.x & 63;
     const int n = lane & 15, g = lane >> 4;
-    const long long task = (long long)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
-    if (task >= ntasks) return;  // wave-uniform; the kernel has no barriers
-    const int qs = (int)(task % qsplit);
-    const long long wh = task / qsplit;
-    const int h = (int)(wh % p.heads);
-    const long long w = wh / p.heads;
-    const int L = p.L, C = p.C;
-    const size_t tile = (size_t)w * L * C + (size_t)h * kHeadDim;
-    const uint16_t* Qw = (const uint16_t*)p.q + tile;
-    const uint16_t* Kw = (const uint16_t*)p.k + tile;
-    const uint16_t* Vw = (const uint16_t*)p.v + tile;
-    uint16_t* Ow = (uint16_t*)p.o + tile;
+    const TileCoord tc = tile_of_wave(gm, p.heads);
+    if (!tc.valid) return;  // wave-uniform; the kernel has no barriers
+    const int L = p.L;
+    const uint32_t row_bytes = (uint32_t)p.C * 2u;
+    const uint32_t tile_bytes = (uint32_t)(L - 1) * row_bytes + 2u * kHeadDim;
+    const size_t tile = ((size_t)tc.w * L * p.C + (size_t)tc.h * kHeadDim) * 2u;
+    const __amdgpu_buffer_rsrc_t rq = make_rsrc((const char*)p.q + tile, tile_bytes);
+    const __amdgpu_buffer_rsrc_t rk = make_rsrc((const char*)p.k + tile, tile_bytes);
+    const __amdgpu_buffer_rsrc_t rv = make_rsrc((const char*)p.v + tile, tile_bytes);
+    const __amdgpu_buffer_rsrc_t ro = make_rsrc((char*)p.o + tile, tile_bytes);
+    const uint32_t off_row = (uint32_t)n * row_bytes + 16u * g;  // 16 B of row n (plus a block offset)
+    const uint32_t off_v = 4u * g * row_bytes + 4u * n;          // channel pair n of row 4g (plus slot offset)
 
-    // K: A operands, lane (g, n) = K[16 jb + n][8g .. 8g+7]
+    // K: A operands of S^T, lane (g, n) = K[16 jb + n][8g .. 8g+7]
     bf16x8 kop[NB];
 #pragma unroll
-    for (int jb = 0; jb < NB; ++jb) {
-        const int row = 16 * jb + n;
-        uint4 t = {0u, 0u, 0u, 0u};
-        if (row < L) t = *(const uint4*)(Kw + (size_t)row * C + 8 * g);
-        kop[jb] = as_bf16x8(t);
-    }
-    // V: B operands for key pairs of blocks, even and odd channel
+    for (int jb = 0; jb < NB; ++jb)
+        kop[jb] = as_bf16x8(__builtin_amdgcn_raw_buffer_load_b128(rk, off_row + 16 * jb * row_bytes, 0, 0));
+    // Q: B operands, one per query block of this wave
+    bf16x8 qop[QPW];
+#pragma unroll
+    for (int t = 0; t < QPW; ++t)
+        qop[t] = as_bf16x8(__builtin_amdgcn_raw_buffer_load_b128(rq, off_row + 16 * (tc.qs * QPW + t) * row_bytes, 0, 0));
+    // V: A operands of O^T per pair of key blocks, even and odd channels
     bf16x8 vop[NB2][2];
 #pragma unroll
     for (int kp = 0; kp < NB2; ++kp) {
         uint32_t d[8];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const int key = 32 * kp + slot_row(g, e);
-            d[e] = 0u;
-            if (key < L) d[e] = *(const uint32_t*)(Vw + (size_t)key * C + 2 * n);
-        }
+        for (int e = 0; e < 8; ++e)
+            d[e] = __builtin_amdgcn_raw_buffer_load_b32(rv, off_v + (32 * kp + slot_row(0, e)) * row_bytes, 0, 0);
         split_pairs(d, vop[kp][0], vop[kp][1]);
     }
 
     const float sl2 = p.scale * kLog2e;
-    const float* bias_h = BM && p.bias ? p.bias + (size_t)h * L * L : nullptr;
-    const float* mask_w = BM && p.mask ? p.mask + (size_t)(w % p.nW) * L * L : nullptr;
+    __amdgpu_buffer_rsrc_t rb = make_rsrc(nullptr, 0), rm = make_rsrc(nullptr, 0);
+    if (BM) {
+        const uint32_t ll = (uint32_t)L * L * 4u;
+        if (p.bias) rb = make_rsrc(p.bias + (size_t)tc.h * L * L, ll);
+        if (p.mask) rm = make_rsrc(p.mask + (size_t)(tc.w % (uint32_t)p.nW) * L * L, ll);
+    }
+    const uint32_t off_b = ((uint32_t)n * L + 4u * g) * 4u;  // B[n][4g] (plus block offsets)
 
-    const int qb_end = min(NB, (qs + 1) * qb_per_split);
-    for (int qb = qs * qb_per_split; qb < qb_end; ++qb) {
-        const int i = 16 * qb + n;  // the query row this lane's scores belong to
-        uint4 t = {0u, 0u, 0u, 0u};
-        if (i < L) t = *(const uint4*)(Qw + (size_t)i * C + 8 * g);
-        const bf16x8 qop = as_bf16x8(t);
+#pragma unroll
+    for (int t = 0; t < QPW; ++t) {
+        const int qb = tc.qs * QPW + t;
+        if (16 * qb >= L) break;  // wave-uniform
 
         f32x4 s[NB];
-        float m = -INFINITY;
 #pragma unroll
         for (int jb = 0; jb < NB; ++jb) {
             const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
-            s[jb] = mfma_bf16(kop[jb], qop, zero);
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int j = 16 * jb + 4 * g + r;
-                float x = s[jb][r] * sl2;
-                if (BM) {
-                    float add = 0.f;
-                    if (i < L && j < L) {
-                        if (bias_h) add += bias_h[(size_t)i * L + j];
-                        if (mask_w) add += mask_w[(size_t)i * L + j];
-                    }
-                    x = fmaf(add, kLog2e, x);
-                }
-                if (jb == NB - 1 && j >= L) x = -INFINITY;
-                s[jb][r] = x;
-                m = fmaxf(m, x);
-            }
+            s[jb] = mfma_bf16(kop[jb], qop[t], zero);  // s[jb][r] = S[16 qb + n][16 jb + 4g + r]
         }
-        m = max_over_g(m);
+        // After this block s holds the score in a unit such that p = exp2(s * mul - mb).
+        float mul, mb;
+        if (BM) {
+            // Rows beyond L fall outside the descriptor (zero); columns beyond L are
+            // overwritten with -inf below, whatever was fetched for them.
+#pragma unroll
+            for (int jb = 0; jb < NB; ++jb)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const uint32_t so = (uint32_t)(16 * qb) * L * 4u;
+                    float add = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rb, off_b + (16 * jb + r) * 4 + so, 0, 0));
+                    add += __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rm, off_b + (16 * jb + r) * 4 + so, 0, 0));
+                    s[jb][r] = fmaf(s[jb][r], sl2, add * kLog2e);
+                }
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+                if (16 * (NB - 1) + 4 * g + r >= L) s[NB - 1][r] = -INFINITY;
+            float m = s[0][0];
+#pragma unroll
+            for (int jb = 0; jb < NB; ++jb) {
+                m = fmaxf(fmaxf(m, s[jb][0]), s[jb][1]);
+                m = fmaxf(fmaxf(m, s[jb][2]), s[jb][3]);
+            }
+            mul = 1.0f;
+            mb = max_over_g(m);
+        } else {
+            // No bias: keep the raw products and fold the scale into the exponent,
+            // p = exp2(s*sl2 - max(s*sl2)).  For sl2 >= 0 the maximum of the scaled
+            // scores is sl2 * max(s); a negative scale uses the minimum instead.
+            const float pad = sl2 >= 0.f ? -INFINITY : INFINITY;
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+                if (16 * (NB - 1) + 4 * g + r >= L) s[NB - 1][r] = pad;
+            float m = s[0][0];
+            if (sl2 >= 0.f) {
+#pragma unroll
+                for (int jb = 0; jb < NB; ++jb) {
+                    m = fmaxf(fmaxf(m, s[jb][0]), s[jb][1]);
+                    m = fmaxf(fmaxf(m, s[jb][2]), s[jb][3]);
+                }
+                m = max_over_g(m);
+            } else {
+#pragma unroll
+                for (int jb = 0; jb < NB; ++jb) {
+                    m = fminf(fminf(m, s[jb][0]), s[jb][1]);
+                    m = fminf(fminf(m, s[jb][2]), s[jb][3]);
+                }
+                m = -max_over_g(-m);
+            }
+            mul = sl2;
+            mb = m * sl2;
+        }
         float sum = 0.f;
 #pragma unroll
         for (int jb = 0; jb < NB; ++jb)
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-                const float e = __builtin_amdgcn_exp2f(s[jb][r] - m);
+                const float e = __builtin_amdgcn_exp2f(fmaf(s[jb][r], mul, -mb));
                 s[jb][r] = e;
                 sum += e;
             }
         sum = sum_over_g(sum);
-        const float inv = 1.0f / sum;
+        const float inv = __builtin_amdgcn_rcpf(sum);
 
         f32x4 oe = {0.f, 0.f, 0.f, 0.f}, oo = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int kp = 0; kp < NB2; ++kp) {
-            uint4 a;
+            u32x4 a;
             a.x = pack_bf16(s[2 * kp][0], s[2 * kp][1]);
             a.y = pack_bf16(s[2 * kp][2], s[2 * kp][3]);
             const int j1 = 2 * kp + 1 < NB ? 2 * kp + 1 : 0;  // odd NB: the last pair has no second tile
             a.z = 2 * kp + 1 < NB ? pack_bf16(s[j1][0], s[j1][1]) : 0u;
             a.w = 2 * kp + 1 < NB ? pack_bf16(s[j1][2], s[j1][3]) : 0u;
             const bf16x8 pop = as_bf16x8(a);
-            oe = mfma_bf16(pop, vop[kp][0], oe);
-            oo = mfma_bf16(pop, vop[kp][1], oo);
+            oe = mfma_bf16(vop[kp][0], pop, oe);  // oe[r] = O[16 qb + n][2 (4g + r)]
+            oo = mfma_bf16(vop[kp][1], pop, oo);  // oo[r] = O[16 qb + n][2 (4g + r) + 1]
         }
-        // accumulators: oe[r] = O[16 qb + 4g + r][2n], oo[r] = ...[2n+1];
-        // the row sum of query 4g + r sits in lane 4g + r (any row).
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const float inv_r = __shfl(inv, 4 * g + r);
-            const int io = 16 * qb + 4 * g + r;
-            if (io < L) *(uint32_t*)(Ow + (size_t)io * C + 2 * n) = pack_bf16(oe[r] * inv_r, oo[r] * inv_r);
-        }
+        u32x4 out;
+        out.x = pack_bf16(oe[0] * inv, oo[0] * inv);
+        out.y = pack_bf16(oe[1] * inv, oo[1] * inv);
+        out.z = pack_bf16(oe[2] * inv, oo[2] * inv);
+        out.w = pack_bf16(oe[3] * inv, oo[3] * inv);
+        __builtin_amdgcn_raw_buffer_store_b128(out, ro, off_row + 16 * qb * row_bytes, 0, 0);
     }
 }
 
 // ---------------------------------------------------------------- fp32 ----
 // Same tile ownership and layouts with v_mfma_f32_16x16x4_f32 (true fp32
 // products): k-slot g of step kk stands for channel 8g + kk in QK^T and for
-// key 16 jb + 4g + r in step (jb, r) of PV.  V is streamed from cache per
-// query block instead of being held in registers.
+// key 16 jb + 4g + r in step (jb, r) of O^T = V^T P^T.  V is streamed from
+// cache per query block instead of being held in registers.
 template <int NB, bool BM>
-__global__ void __launch_bounds__(64 * kWavesPerBlock)
-fwd_f32_kernel(FwdArgs p, int qsplit, int qb_per_split, long long ntasks) {
+__global__ void __launch_bounds__(64 * kWavesPerBlock) fwd_f32_kernel(FwdArgs p, FwdGeom gm) {
+    constexpr int QPW = Tiling<NB>::kQPerWave;
     const int lane = threadIdx.x & 63;
     const int n = lane & 15, g = lane >> 4;
-    const long long task = (long long)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
-    if (task >= ntasks) return;
-    const int qs = (int)(task % qsplit);
-    const long long wh = task / qsplit;
-    const int h = (int)(wh % p.heads);
-    const long long w = wh / p.heads;
-    const int L = p.L, C = p.C;
-    const size_t tile = (size_t)w * L * C + (size_t)h * kHeadDim;
-    const float* Qw = (const float*)p.q + tile;
-    const float* Kw = (const float*)p.k + tile;
-    const float* Vw = (const float*)p.v + tile;
-    float* Ow = (float*)p.o + tile;
+    const TileCoord tc = tile_of_wave(gm, p.heads);
+    if (!tc.valid) return;
+    const int L = p.L;
+    const uint32_t row_bytes = (uint32_t)p.C * 4u;
+    const uint32_t tile_bytes = (uint32_t)(L - 1) * row_bytes + 4u * kHeadDim;
+    const size_t tile = ((size_t)tc.w * L * p.C + (size_t)tc.h * kHeadDim) * 4u;
+    const __amdgpu_buffer_rsrc_t rq = make_rsrc((const char*)p.q + tile, tile_bytes);
+    const __amdgpu_buffer_rsrc_t rk = make_rsrc((const char*)p.k + tile, tile_bytes);
+    const __amdgpu_buffer_rsrc_t rv = make_rsrc((const char*)p.v + tile, tile_bytes);
+    const __amdgpu_buffer_rsrc_t ro = make_rsrc((char*)p.o + tile, tile_bytes);
+    const uint32_t off_row = (uint32_t)n * row_bytes + 32u * g;  // channels 8g..8g+7 of row n
+    const uint32_t off_v = 4u * g * row_bytes + 4u * n;          // channel n of row 4g
 
     float kop[NB][8];
 #pragma unroll
     for (int jb = 0; jb < NB; ++jb) {
-        const int row = 16 * jb + n;
-        float4 a = {0.f, 0.f, 0.f, 0.f}, b = {0.f, 0.f, 0.f, 0.f};
-        if (row < L) {
-            a = *(const float4*)(Kw + (size_t)row * C + 8 * g);
-            b = *(const float4*)(Kw + (size_t)row * C + 8 * g + 4);
+        const f32x4 a = load_f32x4(rk, off_row + 16 * jb * row_bytes);
+        const f32x4 b = load_f32x4(rk, off_row + 16 + 16 * jb * row_bytes);
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            kop[jb][c] = a[c];
+            kop[jb][4 + c] = b[c];
         }
-        kop[jb][0] = a.x; kop[jb][1] = a.y; kop[jb][2] = a.z; kop[jb][3] = a.w;
-        kop[jb][4] = b.x; kop[jb][5] = b.y; kop[jb][6] = b.z; kop[jb][7] = b.w;
     }
-    const float* bias_h = BM && p.bias ? p.bias + (size_t)h * L * L : nullptr;
-    const float* mask_w = BM && p.mask ? p.mask + (size_t)(w % p.nW) * L * L : nullptr;
+    __amdgpu_buffer_rsrc_t rb = make_rsrc(nullptr, 0), rm = make_rsrc(nullptr, 0);
+    if (BM) {
+        const uint32_t ll = (uint32_t)L * L * 4u;
+        if (p.bias) rb = make_rsrc(p.bias + (size_t)tc.h * L * L, ll);
+        if (p.mask) rm = make_rsrc(p.mask + (size_t)(tc.w % (uint32_t)p.nW) * L * L, ll);
+    }
+    const uint32_t off_b = ((uint32_t)n * L + 4u * g) * 4u;
 
-    const int qb_end = min(NB, (qs + 1) * qb_per_split);
-    for (int qb = qs * qb_per_split; qb < qb_end; ++qb) {
-        const int i = 16 * qb + n;
+    for (int t = 0; t < QPW; ++t) {
+        const int qb = tc.qs * QPW + t;
+        if (16 * qb >= L) break;
         float qop[8];
         {
-            float4 a = {0.f, 0.f, 0.f, 0.f}, b = {0.f, 0.f, 0.f, 0.f};
-            if (i < L) {
-                a = *(const float4*)(Qw + (size_t)i * C + 8 * g);
-                b = *(const float4*)(Qw + (size_t)i * C + 8 * g + 4);
+            const f32x4 a = load_f32x4(rq, off_row + 16 * qb * row_bytes);
+            const f32x4 b = load_f32x4(rq, off_row + 16 + 16 * qb * row_bytes);
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                qop[c] = a[c];
+                qop[4 + c] = b[c];
             }
-            qop[0] = a.x; qop[1] = a.y; qop[2] = a.z; qop[3] = a.w;
-            qop[4] = b.x; qop[5] = b.y; qop[6] = b.z; qop[7] = b.w;
         }
         f32x4 s[NB];
         float m = -INFINITY;
@@ -202,15 +275,13 @@ fwd_f32_kernel(FwdArgs p, int qsplit, int qb_per_split, long long ntasks) {
             for (int kk = 0; kk < 8; ++kk) acc = mfma_f32(kop[jb][kk], qop[kk], acc);
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-                const int j = 16 * jb + 4 * g + r;
                 float x = acc[r] * p.scale;
                 if (BM) {
-                    if (i < L && j < L) {
-                        if (bias_h) x += bias_h[(size_t)i * L + j];
-                        if (mask_w) x += mask_w[(size_t)i * L + j];
-                    }
+                    const uint32_t so = (uint32_t)(16 * qb) * L * 4u;
+                    x += __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rb, off_b + (16 * jb + r) * 4 + so, 0, 0));
+                    x += __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rm, off_b + (16 * jb + r) * 4 + so, 0, 0));
                 }
-                if (jb == NB - 1 && j >= L) x = -INFINITY;
+                if (jb == NB - 1 && 16 * jb + 4 * g + r >= L) x = -INFINITY;
                 acc[r] = x;
                 m = fmaxf(m, x);
             }
@@ -233,63 +304,59 @@ fwd_f32_kernel(FwdArgs p, int qsplit, int qb_per_split, long long ntasks) {
         for (int jb = 0; jb < NB; ++jb)
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-                const int key = 16 * jb + 4 * g + r;
-                float v0 = 0.f, v1 = 0.f;
-                if (key < L) {
-                    v0 = Vw[(size_t)key * C + n];
-                    v1 = Vw[(size_t)key * C + 16 + n];
-                }
-                o0 = mfma_f32(s[jb][r], v0, o0);
-                o1 = mfma_f32(s[jb][r], v1, o1);
+                const uint32_t so = (uint32_t)(16 * jb + r) * row_bytes;
+                const float v0 = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rv, off_v + so, 0, 0));
+                const float v1 = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rv, off_v + 64 + so, 0, 0));
+                o0 = mfma_f32(v0, s[jb][r], o0);  // o0[r'] = O[16 qb + n][4g + r']
+                o1 = mfma_f32(v1, s[jb][r], o1);  // o1[r'] = O[16 qb + n][16 + 4g + r']
             }
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const float sum_r = __shfl(sum, 4 * g + r);
-            const int io = 16 * qb + 4 * g + r;
-            if (io < L) {
-                Ow[(size_t)io * C + n] = o0[r] / sum_r;
-                Ow[(size_t)io * C + 16 + n] = o1[r] / sum_r;
-            }
-        }
+        const uint32_t off_o = (uint32_t)n * row_bytes + 16u * g;
+        store_f32x4(o0 / sum, ro, off_o + 16 * qb * row_bytes);
+        store_f32x4(o1 / sum, ro, off_o + 64 + 16 * qb * row_bytes);
     }
 }
 
-struct Split {
-    int qsplit, qb_per_split;
-};
-// How many waves share the query blocks of one tile.
-inline Split choose_split(int nb) {
-    Split s;
-    s.qb_per_split = nb <= 4 ? nb : 4;
-    s.qsplit = (nb + s.qb_per_split - 1) / s.qb_per_split;
-    return s;
+// Heads are 64 B (bf16) slices of a row, so neighbouring heads share 128 B
+// memory lines: the waves of a workgroup take neighbouring heads (all heads of
+// the window when there are at most 4), and the XCD-aware block order keeps
+// the remaining neighbours on one L2.
+template <int NB>
+FwdGeom make_geom(const FwdArgs& a, unsigned* grid, unsigned* block) {
+    FwdGeom gm;
+    const int qsplit = Tiling<NB>::kQSplit;
+    int hpb = kWavesPerBlock / qsplit;  // heads per workgroup
+    if (a.heads < hpb) hpb = a.heads;
+    const uint32_t groups = (uint32_t)((a.heads + hpb - 1) / hpb);
+    gm.groups = make_fastdiv(groups);
+    gm.heads_per_block = (uint32_t)hpb;
+    gm.qsplit_log2 = Tiling<NB>::kQSplitLog2;
+    const uint32_t nblocks = (uint32_t)(a.N * groups);
+    gm.xcd_q = nblocks / 8u;
+    gm.xcd_r = nblocks % 8u;
+    *grid = nblocks;
+    *block = 64u * (unsigned)(hpb * qsplit);
+    return gm;
 }
 
 template <int NB>
 hipError_t launch_bf16_nb(const FwdArgs& a, hipStream_t st) {
-    const Split sp = choose_split(NB);
-    const long long ntasks = a.N * a.heads * sp.qsplit;
-    const unsigned grid = (unsigned)((ntasks + kWavesPerBlock - 1) / kWavesPerBlock);
+    unsigned grid, block;
+    const FwdGeom gm = make_geom<NB>(a, &grid, &block);
     if (a.bias || a.mask)
-        hipLaunchKernelGGL((fwd_bf16_kernel<NB, true>), dim3(grid), dim3(64 * kWavesPerBlock), 0, st, a,
-                           sp.qsplit, sp.qb_per_split, ntasks);
+        hipLaunchKernelGGL((fwd_bf16_kernel<NB, true>), dim3(grid), dim3(block), 0, st, a, gm);
     else
-        hipLaunchKernelGGL((fwd_bf16_kernel<NB, false>), dim3(grid), dim3(64 * kWavesPerBlock), 0, st, a,
-                           sp.qsplit, sp.qb_per_split, ntasks);
+        hipLaunchKernelGGL((fwd_bf16_kernel<NB, false>), dim3(grid), dim3(block), 0, st, a, gm);
     return hipGetLastError();
 }
 
 template <int NB>
 hipError_t launch_f32_nb(const FwdArgs& a, hipStream_t st) {
-    const Split sp = choose_split(NB);
-    const long long ntasks = a.N * a.heads * sp.qsplit;
-    const unsigned grid = (unsigned)((ntasks + kWavesPerBlock - 1) / kWavesPerBlock);
+    unsigned grid, block;
+    const FwdGeom gm = make_geom<NB>(a, &grid, &block);
     if (a.bias || a.mask)
-        hipLaunchKernelGGL((fwd_f32_kernel<NB, true>), dim3(grid), dim3(64 * kWavesPerBlock), 0, st, a,
-                           sp.qsplit, sp.qb_per_split, ntasks);
+        hipLaunchKernelGGL((fwd_f32_kernel<NB, true>), dim3(grid), dim3(block), 0, st, a, gm);
     else
-        hipLaunchKernelGGL((fwd_f32_kernel<NB, false>), dim3(grid), dim3(64 * kWavesPerBlock), 0, st, a,
-                           sp.qsplit, sp.qb_per_split, ntasks);
+        hipLaunchKernelGGL((fwd_f32_kernel<NB, false>), dim3(grid), dim3(block), 0, st, a, gm);
     return hipGetLastError();
 }
 
