@@ -74,7 +74,7 @@ def fwa_status_string(code: int) -> str:
 
 
 def _dtype_code(t) -> int:
-    import torch
+    torch = _torch()
     if t.dtype == torch.float32:
         return FWA_F32
     if t.dtype == torch.bfloat16:
@@ -83,42 +83,67 @@ def _dtype_code(t) -> int:
 
 
 def _dev_ptr(t, name: str, like=None, f32: bool = False) -> Optional[int]:
-    import torch
     if t is None:
         return None
-    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+    if not getattr(t, "is_cuda", False):
         raise TypeError(f"{name} must be a GPU tensor (there is no CPU path)")
     if not t.is_contiguous():
         raise ValueError(f"{name} must be contiguous")
-    if f32 and t.dtype != torch.float32:
+    if f32 and t.dtype != _torch().float32:
         raise TypeError(f"{name} must be float32")
     if like is not None and (t.shape != like.shape or t.dtype != like.dtype or t.device != like.device):
         raise ValueError(f"{name} must match q in shape, dtype and device")
     return t.data_ptr()
 
 
+_torch_mod = None
+
+
+def _torch():
+    global _torch_mod
+    if _torch_mod is None:
+        import torch
+        _torch_mod = torch
+    return _torch_mod
+
+
 def _stream_handle(stream, device) -> int:
-    import torch
     if stream is None:
-        stream = torch.cuda.current_stream(device)
+        return _torch().cuda.current_stream(device).cuda_stream
     return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+
+
+class _on_device:
+    """Make `device` current for the duration of the call, only if it is not already."""
+
+    def __init__(self, device):
+        torch = _torch()
+        self.ctx = None if device.index == torch.cuda.current_device() else torch.cuda.device(device)
+
+    def __enter__(self):
+        if self.ctx is not None:
+            self.ctx.__enter__()
+
+    def __exit__(self, *exc):
+        if self.ctx is not None:
+            self.ctx.__exit__(*exc)
 
 
 def fwa_forward(q, k, v, heads: int, scale: float, bias=None, mask=None, out=None, stream=None):
     """O = softmax(scale*QK^T + B + M) V (paper Algorithm 1).  Tensors are [N, L, C] on the GPU."""
-    import torch
-    lib = load_library()
+    lib = _lib if _lib is not None else load_library()
     N, L, C = q.shape
-    o = torch.empty_like(q) if out is None else out
+    qp = _dev_ptr(q, "q")
+    o = _torch().empty_like(q) if out is None else out
     nW = 0 if mask is None else int(mask.shape[0])
     if bias is not None and tuple(bias.shape) != (heads, L, L):
         raise ValueError("bias must be [heads, L, L]")
     if mask is not None and tuple(mask.shape) != (nW, L, L):
         raise ValueError("mask must be [nW, L, L]")
-    args = (_dev_ptr(q, "q"), _dev_ptr(k, "k", q), _dev_ptr(v, "v", q), _dev_ptr(o, "out", q), N, L, C,
+    args = (qp, _dev_ptr(k, "k", q), _dev_ptr(v, "v", q), _dev_ptr(o, "out", q), N, L, C,
             int(heads), float(scale), _dev_ptr(bias, "bias", f32=True), _dev_ptr(mask, "mask", f32=True), nW,
             _dtype_code(q), _stream_handle(stream, q.device))
-    with torch.cuda.device(q.device):
+    with _on_device(q.device):
         rc = lib.fwa_forward(*args)
     if rc != FWA_OK:
         raise FwaError(rc, "fwa_forward")
@@ -147,7 +172,7 @@ def fwa_backward(q, k, v, d_o, heads: int, scale: float, bias=None, mask=None, w
     if workspace is None and need:
         workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
-    with torch.cuda.device(q.device):
+    with _on_device(q.device):
         rc = lib.fwa_backward(*ptrs, dq.data_ptr(), dk.data_ptr(), dv.data_ptr(),
                               None if dbias is None else dbias.data_ptr(), N, L, C, int(heads),
                               float(scale), _dev_ptr(bias, "bias", f32=True),
@@ -168,7 +193,7 @@ def fwa_bias_gather(table, k: int, stream=None):
         raise ValueError("table must be [heads, (2k-1)^2]")
     tp = _dev_ptr(table, "table", f32=True)
     bias = torch.empty((heads, k * k, k * k), dtype=torch.float32, device=table.device)
-    with torch.cuda.device(table.device):
+    with _on_device(table.device):
         rc = lib.fwa_bias_gather(tp, bias.data_ptr(), heads, int(k),
                                  _stream_handle(stream, table.device))
     if rc != FWA_OK:
@@ -185,7 +210,7 @@ def fwa_bias_scatter(dbias, k: int, stream=None):
         raise ValueError("dbias must be [heads, k*k, k*k]")
     dp = _dev_ptr(dbias, "dbias", f32=True)
     dtable = torch.empty((heads, (2 * k - 1) ** 2), dtype=torch.float32, device=dbias.device)
-    with torch.cuda.device(dbias.device):
+    with _on_device(dbias.device):
         rc = lib.fwa_bias_scatter(dp, dtable.data_ptr(), heads, int(k),
                                   _stream_handle(stream, dbias.device))
     if rc != FWA_OK:

@@ -37,7 +37,8 @@ struct FwdGeom {
     FastDiv groups;        // workgroups per window
     uint32_t heads_per_block;
     uint32_t qsplit_log2;  // waves sharing the query blocks of one tile = 1 << qsplit_log2
-    uint32_t xcd_q, xcd_r; // nblocks / 8, nblocks % 8 for the XCD-aware block order
+    uint32_t xcd_remap;    // use the XCD-aware block order
+    uint32_t xcd_q, xcd_r; // nblocks / 8, nblocks % 8 for that order
 };
 
 template <int NB>
@@ -53,7 +54,7 @@ struct TileCoord {
 };
 __device__ __forceinline__ TileCoord tile_of_wave(const FwdGeom& gm, int heads) {
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const uint32_t lb = xcd_logical_block(blockIdx.x, gm.xcd_q, gm.xcd_r);
+    const uint32_t lb = gm.xcd_remap ? xcd_logical_block(blockIdx.x, gm.xcd_q, gm.xcd_r) : blockIdx.x;
     TileCoord t;
     t.w = fastdiv(lb, gm.groups);
     const uint32_t hg = lb - t.w * gm.groups.d;
@@ -318,8 +319,10 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) fwd_f32_kernel(FwdArgs p,
 
 // Heads are 64 B (bf16) slices of a row, so neighbouring heads share 128 B
 // memory lines: the waves of a workgroup take neighbouring heads (all heads of
-// the window when there are at most 4), and the XCD-aware block order keeps
-// the remaining neighbours on one L2.
+// the window when there are at most 4).  Only when line-sharing heads still end
+// up in different workgroups (an odd number of heads per workgroup) is the
+// XCD-aware block order used, to keep them on one L2; otherwise the plain order
+// is faster (it spreads neighbouring windows over all XCDs and HBM channels).
 template <int NB>
 FwdGeom make_geom(const FwdArgs& a, unsigned* grid, unsigned* block) {
     FwdGeom gm;
@@ -331,6 +334,7 @@ FwdGeom make_geom(const FwdArgs& a, unsigned* grid, unsigned* block) {
     gm.heads_per_block = (uint32_t)hpb;
     gm.qsplit_log2 = Tiling<NB>::kQSplitLog2;
     const uint32_t nblocks = (uint32_t)(a.N * groups);
+    gm.xcd_remap = (groups > 1 && hpb % 2 == 1) ? 1u : 0u;
     gm.xcd_q = nblocks / 8u;
     gm.xcd_r = nblocks % 8u;
     *grid = nblocks;
