@@ -19,6 +19,13 @@ int check_shape(int64_t N, int L, int C, int heads, int dtype) {
     return FWA_OK;
 }
 
+// The backward currently covers bf16 tiles that fit one wave (L <= 64).
+int check_backward_support(int L, int dtype) {
+    if (dtype != FWA_BF16) return FWA_ERR_UNSUPPORTED;
+    if (L > fwa::kMaxBackwardL) return FWA_ERR_UNSUPPORTED;
+    return FWA_OK;
+}
+
 int check_mask(int64_t N, const float* mask, int nW) {
     if (mask == nullptr) return FWA_OK;
     if (nW < 1 || N % nW != 0) return FWA_ERR_SHAPE;
@@ -64,7 +71,7 @@ int fwa_forward(const void* q, const void* k, const void* v, void* o, int64_t N,
 }
 
 size_t fwa_backward_workspace_bytes(int64_t N, int L, int C, int heads, int dtype, int want_dbias) {
-    if (check_shape(N, L, C, heads, dtype) != FWA_OK) return 0;
+    if (check_shape(N, L, C, heads, dtype) != FWA_OK || check_backward_support(L, dtype) != FWA_OK) return 0;
     if (!want_dbias || N == 0) return 0;
     return (size_t)fwa::backward_slots(N, heads) * heads * L * L * sizeof(float);
 }
@@ -73,6 +80,8 @@ int fwa_backward(const void* q, const void* k, const void* v, const void* d_o, v
                  float* dbias, int64_t N, int L, int C, int heads, float scale, const float* bias,
                  const float* mask, int nW, int dtype, void* workspace, size_t workspace_bytes, void* stream) {
     int rc = check_shape(N, L, C, heads, dtype);
+    if (rc != FWA_OK) return rc;
+    rc = check_backward_support(L, dtype);
     if (rc != FWA_OK) return rc;
     rc = check_mask(N, mask, nW);
     if (rc != FWA_OK) return rc;

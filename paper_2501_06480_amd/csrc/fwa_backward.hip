@@ -1,7 +1,366 @@
-// Backward kernels (paper Algorithm 2) -- placeholder until implemented.
+// Backward kernels (paper Algorithm 2): dQ, dK, dV (and dBias) from Q, K, V, dO.
+//
+// The paper's kernel recomputes P on chip, forms dV and dP chunk by chunk,
+// then dS, then re-reads Q and K for dQ and dK.  With a head width of 32 the
+// whole (window, head) problem fits in one wave's registers, so Q, K, V, dO
+// are read from HBM once (the second pass over Q and K of the paper's loop
+// is served on chip) and P, dP, dS never leave the registers.
+//
+// One wave owns one (window, head) tile and walks windows of its head.  Per
+// block of 16 queries ("query on the lane": lane (g, n) holds row
+// i = 16 qb + n and columns j = 16 jb + 4g + r, the forward's layout):
+//
+//   S^T  = K Q^T   -> scores, softmax (row max / sum over the 4 lanes sharing n), P
+//   dP^T = V dO^T  -> delta_i = sum_j P_ij dP_ij,  dS = P (dP - delta)
+//   dQ^T = K^T dS^T: contraction over keys, dS is already a B operand; K^T is
+//                    loaded as channel pairs and split into even/odd channels
+//   dBias += dS    (fp32, before any rounding)
+//
+// dV = P^T dO and dK = dS^T Q contract over the queries and need P and dS with
+// the key on the lane instead.  A 16x16 block is moved to that layout by the
+// matrix core itself: used as the A operand against an identity B operand it
+// comes back as D[4g + r][n] = X[i0 + 4g + r][j0 + n], which is exactly the B
+// operand (k-slots = queries) of the products above.  No LDS, no barriers.
+//
+// Precision: P and dS enter the matrix cores as bf16.  To keep the results
+// within half a bf16 ulp of the exact value they are split into a high and a
+// low bf16 part (x = hi + lo to 16 bits) and every product that consumes them
+// is issued twice; both parts pass the identity product unchanged.
+//
+// dBias: each wave adds the dS of its windows into a private LDS array, writes
+// it to its slot of the workspace at the end, and a second kernel adds the
+// slots in a fixed order, so the result is bit-reproducible.
+#include "fwa_device.h"
 #include "fwa_internal.h"
+
 namespace fwa {
-int backward_slots(long long, int) { return 1; }
-hipError_t launch_backward_bf16(const BwdArgs&, hipStream_t) { return hipErrorNotSupported; }
+namespace {
+
+typedef short bf16x4 __attribute__((ext_vector_type(4)));  // raw bf16 bits, operand of the K=16 matrix op
+
+struct BwdGeom {
+    FastDiv groups;  // workgroups per window position
+    uint32_t heads_per_block;
+    uint32_t slots;  // workgroups along the window axis; window w is handled by slot w % slots
+};
+
+__device__ __forceinline__ f32x4 mfma16(bf16x4 a, bf16x4 b, f32x4 c) {
+    return __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a, b, c, 0, 0, 0);
+}
+__device__ __forceinline__ bf16x4 as_bf16x4(uint2 u) { return __builtin_bit_cast(bf16x4, u); }
+
+// x = hi + lo with hi the upper 16 bits of x (a bf16 by truncation) and lo the
+// remainder rounded to bf16: together 16 significant bits.
+__device__ __forceinline__ void split_hi_lo(const f32x4& x, bf16x4& hi, bf16x4& lo) {
+    uint32_t u[4];
+    float rem[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        const float xc = x[c];
+        u[c] = __builtin_bit_cast(uint32_t, xc);
+        rem[c] = xc - __builtin_bit_cast(float, u[c] & 0xffff0000u);
+    }
+    uint2 h, l;
+    h.x = (u[0] >> 16) | (u[1] & 0xffff0000u);
+    h.y = (u[2] >> 16) | (u[3] & 0xffff0000u);
+    l.x = pack_bf16(rem[0], rem[1]);
+    l.y = pack_bf16(rem[2], rem[3]);
+    hi = as_bf16x4(h);
+    lo = as_bf16x4(l);
+}
+// fp32 values that are exactly bf16 (results of an identity product) -> packed bf16
+__device__ __forceinline__ bf16x4 pack_exact(const f32x4& x) {
+    uint32_t u[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        const float xc = x[c];
+        u[c] = __builtin_bit_cast(uint32_t, xc);
+    }
+    uint2 h;
+    h.x = (u[0] >> 16) | (u[1] & 0xffff0000u);
+    h.y = (u[2] >> 16) | (u[3] & 0xffff0000u);
+    return as_bf16x4(h);
+}
+// Channel pairs of 4 rows -> even-channel and odd-channel operand (4 k-slots each)
+__device__ __forceinline__ void split_pairs4(const uint32_t (&d)[4], bf16x4& even, bf16x4& odd) {
+    uint2 e, o;
+    e.x = (d[0] & 0xffffu) | (d[1] << 16);
+    e.y = (d[2] & 0xffffu) | (d[3] << 16);
+    o.x = (d[0] >> 16) | (d[1] & 0xffff0000u);
+    o.y = (d[2] >> 16) | (d[3] & 0xffff0000u);
+    even = as_bf16x4(e);
+    odd = as_bf16x4(o);
+}
+
+template <int NB, bool BM, bool DB>
+__global__ void __launch_bounds__(64 * kWavesPerBlock, 2) bwd_bf16_kernel(BwdArgs p, BwdGeom gm) {
+    extern __shared__ __attribute__((aligned(16))) float lds_all[];
+    const int lane = threadIdx.x & 63;
+    const int n = lane & 15, g = lane >> 4;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const uint32_t slot = fastdiv(blockIdx.x, gm.groups);
+    const uint32_t hg = blockIdx.x - slot * gm.groups.d;
+    const uint32_t h = hg * gm.heads_per_block + wave;
+    if (h >= (uint32_t)p.heads) return;  // wave-uniform; the kernel has no barriers
+
+    // dBias accumulator of this wave: element ((qb*NB + jb)*4 + r) of lane l sits at
+    // index that*64 + l, so every lane only ever touches its own addresses.
+    float* const dbacc = lds_all + (size_t)wave * (NB * NB * 4 * 64) + lane;
+    if (DB) {
+#pragma unroll
+        for (int e = 0; e < NB * NB * 4; ++e) dbacc[e * 64] = 0.f;
+    }
+
+    const int L = p.L;
+    const uint32_t row_bytes = (uint32_t)p.C * 2u;
+    const uint32_t tile_bytes = (uint32_t)(L - 1) * row_bytes + 2u * kHeadDim;
+    const uint32_t off_row = (uint32_t)n * row_bytes + 16u * g;  // 16 B of row n (plus a block offset)
+    const uint32_t off_col = 4u * g * row_bytes + 4u * n;        // channel pair n of row 4g (plus row offset)
+    const float sl2 = p.scale * kLog2e;
+    const uint32_t off_b = ((uint32_t)n * L + 4u * g) * 4u;      // B[n][4g] (plus block offsets)
+    __amdgpu_buffer_rsrc_t rb = make_rsrc(nullptr, 0);
+    if (BM && p.bias) rb = make_rsrc(p.bias + (size_t)h * L * L, (uint32_t)L * L * 4u);
+
+    // identity B operand: slot e of lane (g, n) is 1.0 iff 4g + e == n
+    uint2 idu;
+    idu.x = (4 * g + 0 == n ? 0x3f80u : 0u) | (4 * g + 1 == n ? 0x3f800000u : 0u);
+    idu.y = (4 * g + 2 == n ? 0x3f80u : 0u) | (4 * g + 3 == n ? 0x3f800000u : 0u);
+    const bf16x4 ident = as_bf16x4(idu);
+    const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+
+    for (long long w = slot; w < p.N; w += gm.slots) {
+        const size_t tile = ((size_t)w * L * p.C + (size_t)h * kHeadDim) * 2u;
+        const __amdgpu_buffer_rsrc_t rq = make_rsrc((const char*)p.q + tile, tile_bytes);
+        const __amdgpu_buffer_rsrc_t rk = make_rsrc((const char*)p.k + tile, tile_bytes);
+        const __amdgpu_buffer_rsrc_t rv = make_rsrc((const char*)p.v + tile, tile_bytes);
+        const __amdgpu_buffer_rsrc_t rg = make_rsrc((const char*)p.d_o + tile, tile_bytes);
+        const __amdgpu_buffer_rsrc_t rdq = make_rsrc((char*)p.dq + tile, tile_bytes);
+        const __amdgpu_buffer_rsrc_t rdk = make_rsrc((char*)p.dk + tile, tile_bytes);
+        const __amdgpu_buffer_rsrc_t rdv = make_rsrc((char*)p.dv + tile, tile_bytes);
+        __amdgpu_buffer_rsrc_t rm = make_rsrc(nullptr, 0);
+        if (BM && p.mask) rm = make_rsrc(p.mask + (size_t)(w % p.nW) * L * L, (uint32_t)L * L * 4u);
+
+        // Row operands (contraction over the 32 channels): lane (g, n) = X[16 b + n][8g .. 8g+7]
+        bf16x8 krow[NB], vrow[NB], qrow[NB], grow[NB];
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            krow[b] = as_bf16x8(__builtin_amdgcn_raw_buffer_load_b128(rk, off_row + 16 * b * row_bytes, 0, 0));
+            qrow[b] = as_bf16x8(__builtin_amdgcn_raw_buffer_load_b128(rq, off_row + 16 * b * row_bytes, 0, 0));
+        }
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            vrow[b] = as_bf16x8(__builtin_amdgcn_raw_buffer_load_b128(rv, off_row + 16 * b * row_bytes, 0, 0));
+            grow[b] = as_bf16x8(__builtin_amdgcn_raw_buffer_load_b128(rg, off_row + 16 * b * row_bytes, 0, 0));
+        }
+        // Column operands (contraction over the 16 rows of a block): lane (g, m) =
+        // X[16 b + 4g + e][channel 2m resp. 2m+1], e = 0..3
+        bf16x4 kcol[NB][2], gcol[NB][2], qcol[NB][2];
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            uint32_t dk_[4], dg_[4], dq_[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const uint32_t off = off_col + (16 * b + e) * row_bytes;
+                dk_[e] = __builtin_amdgcn_raw_buffer_load_b32(rk, off, 0, 0);
+                dg_[e] = __builtin_amdgcn_raw_buffer_load_b32(rg, off, 0, 0);
+                dq_[e] = __builtin_amdgcn_raw_buffer_load_b32(rq, off, 0, 0);
+            }
+            split_pairs4(dk_, kcol[b][0], kcol[b][1]);
+            split_pairs4(dg_, gcol[b][0], gcol[b][1]);
+            split_pairs4(dq_, qcol[b][0], qcol[b][1]);
+        }
+
+        f32x4 ve[NB], vo[NB], ke[NB], ko[NB];  // dV, dK of key block jb: [16 jb + n][2 (4g + r) (+1)]
+#pragma unroll
+        for (int jb = 0; jb < NB; ++jb) ve[jb] = vo[jb] = ke[jb] = ko[jb] = zero;
+
+#pragma unroll
+        for (int qb = 0; qb < NB; ++qb) {
+            f32x4 s[NB], dp[NB];
+#pragma unroll
+            for (int jb = 0; jb < NB; ++jb) {
+                s[jb] = mfma_bf16(krow[jb], qrow[qb], zero);   // S[16 qb + n][16 jb + 4g + r]
+                dp[jb] = mfma_bf16(vrow[jb], grow[qb], zero);  // dP at the same positions
+            }
+#pragma unroll
+            for (int jb = 0; jb < NB; ++jb)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    float x = s[jb][r] * sl2;
+                    if (BM) {
+                        const uint32_t off = off_b + (uint32_t)(16 * qb) * L * 4u + (16 * jb + r) * 4;
+                        const float add = load_f32(rb, off) + load_f32(rm, off);
+                        x = fmaf(add, kLog2e, x);
+                    }
+                    s[jb][r] = x;
+                }
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+                if (16 * (NB - 1) + 4 * g + r >= L) s[NB - 1][r] = -INFINITY;
+            float m = s[0][0];
+#pragma unroll
+            for (int jb = 0; jb < NB; ++jb) {
+                m = fmaxf(fmaxf(m, s[jb][0]), s[jb][1]);
+                m = fmaxf(fmaxf(m, s[jb][2]), s[jb][3]);
+            }
+            m = max_over_g(m);
+            float sum = 0.f;
+#pragma unroll
+            for (int jb = 0; jb < NB; ++jb)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const float e = __builtin_amdgcn_exp2f(s[jb][r] - m);
+                    s[jb][r] = e;
+                    sum += e;
+                }
+            sum = sum_over_g(sum);
+            const float inv = __builtin_amdgcn_rcpf(sum);
+            float delta = 0.f;
+#pragma unroll
+            for (int jb = 0; jb < NB; ++jb)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    s[jb][r] *= inv;  // P
+                    delta = fmaf(s[jb][r], dp[jb][r], delta);
+                }
+            delta = sum_over_g(delta);
+#pragma unroll
+            for (int jb = 0; jb < NB; ++jb)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    dp[jb][r] = s[jb][r] * (dp[jb][r] - delta);  // dS
+                    if (DB) atomicAdd(&dbacc[((qb * NB + jb) * 4 + r) * 64], dp[jb][r]);
+                }
+
+            f32x4 qe = zero, qo = zero;  // dQ[16 qb + n][2 (4g + r) (+1)]
+#pragma unroll
+            for (int jb = 0; jb < NB; ++jb) {
+                bf16x4 p_hi, p_lo, ds_hi, ds_lo;
+                split_hi_lo(s[jb], p_hi, p_lo);
+                split_hi_lo(dp[jb], ds_hi, ds_lo);
+                qe = mfma16(kcol[jb][0], ds_hi, qe);
+                qe = mfma16(kcol[jb][0], ds_lo, qe);
+                qo = mfma16(kcol[jb][1], ds_hi, qo);
+                qo = mfma16(kcol[jb][1], ds_lo, qo);
+                // the block with the key on the lane: t[r] = X[16 qb + 4g + r][16 jb + n]
+                const bf16x4 tp_hi = pack_exact(mfma16(p_hi, ident, zero));
+                const bf16x4 tp_lo = pack_exact(mfma16(p_lo, ident, zero));
+                const bf16x4 ts_hi = pack_exact(mfma16(ds_hi, ident, zero));
+                const bf16x4 ts_lo = pack_exact(mfma16(ds_lo, ident, zero));
+                ve[jb] = mfma16(gcol[qb][0], tp_hi, ve[jb]);
+                ve[jb] = mfma16(gcol[qb][0], tp_lo, ve[jb]);
+                vo[jb] = mfma16(gcol[qb][1], tp_hi, vo[jb]);
+                vo[jb] = mfma16(gcol[qb][1], tp_lo, vo[jb]);
+                ke[jb] = mfma16(qcol[qb][0], ts_hi, ke[jb]);
+                ke[jb] = mfma16(qcol[qb][0], ts_lo, ke[jb]);
+                ko[jb] = mfma16(qcol[qb][1], ts_hi, ko[jb]);
+                ko[jb] = mfma16(qcol[qb][1], ts_lo, ko[jb]);
+            }
+            u32x4 out;
+            out.x = pack_bf16(qe[0] * p.scale, qo[0] * p.scale);
+            out.y = pack_bf16(qe[1] * p.scale, qo[1] * p.scale);
+            out.z = pack_bf16(qe[2] * p.scale, qo[2] * p.scale);
+            out.w = pack_bf16(qe[3] * p.scale, qo[3] * p.scale);
+            __builtin_amdgcn_raw_buffer_store_b128(out, rdq, off_row + 16 * qb * row_bytes, 0, 0);
+        }
+#pragma unroll
+        for (int jb = 0; jb < NB; ++jb) {
+            u32x4 ov, ok;
+            ov.x = pack_bf16(ve[jb][0], vo[jb][0]);
+            ov.y = pack_bf16(ve[jb][1], vo[jb][1]);
+            ov.z = pack_bf16(ve[jb][2], vo[jb][2]);
+            ov.w = pack_bf16(ve[jb][3], vo[jb][3]);
+            ok.x = pack_bf16(ke[jb][0] * p.scale, ko[jb][0] * p.scale);
+            ok.y = pack_bf16(ke[jb][1] * p.scale, ko[jb][1] * p.scale);
+            ok.z = pack_bf16(ke[jb][2] * p.scale, ko[jb][2] * p.scale);
+            ok.w = pack_bf16(ke[jb][3] * p.scale, ko[jb][3] * p.scale);
+            __builtin_amdgcn_raw_buffer_store_b128(ov, rdv, off_row + 16 * jb * row_bytes, 0, 0);
+            __builtin_amdgcn_raw_buffer_store_b128(ok, rdk, off_row + 16 * jb * row_bytes, 0, 0);
+        }
+    }
+
+    if (DB) {
+        float* dst = p.partial + ((size_t)slot * p.heads + h) * L * L;
+#pragma unroll
+        for (int qb = 0; qb < NB; ++qb)
+#pragma unroll
+            for (int jb = 0; jb < NB; ++jb)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int i = 16 * qb + n, j = 16 * jb + 4 * g + r;
+                    if (i < L && j < L) dst[(size_t)i * L + j] = dbacc[((qb * NB + jb) * 4 + r) * 64];
+                }
+    }
+}
+
+// dbias[e] = sum over slots of partial[slot][e], slots added in index order.
+__global__ void dbias_reduce_kernel(const float* __restrict__ partial, float* __restrict__ dbias, int slots,
+                                    size_t count) {
+    const size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= count) return;
+    float acc = 0.f;
+    for (int s = 0; s < slots; ++s) acc += partial[(size_t)s * count + e];
+    dbias[e] = acc;
+}
+
+template <int NB, bool BM, bool DB>
+hipError_t launch_one(const BwdArgs& a, const BwdGeom& gm, unsigned grid, unsigned block, hipStream_t st) {
+    const size_t lds = DB ? (size_t)(block / 64) * NB * NB * 4 * 64 * sizeof(float) : 0;
+    if (lds > 64 * 1024) {
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&bwd_bf16_kernel<NB, BM, DB>),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL((bwd_bf16_kernel<NB, BM, DB>), dim3(grid), dim3(block), lds, st, a, gm);
+    return hipGetLastError();
+}
+
+template <int NB>
+hipError_t launch_bwd_nb(const BwdArgs& a, hipStream_t st) {
+    BwdGeom gm;
+    int hpb = kWavesPerBlock;
+    if (a.heads < hpb) hpb = a.heads;
+    const uint32_t groups = (uint32_t)((a.heads + hpb - 1) / hpb);
+    gm.groups = make_fastdiv(groups);
+    gm.heads_per_block = (uint32_t)hpb;
+    gm.slots = (uint32_t)a.slots;
+    const unsigned grid = gm.slots * groups, block = 64u * (unsigned)hpb;
+    const bool bm = a.bias || a.mask, db = a.dbias != nullptr;
+    hipError_t e;
+    if (bm)
+        e = db ? launch_one<NB, true, true>(a, gm, grid, block, st) : launch_one<NB, true, false>(a, gm, grid, block, st);
+    else
+        e = db ? launch_one<NB, false, true>(a, gm, grid, block, st) : launch_one<NB, false, false>(a, gm, grid, block, st);
+    if (e != hipSuccess || !db) return e;
+    const size_t count = (size_t)a.heads * a.L * a.L;
+    hipLaunchKernelGGL(dbias_reduce_kernel, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, st, a.partial,
+                       a.dbias, a.slots, count);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+// Workgroups along the window axis.  Enough to fill the chip (two waves per
+// SIMD), few enough that the per-slot dBias partial sums stay small.
+int backward_slots(long long N, int heads) {
+    const int hpb = heads < kWavesPerBlock ? heads : kWavesPerBlock;
+    const int groups = (heads + hpb - 1) / hpb;
+    long long slots = (256 * 8 / hpb + groups - 1) / groups;  // ~8 waves per CU over 256 CUs
+    if (slots > N) slots = N;
+    if (slots < 1) slots = 1;
+    return (int)slots;
+}
+
+hipError_t launch_backward_bf16(const BwdArgs& a, hipStream_t s) {
+    switch ((a.L + 15) / 16) {
+        case 1: return launch_bwd_nb<1>(a, s);
+        case 2: return launch_bwd_nb<2>(a, s);
+        case 3: return launch_bwd_nb<3>(a, s);
+        case 4: return launch_bwd_nb<4>(a, s);
+        default: return hipErrorNotSupported;
+    }
+}
+
 hipError_t launch_backward_f32(const BwdArgs&, hipStream_t) { return hipErrorNotSupported; }
+
 }  // namespace fwa

@@ -10,6 +10,7 @@ namespace fwa {
 
 constexpr int kHeadDim = 32;   // the only supported head width
 constexpr int kMaxL = 256;     // 16 key blocks of 16 rows
+constexpr int kMaxBackwardL = 64;  // backward: the whole tile in one wave
 constexpr int kWavesPerBlock = 4;
 
 struct FwdArgs {

@@ -1,0 +1,167 @@
+"""GPU parity of fwa_backward (and the bias scatter) against the fp64 oracle.
+
+dQ, dK, dV are bf16 outputs (one final rounding) and dBias is fp32; all four
+are held to the benchmark's bf16 bound of 1e-2 max-abs against the oracle.
+"""
+import numpy as np
+import pytest
+
+from paper_2501_06480_amd import synth
+from gpu_util import TOL, f32_device, max_abs, to_device, to_f64
+
+pytestmark = pytest.mark.gpu
+
+
+def run_backward(w, x, bias_np, mask_np, want_dbias=True):
+    import torch
+    import paper_2501_06480_amd as fwa
+    q, k, v, g = (to_device(x, w, n) for n in ("q", "k", "v", "d_o"))
+    out = fwa.fwa_backward(q, k, v, g, w.heads, w.scale, f32_device(bias_np), f32_device(mask_np),
+                           want_dbias=want_dbias)
+    torch.cuda.synchronize()
+    return out
+
+
+def check_backward(oracle, w, bias_np, mask_np, label, want_dbias=True):
+    x = synth.draw(w)
+    dq, dk, dv, db = run_backward(w, x, bias_np, mask_np, want_dbias)
+    ref = oracle.backward(x["q"], x["k"], x["v"], x["d_o"], w.heads, w.scale, bias_np, mask_np)
+    errs = {}
+    for name, got, want in (("dq", dq, ref[0]), ("dk", dk, ref[1]), ("dv", dv, ref[2])):
+        got = to_f64(got)
+        assert np.isfinite(got).all(), name
+        errs[name] = (max_abs(got, want), float(np.abs(want).max()))
+    if want_dbias:
+        got = to_f64(db)
+        assert np.isfinite(got).all()
+        errs["dbias"] = (max_abs(got, ref[3]), float(np.abs(ref[3]).max()))
+    else:
+        assert db is None
+    print(label, " ".join(f"{k}: err={e:.2e} (max|ref|={m:.2f})" for k, (e, m) in errs.items()), flush=True)
+    for name, (e, _) in errs.items():
+        assert e <= TOL["bf16"], (label, name, e)
+
+
+@pytest.mark.parametrize("stage,n_small", [(1, 128), (3, 16)])
+def test_config5_shapes_small(oracle, stage, n_small):
+    w = synth.swin_t_stage(stage, shifted=True, backward=True).with_N(n_small)
+    x = synth.draw(w)
+    bias = oracle.bias_gather(x["table"], w.k).astype(np.float32)
+    check_backward(oracle, w, bias, x["mask"], w.name)
+
+
+@pytest.mark.parametrize("stage", [2, 4])
+def test_other_stages_small(oracle, stage):
+    w = synth.swin_t_stage(stage, shifted=True, backward=True)
+    w = w.with_N(max(w.nW, 1) * 2)
+    x = synth.draw(w)
+    bias = oracle.bias_gather(x["table"], w.k).astype(np.float32)
+    check_backward(oracle, w, bias, x["mask"], w.name)
+
+
+@pytest.mark.parametrize("L", [1, 2, 5, 15, 16, 17, 31, 32, 33, 47, 48, 49, 50, 63, 64])
+@pytest.mark.parametrize("use_bm", [False, True])
+def test_window_lengths_up_to_64(oracle, L, use_bm):
+    w = synth.Workload(f"bwd_L{L}", 7, L, 96, 3, "bf16", 5000 + L, 0, backward=True)
+    bias = synth.normal((3, L, L), 11 + L, 0.5) if use_bm else None
+    mask = None
+    if use_bm:
+        w = w.with_N(6)
+        mask = np.where(synth.rng(3 + L).random((3, L, L)) < 0.2, -100.0, 0.0).astype(np.float32)
+        mask[:, np.arange(L), np.arange(L)] = 0.0
+    check_backward(oracle, w, bias, mask, f"L={L} bm={use_bm}")
+
+
+def test_without_dbias_and_many_windows_per_wave(oracle):
+    """More windows than resident waves: every wave loops over several windows."""
+    w = synth.Workload("bwd_loop", 3000, 49, 32, 1, "bf16", 5100, 7, backward=True)
+    check_backward(oracle, w, None, None, "N=3000 heads=1", want_dbias=False)
+    w = synth.Workload("bwd_loop_db", 1500, 49, 64, 2, "bf16", 5101, 7, backward=True)
+    check_backward(oracle, w, None, None, "N=1500 heads=2 dbias", want_dbias=True)
+
+
+def test_backward_is_bit_reproducible():
+    import torch
+    import paper_2501_06480_amd as fwa
+    w = synth.swin_t_stage(2, shifted=True, backward=True).with_N(256)
+    x = synth.draw(w)
+    q, k, v, g = (to_device(x, w, n) for n in ("q", "k", "v", "d_o"))
+    bias = fwa.fwa_bias_gather(f32_device(x["table"]), 7)
+    mask = f32_device(x["mask"])
+    a = fwa.fwa_backward(q, k, v, g, w.heads, w.scale, bias, mask, want_dbias=True)
+    b = fwa.fwa_backward(q, k, v, g, w.heads, w.scale, bias, mask, want_dbias=True)
+    torch.cuda.synchronize()
+    for s, t in zip(a[:3], b[:3]):
+        assert torch.equal(s.view(torch.int16), t.view(torch.int16))
+    assert torch.equal(a[3], b[3])
+
+
+def test_guard_bands_around_outputs_stay_untouched():
+    import torch
+    from paper_2501_06480_amd import binding
+    lib = binding.load_library()
+    N, L, C, heads = 5, 49, 96, 3
+    w = synth.Workload("guard", N, L, C, heads, "bf16", 5200, 7, backward=True)
+    x = synth.draw(w)
+    q, k, v, g = (to_device(x, w, n) for n in ("q", "k", "v", "d_o"))
+    pad, n = 2048, N * L * C
+    bufs = [torch.full((pad + n + pad,), 3.0, dtype=torch.bfloat16, device="cuda") for _ in range(3)]
+    outs = [b[pad:pad + n] for b in bufs]
+    rc = lib.fwa_backward(q.data_ptr(), k.data_ptr(), v.data_ptr(), g.data_ptr(), outs[0].data_ptr(),
+                          outs[1].data_ptr(), outs[2].data_ptr(), None, N, L, C, heads, w.scale, None, None, 0,
+                          binding.FWA_BF16, None, 0, torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    assert rc == 0
+    for b in bufs:
+        assert (b[:pad] == 3.0).all() and (b[-pad:] == 3.0).all()
+        assert not (b[pad:pad + n] == 3.0).all()
+
+
+def test_unsupported_backward_cases_are_rejected():
+    import torch
+    import paper_2501_06480_amd as fwa
+    from paper_2501_06480_amd import binding
+    q = torch.zeros((2, 144, 128), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(fwa.FwaError) as e:
+        fwa.fwa_backward(q, q.clone(), q.clone(), q.clone(), 4, 0.1)
+    assert e.value.code == binding.FWA_ERR_UNSUPPORTED
+    q = torch.zeros((2, 49, 96), dtype=torch.float32, device="cuda")
+    with pytest.raises(fwa.FwaError) as e:
+        fwa.fwa_backward(q, q.clone(), q.clone(), q.clone(), 3, 0.1)
+    assert e.value.code == binding.FWA_ERR_UNSUPPORTED
+
+
+def test_empty_batch_zeroes_dbias():
+    import torch
+    import paper_2501_06480_amd as fwa
+    q = torch.empty((0, 49, 96), dtype=torch.bfloat16, device="cuda")
+    dq, dk, dv, db = fwa.fwa_backward(q, q.clone(), q.clone(), q.clone(), 3, 0.1, want_dbias=True)
+    torch.cuda.synchronize()
+    assert dq.shape == (0, 49, 96) and db.shape == (3, 49, 49) and (db == 0).all()
+
+
+@pytest.mark.parametrize("k", [1, 2, 7, 12, 16])
+def test_bias_scatter_matches_oracle(oracle, k):
+    import torch
+    import paper_2501_06480_amd as fwa
+    heads, L = 3, k * k
+    g = synth.normal((heads, L, L), 60 + k)
+    got = fwa.fwa_bias_scatter(f32_device(g), k)
+    again = fwa.fwa_bias_scatter(f32_device(g), k)
+    torch.cuda.synchronize()
+    want = oracle.bias_scatter(g, k)
+    assert max_abs(to_f64(got), want) <= 1e-4 * max(1.0, np.abs(want).max())
+    assert torch.equal(got, again)
+
+
+def test_full_size_config5_stage1(oracle):
+    """Config 5 stage 1 at full size (N = 8192) against the whole oracle backward."""
+    w = synth.swin_t_stage(1, shifted=True, backward=True)
+    x = synth.draw(w)
+    bias = oracle.bias_gather(x["table"], w.k).astype(np.float32)
+    dq, dk, dv, db = run_backward(w, x, bias, x["mask"])
+    ref = oracle.backward(x["q"], x["k"], x["v"], x["d_o"], w.heads, w.scale, bias, x["mask"])
+    for name, got, want in (("dq", dq, ref[0]), ("dk", dk, ref[1]), ("dv", dv, ref[2]), ("dbias", db, ref[3])):
+        err = max_abs(to_f64(got), want)
+        print(f"config 5 stage 1 full size {name}: err={err:.3e} max|ref|={np.abs(want).max():.2f}", flush=True)
+        assert err <= TOL["bf16"], name
