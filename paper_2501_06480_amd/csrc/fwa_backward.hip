@@ -12,15 +12,17 @@
 //
 //   S^T  = K Q^T   -> scores, softmax (row max / sum over the 4 lanes sharing n), P
 //   dP^T = V dO^T  -> delta_i = sum_j P_ij dP_ij,  dS = P (dP - delta)
-//   dQ^T = K^T dS^T: contraction over keys, dS is already a B operand; K^T is
-//                    loaded as channel pairs and split into even/odd channels
+//   dQ^T = K^T dS^T: contraction over keys, dS is already a B operand
 //   dBias += dS    (fp32, before any rounding)
 //
 // dV = P^T dO and dK = dS^T Q contract over the queries and need P and dS with
 // the key on the lane instead.  A 16x16 block is moved to that layout by the
 // matrix core itself: used as the A operand against an identity B operand it
 // comes back as D[4g + r][n] = X[i0 + 4g + r][j0 + n], which is exactly the B
-// operand (k-slots = queries) of the products above.  No LDS, no barriers.
+// operand (k-slots = queries) of the products above.  The same trick with a 0/1
+// matrix that picks the even (odd) channels turns the row operands of K, Q, dO
+// into the A operands K^T, Q^T, dO^T, so every tensor is loaded once, as rows,
+// with 16-byte loads.  No LDS tiles, no barriers.
 //
 // Precision: P and dS enter the matrix cores as bf16.  To keep the results
 // within half a bf16 ulp of the exact value they are split into a high and a
@@ -61,8 +63,8 @@ __device__ __forceinline__ void split_hi_lo(const f32x4& x, bf16x4& hi, bf16x4& 
         rem[c] = xc - __builtin_bit_cast(float, u[c] & 0xffff0000u);
     }
     uint2 h, l;
-    h.x = (u[0] >> 16) | (u[1] & 0xffff0000u);
-    h.y = (u[2] >> 16) | (u[3] & 0xffff0000u);
+    h.x = upper_halves(u[0], u[1]);
+    h.y = upper_halves(u[2], u[3]);
     l.x = pack_bf16(rem[0], rem[1]);
     l.y = pack_bf16(rem[2], rem[3]);
     hi = as_bf16x4(h);
@@ -77,21 +79,10 @@ __device__ __forceinline__ bf16x4 pack_exact(const f32x4& x) {
         u[c] = __builtin_bit_cast(uint32_t, xc);
     }
     uint2 h;
-    h.x = (u[0] >> 16) | (u[1] & 0xffff0000u);
-    h.y = (u[2] >> 16) | (u[3] & 0xffff0000u);
+    h.x = upper_halves(u[0], u[1]);
+    h.y = upper_halves(u[2], u[3]);
     return as_bf16x4(h);
 }
-// Channel pairs of 4 rows -> even-channel and odd-channel operand (4 k-slots each)
-__device__ __forceinline__ void split_pairs4(const uint32_t (&d)[4], bf16x4& even, bf16x4& odd) {
-    uint2 e, o;
-    e.x = (d[0] & 0xffffu) | (d[1] << 16);
-    e.y = (d[2] & 0xffffu) | (d[3] << 16);
-    o.x = (d[0] >> 16) | (d[1] & 0xffff0000u);
-    o.y = (d[2] >> 16) | (d[3] & 0xffff0000u);
-    even = as_bf16x4(e);
-    odd = as_bf16x4(o);
-}
-
 template <int NB, bool BM, bool DB>
 __global__ void __launch_bounds__(64 * kWavesPerBlock, 2) bwd_bf16_kernel(BwdArgs p, BwdGeom gm) {
     extern __shared__ __attribute__((aligned(16))) float lds_all[];
@@ -103,19 +94,19 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, 2) bwd_bf16_kernel(BwdArg
     const uint32_t h = hg * gm.heads_per_block + wave;
     if (h >= (uint32_t)p.heads) return;  // wave-uniform; the kernel has no barriers
 
-    // dBias accumulator of this wave: element ((qb*NB + jb)*4 + r) of lane l sits at
-    // index that*64 + l, so every lane only ever touches its own addresses.
-    float* const dbacc = lds_all + (size_t)wave * (NB * NB * 4 * 64) + lane;
+    // dBias accumulator of this wave: the 4 values of block (qb, jb) of lane l form one
+    // float4 at index (qb*NB + jb)*64 + l, so every lane only ever touches its own
+    // addresses (plain read-modify-write, no atomics, no barriers, no bank conflicts).
+    f32x4* const dbacc = reinterpret_cast<f32x4*>(lds_all) + (size_t)wave * (NB * NB * 64) + lane;
     if (DB) {
 #pragma unroll
-        for (int e = 0; e < NB * NB * 4; ++e) dbacc[e * 64] = 0.f;
+        for (int e = 0; e < NB * NB; ++e) dbacc[e * 64] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
 
     const int L = p.L;
     const uint32_t row_bytes = (uint32_t)p.C * 2u;
     const uint32_t tile_bytes = (uint32_t)(L - 1) * row_bytes + 2u * kHeadDim;
     const uint32_t off_row = (uint32_t)n * row_bytes + 16u * g;  // 16 B of row n (plus a block offset)
-    const uint32_t off_col = 4u * g * row_bytes + 4u * n;        // channel pair n of row 4g (plus row offset)
     const float sl2 = p.scale * kLog2e;
     const uint32_t off_b = ((uint32_t)n * L + 4u * g) * 4u;      // B[n][4g] (plus block offsets)
     __amdgpu_buffer_rsrc_t rb = make_rsrc(nullptr, 0);
@@ -126,6 +117,16 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, 2) bwd_bf16_kernel(BwdArg
     idu.x = (4 * g + 0 == n ? 0x3f80u : 0u) | (4 * g + 1 == n ? 0x3f800000u : 0u);
     idu.y = (4 * g + 2 == n ? 0x3f80u : 0u) | (4 * g + 3 == n ? 0x3f800000u : 0u);
     const bf16x4 ident = as_bf16x4(idu);
+    // channel-selecting B operands of the K=32 matrix op: slot e of lane (g, n) stands for
+    // channel 8g + e; "even" picks channel 2n into column n, "odd" picks channel 2n + 1
+    u32x4 se = {0u, 0u, 0u, 0u}, so = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const uint32_t one = (e & 1) ? 0x3f800000u : 0x3f80u;
+        if (8 * g + e == 2 * n) se[e >> 1] |= one;
+        if (8 * g + e == 2 * n + 1) so[e >> 1] |= one;
+    }
+    const bf16x8 sel_even = as_bf16x8(se), sel_odd = as_bf16x8(so);
     const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
 
     for (long long w = slot; w < p.N; w += gm.slots) {
@@ -153,21 +154,14 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, 2) bwd_bf16_kernel(BwdArg
             grow[b] = as_bf16x8(__builtin_amdgcn_raw_buffer_load_b128(rg, off_row + 16 * b * row_bytes, 0, 0));
         }
         // Column operands (contraction over the 16 rows of a block): lane (g, m) =
-        // X[16 b + 4g + e][channel 2m resp. 2m+1], e = 0..3
-        bf16x4 kcol[NB][2], gcol[NB][2], qcol[NB][2];
+        // X[16 b + 4g + e][channel 2m resp. 2m+1], e = 0..3.  They are the row operands
+        // seen through the matrix core: rows times a 0/1 matrix that picks the even (odd)
+        // channels returns exactly these values in the accumulator layout.
+        bf16x4 kcol[NB][2];
 #pragma unroll
         for (int b = 0; b < NB; ++b) {
-            uint32_t dk_[4], dg_[4], dq_[4];
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const uint32_t off = off_col + (16 * b + e) * row_bytes;
-                dk_[e] = __builtin_amdgcn_raw_buffer_load_b32(rk, off, 0, 0);
-                dg_[e] = __builtin_amdgcn_raw_buffer_load_b32(rg, off, 0, 0);
-                dq_[e] = __builtin_amdgcn_raw_buffer_load_b32(rq, off, 0, 0);
-            }
-            split_pairs4(dk_, kcol[b][0], kcol[b][1]);
-            split_pairs4(dg_, gcol[b][0], gcol[b][1]);
-            split_pairs4(dq_, qcol[b][0], qcol[b][1]);
+            kcol[b][0] = pack_exact(mfma_bf16(krow[b], sel_even, zero));
+            kcol[b][1] = pack_exact(mfma_bf16(krow[b], sel_odd, zero));
         }
 
         f32x4 ve[NB], vo[NB], ke[NB], ko[NB];  // dV, dK of key block jb: [16 jb + n][2 (4g + r) (+1)]
@@ -176,6 +170,10 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, 2) bwd_bf16_kernel(BwdArg
 
 #pragma unroll
         for (int qb = 0; qb < NB; ++qb) {
+            const bf16x4 gcol0 = pack_exact(mfma_bf16(grow[qb], sel_even, zero));
+            const bf16x4 gcol1 = pack_exact(mfma_bf16(grow[qb], sel_odd, zero));
+            const bf16x4 qcol0 = pack_exact(mfma_bf16(qrow[qb], sel_even, zero));
+            const bf16x4 qcol1 = pack_exact(mfma_bf16(qrow[qb], sel_odd, zero));
             f32x4 s[NB], dp[NB];
 #pragma unroll
             for (int jb = 0; jb < NB; ++jb) {
@@ -183,17 +181,17 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, 2) bwd_bf16_kernel(BwdArg
                 dp[jb] = mfma_bf16(vrow[jb], grow[qb], zero);  // dP at the same positions
             }
 #pragma unroll
-            for (int jb = 0; jb < NB; ++jb)
+            for (int jb = 0; jb < NB; ++jb) {
+                if (BM) {
+                    // 4 consecutive columns of one row: a dword-aligned 16-byte load, range-checked per dword
+                    const uint32_t off = off_b + ((uint32_t)(16 * qb) * L + 16 * jb) * 4u;
+                    const f32x4 add = (load_f32x4(rb, off) + load_f32x4(rm, off)) * kLog2e;
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    float x = s[jb][r] * sl2;
-                    if (BM) {
-                        const uint32_t off = off_b + (uint32_t)(16 * qb) * L * 4u + (16 * jb + r) * 4;
-                        const float add = load_f32(rb, off) + load_f32(rm, off);
-                        x = fmaf(add, kLog2e, x);
-                    }
-                    s[jb][r] = x;
+                    for (int r = 0; r < 4; ++r) s[jb][r] = fmaf(s[jb][r], sl2, add[r]);
+                } else {
+                    s[jb] *= sl2;
                 }
+            }
 #pragma unroll
             for (int r = 0; r < 4; ++r)
                 if (16 * (NB - 1) + 4 * g + r >= L) s[NB - 1][r] = -INFINITY;
@@ -229,8 +227,15 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, 2) bwd_bf16_kernel(BwdArg
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
                     dp[jb][r] = s[jb][r] * (dp[jb][r] - delta);  // dS
-                    if (DB) atomicAdd(&dbacc[((qb * NB + jb) * 4 + r) * 64], dp[jb][r]);
                 }
+            if (DB) {
+                // keep the read-modify-write of this block together: hoisting the LDS reads of
+                // later blocks up here would hold their registers for the whole tile
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int jb = 0; jb < NB; ++jb) dbacc[(qb * NB + jb) * 64] += dp[jb];
+                __builtin_amdgcn_sched_barrier(0);
+            }
 
             f32x4 qe = zero, qo = zero;  // dQ[16 qb + n][2 (4g + r) (+1)]
 #pragma unroll
@@ -239,22 +244,24 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, 2) bwd_bf16_kernel(BwdArg
                 split_hi_lo(s[jb], p_hi, p_lo);
                 split_hi_lo(dp[jb], ds_hi, ds_lo);
                 qe = mfma16(kcol[jb][0], ds_hi, qe);
-                qe = mfma16(kcol[jb][0], ds_lo, qe);
                 qo = mfma16(kcol[jb][1], ds_hi, qo);
-                qo = mfma16(kcol[jb][1], ds_lo, qo);
                 // the block with the key on the lane: t[r] = X[16 qb + 4g + r][16 jb + n]
-                const bf16x4 tp_hi = pack_exact(mfma16(p_hi, ident, zero));
-                const bf16x4 tp_lo = pack_exact(mfma16(p_lo, ident, zero));
-                const bf16x4 ts_hi = pack_exact(mfma16(ds_hi, ident, zero));
-                const bf16x4 ts_lo = pack_exact(mfma16(ds_lo, ident, zero));
-                ve[jb] = mfma16(gcol[qb][0], tp_hi, ve[jb]);
-                ve[jb] = mfma16(gcol[qb][0], tp_lo, ve[jb]);
-                vo[jb] = mfma16(gcol[qb][1], tp_hi, vo[jb]);
-                vo[jb] = mfma16(gcol[qb][1], tp_lo, vo[jb]);
-                ke[jb] = mfma16(qcol[qb][0], ts_hi, ke[jb]);
-                ke[jb] = mfma16(qcol[qb][0], ts_lo, ke[jb]);
-                ko[jb] = mfma16(qcol[qb][1], ts_hi, ko[jb]);
-                ko[jb] = mfma16(qcol[qb][1], ts_lo, ko[jb]);
+                const f32x4 t0 = mfma16(p_hi, ident, zero);
+                const f32x4 t1 = mfma16(p_lo, ident, zero);
+                const f32x4 t2 = mfma16(ds_hi, ident, zero);
+                const f32x4 t3 = mfma16(ds_lo, ident, zero);
+                qe = mfma16(kcol[jb][0], ds_lo, qe);
+                qo = mfma16(kcol[jb][1], ds_lo, qo);
+                const bf16x4 tp_hi = pack_exact(t0), tp_lo = pack_exact(t1);
+                const bf16x4 ts_hi = pack_exact(t2), ts_lo = pack_exact(t3);
+                ve[jb] = mfma16(gcol0, tp_hi, ve[jb]);
+                vo[jb] = mfma16(gcol1, tp_hi, vo[jb]);
+                ke[jb] = mfma16(qcol0, ts_hi, ke[jb]);
+                ko[jb] = mfma16(qcol1, ts_hi, ko[jb]);
+                ve[jb] = mfma16(gcol0, tp_lo, ve[jb]);
+                vo[jb] = mfma16(gcol1, tp_lo, vo[jb]);
+                ke[jb] = mfma16(qcol0, ts_lo, ke[jb]);
+                ko[jb] = mfma16(qcol1, ts_lo, ko[jb]);
             }
             u32x4 out;
             out.x = pack_bf16(qe[0] * p.scale, qo[0] * p.scale);
@@ -284,12 +291,14 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, 2) bwd_bf16_kernel(BwdArg
 #pragma unroll
         for (int qb = 0; qb < NB; ++qb)
 #pragma unroll
-            for (int jb = 0; jb < NB; ++jb)
+            for (int jb = 0; jb < NB; ++jb) {
+                const f32x4 acc = dbacc[(qb * NB + jb) * 64];
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
                     const int i = 16 * qb + n, j = 16 * jb + 4 * g + r;
-                    if (i < L && j < L) dst[(size_t)i * L + j] = dbacc[((qb * NB + jb) * 4 + r) * 64];
+                    if (i < L && j < L) dst[(size_t)i * L + j] = acc[r];
                 }
+            }
     }
 }
 

@@ -126,18 +126,22 @@ __device__ __forceinline__ float sum_over_n(float x) {
     return x;
 }
 
+// (lo16(a), lo16(b)) and (hi16(a), hi16(b)) as one byte-permute each
+__device__ __forceinline__ uint32_t lower_halves(uint32_t a, uint32_t b) { return __builtin_amdgcn_perm(b, a, 0x05040100u); }
+__device__ __forceinline__ uint32_t upper_halves(uint32_t a, uint32_t b) { return __builtin_amdgcn_perm(b, a, 0x07060302u); }
+
 // Split 8 dwords, each holding the bf16 pair (channel 2n, channel 2n+1) of one
 // row, into the operand of the even channel (low halves) and of the odd one.
 __device__ __forceinline__ void split_pairs(const uint32_t (&d)[8], bf16x8& even, bf16x8& odd) {
     uint4 e, o;
-    e.x = (d[0] & 0xffffu) | (d[1] << 16);
-    e.y = (d[2] & 0xffffu) | (d[3] << 16);
-    e.z = (d[4] & 0xffffu) | (d[5] << 16);
-    e.w = (d[6] & 0xffffu) | (d[7] << 16);
-    o.x = (d[0] >> 16) | (d[1] & 0xffff0000u);
-    o.y = (d[2] >> 16) | (d[3] & 0xffff0000u);
-    o.z = (d[4] >> 16) | (d[5] & 0xffff0000u);
-    o.w = (d[6] >> 16) | (d[7] & 0xffff0000u);
+    e.x = lower_halves(d[0], d[1]);
+    e.y = lower_halves(d[2], d[3]);
+    e.z = lower_halves(d[4], d[5]);
+    e.w = lower_halves(d[6], d[7]);
+    o.x = upper_halves(d[0], d[1]);
+    o.y = upper_halves(d[2], d[3]);
+    o.z = upper_halves(d[4], d[5]);
+    o.w = upper_halves(d[6], d[7]);
     even = as_bf16x8(e);
     odd = as_bf16x8(o);
 }

@@ -132,14 +132,14 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) fwd_bf16_kernel(FwdArgs p
             // Rows beyond L fall outside the descriptor (zero); columns beyond L are
             // overwritten with -inf below, whatever was fetched for them.
 #pragma unroll
-            for (int jb = 0; jb < NB; ++jb)
+            for (int jb = 0; jb < NB; ++jb) {
+                // 4 consecutive columns of one row: a 16-byte load that is only dword aligned;
+                // the range check of the descriptor is per dword.
+                const uint32_t off = off_b + ((uint32_t)(16 * qb) * L + 16 * jb) * 4u;
+                const f32x4 add = (load_f32x4(rb, off) + load_f32x4(rm, off)) * kLog2e;
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const uint32_t so = (uint32_t)(16 * qb) * L * 4u;
-                    float add = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rb, off_b + (16 * jb + r) * 4 + so, 0, 0));
-                    add += __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rm, off_b + (16 * jb + r) * 4 + so, 0, 0));
-                    s[jb][r] = fmaf(s[jb][r], sl2, add * kLog2e);
-                }
+                for (int r = 0; r < 4; ++r) s[jb][r] = fmaf(s[jb][r], sl2, add[r]);
+            }
 #pragma unroll
             for (int r = 0; r < 4; ++r)
                 if (16 * (NB - 1) + 4 * g + r >= L) s[NB - 1][r] = -INFINITY;
@@ -274,14 +274,14 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) fwd_f32_kernel(FwdArgs p,
             f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int kk = 0; kk < 8; ++kk) acc = mfma_f32(kop[jb][kk], qop[kk], acc);
+            f32x4 add = {0.f, 0.f, 0.f, 0.f};
+            if (BM) {
+                const uint32_t off = off_b + ((uint32_t)(16 * qb) * L + 16 * jb) * 4u;
+                add = load_f32x4(rb, off) + load_f32x4(rm, off);
+            }
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-                float x = acc[r] * p.scale;
-                if (BM) {
-                    const uint32_t so = (uint32_t)(16 * qb) * L * 4u;
-                    x += __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rb, off_b + (16 * jb + r) * 4 + so, 0, 0));
-                    x += __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rm, off_b + (16 * jb + r) * 4 + so, 0, 0));
-                }
+                float x = acc[r] * p.scale + add[r];
                 if (jb == NB - 1 && 16 * jb + 4 * g + r >= L) x = -INFINITY;
                 acc[r] = x;
                 m = fmaxf(m, x);
