@@ -29,9 +29,11 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E bandwidth
 LLC_BYTES = 256 * 2 ** 20       # Infinity Cache
-# HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE for this
-# workload (see profiles/); None until measured.
-MEASURED_TRAFFIC_BYTES = None
+# HBM bytes per launch of the forward kernel on this workload, from two rocprofv3 --pmc runs
+# (FETCH_SIZE, then WRITE_SIZE, each scaled by what the same counter reads for a plain elementwise
+# kernel of known size; figures and commands in profiles/fwd_bf16_kernel_swin_t_stage1.md):
+# 241.0 MB read + 85.2 MB written.
+MEASURED_TRAFFIC_BYTES = 326.2e6
 EVENT_GROUP = 100
 
 
@@ -73,6 +75,9 @@ def main():
     ap.add_argument("--steps", type=int, default=2000)
     ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (profiling runs)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also launch 5 plain elementwise kernels that read and write one tensor of known size, "
+                         "so that a counter run can scale FETCH_SIZE / WRITE_SIZE against known traffic")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (the workload is data-parallel "
@@ -122,6 +127,12 @@ def main():
     wall = time.perf_counter() - t0
     kernel_ms = sum(marks[gi].elapsed_time(marks[gi + 1]) for gi in range(len(bounds) - 1)) / args.steps
     assert all(torch.isfinite(s[3].float()).all().item() for s in sets)
+
+    if args.calibrate_copy:
+        for i in range(5):
+            q, _, _, o = sets[i % nsets]
+            torch.neg(q, out=o)                  # reads w.N*w.L*w.C*2 bytes, writes as many
+        torch.cuda.synchronize()
 
     wh = w.N * w.heads
     algo_bytes = 4 * w.L * 32 * 2 * wh           # Q, K, V in and O out, once each, bf16
