@@ -150,7 +150,7 @@ def main():
                    "window_heads_per_step": wh},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS, "traffic": MEASURED_TRAFFIC_BYTES,
-                     "kernel": "fwd_bf16_kernel<4,false>", "kernel_ms": kernel_ms,
+                     "kernel": "fwd_bf16_staged_kernel<4,false>", "kernel_ms": kernel_ms,
                      "algorithmic_bytes_per_launch": algo_bytes},
     }
     if not args.no_cpu_baseline:

@@ -26,6 +26,8 @@
 //     columns are set to -inf.  The range check covers the vector offset and
 //     the immediate only, NOT the scalar offset operand, so every offset goes
 //     into the vector operand and the scalar one stays 0.
+#include <stdlib.h>
+
 #include "fwa_device.h"
 #include "fwa_internal.h"
 
@@ -388,6 +390,8 @@ hipError_t launch_f32_nb(const FwdArgs& a, hipStream_t st) {
     }
 
 hipError_t launch_forward_bf16(const FwdArgs& a, hipStream_t s) {
+    static const bool direct_only = getenv("FWA_FWD_DIRECT") != nullptr;  // experiment switch
+    if (!direct_only && staged_heads_per_block(a.L, a.heads) > 0) return launch_forward_bf16_staged(a, s);
     const int nb = (a.L + 15) / 16;
     FWA_NB_SWITCH(launch_bf16_nb, nb, a, s)
 }

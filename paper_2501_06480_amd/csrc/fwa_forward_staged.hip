@@ -1,0 +1,258 @@
+// Forward kernel for L <= 64 with LDS-staged, fully coalesced global traffic.
+//
+// Same arithmetic and register layouts as fwd_bf16_kernel (one wave per
+// (window, head) tile, S^T in the accumulators, softmax across the 4 lanes
+// sharing n, O^T = V^T P^T), but the workgroup moves its slab of Q, K, V --
+// the rows of one window restricted to the workgroup's heads, a run of
+// whole 128-byte lines per row -- with 16-byte loads whose lanes cover
+// consecutive addresses, parks it in LDS, and every wave then picks its own
+// head's operands out of LDS:
+//   K, Q rows : ds_read_b128  (row n, 16 B at 16 g of the head's 64 B slice)
+//   V columns : ds_read_b64_tr_b16, the transposing read: lane t of a row of 16
+//               lanes receives X[i0 + e][j0 + t], e = 0..3, i.e. the k-slots of
+//               the A operand of O^T with the channel on the lane.
+// The output goes back through LDS the same way and leaves as whole rows.
+// Reading 64-byte head slices straight from HBM (the other kernel) costs about
+// 8 % of bandwidth against this pattern.
+#include "fwa_device.h"
+#include "fwa_internal.h"
+
+namespace fwa {
+namespace {
+
+typedef short v4i16 __attribute__((ext_vector_type(4)));
+
+struct StagedGeom {
+    FastDiv groups;            // workgroups per window
+    FastDiv lanes_per_row;     // 4 * heads_per_block lanes move one slab row
+    uint32_t heads_per_block;
+};
+
+// See fwa_backward's description of the same instruction: lane r of a row of 16
+// lanes passes the address of 4 consecutive bf16, lane t receives element (t & 3)
+// of the rows passed by lanes (t >> 2) + 4 e, e = 0..3.
+__device__ __forceinline__ uint2 lds_read_tr(const uint16_t* p) {
+    typedef __attribute__((address_space(3))) v4i16 lds_v4i16;
+    const v4i16 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4i16*)(p));
+    return __builtin_bit_cast(uint2, v);
+}
+
+template <int NB, bool BM>
+__global__ void __launch_bounds__(64 * kWavesPerBlock) fwd_bf16_staged_kernel(FwdArgs p, StagedGeom gm) {
+    constexpr int NB2 = (NB + 1) / 2;
+    constexpr int ROWS = 16 * NB;
+    extern __shared__ __attribute__((aligned(16))) uint4 lds[];  // [3][ROWS][stride]: K, V, Q (then O)
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int n = lane & 15, g = lane >> 4;
+    const uint32_t hl = __builtin_amdgcn_readfirstlane(tid >> 6);  // head inside the workgroup
+    const uint32_t w = fastdiv(blockIdx.x, gm.groups);
+    const uint32_t hg = blockIdx.x - w * gm.groups.d;
+    const uint32_t hpb = gm.heads_per_block;
+    const uint32_t h = hg * hpb + hl;
+    const int L = p.L;
+    const uint32_t row_bytes = (uint32_t)p.C * 2u;
+    const uint32_t stride = 4u * hpb + 1u;  // LDS row stride in 16-byte units (one unit of padding)
+
+    // ---- stage the slab: thread -> (row of a 16-row pass, 16-byte column)
+    const uint32_t rip = fastdiv((uint32_t)tid, gm.lanes_per_row);
+    const uint32_t col = (uint32_t)tid - rip * gm.lanes_per_row.d;
+    const size_t slab = ((size_t)w * L * p.C + (size_t)hg * hpb * kHeadDim) * 2u;
+    const uint32_t slab_bytes = (uint32_t)(L - 1) * row_bytes + hpb * 2u * kHeadDim;
+    const __amdgpu_buffer_rsrc_t rq = make_rsrc((const char*)p.q + slab, slab_bytes);
+    const __amdgpu_buffer_rsrc_t rk = make_rsrc((const char*)p.k + slab, slab_bytes);
+    const __amdgpu_buffer_rsrc_t rv = make_rsrc((const char*)p.v + slab, slab_bytes);
+    const __amdgpu_buffer_rsrc_t ro = make_rsrc((char*)p.o + slab, slab_bytes);
+    const uint32_t goff = rip * row_bytes + col * 16u;  // plus 16 t rows
+    const uint32_t loff = rip * stride + col;           // plus 16 t rows, in uint4 units
+    u32x4 sk[NB], sv[NB], sq[NB];
+#pragma unroll
+    for (int t = 0; t < NB; ++t) {
+        // rows beyond L lie outside the descriptor and arrive as zeros
+        sk[t] = __builtin_amdgcn_raw_buffer_load_b128(rk, goff + 16 * t * row_bytes, 0, 0);
+        sq[t] = __builtin_amdgcn_raw_buffer_load_b128(rq, goff + 16 * t * row_bytes, 0, 0);
+        sv[t] = __builtin_amdgcn_raw_buffer_load_b128(rv, goff + 16 * t * row_bytes, 0, 0);
+    }
+    uint4* const lk = lds;
+    uint4* const lv = lds + ROWS * stride;
+    uint4* const lq = lds + 2 * ROWS * stride;
+#pragma unroll
+    for (int t = 0; t < NB; ++t) {
+        lk[loff + 16 * t * stride] = __builtin_bit_cast(uint4, sk[t]);
+        lq[loff + 16 * t * stride] = __builtin_bit_cast(uint4, sq[t]);
+        lv[loff + 16 * t * stride] = __builtin_bit_cast(uint4, sv[t]);
+    }
+    __syncthreads();
+
+    // ---- operands of this wave's head
+    bf16x8 kop[NB], qop[NB];
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+        kop[b] = __builtin_bit_cast(bf16x8, lk[(16 * b + n) * stride + 4 * hl + g]);
+        qop[b] = __builtin_bit_cast(bf16x8, lq[(16 * b + n) * stride + 4 * hl + g]);
+    }
+    // V: A operands of O^T per pair of key blocks, channels 0..15 and 16..31.
+    // lane r of a row points at V[i0 + (r >> 2)][j0 + 4 (r & 3)], i0 = first key of the 4 the lane row owns
+    bf16x8 vop[NB2][2];
+    {
+        const uint16_t* lvh = reinterpret_cast<const uint16_t*>(lv) + 32 * hl;
+        const uint32_t el = (4 * g + (n >> 2)) * (stride * 8u) + 4 * (n & 3);
+#pragma unroll
+        for (int kp = 0; kp < NB2; ++kp)
+#pragma unroll
+            for (int c = 0; c < 2; ++c) {
+                const uint2 a = lds_read_tr(lvh + el + (32 * kp) * (stride * 8u) + 16 * c);
+                uint2 b = {0u, 0u};
+                if (2 * kp + 1 < NB) b = lds_read_tr(lvh + el + (32 * kp + 16) * (stride * 8u) + 16 * c);
+                const u32x4 v = {a.x, a.y, b.x, b.y};
+                vop[kp][c] = as_bf16x8(v);
+            }
+    }
+
+    const float sl2 = p.scale * kLog2e;
+    __amdgpu_buffer_rsrc_t rb = make_rsrc(nullptr, 0), rm = make_rsrc(nullptr, 0);
+    if (BM) {
+        const uint32_t ll = (uint32_t)L * L * 4u;
+        const uint32_t hh = h < (uint32_t)p.heads ? h : 0u;
+        if (p.bias) rb = make_rsrc(p.bias + (size_t)hh * L * L, ll);
+        if (p.mask) rm = make_rsrc(p.mask + (size_t)(w % (uint32_t)p.nW) * L * L, ll);
+    }
+    const uint32_t off_b = ((uint32_t)n * L + 4u * g) * 4u;
+
+#pragma unroll
+    for (int qb = 0; qb < NB; ++qb) {
+        if (16 * qb >= L) break;  // uniform
+        f32x4 s[NB];
+#pragma unroll
+        for (int jb = 0; jb < NB; ++jb) {
+            const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+            s[jb] = mfma_bf16(kop[jb], qop[qb], zero);  // S[16 qb + n][16 jb + 4g + r]
+        }
+        float mul, mb;  // p = exp2(s * mul - mb)
+        if (BM) {
+#pragma unroll
+            for (int jb = 0; jb < NB; ++jb) {
+                const uint32_t off = off_b + ((uint32_t)(16 * qb) * L + 16 * jb) * 4u;
+                const f32x4 add = (load_f32x4(rb, off) + load_f32x4(rm, off)) * kLog2e;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) s[jb][r] = fmaf(s[jb][r], sl2, add[r]);
+            }
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+                if (16 * (NB - 1) + 4 * g + r >= L) s[NB - 1][r] = -INFINITY;
+            float m = s[0][0];
+#pragma unroll
+            for (int jb = 0; jb < NB; ++jb) {
+                m = fmaxf(fmaxf(m, s[jb][0]), s[jb][1]);
+                m = fmaxf(fmaxf(m, s[jb][2]), s[jb][3]);
+            }
+            mul = 1.0f;
+            mb = max_over_g(m);
+        } else {
+            const float pad = sl2 >= 0.f ? -INFINITY : INFINITY;
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+                if (16 * (NB - 1) + 4 * g + r >= L) s[NB - 1][r] = pad;
+            float m = s[0][0];
+            if (sl2 >= 0.f) {
+#pragma unroll
+                for (int jb = 0; jb < NB; ++jb) {
+                    m = fmaxf(fmaxf(m, s[jb][0]), s[jb][1]);
+                    m = fmaxf(fmaxf(m, s[jb][2]), s[jb][3]);
+                }
+                m = max_over_g(m);
+            } else {
+#pragma unroll
+                for (int jb = 0; jb < NB; ++jb) {
+                    m = fminf(fminf(m, s[jb][0]), s[jb][1]);
+                    m = fminf(fminf(m, s[jb][2]), s[jb][3]);
+                }
+                m = -max_over_g(-m);
+            }
+            mul = sl2;
+            mb = m * sl2;
+        }
+        float sum = 0.f;
+#pragma unroll
+        for (int jb = 0; jb < NB; ++jb)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const float e = __builtin_amdgcn_exp2f(fmaf(s[jb][r], mul, -mb));
+                s[jb][r] = e;
+                sum += e;
+            }
+        sum = sum_over_g(sum);
+        const float inv = __builtin_amdgcn_rcpf(sum);
+
+        f32x4 o0 = {0.f, 0.f, 0.f, 0.f}, o1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int kp = 0; kp < NB2; ++kp) {
+            u32x4 a;
+            a.x = pack_bf16(s[2 * kp][0], s[2 * kp][1]);
+            a.y = pack_bf16(s[2 * kp][2], s[2 * kp][3]);
+            const int j1 = 2 * kp + 1 < NB ? 2 * kp + 1 : 0;
+            a.z = 2 * kp + 1 < NB ? pack_bf16(s[j1][0], s[j1][1]) : 0u;
+            a.w = 2 * kp + 1 < NB ? pack_bf16(s[j1][2], s[j1][3]) : 0u;
+            const bf16x8 pop = as_bf16x8(a);
+            o0 = mfma_bf16(vop[kp][0], pop, o0);  // o0[r] = O[16 qb + n][4g + r]
+            o1 = mfma_bf16(vop[kp][1], pop, o1);  // o1[r] = O[16 qb + n][16 + 4g + r]
+        }
+        // park the row in the Q tile (only this wave reads or writes its head's 64 B slice)
+        uint2 lo, hi;
+        lo.x = pack_bf16(o0[0] * inv, o0[1] * inv);
+        lo.y = pack_bf16(o0[2] * inv, o0[3] * inv);
+        hi.x = pack_bf16(o1[0] * inv, o1[1] * inv);
+        hi.y = pack_bf16(o1[2] * inv, o1[3] * inv);
+        uint2* row = reinterpret_cast<uint2*>(lq + (16 * qb + n) * stride + 4 * hl);
+        row[g] = lo;
+        row[4 + g] = hi;
+    }
+    __syncthreads();
+    // ---- whole rows back to global memory; rows beyond L are dropped by the range check
+#pragma unroll
+    for (int t = 0; t < NB; ++t) {
+        const u32x4 v = __builtin_bit_cast(u32x4, lq[loff + 16 * t * stride]);
+        __builtin_amdgcn_raw_buffer_store_b128(v, ro, goff + 16 * t * row_bytes, 0, 0);
+    }
+}
+
+template <int NB>
+hipError_t launch_staged_nb(const FwdArgs& a, int hpb, hipStream_t st) {
+    StagedGeom gm;
+    const uint32_t groups = (uint32_t)(a.heads / hpb);
+    gm.groups = make_fastdiv(groups);
+    gm.lanes_per_row = make_fastdiv(4u * (uint32_t)hpb);
+    gm.heads_per_block = (uint32_t)hpb;
+    const unsigned grid = (unsigned)(a.N * groups), block = 64u * (unsigned)hpb;
+    const size_t lds = (size_t)3 * 16 * NB * (4 * hpb + 1) * 16;
+    if (a.bias || a.mask)
+        hipLaunchKernelGGL((fwd_bf16_staged_kernel<NB, true>), dim3(grid), dim3(block), lds, st, a, gm);
+    else
+        hipLaunchKernelGGL((fwd_bf16_staged_kernel<NB, false>), dim3(grid), dim3(block), lds, st, a, gm);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+// Heads per workgroup for the staged kernel, or 0 when it does not apply: the
+// slab of a workgroup must consist of whole 128-byte lines per row (an even
+// number of heads) or be the whole row.
+int staged_heads_per_block(int L, int heads) {
+    if (L > 64) return 0;
+    if (heads <= kWavesPerBlock) return heads;
+    if (heads % 4 == 0) return 4;
+    if (heads % 2 == 0) return 2;
+    return 0;
+}
+
+hipError_t launch_forward_bf16_staged(const FwdArgs& a, hipStream_t s) {
+    const int hpb = staged_heads_per_block(a.L, a.heads);
+    switch ((a.L + 15) / 16) {
+        case 1: return launch_staged_nb<1>(a, hpb, s);
+        case 2: return launch_staged_nb<2>(a, hpb, s);
+        case 3: return launch_staged_nb<3>(a, hpb, s);
+        case 4: return launch_staged_nb<4>(a, hpb, s);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace fwa

@@ -52,6 +52,8 @@ struct BwdArgs {
 // Each returns a hipError_t from the launch (hipSuccess when enqueued).
 hipError_t launch_forward_bf16(const FwdArgs& a, hipStream_t s);
 hipError_t launch_forward_f32(const FwdArgs& a, hipStream_t s);
+int staged_heads_per_block(int L, int heads);
+hipError_t launch_forward_bf16_staged(const FwdArgs& a, hipStream_t s);
 hipError_t launch_backward_bf16(const BwdArgs& a, hipStream_t s);
 hipError_t launch_backward_f32(const BwdArgs& a, hipStream_t s);
 int backward_slots(long long N, int heads);
