@@ -31,9 +31,9 @@ HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E bandwidth
 LLC_BYTES = 256 * 2 ** 20       # Infinity Cache
 # HBM bytes per launch of the forward kernel on this workload, from two rocprofv3 --pmc runs
 # (FETCH_SIZE, then WRITE_SIZE, each scaled by what the same counter reads for a plain elementwise
-# kernel of known size; figures and commands in profiles/fwd_bf16_kernel_swin_t_stage1.md):
-# 241.0 MB read + 85.2 MB written.
-MEASURED_TRAFFIC_BYTES = 326.2e6
+# kernel of known size; figures and commands in profiles/fwd_bf16_staged_kernel_swin_t_stage1.md):
+# 232.7 MB read + 77.1 MB written.
+MEASURED_TRAFFIC_BYTES = 309.8e6
 EVENT_GROUP = 100
 
 
