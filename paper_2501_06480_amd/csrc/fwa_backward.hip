@@ -83,7 +83,13 @@ __device__ __forceinline__ bf16x4 pack_exact(const f32x4& x) {
     h.y = upper_halves(u[2], u[3]);
     return as_bf16x4(h);
 }
-template <int NB, bool BM, bool DB>
+// The row operands of the next window are fetched while the current one is computed: the
+// loads write straight into a per-wave LDS stage (one 16-byte slot per lane and 16-row
+// block, i.e. already in operand order) and are picked up at the top of the next iteration.
+typedef const __attribute__((address_space(1))) void* global_cptr;
+typedef __attribute__((address_space(3))) void* lds_vptr;
+
+template <int NB, bool BM, bool DB, bool PF>
 __global__ void __launch_bounds__(64 * kWavesPerBlock, 2) bwd_bf16_kernel(BwdArgs p, BwdGeom gm) {
     extern __shared__ __attribute__((aligned(16))) float lds_all[];
     const int lane = threadIdx.x & 63;
@@ -97,7 +103,10 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, 2) bwd_bf16_kernel(BwdArg
     // dBias accumulator of this wave: the 4 values of block (qb, jb) of lane l form one
     // float4 at index (qb*NB + jb)*64 + l, so every lane only ever touches its own
     // addresses (plain read-modify-write, no atomics, no barriers, no bank conflicts).
-    f32x4* const dbacc = reinterpret_cast<f32x4*>(lds_all) + (size_t)wave * (NB * NB * 64) + lane;
+    constexpr int kAccVecs = DB ? NB * NB * 64 : 0, kStageVecs = PF ? 4 * NB * 64 : 0;
+    f32x4* const wave_lds = reinterpret_cast<f32x4*>(lds_all) + (size_t)wave * (kAccVecs + kStageVecs);
+    f32x4* const dbacc = wave_lds + lane;
+    u32x4* const stage = reinterpret_cast<u32x4*>(wave_lds + kAccVecs);  // [tensor][block][lane]
     if (DB) {
 #pragma unroll
         for (int e = 0; e < NB * NB; ++e) dbacc[e * 64] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -129,6 +138,29 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, 2) bwd_bf16_kernel(BwdArg
     const bf16x8 sel_even = as_bf16x8(se), sel_odd = as_bf16x8(so);
     const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
 
+    // Fetch the rows of window `wn` into the stage.  Rows beyond L are skipped: their slots
+    // keep the zeros written once below.
+    auto stage_rows = [&](long long wn) {
+        const size_t t = ((size_t)wn * L * p.C + (size_t)h * kHeadDim) * 2u + off_row;
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            if (16 * b + n < L) {
+                const size_t o = t + (size_t)(16 * b) * row_bytes;
+                __builtin_amdgcn_global_load_lds((global_cptr)((const char*)p.k + o), (lds_vptr)(stage + (0 * NB + b) * 64), 16, 0, 0);
+                __builtin_amdgcn_global_load_lds((global_cptr)((const char*)p.q + o), (lds_vptr)(stage + (1 * NB + b) * 64), 16, 0, 0);
+                __builtin_amdgcn_global_load_lds((global_cptr)((const char*)p.v + o), (lds_vptr)(stage + (2 * NB + b) * 64), 16, 0, 0);
+                __builtin_amdgcn_global_load_lds((global_cptr)((const char*)p.d_o + o), (lds_vptr)(stage + (3 * NB + b) * 64), 16, 0, 0);
+            }
+        }
+    };
+    if (PF) {
+        const u32x4 z = {0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int e = 0; e < 4 * NB; ++e) stage[e * 64 + lane] = z;
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        if (slot < p.N) stage_rows(slot);
+    }
+
     for (long long w = slot; w < p.N; w += gm.slots) {
         const size_t tile = ((size_t)w * L * p.C + (size_t)h * kHeadDim) * 2u;
         const __amdgpu_buffer_rsrc_t rq = make_rsrc((const char*)p.q + tile, tile_bytes);
@@ -143,15 +175,28 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, 2) bwd_bf16_kernel(BwdArg
 
         // Row operands (contraction over the 32 channels): lane (g, n) = X[16 b + n][8g .. 8g+7]
         bf16x8 krow[NB], vrow[NB], qrow[NB], grow[NB];
+        if (PF) {
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the staged loads of this window have landed
 #pragma unroll
-        for (int b = 0; b < NB; ++b) {
-            krow[b] = as_bf16x8(__builtin_amdgcn_raw_buffer_load_b128(rk, off_row + 16 * b * row_bytes, 0, 0));
-            qrow[b] = as_bf16x8(__builtin_amdgcn_raw_buffer_load_b128(rq, off_row + 16 * b * row_bytes, 0, 0));
-        }
+            for (int b = 0; b < NB; ++b) {
+                krow[b] = as_bf16x8(stage[(0 * NB + b) * 64 + lane]);
+                qrow[b] = as_bf16x8(stage[(1 * NB + b) * 64 + lane]);
+                vrow[b] = as_bf16x8(stage[(2 * NB + b) * 64 + lane]);
+                grow[b] = as_bf16x8(stage[(3 * NB + b) * 64 + lane]);
+            }
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // stage consumed: it may be refilled
+            if (w + gm.slots < p.N) stage_rows(w + gm.slots);
+        } else {
 #pragma unroll
-        for (int b = 0; b < NB; ++b) {
-            vrow[b] = as_bf16x8(__builtin_amdgcn_raw_buffer_load_b128(rv, off_row + 16 * b * row_bytes, 0, 0));
-            grow[b] = as_bf16x8(__builtin_amdgcn_raw_buffer_load_b128(rg, off_row + 16 * b * row_bytes, 0, 0));
+            for (int b = 0; b < NB; ++b) {
+                krow[b] = as_bf16x8(__builtin_amdgcn_raw_buffer_load_b128(rk, off_row + 16 * b * row_bytes, 0, 0));
+                qrow[b] = as_bf16x8(__builtin_amdgcn_raw_buffer_load_b128(rq, off_row + 16 * b * row_bytes, 0, 0));
+            }
+#pragma unroll
+            for (int b = 0; b < NB; ++b) {
+                vrow[b] = as_bf16x8(__builtin_amdgcn_raw_buffer_load_b128(rv, off_row + 16 * b * row_bytes, 0, 0));
+                grow[b] = as_bf16x8(__builtin_amdgcn_raw_buffer_load_b128(rg, off_row + 16 * b * row_bytes, 0, 0));
+            }
         }
         // Column operands (contraction over the 16 rows of a block): lane (g, m) =
         // X[16 b + 4g + e][channel 2m resp. 2m+1], e = 0..3.  They are the row operands
@@ -302,25 +347,46 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, 2) bwd_bf16_kernel(BwdArg
     }
 }
 
-// dbias[e] = sum over slots of partial[slot][e], slots added in index order.
-__global__ void dbias_reduce_kernel(const float* __restrict__ partial, float* __restrict__ dbias, int slots,
-                                    size_t count) {
-    const size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (e >= count) return;
+// dbias[e] = sum over slots of partial[slot][e].  A workgroup of 64 x 16 threads owns 64
+// consecutive elements; thread row y adds slots y, y+16, ... in index order, then the 16 row
+// sums are added in row order: a fixed summation tree, hence bit-reproducible.
+constexpr int kReduceRows = 16;
+__global__ void __launch_bounds__(64 * kReduceRows)
+dbias_reduce_kernel(const float* __restrict__ partial, float* __restrict__ dbias, int slots, size_t count) {
+    __shared__ float part[kReduceRows][64];
+    const int x = threadIdx.x & 63, y = threadIdx.x >> 6;
+    const size_t e = (size_t)blockIdx.x * 64 + x;
     float acc = 0.f;
-    for (int s = 0; s < slots; ++s) acc += partial[(size_t)s * count + e];
-    dbias[e] = acc;
+    if (e < count)
+        for (int s = y; s < slots; s += kReduceRows) acc += partial[(size_t)s * count + e];
+    part[y][x] = acc;
+    __syncthreads();
+    if (y == 0 && e < count) {
+        float total = 0.f;
+#pragma unroll
+        for (int r = 0; r < kReduceRows; ++r) total += part[r][x];
+        dbias[e] = total;
+    }
 }
 
 template <int NB, bool BM, bool DB>
 hipError_t launch_one(const BwdArgs& a, const BwdGeom& gm, unsigned grid, unsigned block, hipStream_t st) {
-    const size_t lds = DB ? (size_t)(block / 64) * NB * NB * 4 * 64 * sizeof(float) : 0;
+    // Prefetching through the LDS stage pays only when nothing else competes for LDS (the dBias
+    // accumulator) or for the in-order load queue (bias/mask loads): measured 195 vs 249 us on the
+    // Swin-T stage-1 shape without bias, no gain with bias, a loss with dBias.
+    const bool pf = !BM && !DB;
+    const size_t per_wave = (DB ? (size_t)NB * NB * 64 * 16 : 0) + (pf ? (size_t)4 * NB * 64 * 16 : 0);
+    const size_t lds = (size_t)(block / 64) * per_wave;
+    const void* fn = pf ? reinterpret_cast<const void*>(&bwd_bf16_kernel<NB, BM, DB, true>)
+                        : reinterpret_cast<const void*>(&bwd_bf16_kernel<NB, BM, DB, false>);
     if (lds > 64 * 1024) {
-        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&bwd_bf16_kernel<NB, BM, DB>),
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        const hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL((bwd_bf16_kernel<NB, BM, DB>), dim3(grid), dim3(block), lds, st, a, gm);
+    if (pf)
+        hipLaunchKernelGGL((bwd_bf16_kernel<NB, BM, DB, true>), dim3(grid), dim3(block), lds, st, a, gm);
+    else
+        hipLaunchKernelGGL((bwd_bf16_kernel<NB, BM, DB, false>), dim3(grid), dim3(block), lds, st, a, gm);
     return hipGetLastError();
 }
 
@@ -342,8 +408,8 @@ hipError_t launch_bwd_nb(const BwdArgs& a, hipStream_t st) {
         e = db ? launch_one<NB, false, true>(a, gm, grid, block, st) : launch_one<NB, false, false>(a, gm, grid, block, st);
     if (e != hipSuccess || !db) return e;
     const size_t count = (size_t)a.heads * a.L * a.L;
-    hipLaunchKernelGGL(dbias_reduce_kernel, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, st, a.partial,
-                       a.dbias, a.slots, count);
+    hipLaunchKernelGGL(dbias_reduce_kernel, dim3((unsigned)((count + 63) / 64)), dim3(64 * kReduceRows), 0, st,
+                       a.partial, a.dbias, a.slots, count);
     return hipGetLastError();
 }
 
