@@ -38,18 +38,11 @@
 namespace fwa {
 namespace {
 
-typedef short bf16x4 __attribute__((ext_vector_type(4)));  // raw bf16 bits, operand of the K=16 matrix op
-
 struct BwdGeom {
     FastDiv groups;  // workgroups per window position
     uint32_t heads_per_block;
     uint32_t slots;  // workgroups along the window axis; window w is handled by slot w % slots
 };
-
-__device__ __forceinline__ f32x4 mfma16(bf16x4 a, bf16x4 b, f32x4 c) {
-    return __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a, b, c, 0, 0, 0);
-}
-__device__ __forceinline__ bf16x4 as_bf16x4(uint2 u) { return __builtin_bit_cast(bf16x4, u); }
 
 // x = hi + lo with hi the upper 16 bits of x (a bf16 by truncation) and lo the
 // remainder rounded to bf16: together 16 significant bits.
@@ -69,19 +62,6 @@ __device__ __forceinline__ void split_hi_lo(const f32x4& x, bf16x4& hi, bf16x4& 
     l.y = pack_bf16(rem[2], rem[3]);
     hi = as_bf16x4(h);
     lo = as_bf16x4(l);
-}
-// fp32 values that are exactly bf16 (results of an identity product) -> packed bf16
-__device__ __forceinline__ bf16x4 pack_exact(const f32x4& x) {
-    uint32_t u[4];
-#pragma unroll
-    for (int c = 0; c < 4; ++c) {
-        const float xc = x[c];
-        u[c] = __builtin_bit_cast(uint32_t, xc);
-    }
-    uint2 h;
-    h.x = upper_halves(u[0], u[1]);
-    h.y = upper_halves(u[2], u[3]);
-    return as_bf16x4(h);
 }
 // The row operands of the next window are fetched while the current one is computed: the
 // loads write straight into a per-wave LDS stage (one 16-byte slot per lane and 16-row
@@ -126,16 +106,7 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, 2) bwd_bf16_kernel(BwdArg
     idu.x = (4 * g + 0 == n ? 0x3f80u : 0u) | (4 * g + 1 == n ? 0x3f800000u : 0u);
     idu.y = (4 * g + 2 == n ? 0x3f80u : 0u) | (4 * g + 3 == n ? 0x3f800000u : 0u);
     const bf16x4 ident = as_bf16x4(idu);
-    // channel-selecting B operands of the K=32 matrix op: slot e of lane (g, n) stands for
-    // channel 8g + e; "even" picks channel 2n into column n, "odd" picks channel 2n + 1
-    u32x4 se = {0u, 0u, 0u, 0u}, so = {0u, 0u, 0u, 0u};
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-        const uint32_t one = (e & 1) ? 0x3f800000u : 0x3f80u;
-        if (8 * g + e == 2 * n) se[e >> 1] |= one;
-        if (8 * g + e == 2 * n + 1) so[e >> 1] |= one;
-    }
-    const bf16x8 sel_even = as_bf16x8(se), sel_odd = as_bf16x8(so);
+    const bf16x8 sel_even = channel_selector(g, n, 0), sel_odd = channel_selector(g, n, 1);
     const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
 
     // Fetch the rows of window `wn` into the stage.  Rows beyond L are skipped: their slots

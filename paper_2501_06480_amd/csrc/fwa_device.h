@@ -130,25 +130,38 @@ __device__ __forceinline__ float sum_over_n(float x) {
 __device__ __forceinline__ uint32_t lower_halves(uint32_t a, uint32_t b) { return __builtin_amdgcn_perm(b, a, 0x05040100u); }
 __device__ __forceinline__ uint32_t upper_halves(uint32_t a, uint32_t b) { return __builtin_amdgcn_perm(b, a, 0x07060302u); }
 
-// Split 8 dwords, each holding the bf16 pair (channel 2n, channel 2n+1) of one
-// row, into the operand of the even channel (low halves) and of the odd one.
-__device__ __forceinline__ void split_pairs(const uint32_t (&d)[8], bf16x8& even, bf16x8& odd) {
-    uint4 e, o;
-    e.x = lower_halves(d[0], d[1]);
-    e.y = lower_halves(d[2], d[3]);
-    e.z = lower_halves(d[4], d[5]);
-    e.w = lower_halves(d[6], d[7]);
-    o.x = upper_halves(d[0], d[1]);
-    o.y = upper_halves(d[2], d[3]);
-    o.z = upper_halves(d[4], d[5]);
-    o.w = upper_halves(d[6], d[7]);
-    even = as_bf16x8(e);
-    odd = as_bf16x8(o);
+typedef short bf16x4 __attribute__((ext_vector_type(4)));  // raw bf16 bits, operand of the K=16 matrix op
+__device__ __forceinline__ f32x4 mfma16(bf16x4 a, bf16x4 b, f32x4 c) {
+    return __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a, b, c, 0, 0, 0);
 }
+__device__ __forceinline__ bf16x4 as_bf16x4(uint2 u) { return __builtin_bit_cast(bf16x4, u); }
 
-// Row index (inside a 32-row group) that k-slot e of lane row g stands for when
-// the A operand is built from two 16x16 accumulator tiles: slots 0..3 are rows
-// 4g..4g+3 of the first tile, slots 4..7 the same rows of the second.
-__device__ __forceinline__ int slot_row(int g, int e) { return (e & 3) + 4 * g + 16 * (e >> 2); }
+// fp32 values that are exactly bf16 (results of a product with a 0/1 matrix) -> packed bf16
+__device__ __forceinline__ uint2 pack_exact_u2(const f32x4& x) {
+    uint32_t u[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        const float xc = x[c];
+        u[c] = __builtin_bit_cast(uint32_t, xc);
+    }
+    uint2 h;
+    h.x = upper_halves(u[0], u[1]);
+    h.y = upper_halves(u[2], u[3]);
+    return h;
+}
+__device__ __forceinline__ bf16x4 pack_exact(const f32x4& x) { return as_bf16x4(pack_exact_u2(x)); }
+
+// B operand of the K=32 matrix op that picks every second channel: slot e of lane (g, n)
+// stands for channel 8g + e; the product rows x selector puts channel 2n + parity of each
+// row into column n, i.e. returns lane (g', n') <- X[row 4g' + r][channel 2n' + parity].
+// This turns a row operand (channels on the k-slots) into the operand with the rows on the
+// k-slots without touching memory.
+__device__ __forceinline__ bf16x8 channel_selector(int g, int n, int parity) {
+    u32x4 s = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+        if (8 * g + e == 2 * n + parity) s[e >> 1] |= (e & 1) ? 0x3f800000u : 0x3f80u;
+    return as_bf16x8(s);
+}
 
 }  // namespace fwa

@@ -14,8 +14,9 @@
 //     two cross-row shuffles each and no LDS;
 //   * in that layout the probabilities of a lane are already a B operand of
 //     O^T = V^T P^T (its k-slots are keys 4g..4g+3 of two neighbouring tiles);
-//     V is loaded as dwords (channel pair 2m, 2m+1 of those same keys) and
-//     split into an even-channel and an odd-channel A operand.  The two
+//     V is loaded as rows like K and turned by the matrix core (rows times a
+//     0/1 channel selector) into an even-channel and an odd-channel A operand
+//     with the keys on the k-slots.  The two
 //     accumulators of lane (g, n) then hold channels 8g..8g+7 of query row n:
 //     the row's softmax sum is in the same lane and the result leaves as one
 //     16-byte store, mirroring the Q load;
@@ -26,10 +27,9 @@
 //     columns are set to -inf.  The range check covers the vector offset and
 //     the immediate only, NOT the scalar offset operand, so every offset goes
 //     into the vector operand and the scalar one stays 0.
-#include <stdlib.h>
-
 #include "fwa_device.h"
 #include "fwa_internal.h"
+#include "fwa_softmax.h"
 
 namespace fwa {
 namespace {
@@ -85,7 +85,6 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) fwd_bf16_kernel(FwdArgs p
     const __amdgpu_buffer_rsrc_t rv = make_rsrc((const char*)p.v + tile, tile_bytes);
     const __amdgpu_buffer_rsrc_t ro = make_rsrc((char*)p.o + tile, tile_bytes);
     const uint32_t off_row = (uint32_t)n * row_bytes + 16u * g;  // 16 B of row n (plus a block offset)
-    const uint32_t off_v = 4u * g * row_bytes + 4u * n;          // channel pair n of row 4g (plus slot offset)
 
     // K: A operands of S^T, lane (g, n) = K[16 jb + n][8g .. 8g+7]
     bf16x8 kop[NB];
@@ -97,15 +96,28 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) fwd_bf16_kernel(FwdArgs p
 #pragma unroll
     for (int t = 0; t < QPW; ++t)
         qop[t] = as_bf16x8(__builtin_amdgcn_raw_buffer_load_b128(rq, off_row + 16 * (tc.qs * QPW + t) * row_bytes, 0, 0));
-    // V: A operands of O^T per pair of key blocks, even and odd channels
+    // V: A operands of O^T per pair of key blocks (keys on the k-slots, even resp. odd
+    // channels on the lane).
     bf16x8 vop[NB2][2];
+    {
+        // V is loaded as rows like K and turned into the operands by the matrix core
+        // (rows x channel selector): 16-byte loads only.
+        bf16x8 vrow[NB];
 #pragma unroll
-    for (int kp = 0; kp < NB2; ++kp) {
-        uint32_t d[8];
+        for (int jb = 0; jb < NB; ++jb)
+            vrow[jb] = as_bf16x8(__builtin_amdgcn_raw_buffer_load_b128(rv, off_row + 16 * jb * row_bytes, 0, 0));
+        const bf16x8 sel[2] = {channel_selector(g, n, 0), channel_selector(g, n, 1)};
+        const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int e = 0; e < 8; ++e)
-            d[e] = __builtin_amdgcn_raw_buffer_load_b32(rv, off_v + (32 * kp + slot_row(0, e)) * row_bytes, 0, 0);
-        split_pairs(d, vop[kp][0], vop[kp][1]);
+        for (int kp = 0; kp < NB2; ++kp)
+#pragma unroll
+            for (int c = 0; c < 2; ++c) {
+                const uint2 a = pack_exact_u2(mfma_bf16(vrow[2 * kp], sel[c], zero));
+                uint2 b = {0u, 0u};
+                if (2 * kp + 1 < NB) b = pack_exact_u2(mfma_bf16(vrow[2 * kp + 1 < NB ? 2 * kp + 1 : 0], sel[c], zero));
+                const u32x4 v = {a.x, a.y, b.x, b.y};
+                vop[kp][c] = as_bf16x8(v);
+            }
     }
 
     const float sl2 = p.scale * kLog2e;
@@ -128,80 +140,12 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) fwd_bf16_kernel(FwdArgs p
             const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
             s[jb] = mfma_bf16(kop[jb], qop[t], zero);  // s[jb][r] = S[16 qb + n][16 jb + 4g + r]
         }
-        // After this block s holds the score in a unit such that p = exp2(s * mul - mb).
-        float mul, mb;
-        if (BM) {
-            // Rows beyond L fall outside the descriptor (zero); columns beyond L are
-            // overwritten with -inf below, whatever was fetched for them.
-#pragma unroll
-            for (int jb = 0; jb < NB; ++jb) {
-                // 4 consecutive columns of one row: a 16-byte load that is only dword aligned;
-                // the range check of the descriptor is per dword.
-                const uint32_t off = off_b + ((uint32_t)(16 * qb) * L + 16 * jb) * 4u;
-                const f32x4 add = (load_f32x4(rb, off) + load_f32x4(rm, off)) * kLog2e;
-#pragma unroll
-                for (int r = 0; r < 4; ++r) s[jb][r] = fmaf(s[jb][r], sl2, add[r]);
-            }
-#pragma unroll
-            for (int r = 0; r < 4; ++r)
-                if (16 * (NB - 1) + 4 * g + r >= L) s[NB - 1][r] = -INFINITY;
-            float m = s[0][0];
-#pragma unroll
-            for (int jb = 0; jb < NB; ++jb) {
-                m = fmaxf(fmaxf(m, s[jb][0]), s[jb][1]);
-                m = fmaxf(fmaxf(m, s[jb][2]), s[jb][3]);
-            }
-            mul = 1.0f;
-            mb = max_over_g(m);
-        } else {
-            // No bias: keep the raw products and fold the scale into the exponent,
-            // p = exp2(s*sl2 - max(s*sl2)).  For sl2 >= 0 the maximum of the scaled
-            // scores is sl2 * max(s); a negative scale uses the minimum instead.
-            const float pad = sl2 >= 0.f ? -INFINITY : INFINITY;
-#pragma unroll
-            for (int r = 0; r < 4; ++r)
-                if (16 * (NB - 1) + 4 * g + r >= L) s[NB - 1][r] = pad;
-            float m = s[0][0];
-            if (sl2 >= 0.f) {
-#pragma unroll
-                for (int jb = 0; jb < NB; ++jb) {
-                    m = fmaxf(fmaxf(m, s[jb][0]), s[jb][1]);
-                    m = fmaxf(fmaxf(m, s[jb][2]), s[jb][3]);
-                }
-                m = max_over_g(m);
-            } else {
-#pragma unroll
-                for (int jb = 0; jb < NB; ++jb) {
-                    m = fminf(fminf(m, s[jb][0]), s[jb][1]);
-                    m = fminf(fminf(m, s[jb][2]), s[jb][3]);
-                }
-                m = -max_over_g(-m);
-            }
-            mul = sl2;
-            mb = m * sl2;
-        }
-        float sum = 0.f;
-#pragma unroll
-        for (int jb = 0; jb < NB; ++jb)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const float e = __builtin_amdgcn_exp2f(fmaf(s[jb][r], mul, -mb));
-                s[jb][r] = e;
-                sum += e;
-            }
-        sum = sum_over_g(sum);
-        const float inv = __builtin_amdgcn_rcpf(sum);
+        const float inv = softmax_block<NB, BM>(s, sl2, rb, rm, off_b + (uint32_t)(16 * qb) * L * 4u, L, g);
 
         f32x4 oe = {0.f, 0.f, 0.f, 0.f}, oo = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int kp = 0; kp < NB2; ++kp) {
-            u32x4 a;
-            a.x = pack_bf16(s[2 * kp][0], s[2 * kp][1]);
-            a.y = pack_bf16(s[2 * kp][2], s[2 * kp][3]);
-            const int j1 = 2 * kp + 1 < NB ? 2 * kp + 1 : 0;  // odd NB: the last pair has no second tile
-            a.z = 2 * kp + 1 < NB ? pack_bf16(s[j1][0], s[j1][1]) : 0u;
-            a.w = 2 * kp + 1 < NB ? pack_bf16(s[j1][2], s[j1][3]) : 0u;
-            const bf16x8 pop = as_bf16x8(a);
+            const bf16x8 pop = prob_operand<NB>(s, kp);
             oe = mfma_bf16(vop[kp][0], pop, oe);  // oe[r] = O[16 qb + n][2 (4g + r)]
             oo = mfma_bf16(vop[kp][1], pop, oo);  // oo[r] = O[16 qb + n][2 (4g + r) + 1]
         }
@@ -389,11 +333,19 @@ hipError_t launch_f32_nb(const FwdArgs& a, hipStream_t st) {
         default: return hipErrorInvalidValue;                         \
     }
 
+// bf16 dispatch: windows of up to 64 tokens whose heads form whole 128-byte lines per
+// workgroup take the LDS-staged kernel, longer windows the LDS row-blocked kernel (both in
+// fwa_forward_staged.hip).  The direct kernel above remains for L <= 64 with an odd number of
+// heads greater than 4, where no such grouping exists.
 hipError_t launch_forward_bf16(const FwdArgs& a, hipStream_t s) {
-    static const bool direct_only = getenv("FWA_FWD_DIRECT") != nullptr;  // experiment switch
-    if (!direct_only && staged_heads_per_block(a.L, a.heads) > 0) return launch_forward_bf16_staged(a, s);
-    const int nb = (a.L + 15) / 16;
-    FWA_NB_SWITCH(launch_bf16_nb, nb, a, s)
+    if (staged_heads_per_block(a.L, a.heads) > 0) return launch_forward_bf16_staged(a, s);
+    switch ((a.L + 15) / 16) {
+        case 1: return launch_bf16_nb<1>(a, s);
+        case 2: return launch_bf16_nb<2>(a, s);
+        case 3: return launch_bf16_nb<3>(a, s);
+        case 4: return launch_bf16_nb<4>(a, s);
+        default: return hipErrorInvalidValue;
+    }
 }
 
 hipError_t launch_forward_f32(const FwdArgs& a, hipStream_t s) {

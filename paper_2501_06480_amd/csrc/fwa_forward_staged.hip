@@ -16,6 +16,7 @@
 // 8 % of bandwidth against this pattern.
 #include "fwa_device.h"
 #include "fwa_internal.h"
+#include "fwa_softmax.h"
 
 namespace fwa {
 namespace {
@@ -127,72 +128,12 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) fwd_bf16_staged_kernel(Fw
             const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
             s[jb] = mfma_bf16(kop[jb], qop[qb], zero);  // S[16 qb + n][16 jb + 4g + r]
         }
-        float mul, mb;  // p = exp2(s * mul - mb)
-        if (BM) {
-#pragma unroll
-            for (int jb = 0; jb < NB; ++jb) {
-                const uint32_t off = off_b + ((uint32_t)(16 * qb) * L + 16 * jb) * 4u;
-                const f32x4 add = (load_f32x4(rb, off) + load_f32x4(rm, off)) * kLog2e;
-#pragma unroll
-                for (int r = 0; r < 4; ++r) s[jb][r] = fmaf(s[jb][r], sl2, add[r]);
-            }
-#pragma unroll
-            for (int r = 0; r < 4; ++r)
-                if (16 * (NB - 1) + 4 * g + r >= L) s[NB - 1][r] = -INFINITY;
-            float m = s[0][0];
-#pragma unroll
-            for (int jb = 0; jb < NB; ++jb) {
-                m = fmaxf(fmaxf(m, s[jb][0]), s[jb][1]);
-                m = fmaxf(fmaxf(m, s[jb][2]), s[jb][3]);
-            }
-            mul = 1.0f;
-            mb = max_over_g(m);
-        } else {
-            const float pad = sl2 >= 0.f ? -INFINITY : INFINITY;
-#pragma unroll
-            for (int r = 0; r < 4; ++r)
-                if (16 * (NB - 1) + 4 * g + r >= L) s[NB - 1][r] = pad;
-            float m = s[0][0];
-            if (sl2 >= 0.f) {
-#pragma unroll
-                for (int jb = 0; jb < NB; ++jb) {
-                    m = fmaxf(fmaxf(m, s[jb][0]), s[jb][1]);
-                    m = fmaxf(fmaxf(m, s[jb][2]), s[jb][3]);
-                }
-                m = max_over_g(m);
-            } else {
-#pragma unroll
-                for (int jb = 0; jb < NB; ++jb) {
-                    m = fminf(fminf(m, s[jb][0]), s[jb][1]);
-                    m = fminf(fminf(m, s[jb][2]), s[jb][3]);
-                }
-                m = -max_over_g(-m);
-            }
-            mul = sl2;
-            mb = m * sl2;
-        }
-        float sum = 0.f;
-#pragma unroll
-        for (int jb = 0; jb < NB; ++jb)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const float e = __builtin_amdgcn_exp2f(fmaf(s[jb][r], mul, -mb));
-                s[jb][r] = e;
-                sum += e;
-            }
-        sum = sum_over_g(sum);
-        const float inv = __builtin_amdgcn_rcpf(sum);
+        const float inv = softmax_block<NB, BM>(s, sl2, rb, rm, off_b + (uint32_t)(16 * qb) * L * 4u, L, g);
 
         f32x4 o0 = {0.f, 0.f, 0.f, 0.f}, o1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int kp = 0; kp < NB2; ++kp) {
-            u32x4 a;
-            a.x = pack_bf16(s[2 * kp][0], s[2 * kp][1]);
-            a.y = pack_bf16(s[2 * kp][2], s[2 * kp][3]);
-            const int j1 = 2 * kp + 1 < NB ? 2 * kp + 1 : 0;
-            a.z = 2 * kp + 1 < NB ? pack_bf16(s[j1][0], s[j1][1]) : 0u;
-            a.w = 2 * kp + 1 < NB ? pack_bf16(s[j1][2], s[j1][3]) : 0u;
-            const bf16x8 pop = as_bf16x8(a);
+            const bf16x8 pop = prob_operand<NB>(s, kp);
             o0 = mfma_bf16(vop[kp][0], pop, o0);  // o0[r] = O[16 qb + n][4g + r]
             o1 = mfma_bf16(vop[kp][1], pop, o1);  // o1[r] = O[16 qb + n][16 + 4g + r]
         }
@@ -213,6 +154,150 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) fwd_bf16_staged_kernel(Fw
         const u32x4 v = __builtin_bit_cast(u32x4, lq[loff + 16 * t * stride]);
         __builtin_amdgcn_raw_buffer_store_b128(v, ro, goff + 16 * t * row_bytes, 0, 0);
     }
+}
+
+// ---------------------------------------------------------------------------
+// Row-blocked forward for 64 < L <= 256 (paper Discussion: such windows do not fit its
+// on-chip tile; here K and V of the head stay on chip and the queries are walked in blocks
+// of 16).  The workgroup parks the K and V slabs of its heads in LDS once; two waves share
+// each head and take alternate 16-query blocks.  Per block a wave reads its K operands
+// (ds_read_b128) and V operands (transposing reads) from LDS, keeps the 16 x L score block
+// in registers, and loads Q / stores O for its own rows directly.
+struct RowBlockGeom {
+    FastDiv groups;         // workgroups per window
+    FastDiv lanes_per_row;  // 4 * heads_per_block
+    uint32_t heads_per_block;
+    uint32_t xcd_remap, xcd_q, xcd_r;
+};
+
+template <int NB, bool BM>
+__global__ void __launch_bounds__(64 * kWavesPerBlock) fwd_bf16_rowblock_kernel(FwdArgs p, RowBlockGeom gm) {
+    constexpr int NB2 = (NB + 1) / 2;
+    constexpr int ROWS = 16 * NB;
+    constexpr int PASSES = (ROWS + 31) / 32;  // the workgroup moves 32 slab rows per pass
+    extern __shared__ __attribute__((aligned(16))) uint4 lds[];  // [2][ROWS][stride]: K, V
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int n = lane & 15, g = lane >> 4;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const uint32_t hl = wave >> 1, qs = wave & 1u;
+    const uint32_t lb = gm.xcd_remap ? xcd_logical_block(blockIdx.x, gm.xcd_q, gm.xcd_r) : blockIdx.x;
+    const uint32_t w = fastdiv(lb, gm.groups);
+    const uint32_t hg = lb - w * gm.groups.d;
+    const uint32_t hpb = gm.heads_per_block;
+    const uint32_t h = hg * hpb + hl;
+    const int L = p.L;
+    const uint32_t row_bytes = (uint32_t)p.C * 2u;
+    const uint32_t stride = 4u * hpb + 1u;  // LDS row stride in 16-byte units
+
+    uint4* const lk = lds;
+    uint4* const lv = lds + ROWS * stride;
+    {
+        const uint32_t rip = fastdiv((uint32_t)tid, gm.lanes_per_row);  // 0..31
+        const uint32_t col = (uint32_t)tid - rip * gm.lanes_per_row.d;
+        const size_t slab = ((size_t)w * L * p.C + (size_t)hg * hpb * kHeadDim) * 2u;
+        const uint32_t slab_bytes = (uint32_t)(L - 1) * row_bytes + hpb * 2u * kHeadDim;
+        const __amdgpu_buffer_rsrc_t rk = make_rsrc((const char*)p.k + slab, slab_bytes);
+        const __amdgpu_buffer_rsrc_t rv = make_rsrc((const char*)p.v + slab, slab_bytes);
+        u32x4 sk[PASSES], sv[PASSES];
+#pragma unroll
+        for (int t = 0; t < PASSES; ++t) {
+            const uint32_t off = (32 * t + rip) * row_bytes + col * 16u;  // rows beyond L arrive as zeros
+            sk[t] = __builtin_amdgcn_raw_buffer_load_b128(rk, off, 0, 0);
+            sv[t] = __builtin_amdgcn_raw_buffer_load_b128(rv, off, 0, 0);
+        }
+#pragma unroll
+        for (int t = 0; t < PASSES; ++t) {
+            const uint32_t row = 32 * t + rip;
+            if (row < (uint32_t)ROWS) {
+                lk[row * stride + col] = __builtin_bit_cast(uint4, sk[t]);
+                lv[row * stride + col] = __builtin_bit_cast(uint4, sv[t]);
+            }
+        }
+    }
+    __syncthreads();
+
+    const uint32_t tile_bytes = (uint32_t)(L - 1) * row_bytes + 2u * kHeadDim;
+    const size_t tile = ((size_t)w * L * p.C + (size_t)h * kHeadDim) * 2u;
+    const __amdgpu_buffer_rsrc_t rq = make_rsrc((const char*)p.q + tile, tile_bytes);
+    const __amdgpu_buffer_rsrc_t ro = make_rsrc((char*)p.o + tile, tile_bytes);
+    const uint32_t off_row = (uint32_t)n * row_bytes + 16u * g;
+    const float sl2 = p.scale * kLog2e;
+    __amdgpu_buffer_rsrc_t rb = make_rsrc(nullptr, 0), rm = make_rsrc(nullptr, 0);
+    if (BM) {
+        const uint32_t ll = (uint32_t)L * L * 4u;
+        if (p.bias) rb = make_rsrc(p.bias + (size_t)h * L * L, ll);
+        if (p.mask) rm = make_rsrc(p.mask + (size_t)(w % (uint32_t)p.nW) * L * L, ll);
+    }
+    const uint32_t off_b = ((uint32_t)n * L + 4u * g) * 4u;
+    const uint4* const lkh = lk + n * stride + 4 * hl + g;  // K[16 jb + n][8g..] at lkh[16 jb * stride]
+    const uint16_t* const lvh = reinterpret_cast<const uint16_t*>(lv) + 32 * hl +
+                                (4 * g + (n >> 2)) * (stride * 8u) + 4 * (n & 3);
+
+    u32x4 qnext = __builtin_amdgcn_raw_buffer_load_b128(rq, off_row + 16 * qs * row_bytes, 0, 0);
+    for (int qb = qs; qb < NB; qb += 2) {
+        const bf16x8 qop = as_bf16x8(qnext);
+        if (qb + 2 < NB) qnext = __builtin_amdgcn_raw_buffer_load_b128(rq, off_row + 16 * (qb + 2) * row_bytes, 0, 0);
+        f32x4 s[NB];
+#pragma unroll
+        for (int jb = 0; jb < NB; ++jb) {
+            const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+            const bf16x8 kop = __builtin_bit_cast(bf16x8, lkh[16 * jb * stride]);
+            s[jb] = mfma_bf16(kop, qop, zero);  // S[16 qb + n][16 jb + 4g + r]
+        }
+        const float inv = softmax_block<NB, BM>(s, sl2, rb, rm, off_b + (uint32_t)(16 * qb) * L * 4u, L, g);
+        f32x4 o0 = {0.f, 0.f, 0.f, 0.f}, o1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int kp = 0; kp < NB2; ++kp) {
+            const bf16x8 pop = prob_operand<NB>(s, kp);
+#pragma unroll
+            for (int c = 0; c < 2; ++c) {
+                const uint2 a = lds_read_tr(lvh + (32 * kp) * (stride * 8u) + 16 * c);
+                uint2 b = {0u, 0u};
+                if (2 * kp + 1 < NB) b = lds_read_tr(lvh + (32 * kp + 16) * (stride * 8u) + 16 * c);
+                const u32x4 v = {a.x, a.y, b.x, b.y};
+                if (c == 0)
+                    o0 = mfma_bf16(as_bf16x8(v), pop, o0);  // o0[r] = O[16 qb + n][4g + r]
+                else
+                    o1 = mfma_bf16(as_bf16x8(v), pop, o1);  // o1[r] = O[16 qb + n][16 + 4g + r]
+            }
+        }
+        typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+        u32x2 lo, hi;
+        lo.x = pack_bf16(o0[0] * inv, o0[1] * inv);
+        lo.y = pack_bf16(o0[2] * inv, o0[3] * inv);
+        hi.x = pack_bf16(o1[0] * inv, o1[1] * inv);
+        hi.y = pack_bf16(o1[2] * inv, o1[3] * inv);
+        const uint32_t off_o = (uint32_t)(16 * qb + n) * row_bytes + 8u * g;
+        __builtin_amdgcn_raw_buffer_store_b64(lo, ro, off_o, 0, 0);
+        __builtin_amdgcn_raw_buffer_store_b64(hi, ro, off_o + 32, 0, 0);
+    }
+}
+
+template <int NB>
+hipError_t launch_rowblock_nb(const FwdArgs& a, hipStream_t st) {
+    RowBlockGeom gm;
+    const int hpb = a.heads % 2 == 0 ? 2 : 1;
+    const uint32_t groups = (uint32_t)(a.heads / hpb);
+    gm.groups = make_fastdiv(groups);
+    gm.lanes_per_row = make_fastdiv(4u * (uint32_t)hpb);
+    gm.heads_per_block = (uint32_t)hpb;
+    const unsigned grid = (unsigned)(a.N * groups), block = 128u * (unsigned)hpb;
+    gm.xcd_remap = (hpb == 1 && groups > 1) ? 1u : 0u;  // 64 B slabs: keep line-sharing heads on one L2
+    gm.xcd_q = grid / 8u;
+    gm.xcd_r = grid % 8u;
+    const size_t lds = (size_t)2 * 16 * NB * (4 * hpb + 1) * 16;
+    const bool bm = a.bias || a.mask;
+    const void* fn = bm ? reinterpret_cast<const void*>(&fwd_bf16_rowblock_kernel<NB, true>)
+                        : reinterpret_cast<const void*>(&fwd_bf16_rowblock_kernel<NB, false>);
+    if (lds > 64 * 1024) {
+        const hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+    }
+    if (bm)
+        hipLaunchKernelGGL((fwd_bf16_rowblock_kernel<NB, true>), dim3(grid), dim3(block), lds, st, a, gm);
+    else
+        hipLaunchKernelGGL((fwd_bf16_rowblock_kernel<NB, false>), dim3(grid), dim3(block), lds, st, a, gm);
+    return hipGetLastError();
 }
 
 template <int NB>
@@ -237,7 +322,7 @@ hipError_t launch_staged_nb(const FwdArgs& a, int hpb, hipStream_t st) {
 // slab of a workgroup must consist of whole 128-byte lines per row (an even
 // number of heads) or be the whole row.
 int staged_heads_per_block(int L, int heads) {
-    if (L > 64) return 0;
+    if (L > 64) return heads % 2 == 0 ? 2 : 1;
     if (heads <= kWavesPerBlock) return heads;
     if (heads % 4 == 0) return 4;
     if (heads % 2 == 0) return 2;
@@ -251,6 +336,18 @@ hipError_t launch_forward_bf16_staged(const FwdArgs& a, hipStream_t s) {
         case 2: return launch_staged_nb<2>(a, hpb, s);
         case 3: return launch_staged_nb<3>(a, hpb, s);
         case 4: return launch_staged_nb<4>(a, hpb, s);
+        case 5: return launch_rowblock_nb<5>(a, s);
+        case 6: return launch_rowblock_nb<6>(a, s);
+        case 7: return launch_rowblock_nb<7>(a, s);
+        case 8: return launch_rowblock_nb<8>(a, s);
+        case 9: return launch_rowblock_nb<9>(a, s);
+        case 10: return launch_rowblock_nb<10>(a, s);
+        case 11: return launch_rowblock_nb<11>(a, s);
+        case 12: return launch_rowblock_nb<12>(a, s);
+        case 13: return launch_rowblock_nb<13>(a, s);
+        case 14: return launch_rowblock_nb<14>(a, s);
+        case 15: return launch_rowblock_nb<15>(a, s);
+        case 16: return launch_rowblock_nb<16>(a, s);
         default: return hipErrorInvalidValue;
     }
 }

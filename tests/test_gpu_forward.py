@@ -102,6 +102,30 @@ def test_window_lengths_that_are_not_squares(oracle, dtype, L):
     assert err <= TOL[dtype]
 
 
+@pytest.mark.parametrize("L", [49, 100])
+@pytest.mark.parametrize("heads", [1, 2, 3, 4, 5, 6, 7, 8, 9, 12])
+def test_head_counts_reach_every_kernel_variant(oracle, heads, L):
+    """Odd/even head counts select different workgroup shapes (and, for L <= 64 with an odd
+    count above 4, the kernel that reads head slices directly)."""
+    import torch
+    import paper_2501_06480_amd as fwa
+    N = 6
+    w = synth.Workload(f"heads{heads}_L{L}", N, L, 32 * heads, heads, "bf16", 6000 + heads + L, 0)
+    x = synth.draw(w)
+    bias = synth.normal((heads, L, L), 13 + heads, 0.5)
+    mask = np.where(synth.rng(17 + heads).random((3, L, L)) < 0.2, -100.0, 0.0).astype(np.float32)
+    mask[:, np.arange(L), np.arange(L)] = 0.0
+    q, k, v = (to_device(x, w, n) for n in ("q", "k", "v"))
+    for use_bm in (False, True):
+        o = fwa.fwa_forward(q, k, v, heads, w.scale, f32_device(bias) if use_bm else None,
+                            f32_device(mask) if use_bm else None)
+        torch.cuda.synchronize()
+        want = oracle.forward(x["q"], x["k"], x["v"], heads, w.scale, bias if use_bm else None,
+                              mask if use_bm else None)
+        err = max_abs(to_f64(o), want)
+        assert err <= TOL["bf16"], (heads, L, use_bm, err)
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_bias_only_mask_only_and_neither(oracle, dtype):
     import torch
