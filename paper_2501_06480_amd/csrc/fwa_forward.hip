@@ -140,7 +140,8 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) fwd_bf16_kernel(FwdArgs p
             const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
             s[jb] = mfma_bf16(kop[jb], qop[t], zero);  // s[jb][r] = S[16 qb + n][16 jb + 4g + r]
         }
-        const float inv = softmax_block<NB, BM>(s, sl2, rb, rm, off_b + (uint32_t)(16 * qb) * L * 4u, L, g);
+        const AddendGlobal addend = {rb, rm, off_b + (uint32_t)(16 * qb) * L * 4u};
+        const float inv = softmax_block<NB, BM>(s, sl2, addend, L, g);
 
         f32x4 oe = {0.f, 0.f, 0.f, 0.f}, oo = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll

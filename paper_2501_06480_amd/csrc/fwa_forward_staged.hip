@@ -128,7 +128,8 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) fwd_bf16_staged_kernel(Fw
             const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
             s[jb] = mfma_bf16(kop[jb], qop[qb], zero);  // S[16 qb + n][16 jb + 4g + r]
         }
-        const float inv = softmax_block<NB, BM>(s, sl2, rb, rm, off_b + (uint32_t)(16 * qb) * L * 4u, L, g);
+        const AddendGlobal addend = {rb, rm, off_b + (uint32_t)(16 * qb) * L * 4u};
+        const float inv = softmax_block<NB, BM>(s, sl2, addend, L, g);
 
         f32x4 o0 = {0.f, 0.f, 0.f, 0.f}, o1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -153,6 +154,142 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) fwd_bf16_staged_kernel(Fw
     for (int t = 0; t < NB; ++t) {
         const u32x4 v = __builtin_bit_cast(u32x4, lq[loff + 16 * t * stride]);
         __builtin_amdgcn_raw_buffer_store_b128(v, ro, goff + 16 * t * row_bytes, 0, 0);
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Persistent variant of the staged kernel for calls with a bias and/or mask.
+//
+// Re-reading the bias tile (L x L fp32 per head, as large as the head's Q/K/V/O traffic) for
+// every window costs as much time as the window's own data even though it comes from L2.  Here a
+// workgroup keeps its heads and walks the windows bw, bw + G, bw + 2G, ...; G is a multiple of
+// nW, so all of them share the mask tile bw % nW.  Each wave therefore loads
+// (bias[h] + mask[bw % nW]) * log2e ONCE, straight into the registers of the score layout, and
+// the per-window work is that of the bias-free kernel plus one fused multiply-add per score.
+// The slab of the next window is requested before the current one is computed.
+template <int NB>
+__global__ void __launch_bounds__(64 * kWavesPerBlock) fwd_bf16_persistent_kernel(FwdArgs p, StagedGeom gm, uint32_t G) {
+    constexpr int NB2 = (NB + 1) / 2;
+    constexpr int ROWS = 16 * NB;
+    extern __shared__ __attribute__((aligned(16))) uint4 lds[];  // [3][ROWS][stride]: K, V, Q (then O)
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int n = lane & 15, g = lane >> 4;
+    const uint32_t hl = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const uint32_t bw = fastdiv(blockIdx.x, gm.groups);
+    const uint32_t hg = blockIdx.x - bw * gm.groups.d;
+    const uint32_t hpb = gm.heads_per_block;
+    const uint32_t h = hg * hpb + hl;
+    const int L = p.L;
+    const uint32_t row_bytes = (uint32_t)p.C * 2u;
+    const uint32_t stride = 4u * hpb + 1u;
+    const float sl2 = p.scale * kLog2e;
+
+    // the additive term of this wave's head and this workgroup's mask tile, in score layout
+    f32x4 add[NB][NB];
+    {
+        const uint32_t ll = (uint32_t)L * L * 4u;
+        const __amdgpu_buffer_rsrc_t rb = p.bias ? make_rsrc(p.bias + (size_t)h * L * L, ll) : make_rsrc(nullptr, 0);
+        const __amdgpu_buffer_rsrc_t rm =
+            p.mask ? make_rsrc(p.mask + (size_t)(bw % (uint32_t)p.nW) * L * L, ll) : make_rsrc(nullptr, 0);
+        const uint32_t off_b = ((uint32_t)n * L + 4u * g) * 4u;
+#pragma unroll
+        for (int qb = 0; qb < NB; ++qb) {
+            const AddendGlobal src = {rb, rm, off_b + (uint32_t)(16 * qb) * L * 4u};
+#pragma unroll
+            for (int jb = 0; jb < NB; ++jb) add[qb][jb] = src(jb);
+        }
+    }
+
+    const uint32_t rip = fastdiv((uint32_t)tid, gm.lanes_per_row);
+    const uint32_t col = (uint32_t)tid - rip * gm.lanes_per_row.d;
+    const uint32_t slab_bytes = (uint32_t)(L - 1) * row_bytes + hpb * 2u * kHeadDim;
+    const uint32_t goff = rip * row_bytes + col * 16u;
+    const uint32_t loff = rip * stride + col;
+    uint4* const lk = lds;
+    uint4* const lv = lds + ROWS * stride;
+    uint4* const lq = lds + 2 * ROWS * stride;
+    const uint16_t* const lvh = reinterpret_cast<const uint16_t*>(lv) + 32 * hl +
+                                (4 * g + (n >> 2)) * (stride * 8u) + 4 * (n & 3);
+
+    u32x4 sk[NB], sv[NB], sq[NB];
+    auto request = [&](uint32_t w) {
+        const size_t slab = ((size_t)w * L * p.C + (size_t)hg * hpb * kHeadDim) * 2u;
+        const __amdgpu_buffer_rsrc_t rq = make_rsrc((const char*)p.q + slab, slab_bytes);
+        const __amdgpu_buffer_rsrc_t rk = make_rsrc((const char*)p.k + slab, slab_bytes);
+        const __amdgpu_buffer_rsrc_t rv = make_rsrc((const char*)p.v + slab, slab_bytes);
+#pragma unroll
+        for (int t = 0; t < NB; ++t) {
+            sk[t] = __builtin_amdgcn_raw_buffer_load_b128(rk, goff + 16 * t * row_bytes, 0, 0);
+            sq[t] = __builtin_amdgcn_raw_buffer_load_b128(rq, goff + 16 * t * row_bytes, 0, 0);
+            sv[t] = __builtin_amdgcn_raw_buffer_load_b128(rv, goff + 16 * t * row_bytes, 0, 0);
+        }
+    };
+    if (bw < (uint32_t)p.N) request(bw);
+
+    for (uint32_t w = bw; w < (uint32_t)p.N; w += G) {
+#pragma unroll
+        for (int t = 0; t < NB; ++t) {
+            lk[loff + 16 * t * stride] = __builtin_bit_cast(uint4, sk[t]);
+            lq[loff + 16 * t * stride] = __builtin_bit_cast(uint4, sq[t]);
+            lv[loff + 16 * t * stride] = __builtin_bit_cast(uint4, sv[t]);
+        }
+        __syncthreads();
+        bf16x8 kop[NB], qop[NB];
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            kop[b] = __builtin_bit_cast(bf16x8, lk[(16 * b + n) * stride + 4 * hl + g]);
+            qop[b] = __builtin_bit_cast(bf16x8, lq[(16 * b + n) * stride + 4 * hl + g]);
+        }
+        bf16x8 vop[NB2][2];
+#pragma unroll
+        for (int kp = 0; kp < NB2; ++kp)
+#pragma unroll
+            for (int c = 0; c < 2; ++c) {
+                const uint2 a = lds_read_tr(lvh + (32 * kp) * (stride * 8u) + 16 * c);
+                uint2 b = {0u, 0u};
+                if (2 * kp + 1 < NB) b = lds_read_tr(lvh + (32 * kp + 16) * (stride * 8u) + 16 * c);
+                const u32x4 v = {a.x, a.y, b.x, b.y};
+                vop[kp][c] = as_bf16x8(v);
+            }
+        if (w + G < (uint32_t)p.N) request(w + G);  // in flight while this window is computed
+
+#pragma unroll
+        for (int qb = 0; qb < NB; ++qb) {
+            f32x4 s[NB];
+#pragma unroll
+            for (int jb = 0; jb < NB; ++jb) {
+                const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+                s[jb] = mfma_bf16(kop[jb], qop[qb], zero);
+            }
+            const AddendRegs<NB> addend = {add[qb]};
+            const float inv = softmax_block<NB, true>(s, sl2, addend, L, g);
+            f32x4 o0 = {0.f, 0.f, 0.f, 0.f}, o1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int kp = 0; kp < NB2; ++kp) {
+                const bf16x8 pop = prob_operand<NB>(s, kp);
+                o0 = mfma_bf16(vop[kp][0], pop, o0);
+                o1 = mfma_bf16(vop[kp][1], pop, o1);
+            }
+            uint2 lo, hi;
+            lo.x = pack_bf16(o0[0] * inv, o0[1] * inv);
+            lo.y = pack_bf16(o0[2] * inv, o0[3] * inv);
+            hi.x = pack_bf16(o1[0] * inv, o1[1] * inv);
+            hi.y = pack_bf16(o1[2] * inv, o1[3] * inv);
+            uint2* row = reinterpret_cast<uint2*>(lq + (16 * qb + n) * stride + 4 * hl);
+            row[g] = lo;
+            row[4 + g] = hi;
+        }
+        __syncthreads();
+        {
+            const size_t slab = ((size_t)w * L * p.C + (size_t)hg * hpb * kHeadDim) * 2u;
+            const __amdgpu_buffer_rsrc_t ro = make_rsrc((char*)p.o + slab, slab_bytes);
+#pragma unroll
+            for (int t = 0; t < NB; ++t) {
+                const u32x4 v = __builtin_bit_cast(u32x4, lq[loff + 16 * t * stride]);
+                __builtin_amdgcn_raw_buffer_store_b128(v, ro, goff + 16 * t * row_bytes, 0, 0);
+            }
+        }
+        __syncthreads();  // the slabs are rewritten at the top of the next iteration
     }
 }
 
@@ -244,7 +381,8 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) fwd_bf16_rowblock_kernel(
             const bf16x8 kop = __builtin_bit_cast(bf16x8, lkh[16 * jb * stride]);
             s[jb] = mfma_bf16(kop, qop, zero);  // S[16 qb + n][16 jb + 4g + r]
         }
-        const float inv = softmax_block<NB, BM>(s, sl2, rb, rm, off_b + (uint32_t)(16 * qb) * L * 4u, L, g);
+        const AddendGlobal addend = {rb, rm, off_b + (uint32_t)(16 * qb) * L * 4u};
+        const float inv = softmax_block<NB, BM>(s, sl2, addend, L, g);
         f32x4 o0 = {0.f, 0.f, 0.f, 0.f}, o1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int kp = 0; kp < NB2; ++kp) {
@@ -309,8 +447,20 @@ hipError_t launch_staged_nb(const FwdArgs& a, int hpb, hipStream_t st) {
     gm.heads_per_block = (uint32_t)hpb;
     const unsigned grid = (unsigned)(a.N * groups), block = 64u * (unsigned)hpb;
     const size_t lds = (size_t)3 * 16 * NB * (4 * hpb + 1) * 16;
-    if (a.bias || a.mask)
+    if (a.bias || a.mask) {
+        // Persistent walk over G window positions: a multiple of nW so that a workgroup always
+        // sees the same mask tile, about 4 workgroups per CU (measured best of 2..8), at least 2
+        // windows per workgroup, and enough workgroups to cover the chip; else one window each.
+        const long long nW = a.mask ? a.nW : 1;
+        long long G = (4 * 256 / (long long)groups) / nW * nW;
+        if (G > a.N / 2) G = (a.N / 2) / nW * nW;
+        if (G >= nW && G > 0 && G * groups >= 512) {
+            hipLaunchKernelGGL((fwd_bf16_persistent_kernel<NB>), dim3((unsigned)(G * groups)), dim3(block), lds, st,
+                               a, gm, (uint32_t)G);
+            return hipGetLastError();
+        }
         hipLaunchKernelGGL((fwd_bf16_staged_kernel<NB, true>), dim3(grid), dim3(block), lds, st, a, gm);
+    }
     else
         hipLaunchKernelGGL((fwd_bf16_staged_kernel<NB, false>), dim3(grid), dim3(block), lds, st, a, gm);
     return hipGetLastError();

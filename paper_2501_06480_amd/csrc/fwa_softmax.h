@@ -7,22 +7,38 @@
 
 namespace fwa {
 
+// Where the additive term of the scores (bias + mask, in log2 units) comes from.
+// AddendGlobal: two buffer descriptors (absent tensor = null descriptor = zeros); every load
+// takes 4 consecutive columns of one row: 16 bytes, only dword aligned; the range check is per
+// dword, rows beyond L fall outside the descriptor and read as zero.
+struct AddendGlobal {
+    __amdgpu_buffer_rsrc_t rb, rm;
+    uint32_t off;  // byte offset of element [i0 + n][4g] of the tile
+    __device__ __forceinline__ f32x4 operator()(int jb) const {
+        return (load_f32x4(rb, off + 16 * jb * 4u) + load_f32x4(rm, off + 16 * jb * 4u)) * kLog2e;
+    }
+};
+// AddendRegs: the term is already in registers (one f32x4 per key block), times log2e.
+template <int NB>
+struct AddendRegs {
+    const f32x4 (&a)[NB];
+    __device__ __forceinline__ f32x4 operator()(int jb) const { return a[jb]; }
+};
+struct AddendNone {
+    __device__ __forceinline__ f32x4 operator()(int) const { return f32x4{0.f, 0.f, 0.f, 0.f}; }
+};
+
 // On entry s holds the raw products.  On exit s holds exp(score - rowmax), not yet
-// normalised; the return value is 1 / rowsum.  Scores are
-//     scale * s + B[i][j] + M[i][j]        (B, M through the descriptors rb, rm; absent = zeros)
-// and columns j >= L are excluded.  off_b is the byte offset of B[i0 + n][4g] in the tile.
-template <int NB, bool BM>
-__device__ __forceinline__ float softmax_block(f32x4 (&s)[NB], float sl2, __amdgpu_buffer_rsrc_t rb,
-                                               __amdgpu_buffer_rsrc_t rm, uint32_t off_b, int L, int g) {
+// normalised; the return value is 1 / rowsum.  Scores are scale * s + addend (BM) or
+// scale * s (no bias/mask), and columns j >= L are excluded.
+template <int NB, bool BM, class Addend>
+__device__ __forceinline__ float softmax_block(f32x4 (&s)[NB], float sl2, const Addend& addend, int L, int g) {
     float mul, mb;  // p = exp2(s * mul - mb)
     if (BM) {
-        // Rows beyond L fall outside the descriptors (zeros); columns beyond L are overwritten
-        // with -inf below, whatever was fetched for them.  Each load takes 4 consecutive columns
-        // of one row: 16 bytes, only dword aligned; the range check is per dword.
+        // Columns beyond L are overwritten with -inf below, whatever was fetched for them.
 #pragma unroll
         for (int jb = 0; jb < NB; ++jb) {
-            const uint32_t off = off_b + 16 * jb * 4u;
-            const f32x4 add = (load_f32x4(rb, off) + load_f32x4(rm, off)) * kLog2e;
+            const f32x4 add = addend(jb);
 #pragma unroll
             for (int r = 0; r < 4; ++r) s[jb][r] = fmaf(s[jb][r], sl2, add[r]);
         }

@@ -63,6 +63,27 @@ def test_swin_t_stages_bias_and_mask_bf16(oracle, stage, shifted):
     check_forward(oracle, w.with_N(n_small))
 
 
+@pytest.mark.parametrize("stage,N", [(1, 2560), (2, 1008), (3, 1028)])
+@pytest.mark.parametrize("which", ["bias+mask", "bias", "mask"])
+def test_many_windows_per_workgroup_with_bias_and_mask(oracle, stage, N, which):
+    """Enough windows that each workgroup walks several of them with its bias/mask term held
+    on chip (the window count is not a multiple of the workgroup count: uneven walks)."""
+    import torch
+    import paper_2501_06480_amd as fwa
+    w = synth.swin_t_stage(stage, shifted=True).with_N(N)
+    assert N % w.nW == 0
+    x = synth.draw(w)
+    bias64 = oracle.bias_gather(x["table"], w.k) if "bias" in which else None
+    mask = x["mask"] if "mask" in which else None
+    q, k, v = (to_device(x, w, n) for n in ("q", "k", "v"))
+    o = fwa.fwa_forward(q, k, v, w.heads, w.scale, f32_device(bias64), f32_device(mask))
+    torch.cuda.synchronize()
+    want = oracle.forward(x["q"], x["k"], x["v"], w.heads, w.scale, bias64, mask)
+    err = max_abs(to_f64(o), want)
+    print(f"{w.name} {which}: err={err:.3e}", flush=True)
+    assert err <= TOL["bf16"]
+
+
 def test_stage4_single_window_map_with_mask(oracle):
     """A 7x7 map is one window; the shift mask then has 4 regions inside it."""
     w = synth.Workload("s4_masked", 8, 49, 768, 24, "bf16", 1234, 7, 7, True, 3)
