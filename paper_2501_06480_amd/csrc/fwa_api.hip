@@ -73,7 +73,8 @@ int fwa_forward(const void* q, const void* k, const void* v, void* o, int64_t N,
 size_t fwa_backward_workspace_bytes(int64_t N, int L, int C, int heads, int dtype, int want_dbias) {
     if (check_shape(N, L, C, heads, dtype) != FWA_OK || check_backward_support(L, dtype) != FWA_OK) return 0;
     if (!want_dbias || N == 0) return 0;
-    return (size_t)fwa::backward_slots(N, heads) * heads * L * L * sizeof(float);
+    // the slot count depends on the mask period; this is its upper bound over all periods
+    return (size_t)fwa::backward_max_slots(N, heads) * heads * L * L * sizeof(float);
 }
 
 int fwa_backward(const void* q, const void* k, const void* v, const void* d_o, void* dq, void* dk, void* dv,
@@ -114,7 +115,7 @@ int fwa_backward(const void* q, const void* k, const void* v, const void* d_o, v
     a.partial = dbias ? static_cast<float*>(workspace) : nullptr;
     a.bias = bias; a.mask = mask;
     a.N = N; a.L = L; a.C = C; a.heads = heads; a.nW = mask ? nW : 1; a.scale = scale;
-    a.slots = fwa::backward_slots(N, heads);
+    a.slots = fwa::backward_slots(N, heads, mask ? nW : 1);
     const hipError_t e = dtype == FWA_BF16 ? fwa::launch_backward_bf16(a, st) : fwa::launch_backward_f32(a, st);
     return e == hipSuccess ? FWA_OK : FWA_ERR_LAUNCH;
 }

@@ -44,25 +44,6 @@ struct BwdGeom {
     uint32_t slots;  // workgroups along the window axis; window w is handled by slot w % slots
 };
 
-// x = hi + lo with hi the upper 16 bits of x (a bf16 by truncation) and lo the
-// remainder rounded to bf16: together 16 significant bits.
-__device__ __forceinline__ void split_hi_lo(const f32x4& x, bf16x4& hi, bf16x4& lo) {
-    uint32_t u[4];
-    float rem[4];
-#pragma unroll
-    for (int c = 0; c < 4; ++c) {
-        const float xc = x[c];
-        u[c] = __builtin_bit_cast(uint32_t, xc);
-        rem[c] = xc - __builtin_bit_cast(float, u[c] & 0xffff0000u);
-    }
-    uint2 h, l;
-    h.x = upper_halves(u[0], u[1]);
-    h.y = upper_halves(u[2], u[3]);
-    l.x = pack_bf16(rem[0], rem[1]);
-    l.y = pack_bf16(rem[2], rem[3]);
-    hi = as_bf16x4(h);
-    lo = as_bf16x4(l);
-}
 // The row operands of the next window are fetched while the current one is computed: the
 // loads write straight into a per-wave LDS stage (one 16-byte slot per lane and 16-row
 // block, i.e. already in operand order) and are picked up at the top of the next iteration.
@@ -377,18 +358,15 @@ hipError_t launch_bwd_nb(const BwdArgs& a, hipStream_t st) {
         e = db ? launch_one<NB, true, true>(a, gm, grid, block, st) : launch_one<NB, true, false>(a, gm, grid, block, st);
     else
         e = db ? launch_one<NB, false, true>(a, gm, grid, block, st) : launch_one<NB, false, false>(a, gm, grid, block, st);
-    if (e != hipSuccess || !db) return e;
-    const size_t count = (size_t)a.heads * a.L * a.L;
-    hipLaunchKernelGGL(dbias_reduce_kernel, dim3((unsigned)((count + 63) / 64)), dim3(64 * kReduceRows), 0, st,
-                       a.partial, a.dbias, a.slots, count);
-    return hipGetLastError();
+    return e;
 }
 
 }  // namespace
 
-// Workgroups along the window axis.  Enough to fill the chip (two waves per
-// SIMD), few enough that the per-slot dBias partial sums stay small.
-int backward_slots(long long N, int heads) {
+// Workgroups along the window axis (= dBias slots).  The cooperative kernel is used whenever
+// its workgroup shape fits the head count and the mask period; the single-wave kernel
+// otherwise, with enough slots to fill the chip (two waves per SIMD).
+static int single_slots(long long N, int heads) {
     const int hpb = heads < kWavesPerBlock ? heads : kWavesPerBlock;
     const int groups = (heads + hpb - 1) / hpb;
     long long slots = (256 * 8 / hpb + groups - 1) / groups;  // ~8 waves per CU over 256 CUs
@@ -397,7 +375,17 @@ int backward_slots(long long N, int heads) {
     return (int)slots;
 }
 
-hipError_t launch_backward_bf16(const BwdArgs& a, hipStream_t s) {
+int backward_slots(long long N, int heads, int nW) {
+    const int c = coop_slots(N, heads, nW);
+    return c > 0 ? c : single_slots(N, heads);
+}
+
+int backward_max_slots(long long N, int heads) {
+    const int a = coop_slots(N, heads, 1), b = single_slots(N, heads);  // period 1 gives the largest count
+    return a > b ? a : b;
+}
+
+hipError_t launch_backward_bf16_single(const BwdArgs& a, hipStream_t s) {
     switch ((a.L + 15) / 16) {
         case 1: return launch_bwd_nb<1>(a, s);
         case 2: return launch_bwd_nb<2>(a, s);
@@ -405,6 +393,17 @@ hipError_t launch_backward_bf16(const BwdArgs& a, hipStream_t s) {
         case 4: return launch_bwd_nb<4>(a, s);
         default: return hipErrorNotSupported;
     }
+}
+
+// dbias[h][i][j] = sum over the slots of partial[slot][h][i][j]
+hipError_t launch_backward_bf16(const BwdArgs& a, hipStream_t s) {
+    const bool coop = coop_slots(a.N, a.heads, a.mask ? a.nW : 1) > 0;
+    const hipError_t e = coop ? launch_backward_bf16_coop(a, s) : launch_backward_bf16_single(a, s);
+    if (e != hipSuccess || a.dbias == nullptr) return e;
+    const size_t count = (size_t)a.heads * a.L * a.L;
+    hipLaunchKernelGGL(dbias_reduce_kernel, dim3((unsigned)((count + 63) / 64)), dim3(64 * kReduceRows), 0, s,
+                       a.partial, a.dbias, a.slots, count);
+    return hipGetLastError();
 }
 
 hipError_t launch_backward_f32(const BwdArgs&, hipStream_t) { return hipErrorNotSupported; }

@@ -151,6 +151,36 @@ __device__ __forceinline__ uint2 pack_exact_u2(const f32x4& x) {
 }
 __device__ __forceinline__ bf16x4 pack_exact(const f32x4& x) { return as_bf16x4(pack_exact_u2(x)); }
 
+// x = hi + lo with hi the upper 16 bits of x (a bf16 by truncation) and lo the
+// remainder rounded to bf16: together 16 significant bits.
+__device__ __forceinline__ void split_hi_lo(const f32x4& x, bf16x4& hi, bf16x4& lo) {
+    uint32_t u[4];
+    float rem[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        const float xc = x[c];
+        u[c] = __builtin_bit_cast(uint32_t, xc);
+        rem[c] = xc - __builtin_bit_cast(float, u[c] & 0xffff0000u);
+    }
+    uint2 h, l;
+    h.x = upper_halves(u[0], u[1]);
+    h.y = upper_halves(u[2], u[3]);
+    l.x = pack_bf16(rem[0], rem[1]);
+    l.y = pack_bf16(rem[2], rem[3]);
+    hi = as_bf16x4(h);
+    lo = as_bf16x4(l);
+}
+
+// B operand of the K=16 matrix op that is the 16x16 identity: slot e of lane (g, n) is 1.0 iff
+// 4g + e == n.  X (as A operand) times it returns X in the accumulator layout, i.e. with the
+// other index on the lane: lane (g', n') <- X[row 4g' + r][column n'].
+__device__ __forceinline__ bf16x4 identity_operand(int g, int n) {
+    uint2 u;
+    u.x = (4 * g + 0 == n ? 0x3f80u : 0u) | (4 * g + 1 == n ? 0x3f800000u : 0u);
+    u.y = (4 * g + 2 == n ? 0x3f80u : 0u) | (4 * g + 3 == n ? 0x3f800000u : 0u);
+    return as_bf16x4(u);
+}
+
 // B operand of the K=32 matrix op that picks every second channel: slot e of lane (g, n)
 // stands for channel 8g + e; the product rows x selector puts channel 2n + parity of each
 // row into column n, i.e. returns lane (g', n') <- X[row 4g' + r][channel 2n' + parity].

@@ -56,7 +56,11 @@ int staged_heads_per_block(int L, int heads);
 hipError_t launch_forward_bf16_staged(const FwdArgs& a, hipStream_t s);
 hipError_t launch_backward_bf16(const BwdArgs& a, hipStream_t s);
 hipError_t launch_backward_f32(const BwdArgs& a, hipStream_t s);
-int backward_slots(long long N, int heads);
+int backward_slots(long long N, int heads, int nW);
+int backward_max_slots(long long N, int heads);
+int coop_slots(long long N, int heads, int nW);
+hipError_t launch_backward_bf16_coop(const BwdArgs& a, hipStream_t s);
+hipError_t launch_backward_bf16_single(const BwdArgs& a, hipStream_t s);
 hipError_t launch_zero_f32(float* dst, size_t count, hipStream_t s);
 hipError_t launch_bias_gather(const float* table, float* bias, int heads, int k, hipStream_t s);
 hipError_t launch_bias_scatter(const float* dbias, float* dtable, int heads, int k, hipStream_t s);
