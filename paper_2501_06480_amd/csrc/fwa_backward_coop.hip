@@ -8,11 +8,12 @@
 //       S^T = K Q^T, softmax, dP^T = V dO^T, delta, dS          (K, V rows read from LDS)
 //       dQ rows of its block (contraction over keys: dS is already the B operand)
 //       dBias rows of its block, accumulated in registers across windows
-//       P and dS blocks moved to "key on the lane" by an identity product on the matrix core,
-//       as hi + lo bf16, and left in an LDS exchange area
+//       P and dS rows of its block, as hi + lo bf16, written row-major into LDS tiles
 //   phase B, wave jb (16 keys):
-//       dV, dK rows of its block = contraction over all queries of the exchanged blocks with
-//       dO^T resp. Q^T (row operands times a channel selector on the matrix core)
+//       dV, dK rows of its block = contraction over all queries of P resp. dS with dO^T resp.
+//       Q^T.  The operands with the queries on the k-slots come out of LDS through the
+//       transposing read ds_read_b64_tr_b16: the P/dS tiles with the key on the lane, the
+//       dO/Q slabs (and the K slab for dQ in phase A) with the channel on the lane.
 //
 // The workgroup loads the Q, K, V, dO slabs of its heads (whole 128-byte lines per row) with
 // coalesced 16-byte loads into LDS once per window and requests the next window's slabs before
@@ -23,6 +24,26 @@
 
 namespace fwa {
 namespace {
+
+typedef short v4i16 __attribute__((ext_vector_type(4)));
+
+// Transposing LDS read: lane r of a row of 16 lanes passes the address of 4 consecutive bf16,
+// lane t receives element (t & 3) of the rows passed by lanes (t >> 2) + 4 e, e = 0..3.  With
+// lane r pointing at X[i0 + (r >> 2)][j0 + 4 (r & 3)] lane t receives X[i0 + e][j0 + t].
+__device__ __forceinline__ uint2 lds_read_tr(const uint16_t* p) {
+    typedef __attribute__((address_space(3))) v4i16 lds_v4i16;
+    const v4i16 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4i16*)(p));
+    return __builtin_bit_cast(uint2, v);
+}
+// Operand whose 8 k-slots are rows i0 + 4g + e (e < 4) and i0 + 16 + 4g + (e - 4) of a row-major
+// bf16 tile and whose lane index is column j0 + n; `p` = &X[i0 + 4g + (n >> 2)][j0 + 4 (n & 3)],
+// `rows16` = elements between row i and row i + 16.  `two` = the second 16 rows exist.
+__device__ __forceinline__ bf16x8 operand_tr(const uint16_t* p, uint32_t rows16, bool two) {
+    const uint2 a = lds_read_tr(p);
+    uint2 b = {0u, 0u};
+    if (two) b = lds_read_tr(p + rows16);
+    return as_bf16x8(u32x4{a.x, a.y, b.x, b.y});
+}
 
 constexpr int kCoopWavesPerTile = 4;
 constexpr int kCoopMaxHeads = 3;  // heads per workgroup: 12 waves, 3 per SIMD, <= 170 VGPRs each
@@ -54,13 +75,18 @@ __global__ void __launch_bounds__(64 * kCoopWavesPerTile * kCoopMaxHeads) bwd_bf
     const float sl2 = p.scale * kLog2e;
     const bool active = role < NB;
 
-    // LDS: slabs [K][V][Q][dO], each [ROWS][stride] uint4; then per head the exchange area
-    // [jb][qb][P_hi, P_lo, dS_hi, dS_lo][lane] of 8 bytes.
+    // LDS: slabs [K][V][Q][dO], each [ROWS][stride] uint4; then per head four bf16 tiles.
     uint4* const lk = lds;
     uint4* const lv = lds + ROWS * stride;
     uint4* const lq = lds + 2 * ROWS * stride;
     uint4* const lg = lds + 3 * ROWS * stride;
-    uint2* const ex = reinterpret_cast<uint2*>(lds + 4 * ROWS * stride) + (size_t)hl * (NB * NB * 4 * 64) + lane;
+    // P_hi, P_lo, dS_hi, dS_lo tiles of this head: [ROWS][XS] bf16, row-major, XS = ROWS + 4
+    constexpr uint32_t XS = ROWS + 4, XT = ROWS * XS;
+    uint16_t* const ex = reinterpret_cast<uint16_t*>(lds + 4 * ROWS * stride) + (size_t)hl * (4 * XT);
+    const uint32_t srow = stride * 8u;  // slab row stride in bf16 elements
+    // transposing-read base of this lane inside a slab (channel on the lane) and inside a tile
+    const uint32_t trs = (4u * g + (n >> 2)) * srow + 32u * hl + 4u * (n & 3);
+    const uint32_t trx = (4u * g + (n >> 2)) * XS + 4u * (n & 3);
     const uint32_t opd = (uint32_t)n * stride + 4u * hl + g;  // operand of row block b: slab[opd + 16 b stride]
 
     // additive score term of this wave's query rows, in registers (see the file comment)
@@ -79,8 +105,6 @@ __global__ void __launch_bounds__(64 * kCoopWavesPerTile * kCoopMaxHeads) bwd_bf
 #pragma unroll
     for (int jb = 0; jb < NB; ++jb) dbacc[jb] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    const bf16x4 ident = identity_operand(g, n);
-    const bf16x8 sel_even = channel_selector(g, n, 0), sel_odd = channel_selector(g, n, 1);
     const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
 
     // slab movement: thread -> (row, 16-byte column); one pass covers 64 rows
@@ -101,7 +125,7 @@ __global__ void __launch_bounds__(64 * kCoopWavesPerTile * kCoopMaxHeads) bwd_bf
     if (bw < (uint32_t)p.N) request(bw);
 
     const uint32_t tile_bytes = (uint32_t)(L - 1) * row_bytes + 2u * kHeadDim;
-    const uint32_t off_row = (uint32_t)n * row_bytes + 16u * g;
+    const uint32_t off_half = (uint32_t)n * row_bytes + 8u * g;  // channels 4g..4g+3 of row n (+32 B: 16+4g..)
 
     for (uint32_t w = bw; w < (uint32_t)p.N; w += gm.G) {
         if (rip < (uint32_t)ROWS) {
@@ -170,111 +194,89 @@ __global__ void __launch_bounds__(64 * kCoopWavesPerTile * kCoopMaxHeads) bwd_bf
                 for (int r = 0; r < 4; ++r) dp[jb][r] = s[jb][r] * (dp[jb][r] - delta);  // dS
                 if (DB) dbacc[jb] += dp[jb];
             }
-            // hi + lo bf16 parts; the blocks with the key on the lane go to the exchange area
+            // hi + lo bf16 parts of P and dS: rows of this block into the LDS tiles for phase B
             bf16x4 ds_hi[NB], ds_lo[NB];
 #pragma unroll
             for (int jb = 0; jb < NB; ++jb) {
                 bf16x4 p_hi, p_lo;
                 split_hi_lo(s[jb], p_hi, p_lo);
                 split_hi_lo(dp[jb], ds_hi[jb], ds_lo[jb]);
-                uint2* slot = ex + ((jb * NB + qb) * 4) * 64;
-                slot[0 * 64] = pack_exact_u2(mfma16(p_hi, ident, zero));
-                slot[1 * 64] = pack_exact_u2(mfma16(p_lo, ident, zero));
-                slot[2 * 64] = pack_exact_u2(mfma16(ds_hi[jb], ident, zero));
-                slot[3 * 64] = pack_exact_u2(mfma16(ds_lo[jb], ident, zero));
+                uint16_t* cell = ex + (16 * qb + n) * XS + 16 * jb + 4 * g;
+                *reinterpret_cast<uint2*>(cell + 0 * XT) = __builtin_bit_cast(uint2, p_hi);
+                *reinterpret_cast<uint2*>(cell + 1 * XT) = __builtin_bit_cast(uint2, p_lo);
+                *reinterpret_cast<uint2*>(cell + 2 * XT) = __builtin_bit_cast(uint2, ds_hi[jb]);
+                *reinterpret_cast<uint2*>(cell + 3 * XT) = __builtin_bit_cast(uint2, ds_lo[jb]);
             }
-            // dQ^T = K^T dS^T over pairs of key blocks
-            f32x4 qe = zero, qo = zero;
+            // dQ^T = K^T dS^T over pairs of key blocks; K^T (channels 0..15 / 16..31 on the lane)
+            // straight from the K slab
+            f32x4 q0 = zero, q1 = zero;  // dQ[16 qb + n][4g + r], dQ[16 qb + n][16 + 4g + r]
+            const uint16_t* lk16 = reinterpret_cast<const uint16_t*>(lk) + trs;
 #pragma unroll
             for (int kp = 0; kp < NB2; ++kp) {
                 const bool two = 2 * kp + 1 < NB;
                 const int j1 = two ? 2 * kp + 1 : 0;
-                const bf16x8 k0 = __builtin_bit_cast(bf16x8, lk[opd + 16 * (2 * kp) * stride]);
-                const bf16x8 k1 = __builtin_bit_cast(bf16x8, lk[opd + 16 * j1 * stride]);
-                const uint2 e0 = pack_exact_u2(mfma_bf16(k0, sel_even, zero)), o0 = pack_exact_u2(mfma_bf16(k0, sel_odd, zero));
-                uint2 e1 = {0u, 0u}, o1 = {0u, 0u};
-                if (two) {
-                    e1 = pack_exact_u2(mfma_bf16(k1, sel_even, zero));
-                    o1 = pack_exact_u2(mfma_bf16(k1, sel_odd, zero));
-                }
+                const bf16x8 k0 = operand_tr(lk16 + (32 * kp) * srow, 16 * srow, two);
+                const bf16x8 k1 = operand_tr(lk16 + (32 * kp) * srow + 16, 16 * srow, two);
                 const uint2 h0 = __builtin_bit_cast(uint2, ds_hi[2 * kp]), l0 = __builtin_bit_cast(uint2, ds_lo[2 * kp]);
                 uint2 h1 = {0u, 0u}, l1 = {0u, 0u};
                 if (two) {
                     h1 = __builtin_bit_cast(uint2, ds_hi[j1]);
                     l1 = __builtin_bit_cast(uint2, ds_lo[j1]);
                 }
-                const bf16x8 ke = as_bf16x8(u32x4{e0.x, e0.y, e1.x, e1.y}), ko = as_bf16x8(u32x4{o0.x, o0.y, o1.x, o1.y});
                 const bf16x8 dh = as_bf16x8(u32x4{h0.x, h0.y, h1.x, h1.y}), dl = as_bf16x8(u32x4{l0.x, l0.y, l1.x, l1.y});
-                qe = mfma_bf16(ke, dh, qe);
-                qo = mfma_bf16(ko, dh, qo);
-                qe = mfma_bf16(ke, dl, qe);
-                qo = mfma_bf16(ko, dl, qo);
+                q0 = mfma_bf16(k0, dh, q0);
+                q1 = mfma_bf16(k1, dh, q1);
+                q0 = mfma_bf16(k0, dl, q0);
+                q1 = mfma_bf16(k1, dl, q1);
             }
-            u32x4 out;
-            out.x = pack_bf16(qe[0] * p.scale, qo[0] * p.scale);
-            out.y = pack_bf16(qe[1] * p.scale, qo[1] * p.scale);
-            out.z = pack_bf16(qe[2] * p.scale, qo[2] * p.scale);
-            out.w = pack_bf16(qe[3] * p.scale, qo[3] * p.scale);
-            __builtin_amdgcn_raw_buffer_store_b128(out, make_rsrc((char*)p.dq + tile, tile_bytes),
-                                                   off_row + 16 * qb * row_bytes, 0, 0);
+            typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+            const u32x2 lo2 = {pack_bf16(q0[0] * p.scale, q0[1] * p.scale), pack_bf16(q0[2] * p.scale, q0[3] * p.scale)};
+            const u32x2 hi2 = {pack_bf16(q1[0] * p.scale, q1[1] * p.scale), pack_bf16(q1[2] * p.scale, q1[3] * p.scale)};
+            const __amdgpu_buffer_rsrc_t rdq = make_rsrc((char*)p.dq + tile, tile_bytes);
+            __builtin_amdgcn_raw_buffer_store_b64(lo2, rdq, off_half + 16 * qb * row_bytes, 0, 0);
+            __builtin_amdgcn_raw_buffer_store_b64(hi2, rdq, off_half + 32 + 16 * qb * row_bytes, 0, 0);
         }
         __syncthreads();
         // ---------------- phase B: key block `role` ----------------
         if (active) {
             const int jb = role;
-            f32x4 ve = zero, vo = zero, ke = zero, ko = zero;
+            f32x4 v0 = zero, v1 = zero, k0 = zero, k1 = zero;  // dV, dK [16 jb + n][4g + r] and [..][16 + 4g + r]
+            const uint16_t* lg16 = reinterpret_cast<const uint16_t*>(lg) + trs;
+            const uint16_t* lq16 = reinterpret_cast<const uint16_t*>(lq) + trs;
+            const uint16_t* xt = ex + trx + 16 * jb;
 #pragma unroll
             for (int qp = 0; qp < NB2; ++qp) {
                 const bool two = 2 * qp + 1 < NB;
-                const int q1 = two ? 2 * qp + 1 : 0;
-                // dO^T and Q^T of the 32 queries: row operands times the channel selectors
-                const bf16x8 g0 = __builtin_bit_cast(bf16x8, lg[opd + 16 * (2 * qp) * stride]);
-                const bf16x8 g1 = __builtin_bit_cast(bf16x8, lg[opd + 16 * q1 * stride]);
-                const bf16x8 x0 = __builtin_bit_cast(bf16x8, lq[opd + 16 * (2 * qp) * stride]);
-                const bf16x8 x1 = __builtin_bit_cast(bf16x8, lq[opd + 16 * q1 * stride]);
-                const uint2 ge0 = pack_exact_u2(mfma_bf16(g0, sel_even, zero)), go0 = pack_exact_u2(mfma_bf16(g0, sel_odd, zero));
-                const uint2 xe0 = pack_exact_u2(mfma_bf16(x0, sel_even, zero)), xo0 = pack_exact_u2(mfma_bf16(x0, sel_odd, zero));
-                uint2 ge1 = {0u, 0u}, go1 = {0u, 0u}, xe1 = {0u, 0u}, xo1 = {0u, 0u};
-                const uint2* s0 = ex + ((jb * NB + 2 * qp) * 4) * 64;
-                const uint2 ph0 = s0[0 * 64], pl0 = s0[1 * 64], sh0 = s0[2 * 64], sl0 = s0[3 * 64];
-                uint2 ph1 = {0u, 0u}, pl1 = {0u, 0u}, sh1 = {0u, 0u}, sl1 = {0u, 0u};
-                if (two) {
-                    ge1 = pack_exact_u2(mfma_bf16(g1, sel_even, zero));
-                    go1 = pack_exact_u2(mfma_bf16(g1, sel_odd, zero));
-                    xe1 = pack_exact_u2(mfma_bf16(x1, sel_even, zero));
-                    xo1 = pack_exact_u2(mfma_bf16(x1, sel_odd, zero));
-                    const uint2* s1 = ex + ((jb * NB + q1) * 4) * 64;
-                    ph1 = s1[0 * 64];
-                    pl1 = s1[1 * 64];
-                    sh1 = s1[2 * 64];
-                    sl1 = s1[3 * 64];
-                }
-                const bf16x8 ge = as_bf16x8(u32x4{ge0.x, ge0.y, ge1.x, ge1.y}), go = as_bf16x8(u32x4{go0.x, go0.y, go1.x, go1.y});
-                const bf16x8 xe = as_bf16x8(u32x4{xe0.x, xe0.y, xe1.x, xe1.y}), xo = as_bf16x8(u32x4{xo0.x, xo0.y, xo1.x, xo1.y});
-                const bf16x8 ph = as_bf16x8(u32x4{ph0.x, ph0.y, ph1.x, ph1.y}), pl = as_bf16x8(u32x4{pl0.x, pl0.y, pl1.x, pl1.y});
-                const bf16x8 sh = as_bf16x8(u32x4{sh0.x, sh0.y, sh1.x, sh1.y}), sl = as_bf16x8(u32x4{sl0.x, sl0.y, sl1.x, sl1.y});
-                ve = mfma_bf16(ge, ph, ve);  // dV[16 jb + n][2 (4g + r)]
-                vo = mfma_bf16(go, ph, vo);
-                ke = mfma_bf16(xe, sh, ke);  // dK[16 jb + n][2 (4g + r)]
-                ko = mfma_bf16(xo, sh, ko);
-                ve = mfma_bf16(ge, pl, ve);
-                vo = mfma_bf16(go, pl, vo);
-                ke = mfma_bf16(xe, sl, ke);
-                ko = mfma_bf16(xo, sl, ko);
+                // dO^T and Q^T of the 32 queries (channel on the lane), P and dS of the same
+                // queries (key on the lane)
+                const bf16x8 g0 = operand_tr(lg16 + (32 * qp) * srow, 16 * srow, two);
+                const bf16x8 g1 = operand_tr(lg16 + (32 * qp) * srow + 16, 16 * srow, two);
+                const bf16x8 x0 = operand_tr(lq16 + (32 * qp) * srow, 16 * srow, two);
+                const bf16x8 x1 = operand_tr(lq16 + (32 * qp) * srow + 16, 16 * srow, two);
+                const bf16x8 ph = operand_tr(xt + 0 * XT + (32 * qp) * XS, 16 * XS, two);
+                const bf16x8 pl = operand_tr(xt + 1 * XT + (32 * qp) * XS, 16 * XS, two);
+                const bf16x8 sh = operand_tr(xt + 2 * XT + (32 * qp) * XS, 16 * XS, two);
+                const bf16x8 sl = operand_tr(xt + 3 * XT + (32 * qp) * XS, 16 * XS, two);
+                v0 = mfma_bf16(g0, ph, v0);
+                v1 = mfma_bf16(g1, ph, v1);
+                k0 = mfma_bf16(x0, sh, k0);
+                k1 = mfma_bf16(x1, sh, k1);
+                v0 = mfma_bf16(g0, pl, v0);
+                v1 = mfma_bf16(g1, pl, v1);
+                k0 = mfma_bf16(x0, sl, k0);
+                k1 = mfma_bf16(x1, sl, k1);
             }
-            u32x4 ov, ok;
-            ov.x = pack_bf16(ve[0], vo[0]);
-            ov.y = pack_bf16(ve[1], vo[1]);
-            ov.z = pack_bf16(ve[2], vo[2]);
-            ov.w = pack_bf16(ve[3], vo[3]);
-            ok.x = pack_bf16(ke[0] * p.scale, ko[0] * p.scale);
-            ok.y = pack_bf16(ke[1] * p.scale, ko[1] * p.scale);
-            ok.z = pack_bf16(ke[2] * p.scale, ko[2] * p.scale);
-            ok.w = pack_bf16(ke[3] * p.scale, ko[3] * p.scale);
-            __builtin_amdgcn_raw_buffer_store_b128(ov, make_rsrc((char*)p.dv + tile, tile_bytes),
-                                                   off_row + 16 * jb * row_bytes, 0, 0);
-            __builtin_amdgcn_raw_buffer_store_b128(ok, make_rsrc((char*)p.dk + tile, tile_bytes),
-                                                   off_row + 16 * jb * row_bytes, 0, 0);
+            typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+            const u32x2 va = {pack_bf16(v0[0], v0[1]), pack_bf16(v0[2], v0[3])};
+            const u32x2 vb = {pack_bf16(v1[0], v1[1]), pack_bf16(v1[2], v1[3])};
+            const u32x2 ka = {pack_bf16(k0[0] * p.scale, k0[1] * p.scale), pack_bf16(k0[2] * p.scale, k0[3] * p.scale)};
+            const u32x2 kb = {pack_bf16(k1[0] * p.scale, k1[1] * p.scale), pack_bf16(k1[2] * p.scale, k1[3] * p.scale)};
+            const __amdgpu_buffer_rsrc_t rdv = make_rsrc((char*)p.dv + tile, tile_bytes);
+            const __amdgpu_buffer_rsrc_t rdk = make_rsrc((char*)p.dk + tile, tile_bytes);
+            __builtin_amdgcn_raw_buffer_store_b64(va, rdv, off_half + 16 * jb * row_bytes, 0, 0);
+            __builtin_amdgcn_raw_buffer_store_b64(vb, rdv, off_half + 32 + 16 * jb * row_bytes, 0, 0);
+            __builtin_amdgcn_raw_buffer_store_b64(ka, rdk, off_half + 16 * jb * row_bytes, 0, 0);
+            __builtin_amdgcn_raw_buffer_store_b64(kb, rdk, off_half + 32 + 16 * jb * row_bytes, 0, 0);
         }
         __syncthreads();  // slabs and exchange area are rewritten by the next window
     }
@@ -312,7 +314,7 @@ hipError_t launch_coop_nb(const BwdArgs& a, int hpb, hipStream_t st) {
     gm.heads_per_block = (uint32_t)hpb;
     gm.G = (uint32_t)a.slots;
     const unsigned grid = gm.G * groups, block = 64u * kCoopWavesPerTile * (unsigned)hpb;
-    const size_t lds = (size_t)4 * 16 * NB * (4 * hpb + 1) * 16 + (size_t)hpb * NB * NB * 4 * 64 * 8;
+    const size_t lds = (size_t)4 * 16 * NB * (4 * hpb + 1) * 16 + (size_t)hpb * 4 * (16 * NB) * (16 * NB + 4) * 2;
     const bool bm = a.bias || a.mask, db = a.dbias != nullptr;
     if (bm)
         return db ? launch_coop_one<NB, true, true>(a, gm, grid, block, lds, st)

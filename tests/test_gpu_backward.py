@@ -80,6 +80,29 @@ def test_without_dbias_and_many_windows_per_wave(oracle):
     check_backward(oracle, w, None, None, "N=1500 heads=2 dbias", want_dbias=True)
 
 
+@pytest.mark.parametrize("heads", [1, 2, 3, 4, 5, 6, 7, 9, 12])
+def test_head_counts_reach_both_backward_kernels(oracle, heads):
+    """Head counts 1-3, even counts and multiples of 3 take the cooperative kernel; 5 and 7 have
+    no workgroup shape made of whole memory lines and take the single-wave kernel."""
+    L, N = 49, 6
+    w = synth.Workload(f"bwd_heads{heads}", N, L, 32 * heads, heads, "bf16", 7000 + heads, 0, backward=True)
+    bias = synth.normal((heads, L, L), 23 + heads, 0.5)
+    mask = np.where(synth.rng(29 + heads).random((3, L, L)) < 0.2, -100.0, 0.0).astype(np.float32)
+    mask[:, np.arange(L), np.arange(L)] = 0.0
+    check_backward(oracle, w, bias, mask, f"heads={heads}")
+
+
+def test_mask_period_too_long_for_the_cooperative_kernel(oracle):
+    """nW larger than the number of workgroups the cooperative kernel walks in parallel:
+    the single-wave kernel, which reads the mask tile per window, takes over."""
+    L, heads, nW = 33, 3, 300
+    w = synth.Workload("bwd_long_period", 2 * nW, L, 32 * heads, heads, "bf16", 7100, 0, backward=True)
+    bias = synth.normal((heads, L, L), 31, 0.5)
+    mask = np.where(synth.rng(37).random((nW, L, L)) < 0.2, -100.0, 0.0).astype(np.float32)
+    mask[:, np.arange(L), np.arange(L)] = 0.0
+    check_backward(oracle, w, bias, mask, "nW=300")
+
+
 def test_backward_is_bit_reproducible():
     import torch
     import paper_2501_06480_amd as fwa
