@@ -69,12 +69,68 @@ def cpu_baseline(workload):
                       f"{dt:.2f} s wall = {dt * cores:.0f} core-seconds"}
 
 
+def time_other_workloads(torch, fwa, synth, dev):
+    """Short HIP-event timings of the other configurations (context next to the headline line):
+    Swin-T stage 1 with bias + shift mask, the large windows, and the backward.  Same buffer
+    rotation rule as the headline (cycle larger than twice the last-level cache)."""
+    out = []
+
+    def run(name, w, backward, iters):
+        shape = (w.N, w.L, w.C)
+        per_set = (7 if backward else 4) * w.N * w.L * w.C * 2
+        nsets = max(2, -(-2 * LLC_BYTES // per_set) + 1)
+        g = torch.Generator(device=dev).manual_seed(w.seed)
+        sets = [[torch.randn(shape, device=dev, generator=g).to(torch.bfloat16) for _ in range(4 if backward else 3)]
+                for _ in range(nsets)]
+        outs = [torch.empty(shape, device=dev, dtype=torch.bfloat16) for _ in range(nsets)]
+        bias = mask = ws = None
+        if w.use_bias:
+            bias = fwa.fwa_bias_gather(torch.from_numpy(synth.bias_table(w.heads, w.k, w.seed)).to(dev), w.k)
+        if w.shift:
+            mask = torch.from_numpy(synth.shift_mask(w.map_hw, w.map_hw, w.k, w.shift)).to(dev)
+        if backward:
+            need = fwa.fwa_backward_workspace_bytes(w.N, w.L, w.C, w.heads, 1, True)
+            ws = torch.empty(max(need, 16), dtype=torch.uint8, device=dev)
+
+        def step(i):
+            t = sets[i % nsets]
+            if backward:
+                fwa.fwa_backward(t[0], t[1], t[2], t[3], w.heads, w.scale, bias, mask, want_dbias=True, workspace=ws)
+            else:
+                fwa.fwa_forward(t[0], t[1], t[2], w.heads, w.scale, bias, mask, out=outs[i % nsets])
+
+        for i in range(10):
+            step(i)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for i in range(iters):
+            step(i)
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) / iters * 1e3
+        wh = w.N * w.heads
+        algo = (7 if backward else 4) * w.L * 32 * 2 * wh
+        out.append({"workload": name, "us_per_call": round(us, 2), "window_heads_per_s": wh / us * 1e6,
+                    "algorithmic_GBps": algo / us / 1e3, "frac_of_hbm_peak": algo / us / 1e3 / HBM_PEAK_GBPS})
+
+    run("swin_t_stage1_fwd_bias_shiftmask (N=8192, L=49, 3 heads)", synth.swin_t_stage(1, shifted=True), False, 200)
+    l144, l256 = synth.config4()
+    run("window12_fwd_bias (N=1024, L=144, 4 heads)", l144, False, 100)
+    run("window16_fwd_bias (N=1024, L=256, 4 heads)", l256, False, 50)
+    s1, s3 = synth.config5()
+    run("swin_t_stage1_bwd_bias_shiftmask_dbias (N=8192, L=49, 3 heads)", s1, True, 100)
+    run("swin_t_stage3_bwd_bias_shiftmask_dbias (N=512, L=49, 12 heads)", s3, True, 100)
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=2000)
     ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (profiling runs)")
+    ap.add_argument("--no-other-workloads", action="store_true", help="skip the short timings of the other configs")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch 5 plain elementwise kernels that read and write one tensor of known size, "
                          "so that a counter run can scale FETCH_SIZE / WRITE_SIZE against known traffic")
@@ -153,6 +209,10 @@ def main():
                      "kernel": "fwd_bf16_staged_kernel<4,false>", "kernel_ms": kernel_ms,
                      "algorithmic_bytes_per_launch": algo_bytes},
     }
+    if not args.no_other_workloads:
+        del sets
+        torch.cuda.empty_cache()
+        line["other_workloads"] = time_other_workloads(torch, fwa, synth, dev)
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(w)
     print(json.dumps(line))
