@@ -74,7 +74,8 @@ size_t fwa_backward_workspace_bytes(int64_t N, int L, int C, int heads, int dtyp
     if (check_shape(N, L, C, heads, dtype) != FWA_OK || check_backward_support(L, dtype) != FWA_OK) return 0;
     if (!want_dbias || N == 0) return 0;
     // the slot count depends on the mask period; this is its upper bound over all periods
-    return (size_t)fwa::backward_max_slots(N, heads) * heads * L * L * sizeof(float);
+    const size_t nb = (size_t)(L + 15) / 16;  // partial sums are kept per 16 x 16 block, padded
+    return (size_t)fwa::backward_max_slots(N, heads) * heads * nb * nb * 256 * sizeof(float);
 }
 
 int fwa_backward(const void* q, const void* k, const void* v, const void* d_o, void* dq, void* dk, void* dv,

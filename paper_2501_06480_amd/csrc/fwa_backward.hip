@@ -284,40 +284,46 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, 2) bwd_bf16_kernel(BwdArg
     }
 
     if (DB) {
-        float* dst = p.partial + ((size_t)slot * p.heads + h) * L * L;
+        // partial sums in register order: [slot][head][qb][jb][lane] float4 -- contiguous 16-byte stores
+        f32x4* dst = reinterpret_cast<f32x4*>(p.partial) + ((size_t)slot * p.heads + h) * (NB * NB * 64) + lane;
 #pragma unroll
         for (int qb = 0; qb < NB; ++qb)
 #pragma unroll
-            for (int jb = 0; jb < NB; ++jb) {
-                const f32x4 acc = dbacc[(qb * NB + jb) * 64];
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const int i = 16 * qb + n, j = 16 * jb + 4 * g + r;
-                    if (i < L && j < L) dst[(size_t)i * L + j] = acc[r];
-                }
-            }
+            for (int jb = 0; jb < NB; ++jb) dst[(qb * NB + jb) * 64] = dbacc[(qb * NB + jb) * 64];
     }
 }
 
-// dbias[e] = sum over slots of partial[slot][e].  A workgroup of 64 x 16 threads owns 64
-// consecutive elements; thread row y adds slots y, y+16, ... in index order, then the 16 row
-// sums are added in row order: a fixed summation tree, hence bit-reproducible.
+// dbias[h][i][j] = sum over slots of the partial sums, which the backward kernels leave in
+// register order: per slot and head, block (qb, jb) holds 64 float4, the one of lane (g, n)
+// carrying elements (i, j) = (16 qb + n, 16 jb + 4 g + r), r = 0..3.  A workgroup of 16 x 16
+// threads owns 16 consecutive float4 of that array; thread row y adds slots y, y+16, ... in
+// index order (contiguous 256-byte reads), then the 16 row sums are added in row order: a
+// fixed summation tree, hence bit-reproducible.
 constexpr int kReduceRows = 16;
-__global__ void __launch_bounds__(64 * kReduceRows)
-dbias_reduce_kernel(const float* __restrict__ partial, float* __restrict__ dbias, int slots, size_t count) {
-    __shared__ float part[kReduceRows][64];
-    const int x = threadIdx.x & 63, y = threadIdx.x >> 6;
-    const size_t e = (size_t)blockIdx.x * 64 + x;
-    float acc = 0.f;
-    if (e < count)
-        for (int s = y; s < slots; s += kReduceRows) acc += partial[(size_t)s * count + e];
+__global__ void __launch_bounds__(16 * kReduceRows)
+dbias_reduce_kernel(const f32x4* __restrict__ partial, float* __restrict__ dbias, int slots, int heads, int L) {
+    __shared__ f32x4 part[kReduceRows][16];
+    const int x = threadIdx.x & 15, y = threadIdx.x >> 4;
+    const int nb = (L + 15) / 16;
+    const size_t padded = (size_t)heads * nb * nb * 64;  // float4 per slot
+    const size_t f = (size_t)blockIdx.x * 16 + x;        // < padded: the grid is padded / 16
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    for (int s = y; s < slots; s += kReduceRows) acc += partial[(size_t)s * padded + f];
     part[y][x] = acc;
     __syncthreads();
-    if (y == 0 && e < count) {
-        float total = 0.f;
+    if (y == 0) {
+        f32x4 total = part[0][x];
 #pragma unroll
-        for (int r = 0; r < kReduceRows; ++r) total += part[r][x];
-        dbias[e] = total;
+        for (int r = 1; r < kReduceRows; ++r) total += part[r][x];
+        const int lane = (int)(f & 63), blk = (int)(f >> 6);
+        const int jb = blk % nb, qb = (blk / nb) % nb, h = blk / (nb * nb);
+        const int i = 16 * qb + (lane & 15), j = 16 * jb + 4 * (lane >> 4);
+        if (i < L) {
+            float* row = dbias + ((size_t)h * L + i) * L;
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+                if (j + r < L) row[j + r] = total[r];
+        }
     }
 }
 
@@ -400,9 +406,9 @@ hipError_t launch_backward_bf16(const BwdArgs& a, hipStream_t s) {
     const bool coop = coop_slots(a.N, a.heads, a.mask ? a.nW : 1) > 0;
     const hipError_t e = coop ? launch_backward_bf16_coop(a, s) : launch_backward_bf16_single(a, s);
     if (e != hipSuccess || a.dbias == nullptr) return e;
-    const size_t count = (size_t)a.heads * a.L * a.L;
-    hipLaunchKernelGGL(dbias_reduce_kernel, dim3((unsigned)((count + 63) / 64)), dim3(64 * kReduceRows), 0, s,
-                       a.partial, a.dbias, a.slots, count);
+    const int nb = (a.L + 15) / 16;
+    hipLaunchKernelGGL(dbias_reduce_kernel, dim3((unsigned)(a.heads * nb * nb * 4)), dim3(16 * kReduceRows), 0, s,
+                       reinterpret_cast<const f32x4*>(a.partial), a.dbias, a.slots, a.heads, a.L);
     return hipGetLastError();
 }
 

@@ -282,14 +282,10 @@ __global__ void __launch_bounds__(64 * kCoopWavesPerTile * kCoopMaxHeads) bwd_bf
     }
 
     if (DB && active) {
-        float* dst = p.partial + ((size_t)bw * p.heads + h) * L * L;
+        // partial sums in register order: [slot][head][qb][jb][lane] float4 -- contiguous 16-byte stores
+        f32x4* dst = reinterpret_cast<f32x4*>(p.partial) + ((size_t)bw * p.heads + h) * (NB * NB * 64) + lane;
 #pragma unroll
-        for (int jb = 0; jb < NB; ++jb)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int i = 16 * role + n, j = 16 * jb + 4 * g + r;
-                if (i < L && j < L) dst[(size_t)i * L + j] = dbacc[jb][r];
-            }
+        for (int jb = 0; jb < NB; ++jb) dst[(role * NB + jb) * 64] = dbacc[jb];
     }
 }
 

@@ -88,7 +88,7 @@ def test_backward_rejects_bad_arguments(lib):
     assert bwd(lib, dk=P + 0x4000) == b.FWA_ERR_ALIAS              # dk == dq
     assert bwd(lib, mask=P + 0x9000, nW=8) == b.FWA_ERR_SHAPE
     need = lib.fwa_backward_workspace_bytes(4, 49, 96, 3, 1, 1)
-    assert need >= 3 * 49 * 49 * 4
+    assert need >= 3 * 64 * 64 * 4
     assert bwd(lib, dbias=P + 0x7000) == b.FWA_ERR_WORKSPACE
     assert bwd(lib, dbias=P + 0x7000, ws=P + 0x8000, ws_bytes=need - 1) == b.FWA_ERR_WORKSPACE
     assert lib.fwa_backward_workspace_bytes(4, 49, 96, 3, 1, 0) == 0
