@@ -411,6 +411,168 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) fwd_bf16_rowblock_kernel(
     }
 }
 
+// ---------------------------------------------------------------------------
+// Row-blocked forward with bias / mask, persistent.  At these sizes the additive term is
+// 4 L^2 bytes per head against 256 L bytes of Q, K, V, O per tile, and a lane's part of it
+// (one query row, 4 consecutive keys per key block) is 16 bytes in a row of its own, so
+// re-reading it for every window costs more than everything else.  Here a wave keeps one
+// 16-query block of one head for its whole life: (bias[h] + mask[w % nW]) * log2e of those
+// 16 rows sits in registers (NB float4 per lane), and the workgroup (W waves = W consecutive
+// query blocks of the head; the head is split over `parts` workgroups when NB > 12) walks the
+// windows bw, bw + G, ... with G a multiple of nW.  K and V of the head go through a double
+// buffered LDS slab, requested one window ahead; one barrier per window.  Workgroups that
+// share 128-byte lines (the two heads of a pair, the parts of a head) are neighbours in the
+// logical block order, which is mapped so that neighbours run on the same XCD.
+struct RowPersistGeom {
+    uint32_t heads, parts, G;
+    uint32_t xcd_q, xcd_r;
+};
+
+constexpr int rowpersist_waves(int nb) { return nb <= 12 ? nb : (nb + 1) / 2; }
+
+template <int NB>
+__global__ void __launch_bounds__(64 * rowpersist_waves(NB)) fwd_bf16_rowpersist_kernel(FwdArgs p, RowPersistGeom gm) {
+    constexpr int W = rowpersist_waves(NB);
+    constexpr int NB2 = (NB + 1) / 2;
+    constexpr int ROWS = 16 * NB;
+    constexpr int PASSES = (ROWS + 16 * W - 1) / (16 * W);  // the workgroup moves 16 W slab rows per pass
+    constexpr uint32_t STRIDE = 5;                           // LDS row: 64 bytes of data + 16 of padding
+    extern __shared__ __attribute__((aligned(16))) uint4 lds[];  // [2 buffers][K, V][ROWS][STRIDE]
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int n = lane & 15, g = lane >> 4;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const uint32_t lb = xcd_logical_block(blockIdx.x, gm.xcd_q, gm.xcd_r);
+    const uint32_t part = lb % gm.parts, bh = lb / gm.parts;
+    const uint32_t h = bh % gm.heads, bw = bh / gm.heads;
+    const int qb = (int)(part * W + wave);
+    const bool active = qb < NB;
+    const int L = p.L;
+    const uint32_t row_bytes = (uint32_t)p.C * 2u;
+    const float sl2 = p.scale * kLog2e;
+
+    f32x4 add[NB];
+    {
+        const uint32_t ll = (uint32_t)L * L * 4u;
+        const __amdgpu_buffer_rsrc_t rb = p.bias ? make_rsrc(p.bias + (size_t)h * L * L, ll) : make_rsrc(nullptr, 0);
+        const __amdgpu_buffer_rsrc_t rm =
+            p.mask ? make_rsrc(p.mask + (size_t)(bw % (uint32_t)p.nW) * L * L, ll) : make_rsrc(nullptr, 0);
+        // rows beyond L (and the whole block of an idle wave) fall outside the descriptors: zeros
+        const uint32_t off = active ? (((uint32_t)(16 * qb + n)) * L + 4u * g) * 4u : ll;
+#pragma unroll
+        for (int jb = 0; jb < NB; ++jb)
+            add[jb] = (load_f32x4(rb, off + 16 * jb * 4u) + load_f32x4(rm, off + 16 * jb * 4u)) * kLog2e;
+    }
+
+    const uint32_t srow = (uint32_t)tid >> 2, scol = (uint32_t)tid & 3u;  // slab movement: thread -> (row, 16 B column)
+    const uint32_t tile_bytes = (uint32_t)(L - 1) * row_bytes + 2u * kHeadDim;
+    const uint32_t off_row = (uint32_t)(16 * qb + n) * row_bytes + 16u * g;
+    u32x4 pk[PASSES], pv[PASSES], qnext = {0u, 0u, 0u, 0u};
+    auto request = [&](uint32_t w) {
+        const size_t tile = ((size_t)w * L * p.C + (size_t)h * kHeadDim) * 2u;
+        const __amdgpu_buffer_rsrc_t rk = make_rsrc((const char*)p.k + tile, tile_bytes);
+        const __amdgpu_buffer_rsrc_t rv = make_rsrc((const char*)p.v + tile, tile_bytes);
+#pragma unroll
+        for (int t = 0; t < PASSES; ++t) {
+            const uint32_t off = (16 * W * t + srow) * row_bytes + scol * 16u;  // rows beyond L arrive as zeros
+            pk[t] = __builtin_amdgcn_raw_buffer_load_b128(rk, off, 0, 0);
+            pv[t] = __builtin_amdgcn_raw_buffer_load_b128(rv, off, 0, 0);
+        }
+        if (active)
+            qnext = __builtin_amdgcn_raw_buffer_load_b128(make_rsrc((const char*)p.q + tile, tile_bytes), off_row, 0, 0);
+    };
+    if (bw < (uint32_t)p.N) request(bw);
+
+    uint32_t buf = 0;
+    for (uint32_t w = bw; w < (uint32_t)p.N; w += gm.G, buf ^= 1u) {
+        uint4* const lk = lds + buf * (2 * ROWS * STRIDE);
+        uint4* const lv = lk + ROWS * STRIDE;
+#pragma unroll
+        for (int t = 0; t < PASSES; ++t) {
+            const uint32_t row = 16 * W * t + srow;
+            if (row < (uint32_t)ROWS) {
+                lk[row * STRIDE + scol] = __builtin_bit_cast(uint4, pk[t]);
+                lv[row * STRIDE + scol] = __builtin_bit_cast(uint4, pv[t]);
+            }
+        }
+        const bf16x8 qop = as_bf16x8(qnext);
+        if (w + gm.G < (uint32_t)p.N) request(w + gm.G);  // in flight while this window is computed
+        // One barrier per window: the other buffer was last read in the previous iteration, which
+        // every wave has left before any wave passes this barrier and goes on to overwrite it.
+        __syncthreads();
+        if (!active) continue;
+
+        const uint4* const lkh = lk + n * STRIDE + g;  // K[16 jb + n][8g..] at lkh[16 jb * STRIDE]
+        const uint16_t* const lvh =
+            reinterpret_cast<const uint16_t*>(lv) + (4 * g + (n >> 2)) * (STRIDE * 8u) + 4 * (n & 3);
+        f32x4 s[NB];
+#pragma unroll
+        for (int jb = 0; jb < NB; ++jb) {
+            const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+            s[jb] = mfma_bf16(__builtin_bit_cast(bf16x8, lkh[16 * jb * STRIDE]), qop, zero);  // S[16 qb + n][16 jb + 4g + r]
+        }
+        const AddendRegs<NB> addend = {add};
+        const float inv = softmax_block<NB, true>(s, sl2, addend, L, g);
+        f32x4 o0 = {0.f, 0.f, 0.f, 0.f}, o1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int kp = 0; kp < NB2; ++kp) {
+            const bf16x8 pop = prob_operand<NB>(s, kp);
+#pragma unroll
+            for (int c = 0; c < 2; ++c) {
+                const uint2 a = lds_read_tr(lvh + (32 * kp) * (STRIDE * 8u) + 16 * c);
+                uint2 b = {0u, 0u};
+                if (2 * kp + 1 < NB) b = lds_read_tr(lvh + (32 * kp + 16) * (STRIDE * 8u) + 16 * c);
+                const u32x4 v = {a.x, a.y, b.x, b.y};
+                if (c == 0)
+                    o0 = mfma_bf16(as_bf16x8(v), pop, o0);  // o0[r] = O[16 qb + n][4g + r]
+                else
+                    o1 = mfma_bf16(as_bf16x8(v), pop, o1);  // o1[r] = O[16 qb + n][16 + 4g + r]
+            }
+        }
+        typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+        u32x2 lo, hi;
+        lo.x = pack_bf16(o0[0] * inv, o0[1] * inv);
+        lo.y = pack_bf16(o0[2] * inv, o0[3] * inv);
+        hi.x = pack_bf16(o1[0] * inv, o1[1] * inv);
+        hi.y = pack_bf16(o1[2] * inv, o1[3] * inv);
+        const size_t tile = ((size_t)w * L * p.C + (size_t)h * kHeadDim) * 2u;
+        const __amdgpu_buffer_rsrc_t ro = make_rsrc((char*)p.o + tile, tile_bytes);
+        const uint32_t off_o = (uint32_t)(16 * qb + n) * row_bytes + 8u * g;
+        __builtin_amdgcn_raw_buffer_store_b64(lo, ro, off_o, 0, 0);
+        __builtin_amdgcn_raw_buffer_store_b64(hi, ro, off_o + 32, 0, 0);
+    }
+}
+
+// Window positions walked in parallel by the persistent row-blocked kernel (about one
+// workgroup per CU, a multiple of the mask period, at least two windows per workgroup);
+// 0 = use the plain row-blocked kernel.
+template <int NB>
+long long rowpersist_slots(const FwdArgs& a) {
+    const long long parts = NB <= 12 ? 1 : 2;
+    const long long nW = a.mask ? a.nW : 1;
+    long long G = (256 / ((long long)a.heads * parts)) / nW * nW;
+    if (G > a.N / 2) G = (a.N / 2) / nW * nW;
+    return G >= nW && G > 0 ? G : 0;
+}
+
+template <int NB>
+hipError_t launch_rowpersist_nb(const FwdArgs& a, long long G, hipStream_t st) {
+    RowPersistGeom gm;
+    gm.heads = (uint32_t)a.heads;
+    gm.parts = NB <= 12 ? 1u : 2u;
+    gm.G = (uint32_t)G;
+    const unsigned grid = gm.G * gm.heads * gm.parts, block = 64u * (unsigned)rowpersist_waves(NB);
+    gm.xcd_q = grid / 8u;
+    gm.xcd_r = grid % 8u;
+    const size_t lds = (size_t)2 * 2 * 16 * NB * 5 * 16;
+    if (lds > 64 * 1024) {
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&fwd_bf16_rowpersist_kernel<NB>),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL((fwd_bf16_rowpersist_kernel<NB>), dim3(grid), dim3(block), lds, st, a, gm);
+    return hipGetLastError();
+}
+
 template <int NB>
 hipError_t launch_rowblock_nb(const FwdArgs& a, hipStream_t st) {
     RowBlockGeom gm;
@@ -425,6 +587,10 @@ hipError_t launch_rowblock_nb(const FwdArgs& a, hipStream_t st) {
     gm.xcd_r = grid % 8u;
     const size_t lds = (size_t)2 * 16 * NB * (4 * hpb + 1) * 16;
     const bool bm = a.bias || a.mask;
+    if (bm) {  // without an additive term the walk over windows gains nothing (measured slower)
+        const long long G = rowpersist_slots<NB>(a);
+        if (G > 0) return launch_rowpersist_nb<NB>(a, G, st);
+    }
     const void* fn = bm ? reinterpret_cast<const void*>(&fwd_bf16_rowblock_kernel<NB, true>)
                         : reinterpret_cast<const void*>(&fwd_bf16_rowblock_kernel<NB, false>);
     if (lds > 64 * 1024) {

@@ -84,6 +84,28 @@ def test_many_windows_per_workgroup_with_bias_and_mask(oracle, stage, N, which):
     assert err <= TOL["bf16"]
 
 
+@pytest.mark.parametrize("L,k,hw,heads,N", [(144, 12, 48, 4, 176), (256, 16, 64, 4, 80), (196, 14, 56, 3, 48),
+                                            (81, 9, 18, 2, 300)])
+@pytest.mark.parametrize("which", ["bias+mask", "bias", "mask"])
+def test_large_windows_many_windows_per_workgroup(oracle, L, k, hw, heads, N, which):
+    """Large windows with bias / mask: each wave keeps the additive term of its 16 query rows on
+    chip and walks several windows (one or two workgroups per head, uneven walks)."""
+    import torch
+    import paper_2501_06480_amd as fwa
+    w = synth.Workload(f"L{L}_h{heads}", N, L, 32 * heads, heads, "bf16", 7000 + L, k, hw, True, k // 2)
+    assert N % w.nW == 0
+    x = synth.draw(w)
+    bias64 = oracle.bias_gather(x["table"], w.k) if "bias" in which else None
+    mask = x["mask"] if "mask" in which else None
+    q, kk, v = (to_device(x, w, n) for n in ("q", "k", "v"))
+    o = fwa.fwa_forward(q, kk, v, w.heads, w.scale, f32_device(bias64), f32_device(mask))
+    torch.cuda.synchronize()
+    want = oracle.forward(x["q"], x["k"], x["v"], w.heads, w.scale, bias64, mask)
+    err = max_abs(to_f64(o), want)
+    print(f"{w.name} N={N} {which}: err={err:.3e}", flush=True)
+    assert err <= TOL["bf16"]
+
+
 def test_stage4_single_window_map_with_mask(oracle):
     """A 7x7 map is one window; the shift mask then has 4 regions inside it."""
     w = synth.Workload("s4_masked", 8, 49, 768, 24, "bf16", 1234, 7, 7, True, 3)
