@@ -19,10 +19,10 @@ int check_shape(int64_t N, int L, int C, int heads, int dtype) {
     return FWA_OK;
 }
 
-// The backward currently covers bf16 tiles that fit one wave (L <= 64).
-int check_backward_support(int L, int dtype) {
+// The backward covers bf16 data; dBias only for windows whose score tile stays on chip (L <= 64).
+int check_backward_support(int L, int dtype, bool want_dbias) {
     if (dtype != FWA_BF16) return FWA_ERR_UNSUPPORTED;
-    if (L > fwa::kMaxBackwardL) return FWA_ERR_UNSUPPORTED;
+    if (want_dbias && L > fwa::kMaxBackwardL) return FWA_ERR_UNSUPPORTED;
     return FWA_OK;
 }
 
@@ -71,7 +71,8 @@ int fwa_forward(const void* q, const void* k, const void* v, void* o, int64_t N,
 }
 
 size_t fwa_backward_workspace_bytes(int64_t N, int L, int C, int heads, int dtype, int want_dbias) {
-    if (check_shape(N, L, C, heads, dtype) != FWA_OK || check_backward_support(L, dtype) != FWA_OK) return 0;
+    if (check_shape(N, L, C, heads, dtype) != FWA_OK || check_backward_support(L, dtype, want_dbias != 0) != FWA_OK)
+        return 0;
     if (!want_dbias || N == 0) return 0;
     // the slot count depends on the mask period; this is its upper bound over all periods
     const size_t nb = (size_t)(L + 15) / 16;  // partial sums are kept per 16 x 16 block, padded
@@ -83,7 +84,7 @@ int fwa_backward(const void* q, const void* k, const void* v, const void* d_o, v
                  const float* mask, int nW, int dtype, void* workspace, size_t workspace_bytes, void* stream) {
     int rc = check_shape(N, L, C, heads, dtype);
     if (rc != FWA_OK) return rc;
-    rc = check_backward_support(L, dtype);
+    rc = check_backward_support(L, dtype, dbias != nullptr);
     if (rc != FWA_OK) return rc;
     rc = check_mask(N, mask, nW);
     if (rc != FWA_OK) return rc;

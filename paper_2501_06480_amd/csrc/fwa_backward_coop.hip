@@ -25,26 +25,6 @@
 namespace fwa {
 namespace {
 
-typedef short v4i16 __attribute__((ext_vector_type(4)));
-
-// Transposing LDS read: lane r of a row of 16 lanes passes the address of 4 consecutive bf16,
-// lane t receives element (t & 3) of the rows passed by lanes (t >> 2) + 4 e, e = 0..3.  With
-// lane r pointing at X[i0 + (r >> 2)][j0 + 4 (r & 3)] lane t receives X[i0 + e][j0 + t].
-__device__ __forceinline__ uint2 lds_read_tr(const uint16_t* p) {
-    typedef __attribute__((address_space(3))) v4i16 lds_v4i16;
-    const v4i16 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4i16*)(p));
-    return __builtin_bit_cast(uint2, v);
-}
-// Operand whose 8 k-slots are rows i0 + 4g + e (e < 4) and i0 + 16 + 4g + (e - 4) of a row-major
-// bf16 tile and whose lane index is column j0 + n; `p` = &X[i0 + 4g + (n >> 2)][j0 + 4 (n & 3)],
-// `rows16` = elements between row i and row i + 16.  `two` = the second 16 rows exist.
-__device__ __forceinline__ bf16x8 operand_tr(const uint16_t* p, uint32_t rows16, bool two) {
-    const uint2 a = lds_read_tr(p);
-    uint2 b = {0u, 0u};
-    if (two) b = lds_read_tr(p + rows16);
-    return as_bf16x8(u32x4{a.x, a.y, b.x, b.y});
-}
-
 constexpr int kCoopWavesPerTile = 4;
 constexpr int kCoopMaxHeads = 3;  // heads per workgroup: 12 waves, 3 per SIMD, <= 170 VGPRs each
 

@@ -21,22 +21,11 @@
 namespace fwa {
 namespace {
 
-typedef short v4i16 __attribute__((ext_vector_type(4)));
-
 struct StagedGeom {
     FastDiv groups;            // workgroups per window
     FastDiv lanes_per_row;     // 4 * heads_per_block lanes move one slab row
     uint32_t heads_per_block;
 };
-
-// See fwa_backward's description of the same instruction: lane r of a row of 16
-// lanes passes the address of 4 consecutive bf16, lane t receives element (t & 3)
-// of the rows passed by lanes (t >> 2) + 4 e, e = 0..3.
-__device__ __forceinline__ uint2 lds_read_tr(const uint16_t* p) {
-    typedef __attribute__((address_space(3))) v4i16 lds_v4i16;
-    const v4i16 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4i16*)(p));
-    return __builtin_bit_cast(uint2, v);
-}
 
 template <int NB, bool BM>
 __global__ void __launch_bounds__(64 * kWavesPerBlock) fwd_bf16_staged_kernel(FwdArgs p, StagedGeom gm) {

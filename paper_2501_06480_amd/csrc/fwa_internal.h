@@ -10,7 +10,7 @@ namespace fwa {
 
 constexpr int kHeadDim = 32;   // the only supported head width
 constexpr int kMaxL = 256;     // 16 key blocks of 16 rows
-constexpr int kMaxBackwardL = 64;  // backward: the whole tile in one wave
+constexpr int kMaxBackwardL = 64;  // backward: largest window whose score tile stays on chip (and that has dBias)
 constexpr int kWavesPerBlock = 4;
 
 struct FwdArgs {
@@ -61,6 +61,7 @@ int backward_max_slots(long long N, int heads);
 int coop_slots(long long N, int heads, int nW);
 hipError_t launch_backward_bf16_coop(const BwdArgs& a, hipStream_t s);
 hipError_t launch_backward_bf16_single(const BwdArgs& a, hipStream_t s);
+hipError_t launch_backward_bf16_large(const BwdArgs& a, hipStream_t s);
 hipError_t launch_zero_f32(float* dst, size_t count, hipStream_t s);
 hipError_t launch_bias_gather(const float* table, float* bias, int heads, int k, hipStream_t s);
 hipError_t launch_bias_scatter(const float* dbias, float* dtable, int heads, int k, hipStream_t s);

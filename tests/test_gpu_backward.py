@@ -103,6 +103,30 @@ def test_mask_period_too_long_for_the_cooperative_kernel(oracle):
     check_backward(oracle, w, bias, mask, "nW=300")
 
 
+@pytest.mark.parametrize("L", [65, 80, 81, 100, 127, 128, 129, 144, 145, 176, 177, 200, 225, 240, 250, 256])
+@pytest.mark.parametrize("use_bm", [False, True])
+def test_window_lengths_above_64(oracle, L, use_bm):
+    """Every block count 5..16 of the two-pass kernel, ragged and full last blocks; three heads,
+    more windows than the mask period."""
+    w = synth.Workload(f"bwd_L{L}", 6, L, 96, 3, "bf16", 5200 + L, 0, backward=True)
+    bias = synth.normal((3, L, L), 13 + L, 0.5) if use_bm else None
+    mask = None
+    if use_bm:
+        mask = np.where(synth.rng(7 + L).random((3, L, L)) < 0.2, -100.0, 0.0).astype(np.float32)
+        mask[:, np.arange(L), np.arange(L)] = 0.0
+    check_backward(oracle, w, bias, mask, f"L={L} bm={use_bm}", want_dbias=False)
+
+
+@pytest.mark.parametrize("L,k,hw,heads,N", [(144, 12, 48, 4, 160), (256, 16, 64, 4, 144), (196, 14, 56, 3, 208)])
+def test_large_windows_many_windows_per_workgroup(oracle, L, k, hw, heads, N):
+    """Config-4 shapes with bias and the shift mask, more windows than resident workgroups."""
+    w = synth.Workload(f"bwd_L{L}_h{heads}", N, L, 32 * heads, heads, "bf16", 5300 + L, k, hw, True, k // 2, True)
+    assert N % w.nW == 0
+    x = synth.draw(w)
+    bias = oracle.bias_gather(x["table"], w.k).astype(np.float32)
+    check_backward(oracle, w, bias, x["mask"], w.name, want_dbias=False)
+
+
 def test_backward_is_bit_reproducible():
     import torch
     import paper_2501_06480_amd as fwa
@@ -145,8 +169,8 @@ def test_unsupported_backward_cases_are_rejected():
     import paper_2501_06480_amd as fwa
     from paper_2501_06480_amd import binding
     q = torch.zeros((2, 144, 128), dtype=torch.bfloat16, device="cuda")
-    with pytest.raises(fwa.FwaError) as e:
-        fwa.fwa_backward(q, q.clone(), q.clone(), q.clone(), 4, 0.1)
+    with pytest.raises(fwa.FwaError) as e:   # dBias exists only for windows of up to 64 tokens
+        fwa.fwa_backward(q, q.clone(), q.clone(), q.clone(), 4, 0.1, want_dbias=True)
     assert e.value.code == binding.FWA_ERR_UNSUPPORTED
     q = torch.zeros((2, 49, 96), dtype=torch.float32, device="cuda")
     with pytest.raises(fwa.FwaError) as e:
