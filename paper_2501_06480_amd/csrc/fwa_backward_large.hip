@@ -46,8 +46,10 @@ __device__ __forceinline__ bf16x8 pair_operand(bf16x4 a, bf16x4 b) {
     return as_bf16x8(u32x4{ua.x, ua.y, ub.x, ub.y});
 }
 
-template <int NB, bool BM>
+// HB / HM: a bias / a mask is present (the absent one costs neither loads nor registers)
+template <int NB, bool HB, bool HM>
 __global__ void __launch_bounds__(64 * large_waves(NB)) bwd_bf16_large_kernel(BwdArgs p, LargeGeom gm) {
+    constexpr bool BM = HB || HM;
     constexpr int W = large_waves(NB);
     constexpr int NB2 = (NB + 1) / 2;
     constexpr int ROWS = 16 * NB;
@@ -77,7 +79,7 @@ __global__ void __launch_bounds__(64 * large_waves(NB)) bwd_bf16_large_kernel(Bw
 
     const uint32_t ll = (uint32_t)L * L * 4u;
     const __amdgpu_buffer_rsrc_t rb =
-        (BM && p.bias) ? make_rsrc(p.bias + (size_t)h * L * L, ll) : make_rsrc(nullptr, 0);
+        HB ? make_rsrc(p.bias + (size_t)h * L * L, ll) : make_rsrc(nullptr, 0);
 
     const uint32_t srow = (uint32_t)tid >> 2, scol = (uint32_t)tid & 3u;  // slab movement: (row, 16 B column)
     const uint32_t tile_bytes = (uint32_t)(L - 1) * row_bytes + 2u * kHeadDim;
@@ -115,31 +117,46 @@ __global__ void __launch_bounds__(64 * large_waves(NB)) bwd_bf16_large_kernel(Bw
         }
         __syncthreads();
         const __amdgpu_buffer_rsrc_t rm =
-            (BM && p.mask) ? make_rsrc(p.mask + (size_t)(w % (uint32_t)p.nW) * L * L, ll) : make_rsrc(nullptr, 0);
+            HM ? make_rsrc(p.mask + (size_t)(w % (uint32_t)p.nW) * L * L, ll) : make_rsrc(nullptr, 0);
 
         // ---------------- pass 1: query blocks wave, wave + W ----------------
         for (int qb = (int)wave; qb < NB; qb += W) {
             const bf16x8 qop = __builtin_bit_cast(bf16x8, lq[opd + 16 * qb * STRIDE]);
             const bf16x8 gop = __builtin_bit_cast(bf16x8, lg[opd + 16 * qb * STRIDE]);
+            // rows 16 qb .. 16 qb + 15 of (bias + mask), 64 columns at a time: lane -> (row 4t + lane / 16,
+            // columns 4 (lane % 16) ..), 256 contiguous bytes per 16 lanes; rows beyond L lie outside the
+            // descriptors and read as zero, columns beyond L are overwritten with -inf below.  The first
+            // patch is requested before the products are formed, each further one a patch ahead.
+            const uint32_t prow = (uint32_t)lane >> 4, pcol = 4u * ((uint32_t)lane & 15u);
+            constexpr int CH = (NB + 3) / 4;
+            f32x4 tb[2][4], tm[2][4];
+            const uint32_t qrow = (uint32_t)(16 * qb) * L * 4u;  // < ll: the block starts inside the tile
+            const __amdgpu_buffer_rsrc_t rbq = HB ? make_rsrc(p.bias + (size_t)h * L * L + (size_t)16 * qb * L, ll - qrow) : rb;
+            const __amdgpu_buffer_rsrc_t rmq =
+                HM ? make_rsrc(p.mask + (size_t)(w % (uint32_t)p.nW) * L * L + (size_t)16 * qb * L, ll - qrow) : rm;
+            auto request_patch = [&](int ch, int slot) {
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    const uint32_t off = ((uint32_t)(4 * t + prow) * L + pcol) * 4u + 256u * ch;
+                    if (HB) tb[slot][t] = load_f32x4(rbq, off);
+                    if (HM) tm[slot][t] = load_f32x4(rmq, off);
+                }
+            };
+            if (BM) request_patch(0, 0);
             f32x4 s[NB];
 #pragma unroll
             for (int jb = 0; jb < NB; ++jb)
                 s[jb] = mfma_bf16(__builtin_bit_cast(bf16x8, lk[opd + 16 * jb * STRIDE]), qop, zero);
             if (BM) {
-                // rows 16 qb .. 16 qb + 15 of (bias + mask), 64 columns at a time: lane -> (row 4t + lane / 16,
-                // columns 4 (lane % 16) ..), 256 contiguous bytes per 16 lanes; rows beyond L lie outside the
-                // descriptors and read as zero, columns beyond L are overwritten with -inf below
-                const uint32_t prow = (uint32_t)lane >> 4, pcol = 4u * ((uint32_t)lane & 15u);
 #pragma unroll
-                for (int ch = 0; ch < (NB + 3) / 4; ++ch) {
-                    f32x4 t4[4];
+                for (int ch = 0; ch < CH; ++ch) {
+                    const int cur = ch & 1;
+                    if (ch + 1 < CH) request_patch(ch + 1, cur ^ 1);
+                    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                    for (int t = 0; t < 4; ++t) {
-                        const uint32_t off = ((uint32_t)(16 * qb + 4 * t + prow) * L + 64 * ch + pcol) * 4u;
-                        t4[t] = (load_f32x4(rb, off) + load_f32x4(rm, off)) * kLog2e;
-                    }
-#pragma unroll
-                    for (int t = 0; t < 4; ++t) *reinterpret_cast<f32x4*>(patch + (4 * t + prow) * SG + pcol) = t4[t];
+                    for (int t = 0; t < 4; ++t)
+                        *reinterpret_cast<f32x4*>(patch + (4 * t + prow) * SG + pcol) =
+                            (HB && HM ? tb[cur][t] + tm[cur][t] : (HB ? tb[cur][t] : tm[cur][t])) * kLog2e;
 #pragma unroll
                     for (int b = 0; b < 4; ++b) {
                         const int jb = 4 * ch + b;
@@ -184,35 +201,52 @@ __global__ void __launch_bounds__(64 * large_waves(NB)) bwd_bf16_large_kernel(Bw
                 for (int r = 0; r < 4; ++r) delta = fmaf(s[jb][r], dp[r], delta);
             }
             delta = sum_over_g(delta) * inv;
+#pragma unroll
+            for (int jb = 0; jb < NB; ++jb) s[jb] *= inv;  // P
             if (g == 0) {
                 stM[16 * qb + n] = m + __builtin_amdgcn_logf(sum);  // p_ij = exp2(score_ij - M_i)
                 stD[16 * qb + n] = delta;
             }
-            // dQ^T = K^T dS^T over pairs of key blocks
+            // dQ^T = K^T dS^T over pairs of key blocks; the operands of the next pair are fetched ahead
             f32x4 q0 = zero, q1 = zero;  // dQ[16 qb + n][4g + r], dQ[16 qb + n][16 + 4g + r]
             const uint16_t* lk16 = reinterpret_cast<const uint16_t*>(lk) + trs;
+            bf16x8 ov[2][2], tk0[2], tk1[2];
+            auto fetch1 = [&](int kp, int slot) {
+                const bool two = 2 * kp + 1 < NB;
+                ov[slot][0] = __builtin_bit_cast(bf16x8, lv[opd + 16 * (2 * kp) * STRIDE]);
+                if (two) ov[slot][1] = __builtin_bit_cast(bf16x8, lv[opd + 16 * (2 * kp + 1) * STRIDE]);
+                tk0[slot] = operand_tr(lk16 + (32 * kp) * SROW, 16 * SROW, two);
+                tk1[slot] = operand_tr(lk16 + (32 * kp) * SROW + 16, 16 * SROW, two);
+            };
+            fetch1(0, 0);
 #pragma unroll
             for (int kp = 0; kp < NB2; ++kp) {
                 const bool two = 2 * kp + 1 < NB;
+                const int cur = kp & 1;
+                if (kp + 1 < NB2) fetch1(kp + 1, cur ^ 1);
+                __builtin_amdgcn_sched_barrier(0);
                 bf16x4 hi[2], lo[2];
                 hi[1] = lo[1] = as_bf16x4(uint2{0u, 0u});
+                f32x4 dp[2];
+#pragma unroll
+                for (int u = 0; u < 2; ++u) {
+                    if (u == 1 && !two) break;
+                    dp[u] = mfma_bf16(ov[cur][u], gop, zero);
+                }
 #pragma unroll
                 for (int u = 0; u < 2; ++u) {
                     if (u == 1 && !two) break;
                     const int jb = 2 * kp + u;
-                    const f32x4 dp = mfma_bf16(__builtin_bit_cast(bf16x8, lv[opd + 16 * jb * STRIDE]), gop, zero);
                     f32x4 ds;
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) ds[r] = s[jb][r] * inv * (dp[r] - delta);
+                    for (int r = 0; r < 4; ++r) ds[r] = s[jb][r] * (dp[u][r] - delta);
                     split_hi_lo(ds, hi[u], lo[u]);
                 }
                 const bf16x8 dh = pair_operand(hi[0], hi[1]), dl = pair_operand(lo[0], lo[1]);
-                const bf16x8 k0 = operand_tr(lk16 + (32 * kp) * SROW, 16 * SROW, two);
-                const bf16x8 k1 = operand_tr(lk16 + (32 * kp) * SROW + 16, 16 * SROW, two);
-                q0 = mfma_bf16(k0, dh, q0);
-                q1 = mfma_bf16(k1, dh, q1);
-                q0 = mfma_bf16(k0, dl, q0);
-                q1 = mfma_bf16(k1, dl, q1);
+                q0 = mfma_bf16(tk0[cur], dh, q0);
+                q1 = mfma_bf16(tk1[cur], dh, q1);
+                q0 = mfma_bf16(tk0[cur], dl, q0);
+                q1 = mfma_bf16(tk1[cur], dl, q1);
                 __builtin_amdgcn_sched_barrier(0);
             }
             const u32x2 lo2 = {pack_bf16(q0[0] * p.scale, q0[1] * p.scale), pack_bf16(q0[2] * p.scale, q0[3] * p.scale)};
@@ -232,54 +266,95 @@ __global__ void __launch_bounds__(64 * large_waves(NB)) bwd_bf16_large_kernel(Bw
             f32x4 v0 = zero, v1 = zero, k0 = zero, k1 = zero;  // dV, dK [16 jb + n][4g + r] and [..][16 + 4g + r]
             const uint16_t* lg16 = reinterpret_cast<const uint16_t*>(lg) + trs;
             const uint16_t* lq16 = reinterpret_cast<const uint16_t*>(lq) + trs;
+            // Operands (LDS) and additive terms (L2) of a pair of query blocks are fetched one pair ahead;
+            // the scheduling barriers keep the compiler from hoisting more than that.
+            uint32_t aoff[4];
 #pragma unroll
-            for (int qp = 0; qp < NB2; ++qp) {
+            for (int r = 0; r < 4; ++r) aoff[r] = ((uint32_t)(4 * g + r) * L + jcol) * 4u;
+            bf16x8 oq[2][2], og[2][2], tg0[2], tg1[2], tx0[2], tx1[2];
+            f32x4 oM[2][2], oD[2][2], ab[2][2], am[2][2];
+            auto fetch = [&](int qp, int slot) {
                 const bool two = 2 * qp + 1 < NB;
-                bf16x4 ph[2], pl[2], sh[2], sl[2];
-                ph[1] = pl[1] = sh[1] = sl[1] = as_bf16x4(uint2{0u, 0u});
 #pragma unroll
                 for (int u = 0; u < 2; ++u) {
                     if (u == 1 && !two) break;
                     const int qb = 2 * qp + u;
-                    f32x4 add = zero;
-                    if (BM) {
-                        // rows beyond L lie outside the descriptors; a key beyond L gets p = 0 below
+                    oq[slot][u] = __builtin_bit_cast(bf16x8, lq[opd + 16 * qb * STRIDE]);
+                    og[slot][u] = __builtin_bit_cast(bf16x8, lg[opd + 16 * qb * STRIDE]);
+                    oM[slot][u] = *reinterpret_cast<const f32x4*>(stM + 16 * qb + 4 * g);
+                    oD[slot][u] = *reinterpret_cast<const f32x4*>(stD + 16 * qb + 4 * g);
+                }
+                // dO^T and Q^T of the 32 queries (channel on the lane)
+                tg0[slot] = operand_tr(lg16 + (32 * qp) * SROW, 16 * SROW, two);
+                tg1[slot] = operand_tr(lg16 + (32 * qp) * SROW + 16, 16 * SROW, two);
+                tx0[slot] = operand_tr(lq16 + (32 * qp) * SROW, 16 * SROW, two);
+                tx1[slot] = operand_tr(lq16 + (32 * qp) * SROW + 16, 16 * SROW, two);
+            };
+            auto fetch_add = [&](int qp, int slot) {
+                // rows beyond L lie outside the descriptors (which start at the first row of the query
+                // block, so that the 4 lane offsets serve every block); a key beyond L gets p = 0 below
 #pragma unroll
-                        for (int r = 0; r < 4; ++r) {
-                            const uint32_t off = ((uint32_t)(16 * qb + 4 * g + r) * L + jcol) * 4u;
-                            add[r] = (load_f32(rb, off) + load_f32(rm, off)) * kLog2e;
-                        }
+                for (int u = 0; u < 2; ++u) {
+                    if (u == 1 && 2 * qp + 1 >= NB) break;
+                    const uint32_t qrow = (uint32_t)(16 * (2 * qp + u)) * L;
+                    const __amdgpu_buffer_rsrc_t rbq = HB ? make_rsrc(p.bias + (size_t)h * L * L + qrow, ll - 4u * qrow) : rb;
+                    const __amdgpu_buffer_rsrc_t rmq =
+                        HM ? make_rsrc(p.mask + (size_t)(w % (uint32_t)p.nW) * L * L + qrow, ll - 4u * qrow) : rm;
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        if (HB) ab[slot][u][r] = load_f32(rbq, aoff[r]);
+                        if (HM) am[slot][u][r] = load_f32(rmq, aoff[r]);
                     }
-                    const f32x4 sc = mfma_bf16(__builtin_bit_cast(bf16x8, lq[opd + 16 * qb * STRIDE]), kop, zero);
-                    const f32x4 dp = mfma_bf16(__builtin_bit_cast(bf16x8, lg[opd + 16 * qb * STRIDE]), vop, zero);
-                    const f32x4 M4 = *reinterpret_cast<const f32x4*>(stM + 16 * qb + 4 * g);
-                    const f32x4 D4 = *reinterpret_cast<const f32x4*>(stD + 16 * qb + 4 * g);
+                }
+            };
+            if (BM) fetch_add(0, 0);
+            fetch(0, 0);
+#pragma unroll
+            for (int qp = 0; qp < NB2; ++qp) {
+                const bool two = 2 * qp + 1 < NB;
+                const int cur = qp & 1;
+                if (BM && qp + 1 < NB2) fetch_add(qp + 1, cur ^ 1);
+                if (qp + 1 < NB2) fetch(qp + 1, cur ^ 1);
+                __builtin_amdgcn_sched_barrier(0);
+                bf16x4 ph[2], pl[2], sh[2], sl[2];
+                ph[1] = pl[1] = sh[1] = sl[1] = as_bf16x4(uint2{0u, 0u});
+                f32x4 sc[2], dp[2];
+#pragma unroll
+                for (int u = 0; u < 2; ++u) {
+                    if (u == 1 && !two) break;
+                    sc[u] = mfma_bf16(oq[cur][u], kop, zero);  // sc[r] = <q_i, k_j>, i = 16 qb + 4g + r, j = jcol
+                    dp[u] = mfma_bf16(og[cur][u], vop, zero);
+                }
+#pragma unroll
+                for (int u = 0; u < 2; ++u) {
+                    if (u == 1 && !two) break;
                     f32x4 pr, ds;
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
-                        const float x = BM ? fmaf(sc[r], sl2, add[r]) - M4[r] : fmaf(sc[r], sl2, -M4[r]);
+                        float x;
+                        if (BM) {
+                            const float add = HB && HM ? ab[cur][u][r] + am[cur][u][r] : (HB ? ab[cur][u][r] : am[cur][u][r]);
+                            x = fmaf(sc[u][r], sl2, fmaf(add, kLog2e, -oM[cur][u][r]));
+                        }
+                        else
+                            x = fmaf(sc[u][r], sl2, -oM[cur][u][r]);
                         pr[r] = valid ? __builtin_amdgcn_exp2f(x) : 0.f;
-                        ds[r] = pr[r] * (dp[r] - D4[r]);
+                        ds[r] = pr[r] * (dp[u][r] - oD[cur][u][r]);
                     }
                     split_hi_lo(pr, ph[u], pl[u]);
                     split_hi_lo(ds, sh[u], sl[u]);
                 }
                 const bf16x8 PH = pair_operand(ph[0], ph[1]), PL = pair_operand(pl[0], pl[1]);
                 const bf16x8 SH = pair_operand(sh[0], sh[1]), SL = pair_operand(sl[0], sl[1]);
-                // dO^T and Q^T of the 32 queries (channel on the lane)
-                const bf16x8 g0 = operand_tr(lg16 + (32 * qp) * SROW, 16 * SROW, two);
-                const bf16x8 g1 = operand_tr(lg16 + (32 * qp) * SROW + 16, 16 * SROW, two);
-                const bf16x8 x0 = operand_tr(lq16 + (32 * qp) * SROW, 16 * SROW, two);
-                const bf16x8 x1 = operand_tr(lq16 + (32 * qp) * SROW + 16, 16 * SROW, two);
-                v0 = mfma_bf16(g0, PH, v0);
-                v1 = mfma_bf16(g1, PH, v1);
-                k0 = mfma_bf16(x0, SH, k0);
-                k1 = mfma_bf16(x1, SH, k1);
-                v0 = mfma_bf16(g0, PL, v0);
-                v1 = mfma_bf16(g1, PL, v1);
-                k0 = mfma_bf16(x0, SL, k0);
-                k1 = mfma_bf16(x1, SL, k1);
-                __builtin_amdgcn_sched_barrier(0);  // keep the next pair's loads from being hoisted over this one
+                v0 = mfma_bf16(tg0[cur], PH, v0);
+                v1 = mfma_bf16(tg1[cur], PH, v1);
+                k0 = mfma_bf16(tx0[cur], SH, k0);
+                k1 = mfma_bf16(tx1[cur], SH, k1);
+                v0 = mfma_bf16(tg0[cur], PL, v0);
+                v1 = mfma_bf16(tg1[cur], PL, v1);
+                k0 = mfma_bf16(tx0[cur], SL, k0);
+                k1 = mfma_bf16(tx1[cur], SL, k1);
+                __builtin_amdgcn_sched_barrier(0);
             }
             const u32x2 va = {pack_bf16(v0[0], v0[1]), pack_bf16(v0[2], v0[3])};
             const u32x2 vb = {pack_bf16(v1[0], v1[1]), pack_bf16(v1[2], v1[3])};
@@ -296,10 +371,11 @@ __global__ void __launch_bounds__(64 * large_waves(NB)) bwd_bf16_large_kernel(Bw
     }
 }
 
-template <int NB, bool BM>
+template <int NB, bool HB, bool HM>
 hipError_t launch_large_one(const BwdArgs& a, hipStream_t st) {
+    constexpr bool BM = HB || HM;
     constexpr int W = large_waves(NB);
-    const void* fn = reinterpret_cast<const void*>(&bwd_bf16_large_kernel<NB, BM>);
+    const void* fn = reinterpret_cast<const void*>(&bwd_bf16_large_kernel<NB, HB, HM>);
     const unsigned block = 64u * W;
     const size_t lds = (size_t)4 * 16 * NB * 5 * 16 + (size_t)2 * 16 * NB * 4 + (BM ? (size_t)W * 16 * 68 * 4 : 0);
     // Workgroups one CU holds (LDS and registers decide), asked once per kernel.
@@ -323,13 +399,14 @@ hipError_t launch_large_one(const BwdArgs& a, hipStream_t st) {
     const unsigned grid = gm.G * gm.heads;
     gm.xcd_q = grid / 8u;
     gm.xcd_r = grid % 8u;
-    hipLaunchKernelGGL((bwd_bf16_large_kernel<NB, BM>), dim3(grid), dim3(block), lds, st, a, gm);
+    hipLaunchKernelGGL((bwd_bf16_large_kernel<NB, HB, HM>), dim3(grid), dim3(block), lds, st, a, gm);
     return hipGetLastError();
 }
 
 template <int NB>
 hipError_t launch_large_nb(const BwdArgs& a, hipStream_t st) {
-    return (a.bias || a.mask) ? launch_large_one<NB, true>(a, st) : launch_large_one<NB, false>(a, st);
+    if (a.bias) return a.mask ? launch_large_one<NB, true, true>(a, st) : launch_large_one<NB, true, false>(a, st);
+    return a.mask ? launch_large_one<NB, false, true>(a, st) : launch_large_one<NB, false, false>(a, st);
 }
 
 }  // namespace
