@@ -75,7 +75,7 @@ def time_other_workloads(torch, fwa, synth, dev):
     rotation rule as the headline (cycle larger than twice the last-level cache)."""
     out = []
 
-    def run(name, w, backward, iters):
+    def run(name, w, backward, iters, want_dbias=True):
         shape = (w.N, w.L, w.C)
         per_set = (7 if backward else 4) * w.N * w.L * w.C * 2
         nsets = max(2, -(-2 * LLC_BYTES // per_set) + 1)
@@ -89,13 +89,13 @@ def time_other_workloads(torch, fwa, synth, dev):
         if w.shift:
             mask = torch.from_numpy(synth.shift_mask(w.map_hw, w.map_hw, w.k, w.shift)).to(dev)
         if backward:
-            need = fwa.fwa_backward_workspace_bytes(w.N, w.L, w.C, w.heads, 1, True)
+            need = fwa.fwa_backward_workspace_bytes(w.N, w.L, w.C, w.heads, 1, want_dbias)
             ws = torch.empty(max(need, 16), dtype=torch.uint8, device=dev)
 
         def step(i):
             t = sets[i % nsets]
             if backward:
-                fwa.fwa_backward(t[0], t[1], t[2], t[3], w.heads, w.scale, bias, mask, want_dbias=True, workspace=ws)
+                fwa.fwa_backward(t[0], t[1], t[2], t[3], w.heads, w.scale, bias, mask, want_dbias=want_dbias, workspace=ws)
             else:
                 fwa.fwa_forward(t[0], t[1], t[2], w.heads, w.scale, bias, mask, out=outs[i % nsets])
 
@@ -121,6 +121,8 @@ def time_other_workloads(torch, fwa, synth, dev):
     s1, s3 = synth.config5()
     run("swin_t_stage1_bwd_bias_shiftmask_dbias (N=8192, L=49, 3 heads)", s1, True, 100)
     run("swin_t_stage3_bwd_bias_shiftmask_dbias (N=512, L=49, 12 heads)", s3, True, 100)
+    run("window12_bwd_bias (N=1024, L=144, 4 heads; dQ, dK, dV)", l144, True, 30, want_dbias=False)
+    run("window16_bwd_bias (N=1024, L=256, 4 heads; dQ, dK, dV)", l256, True, 20, want_dbias=False)
     return out
 
 
