@@ -67,8 +67,9 @@ int fwa_forward(const void* q, const void* k, const void* v, void* o,
 
 /*
  * Backward pass (paper Algorithm 2).  Inputs are Q, K, V and dO only.
- * Currently supported: dtype FWA_BF16 and L <= 64 (one wave owns a whole
- * window-head tile); other combinations return FWA_ERR_UNSUPPORTED.
+ * Supported: dtype FWA_BF16, any L <= 256 for dQ, dK, dV; dbias only for
+ * L <= 64 (windows whose L x L tile stays on chip).  fp32 data, and dbias with
+ * L > 64, return FWA_ERR_UNSUPPORTED.
  *   d_o        : in,  [N, L, C], dtype
  *   dq, dk, dv : out, [N, L, C], dtype, fully overwritten
  *   dbias      : NULL, or out [heads, L, L] fp32 = sum over all N windows of
