@@ -33,6 +33,7 @@ struct CoopGeom {
     FastDiv lanes_per_row;  // 4 * heads_per_block
     uint32_t heads_per_block;
     uint32_t G;             // window positions walked in parallel (= dBias slots)
+    uint32_t xcd_remap, xcd_q, xcd_r;
 };
 
 template <int NB, bool BM, bool DB>
@@ -45,8 +46,11 @@ __global__ void __launch_bounds__(64 * kCoopWavesPerTile * kCoopMaxHeads) bwd_bf
     const uint32_t wv = __builtin_amdgcn_readfirstlane(tid >> 6);
     const uint32_t hl = wv >> 2;            // head inside the workgroup
     const int role = (int)(wv & 3u);        // query block in phase A, key block in phase B
-    const uint32_t bw = fastdiv(blockIdx.x, gm.groups);
-    const uint32_t hg = blockIdx.x - bw * gm.groups.d;
+    // workgroups that share 128-byte lines (head groups of one window) are neighbours in the logical
+    // order; when a group is not made of whole lines the order is mapped so that they share an XCD
+    const uint32_t lb = gm.xcd_remap ? xcd_logical_block(blockIdx.x, gm.xcd_q, gm.xcd_r) : blockIdx.x;
+    const uint32_t bw = fastdiv(lb, gm.groups);
+    const uint32_t hg = lb - bw * gm.groups.d;
     const uint32_t hpb = gm.heads_per_block;
     const uint32_t h = hg * hpb + hl;
     const int L = p.L;
@@ -60,13 +64,17 @@ __global__ void __launch_bounds__(64 * kCoopWavesPerTile * kCoopMaxHeads) bwd_bf
     uint4* const lv = lds + ROWS * stride;
     uint4* const lq = lds + 2 * ROWS * stride;
     uint4* const lg = lds + 3 * ROWS * stride;
-    // P_hi, P_lo, dS_hi, dS_lo tiles of this head: [ROWS][XS] bf16, row-major, XS = ROWS + 4
-    constexpr uint32_t XS = ROWS + 4, XT = ROWS * XS;
+    // P_hi, P_lo, dS_hi, dS_lo tiles of this head: [ROWS][64] bf16.  A row is 16 units of 4 keys; unit
+    // (block b, quarter c) of row i sits at unit (b ^ (i & 3), c ^ ((i >> 2) & 3)): the 16 lanes of a
+    // write (16 rows, one unit each) and of a transposing read (4 rows x 4 units) then touch 16
+    // different units, i.e. every bank once.
+    constexpr uint32_t XS = 64, XT = ROWS * XS;
     uint16_t* const ex = reinterpret_cast<uint16_t*>(lds + 4 * ROWS * stride) + (size_t)hl * (4 * XT);
     const uint32_t srow = stride * 8u;  // slab row stride in bf16 elements
     // transposing-read base of this lane inside a slab (channel on the lane) and inside a tile
     const uint32_t trs = (4u * g + (n >> 2)) * srow + 32u * hl + 4u * (n & 3);
-    const uint32_t trx = (4u * g + (n >> 2)) * XS + 4u * (n & 3);
+    // transposing read of key block jb = role: row 4g + (n >> 2) (+ 16, 32, ...: same low row bits)
+    const uint32_t trx = (4u * g + (n >> 2)) * XS + ((((uint32_t)role) ^ (uint32_t)(n >> 2)) << 4) + ((((uint32_t)n & 3u) ^ (uint32_t)g) << 2);
     const uint32_t opd = (uint32_t)n * stride + 4u * hl + g;  // operand of row block b: slab[opd + 16 b stride]
 
     // additive score term of this wave's query rows, in registers (see the file comment)
@@ -102,19 +110,29 @@ __global__ void __launch_bounds__(64 * kCoopWavesPerTile * kCoopMaxHeads) bwd_bf
         pq = __builtin_amdgcn_raw_buffer_load_b128(make_rsrc((const char*)p.q + slab, slab_bytes), goff, 0, 0);
         pg = __builtin_amdgcn_raw_buffer_load_b128(make_rsrc((const char*)p.d_o + slab, slab_bytes), goff, 0, 0);
     };
-    if (bw < (uint32_t)p.N) request(bw);
-
-    const uint32_t tile_bytes = (uint32_t)(L - 1) * row_bytes + 2u * kHeadDim;
-    const uint32_t off_half = (uint32_t)n * row_bytes + 8u * g;  // channels 4g..4g+3 of row n (+32 B: 16+4g..)
-
-    for (uint32_t w = bw; w < (uint32_t)p.N; w += gm.G) {
+    auto park = [&]() {
         if (rip < (uint32_t)ROWS) {
             lk[loff] = __builtin_bit_cast(uint4, pk);
             lv[loff] = __builtin_bit_cast(uint4, pv);
             lq[loff] = __builtin_bit_cast(uint4, pq);
             lg[loff] = __builtin_bit_cast(uint4, pg);
         }
-        if (w + gm.G < (uint32_t)p.N) request(w + gm.G);  // in flight while this window is computed
+    };
+    if (bw < (uint32_t)p.N) {
+        request(bw);
+        park();
+    }
+
+    const uint32_t tile_bytes = (uint32_t)(L - 1) * row_bytes + 2u * kHeadDim;
+    const uint32_t off_half = (uint32_t)n * row_bytes + 8u * g;  // channels 4g..4g+3 of row n (+32 B: 16+4g..)
+
+    // The next window's slabs are requested at the top of an iteration and parked in LDS at its
+    // end, i.e. always with this iteration's output stores younger than them in the memory queue:
+    // the wait in front of the LDS writes then counts those stores out instead of waiting for them
+    // (at the top of the loop the compiler has to assume the worst of both ways in).
+    for (uint32_t w = bw; w < (uint32_t)p.N; w += gm.G) {
+        const bool has_next = w + gm.G < (uint32_t)p.N;
+        if (has_next) request(w + gm.G);  // in flight while this window is computed
         __syncthreads();
 
         const size_t tile = ((size_t)w * L * p.C + (size_t)h * kHeadDim) * 2u;
@@ -181,7 +199,7 @@ __global__ void __launch_bounds__(64 * kCoopWavesPerTile * kCoopMaxHeads) bwd_bf
                 bf16x4 p_hi, p_lo;
                 split_hi_lo(s[jb], p_hi, p_lo);
                 split_hi_lo(dp[jb], ds_hi[jb], ds_lo[jb]);
-                uint16_t* cell = ex + (16 * qb + n) * XS + 16 * jb + 4 * g;
+                uint16_t* cell = ex + (16 * qb + n) * XS + ((jb ^ (n & 3)) << 4) + ((g ^ ((n >> 2) & 3)) << 2);
                 *reinterpret_cast<uint2*>(cell + 0 * XT) = __builtin_bit_cast(uint2, p_hi);
                 *reinterpret_cast<uint2*>(cell + 1 * XT) = __builtin_bit_cast(uint2, p_lo);
                 *reinterpret_cast<uint2*>(cell + 2 * XT) = __builtin_bit_cast(uint2, ds_hi[jb]);
@@ -223,7 +241,7 @@ __global__ void __launch_bounds__(64 * kCoopWavesPerTile * kCoopMaxHeads) bwd_bf
             f32x4 v0 = zero, v1 = zero, k0 = zero, k1 = zero;  // dV, dK [16 jb + n][4g + r] and [..][16 + 4g + r]
             const uint16_t* lg16 = reinterpret_cast<const uint16_t*>(lg) + trs;
             const uint16_t* lq16 = reinterpret_cast<const uint16_t*>(lq) + trs;
-            const uint16_t* xt = ex + trx + 16 * jb;
+            const uint16_t* xt = ex + trx;
 #pragma unroll
             for (int qp = 0; qp < NB2; ++qp) {
                 const bool two = 2 * qp + 1 < NB;
@@ -259,6 +277,7 @@ __global__ void __launch_bounds__(64 * kCoopWavesPerTile * kCoopMaxHeads) bwd_bf
             __builtin_amdgcn_raw_buffer_store_b64(kb, rdk, off_half + 32 + 16 * jb * row_bytes, 0, 0);
         }
         __syncthreads();  // slabs and exchange area are rewritten by the next window
+        if (has_next) park();
     }
 
     if (DB && active) {
@@ -290,7 +309,10 @@ hipError_t launch_coop_nb(const BwdArgs& a, int hpb, hipStream_t st) {
     gm.heads_per_block = (uint32_t)hpb;
     gm.G = (uint32_t)a.slots;
     const unsigned grid = gm.G * groups, block = 64u * kCoopWavesPerTile * (unsigned)hpb;
-    const size_t lds = (size_t)4 * 16 * NB * (4 * hpb + 1) * 16 + (size_t)hpb * 4 * (16 * NB) * (16 * NB + 4) * 2;
+    const size_t lds = (size_t)4 * 16 * NB * (4 * hpb + 1) * 16 + (size_t)hpb * 4 * (16 * NB) * 64 * 2;
+    gm.xcd_remap = (hpb % 2 == 1 && groups > 1) ? 1u : 0u;
+    gm.xcd_q = grid / 8u;
+    gm.xcd_r = grid % 8u;
     const bool bm = a.bias || a.mask, db = a.dbias != nullptr;
     if (bm)
         return db ? launch_coop_one<NB, true, true>(a, gm, grid, block, lds, st)
@@ -301,14 +323,13 @@ hipError_t launch_coop_nb(const BwdArgs& a, int hpb, hipStream_t st) {
 
 }  // namespace
 
-// Heads per workgroup of the cooperative kernel: a divisor of `heads` whose slab is whole
-// 128-byte lines per row (an even count) or the whole row; 0 = not applicable.
-int coop_heads_per_block(int heads) {
-    if (heads <= kCoopMaxHeads) return heads;
-    if (heads % 2 == 0) return 2;
-    if (heads % 3 == 0) return 3;
-    return 0;
-}
+// Heads per workgroup of the cooperative kernel: all of them when the row has at most 3 (the
+// slab is then whole rows: full 128-byte lines in and out); otherwise one, three 4-wave
+// workgroups per CU that run their phases independently of each other.  With one head per
+// workgroup the 64-byte halves of a line are fetched by two workgroups (measured x1.4 fetch
+// traffic even with both on one XCD), yet over the Swin-T stages with 6, 12 and 24 heads it is
+// 3-4 % faster than groups of 2 or 3 heads, which fit only one workgroup per CU.
+int coop_heads_per_block(int heads) { return heads <= kCoopMaxHeads ? heads : 1; }
 
 // Window positions walked in parallel: about one workgroup per CU (LDS allows no more), a
 // multiple of nW so that every workgroup keeps one mask tile; 0 = the kernel does not apply.

@@ -81,9 +81,9 @@ def test_without_dbias_and_many_windows_per_wave(oracle):
 
 
 @pytest.mark.parametrize("heads", [1, 2, 3, 4, 5, 6, 7, 9, 12])
-def test_head_counts_reach_both_backward_kernels(oracle, heads):
-    """Head counts 1-3, even counts and multiples of 3 take the cooperative kernel; 5 and 7 have
-    no workgroup shape made of whole memory lines and take the single-wave kernel."""
+def test_head_counts_reach_every_workgroup_shape(oracle, heads):
+    """Up to 3 heads share one workgroup (whole rows); above that every head has its own
+    workgroup and the head groups of a window are spread over neighbouring workgroups."""
     L, N = 49, 6
     w = synth.Workload(f"bwd_heads{heads}", N, L, 32 * heads, heads, "bf16", 7000 + heads, 0, backward=True)
     bias = synth.normal((heads, L, L), 23 + heads, 0.5)
