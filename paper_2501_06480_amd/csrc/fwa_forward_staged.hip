@@ -213,15 +213,24 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) fwd_bf16_persistent_kerne
             sv[t] = __builtin_amdgcn_raw_buffer_load_b128(rv, goff + 16 * t * row_bytes, 0, 0);
         }
     };
-    if (bw < (uint32_t)p.N) request(bw);
-
-    for (uint32_t w = bw; w < (uint32_t)p.N; w += G) {
+    auto park = [&]() {
 #pragma unroll
         for (int t = 0; t < NB; ++t) {
             lk[loff + 16 * t * stride] = __builtin_bit_cast(uint4, sk[t]);
             lq[loff + 16 * t * stride] = __builtin_bit_cast(uint4, sq[t]);
             lv[loff + 16 * t * stride] = __builtin_bit_cast(uint4, sv[t]);
         }
+    };
+    if (bw < (uint32_t)p.N) {
+        request(bw);
+        park();
+    }
+
+    // The next slab is parked at the END of an iteration: there the loads it waits for are always
+    // older than this iteration's output stores, so the wait counts the stores out.  At the top of
+    // the loop the compiler must assume the worse of the two ways in and would wait for the stores.
+    for (uint32_t w = bw; w < (uint32_t)p.N; w += G) {
+        const bool has_next = w + G < (uint32_t)p.N;
         __syncthreads();
         bf16x8 kop[NB], qop[NB];
 #pragma unroll
@@ -240,7 +249,7 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) fwd_bf16_persistent_kerne
                 const u32x4 v = {a.x, a.y, b.x, b.y};
                 vop[kp][c] = as_bf16x8(v);
             }
-        if (w + G < (uint32_t)p.N) request(w + G);  // in flight while this window is computed
+        if (has_next) request(w + G);  // in flight while this window is computed
 
 #pragma unroll
         for (int qb = 0; qb < NB; ++qb) {
@@ -278,7 +287,8 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) fwd_bf16_persistent_kerne
                 __builtin_amdgcn_raw_buffer_store_b128(v, ro, goff + 16 * t * row_bytes, 0, 0);
             }
         }
-        __syncthreads();  // the slabs are rewritten at the top of the next iteration
+        __syncthreads();  // every wave has copied its output rows out of the Q tile
+        if (has_next) park();
     }
 }
 
@@ -469,26 +479,39 @@ __global__ void __launch_bounds__(64 * rowpersist_waves(NB)) fwd_bf16_rowpersist
         if (active)
             qnext = __builtin_amdgcn_raw_buffer_load_b128(make_rsrc((const char*)p.q + tile, tile_bytes), off_row, 0, 0);
     };
-    if (bw < (uint32_t)p.N) request(bw);
-
-    uint32_t buf = 0;
-    for (uint32_t w = bw; w < (uint32_t)p.N; w += gm.G, buf ^= 1u) {
-        uint4* const lk = lds + buf * (2 * ROWS * STRIDE);
-        uint4* const lv = lk + ROWS * STRIDE;
+    auto park = [&](uint32_t b) {
+        uint4* const dk = lds + b * (2 * ROWS * STRIDE);
+        uint4* const dv = dk + ROWS * STRIDE;
 #pragma unroll
         for (int t = 0; t < PASSES; ++t) {
             const uint32_t row = 16 * W * t + srow;
             if (row < (uint32_t)ROWS) {
-                lk[row * STRIDE + scol] = __builtin_bit_cast(uint4, pk[t]);
-                lv[row * STRIDE + scol] = __builtin_bit_cast(uint4, pv[t]);
+                dk[row * STRIDE + scol] = __builtin_bit_cast(uint4, pk[t]);
+                dv[row * STRIDE + scol] = __builtin_bit_cast(uint4, pv[t]);
             }
         }
+    };
+    if (bw < (uint32_t)p.N) {
+        request(bw);
+        park(0);
+    }
+
+    // Per window: request the next slabs, one barrier, compute from buffer `buf`, store, then park
+    // the next slabs in the other buffer.  That buffer was last read in the previous iteration,
+    // which every wave has left before any wave passes this iteration's barrier; and parking after
+    // the stores means the wait in front of it counts the stores out instead of waiting for them.
+    uint32_t buf = 0;
+    for (uint32_t w = bw; w < (uint32_t)p.N; w += gm.G, buf ^= 1u) {
+        const bool has_next = w + gm.G < (uint32_t)p.N;
+        uint4* const lk = lds + buf * (2 * ROWS * STRIDE);
+        uint4* const lv = lk + ROWS * STRIDE;
         const bf16x8 qop = as_bf16x8(qnext);
-        if (w + gm.G < (uint32_t)p.N) request(w + gm.G);  // in flight while this window is computed
-        // One barrier per window: the other buffer was last read in the previous iteration, which
-        // every wave has left before any wave passes this barrier and goes on to overwrite it.
+        if (has_next) request(w + gm.G);  // in flight while this window is computed
         __syncthreads();
-        if (!active) continue;
+        if (!active) {
+            if (has_next) park(buf ^ 1u);
+            continue;
+        }
 
         const uint4* const lkh = lk + n * STRIDE + g;  // K[16 jb + n][8g..] at lkh[16 jb * STRIDE]
         const uint16_t* const lvh =
@@ -528,6 +551,7 @@ __global__ void __launch_bounds__(64 * rowpersist_waves(NB)) fwd_bf16_rowpersist
         const uint32_t off_o = (uint32_t)(16 * qb + n) * row_bytes + 8u * g;
         __builtin_amdgcn_raw_buffer_store_b64(lo, ro, off_o, 0, 0);
         __builtin_amdgcn_raw_buffer_store_b64(hi, ro, off_o + 32, 0, 0);
+        if (has_next) park(buf ^ 1u);
     }
 }
 
