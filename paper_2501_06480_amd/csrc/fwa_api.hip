@@ -8,11 +8,14 @@ namespace {
 inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
 
 // Shape checks shared by forward, backward and the workspace query.
-int check_shape(int64_t N, int L, int C, int heads, int dtype) {
+// Head width 32 everywhere; the bf16 forward also takes 64, 128 and 256 for L <= 64.
+int check_shape(int64_t N, int L, int C, int heads, int dtype, bool forward) {
     if (N < 0 || L < 1 || C < 1 || heads < 1) return FWA_ERR_SHAPE;
     if (C % heads != 0) return FWA_ERR_SHAPE;
     if (dtype != FWA_F32 && dtype != FWA_BF16) return FWA_ERR_UNSUPPORTED;
-    if (C / heads != fwa::kHeadDim) return FWA_ERR_UNSUPPORTED;
+    if (C / heads != fwa::kHeadDim &&
+        !(forward && dtype == FWA_BF16 && fwa::forward_wide_supported(L, C / heads)))
+        return FWA_ERR_UNSUPPORTED;
     if (L > fwa::kMaxL) return FWA_ERR_UNSUPPORTED;
     // one launch: the number of wave tasks (at most 4 per window-head) must fit a 32-bit grid
     if ((double)N * heads * 4.0 > 2.0e9) return FWA_ERR_UNSUPPORTED;
@@ -52,7 +55,7 @@ const char* fwa_status_string(int code) {
 
 int fwa_forward(const void* q, const void* k, const void* v, void* o, int64_t N, int L, int C, int heads,
                 float scale, const float* bias, const float* mask, int nW, int dtype, void* stream) {
-    int rc = check_shape(N, L, C, heads, dtype);
+    int rc = check_shape(N, L, C, heads, dtype, true);
     if (rc != FWA_OK) return rc;
     rc = check_mask(N, mask, nW);
     if (rc != FWA_OK) return rc;
@@ -66,12 +69,14 @@ int fwa_forward(const void* q, const void* k, const void* v, void* o, int64_t N,
     a.bias = bias; a.mask = mask;
     a.N = N; a.L = L; a.C = C; a.heads = heads; a.nW = mask ? nW : 1; a.scale = scale;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    const hipError_t e = dtype == FWA_BF16 ? fwa::launch_forward_bf16(a, st) : fwa::launch_forward_f32(a, st);
+    const hipError_t e = dtype != FWA_BF16            ? fwa::launch_forward_f32(a, st)
+                         : C / heads != fwa::kHeadDim ? fwa::launch_forward_bf16_wide(a, st)
+                                                      : fwa::launch_forward_bf16(a, st);
     return e == hipSuccess ? FWA_OK : FWA_ERR_LAUNCH;
 }
 
 size_t fwa_backward_workspace_bytes(int64_t N, int L, int C, int heads, int dtype, int want_dbias) {
-    if (check_shape(N, L, C, heads, dtype) != FWA_OK || check_backward_support(L, dtype, want_dbias != 0) != FWA_OK)
+    if (check_shape(N, L, C, heads, dtype, false) != FWA_OK || check_backward_support(L, dtype, want_dbias != 0) != FWA_OK)
         return 0;
     if (!want_dbias || N == 0) return 0;
     // the slot count depends on the mask period; this is its upper bound over all periods
@@ -82,7 +87,7 @@ size_t fwa_backward_workspace_bytes(int64_t N, int L, int C, int heads, int dtyp
 int fwa_backward(const void* q, const void* k, const void* v, const void* d_o, void* dq, void* dk, void* dv,
                  float* dbias, int64_t N, int L, int C, int heads, float scale, const float* bias,
                  const float* mask, int nW, int dtype, void* workspace, size_t workspace_bytes, void* stream) {
-    int rc = check_shape(N, L, C, heads, dtype);
+    int rc = check_shape(N, L, C, heads, dtype, false);
     if (rc != FWA_OK) return rc;
     rc = check_backward_support(L, dtype, dbias != nullptr);
     if (rc != FWA_OK) return rc;

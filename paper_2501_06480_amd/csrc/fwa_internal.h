@@ -8,7 +8,8 @@
 
 namespace fwa {
 
-constexpr int kHeadDim = 32;   // the only supported head width
+constexpr int kHeadDim = 32;   // head width of every path but the wide-head forward
+constexpr int kMaxWideL = 64;  // wide-head forward (head widths 64, 128, 256): the tile of one window
 constexpr int kMaxL = 256;     // 16 key blocks of 16 rows
 constexpr int kMaxBackwardL = 64;  // backward: largest window whose score tile stays on chip (and that has dBias)
 constexpr int kWavesPerBlock = 4;
@@ -54,6 +55,8 @@ hipError_t launch_forward_bf16(const FwdArgs& a, hipStream_t s);
 hipError_t launch_forward_f32(const FwdArgs& a, hipStream_t s);
 int staged_heads_per_block(int L, int heads);
 hipError_t launch_forward_bf16_staged(const FwdArgs& a, hipStream_t s);
+bool forward_wide_supported(int L, int head_dim);
+hipError_t launch_forward_bf16_wide(const FwdArgs& a, hipStream_t s);
 hipError_t launch_backward_bf16(const BwdArgs& a, hipStream_t s);
 hipError_t launch_backward_f32(const BwdArgs& a, hipStream_t s);
 int backward_slots(long long N, int heads, int nW);

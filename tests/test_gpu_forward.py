@@ -106,6 +106,32 @@ def test_large_windows_many_windows_per_workgroup(oracle, L, k, hw, heads, N, wh
     assert err <= TOL["bf16"]
 
 
+@pytest.mark.parametrize("d", [64, 128, 256])
+@pytest.mark.parametrize("L", [64, 49, 33, 16, 7])
+@pytest.mark.parametrize("use_bm", [False, True])
+def test_wide_heads(oracle, d, L, use_bm):
+    """Head widths of the paper's kernel benchmark (L = 64, 4 heads, width per head swept): the
+    score product runs over d / 32 chunks, the output over d / 16 channel blocks."""
+    import torch
+    import paper_2501_06480_amd as fwa
+    heads, N = 4, 12
+    w = synth.Workload(f"wide_d{d}_L{L}", N, L, d * heads, heads, "bf16", 8000 + d + L, 0)
+    assert abs(w.scale - d ** -0.5) < 1e-12
+    x = synth.draw(w)
+    bias = mask = None
+    if use_bm:
+        bias = synth.normal((heads, L, L), 41 + L, 0.5)
+        mask = np.where(synth.rng(43 + L + d).random((3, L, L)) < 0.2, -100.0, 0.0).astype(np.float32)
+        mask[:, np.arange(L), np.arange(L)] = 0.0
+    q, k, v = (to_device(x, w, n) for n in ("q", "k", "v"))
+    o = fwa.fwa_forward(q, k, v, heads, w.scale, f32_device(bias), f32_device(mask))
+    torch.cuda.synchronize()
+    want = oracle.forward(x["q"], x["k"], x["v"], heads, w.scale, bias, mask)
+    err = max_abs(to_f64(o), want)
+    print(f"d={d} L={L} bm={use_bm}: max|ref|={np.abs(want).max():.2f} err={err:.3e}", flush=True)
+    assert err <= TOL["bf16"]
+
+
 def test_stage4_single_window_map_with_mask(oracle):
     """A 7x7 map is one window; the shift mask then has 4 regions inside it."""
     w = synth.Workload("s4_masked", 8, 49, 768, 24, "bf16", 1234, 7, 7, True, 3)
