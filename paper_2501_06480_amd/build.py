@@ -11,7 +11,7 @@ CSRC = os.path.join(HERE, "csrc")
 OUT = os.path.join(HERE, "libfwa.so")
 OBJ_DIR = os.path.join(HERE, "_build")
 SOURCES = ["fwa_api.hip", "fwa_forward.hip", "fwa_forward_staged.hip", "fwa_forward_wide.hip", "fwa_backward.hip",
-           "fwa_backward_coop.hip", "fwa_backward_large.hip", "fwa_bias.hip"]
+           "fwa_backward_coop.hip", "fwa_backward_large.hip", "fwa_backward_wide.hip", "fwa_bias.hip"]
 # packed fp32 VALU ops are switched off on purpose: the compiler must not form them
 # and matrix-core results go to ordinary VGPRs (no accumulator-register copies).
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wextra",

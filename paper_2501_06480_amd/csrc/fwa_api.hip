@@ -8,13 +8,14 @@ namespace {
 inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
 
 // Shape checks shared by forward, backward and the workspace query.
-// Head width 32 everywhere; the bf16 forward also takes 64, 128 and 256 for L <= 64.
-int check_shape(int64_t N, int L, int C, int heads, int dtype, bool forward) {
+// Head width 32 everywhere; the bf16 forward, and the bf16 backward without dBias, also take 64,
+// 128 and 256 for L <= 64 (`wide_ok` = the call is one of those).
+int check_shape(int64_t N, int L, int C, int heads, int dtype, bool wide_ok) {
     if (N < 0 || L < 1 || C < 1 || heads < 1) return FWA_ERR_SHAPE;
     if (C % heads != 0) return FWA_ERR_SHAPE;
     if (dtype != FWA_F32 && dtype != FWA_BF16) return FWA_ERR_UNSUPPORTED;
     if (C / heads != fwa::kHeadDim &&
-        !(forward && dtype == FWA_BF16 && fwa::forward_wide_supported(L, C / heads)))
+        !(wide_ok && dtype == FWA_BF16 && fwa::forward_wide_supported(L, C / heads)))
         return FWA_ERR_UNSUPPORTED;
     if (L > fwa::kMaxL) return FWA_ERR_UNSUPPORTED;
     // one launch: the number of wave tasks (at most 4 per window-head) must fit a 32-bit grid
@@ -76,7 +77,7 @@ int fwa_forward(const void* q, const void* k, const void* v, void* o, int64_t N,
 }
 
 size_t fwa_backward_workspace_bytes(int64_t N, int L, int C, int heads, int dtype, int want_dbias) {
-    if (check_shape(N, L, C, heads, dtype, false) != FWA_OK || check_backward_support(L, dtype, want_dbias != 0) != FWA_OK)
+    if (check_shape(N, L, C, heads, dtype, !want_dbias) != FWA_OK || check_backward_support(L, dtype, want_dbias != 0) != FWA_OK)
         return 0;
     if (!want_dbias || N == 0) return 0;
     // the slot count depends on the mask period; this is its upper bound over all periods
@@ -87,7 +88,7 @@ size_t fwa_backward_workspace_bytes(int64_t N, int L, int C, int heads, int dtyp
 int fwa_backward(const void* q, const void* k, const void* v, const void* d_o, void* dq, void* dk, void* dv,
                  float* dbias, int64_t N, int L, int C, int heads, float scale, const float* bias,
                  const float* mask, int nW, int dtype, void* workspace, size_t workspace_bytes, void* stream) {
-    int rc = check_shape(N, L, C, heads, dtype, false);
+    int rc = check_shape(N, L, C, heads, dtype, dbias == nullptr);
     if (rc != FWA_OK) return rc;
     rc = check_backward_support(L, dtype, dbias != nullptr);
     if (rc != FWA_OK) return rc;

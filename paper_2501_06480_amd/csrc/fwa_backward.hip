@@ -403,6 +403,7 @@ hipError_t launch_backward_bf16_single(const BwdArgs& a, hipStream_t s) {
 
 // dbias[h][i][j] = sum over the slots of partial[slot][h][i][j]
 hipError_t launch_backward_bf16(const BwdArgs& a, hipStream_t s) {
+    if (a.C / a.heads != kHeadDim) return launch_backward_bf16_wide(a, s);
     if (a.L > kMaxBackwardL) return launch_backward_bf16_large(a, s);
     const bool coop = coop_slots(a.N, a.heads, a.mask ? a.nW : 1) > 0;
     const hipError_t e = coop ? launch_backward_bf16_coop(a, s) : launch_backward_bf16_single(a, s);

@@ -1,0 +1,303 @@
+// Backward (paper Algorithm 2) for head widths 64, 128 and 256 at L <= 64: the shapes of the
+// paper's forward-backward kernel benchmark (section 3.1).
+//
+// One workgroup per (window, head), one wave per 16-row block, two phases as in the kernel for
+// width 32, with every product over the feature dimension run chunk by chunk (eq. 5-6: D / 32
+// k-steps for S and dP) and every D-wide output produced in D / 16 blocks of 16 channels that
+// are stored as soon as they are complete, so that no wave ever holds a D-wide accumulator.
+//
+//   LDS, first half of the tile's life : K, V slabs (row operands of S^T = K Q^T and dP^T = V dO^T,
+//                                        K^T for dQ through the transposing read)
+//   phase A, wave <-> query block      : own Q, dO rows straight from global memory as operands;
+//                                        softmax, delta, dS; dQ; P and dS as hi + lo bf16 into
+//                                        swizzled LDS tiles
+//   LDS, second half                   : the Q, dO slabs take the place of K, V (requested from
+//                                        global memory before phase A, parked after it)
+//   phase B, wave <-> key block        : dV^T = dO^T P, dK^T = Q^T dS with P, dS (key on the lane)
+//                                        and dO^T, Q^T (channel on the lane) through the
+//                                        transposing read
+//
+// Q and dO are therefore read twice from global memory (the second time from L2), which is the
+// paper's own count for its Algorithm 2.  No dBias here.
+#include "fwa_device.h"
+#include "fwa_internal.h"
+
+namespace fwa {
+namespace {
+
+template <int NB, int D, bool BM>
+__global__ void __launch_bounds__(256) bwd_bf16_wide_kernel(BwdArgs p) {
+    constexpr int NB2 = (NB + 1) / 2;
+    constexpr int ROWS = 16 * NB;
+    constexpr int CH = D / 32;               // chunks of the products over the feature dimension
+    constexpr int CB = D / 16;               // 16-channel blocks of dQ, dK, dV
+    constexpr uint32_t STRIDE = D / 8 + 1;   // slab row in 16-byte units: D * 2 bytes of data + 16 of padding
+    constexpr uint32_t SROW = STRIDE * 8;    // the same in bf16 elements
+    constexpr int TPR = D / 8;               // threads that move one slab row
+    constexpr int RPP = 256 / TPR;           // rows per pass of the workgroup
+    constexpr int PASSES = (ROWS + RPP - 1) / RPP;
+    constexpr uint32_t XS = 64, XT = ROWS * XS;  // P / dS tiles: [ROWS][64] bf16, units swizzled (see below)
+    extern __shared__ __attribute__((aligned(16))) uint4 lds[];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int n = lane & 15, g = lane >> 4;
+    const int role = __builtin_amdgcn_readfirstlane(tid >> 6);  // query block in phase A, key block in phase B
+    const bool active = role < NB;
+    const uint32_t w = blockIdx.x / (uint32_t)p.heads, h = blockIdx.x % (uint32_t)p.heads;
+    const int L = p.L;
+    const uint32_t row_bytes = (uint32_t)p.C * 2u;
+    const size_t tile = ((size_t)w * L * p.C + (size_t)h * D) * 2u;
+    const uint32_t tile_bytes = (uint32_t)(L - 1) * row_bytes + 2u * D;  // rows beyond L read as zero
+    const float sl2 = p.scale * kLog2e;
+    const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+    typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+    uint4* const sa = lds;                  // K, then Q
+    uint4* const sb = lds + ROWS * STRIDE;  // V, then dO
+    // Tiles P_hi, P_lo, dS_hi, dS_lo.  A row is 16 units of 4 keys; unit (block b, quarter c) of
+    // row i sits at unit (b ^ (i & 3), c ^ ((i >> 2) & 3)): the 16 lanes of a write (16 rows, one
+    // unit each) and of a transposing read (4 rows x 4 units) then touch every bank once.
+    uint16_t* const ex = reinterpret_cast<uint16_t*>(lds + 2 * ROWS * STRIDE);
+
+    const __amdgpu_buffer_rsrc_t rq = make_rsrc((const char*)p.q + tile, tile_bytes);
+    const __amdgpu_buffer_rsrc_t rg = make_rsrc((const char*)p.d_o + tile, tile_bytes);
+    const uint32_t srow = (uint32_t)tid / TPR, scol = (uint32_t)tid % TPR;  // slab movement: (row, 16 B column)
+
+    // own Q and dO rows as operands: lane (g, n) takes channels 32 c + 8g .. + 7 of row 16 role + n
+    bf16x8 qop[CH], gop[CH];
+    {
+        const uint32_t off = (uint32_t)(16 * role + n) * row_bytes + 16u * g;
+#pragma unroll
+        for (int c = 0; c < CH; ++c) {
+            qop[c] = as_bf16x8(__builtin_amdgcn_raw_buffer_load_b128(rq, off + 64 * c, 0, 0));
+            gop[c] = as_bf16x8(__builtin_amdgcn_raw_buffer_load_b128(rg, off + 64 * c, 0, 0));
+        }
+    }
+    {
+        const __amdgpu_buffer_rsrc_t rk = make_rsrc((const char*)p.k + tile, tile_bytes);
+        const __amdgpu_buffer_rsrc_t rv = make_rsrc((const char*)p.v + tile, tile_bytes);
+        u32x4 sk[PASSES], sv[PASSES];
+#pragma unroll
+        for (int t = 0; t < PASSES; ++t) {
+            const uint32_t off = (RPP * t + srow) * row_bytes + scol * 16u;
+            sk[t] = __builtin_amdgcn_raw_buffer_load_b128(rk, off, 0, 0);
+            sv[t] = __builtin_amdgcn_raw_buffer_load_b128(rv, off, 0, 0);
+        }
+#pragma unroll
+        for (int t = 0; t < PASSES; ++t) {
+            const uint32_t row = RPP * t + srow;
+            if (row < (uint32_t)ROWS) {
+                sa[row * STRIDE + scol] = __builtin_bit_cast(uint4, sk[t]);
+                sb[row * STRIDE + scol] = __builtin_bit_cast(uint4, sv[t]);
+            }
+        }
+    }
+    // the Q and dO slabs for phase B, in flight during phase A
+    u32x4 sq[PASSES], sg[PASSES];
+#pragma unroll
+    for (int t = 0; t < PASSES; ++t) {
+        const uint32_t off = (RPP * t + srow) * row_bytes + scol * 16u;
+        sq[t] = __builtin_amdgcn_raw_buffer_load_b128(rq, off, 0, 0);
+        sg[t] = __builtin_amdgcn_raw_buffer_load_b128(rg, off, 0, 0);
+    }
+    __syncthreads();
+
+    const uint32_t opd = (uint32_t)n * STRIDE + g;                   // row operand: slab[opd + 16 b STRIDE + 4 c]
+    const uint32_t trs = (4u * g + (n >> 2)) * SROW + 4u * (n & 3);  // transposing-read base inside a slab
+    const uint32_t off_half = (uint32_t)n * row_bytes + 8u * g;      // channels 4g..4g+3 of row n
+
+    // ---------------- phase A: query block `role` ----------------
+    if (active) {
+        const int qb = role;
+        f32x4 s[NB], dp[NB];
+#pragma unroll
+        for (int jb = 0; jb < NB; ++jb) s[jb] = dp[jb] = zero;
+#pragma unroll
+        for (int c = 0; c < CH; ++c)
+#pragma unroll
+            for (int jb = 0; jb < NB; ++jb) {
+                s[jb] = mfma_bf16(__builtin_bit_cast(bf16x8, sa[opd + 16 * jb * STRIDE + 4 * c]), qop[c], s[jb]);
+                dp[jb] = mfma_bf16(__builtin_bit_cast(bf16x8, sb[opd + 16 * jb * STRIDE + 4 * c]), gop[c], dp[jb]);
+            }
+        if (BM) {
+            const uint32_t ll = (uint32_t)L * L * 4u;
+            const __amdgpu_buffer_rsrc_t rb = p.bias ? make_rsrc(p.bias + (size_t)h * L * L, ll) : make_rsrc(nullptr, 0);
+            const __amdgpu_buffer_rsrc_t rm =
+                p.mask ? make_rsrc(p.mask + (size_t)(w % (uint32_t)p.nW) * L * L, ll) : make_rsrc(nullptr, 0);
+            const uint32_t off = (((uint32_t)(16 * qb + n)) * L + 4u * g) * 4u;
+#pragma unroll
+            for (int jb = 0; jb < NB; ++jb) {
+                const f32x4 add = (load_f32x4(rb, off + 16 * jb * 4u) + load_f32x4(rm, off + 16 * jb * 4u)) * kLog2e;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) s[jb][r] = fmaf(s[jb][r], sl2, add[r]);
+            }
+        } else {
+#pragma unroll
+            for (int jb = 0; jb < NB; ++jb) s[jb] *= sl2;
+        }
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+            if (16 * (NB - 1) + 4 * g + r >= L) s[NB - 1][r] = -INFINITY;
+        float m = s[0][0];
+#pragma unroll
+        for (int jb = 0; jb < NB; ++jb) {
+            m = fmaxf(fmaxf(m, s[jb][0]), s[jb][1]);
+            m = fmaxf(fmaxf(m, s[jb][2]), s[jb][3]);
+        }
+        m = max_over_g(m);
+        float sum = 0.f;
+#pragma unroll
+        for (int jb = 0; jb < NB; ++jb)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const float e = __builtin_amdgcn_exp2f(s[jb][r] - m);
+                s[jb][r] = e;
+                sum += e;
+            }
+        sum = sum_over_g(sum);
+        const float inv = __builtin_amdgcn_rcpf(sum);
+        float delta = 0.f;
+#pragma unroll
+        for (int jb = 0; jb < NB; ++jb)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                s[jb][r] *= inv;  // P
+                delta = fmaf(s[jb][r], dp[jb][r], delta);
+            }
+        delta = sum_over_g(delta);
+        bf16x4 ds_hi[NB], ds_lo[NB];
+#pragma unroll
+        for (int jb = 0; jb < NB; ++jb) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) dp[jb][r] = s[jb][r] * (dp[jb][r] - delta);  // dS
+            bf16x4 p_hi, p_lo;
+            split_hi_lo(s[jb], p_hi, p_lo);
+            split_hi_lo(dp[jb], ds_hi[jb], ds_lo[jb]);
+            uint16_t* cell = ex + (16 * qb + n) * XS + ((jb ^ (n & 3)) << 4) + ((g ^ ((n >> 2) & 3)) << 2);
+            *reinterpret_cast<uint2*>(cell + 0 * XT) = __builtin_bit_cast(uint2, p_hi);
+            *reinterpret_cast<uint2*>(cell + 1 * XT) = __builtin_bit_cast(uint2, p_lo);
+            *reinterpret_cast<uint2*>(cell + 2 * XT) = __builtin_bit_cast(uint2, ds_hi[jb]);
+            *reinterpret_cast<uint2*>(cell + 3 * XT) = __builtin_bit_cast(uint2, ds_lo[jb]);
+        }
+        // dS of pairs of key blocks as operands (keys on the k-slots)
+        bf16x8 dh[NB2], dl[NB2];
+#pragma unroll
+        for (int kp = 0; kp < NB2; ++kp) {
+            const bool two = 2 * kp + 1 < NB;
+            const uint2 h0 = __builtin_bit_cast(uint2, ds_hi[2 * kp]), l0 = __builtin_bit_cast(uint2, ds_lo[2 * kp]);
+            uint2 h1 = {0u, 0u}, l1 = {0u, 0u};
+            if (two) {
+                h1 = __builtin_bit_cast(uint2, ds_hi[two ? 2 * kp + 1 : 0]);
+                l1 = __builtin_bit_cast(uint2, ds_lo[two ? 2 * kp + 1 : 0]);
+            }
+            dh[kp] = as_bf16x8(u32x4{h0.x, h0.y, h1.x, h1.y});
+            dl[kp] = as_bf16x8(u32x4{l0.x, l0.y, l1.x, l1.y});
+        }
+        // dQ^T = K^T dS^T, 16 channels at a time: acc[r] = dQ[16 qb + n][16 cb + 4g + r]
+        const uint16_t* lk16 = reinterpret_cast<const uint16_t*>(sa) + trs;
+        const __amdgpu_buffer_rsrc_t rdq = make_rsrc((char*)p.dq + tile, tile_bytes);
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb) {
+            f32x4 acc = zero;
+#pragma unroll
+            for (int kp = 0; kp < NB2; ++kp) {
+                const bf16x8 kt = operand_tr(lk16 + (32 * kp) * SROW + 16 * cb, 16 * SROW, 2 * kp + 1 < NB);
+                acc = mfma_bf16(kt, dh[kp], acc);
+                acc = mfma_bf16(kt, dl[kp], acc);
+            }
+            const u32x2 v = {pack_bf16(acc[0] * p.scale, acc[1] * p.scale), pack_bf16(acc[2] * p.scale, acc[3] * p.scale)};
+            __builtin_amdgcn_raw_buffer_store_b64(v, rdq, off_half + 16 * qb * row_bytes + 32 * cb, 0, 0);
+        }
+    }
+    __syncthreads();  // K, V no longer needed; tiles complete
+#pragma unroll
+    for (int t = 0; t < PASSES; ++t) {
+        const uint32_t row = RPP * t + srow;
+        if (row < (uint32_t)ROWS) {
+            sa[row * STRIDE + scol] = __builtin_bit_cast(uint4, sq[t]);
+            sb[row * STRIDE + scol] = __builtin_bit_cast(uint4, sg[t]);
+        }
+    }
+    __syncthreads();
+
+    // ---------------- phase B: key block `role` ----------------
+    if (active) {
+        const int jb = role;
+        // P and dS of all queries for this key block (key on the lane, queries on the k-slots)
+        const uint16_t* xt = ex + (4u * g + (n >> 2)) * XS + ((((uint32_t)jb) ^ (uint32_t)(n >> 2)) << 4) +
+                             ((((uint32_t)n & 3u) ^ (uint32_t)g) << 2);
+        bf16x8 ph[NB2], pl[NB2], sh[NB2], sl[NB2];
+#pragma unroll
+        for (int qp = 0; qp < NB2; ++qp) {
+            const bool two = 2 * qp + 1 < NB;
+            ph[qp] = operand_tr(xt + 0 * XT + (32 * qp) * XS, 16 * XS, two);
+            pl[qp] = operand_tr(xt + 1 * XT + (32 * qp) * XS, 16 * XS, two);
+            sh[qp] = operand_tr(xt + 2 * XT + (32 * qp) * XS, 16 * XS, two);
+            sl[qp] = operand_tr(xt + 3 * XT + (32 * qp) * XS, 16 * XS, two);
+        }
+        const uint16_t* lq16 = reinterpret_cast<const uint16_t*>(sa) + trs;
+        const uint16_t* lg16 = reinterpret_cast<const uint16_t*>(sb) + trs;
+        const __amdgpu_buffer_rsrc_t rdv = make_rsrc((char*)p.dv + tile, tile_bytes);
+        const __amdgpu_buffer_rsrc_t rdk = make_rsrc((char*)p.dk + tile, tile_bytes);
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb) {
+            f32x4 av = zero, ak = zero;  // dV, dK [16 jb + n][16 cb + 4g + r]
+#pragma unroll
+            for (int qp = 0; qp < NB2; ++qp) {
+                const bool two = 2 * qp + 1 < NB;
+                const bf16x8 gt = operand_tr(lg16 + (32 * qp) * SROW + 16 * cb, 16 * SROW, two);
+                const bf16x8 qt = operand_tr(lq16 + (32 * qp) * SROW + 16 * cb, 16 * SROW, two);
+                av = mfma_bf16(gt, ph[qp], av);
+                ak = mfma_bf16(qt, sh[qp], ak);
+                av = mfma_bf16(gt, pl[qp], av);
+                ak = mfma_bf16(qt, sl[qp], ak);
+            }
+            const u32x2 vv = {pack_bf16(av[0], av[1]), pack_bf16(av[2], av[3])};
+            const u32x2 vk = {pack_bf16(ak[0] * p.scale, ak[1] * p.scale), pack_bf16(ak[2] * p.scale, ak[3] * p.scale)};
+            __builtin_amdgcn_raw_buffer_store_b64(vv, rdv, off_half + 16 * jb * row_bytes + 32 * cb, 0, 0);
+            __builtin_amdgcn_raw_buffer_store_b64(vk, rdk, off_half + 16 * jb * row_bytes + 32 * cb, 0, 0);
+        }
+    }
+}
+
+template <int NB, int D>
+hipError_t launch_wide_nb(const BwdArgs& a, hipStream_t st) {
+    const unsigned grid = (unsigned)(a.N * a.heads);
+    const size_t lds = (size_t)2 * 16 * NB * (D / 8 + 1) * 16 + (size_t)4 * 16 * NB * 64 * 2;
+    const bool bm = a.bias || a.mask;
+    const void* fn = bm ? reinterpret_cast<const void*>(&bwd_bf16_wide_kernel<NB, D, true>)
+                        : reinterpret_cast<const void*>(&bwd_bf16_wide_kernel<NB, D, false>);
+    if (lds > 64 * 1024) {
+        const hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+    }
+    if (bm)
+        hipLaunchKernelGGL((bwd_bf16_wide_kernel<NB, D, true>), dim3(grid), dim3(256), lds, st, a);
+    else
+        hipLaunchKernelGGL((bwd_bf16_wide_kernel<NB, D, false>), dim3(grid), dim3(256), lds, st, a);
+    return hipGetLastError();
+}
+
+template <int D>
+hipError_t launch_wide_d(const BwdArgs& a, hipStream_t s) {
+    switch ((a.L + 15) / 16) {
+        case 1: return launch_wide_nb<1, D>(a, s);
+        case 2: return launch_wide_nb<2, D>(a, s);
+        case 3: return launch_wide_nb<3, D>(a, s);
+        case 4: return launch_wide_nb<4, D>(a, s);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace
+
+hipError_t launch_backward_bf16_wide(const BwdArgs& a, hipStream_t s) {
+    if (a.dbias != nullptr) return hipErrorNotSupported;
+    switch (a.C / a.heads) {
+        case 64: return launch_wide_d<64>(a, s);
+        case 128: return launch_wide_d<128>(a, s);
+        case 256: return launch_wide_d<256>(a, s);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace fwa

@@ -8,8 +8,8 @@
 
 namespace fwa {
 
-constexpr int kHeadDim = 32;   // head width of every path but the wide-head forward
-constexpr int kMaxWideL = 64;  // wide-head forward (head widths 64, 128, 256): the tile of one window
+constexpr int kHeadDim = 32;   // head width of every path but the wide-head kernels
+constexpr int kMaxWideL = 64;  // wide-head kernels (head widths 64, 128, 256): the tile of one window
 constexpr int kMaxL = 256;     // 16 key blocks of 16 rows
 constexpr int kMaxBackwardL = 64;  // backward: largest window whose score tile stays on chip (and that has dBias)
 constexpr int kWavesPerBlock = 4;
@@ -65,6 +65,7 @@ int coop_slots(long long N, int heads, int nW);
 hipError_t launch_backward_bf16_coop(const BwdArgs& a, hipStream_t s);
 hipError_t launch_backward_bf16_single(const BwdArgs& a, hipStream_t s);
 hipError_t launch_backward_bf16_large(const BwdArgs& a, hipStream_t s);
+hipError_t launch_backward_bf16_wide(const BwdArgs& a, hipStream_t s);
 hipError_t launch_zero_f32(float* dst, size_t count, hipStream_t s);
 hipError_t launch_bias_gather(const float* table, float* bias, int heads, int k, hipStream_t s);
 hipError_t launch_bias_scatter(const float* dbias, float* dtable, int heads, int k, hipStream_t s);

@@ -30,3 +30,22 @@ def bf16_round_f64(x):
     """fp64 reference rounded to bf16 (via fp32), to separate kernel error from output rounding."""
     from paper_2501_06480_amd import synth
     return synth.bf16_round(x.astype(np.float32))[0].astype(np.float64)
+
+
+def check_bf16_output(got, want, what):
+    """The benchmark's bf16 bound: max-abs 1e-2 against the un-rounded fp64 oracle.  A bf16 output of
+    magnitude >= 4 cannot meet it whatever the kernel does (half an ulp is 0.0156 on [4, 8)), so
+    such elements -- counted and reported -- are held to half a bf16 ulp of the reference plus the
+    2e-3 allowed to the kernel's internal error, and all others to 1e-2.  Returns the largest
+    error among the elements below 4."""
+    err = np.abs(got - want)
+    big = np.abs(want) >= 4.0
+    small_err = float(err[~big].max()) if (~big).any() else 0.0
+    assert small_err <= TOL["bf16"], (what, small_err)
+    if big.any():
+        half_ulp = 2.0 ** (np.floor(np.log2(np.abs(want[big]))) - 8)
+        excess = float((err[big] - half_ulp).max())
+        print(f"{what}: {int(big.sum())} elements with |ref| >= 4 (max {np.abs(want).max():.2f}), "
+              f"error beyond half a bf16 ulp {excess:.2e}", flush=True)
+        assert excess <= 2e-3, (what, excess)
+    return small_err
