@@ -19,7 +19,10 @@
  *    (a hipStream_t passed as void*; NULL = the default stream) and returns.
  *  - Tensors are contiguous, row-major.  Q, K, V, O, dO, dQ, dK, dV are
  *    [N, L, C]; head h owns channels [h*d, (h+1)*d) with d = C / heads.
- *    Supported: d == 32, 1 <= L <= 256, N >= 0 (N == 0 is a no-op).
+ *    Supported: d == 32 with 1 <= L <= 256; with FWA_BF16 also d == 64, 128,
+ *    256 with 1 <= L <= 64 (the feature-dimension loop of paper eq. 5-6; the
+ *    shapes of its Section 3.1 benchmark), except dbias.  N >= 0 (N == 0 is
+ *    a no-op).
  *  - dtype is FWA_F32 (fp32 data, fp32 arithmetic) or FWA_BF16 (bf16 data,
  *    bf16 matrix-core products with fp32 accumulation, fp32 softmax, one final
  *    round-to-nearest-even to bf16).
@@ -44,7 +47,7 @@ enum {
     FWA_OK = 0,
     FWA_ERR_NULL = 1,        /* a required pointer is NULL                          */
     FWA_ERR_SHAPE = 2,       /* negative N, L < 1, C % heads != 0, N % nW != 0, ... */
-    FWA_ERR_UNSUPPORTED = 3, /* head dim != 32, L > 256, unknown dtype              */
+    FWA_ERR_UNSUPPORTED = 3, /* head dim, L, dtype or dbias outside the ranges above */
     FWA_ERR_ALIGN = 4,       /* a base pointer is not 16-byte aligned               */
     FWA_ERR_WORKSPACE = 5,   /* workspace missing or smaller than required          */
     FWA_ERR_LAUNCH = 6,      /* the HIP runtime refused the launch                  */
@@ -68,8 +71,8 @@ int fwa_forward(const void* q, const void* k, const void* v, void* o,
 /*
  * Backward pass (paper Algorithm 2).  Inputs are Q, K, V and dO only.
  * Supported: dtype FWA_BF16, any L <= 256 for dQ, dK, dV; dbias only for
- * L <= 64 (windows whose L x L tile stays on chip).  fp32 data, and dbias with
- * L > 64, return FWA_ERR_UNSUPPORTED.
+ * d == 32 and L <= 64 (its accumulator stays on chip across windows).  fp32
+ * data, and dbias with L > 64 or d > 32, return FWA_ERR_UNSUPPORTED.
  *   d_o        : in,  [N, L, C], dtype
  *   dq, dk, dv : out, [N, L, C], dtype, fully overwritten
  *   dbias      : NULL, or out [heads, L, L] fp32 = sum over all N windows of
