@@ -2,18 +2,19 @@
 // the registers of a few waves, so it is produced twice, block by block, in the two
 // orientations the two kinds of output need, and never leaves the registers.
 //
-// A workgroup of W = ceil(NB / 2) waves (NB = ceil(L / 16) blocks of 16 rows) owns one head,
+// A workgroup of W = 4 (NB <= 10) or 8 waves (NB = ceil(L / 16) blocks of 16 rows; a multiple of
+// the 4 SIMDs, so that two 4-wave workgroups or one 8-wave workgroup load a CU evenly) owns one head,
 // parks the K, V, Q, dO slabs of the current window in LDS and walks the windows
 // bw, bw + G, ...  Per window:
 //
-//   pass 1, wave <-> 16-query block qb ("query on the lane": lane (g, n), slot r of key block
+//   pass 1, wave <-> 16-query blocks qb = wave, wave + W, ... ("query on the lane": lane (g, n), slot r of key block
 //   jb stands for query 16 qb + n and key 16 jb + 4g + r):
 //       S^T = K Q^T for all key blocks, + bias + mask, row max, exp, row sum
 //       delta_i = sum_j P_ij dP_ij with dP^T = V dO^T produced block by block
 //       M_i = max_i + log2(sum_i) and delta_i go to LDS for pass 2
 //       dQ rows of the block: dS^T is already the operand of dQ^T = K^T dS^T (dP recomputed
 //       block by block; K^T through the transposing LDS read)
-//   pass 2, wave <-> 16-key block jb ("key on the lane": lane (g, n), slot r of query block qb
+//   pass 2, wave <-> 16-key blocks jb = wave, wave + W, ... ("key on the lane": lane (g, n), slot r of query block qb
 //   stands for query 16 qb + 4g + r and key 16 jb + n):
 //       S = Q K^T and dP = dO V^T block by block, P = exp2(score - M_i), dS = P (dP - delta_i):
 //       the accumulator layout is exactly the operand layout of dV^T = dO^T P and dK^T = Q^T dS
@@ -39,7 +40,7 @@ struct LargeGeom {
     uint32_t xcd_q, xcd_r;
 };
 
-constexpr int large_waves(int nb) { return (nb + 1) / 2; }
+constexpr int large_waves(int nb) { return nb <= 10 ? 4 : 8; }
 
 __device__ __forceinline__ bf16x8 pair_operand(bf16x4 a, bf16x4 b) {
     const uint2 ua = __builtin_bit_cast(uint2, a), ub = __builtin_bit_cast(uint2, b);
