@@ -69,6 +69,20 @@ int fwa_forward(const void* q, const void* k, const void* v, void* o,
                 int dtype, void* stream);
 
 /*
+ * The same with row strides: token row (n, l) of q, k and v starts ld_qkv elements after row
+ * (n, l) - 1 (window n begins at row n*L), and likewise ld_o for o; ld == C is the contiguous
+ * case above.  This reads Q, K, V in place out of a fused projection output [N, L, 3, heads, d]
+ * (q = base, k = base + C, v = base + 2C elements, ld_qkv = 3C), saving the permute and copy in
+ * front of the kernel.  Strides must be >= C and keep rows 16-byte aligned (FWA_ERR_SHAPE /
+ * FWA_ERR_ALIGN otherwise).
+ */
+int fwa_forward_strided(const void* q, const void* k, const void* v, void* o,
+                        int64_t N, int L, int C, int heads, float scale,
+                        int64_t ld_qkv, int64_t ld_o,
+                        const float* bias, const float* mask, int nW,
+                        int dtype, void* stream);
+
+/*
  * Backward pass (paper Algorithm 2).  Inputs are Q, K, V and dO only.
  * Supported: dtype FWA_BF16, any L <= 256 for dQ, dK, dV; dbias only for
  * d == 32 and L <= 64 (its accumulator stays on chip across windows).  fp32
@@ -87,6 +101,16 @@ int fwa_backward(const void* q, const void* k, const void* v, const void* d_o,
                  int64_t N, int L, int C, int heads, float scale,
                  const float* bias, const float* mask, int nW,
                  int dtype, void* workspace, size_t workspace_bytes, void* stream);
+
+/* The same with row strides (see fwa_forward_strided): ld_qkv for q, k, v; ld_do for d_o;
+ * ld_dqkv for dq, dk, dv, so that the three gradients can be written straight into a fused
+ * [N, L, 3, heads, d] gradient buffer. */
+int fwa_backward_strided(const void* q, const void* k, const void* v, const void* d_o,
+                         void* dq, void* dk, void* dv, float* dbias,
+                         int64_t N, int L, int C, int heads, float scale,
+                         int64_t ld_qkv, int64_t ld_do, int64_t ld_dqkv,
+                         const float* bias, const float* mask, int nW,
+                         int dtype, void* workspace, size_t workspace_bytes, void* stream);
 
 /* Bytes of workspace fwa_backward needs for these arguments (0 if none).
  * Returns 0 for arguments fwa_backward would reject. */

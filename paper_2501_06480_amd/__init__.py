@@ -1,7 +1,9 @@
 """Flash Window Attention hot path for MI355X (gfx950).
 
 ``binding`` is the thin ctypes layer over the C-ABI library built from
-``csrc/`` (hand-written HIP); ``synth`` draws seeded synthetic workloads.
+``csrc/`` (hand-written HIP); ``autograd`` wraps its calls as differentiable torch
+functions (imported on demand: ``from paper_2501_06480_amd import autograd``);
+``synth`` draws seeded synthetic workloads.
 Nothing here computes attention on the CPU: if the HIP library is missing,
 calls fail loudly.
 """

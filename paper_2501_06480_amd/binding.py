@@ -27,8 +27,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libfwa.so")
 _lib = None
 
-EXPORTS = ("fwa_forward", "fwa_backward", "fwa_backward_workspace_bytes", "fwa_bias_gather",
-           "fwa_bias_scatter", "fwa_status_string")
+EXPORTS = ("fwa_forward", "fwa_forward_strided", "fwa_backward", "fwa_backward_strided",
+           "fwa_backward_workspace_bytes", "fwa_bias_gather", "fwa_bias_scatter", "fwa_status_string")
 
 
 class FwaError(RuntimeError):
@@ -54,9 +54,14 @@ def load_library():
     vp, i64, ci, cf, sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_float, ctypes.c_size_t
     lib.fwa_forward.restype = ci
     lib.fwa_forward.argtypes = [vp, vp, vp, vp, i64, ci, ci, ci, cf, vp, vp, ci, ci, vp]
+    lib.fwa_forward_strided.restype = ci
+    lib.fwa_forward_strided.argtypes = [vp, vp, vp, vp, i64, ci, ci, ci, cf, i64, i64, vp, vp, ci, ci, vp]
     lib.fwa_backward.restype = ci
     lib.fwa_backward.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i64, ci, ci, ci, cf, vp, vp, ci, ci,
                                  vp, sz, vp]
+    lib.fwa_backward_strided.restype = ci
+    lib.fwa_backward_strided.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i64, ci, ci, ci, cf, i64, i64, i64,
+                                         vp, vp, ci, ci, vp, sz, vp]
     lib.fwa_backward_workspace_bytes.restype = sz
     lib.fwa_backward_workspace_bytes.argtypes = [i64, ci, ci, ci, ci, ci]
     lib.fwa_bias_gather.restype = ci
@@ -96,6 +101,25 @@ def _dev_ptr(t, name: str, like=None, f32: bool = False) -> Optional[int]:
     return t.data_ptr()
 
 
+def _row_ptr(t, name: str, like=None):
+    """(device pointer, row stride in elements) of an [N, L, C] tensor whose channels are
+    contiguous and whose token rows are evenly spaced, e.g. a q/k/v view of a fused
+    [N, L, 3, heads, d] projection output.  A contiguous tensor has row stride C."""
+    if not getattr(t, "is_cuda", False):
+        raise TypeError(f"{name} must be a GPU tensor (there is no CPU path)")
+    if t.dim() != 3:
+        raise ValueError(f"{name} must be [N, L, C]")
+    if like is not None and (t.shape != like.shape or t.dtype != like.dtype or t.device != like.device):
+        raise ValueError(f"{name} must match q in shape, dtype and device")
+    N, L, C = t.shape
+    if t.is_contiguous():
+        return t.data_ptr(), C
+    s0, s1, s2 = t.stride()
+    if (C > 1 and s2 != 1) or (L > 1 and s1 < C) or (N > 1 and s0 != L * s1):
+        raise ValueError(f"{name}: channels must be contiguous and token rows evenly spaced (stride {t.stride()})")
+    return t.data_ptr(), (s1 if L > 1 else (s0 if N > 1 else C))
+
+
 _torch_mod = None
 
 
@@ -130,23 +154,33 @@ class _on_device:
 
 
 def fwa_forward(q, k, v, heads: int, scale: float, bias=None, mask=None, out=None, stream=None):
-    """O = softmax(scale*QK^T + B + M) V (paper Algorithm 1).  Tensors are [N, L, C] on the GPU."""
+    """O = softmax(scale*QK^T + B + M) V (paper Algorithm 1).  Tensors are [N, L, C] on the GPU;
+    q, k, v (and `out`) may be row-strided views, e.g. of a fused [N, L, 3, heads, d] tensor."""
     lib = _lib if _lib is not None else load_library()
     N, L, C = q.shape
-    qp = _dev_ptr(q, "q")
-    o = _torch().empty_like(q) if out is None else out
+    o = _torch().empty_like(q, memory_format=_torch().contiguous_format) if out is None else out
     nW = 0 if mask is None else int(mask.shape[0])
     if bias is not None and tuple(bias.shape) != (heads, L, L):
         raise ValueError("bias must be [heads, L, L]")
     if mask is not None and tuple(mask.shape) != (nW, L, L):
         raise ValueError("mask must be [nW, L, L]")
-    args = (qp, _dev_ptr(k, "k", q), _dev_ptr(v, "v", q), _dev_ptr(o, "out", q), N, L, C,
-            int(heads), float(scale), _dev_ptr(bias, "bias", f32=True), _dev_ptr(mask, "mask", f32=True), nW,
-            _dtype_code(q), _stream_handle(stream, q.device))
+    tail = (_dev_ptr(bias, "bias", f32=True), _dev_ptr(mask, "mask", f32=True), nW, _dtype_code(q),
+            _stream_handle(stream, q.device))
+    if q.is_contiguous() and k.is_contiguous() and v.is_contiguous() and o.is_contiguous():
+        args = (_dev_ptr(q, "q"), _dev_ptr(k, "k", q), _dev_ptr(v, "v", q), _dev_ptr(o, "out", q), N, L, C,
+                int(heads), float(scale)) + tail
+        fn, what = lib.fwa_forward, "fwa_forward"
+    else:
+        (qp, ld), (kp, ldk), (vp, ldv), (op, ldo) = (_row_ptr(q, "q"), _row_ptr(k, "k", q), _row_ptr(v, "v", q),
+                                                    _row_ptr(o, "out", q))
+        if not ld == ldk == ldv:
+            raise ValueError("q, k and v must share one row stride")
+        args = (qp, kp, vp, op, N, L, C, int(heads), float(scale), ld, ldo) + tail
+        fn, what = lib.fwa_forward_strided, "fwa_forward_strided"
     with _on_device(q.device):
-        rc = lib.fwa_forward(*args)
+        rc = fn(*args)
     if rc != FWA_OK:
-        raise FwaError(rc, "fwa_forward")
+        raise FwaError(rc, what)
     return o
 
 
@@ -155,13 +189,17 @@ def fwa_backward_workspace_bytes(N: int, L: int, C: int, heads: int, dtype: int,
 
 
 def fwa_backward(q, k, v, d_o, heads: int, scale: float, bias=None, mask=None, want_dbias: bool = False,
-                 workspace=None, stream=None):
-    """(dQ, dK, dV, dBias) from Q, K, V, dO (paper Algorithm 2).  dBias is None unless asked for."""
+                 workspace=None, stream=None, out=None):
+    """(dQ, dK, dV, dBias) from Q, K, V, dO (paper Algorithm 2).  dBias is None unless asked for.
+    q, k, v, d_o may be row-strided views; `out` = (dq, dk, dv) writes the gradients into given
+    tensors, e.g. the three views of a fused [N, L, 3, heads, d] gradient buffer."""
     import torch
     lib = load_library()
     N, L, C = q.shape
-    ptrs = (_dev_ptr(q, "q"), _dev_ptr(k, "k", q), _dev_ptr(v, "v", q), _dev_ptr(d_o, "d_o", q))
-    dq, dk, dv = torch.empty_like(q), torch.empty_like(q), torch.empty_like(q)
+    if out is None:
+        dq, dk, dv = (torch.empty_like(q, memory_format=torch.contiguous_format) for _ in range(3))
+    else:
+        dq, dk, dv = out
     dbias = torch.empty((heads, L, L), dtype=torch.float32, device=q.device) if want_dbias else None
     nW = 0 if mask is None else int(mask.shape[0])
     if bias is not None and tuple(bias.shape) != (heads, L, L):
@@ -172,15 +210,27 @@ def fwa_backward(q, k, v, d_o, heads: int, scale: float, bias=None, mask=None, w
     if workspace is None and need:
         workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    tail = (_dev_ptr(bias, "bias", f32=True), _dev_ptr(mask, "mask", f32=True), nW, _dtype_code(q),
+            None if workspace is None else workspace.data_ptr(), ws_bytes, _stream_handle(stream, q.device))
+    tensors = (q, k, v, d_o, dq, dk, dv)
+    if all(t.is_contiguous() for t in tensors):
+        ptrs = (_dev_ptr(q, "q"), _dev_ptr(k, "k", q), _dev_ptr(v, "v", q), _dev_ptr(d_o, "d_o", q),
+                _dev_ptr(dq, "dq", q), _dev_ptr(dk, "dk", q), _dev_ptr(dv, "dv", q))
+        args = ptrs + (None if dbias is None else dbias.data_ptr(), N, L, C, int(heads), float(scale)) + tail
+        fn, what = lib.fwa_backward, "fwa_backward"
+    else:
+        rows = [_row_ptr(t, nm, None if nm == "q" else q) for t, nm in zip(tensors, ("q", "k", "v", "d_o", "dq", "dk", "dv"))]
+        if not rows[0][1] == rows[1][1] == rows[2][1]:
+            raise ValueError("q, k and v must share one row stride")
+        if not rows[4][1] == rows[5][1] == rows[6][1]:
+            raise ValueError("dq, dk and dv must share one row stride")
+        args = tuple(r[0] for r in rows) + (None if dbias is None else dbias.data_ptr(), N, L, C, int(heads),
+                                            float(scale), rows[0][1], rows[3][1], rows[4][1]) + tail
+        fn, what = lib.fwa_backward_strided, "fwa_backward_strided"
     with _on_device(q.device):
-        rc = lib.fwa_backward(*ptrs, dq.data_ptr(), dk.data_ptr(), dv.data_ptr(),
-                              None if dbias is None else dbias.data_ptr(), N, L, C, int(heads),
-                              float(scale), _dev_ptr(bias, "bias", f32=True),
-                              _dev_ptr(mask, "mask", f32=True), nW, _dtype_code(q),
-                              None if workspace is None else workspace.data_ptr(), ws_bytes,
-                              _stream_handle(stream, q.device))
+        rc = fn(*args)
     if rc != FWA_OK:
-        raise FwaError(rc, "fwa_backward")
+        raise FwaError(rc, what)
     return dq, dk, dv, dbias
 
 

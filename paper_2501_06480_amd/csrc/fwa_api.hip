@@ -30,6 +30,16 @@ int check_backward_support(int L, int dtype, bool want_dbias) {
     return FWA_OK;
 }
 
+// Row stride of a strided tensor, in elements: at least C, rows 16-byte aligned, and small enough
+// that the byte offsets inside one window fit 32 bits with room to spare.
+int check_row_stride(int64_t ld, int C, int dtype) {
+    const int64_t per16 = dtype == FWA_BF16 ? 8 : 4;
+    if (ld < C) return FWA_ERR_SHAPE;
+    if (ld % per16 != 0) return FWA_ERR_ALIGN;
+    if (ld > (int64_t)1 << 20) return FWA_ERR_UNSUPPORTED;
+    return FWA_OK;
+}
+
 int check_mask(int64_t N, const float* mask, int nW) {
     if (mask == nullptr) return FWA_OK;
     if (nW < 1 || N % nW != 0) return FWA_ERR_SHAPE;
@@ -54,11 +64,16 @@ const char* fwa_status_string(int code) {
     }
 }
 
-int fwa_forward(const void* q, const void* k, const void* v, void* o, int64_t N, int L, int C, int heads,
-                float scale, const float* bias, const float* mask, int nW, int dtype, void* stream) {
+int fwa_forward_strided(const void* q, const void* k, const void* v, void* o, int64_t N, int L, int C, int heads,
+                        float scale, int64_t ld_qkv, int64_t ld_o, const float* bias, const float* mask, int nW,
+                        int dtype, void* stream) {
     int rc = check_shape(N, L, C, heads, dtype, true);
     if (rc != FWA_OK) return rc;
     rc = check_mask(N, mask, nW);
+    if (rc != FWA_OK) return rc;
+    rc = check_row_stride(ld_qkv, C, dtype);
+    if (rc != FWA_OK) return rc;
+    rc = check_row_stride(ld_o, C, dtype);
     if (rc != FWA_OK) return rc;
     if (N == 0) return FWA_OK;
     if (!q || !k || !v || !o) return FWA_ERR_NULL;
@@ -69,11 +84,17 @@ int fwa_forward(const void* q, const void* k, const void* v, void* o, int64_t N,
     a.q = q; a.k = k; a.v = v; a.o = o;
     a.bias = bias; a.mask = mask;
     a.N = N; a.L = L; a.C = C; a.heads = heads; a.nW = mask ? nW : 1; a.scale = scale;
+    a.ldq = (int)ld_qkv; a.ldo = (int)ld_o;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const hipError_t e = dtype != FWA_BF16            ? fwa::launch_forward_f32(a, st)
                          : C / heads != fwa::kHeadDim ? fwa::launch_forward_bf16_wide(a, st)
                                                       : fwa::launch_forward_bf16(a, st);
     return e == hipSuccess ? FWA_OK : FWA_ERR_LAUNCH;
+}
+
+int fwa_forward(const void* q, const void* k, const void* v, void* o, int64_t N, int L, int C, int heads,
+                float scale, const float* bias, const float* mask, int nW, int dtype, void* stream) {
+    return fwa_forward_strided(q, k, v, o, N, L, C, heads, scale, C, C, bias, mask, nW, dtype, stream);
 }
 
 size_t fwa_backward_workspace_bytes(int64_t N, int L, int C, int heads, int dtype, int want_dbias) {
@@ -85,10 +106,17 @@ size_t fwa_backward_workspace_bytes(int64_t N, int L, int C, int heads, int dtyp
     return (size_t)fwa::backward_max_slots(N, heads) * heads * nb * nb * 256 * sizeof(float);
 }
 
-int fwa_backward(const void* q, const void* k, const void* v, const void* d_o, void* dq, void* dk, void* dv,
-                 float* dbias, int64_t N, int L, int C, int heads, float scale, const float* bias,
-                 const float* mask, int nW, int dtype, void* workspace, size_t workspace_bytes, void* stream) {
+int fwa_backward_strided(const void* q, const void* k, const void* v, const void* d_o, void* dq, void* dk, void* dv,
+                         float* dbias, int64_t N, int L, int C, int heads, float scale, int64_t ld_qkv,
+                         int64_t ld_do, int64_t ld_dqkv, const float* bias, const float* mask, int nW, int dtype,
+                         void* workspace, size_t workspace_bytes, void* stream) {
     int rc = check_shape(N, L, C, heads, dtype, dbias == nullptr);
+    if (rc != FWA_OK) return rc;
+    rc = check_row_stride(ld_qkv, C, dtype);
+    if (rc != FWA_OK) return rc;
+    rc = check_row_stride(ld_do, C, dtype);
+    if (rc != FWA_OK) return rc;
+    rc = check_row_stride(ld_dqkv, C, dtype);
     if (rc != FWA_OK) return rc;
     rc = check_backward_support(L, dtype, dbias != nullptr);
     if (rc != FWA_OK) return rc;
@@ -124,8 +152,16 @@ int fwa_backward(const void* q, const void* k, const void* v, const void* d_o, v
     a.bias = bias; a.mask = mask;
     a.N = N; a.L = L; a.C = C; a.heads = heads; a.nW = mask ? nW : 1; a.scale = scale;
     a.slots = fwa::backward_slots(N, heads, mask ? nW : 1);
+    a.ldq = (int)ld_qkv; a.ldg = (int)ld_do; a.ldd = (int)ld_dqkv;
     const hipError_t e = dtype == FWA_BF16 ? fwa::launch_backward_bf16(a, st) : fwa::launch_backward_f32(a, st);
     return e == hipSuccess ? FWA_OK : FWA_ERR_LAUNCH;
+}
+
+int fwa_backward(const void* q, const void* k, const void* v, const void* d_o, void* dq, void* dk, void* dv,
+                 float* dbias, int64_t N, int L, int C, int heads, float scale, const float* bias,
+                 const float* mask, int nW, int dtype, void* workspace, size_t workspace_bytes, void* stream) {
+    return fwa_backward_strided(q, k, v, d_o, dq, dk, dv, dbias, N, L, C, heads, scale, C, C, C, bias, mask, nW,
+                                dtype, workspace, workspace_bytes, stream);
 }
 
 int fwa_bias_gather(const float* table, float* bias, int heads, int k, void* stream) {

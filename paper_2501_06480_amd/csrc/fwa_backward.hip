@@ -74,9 +74,13 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, 2) bwd_bf16_kernel(BwdArg
     }
 
     const int L = p.L;
-    const uint32_t row_bytes = (uint32_t)p.C * 2u;
+    // token rows are p.ldq (q, k, v), p.ldg (d_o), p.ldd (dq, dk, dv) elements apart; window w starts at row w L
+    const uint32_t row_bytes = (uint32_t)p.ldq * 2u, row_g = (uint32_t)p.ldg * 2u, row_d = (uint32_t)p.ldd * 2u;
     const uint32_t tile_bytes = (uint32_t)(L - 1) * row_bytes + 2u * kHeadDim;
+    const uint32_t tile_bytes_g = (uint32_t)(L - 1) * row_g + 2u * kHeadDim;
+    const uint32_t tile_bytes_d = (uint32_t)(L - 1) * row_d + 2u * kHeadDim;
     const uint32_t off_row = (uint32_t)n * row_bytes + 16u * g;  // 16 B of row n (plus a block offset)
+    const uint32_t off_row_g = (uint32_t)n * row_g + 16u * g, off_row_d = (uint32_t)n * row_d + 16u * g;
     const float sl2 = p.scale * kLog2e;
     const uint32_t off_b = ((uint32_t)n * L + 4u * g) * 4u;      // B[n][4g] (plus block offsets)
     __amdgpu_buffer_rsrc_t rb = make_rsrc(nullptr, 0);
@@ -93,15 +97,17 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, 2) bwd_bf16_kernel(BwdArg
     // Fetch the rows of window `wn` into the stage.  Rows beyond L are skipped: their slots
     // keep the zeros written once below.
     auto stage_rows = [&](long long wn) {
-        const size_t t = ((size_t)wn * L * p.C + (size_t)h * kHeadDim) * 2u + off_row;
+        const size_t t = ((size_t)wn * L * p.ldq + (size_t)h * kHeadDim) * 2u + off_row;
+        const size_t tg = ((size_t)wn * L * p.ldg + (size_t)h * kHeadDim) * 2u + off_row_g;
 #pragma unroll
         for (int b = 0; b < NB; ++b) {
             if (16 * b + n < L) {
                 const size_t o = t + (size_t)(16 * b) * row_bytes;
+                const size_t og = tg + (size_t)(16 * b) * row_g;
                 __builtin_amdgcn_global_load_lds((global_cptr)((const char*)p.k + o), (lds_vptr)(stage + (0 * NB + b) * 64), 16, 0, 0);
                 __builtin_amdgcn_global_load_lds((global_cptr)((const char*)p.q + o), (lds_vptr)(stage + (1 * NB + b) * 64), 16, 0, 0);
                 __builtin_amdgcn_global_load_lds((global_cptr)((const char*)p.v + o), (lds_vptr)(stage + (2 * NB + b) * 64), 16, 0, 0);
-                __builtin_amdgcn_global_load_lds((global_cptr)((const char*)p.d_o + o), (lds_vptr)(stage + (3 * NB + b) * 64), 16, 0, 0);
+                __builtin_amdgcn_global_load_lds((global_cptr)((const char*)p.d_o + og), (lds_vptr)(stage + (3 * NB + b) * 64), 16, 0, 0);
             }
         }
     };
@@ -114,14 +120,16 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, 2) bwd_bf16_kernel(BwdArg
     }
 
     for (long long w = slot; w < p.N; w += gm.slots) {
-        const size_t tile = ((size_t)w * L * p.C + (size_t)h * kHeadDim) * 2u;
+        const size_t tile = ((size_t)w * L * p.ldq + (size_t)h * kHeadDim) * 2u;
+        const size_t tile_g = ((size_t)w * L * p.ldg + (size_t)h * kHeadDim) * 2u;
+        const size_t tile_d = ((size_t)w * L * p.ldd + (size_t)h * kHeadDim) * 2u;
         const __amdgpu_buffer_rsrc_t rq = make_rsrc((const char*)p.q + tile, tile_bytes);
         const __amdgpu_buffer_rsrc_t rk = make_rsrc((const char*)p.k + tile, tile_bytes);
         const __amdgpu_buffer_rsrc_t rv = make_rsrc((const char*)p.v + tile, tile_bytes);
-        const __amdgpu_buffer_rsrc_t rg = make_rsrc((const char*)p.d_o + tile, tile_bytes);
-        const __amdgpu_buffer_rsrc_t rdq = make_rsrc((char*)p.dq + tile, tile_bytes);
-        const __amdgpu_buffer_rsrc_t rdk = make_rsrc((char*)p.dk + tile, tile_bytes);
-        const __amdgpu_buffer_rsrc_t rdv = make_rsrc((char*)p.dv + tile, tile_bytes);
+        const __amdgpu_buffer_rsrc_t rg = make_rsrc((const char*)p.d_o + tile_g, tile_bytes_g);
+        const __amdgpu_buffer_rsrc_t rdq = make_rsrc((char*)p.dq + tile_d, tile_bytes_d);
+        const __amdgpu_buffer_rsrc_t rdk = make_rsrc((char*)p.dk + tile_d, tile_bytes_d);
+        const __amdgpu_buffer_rsrc_t rdv = make_rsrc((char*)p.dv + tile_d, tile_bytes_d);
         __amdgpu_buffer_rsrc_t rm = make_rsrc(nullptr, 0);
         if (BM && p.mask) rm = make_rsrc(p.mask + (size_t)(w % p.nW) * L * L, (uint32_t)L * L * 4u);
 
@@ -147,7 +155,7 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, 2) bwd_bf16_kernel(BwdArg
 #pragma unroll
             for (int b = 0; b < NB; ++b) {
                 vrow[b] = as_bf16x8(__builtin_amdgcn_raw_buffer_load_b128(rv, off_row + 16 * b * row_bytes, 0, 0));
-                grow[b] = as_bf16x8(__builtin_amdgcn_raw_buffer_load_b128(rg, off_row + 16 * b * row_bytes, 0, 0));
+                grow[b] = as_bf16x8(__builtin_amdgcn_raw_buffer_load_b128(rg, off_row_g + 16 * b * row_g, 0, 0));
             }
         }
         // Column operands (contraction over the 16 rows of a block): lane (g, m) =
@@ -265,7 +273,7 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, 2) bwd_bf16_kernel(BwdArg
             out.y = pack_bf16(qe[1] * p.scale, qo[1] * p.scale);
             out.z = pack_bf16(qe[2] * p.scale, qo[2] * p.scale);
             out.w = pack_bf16(qe[3] * p.scale, qo[3] * p.scale);
-            __builtin_amdgcn_raw_buffer_store_b128(out, rdq, off_row + 16 * qb * row_bytes, 0, 0);
+            __builtin_amdgcn_raw_buffer_store_b128(out, rdq, off_row_d + 16 * qb * row_d, 0, 0);
         }
 #pragma unroll
         for (int jb = 0; jb < NB; ++jb) {
@@ -278,8 +286,8 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, 2) bwd_bf16_kernel(BwdArg
             ok.y = pack_bf16(ke[jb][1] * p.scale, ko[jb][1] * p.scale);
             ok.z = pack_bf16(ke[jb][2] * p.scale, ko[jb][2] * p.scale);
             ok.w = pack_bf16(ke[jb][3] * p.scale, ko[jb][3] * p.scale);
-            __builtin_amdgcn_raw_buffer_store_b128(ov, rdv, off_row + 16 * jb * row_bytes, 0, 0);
-            __builtin_amdgcn_raw_buffer_store_b128(ok, rdk, off_row + 16 * jb * row_bytes, 0, 0);
+            __builtin_amdgcn_raw_buffer_store_b128(ov, rdv, off_row_d + 16 * jb * row_d, 0, 0);
+            __builtin_amdgcn_raw_buffer_store_b128(ok, rdk, off_row_d + 16 * jb * row_d, 0, 0);
         }
     }
 

@@ -54,7 +54,8 @@ __global__ void __launch_bounds__(64 * kCoopWavesPerTile * kCoopMaxHeads) bwd_bf
     const uint32_t hpb = gm.heads_per_block;
     const uint32_t h = hg * hpb + hl;
     const int L = p.L;
-    const uint32_t row_bytes = (uint32_t)p.C * 2u;
+    // token rows are p.ldq (q, k, v), p.ldg (d_o), p.ldd (dq, dk, dv) elements apart; window w starts at row w L
+    const uint32_t row_bytes = (uint32_t)p.ldq * 2u, row_g = (uint32_t)p.ldg * 2u, row_d = (uint32_t)p.ldd * 2u;
     const uint32_t stride = 4u * hpb + 1u;  // slab row stride in 16-byte units
     const float sl2 = p.scale * kLog2e;
     const bool active = role < NB;
@@ -99,16 +100,19 @@ __global__ void __launch_bounds__(64 * kCoopWavesPerTile * kCoopMaxHeads) bwd_bf
     const uint32_t rip = fastdiv((uint32_t)tid, gm.lanes_per_row);
     const uint32_t col = (uint32_t)tid - rip * gm.lanes_per_row.d;
     const uint32_t slab_bytes = (uint32_t)(L - 1) * row_bytes + hpb * 2u * kHeadDim;
+    const uint32_t slab_bytes_g = (uint32_t)(L - 1) * row_g + hpb * 2u * kHeadDim;
     const uint32_t goff = rip * row_bytes + col * 16u;
+    const uint32_t goff_g = rip * row_g + col * 16u;
     const uint32_t loff = rip * stride + col;
     u32x4 pk, pv, pq, pg;
     auto request = [&](uint32_t w) {
-        const size_t slab = ((size_t)w * L * p.C + (size_t)hg * hpb * kHeadDim) * 2u;
+        const size_t slab = ((size_t)w * L * p.ldq + (size_t)hg * hpb * kHeadDim) * 2u;
+        const size_t slab_g = ((size_t)w * L * p.ldg + (size_t)hg * hpb * kHeadDim) * 2u;
         // rows beyond L lie outside the descriptors and arrive as zeros
         pk = __builtin_amdgcn_raw_buffer_load_b128(make_rsrc((const char*)p.k + slab, slab_bytes), goff, 0, 0);
         pv = __builtin_amdgcn_raw_buffer_load_b128(make_rsrc((const char*)p.v + slab, slab_bytes), goff, 0, 0);
         pq = __builtin_amdgcn_raw_buffer_load_b128(make_rsrc((const char*)p.q + slab, slab_bytes), goff, 0, 0);
-        pg = __builtin_amdgcn_raw_buffer_load_b128(make_rsrc((const char*)p.d_o + slab, slab_bytes), goff, 0, 0);
+        pg = __builtin_amdgcn_raw_buffer_load_b128(make_rsrc((const char*)p.d_o + slab_g, slab_bytes_g), goff_g, 0, 0);
     };
     auto park = [&]() {
         if (rip < (uint32_t)ROWS) {
@@ -123,8 +127,8 @@ __global__ void __launch_bounds__(64 * kCoopWavesPerTile * kCoopMaxHeads) bwd_bf
         park();
     }
 
-    const uint32_t tile_bytes = (uint32_t)(L - 1) * row_bytes + 2u * kHeadDim;
-    const uint32_t off_half = (uint32_t)n * row_bytes + 8u * g;  // channels 4g..4g+3 of row n (+32 B: 16+4g..)
+    const uint32_t tile_bytes = (uint32_t)(L - 1) * row_d + 2u * kHeadDim;  // of an output tile
+    const uint32_t off_half = (uint32_t)n * row_d + 8u * g;  // channels 4g..4g+3 of row n (+32 B: 16+4g..)
 
     // The next window's slabs are requested at the top of an iteration and parked in LDS at its
     // end, i.e. always with this iteration's output stores younger than them in the memory queue:
@@ -135,7 +139,7 @@ __global__ void __launch_bounds__(64 * kCoopWavesPerTile * kCoopMaxHeads) bwd_bf
         if (has_next) request(w + gm.G);  // in flight while this window is computed
         __syncthreads();
 
-        const size_t tile = ((size_t)w * L * p.C + (size_t)h * kHeadDim) * 2u;
+        const size_t tile = ((size_t)w * L * p.ldd + (size_t)h * kHeadDim) * 2u;
         // ---------------- phase A: query block `role` ----------------
         if (active) {
             const int qb = role;
@@ -231,8 +235,8 @@ __global__ void __launch_bounds__(64 * kCoopWavesPerTile * kCoopMaxHeads) bwd_bf
             const u32x2 lo2 = {pack_bf16(q0[0] * p.scale, q0[1] * p.scale), pack_bf16(q0[2] * p.scale, q0[3] * p.scale)};
             const u32x2 hi2 = {pack_bf16(q1[0] * p.scale, q1[1] * p.scale), pack_bf16(q1[2] * p.scale, q1[3] * p.scale)};
             const __amdgpu_buffer_rsrc_t rdq = make_rsrc((char*)p.dq + tile, tile_bytes);
-            __builtin_amdgcn_raw_buffer_store_b64(lo2, rdq, off_half + 16 * qb * row_bytes, 0, 0);
-            __builtin_amdgcn_raw_buffer_store_b64(hi2, rdq, off_half + 32 + 16 * qb * row_bytes, 0, 0);
+            __builtin_amdgcn_raw_buffer_store_b64(lo2, rdq, off_half + 16 * qb * row_d, 0, 0);
+            __builtin_amdgcn_raw_buffer_store_b64(hi2, rdq, off_half + 32 + 16 * qb * row_d, 0, 0);
         }
         __syncthreads();
         // ---------------- phase B: key block `role` ----------------
@@ -271,10 +275,10 @@ __global__ void __launch_bounds__(64 * kCoopWavesPerTile * kCoopMaxHeads) bwd_bf
             const u32x2 kb = {pack_bf16(k1[0] * p.scale, k1[1] * p.scale), pack_bf16(k1[2] * p.scale, k1[3] * p.scale)};
             const __amdgpu_buffer_rsrc_t rdv = make_rsrc((char*)p.dv + tile, tile_bytes);
             const __amdgpu_buffer_rsrc_t rdk = make_rsrc((char*)p.dk + tile, tile_bytes);
-            __builtin_amdgcn_raw_buffer_store_b64(va, rdv, off_half + 16 * jb * row_bytes, 0, 0);
-            __builtin_amdgcn_raw_buffer_store_b64(vb, rdv, off_half + 32 + 16 * jb * row_bytes, 0, 0);
-            __builtin_amdgcn_raw_buffer_store_b64(ka, rdk, off_half + 16 * jb * row_bytes, 0, 0);
-            __builtin_amdgcn_raw_buffer_store_b64(kb, rdk, off_half + 32 + 16 * jb * row_bytes, 0, 0);
+            __builtin_amdgcn_raw_buffer_store_b64(va, rdv, off_half + 16 * jb * row_d, 0, 0);
+            __builtin_amdgcn_raw_buffer_store_b64(vb, rdv, off_half + 32 + 16 * jb * row_d, 0, 0);
+            __builtin_amdgcn_raw_buffer_store_b64(ka, rdk, off_half + 16 * jb * row_d, 0, 0);
+            __builtin_amdgcn_raw_buffer_store_b64(kb, rdk, off_half + 32 + 16 * jb * row_d, 0, 0);
         }
         __syncthreads();  // slabs and exchange area are rewritten by the next window
         if (has_next) park();

@@ -65,7 +65,8 @@ __global__ void __launch_bounds__(64 * large_waves(NB)) bwd_bf16_large_kernel(Bw
     const uint32_t lb = xcd_logical_block(blockIdx.x, gm.xcd_q, gm.xcd_r);  // heads of a window: one XCD
     const uint32_t h = lb % gm.heads, bw = lb / gm.heads;
     const int L = p.L;
-    const uint32_t row_bytes = (uint32_t)p.C * 2u;
+    // token rows are p.ldq (q, k, v), p.ldg (d_o), p.ldd (dq, dk, dv) elements apart; window w starts at row w L
+    const uint32_t row_bytes = (uint32_t)p.ldq * 2u, row_g = (uint32_t)p.ldg * 2u, row_d = (uint32_t)p.ldd * 2u;
     const float sl2 = p.scale * kLog2e;
     const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
 
@@ -86,16 +87,20 @@ __global__ void __launch_bounds__(64 * large_waves(NB)) bwd_bf16_large_kernel(Bw
     const uint32_t tile_bytes = (uint32_t)(L - 1) * row_bytes + 2u * kHeadDim;
     const uint32_t trs = (4u * g + (n >> 2)) * SROW + 4u * (n & 3);  // transposing-read base inside a slab
     const uint32_t opd = (uint32_t)n * STRIDE + g;                   // row operand of block b: slab[opd + 16 b STRIDE]
-    const uint32_t off_half = (uint32_t)n * row_bytes + 8u * g;      // channels 4g..4g+3 of row n (+32 B: 16+4g..)
+    const uint32_t tile_bytes_g = (uint32_t)(L - 1) * row_g + 2u * kHeadDim;
+    const uint32_t tile_bytes_d = (uint32_t)(L - 1) * row_d + 2u * kHeadDim;
+    const uint32_t off_half = (uint32_t)n * row_d + 8u * g;          // channels 4g..4g+3 of output row n (+32 B: 16+4g..)
     typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
     for (uint32_t w = bw; w < (uint32_t)p.N; w += gm.G) {
-        const size_t tile = ((size_t)w * L * p.C + (size_t)h * kHeadDim) * 2u;
+        const size_t tile = ((size_t)w * L * p.ldq + (size_t)h * kHeadDim) * 2u;
+        const size_t tile_g = ((size_t)w * L * p.ldg + (size_t)h * kHeadDim) * 2u;
+        const size_t tile_d = ((size_t)w * L * p.ldd + (size_t)h * kHeadDim) * 2u;
         {
             const __amdgpu_buffer_rsrc_t rk = make_rsrc((const char*)p.k + tile, tile_bytes);
             const __amdgpu_buffer_rsrc_t rv = make_rsrc((const char*)p.v + tile, tile_bytes);
             const __amdgpu_buffer_rsrc_t rq = make_rsrc((const char*)p.q + tile, tile_bytes);
-            const __amdgpu_buffer_rsrc_t rg = make_rsrc((const char*)p.d_o + tile, tile_bytes);
+            const __amdgpu_buffer_rsrc_t rg = make_rsrc((const char*)p.d_o + tile_g, tile_bytes_g);
             u32x4 pk[PASSES], pv[PASSES], pq[PASSES], pg[PASSES];
 #pragma unroll
             for (int t = 0; t < PASSES; ++t) {
@@ -103,7 +108,7 @@ __global__ void __launch_bounds__(64 * large_waves(NB)) bwd_bf16_large_kernel(Bw
                 pk[t] = __builtin_amdgcn_raw_buffer_load_b128(rk, off, 0, 0);
                 pv[t] = __builtin_amdgcn_raw_buffer_load_b128(rv, off, 0, 0);
                 pq[t] = __builtin_amdgcn_raw_buffer_load_b128(rq, off, 0, 0);
-                pg[t] = __builtin_amdgcn_raw_buffer_load_b128(rg, off, 0, 0);
+                pg[t] = __builtin_amdgcn_raw_buffer_load_b128(rg, (16 * W * t + srow) * row_g + scol * 16u, 0, 0);
             }
 #pragma unroll
             for (int t = 0; t < PASSES; ++t) {
@@ -252,9 +257,9 @@ __global__ void __launch_bounds__(64 * large_waves(NB)) bwd_bf16_large_kernel(Bw
             }
             const u32x2 lo2 = {pack_bf16(q0[0] * p.scale, q0[1] * p.scale), pack_bf16(q0[2] * p.scale, q0[3] * p.scale)};
             const u32x2 hi2 = {pack_bf16(q1[0] * p.scale, q1[1] * p.scale), pack_bf16(q1[2] * p.scale, q1[3] * p.scale)};
-            const __amdgpu_buffer_rsrc_t rdq = make_rsrc((char*)p.dq + tile, tile_bytes);
-            __builtin_amdgcn_raw_buffer_store_b64(lo2, rdq, off_half + 16 * qb * row_bytes, 0, 0);
-            __builtin_amdgcn_raw_buffer_store_b64(hi2, rdq, off_half + 32 + 16 * qb * row_bytes, 0, 0);
+            const __amdgpu_buffer_rsrc_t rdq = make_rsrc((char*)p.dq + tile_d, tile_bytes_d);
+            __builtin_amdgcn_raw_buffer_store_b64(lo2, rdq, off_half + 16 * qb * row_d, 0, 0);
+            __builtin_amdgcn_raw_buffer_store_b64(hi2, rdq, off_half + 32 + 16 * qb * row_d, 0, 0);
         }
         __syncthreads();
 
@@ -361,12 +366,12 @@ __global__ void __launch_bounds__(64 * large_waves(NB)) bwd_bf16_large_kernel(Bw
             const u32x2 vb = {pack_bf16(v1[0], v1[1]), pack_bf16(v1[2], v1[3])};
             const u32x2 ka = {pack_bf16(k0[0] * p.scale, k0[1] * p.scale), pack_bf16(k0[2] * p.scale, k0[3] * p.scale)};
             const u32x2 kb = {pack_bf16(k1[0] * p.scale, k1[1] * p.scale), pack_bf16(k1[2] * p.scale, k1[3] * p.scale)};
-            const __amdgpu_buffer_rsrc_t rdv = make_rsrc((char*)p.dv + tile, tile_bytes);
-            const __amdgpu_buffer_rsrc_t rdk = make_rsrc((char*)p.dk + tile, tile_bytes);
-            __builtin_amdgcn_raw_buffer_store_b64(va, rdv, off_half + 16 * jb * row_bytes, 0, 0);
-            __builtin_amdgcn_raw_buffer_store_b64(vb, rdv, off_half + 32 + 16 * jb * row_bytes, 0, 0);
-            __builtin_amdgcn_raw_buffer_store_b64(ka, rdk, off_half + 16 * jb * row_bytes, 0, 0);
-            __builtin_amdgcn_raw_buffer_store_b64(kb, rdk, off_half + 32 + 16 * jb * row_bytes, 0, 0);
+            const __amdgpu_buffer_rsrc_t rdv = make_rsrc((char*)p.dv + tile_d, tile_bytes_d);
+            const __amdgpu_buffer_rsrc_t rdk = make_rsrc((char*)p.dk + tile_d, tile_bytes_d);
+            __builtin_amdgcn_raw_buffer_store_b64(va, rdv, off_half + 16 * jb * row_d, 0, 0);
+            __builtin_amdgcn_raw_buffer_store_b64(vb, rdv, off_half + 32 + 16 * jb * row_d, 0, 0);
+            __builtin_amdgcn_raw_buffer_store_b64(ka, rdk, off_half + 16 * jb * row_d, 0, 0);
+            __builtin_amdgcn_raw_buffer_store_b64(kb, rdk, off_half + 32 + 16 * jb * row_d, 0, 0);
         }
         __syncthreads();  // the slabs are rewritten for the next window
     }

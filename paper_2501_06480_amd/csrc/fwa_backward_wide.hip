@@ -44,9 +44,14 @@ __global__ void __launch_bounds__(256) bwd_bf16_wide_kernel(BwdArgs p) {
     const bool active = role < NB;
     const uint32_t w = blockIdx.x / (uint32_t)p.heads, h = blockIdx.x % (uint32_t)p.heads;
     const int L = p.L;
-    const uint32_t row_bytes = (uint32_t)p.C * 2u;
-    const size_t tile = ((size_t)w * L * p.C + (size_t)h * D) * 2u;
+    // token rows are p.ldq (q, k, v), p.ldg (d_o), p.ldd (dq, dk, dv) elements apart; window w starts at row w L
+    const uint32_t row_bytes = (uint32_t)p.ldq * 2u, row_g = (uint32_t)p.ldg * 2u, row_d = (uint32_t)p.ldd * 2u;
+    const size_t tile = ((size_t)w * L * p.ldq + (size_t)h * D) * 2u;
+    const size_t tile_g = ((size_t)w * L * p.ldg + (size_t)h * D) * 2u;
+    const size_t tile_d = ((size_t)w * L * p.ldd + (size_t)h * D) * 2u;
     const uint32_t tile_bytes = (uint32_t)(L - 1) * row_bytes + 2u * D;  // rows beyond L read as zero
+    const uint32_t tile_bytes_g = (uint32_t)(L - 1) * row_g + 2u * D;
+    const uint32_t tile_bytes_d = (uint32_t)(L - 1) * row_d + 2u * D;
     const float sl2 = p.scale * kLog2e;
     const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
     typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
@@ -59,17 +64,18 @@ __global__ void __launch_bounds__(256) bwd_bf16_wide_kernel(BwdArgs p) {
     uint16_t* const ex = reinterpret_cast<uint16_t*>(lds + 2 * ROWS * STRIDE);
 
     const __amdgpu_buffer_rsrc_t rq = make_rsrc((const char*)p.q + tile, tile_bytes);
-    const __amdgpu_buffer_rsrc_t rg = make_rsrc((const char*)p.d_o + tile, tile_bytes);
+    const __amdgpu_buffer_rsrc_t rg = make_rsrc((const char*)p.d_o + tile_g, tile_bytes_g);
     const uint32_t srow = (uint32_t)tid / TPR, scol = (uint32_t)tid % TPR;  // slab movement: (row, 16 B column)
 
     // own Q and dO rows as operands: lane (g, n) takes channels 32 c + 8g .. + 7 of row 16 role + n
     bf16x8 qop[CH], gop[CH];
     {
         const uint32_t off = (uint32_t)(16 * role + n) * row_bytes + 16u * g;
+        const uint32_t off_g = (uint32_t)(16 * role + n) * row_g + 16u * g;
 #pragma unroll
         for (int c = 0; c < CH; ++c) {
             qop[c] = as_bf16x8(__builtin_amdgcn_raw_buffer_load_b128(rq, off + 64 * c, 0, 0));
-            gop[c] = as_bf16x8(__builtin_amdgcn_raw_buffer_load_b128(rg, off + 64 * c, 0, 0));
+            gop[c] = as_bf16x8(__builtin_amdgcn_raw_buffer_load_b128(rg, off_g + 64 * c, 0, 0));
         }
     }
     {
@@ -95,15 +101,14 @@ __global__ void __launch_bounds__(256) bwd_bf16_wide_kernel(BwdArgs p) {
     u32x4 sq[PASSES], sg[PASSES];
 #pragma unroll
     for (int t = 0; t < PASSES; ++t) {
-        const uint32_t off = (RPP * t + srow) * row_bytes + scol * 16u;
-        sq[t] = __builtin_amdgcn_raw_buffer_load_b128(rq, off, 0, 0);
-        sg[t] = __builtin_amdgcn_raw_buffer_load_b128(rg, off, 0, 0);
+        sq[t] = __builtin_amdgcn_raw_buffer_load_b128(rq, (RPP * t + srow) * row_bytes + scol * 16u, 0, 0);
+        sg[t] = __builtin_amdgcn_raw_buffer_load_b128(rg, (RPP * t + srow) * row_g + scol * 16u, 0, 0);
     }
     __syncthreads();
 
     const uint32_t opd = (uint32_t)n * STRIDE + g;                   // row operand: slab[opd + 16 b STRIDE + 4 c]
     const uint32_t trs = (4u * g + (n >> 2)) * SROW + 4u * (n & 3);  // transposing-read base inside a slab
-    const uint32_t off_half = (uint32_t)n * row_bytes + 8u * g;      // channels 4g..4g+3 of row n
+    const uint32_t off_half = (uint32_t)n * row_d + 8u * g;          // channels 4g..4g+3 of output row n
 
     // ---------------- phase A: query block `role` ----------------
     if (active) {
@@ -194,7 +199,7 @@ __global__ void __launch_bounds__(256) bwd_bf16_wide_kernel(BwdArgs p) {
         }
         // dQ^T = K^T dS^T, 16 channels at a time: acc[r] = dQ[16 qb + n][16 cb + 4g + r]
         const uint16_t* lk16 = reinterpret_cast<const uint16_t*>(sa) + trs;
-        const __amdgpu_buffer_rsrc_t rdq = make_rsrc((char*)p.dq + tile, tile_bytes);
+        const __amdgpu_buffer_rsrc_t rdq = make_rsrc((char*)p.dq + tile_d, tile_bytes_d);
 #pragma unroll
         for (int cb = 0; cb < CB; ++cb) {
             f32x4 acc = zero;
@@ -205,7 +210,7 @@ __global__ void __launch_bounds__(256) bwd_bf16_wide_kernel(BwdArgs p) {
                 acc = mfma_bf16(kt, dl[kp], acc);
             }
             const u32x2 v = {pack_bf16(acc[0] * p.scale, acc[1] * p.scale), pack_bf16(acc[2] * p.scale, acc[3] * p.scale)};
-            __builtin_amdgcn_raw_buffer_store_b64(v, rdq, off_half + 16 * qb * row_bytes + 32 * cb, 0, 0);
+            __builtin_amdgcn_raw_buffer_store_b64(v, rdq, off_half + 16 * qb * row_d + 32 * cb, 0, 0);
         }
     }
     __syncthreads();  // K, V no longer needed; tiles complete
@@ -236,8 +241,8 @@ __global__ void __launch_bounds__(256) bwd_bf16_wide_kernel(BwdArgs p) {
         }
         const uint16_t* lq16 = reinterpret_cast<const uint16_t*>(sa) + trs;
         const uint16_t* lg16 = reinterpret_cast<const uint16_t*>(sb) + trs;
-        const __amdgpu_buffer_rsrc_t rdv = make_rsrc((char*)p.dv + tile, tile_bytes);
-        const __amdgpu_buffer_rsrc_t rdk = make_rsrc((char*)p.dk + tile, tile_bytes);
+        const __amdgpu_buffer_rsrc_t rdv = make_rsrc((char*)p.dv + tile_d, tile_bytes_d);
+        const __amdgpu_buffer_rsrc_t rdk = make_rsrc((char*)p.dk + tile_d, tile_bytes_d);
 #pragma unroll
         for (int cb = 0; cb < CB; ++cb) {
             f32x4 av = zero, ak = zero;  // dV, dK [16 jb + n][16 cb + 4g + r]
@@ -253,8 +258,8 @@ __global__ void __launch_bounds__(256) bwd_bf16_wide_kernel(BwdArgs p) {
             }
             const u32x2 vv = {pack_bf16(av[0], av[1]), pack_bf16(av[2], av[3])};
             const u32x2 vk = {pack_bf16(ak[0] * p.scale, ak[1] * p.scale), pack_bf16(ak[2] * p.scale, ak[3] * p.scale)};
-            __builtin_amdgcn_raw_buffer_store_b64(vv, rdv, off_half + 16 * jb * row_bytes + 32 * cb, 0, 0);
-            __builtin_amdgcn_raw_buffer_store_b64(vk, rdk, off_half + 16 * jb * row_bytes + 32 * cb, 0, 0);
+            __builtin_amdgcn_raw_buffer_store_b64(vv, rdv, off_half + 16 * jb * row_d + 32 * cb, 0, 0);
+            __builtin_amdgcn_raw_buffer_store_b64(vk, rdk, off_half + 16 * jb * row_d + 32 * cb, 0, 0);
         }
     }
 }

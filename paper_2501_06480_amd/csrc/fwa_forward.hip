@@ -77,13 +77,15 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) fwd_bf16_kernel(FwdArgs p
     const TileCoord tc = tile_of_wave(gm, p.heads);
     if (!tc.valid) return;  // wave-uniform; the kernel has no barriers
     const int L = p.L;
-    const uint32_t row_bytes = (uint32_t)p.C * 2u;
+    // token rows are p.ldq (q, k, v) resp. p.ldo (o) elements apart; window w starts at row w L
+    const uint32_t row_bytes = (uint32_t)p.ldq * 2u, row_out = (uint32_t)p.ldo * 2u;
     const uint32_t tile_bytes = (uint32_t)(L - 1) * row_bytes + 2u * kHeadDim;
-    const size_t tile = ((size_t)tc.w * L * p.C + (size_t)tc.h * kHeadDim) * 2u;
+    const size_t tile = ((size_t)tc.w * L * p.ldq + (size_t)tc.h * kHeadDim) * 2u;
     const __amdgpu_buffer_rsrc_t rq = make_rsrc((const char*)p.q + tile, tile_bytes);
     const __amdgpu_buffer_rsrc_t rk = make_rsrc((const char*)p.k + tile, tile_bytes);
     const __amdgpu_buffer_rsrc_t rv = make_rsrc((const char*)p.v + tile, tile_bytes);
-    const __amdgpu_buffer_rsrc_t ro = make_rsrc((char*)p.o + tile, tile_bytes);
+    const __amdgpu_buffer_rsrc_t ro = make_rsrc((char*)p.o + ((size_t)tc.w * L * p.ldo + (size_t)tc.h * kHeadDim) * 2u,
+                                                (uint32_t)(L - 1) * row_out + 2u * kHeadDim);
     const uint32_t off_row = (uint32_t)n * row_bytes + 16u * g;  // 16 B of row n (plus a block offset)
 
     // K: A operands of S^T, lane (g, n) = K[16 jb + n][8g .. 8g+7]
@@ -155,7 +157,7 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) fwd_bf16_kernel(FwdArgs p
         out.y = pack_bf16(oe[1] * inv, oo[1] * inv);
         out.z = pack_bf16(oe[2] * inv, oo[2] * inv);
         out.w = pack_bf16(oe[3] * inv, oo[3] * inv);
-        __builtin_amdgcn_raw_buffer_store_b128(out, ro, off_row + 16 * qb * row_bytes, 0, 0);
+        __builtin_amdgcn_raw_buffer_store_b128(out, ro, (uint32_t)(16 * qb + n) * row_out + 16u * g, 0, 0);
     }
 }
 
@@ -172,13 +174,14 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) fwd_f32_kernel(FwdArgs p,
     const TileCoord tc = tile_of_wave(gm, p.heads);
     if (!tc.valid) return;
     const int L = p.L;
-    const uint32_t row_bytes = (uint32_t)p.C * 4u;
+    const uint32_t row_bytes = (uint32_t)p.ldq * 4u, row_out = (uint32_t)p.ldo * 4u;
     const uint32_t tile_bytes = (uint32_t)(L - 1) * row_bytes + 4u * kHeadDim;
-    const size_t tile = ((size_t)tc.w * L * p.C + (size_t)tc.h * kHeadDim) * 4u;
+    const size_t tile = ((size_t)tc.w * L * p.ldq + (size_t)tc.h * kHeadDim) * 4u;
     const __amdgpu_buffer_rsrc_t rq = make_rsrc((const char*)p.q + tile, tile_bytes);
     const __amdgpu_buffer_rsrc_t rk = make_rsrc((const char*)p.k + tile, tile_bytes);
     const __amdgpu_buffer_rsrc_t rv = make_rsrc((const char*)p.v + tile, tile_bytes);
-    const __amdgpu_buffer_rsrc_t ro = make_rsrc((char*)p.o + tile, tile_bytes);
+    const __amdgpu_buffer_rsrc_t ro = make_rsrc((char*)p.o + ((size_t)tc.w * L * p.ldo + (size_t)tc.h * kHeadDim) * 4u,
+                                                (uint32_t)(L - 1) * row_out + 4u * kHeadDim);
     const uint32_t off_row = (uint32_t)n * row_bytes + 32u * g;  // channels 8g..8g+7 of row n
     const uint32_t off_v = 4u * g * row_bytes + 4u * n;          // channel n of row 4g
 
@@ -258,9 +261,9 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) fwd_f32_kernel(FwdArgs p,
                 o0 = mfma_f32(v0, s[jb][r], o0);  // o0[r'] = O[16 qb + n][4g + r']
                 o1 = mfma_f32(v1, s[jb][r], o1);  // o1[r'] = O[16 qb + n][16 + 4g + r']
             }
-        const uint32_t off_o = (uint32_t)n * row_bytes + 16u * g;
-        store_f32x4(o0 / sum, ro, off_o + 16 * qb * row_bytes);
-        store_f32x4(o1 / sum, ro, off_o + 64 + 16 * qb * row_bytes);
+        const uint32_t off_o = (uint32_t)(16 * qb + n) * row_out + 16u * g;
+        store_f32x4(o0 / sum, ro, off_o);
+        store_f32x4(o1 / sum, ro, off_o + 64);
     }
 }
 

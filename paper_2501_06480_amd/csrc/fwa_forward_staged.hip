@@ -40,19 +40,22 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) fwd_bf16_staged_kernel(Fw
     const uint32_t hpb = gm.heads_per_block;
     const uint32_t h = hg * hpb + hl;
     const int L = p.L;
-    const uint32_t row_bytes = (uint32_t)p.C * 2u;
+    // token rows are p.ldq (q, k, v) resp. p.ldo (o) elements apart; window w starts at row w L
+    const uint32_t row_bytes = (uint32_t)p.ldq * 2u, row_out = (uint32_t)p.ldo * 2u;
     const uint32_t stride = 4u * hpb + 1u;  // LDS row stride in 16-byte units (one unit of padding)
 
     // ---- stage the slab: thread -> (row of a 16-row pass, 16-byte column)
     const uint32_t rip = fastdiv((uint32_t)tid, gm.lanes_per_row);
     const uint32_t col = (uint32_t)tid - rip * gm.lanes_per_row.d;
-    const size_t slab = ((size_t)w * L * p.C + (size_t)hg * hpb * kHeadDim) * 2u;
+    const size_t slab = ((size_t)w * L * p.ldq + (size_t)hg * hpb * kHeadDim) * 2u;
     const uint32_t slab_bytes = (uint32_t)(L - 1) * row_bytes + hpb * 2u * kHeadDim;
     const __amdgpu_buffer_rsrc_t rq = make_rsrc((const char*)p.q + slab, slab_bytes);
     const __amdgpu_buffer_rsrc_t rk = make_rsrc((const char*)p.k + slab, slab_bytes);
     const __amdgpu_buffer_rsrc_t rv = make_rsrc((const char*)p.v + slab, slab_bytes);
-    const __amdgpu_buffer_rsrc_t ro = make_rsrc((char*)p.o + slab, slab_bytes);
+    const __amdgpu_buffer_rsrc_t ro = make_rsrc((char*)p.o + ((size_t)w * L * p.ldo + (size_t)hg * hpb * kHeadDim) * 2u,
+                                                (uint32_t)(L - 1) * row_out + hpb * 2u * kHeadDim);
     const uint32_t goff = rip * row_bytes + col * 16u;  // plus 16 t rows
+    const uint32_t goff_o = rip * row_out + col * 16u;
     const uint32_t loff = rip * stride + col;           // plus 16 t rows, in uint4 units
     u32x4 sk[NB], sv[NB], sq[NB];
 #pragma unroll
@@ -142,7 +145,7 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) fwd_bf16_staged_kernel(Fw
 #pragma unroll
     for (int t = 0; t < NB; ++t) {
         const u32x4 v = __builtin_bit_cast(u32x4, lq[loff + 16 * t * stride]);
-        __builtin_amdgcn_raw_buffer_store_b128(v, ro, goff + 16 * t * row_bytes, 0, 0);
+        __builtin_amdgcn_raw_buffer_store_b128(v, ro, goff_o + 16 * t * row_out, 0, 0);
     }
 }
 
@@ -169,7 +172,7 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) fwd_bf16_persistent_kerne
     const uint32_t hpb = gm.heads_per_block;
     const uint32_t h = hg * hpb + hl;
     const int L = p.L;
-    const uint32_t row_bytes = (uint32_t)p.C * 2u;
+    const uint32_t row_bytes = (uint32_t)p.ldq * 2u, row_out = (uint32_t)p.ldo * 2u;
     const uint32_t stride = 4u * hpb + 1u;
     const float sl2 = p.scale * kLog2e;
 
@@ -193,6 +196,7 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) fwd_bf16_persistent_kerne
     const uint32_t col = (uint32_t)tid - rip * gm.lanes_per_row.d;
     const uint32_t slab_bytes = (uint32_t)(L - 1) * row_bytes + hpb * 2u * kHeadDim;
     const uint32_t goff = rip * row_bytes + col * 16u;
+    const uint32_t goff_o = rip * row_out + col * 16u;
     const uint32_t loff = rip * stride + col;
     uint4* const lk = lds;
     uint4* const lv = lds + ROWS * stride;
@@ -202,7 +206,7 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) fwd_bf16_persistent_kerne
 
     u32x4 sk[NB], sv[NB], sq[NB];
     auto request = [&](uint32_t w) {
-        const size_t slab = ((size_t)w * L * p.C + (size_t)hg * hpb * kHeadDim) * 2u;
+        const size_t slab = ((size_t)w * L * p.ldq + (size_t)hg * hpb * kHeadDim) * 2u;
         const __amdgpu_buffer_rsrc_t rq = make_rsrc((const char*)p.q + slab, slab_bytes);
         const __amdgpu_buffer_rsrc_t rk = make_rsrc((const char*)p.k + slab, slab_bytes);
         const __amdgpu_buffer_rsrc_t rv = make_rsrc((const char*)p.v + slab, slab_bytes);
@@ -279,12 +283,12 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) fwd_bf16_persistent_kerne
         }
         __syncthreads();
         {
-            const size_t slab = ((size_t)w * L * p.C + (size_t)hg * hpb * kHeadDim) * 2u;
-            const __amdgpu_buffer_rsrc_t ro = make_rsrc((char*)p.o + slab, slab_bytes);
+            const size_t slab = ((size_t)w * L * p.ldo + (size_t)hg * hpb * kHeadDim) * 2u;
+            const __amdgpu_buffer_rsrc_t ro = make_rsrc((char*)p.o + slab, (uint32_t)(L - 1) * row_out + hpb * 2u * kHeadDim);
 #pragma unroll
             for (int t = 0; t < NB; ++t) {
                 const u32x4 v = __builtin_bit_cast(u32x4, lq[loff + 16 * t * stride]);
-                __builtin_amdgcn_raw_buffer_store_b128(v, ro, goff + 16 * t * row_bytes, 0, 0);
+                __builtin_amdgcn_raw_buffer_store_b128(v, ro, goff_o + 16 * t * row_out, 0, 0);
             }
         }
         __syncthreads();  // every wave has copied its output rows out of the Q tile
@@ -322,7 +326,7 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) fwd_bf16_rowblock_kernel(
     const uint32_t hpb = gm.heads_per_block;
     const uint32_t h = hg * hpb + hl;
     const int L = p.L;
-    const uint32_t row_bytes = (uint32_t)p.C * 2u;
+    const uint32_t row_bytes = (uint32_t)p.ldq * 2u, row_out = (uint32_t)p.ldo * 2u;
     const uint32_t stride = 4u * hpb + 1u;  // LDS row stride in 16-byte units
 
     uint4* const lk = lds;
@@ -330,7 +334,7 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) fwd_bf16_rowblock_kernel(
     {
         const uint32_t rip = fastdiv((uint32_t)tid, gm.lanes_per_row);  // 0..31
         const uint32_t col = (uint32_t)tid - rip * gm.lanes_per_row.d;
-        const size_t slab = ((size_t)w * L * p.C + (size_t)hg * hpb * kHeadDim) * 2u;
+        const size_t slab = ((size_t)w * L * p.ldq + (size_t)hg * hpb * kHeadDim) * 2u;
         const uint32_t slab_bytes = (uint32_t)(L - 1) * row_bytes + hpb * 2u * kHeadDim;
         const __amdgpu_buffer_rsrc_t rk = make_rsrc((const char*)p.k + slab, slab_bytes);
         const __amdgpu_buffer_rsrc_t rv = make_rsrc((const char*)p.v + slab, slab_bytes);
@@ -353,9 +357,10 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) fwd_bf16_rowblock_kernel(
     __syncthreads();
 
     const uint32_t tile_bytes = (uint32_t)(L - 1) * row_bytes + 2u * kHeadDim;
-    const size_t tile = ((size_t)w * L * p.C + (size_t)h * kHeadDim) * 2u;
+    const size_t tile = ((size_t)w * L * p.ldq + (size_t)h * kHeadDim) * 2u;
     const __amdgpu_buffer_rsrc_t rq = make_rsrc((const char*)p.q + tile, tile_bytes);
-    const __amdgpu_buffer_rsrc_t ro = make_rsrc((char*)p.o + tile, tile_bytes);
+    const __amdgpu_buffer_rsrc_t ro = make_rsrc((char*)p.o + ((size_t)w * L * p.ldo + (size_t)h * kHeadDim) * 2u,
+                                                (uint32_t)(L - 1) * row_out + 2u * kHeadDim);
     const uint32_t off_row = (uint32_t)n * row_bytes + 16u * g;
     const float sl2 = p.scale * kLog2e;
     __amdgpu_buffer_rsrc_t rb = make_rsrc(nullptr, 0), rm = make_rsrc(nullptr, 0);
@@ -404,7 +409,7 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) fwd_bf16_rowblock_kernel(
         lo.y = pack_bf16(o0[2] * inv, o0[3] * inv);
         hi.x = pack_bf16(o1[0] * inv, o1[1] * inv);
         hi.y = pack_bf16(o1[2] * inv, o1[3] * inv);
-        const uint32_t off_o = (uint32_t)(16 * qb + n) * row_bytes + 8u * g;
+        const uint32_t off_o = (uint32_t)(16 * qb + n) * row_out + 8u * g;
         __builtin_amdgcn_raw_buffer_store_b64(lo, ro, off_o, 0, 0);
         __builtin_amdgcn_raw_buffer_store_b64(hi, ro, off_o + 32, 0, 0);
     }
@@ -446,7 +451,7 @@ __global__ void __launch_bounds__(64 * rowpersist_waves(NB)) fwd_bf16_rowpersist
     const int qb = (int)(part * W + wave);
     const bool active = qb < NB;
     const int L = p.L;
-    const uint32_t row_bytes = (uint32_t)p.C * 2u;
+    const uint32_t row_bytes = (uint32_t)p.ldq * 2u, row_out = (uint32_t)p.ldo * 2u;
     const float sl2 = p.scale * kLog2e;
 
     f32x4 add[NB];
@@ -467,7 +472,7 @@ __global__ void __launch_bounds__(64 * rowpersist_waves(NB)) fwd_bf16_rowpersist
     const uint32_t off_row = (uint32_t)(16 * qb + n) * row_bytes + 16u * g;
     u32x4 pk[PASSES], pv[PASSES], qnext = {0u, 0u, 0u, 0u};
     auto request = [&](uint32_t w) {
-        const size_t tile = ((size_t)w * L * p.C + (size_t)h * kHeadDim) * 2u;
+        const size_t tile = ((size_t)w * L * p.ldq + (size_t)h * kHeadDim) * 2u;
         const __amdgpu_buffer_rsrc_t rk = make_rsrc((const char*)p.k + tile, tile_bytes);
         const __amdgpu_buffer_rsrc_t rv = make_rsrc((const char*)p.v + tile, tile_bytes);
 #pragma unroll
@@ -546,9 +551,9 @@ __global__ void __launch_bounds__(64 * rowpersist_waves(NB)) fwd_bf16_rowpersist
         lo.y = pack_bf16(o0[2] * inv, o0[3] * inv);
         hi.x = pack_bf16(o1[0] * inv, o1[1] * inv);
         hi.y = pack_bf16(o1[2] * inv, o1[3] * inv);
-        const size_t tile = ((size_t)w * L * p.C + (size_t)h * kHeadDim) * 2u;
-        const __amdgpu_buffer_rsrc_t ro = make_rsrc((char*)p.o + tile, tile_bytes);
-        const uint32_t off_o = (uint32_t)(16 * qb + n) * row_bytes + 8u * g;
+        const size_t tile = ((size_t)w * L * p.ldo + (size_t)h * kHeadDim) * 2u;
+        const __amdgpu_buffer_rsrc_t ro = make_rsrc((char*)p.o + tile, (uint32_t)(L - 1) * row_out + 2u * kHeadDim);
+        const uint32_t off_o = (uint32_t)(16 * qb + n) * row_out + 8u * g;
         __builtin_amdgcn_raw_buffer_store_b64(lo, ro, off_o, 0, 0);
         __builtin_amdgcn_raw_buffer_store_b64(hi, ro, off_o + 32, 0, 0);
         if (has_next) park(buf ^ 1u);

@@ -34,8 +34,8 @@ __global__ void __launch_bounds__(256) fwd_bf16_wide_kernel(FwdArgs p) {
     const int qb = __builtin_amdgcn_readfirstlane(tid >> 6);
     const uint32_t w = blockIdx.x / (uint32_t)p.heads, h = blockIdx.x % (uint32_t)p.heads;
     const int L = p.L;
-    const uint32_t row_bytes = (uint32_t)p.C * 2u;
-    const size_t tile = ((size_t)w * L * p.C + (size_t)h * D) * 2u;
+    const uint32_t row_bytes = (uint32_t)p.ldq * 2u, row_out = (uint32_t)p.ldo * 2u;  // token rows: ldq / ldo elements apart
+    const size_t tile = ((size_t)w * L * p.ldq + (size_t)h * D) * 2u;
     const uint32_t tile_bytes = (uint32_t)(L - 1) * row_bytes + 2u * D;  // rows beyond L read as zero
     uint4* const lk = lds;
     uint4* const lv = lds + ROWS * STRIDE;
@@ -100,8 +100,9 @@ __global__ void __launch_bounds__(256) fwd_bf16_wide_kernel(FwdArgs p) {
 
     // O^T = V^T P^T, 16 channels at a time: o[r] = O[16 qb + n][16 cb + 4g + r]
     const uint16_t* const lvh = reinterpret_cast<const uint16_t*>(lv) + (4 * g + (n >> 2)) * SROW + 4 * (n & 3);
-    const __amdgpu_buffer_rsrc_t ro = make_rsrc((char*)p.o + tile, tile_bytes);
-    const uint32_t off_o = (uint32_t)(16 * qb + n) * row_bytes + 8u * g;
+    const __amdgpu_buffer_rsrc_t ro = make_rsrc((char*)p.o + ((size_t)w * L * p.ldo + (size_t)h * D) * 2u,
+                                                (uint32_t)(L - 1) * row_out + 2u * D);
+    const uint32_t off_o = (uint32_t)(16 * qb + n) * row_out + 8u * g;
     typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 #pragma unroll
     for (int cb = 0; cb < CB; ++cb) {

@@ -27,6 +27,8 @@ struct FwdArgs {
     int heads;
     int nW;
     float scale;
+    int ldq;             // elements between consecutive token rows of q, k, v (C when contiguous)
+    int ldo;             // the same for o
 };
 
 struct BwdArgs {
@@ -48,6 +50,9 @@ struct BwdArgs {
     int nW;
     float scale;
     int slots;           // number of partial-sum slots per head in `partial`
+    int ldq;             // elements between consecutive token rows of q, k, v (C when contiguous)
+    int ldg;             // the same for d_o
+    int ldd;             // the same for dq, dk, dv
 };
 
 // Each returns a hipError_t from the launch (hipSuccess when enqueued).
