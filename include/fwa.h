@@ -21,8 +21,7 @@
  *    [N, L, C]; head h owns channels [h*d, (h+1)*d) with d = C / heads.
  *    Supported: d == 32 with 1 <= L <= 256; with FWA_BF16 also d == 64, 128,
  *    256 with 1 <= L <= 64 (the feature-dimension loop of paper eq. 5-6; the
- *    shapes of its Section 3.1 benchmark), except dbias.  N >= 0 (N == 0 is
- *    a no-op).
+ *    shapes of its Section 3.1 benchmark).  N >= 0 (N == 0 is a no-op).
  *  - dtype is FWA_F32 (fp32 data, fp32 arithmetic) or FWA_BF16 (bf16 data,
  *    bf16 matrix-core products with fp32 accumulation, fp32 softmax, one final
  *    round-to-nearest-even to bf16).
@@ -85,8 +84,8 @@ int fwa_forward_strided(const void* q, const void* k, const void* v, void* o,
 /*
  * Backward pass (paper Algorithm 2).  Inputs are Q, K, V and dO only.
  * Supported: dtype FWA_BF16, any L <= 256 for dQ, dK, dV; dbias only for
- * d == 32 and L <= 64 (its accumulator stays on chip across windows).  fp32
- * data, and dbias with L > 64 or d > 32, return FWA_ERR_UNSUPPORTED.
+ * L <= 64 (its accumulator stays on chip across windows).  fp32 data, and
+ * dbias with L > 64, return FWA_ERR_UNSUPPORTED.
  *   d_o        : in,  [N, L, C], dtype
  *   dq, dk, dv : out, [N, L, C], dtype, fully overwritten
  *   dbias      : NULL, or out [heads, L, L] fp32 = sum over all N windows of

@@ -17,7 +17,7 @@ def _check_dbias_supported(q, heads, bias):
     if bias is not None and bias.requires_grad:
         N, L, C = q.shape
         if binding.fwa_backward_workspace_bytes(max(N, 1), L, C, heads, binding.FWA_BF16, True) == 0 and N > 0:
-            raise NotImplementedError("the gradient of the bias exists for head width 32 and L <= 64 only")
+            raise NotImplementedError("the gradient of the bias exists for L <= 64 only")
 
 
 class _WindowAttention(torch.autograd.Function):

@@ -8,8 +8,8 @@ namespace {
 inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
 
 // Shape checks shared by forward, backward and the workspace query.
-// Head width 32 everywhere; the bf16 forward, and the bf16 backward without dBias, also take 64,
-// 128 and 256 for L <= 64 (`wide_ok` = the call is one of those).
+// Head width 32 everywhere; the bf16 forward and backward also take 64, 128 and 256 for
+// L <= 64 (`wide_ok` = the call is one of those).
 int check_shape(int64_t N, int L, int C, int heads, int dtype, bool wide_ok) {
     if (N < 0 || L < 1 || C < 1 || heads < 1) return FWA_ERR_SHAPE;
     if (C % heads != 0) return FWA_ERR_SHAPE;
@@ -23,7 +23,8 @@ int check_shape(int64_t N, int L, int C, int heads, int dtype, bool wide_ok) {
     return FWA_OK;
 }
 
-// The backward covers bf16 data; dBias only for windows whose score tile stays on chip (L <= 64).
+// The backward covers bf16 data; dBias only for windows whose score tile stays on chip (L <= 64:
+// every wide-head shape qualifies).
 int check_backward_support(int L, int dtype, bool want_dbias) {
     if (dtype != FWA_BF16) return FWA_ERR_UNSUPPORTED;
     if (want_dbias && L > fwa::kMaxBackwardL) return FWA_ERR_UNSUPPORTED;
@@ -98,7 +99,7 @@ int fwa_forward(const void* q, const void* k, const void* v, void* o, int64_t N,
 }
 
 size_t fwa_backward_workspace_bytes(int64_t N, int L, int C, int heads, int dtype, int want_dbias) {
-    if (check_shape(N, L, C, heads, dtype, !want_dbias) != FWA_OK || check_backward_support(L, dtype, want_dbias != 0) != FWA_OK)
+    if (check_shape(N, L, C, heads, dtype, true) != FWA_OK || check_backward_support(L, dtype, want_dbias != 0) != FWA_OK)
         return 0;
     if (!want_dbias || N == 0) return 0;
     // the slot count depends on the mask period; this is its upper bound over all periods
@@ -110,7 +111,7 @@ int fwa_backward_strided(const void* q, const void* k, const void* v, const void
                          float* dbias, int64_t N, int L, int C, int heads, float scale, int64_t ld_qkv,
                          int64_t ld_do, int64_t ld_dqkv, const float* bias, const float* mask, int nW, int dtype,
                          void* workspace, size_t workspace_bytes, void* stream) {
-    int rc = check_shape(N, L, C, heads, dtype, dbias == nullptr);
+    int rc = check_shape(N, L, C, heads, dtype, true);
     if (rc != FWA_OK) return rc;
     rc = check_row_stride(ld_qkv, C, dtype);
     if (rc != FWA_OK) return rc;
@@ -151,7 +152,7 @@ int fwa_backward_strided(const void* q, const void* k, const void* v, const void
     a.partial = dbias ? static_cast<float*>(workspace) : nullptr;
     a.bias = bias; a.mask = mask;
     a.N = N; a.L = L; a.C = C; a.heads = heads; a.nW = mask ? nW : 1; a.scale = scale;
-    a.slots = fwa::backward_slots(N, heads, mask ? nW : 1);
+    a.slots = C / heads != fwa::kHeadDim ? fwa::backward_wide_slots(N, heads) : fwa::backward_slots(N, heads, mask ? nW : 1);
     a.ldq = (int)ld_qkv; a.ldg = (int)ld_do; a.ldd = (int)ld_dqkv;
     const hipError_t e = dtype == FWA_BF16 ? fwa::launch_backward_bf16(a, st) : fwa::launch_backward_f32(a, st);
     return e == hipSuccess ? FWA_OK : FWA_ERR_LAUNCH;

@@ -416,6 +416,11 @@ hipError_t launch_backward_bf16(const BwdArgs& a, hipStream_t s) {
     const bool coop = coop_slots(a.N, a.heads, a.mask ? a.nW : 1) > 0;
     const hipError_t e = coop ? launch_backward_bf16_coop(a, s) : launch_backward_bf16_single(a, s);
     if (e != hipSuccess || a.dbias == nullptr) return e;
+    return launch_dbias_reduce(a, s);
+}
+
+// dbias = sum over a.slots slots of the partial sums a backward kernel left in a.partial
+hipError_t launch_dbias_reduce(const BwdArgs& a, hipStream_t s) {
     const int nb = (a.L + 15) / 16;
     hipLaunchKernelGGL(dbias_reduce_kernel, dim3((unsigned)(a.heads * nb * nb * 4)), dim3(16 * kReduceRows), 0, s,
                        reinterpret_cast<const f32x4*>(a.partial), a.dbias, a.slots, a.heads, a.L);

@@ -18,15 +18,20 @@
 //                                        transposing read
 //
 // Q and dO are therefore read twice from global memory (the second time from L2), which is the
-// paper's own count for its Algorithm 2.  No dBias here.
+// paper's own count for its Algorithm 2.
+//
+// A workgroup walks the windows bw, bw + G, ... of its head (G = N, one window each, unless dBias
+// is wanted).  dBias rows of a wave's query block are summed in registers across its windows and
+// leave as per-workgroup partial sums in register order, like those of the kernel for width 32;
+// the same reduce kernel adds the slots.
 #include "fwa_device.h"
 #include "fwa_internal.h"
 
 namespace fwa {
 namespace {
 
-template <int NB, int D, bool BM>
-__global__ void __launch_bounds__(256) bwd_bf16_wide_kernel(BwdArgs p) {
+template <int NB, int D, bool BM, bool DB>
+__global__ void __launch_bounds__(256) bwd_bf16_wide_kernel(BwdArgs p, uint32_t G) {
     constexpr int NB2 = (NB + 1) / 2;
     constexpr int ROWS = 16 * NB;
     constexpr int CH = D / 32;               // chunks of the products over the feature dimension
@@ -42,13 +47,10 @@ __global__ void __launch_bounds__(256) bwd_bf16_wide_kernel(BwdArgs p) {
     const int n = lane & 15, g = lane >> 4;
     const int role = __builtin_amdgcn_readfirstlane(tid >> 6);  // query block in phase A, key block in phase B
     const bool active = role < NB;
-    const uint32_t w = blockIdx.x / (uint32_t)p.heads, h = blockIdx.x % (uint32_t)p.heads;
+    const uint32_t bw = blockIdx.x / (uint32_t)p.heads, h = blockIdx.x % (uint32_t)p.heads;
     const int L = p.L;
     // token rows are p.ldq (q, k, v), p.ldg (d_o), p.ldd (dq, dk, dv) elements apart; window w starts at row w L
     const uint32_t row_bytes = (uint32_t)p.ldq * 2u, row_g = (uint32_t)p.ldg * 2u, row_d = (uint32_t)p.ldd * 2u;
-    const size_t tile = ((size_t)w * L * p.ldq + (size_t)h * D) * 2u;
-    const size_t tile_g = ((size_t)w * L * p.ldg + (size_t)h * D) * 2u;
-    const size_t tile_d = ((size_t)w * L * p.ldd + (size_t)h * D) * 2u;
     const uint32_t tile_bytes = (uint32_t)(L - 1) * row_bytes + 2u * D;  // rows beyond L read as zero
     const uint32_t tile_bytes_g = (uint32_t)(L - 1) * row_g + 2u * D;
     const uint32_t tile_bytes_d = (uint32_t)(L - 1) * row_d + 2u * D;
@@ -62,10 +64,20 @@ __global__ void __launch_bounds__(256) bwd_bf16_wide_kernel(BwdArgs p) {
     // row i sits at unit (b ^ (i & 3), c ^ ((i >> 2) & 3)): the 16 lanes of a write (16 rows, one
     // unit each) and of a transposing read (4 rows x 4 units) then touch every bank once.
     uint16_t* const ex = reinterpret_cast<uint16_t*>(lds + 2 * ROWS * STRIDE);
+    const uint32_t srow = (uint32_t)tid / TPR, scol = (uint32_t)tid % TPR;  // slab movement: (row, 16 B column)
+    const uint32_t opd = (uint32_t)n * STRIDE + g;                   // row operand: slab[opd + 16 b STRIDE + 4 c]
+    const uint32_t trs = (4u * g + (n >> 2)) * SROW + 4u * (n & 3);  // transposing-read base inside a slab
+    const uint32_t off_half = (uint32_t)n * row_d + 8u * g;          // channels 4g..4g+3 of output row n
+    f32x4 dbacc[NB];
+#pragma unroll
+    for (int jb = 0; jb < NB; ++jb) dbacc[jb] = zero;
 
+    for (uint32_t w = bw; w < (uint32_t)p.N; w += G) {
+    const size_t tile = ((size_t)w * L * p.ldq + (size_t)h * D) * 2u;
+    const size_t tile_g = ((size_t)w * L * p.ldg + (size_t)h * D) * 2u;
+    const size_t tile_d = ((size_t)w * L * p.ldd + (size_t)h * D) * 2u;
     const __amdgpu_buffer_rsrc_t rq = make_rsrc((const char*)p.q + tile, tile_bytes);
     const __amdgpu_buffer_rsrc_t rg = make_rsrc((const char*)p.d_o + tile_g, tile_bytes_g);
-    const uint32_t srow = (uint32_t)tid / TPR, scol = (uint32_t)tid % TPR;  // slab movement: (row, 16 B column)
 
     // own Q and dO rows as operands: lane (g, n) takes channels 32 c + 8g .. + 7 of row 16 role + n
     bf16x8 qop[CH], gop[CH];
@@ -105,10 +117,6 @@ __global__ void __launch_bounds__(256) bwd_bf16_wide_kernel(BwdArgs p) {
         sg[t] = __builtin_amdgcn_raw_buffer_load_b128(rg, (RPP * t + srow) * row_g + scol * 16u, 0, 0);
     }
     __syncthreads();
-
-    const uint32_t opd = (uint32_t)n * STRIDE + g;                   // row operand: slab[opd + 16 b STRIDE + 4 c]
-    const uint32_t trs = (4u * g + (n >> 2)) * SROW + 4u * (n & 3);  // transposing-read base inside a slab
-    const uint32_t off_half = (uint32_t)n * row_d + 8u * g;          // channels 4g..4g+3 of output row n
 
     // ---------------- phase A: query block `role` ----------------
     if (active) {
@@ -174,6 +182,7 @@ __global__ void __launch_bounds__(256) bwd_bf16_wide_kernel(BwdArgs p) {
         for (int jb = 0; jb < NB; ++jb) {
 #pragma unroll
             for (int r = 0; r < 4; ++r) dp[jb][r] = s[jb][r] * (dp[jb][r] - delta);  // dS
+            if (DB) dbacc[jb] += dp[jb];
             bf16x4 p_hi, p_lo;
             split_hi_lo(s[jb], p_hi, p_lo);
             split_hi_lo(dp[jb], ds_hi[jb], ds_lo[jb]);
@@ -262,24 +271,39 @@ __global__ void __launch_bounds__(256) bwd_bf16_wide_kernel(BwdArgs p) {
             __builtin_amdgcn_raw_buffer_store_b64(vk, rdk, off_half + 16 * jb * row_d + 32 * cb, 0, 0);
         }
     }
+    if (w + G < (uint32_t)p.N) __syncthreads();  // slabs and tiles are rewritten for the next window
+    }
+
+    if (DB && active) {
+        // partial sums in register order: [slot][head][qb][jb][lane] float4 -- contiguous 16-byte stores
+        f32x4* dst = reinterpret_cast<f32x4*>(p.partial) + ((size_t)bw * p.heads + h) * (NB * NB * 64) + lane;
+#pragma unroll
+        for (int jb = 0; jb < NB; ++jb) dst[(role * NB + jb) * 64] = dbacc[jb];
+    }
+}
+
+template <int NB, int D, bool BM, bool DB>
+hipError_t launch_wide_one(const BwdArgs& a, unsigned G, size_t lds, hipStream_t st) {
+    if (lds > 64 * 1024) {
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&bwd_bf16_wide_kernel<NB, D, BM, DB>),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL((bwd_bf16_wide_kernel<NB, D, BM, DB>), dim3(G * (unsigned)a.heads), dim3(256), lds, st, a, G);
+    return hipGetLastError();
 }
 
 template <int NB, int D>
 hipError_t launch_wide_nb(const BwdArgs& a, hipStream_t st) {
-    const unsigned grid = (unsigned)(a.N * a.heads);
     const size_t lds = (size_t)2 * 16 * NB * (D / 8 + 1) * 16 + (size_t)4 * 16 * NB * 64 * 2;
     const bool bm = a.bias || a.mask;
-    const void* fn = bm ? reinterpret_cast<const void*>(&bwd_bf16_wide_kernel<NB, D, true>)
-                        : reinterpret_cast<const void*>(&bwd_bf16_wide_kernel<NB, D, false>);
-    if (lds > 64 * 1024) {
-        const hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-    }
-    if (bm)
-        hipLaunchKernelGGL((bwd_bf16_wide_kernel<NB, D, true>), dim3(grid), dim3(256), lds, st, a);
-    else
-        hipLaunchKernelGGL((bwd_bf16_wide_kernel<NB, D, false>), dim3(grid), dim3(256), lds, st, a);
-    return hipGetLastError();
+    if (a.dbias == nullptr)  // one window per workgroup
+        return bm ? launch_wide_one<NB, D, true, false>(a, (unsigned)a.N, lds, st)
+                  : launch_wide_one<NB, D, false, false>(a, (unsigned)a.N, lds, st);
+    const unsigned G = (unsigned)a.slots;
+    const hipError_t e = bm ? launch_wide_one<NB, D, true, true>(a, G, lds, st)
+                            : launch_wide_one<NB, D, false, true>(a, G, lds, st);
+    return e != hipSuccess ? e : launch_dbias_reduce(a, st);
 }
 
 template <int D>
@@ -295,8 +319,15 @@ hipError_t launch_wide_d(const BwdArgs& a, hipStream_t s) {
 
 }  // namespace
 
+// Window positions walked in parallel (= dBias slots) when dBias is wanted: two or three resident
+// workgroups per CU; never more than the single-wave kernel's count, which sizes the workspace.
+int backward_wide_slots(long long N, int heads) {
+    long long G = 512 / heads;
+    if (G < 1) G = 1;
+    return (int)(G > N ? N : G);
+}
+
 hipError_t launch_backward_bf16_wide(const BwdArgs& a, hipStream_t s) {
-    if (a.dbias != nullptr) return hipErrorNotSupported;
     switch (a.C / a.heads) {
         case 64: return launch_wide_d<64>(a, s);
         case 128: return launch_wide_d<128>(a, s);

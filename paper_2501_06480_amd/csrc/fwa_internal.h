@@ -71,6 +71,8 @@ hipError_t launch_backward_bf16_coop(const BwdArgs& a, hipStream_t s);
 hipError_t launch_backward_bf16_single(const BwdArgs& a, hipStream_t s);
 hipError_t launch_backward_bf16_large(const BwdArgs& a, hipStream_t s);
 hipError_t launch_backward_bf16_wide(const BwdArgs& a, hipStream_t s);
+int backward_wide_slots(long long N, int heads);
+hipError_t launch_dbias_reduce(const BwdArgs& a, hipStream_t s);
 hipError_t launch_zero_f32(float* dst, size_t count, hipStream_t s);
 hipError_t launch_bias_gather(const float* table, float* bias, int heads, int k, hipStream_t s);
 hipError_t launch_bias_scatter(const float* dbias, float* dtable, int heads, int k, hipStream_t s);

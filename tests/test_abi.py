@@ -82,7 +82,7 @@ def test_forward_rejects_bad_arguments(lib):
 def test_backward_rejects_bad_arguments(lib):
     from paper_2501_06480_amd import binding as b
     assert bwd(lib, N=-1) == b.FWA_ERR_SHAPE
-    assert bwd(lib, C=128, heads=2, dbias=P + 0x7000, ws=P + 0x8000, ws_bytes=1 << 30) == b.FWA_ERR_UNSUPPORTED  # width 64 has no dBias
+    assert bwd(lib, C=128, heads=2, L=65) == b.FWA_ERR_UNSUPPORTED    # head dim 64 beyond one tile
     assert bwd(lib, C=96, heads=2) == b.FWA_ERR_UNSUPPORTED      # head dim 48
     assert bwd(lib, L=300) == b.FWA_ERR_UNSUPPORTED
     assert bwd(lib, g=None) == b.FWA_ERR_NULL

@@ -141,6 +141,17 @@ def test_wide_heads(oracle, d, L, use_bm):
     check_backward(oracle, w, bias, mask, f"d={d} L={L} bm={use_bm}", want_dbias=False)
 
 
+@pytest.mark.parametrize("d,L,N", [(64, 64, 300), (128, 49, 200), (256, 33, 140)])
+def test_wide_heads_dbias_over_many_windows(oracle, d, L, N):
+    """dBias for wide heads: workgroups walk several windows (N exceeds the slot count of 128)."""
+    heads = 4
+    w = synth.Workload(f"bwd_wide_db_d{d}_L{L}", N, L, d * heads, heads, "bf16", 8200 + d + L, 0, backward=True)
+    bias = synth.normal((heads, L, L), 59 + L, 0.5)
+    mask = np.where(synth.rng(71 + L + d).random((4, L, L)) < 0.2, -100.0, 0.0).astype(np.float32)
+    mask[:, np.arange(L), np.arange(L)] = 0.0
+    check_backward(oracle, w, bias, mask, f"d={d} L={L} N={N} dbias", want_dbias=True)
+
+
 def test_backward_is_bit_reproducible():
     import torch
     import paper_2501_06480_amd as fwa
