@@ -78,18 +78,6 @@ __global__ void __launch_bounds__(64 * kCoopWavesPerTile * kCoopMaxHeads) bwd_bf
     const uint32_t trx = (4u * g + (n >> 2)) * XS + ((((uint32_t)role) ^ (uint32_t)(n >> 2)) << 4) + ((((uint32_t)n & 3u) ^ (uint32_t)g) << 2);
     const uint32_t opd = (uint32_t)n * stride + 4u * hl + g;  // operand of row block b: slab[opd + 16 b stride]
 
-    // additive score term of this wave's query rows, in registers (see the file comment)
-    f32x4 add[NB];
-    if (BM && active) {
-        const uint32_t ll = (uint32_t)L * L * 4u;
-        const __amdgpu_buffer_rsrc_t rb = p.bias ? make_rsrc(p.bias + (size_t)h * L * L, ll) : make_rsrc(nullptr, 0);
-        const __amdgpu_buffer_rsrc_t rm =
-            p.mask ? make_rsrc(p.mask + (size_t)(bw % (uint32_t)p.nW) * L * L, ll) : make_rsrc(nullptr, 0);
-        const uint32_t off = (((uint32_t)(16 * role + n)) * L + 4u * g) * 4u;
-#pragma unroll
-        for (int jb = 0; jb < NB; ++jb)
-            add[jb] = (load_f32x4(rb, off + 16 * jb * 4u) + load_f32x4(rm, off + 16 * jb * 4u)) * kLog2e;
-    }
     f32x4 dbacc[NB];
 #pragma unroll
     for (int jb = 0; jb < NB; ++jb) dbacc[jb] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -122,10 +110,20 @@ __global__ void __launch_bounds__(64 * kCoopWavesPerTile * kCoopMaxHeads) bwd_bf
             lg[loff] = __builtin_bit_cast(uint4, pg);
         }
     };
-    if (bw < (uint32_t)p.N) {
-        request(bw);
-        park();
+    if (bw < (uint32_t)p.N) request(bw);  // in flight while the additive term is fetched
+    // additive score term of this wave's query rows, in registers (see the file comment)
+    f32x4 add[NB];
+    if (BM && active) {
+        const uint32_t ll = (uint32_t)L * L * 4u;
+        const __amdgpu_buffer_rsrc_t rb = p.bias ? make_rsrc(p.bias + (size_t)h * L * L, ll) : make_rsrc(nullptr, 0);
+        const __amdgpu_buffer_rsrc_t rm =
+            p.mask ? make_rsrc(p.mask + (size_t)(bw % (uint32_t)p.nW) * L * L, ll) : make_rsrc(nullptr, 0);
+        const uint32_t off = (((uint32_t)(16 * role + n)) * L + 4u * g) * 4u;
+#pragma unroll
+        for (int jb = 0; jb < NB; ++jb)
+            add[jb] = (load_f32x4(rb, off + 16 * jb * 4u) + load_f32x4(rm, off + 16 * jb * 4u)) * kLog2e;
     }
+    if (bw < (uint32_t)p.N) park();
 
     const uint32_t tile_bytes = (uint32_t)(L - 1) * row_d + 2u * kHeadDim;  // of an output tile
     const uint32_t off_half = (uint32_t)n * row_d + 8u * g;  // channels 4g..4g+3 of row n (+32 B: 16+4g..)

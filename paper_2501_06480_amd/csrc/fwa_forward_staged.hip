@@ -176,22 +176,6 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) fwd_bf16_persistent_kerne
     const uint32_t stride = 4u * hpb + 1u;
     const float sl2 = p.scale * kLog2e;
 
-    // the additive term of this wave's head and this workgroup's mask tile, in score layout
-    f32x4 add[NB][NB];
-    {
-        const uint32_t ll = (uint32_t)L * L * 4u;
-        const __amdgpu_buffer_rsrc_t rb = p.bias ? make_rsrc(p.bias + (size_t)h * L * L, ll) : make_rsrc(nullptr, 0);
-        const __amdgpu_buffer_rsrc_t rm =
-            p.mask ? make_rsrc(p.mask + (size_t)(bw % (uint32_t)p.nW) * L * L, ll) : make_rsrc(nullptr, 0);
-        const uint32_t off_b = ((uint32_t)n * L + 4u * g) * 4u;
-#pragma unroll
-        for (int qb = 0; qb < NB; ++qb) {
-            const AddendGlobal src = {rb, rm, off_b + (uint32_t)(16 * qb) * L * 4u};
-#pragma unroll
-            for (int jb = 0; jb < NB; ++jb) add[qb][jb] = src(jb);
-        }
-    }
-
     const uint32_t rip = fastdiv((uint32_t)tid, gm.lanes_per_row);
     const uint32_t col = (uint32_t)tid - rip * gm.lanes_per_row.d;
     const uint32_t slab_bytes = (uint32_t)(L - 1) * row_bytes + hpb * 2u * kHeadDim;
@@ -225,10 +209,24 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) fwd_bf16_persistent_kerne
             lv[loff + 16 * t * stride] = __builtin_bit_cast(uint4, sv[t]);
         }
     };
-    if (bw < (uint32_t)p.N) {
-        request(bw);
-        park();
+    if (bw < (uint32_t)p.N) request(bw);  // in flight while the additive term is fetched
+    // the additive term of this wave's head and this workgroup's mask tile, in score layout
+    f32x4 add[NB][NB];
+    {
+        const uint32_t ll = (uint32_t)L * L * 4u;
+        const __amdgpu_buffer_rsrc_t rb = p.bias ? make_rsrc(p.bias + (size_t)h * L * L, ll) : make_rsrc(nullptr, 0);
+        const __amdgpu_buffer_rsrc_t rm =
+            p.mask ? make_rsrc(p.mask + (size_t)(bw % (uint32_t)p.nW) * L * L, ll) : make_rsrc(nullptr, 0);
+        const uint32_t off_b = ((uint32_t)n * L + 4u * g) * 4u;
+#pragma unroll
+        for (int qb = 0; qb < NB; ++qb) {
+            const AddendGlobal src = {rb, rm, off_b + (uint32_t)(16 * qb) * L * 4u};
+#pragma unroll
+            for (int jb = 0; jb < NB; ++jb) add[qb][jb] = src(jb);
+        }
     }
+
+    if (bw < (uint32_t)p.N) park();
 
     // The next slab is parked at the END of an iteration: there the loads it waits for are always
     // older than this iteration's output stores, so the wait counts the stores out.  At the top of
@@ -454,19 +452,6 @@ __global__ void __launch_bounds__(64 * rowpersist_waves(NB)) fwd_bf16_rowpersist
     const uint32_t row_bytes = (uint32_t)p.ldq * 2u, row_out = (uint32_t)p.ldo * 2u;
     const float sl2 = p.scale * kLog2e;
 
-    f32x4 add[NB];
-    {
-        const uint32_t ll = (uint32_t)L * L * 4u;
-        const __amdgpu_buffer_rsrc_t rb = p.bias ? make_rsrc(p.bias + (size_t)h * L * L, ll) : make_rsrc(nullptr, 0);
-        const __amdgpu_buffer_rsrc_t rm =
-            p.mask ? make_rsrc(p.mask + (size_t)(bw % (uint32_t)p.nW) * L * L, ll) : make_rsrc(nullptr, 0);
-        // rows beyond L (and the whole block of an idle wave) fall outside the descriptors: zeros
-        const uint32_t off = active ? (((uint32_t)(16 * qb + n)) * L + 4u * g) * 4u : ll;
-#pragma unroll
-        for (int jb = 0; jb < NB; ++jb)
-            add[jb] = (load_f32x4(rb, off + 16 * jb * 4u) + load_f32x4(rm, off + 16 * jb * 4u)) * kLog2e;
-    }
-
     const uint32_t srow = (uint32_t)tid >> 2, scol = (uint32_t)tid & 3u;  // slab movement: thread -> (row, 16 B column)
     const uint32_t tile_bytes = (uint32_t)(L - 1) * row_bytes + 2u * kHeadDim;
     const uint32_t off_row = (uint32_t)(16 * qb + n) * row_bytes + 16u * g;
@@ -496,10 +481,20 @@ __global__ void __launch_bounds__(64 * rowpersist_waves(NB)) fwd_bf16_rowpersist
             }
         }
     };
-    if (bw < (uint32_t)p.N) {
-        request(bw);
-        park(0);
+    if (bw < (uint32_t)p.N) request(bw);  // in flight while the additive term is fetched
+    f32x4 add[NB];
+    {
+        const uint32_t ll = (uint32_t)L * L * 4u;
+        const __amdgpu_buffer_rsrc_t rb = p.bias ? make_rsrc(p.bias + (size_t)h * L * L, ll) : make_rsrc(nullptr, 0);
+        const __amdgpu_buffer_rsrc_t rm =
+            p.mask ? make_rsrc(p.mask + (size_t)(bw % (uint32_t)p.nW) * L * L, ll) : make_rsrc(nullptr, 0);
+        // rows beyond L (and the whole block of an idle wave) fall outside the descriptors: zeros
+        const uint32_t off = active ? (((uint32_t)(16 * qb + n)) * L + 4u * g) * 4u : ll;
+#pragma unroll
+        for (int jb = 0; jb < NB; ++jb)
+            add[jb] = (load_f32x4(rb, off + 16 * jb * 4u) + load_f32x4(rm, off + 16 * jb * 4u)) * kLog2e;
     }
+    if (bw < (uint32_t)p.N) park(0);
 
     // Per window: request the next slabs, one barrier, compute from buffer `buf`, store, then park
     // the next slabs in the other buffer.  That buffer was last read in the previous iteration,
