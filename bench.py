@@ -135,7 +135,45 @@ def time_other_workloads(torch, fwa, synth, dev):
         out.append({"workload": name, "us_per_call": round(us, 2), "window_heads_per_s": wh / us * 1e6,
                     "algorithmic_GBps": algo / us / 1e3, "frac_of_hbm_peak": algo / us / 1e3 / HBM_PEAK_GBPS})
 
+    def run_small(name, w, launches=16, replays=60):
+        """A launch-bound shape, eager and as one HIP graph of `launches` forward calls (distinct buffers)."""
+        shape = (w.N, w.L, w.C)
+        g = torch.Generator(device=dev).manual_seed(w.seed)
+        sets = [[torch.randn(shape, device=dev, generator=g).to(torch.bfloat16) for _ in range(3)] for _ in range(launches)]
+        outs = [torch.empty(shape, device=dev, dtype=torch.bfloat16) for _ in range(launches)]
+        bias = fwa.fwa_bias_gather(torch.from_numpy(synth.bias_table(w.heads, w.k, w.seed)).to(dev), w.k)
+
+        def chain(stream=None):
+            for t, o in zip(sets, outs):
+                fwa.fwa_forward(t[0], t[1], t[2], w.heads, w.scale, bias, None, out=o, stream=stream)
+
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+        def timed(fn):
+            for _ in range(5):
+                fn()
+            torch.cuda.synchronize()
+            e0.record()
+            for _ in range(replays):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / (replays * launches) * 1e3
+
+        us_eager = timed(chain)
+        side, graph = torch.cuda.Stream(), torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            chain(torch.cuda.current_stream())
+        us_graph = timed(graph.replay)
+        wh = w.N * w.heads
+        algo = 4 * w.L * 32 * 2 * wh
+        for label, us in (("eager", us_eager), (f"HIP graph of {launches} launches", us_graph)):
+            out.append({"workload": f"{name}, {label}", "us_per_call": round(us, 2), "window_heads_per_s": wh / us * 1e6,
+                        "algorithmic_GBps": algo / us / 1e3, "frac_of_hbm_peak": algo / us / 1e3 / HBM_PEAK_GBPS})
+
     run("swin_t_stage1_fwd_bias_shiftmask (N=8192, L=49, 3 heads)", synth.swin_t_stage(1, shifted=True), False, 400)
+    run_small("swin_t_stage3_fwd_bias (N=512, L=49, 12 heads)", synth.swin_t_stage(3))
+    run_small("swin_t_stage4_fwd_bias (N=128, L=49, 24 heads)", synth.swin_t_stage(4))
     l144, l256 = synth.config4()
     run("window12_fwd_bias (N=1024, L=144, 4 heads)", l144, False, 100)
     run("window16_fwd_bias (N=1024, L=256, 4 heads)", l256, False, 50)
@@ -234,7 +272,7 @@ def main():
                    "window_heads_per_step": wh},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS, "traffic": MEASURED_TRAFFIC_BYTES,
-                     "kernel": "fwd_bf16_staged_kernel<4,false>", "kernel_ms": kernel_ms,
+                     "kernel": "fwd_bf16_staged_kernel<4,false,1>", "kernel_ms": kernel_ms,
                      "algorithmic_bytes_per_launch": algo_bytes},
     }
     line["copy_ceiling"] = copy_ceiling(torch, sets)

@@ -27,14 +27,19 @@ struct StagedGeom {
     uint32_t heads_per_block;
 };
 
-template <int NB, bool BM>
-__global__ void __launch_bounds__(64 * kWavesPerBlock) fwd_bf16_staged_kernel(FwdArgs p, StagedGeom gm) {
+// QS = waves per head: 1 (a wave walks all query blocks of its head) or 4 (one wave per query
+// block: a quarter of the work per wave, for calls with too few tiles to fill the chip otherwise).
+template <int NB, bool BM, int QS>
+__global__ void __launch_bounds__(64 * kWavesPerBlock * QS) fwd_bf16_staged_kernel(FwdArgs p, StagedGeom gm) {
     constexpr int NB2 = (NB + 1) / 2;
     constexpr int ROWS = 16 * NB;
+    constexpr int PASSES = (NB + QS - 1) / QS;  // the workgroup moves 16 QS slab rows per pass
     extern __shared__ __attribute__((aligned(16))) uint4 lds[];  // [3][ROWS][stride]: K, V, Q (then O)
     const int tid = threadIdx.x, lane = tid & 63;
     const int n = lane & 15, g = lane >> 4;
-    const uint32_t hl = __builtin_amdgcn_readfirstlane(tid >> 6);  // head inside the workgroup
+    const uint32_t wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const uint32_t hl = wv / QS;  // head inside the workgroup
+    const int qs = (int)(wv % QS);
     const uint32_t w = fastdiv(blockIdx.x, gm.groups);
     const uint32_t hg = blockIdx.x - w * gm.groups.d;
     const uint32_t hpb = gm.heads_per_block;
@@ -57,32 +62,52 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) fwd_bf16_staged_kernel(Fw
     const uint32_t goff = rip * row_bytes + col * 16u;  // plus 16 t rows
     const uint32_t goff_o = rip * row_out + col * 16u;
     const uint32_t loff = rip * stride + col;           // plus 16 t rows, in uint4 units
-    u32x4 sk[NB], sv[NB], sq[NB];
+    u32x4 sk[PASSES], sv[PASSES], sq[PASSES];
 #pragma unroll
-    for (int t = 0; t < NB; ++t) {
+    for (int t = 0; t < PASSES; ++t) {
         // rows beyond L lie outside the descriptor and arrive as zeros
-        sk[t] = __builtin_amdgcn_raw_buffer_load_b128(rk, goff + 16 * t * row_bytes, 0, 0);
-        sq[t] = __builtin_amdgcn_raw_buffer_load_b128(rq, goff + 16 * t * row_bytes, 0, 0);
-        sv[t] = __builtin_amdgcn_raw_buffer_load_b128(rv, goff + 16 * t * row_bytes, 0, 0);
+        sk[t] = __builtin_amdgcn_raw_buffer_load_b128(rk, goff + 16 * QS * t * row_bytes, 0, 0);
+        sq[t] = __builtin_amdgcn_raw_buffer_load_b128(rq, goff + 16 * QS * t * row_bytes, 0, 0);
+        sv[t] = __builtin_amdgcn_raw_buffer_load_b128(rv, goff + 16 * QS * t * row_bytes, 0, 0);
+    }
+    // The additive term of this wave's query blocks, requested right behind the slab so that its
+    // trip to L2 overlaps the slab's trip to HBM instead of following the score products.
+    constexpr int NQ = QS == 1 ? NB : 1;  // query blocks of this wave: all, or block qs alone
+    f32x4 add[NQ][NB];
+    if (BM) {
+        const uint32_t ll = (uint32_t)L * L * 4u;
+        const uint32_t hh = h < (uint32_t)p.heads ? h : 0u;
+        const __amdgpu_buffer_rsrc_t rb = p.bias ? make_rsrc(p.bias + (size_t)hh * L * L, ll) : make_rsrc(nullptr, 0);
+        const __amdgpu_buffer_rsrc_t rm =
+            p.mask ? make_rsrc(p.mask + (size_t)(w % (uint32_t)p.nW) * L * L, ll) : make_rsrc(nullptr, 0);
+        const uint32_t off_b = ((uint32_t)n * L + 4u * g) * 4u;
+#pragma unroll
+        for (int it = 0; it < NQ; ++it) {
+            const AddendGlobal src = {rb, rm, off_b + (uint32_t)(16 * (QS == 1 ? it : qs)) * L * 4u};
+#pragma unroll
+            for (int jb = 0; jb < NB; ++jb) add[it][jb] = src(jb);
+        }
     }
     uint4* const lk = lds;
     uint4* const lv = lds + ROWS * stride;
     uint4* const lq = lds + 2 * ROWS * stride;
 #pragma unroll
-    for (int t = 0; t < NB; ++t) {
-        lk[loff + 16 * t * stride] = __builtin_bit_cast(uint4, sk[t]);
-        lq[loff + 16 * t * stride] = __builtin_bit_cast(uint4, sq[t]);
-        lv[loff + 16 * t * stride] = __builtin_bit_cast(uint4, sv[t]);
+    for (int t = 0; t < PASSES; ++t) {
+        if (QS == 1 || 16 * QS * t + rip < (uint32_t)ROWS) {
+            lk[loff + 16 * QS * t * stride] = __builtin_bit_cast(uint4, sk[t]);
+            lq[loff + 16 * QS * t * stride] = __builtin_bit_cast(uint4, sq[t]);
+            lv[loff + 16 * QS * t * stride] = __builtin_bit_cast(uint4, sv[t]);
+        }
     }
     __syncthreads();
 
     // ---- operands of this wave's head
-    bf16x8 kop[NB], qop[NB];
+    bf16x8 kop[NB], qop[NQ];
 #pragma unroll
-    for (int b = 0; b < NB; ++b) {
-        kop[b] = __builtin_bit_cast(bf16x8, lk[(16 * b + n) * stride + 4 * hl + g]);
-        qop[b] = __builtin_bit_cast(bf16x8, lq[(16 * b + n) * stride + 4 * hl + g]);
-    }
+    for (int b = 0; b < NB; ++b) kop[b] = __builtin_bit_cast(bf16x8, lk[(16 * b + n) * stride + 4 * hl + g]);
+#pragma unroll
+    for (int b = 0; b < NQ; ++b)
+        qop[b] = __builtin_bit_cast(bf16x8, lq[(16 * (QS == 1 ? b : qs) + n) * stride + 4 * hl + g]);
     // V: A operands of O^T per pair of key blocks, channels 0..15 and 16..31.
     // lane r of a row points at V[i0 + (r >> 2)][j0 + 4 (r & 3)], i0 = first key of the 4 the lane row owns
     bf16x8 vop[NB2][2];
@@ -102,25 +127,18 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) fwd_bf16_staged_kernel(Fw
     }
 
     const float sl2 = p.scale * kLog2e;
-    __amdgpu_buffer_rsrc_t rb = make_rsrc(nullptr, 0), rm = make_rsrc(nullptr, 0);
-    if (BM) {
-        const uint32_t ll = (uint32_t)L * L * 4u;
-        const uint32_t hh = h < (uint32_t)p.heads ? h : 0u;
-        if (p.bias) rb = make_rsrc(p.bias + (size_t)hh * L * L, ll);
-        if (p.mask) rm = make_rsrc(p.mask + (size_t)(w % (uint32_t)p.nW) * L * L, ll);
-    }
-    const uint32_t off_b = ((uint32_t)n * L + 4u * g) * 4u;
 
 #pragma unroll
-    for (int qb = 0; qb < NB; ++qb) {
+    for (int it = 0; it < NQ; ++it) {
+        const int qb = QS == 1 ? it : qs;
         if (16 * qb >= L) break;  // uniform
         f32x4 s[NB];
 #pragma unroll
         for (int jb = 0; jb < NB; ++jb) {
             const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
-            s[jb] = mfma_bf16(kop[jb], qop[qb], zero);  // S[16 qb + n][16 jb + 4g + r]
+            s[jb] = mfma_bf16(kop[jb], qop[it], zero);  // S[16 qb + n][16 jb + 4g + r]
         }
-        const AddendGlobal addend = {rb, rm, off_b + (uint32_t)(16 * qb) * L * 4u};
+        const AddendRegs<NB> addend = {add[it]};
         const float inv = softmax_block<NB, BM>(s, sl2, addend, L, g);
 
         f32x4 o0 = {0.f, 0.f, 0.f, 0.f}, o1 = {0.f, 0.f, 0.f, 0.f};
@@ -143,9 +161,11 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) fwd_bf16_staged_kernel(Fw
     __syncthreads();
     // ---- whole rows back to global memory; rows beyond L are dropped by the range check
 #pragma unroll
-    for (int t = 0; t < NB; ++t) {
-        const u32x4 v = __builtin_bit_cast(u32x4, lq[loff + 16 * t * stride]);
-        __builtin_amdgcn_raw_buffer_store_b128(v, ro, goff_o + 16 * t * row_out, 0, 0);
+    for (int t = 0; t < PASSES; ++t) {
+        if (QS == 1 || 16 * QS * t + rip < (uint32_t)ROWS) {
+            const u32x4 v = __builtin_bit_cast(u32x4, lq[loff + 16 * QS * t * stride]);
+            __builtin_amdgcn_raw_buffer_store_b128(v, ro, goff_o + 16 * QS * t * row_out, 0, 0);
+        }
     }
 }
 
@@ -626,6 +646,9 @@ hipError_t launch_staged_nb(const FwdArgs& a, int hpb, hipStream_t st) {
     gm.heads_per_block = (uint32_t)hpb;
     const unsigned grid = (unsigned)(a.N * groups), block = 64u * (unsigned)hpb;
     const size_t lds = (size_t)3 * 16 * NB * (4 * hpb + 1) * 16;
+    // Fewer window-heads than the chip holds waves (4 per SIMD): one wave per query block instead of
+    // one per head, so that the call is not one long round of under-occupied CUs.
+    const bool few_tiles = NB > 1 && a.N * a.heads <= 4096;
     if (a.bias || a.mask) {
         // Persistent walk over G window positions: a multiple of nW so that a workgroup always
         // sees the same mask tile, about 4 workgroups per CU (measured best of 2..8), at least 2
@@ -638,10 +661,15 @@ hipError_t launch_staged_nb(const FwdArgs& a, int hpb, hipStream_t st) {
                                a, gm, (uint32_t)G);
             return hipGetLastError();
         }
-        hipLaunchKernelGGL((fwd_bf16_staged_kernel<NB, true>), dim3(grid), dim3(block), lds, st, a, gm);
+        if (few_tiles)
+            hipLaunchKernelGGL((fwd_bf16_staged_kernel<NB, true, 4>), dim3(grid), dim3(4 * block), lds, st, a, gm);
+        else
+            hipLaunchKernelGGL((fwd_bf16_staged_kernel<NB, true, 1>), dim3(grid), dim3(block), lds, st, a, gm);
+    } else if (few_tiles) {
+        hipLaunchKernelGGL((fwd_bf16_staged_kernel<NB, false, 4>), dim3(grid), dim3(4 * block), lds, st, a, gm);
+    } else {
+        hipLaunchKernelGGL((fwd_bf16_staged_kernel<NB, false, 1>), dim3(grid), dim3(block), lds, st, a, gm);
     }
-    else
-        hipLaunchKernelGGL((fwd_bf16_staged_kernel<NB, false>), dim3(grid), dim3(block), lds, st, a, gm);
     return hipGetLastError();
 }
 

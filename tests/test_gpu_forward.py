@@ -132,6 +132,30 @@ def test_wide_heads(oracle, d, L, use_bm):
     assert err <= TOL["bf16"]
 
 
+@pytest.mark.parametrize("N", [1365, 1366])
+@pytest.mark.parametrize("which", ["none", "bias+own_mask"])
+def test_both_sides_of_the_few_tiles_threshold(oracle, N, which):
+    """Up to 4096 window-heads a wave takes one query block (4 waves per head), above that a wave
+    walks all query blocks of its head: 1365 x 3 = 4095 and 1366 x 3 = 4098 window-heads.  A mask
+    with one tile per window (period N) keeps the call off the kernel that walks windows."""
+    import torch
+    import paper_2501_06480_amd as fwa
+    w = synth.Workload(f"few_tiles_N{N}", N, 49, 96, 3, "bf16", 7700 + N, 7, 0, True)
+    x = synth.draw(w)
+    bias64 = mask = None
+    if which != "none":
+        bias64 = oracle.bias_gather(x["table"], w.k)
+        mask = np.where(synth.rng(7800 + N).random((N, 49, 49)) < 0.2, -100.0, 0.0).astype(np.float32)
+        mask[:, np.arange(49), np.arange(49)] = 0.0
+    q, k, v = (to_device(x, w, n) for n in ("q", "k", "v"))
+    o = fwa.fwa_forward(q, k, v, w.heads, w.scale, f32_device(bias64), f32_device(mask))
+    torch.cuda.synchronize()
+    want = oracle.forward(x["q"], x["k"], x["v"], w.heads, w.scale, bias64, mask)
+    err = max_abs(to_f64(o), want)
+    print(f"N={N} {which}: err={err:.3e}", flush=True)
+    assert err <= TOL["bf16"]
+
+
 def test_stage4_single_window_map_with_mask(oracle):
     """A 7x7 map is one window; the shift mask then has 4 regions inside it."""
     w = synth.Workload("s4_masked", 8, 49, 768, 24, "bf16", 1234, 7, 7, True, 3)
