@@ -83,16 +83,17 @@ int fwa_forward_strided(const void* q, const void* k, const void* v, void* o,
 
 /*
  * Backward pass (paper Algorithm 2).  Inputs are Q, K, V and dO only.
- * Supported: dtype FWA_BF16, any L <= 256 for dQ, dK, dV; dbias only for
- * L <= 64 (its accumulator stays on chip across windows).  fp32 data, and
- * dbias with L > 64, return FWA_ERR_UNSUPPORTED.
+ * Supported: dtype FWA_BF16 in every shape the forward takes; fp32 data
+ * returns FWA_ERR_UNSUPPORTED.
  *   d_o        : in,  [N, L, C], dtype
  *   dq, dk, dv : out, [N, L, C], dtype, fully overwritten
  *   dbias      : NULL, or out [heads, L, L] fp32 = sum over all N windows of
  *                dS; overwritten, not accumulated.  The mask gets no gradient.
  *   workspace  : device scratch of at least fwa_backward_workspace_bytes(...)
- *                bytes, 16-byte aligned; may be NULL when that size is 0.
- *                Contents on entry are ignored and undefined on exit.
+ *                bytes, 16-byte aligned; may be NULL when that size is 0 (it is
+ *                0 unless dbias is wanted: it holds per-workgroup partial sums
+ *                of dbias and, for L > 64, the softmax statistics of every
+ *                row).  Contents on entry are ignored and undefined on exit.
  * Results are bit-reproducible from run to run for fixed arguments.
  */
 int fwa_backward(const void* q, const void* k, const void* v, const void* d_o,

@@ -23,12 +23,16 @@ int check_shape(int64_t N, int L, int C, int heads, int dtype, bool wide_ok) {
     return FWA_OK;
 }
 
-// The backward covers bf16 data; dBias only for windows whose score tile stays on chip (L <= 64:
-// every wide-head shape qualifies).
-int check_backward_support(int L, int dtype, bool want_dbias) {
+// The backward covers bf16 data.
+int check_backward_support(int, int dtype, bool) {
     if (dtype != FWA_BF16) return FWA_ERR_UNSUPPORTED;
-    if (want_dbias && L > fwa::kMaxBackwardL) return FWA_ERR_UNSUPPORTED;
     return FWA_OK;
+}
+
+// Row statistics the large-window backward leaves for its dBias kernel: [N, heads, 2, 16 nb] floats
+size_t large_stats_bytes(int64_t N, int L, int heads) {
+    const size_t nb = (size_t)(L + 15) / 16;
+    return (size_t)N * heads * 2 * 16 * nb * sizeof(float);
 }
 
 // Row stride of a strided tensor, in elements: at least C, rows 16-byte aligned, and small enough
@@ -104,6 +108,8 @@ size_t fwa_backward_workspace_bytes(int64_t N, int L, int C, int heads, int dtyp
     if (!want_dbias || N == 0) return 0;
     // the slot count depends on the mask period; this is its upper bound over all periods
     const size_t nb = (size_t)(L + 15) / 16;  // partial sums are kept per 16 x 16 block, padded
+    if (L > fwa::kMaxBackwardL)
+        return large_stats_bytes(N, L, heads) + (size_t)fwa::backward_large_slots(N, heads, L) * heads * nb * nb * 256 * sizeof(float);
     return (size_t)fwa::backward_max_slots(N, heads) * heads * nb * nb * 256 * sizeof(float);
 }
 
@@ -150,9 +156,16 @@ int fwa_backward_strided(const void* q, const void* k, const void* v, const void
     a.q = q; a.k = k; a.v = v; a.d_o = d_o;
     a.dq = dq; a.dk = dk; a.dv = dv; a.dbias = dbias;
     a.partial = dbias ? static_cast<float*>(workspace) : nullptr;
+    a.stats = nullptr;
+    if (dbias && L > fwa::kMaxBackwardL) {  // workspace = [row statistics][partial sums]
+        a.stats = static_cast<float*>(workspace);
+        a.partial = reinterpret_cast<float*>(static_cast<char*>(workspace) + large_stats_bytes(N, L, heads));
+    }
     a.bias = bias; a.mask = mask;
     a.N = N; a.L = L; a.C = C; a.heads = heads; a.nW = mask ? nW : 1; a.scale = scale;
-    a.slots = C / heads != fwa::kHeadDim ? fwa::backward_wide_slots(N, heads) : fwa::backward_slots(N, heads, mask ? nW : 1);
+    a.slots = C / heads != fwa::kHeadDim ? fwa::backward_wide_slots(N, heads)
+              : L > fwa::kMaxBackwardL   ? fwa::backward_large_slots(N, heads, L)
+                                         : fwa::backward_slots(N, heads, mask ? nW : 1);
     a.ldq = (int)ld_qkv; a.ldg = (int)ld_do; a.ldd = (int)ld_dqkv;
     const hipError_t e = dtype == FWA_BF16 ? fwa::launch_backward_bf16(a, st) : fwa::launch_backward_f32(a, st);
     return e == hipSuccess ? FWA_OK : FWA_ERR_LAUNCH;

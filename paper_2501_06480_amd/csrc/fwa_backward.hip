@@ -309,7 +309,8 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, 2) bwd_bf16_kernel(BwdArg
 // fixed summation tree, hence bit-reproducible.
 constexpr int kReduceRows = 16;
 __global__ void __launch_bounds__(16 * kReduceRows)
-dbias_reduce_kernel(const f32x4* __restrict__ partial, float* __restrict__ dbias, int slots, int heads, int L) {
+dbias_reduce_kernel(const f32x4* __restrict__ partial, float* __restrict__ dbias, int slots, int heads, int L,
+                    int key_on_lane) {
     __shared__ f32x4 part[kReduceRows][16];
     const int x = threadIdx.x & 15, y = threadIdx.x >> 4;
     const int nb = (L + 15) / 16;
@@ -324,13 +325,24 @@ dbias_reduce_kernel(const f32x4* __restrict__ partial, float* __restrict__ dbias
 #pragma unroll
         for (int r = 1; r < kReduceRows; ++r) total += part[r][x];
         const int lane = (int)(f & 63), blk = (int)(f >> 6);
-        const int jb = blk % nb, qb = (blk / nb) % nb, h = blk / (nb * nb);
-        const int i = 16 * qb + (lane & 15), j = 16 * jb + 4 * (lane >> 4);
-        if (i < L) {
-            float* row = dbias + ((size_t)h * L + i) * L;
+        const int b1 = blk % nb, b0 = (blk / nb) % nb, h = blk / (nb * nb);
+        if (!key_on_lane) {
+            // blocks [qb][jb]; lane (g, n) holds query 16 qb + n, keys 16 jb + 4g + r
+            const int i = 16 * b0 + (lane & 15), j = 16 * b1 + 4 * (lane >> 4);
+            if (i < L) {
+                float* row = dbias + ((size_t)h * L + i) * L;
 #pragma unroll
-            for (int r = 0; r < 4; ++r)
-                if (j + r < L) row[j + r] = total[r];
+                for (int r = 0; r < 4; ++r)
+                    if (j + r < L) row[j + r] = total[r];
+            }
+        } else {
+            // blocks [jb][qb]; lane (g, n) holds key 16 jb + n, queries 16 qb + 4g + r
+            const int j = 16 * b0 + (lane & 15), i = 16 * b1 + 4 * (lane >> 4);
+            if (j < L) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    if (i + r < L) dbias[((size_t)h * L + i + r) * L + j] = total[r];
+            }
         }
     }
 }
@@ -420,10 +432,10 @@ hipError_t launch_backward_bf16(const BwdArgs& a, hipStream_t s) {
 }
 
 // dbias = sum over a.slots slots of the partial sums a backward kernel left in a.partial
-hipError_t launch_dbias_reduce(const BwdArgs& a, hipStream_t s) {
+hipError_t launch_dbias_reduce(const BwdArgs& a, hipStream_t s, bool key_on_lane) {
     const int nb = (a.L + 15) / 16;
     hipLaunchKernelGGL(dbias_reduce_kernel, dim3((unsigned)(a.heads * nb * nb * 4)), dim3(16 * kReduceRows), 0, s,
-                       reinterpret_cast<const f32x4*>(a.partial), a.dbias, a.slots, a.heads, a.L);
+                       reinterpret_cast<const f32x4*>(a.partial), a.dbias, a.slots, a.heads, a.L, key_on_lane ? 1 : 0);
     return hipGetLastError();
 }
 

@@ -210,8 +210,14 @@ __global__ void __launch_bounds__(64 * large_waves(NB)) bwd_bf16_large_kernel(Bw
 #pragma unroll
             for (int jb = 0; jb < NB; ++jb) s[jb] *= inv;  // P
             if (g == 0) {
-                stM[16 * qb + n] = m + __builtin_amdgcn_logf(sum);  // p_ij = exp2(score_ij - M_i)
+                const float Mi = m + __builtin_amdgcn_logf(sum);  // p_ij = exp2(score_ij - M_i)
+                stM[16 * qb + n] = Mi;
                 stD[16 * qb + n] = delta;
+                if (p.stats) {  // kept for the dBias kernel, which redoes pass 2 only
+                    float* gs = p.stats + ((size_t)w * p.heads + h) * (2 * ROWS) + 16 * qb + n;
+                    gs[0] = Mi;
+                    gs[ROWS] = delta;
+                }
             }
             // dQ^T = K^T dS^T over pairs of key blocks; the operands of the next pair are fetched ahead
             f32x4 q0 = zero, q1 = zero;  // dQ[16 qb + n][4g + r], dQ[16 qb + n][16 + 4g + r]
@@ -377,6 +383,189 @@ __global__ void __launch_bounds__(64 * large_waves(NB)) bwd_bf16_large_kernel(Bw
     }
 }
 
+// dBias for 64 < L <= 256.  Its accumulator is L x L fp32 per head (256 KB at L = 256): half of
+// a CU's register file, which the two passes above need themselves.  So it has a kernel of its
+// own that redoes pass 2 only -- S and dP block by block in the "key on the lane" orientation,
+// P = exp2(score - M_i), dS = P (dP - delta_i) with M_i, delta_i as the main kernel left them in
+// global memory -- and keeps nothing but the sums: a wave owns key blocks jb = wave, wave + W, ...
+// of one head for its whole life, holds dBias[all queries][its keys] in registers across the
+// windows bw, bw + G, ... and writes them out once, in register order, as one of G partial
+// sums per head (the reduce kernel adds the slots in a fixed order).
+template <int NB, bool HB, bool HM>
+__global__ void __launch_bounds__(64 * large_waves(NB)) dbias_large_kernel(BwdArgs p, LargeGeom gm) {
+    constexpr bool BM = HB || HM;
+    constexpr int W = large_waves(NB);
+    constexpr int JPW = (NB + W - 1) / W;  // key blocks per wave
+    constexpr int NB2 = (NB + 1) / 2;
+    constexpr int ROWS = 16 * NB;
+    constexpr int PASSES = (ROWS + 16 * W - 1) / (16 * W);
+    constexpr uint32_t STRIDE = 5;
+    extern __shared__ __attribute__((aligned(16))) uint4 lds[];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int n = lane & 15, g = lane >> 4;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const uint32_t lb = xcd_logical_block(blockIdx.x, gm.xcd_q, gm.xcd_r);
+    const uint32_t h = lb % gm.heads, bw = lb / gm.heads;
+    const int L = p.L;
+    const uint32_t row_bytes = (uint32_t)p.ldq * 2u, row_g = (uint32_t)p.ldg * 2u;
+    const float sl2 = p.scale * kLog2e;
+    const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+
+    uint4* const lk = lds;
+    uint4* const lv = lds + ROWS * STRIDE;
+    uint4* const lq = lds + 2 * ROWS * STRIDE;
+    uint4* const lg = lds + 3 * ROWS * STRIDE;
+    float* const stM = reinterpret_cast<float*>(lds + 4 * ROWS * STRIDE);  // M[ROWS] then delta[ROWS]
+
+    const uint32_t ll = (uint32_t)L * L * 4u;
+    const uint32_t srow = (uint32_t)tid >> 2, scol = (uint32_t)tid & 3u;
+    const uint32_t tile_bytes = (uint32_t)(L - 1) * row_bytes + 2u * kHeadDim;
+    const uint32_t tile_bytes_g = (uint32_t)(L - 1) * row_g + 2u * kHeadDim;
+    const uint32_t opd = (uint32_t)n * STRIDE + g;
+
+    f32x4 dbacc[JPW][NB];
+#pragma unroll
+    for (int a = 0; a < JPW; ++a)
+#pragma unroll
+        for (int b = 0; b < NB; ++b) dbacc[a][b] = zero;
+
+    for (uint32_t w = bw; w < (uint32_t)p.N; w += gm.G) {
+        {
+            const size_t tile = ((size_t)w * L * p.ldq + (size_t)h * kHeadDim) * 2u;
+            const size_t tile_g = ((size_t)w * L * p.ldg + (size_t)h * kHeadDim) * 2u;
+            const __amdgpu_buffer_rsrc_t rk = make_rsrc((const char*)p.k + tile, tile_bytes);
+            const __amdgpu_buffer_rsrc_t rv = make_rsrc((const char*)p.v + tile, tile_bytes);
+            const __amdgpu_buffer_rsrc_t rq = make_rsrc((const char*)p.q + tile, tile_bytes);
+            const __amdgpu_buffer_rsrc_t rg = make_rsrc((const char*)p.d_o + tile_g, tile_bytes_g);
+            const __amdgpu_buffer_rsrc_t rs =
+                make_rsrc(p.stats + ((size_t)w * p.heads + h) * (2 * ROWS), (uint32_t)(2 * ROWS * 4));
+            u32x4 pk[PASSES], pv[PASSES], pq[PASSES], pg[PASSES];
+#pragma unroll
+            for (int t = 0; t < PASSES; ++t) {
+                const uint32_t off = (16 * W * t + srow) * row_bytes + scol * 16u;  // rows beyond L arrive as zeros
+                pk[t] = __builtin_amdgcn_raw_buffer_load_b128(rk, off, 0, 0);
+                pv[t] = __builtin_amdgcn_raw_buffer_load_b128(rv, off, 0, 0);
+                pq[t] = __builtin_amdgcn_raw_buffer_load_b128(rq, off, 0, 0);
+                pg[t] = __builtin_amdgcn_raw_buffer_load_b128(rg, (16 * W * t + srow) * row_g + scol * 16u, 0, 0);
+            }
+            // 2 ROWS floats of statistics: 16 bytes per thread, the first ROWS / 2 threads
+            const u32x4 st4 = __builtin_amdgcn_raw_buffer_load_b128(rs, (uint32_t)tid * 16u, 0, 0);
+#pragma unroll
+            for (int t = 0; t < PASSES; ++t) {
+                const uint32_t row = 16 * W * t + srow;
+                if (row < (uint32_t)ROWS) {
+                    lk[row * STRIDE + scol] = __builtin_bit_cast(uint4, pk[t]);
+                    lv[row * STRIDE + scol] = __builtin_bit_cast(uint4, pv[t]);
+                    lq[row * STRIDE + scol] = __builtin_bit_cast(uint4, pq[t]);
+                    lg[row * STRIDE + scol] = __builtin_bit_cast(uint4, pg[t]);
+                }
+            }
+            if (tid < ROWS / 2) reinterpret_cast<uint4*>(stM)[tid] = __builtin_bit_cast(uint4, st4);
+        }
+        __syncthreads();
+        const float* const stD = stM + ROWS;
+
+#pragma unroll
+        for (int a = 0; a < JPW; ++a) {
+            const int jb = (int)wave + a * W;
+            if (jb < NB) {
+                const bf16x8 kop = __builtin_bit_cast(bf16x8, lk[opd + 16 * jb * STRIDE]);
+                const bf16x8 vop = __builtin_bit_cast(bf16x8, lv[opd + 16 * jb * STRIDE]);
+                const uint32_t jcol = 16u * jb + n;
+                const bool valid = jcol < (uint32_t)L;
+                uint32_t aoff[4];
+#pragma unroll
+                for (int r = 0; r < 4; ++r) aoff[r] = ((uint32_t)(4 * g + r) * L + jcol) * 4u;
+                bf16x8 oq[2][2], og[2][2];
+                f32x4 oM[2][2], oD[2][2], ab[2][2], am[2][2];
+                auto fetch = [&](int qp, int slot) {
+#pragma unroll
+                    for (int u = 0; u < 2; ++u) {
+                        if (u == 1 && 2 * qp + 1 >= NB) break;
+                        const int qb = 2 * qp + u;
+                        oq[slot][u] = __builtin_bit_cast(bf16x8, lq[opd + 16 * qb * STRIDE]);
+                        og[slot][u] = __builtin_bit_cast(bf16x8, lg[opd + 16 * qb * STRIDE]);
+                        oM[slot][u] = *reinterpret_cast<const f32x4*>(stM + 16 * qb + 4 * g);
+                        oD[slot][u] = *reinterpret_cast<const f32x4*>(stD + 16 * qb + 4 * g);
+                        if (BM) {
+                            const uint32_t qrow = (uint32_t)(16 * qb) * L;
+                            const __amdgpu_buffer_rsrc_t rbq =
+                                HB ? make_rsrc(p.bias + (size_t)h * L * L + qrow, ll - 4u * qrow) : make_rsrc(nullptr, 0);
+                            const __amdgpu_buffer_rsrc_t rmq =
+                                HM ? make_rsrc(p.mask + (size_t)(w % (uint32_t)p.nW) * L * L + qrow, ll - 4u * qrow)
+                                   : make_rsrc(nullptr, 0);
+#pragma unroll
+                            for (int r = 0; r < 4; ++r) {
+                                if (HB) ab[slot][u][r] = load_f32(rbq, aoff[r]);
+                                if (HM) am[slot][u][r] = load_f32(rmq, aoff[r]);
+                            }
+                        }
+                    }
+                };
+                fetch(0, 0);
+#pragma unroll
+                for (int qp = 0; qp < NB2; ++qp) {
+                    const int cur = qp & 1;
+                    if (qp + 1 < NB2) fetch(qp + 1, cur ^ 1);
+                    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                    for (int u = 0; u < 2; ++u) {
+                        if (u == 1 && 2 * qp + 1 >= NB) break;
+                        const f32x4 sc = mfma_bf16(oq[cur][u], kop, zero);  // <q_i, k_j>, i = 16 qb + 4g + r, j = jcol
+                        const f32x4 dp = mfma_bf16(og[cur][u], vop, zero);
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) {
+                            float x;
+                            if (BM) {
+                                const float add = HB && HM ? ab[cur][u][r] + am[cur][u][r] : (HB ? ab[cur][u][r] : am[cur][u][r]);
+                                x = fmaf(sc[r], sl2, fmaf(add, kLog2e, -oM[cur][u][r]));
+                            } else {
+                                x = fmaf(sc[r], sl2, -oM[cur][u][r]);
+                            }
+                            const float pr = valid ? __builtin_amdgcn_exp2f(x) : 0.f;
+                            dbacc[a][2 * qp + u][r] += pr * (dp[r] - oD[cur][u][r]);
+                        }
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+        }
+        __syncthreads();  // the slabs are rewritten for the next window
+    }
+
+    // partial sums in register order: [slot][head][jb][qb][lane] float4, element r of lane (g, n) being
+    // dS summed over windows for query 16 qb + 4g + r and key 16 jb + n
+    f32x4* dst = reinterpret_cast<f32x4*>(p.partial) + ((size_t)bw * p.heads + h) * (NB * NB * 64) + lane;
+#pragma unroll
+    for (int a = 0; a < JPW; ++a) {
+        const int jb = (int)wave + a * W;
+        if (jb < NB) {
+#pragma unroll
+            for (int qb = 0; qb < NB; ++qb) dst[(jb * NB + qb) * 64] = dbacc[a][qb];
+        }
+    }
+}
+
+template <int NB, bool HB, bool HM>
+hipError_t launch_dbias_large(const BwdArgs& a, hipStream_t st) {
+    constexpr int W = large_waves(NB);
+    const void* fn = reinterpret_cast<const void*>(&dbias_large_kernel<NB, HB, HM>);
+    const unsigned block = 64u * W;
+    const size_t lds = (size_t)4 * 16 * NB * 5 * 16 + (size_t)2 * 16 * NB * 4;
+    if (lds > 64 * 1024) {
+        const hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+    }
+    LargeGeom gm;
+    gm.heads = (uint32_t)a.heads;
+    gm.G = (uint32_t)a.slots;
+    const unsigned grid = gm.G * gm.heads;
+    gm.xcd_q = grid / 8u;
+    gm.xcd_r = grid % 8u;
+    hipLaunchKernelGGL((dbias_large_kernel<NB, HB, HM>), dim3(grid), dim3(block), lds, st, a, gm);
+    return hipGetLastError();
+}
+
 template <int NB, bool HB, bool HM>
 hipError_t launch_large_one(const BwdArgs& a, hipStream_t st) {
     constexpr bool BM = HB || HM;
@@ -409,16 +598,31 @@ hipError_t launch_large_one(const BwdArgs& a, hipStream_t st) {
     return hipGetLastError();
 }
 
+template <int NB, bool HB, bool HM>
+hipError_t launch_large_both(const BwdArgs& a, hipStream_t st) {
+    hipError_t e = launch_large_one<NB, HB, HM>(a, st);
+    if (e != hipSuccess || a.dbias == nullptr) return e;
+    e = launch_dbias_large<NB, HB, HM>(a, st);
+    return e != hipSuccess ? e : launch_dbias_reduce(a, st, true);
+}
+
 template <int NB>
 hipError_t launch_large_nb(const BwdArgs& a, hipStream_t st) {
-    if (a.bias) return a.mask ? launch_large_one<NB, true, true>(a, st) : launch_large_one<NB, true, false>(a, st);
-    return a.mask ? launch_large_one<NB, false, true>(a, st) : launch_large_one<NB, false, false>(a, st);
+    if (a.bias) return a.mask ? launch_large_both<NB, true, true>(a, st) : launch_large_both<NB, true, false>(a, st);
+    return a.mask ? launch_large_both<NB, false, true>(a, st) : launch_large_both<NB, false, false>(a, st);
 }
 
 }  // namespace
 
+// Slots of dBias partial sums for large windows: one resident workgroup of the dBias kernel per CU
+// when its slabs fill most of the LDS (more than 10 blocks of 16 rows), two otherwise
+int backward_large_slots(long long N, int heads, int L) {
+    long long G = (L > 160 ? 256 : 512) / heads;
+    if (G < 1) G = 1;
+    return (int)(G > N ? N : G);
+}
+
 hipError_t launch_backward_bf16_large(const BwdArgs& a, hipStream_t s) {
-    if (a.dbias != nullptr) return hipErrorNotSupported;
     switch ((a.L + 15) / 16) {
         case 5: return launch_large_nb<5>(a, s);
         case 6: return launch_large_nb<6>(a, s);

@@ -41,6 +41,7 @@ struct BwdArgs {
     void* dv;
     float* dbias;        // [heads, L, L] or nullptr
     float* partial;      // workspace for per-slot dS sums, or nullptr
+    float* stats;        // workspace [N, heads, 2, 16 * ceil(L / 16)] for the row statistics (L > 64 with dbias), or nullptr
     const float* bias;
     const float* mask;
     long long N;
@@ -72,7 +73,8 @@ hipError_t launch_backward_bf16_single(const BwdArgs& a, hipStream_t s);
 hipError_t launch_backward_bf16_large(const BwdArgs& a, hipStream_t s);
 hipError_t launch_backward_bf16_wide(const BwdArgs& a, hipStream_t s);
 int backward_wide_slots(long long N, int heads);
-hipError_t launch_dbias_reduce(const BwdArgs& a, hipStream_t s);
+hipError_t launch_dbias_reduce(const BwdArgs& a, hipStream_t s, bool key_on_lane = false);
+int backward_large_slots(long long N, int heads, int L);
 hipError_t launch_zero_f32(float* dst, size_t count, hipStream_t s);
 hipError_t launch_bias_gather(const float* table, float* bias, int heads, int k, hipStream_t s);
 hipError_t launch_bias_scatter(const float* dbias, float* dtable, int heads, int k, hipStream_t s);

@@ -123,7 +123,21 @@ def test_large_windows_many_windows_per_workgroup(oracle, L, k, hw, heads, N):
     assert N % w.nW == 0
     x = synth.draw(w)
     bias = oracle.bias_gather(x["table"], w.k).astype(np.float32)
-    check_backward(oracle, w, bias, x["mask"], w.name, want_dbias=False)
+    check_backward(oracle, w, bias, x["mask"], w.name, want_dbias=True)
+
+
+@pytest.mark.parametrize("L", [65, 100, 144, 145, 177, 256])
+@pytest.mark.parametrize("use_bm", [False, True])
+def test_dbias_for_window_lengths_above_64(oracle, L, use_bm):
+    """dBias of large windows comes from a kernel of its own (row statistics handed over through
+    the workspace); 37 windows over at most 2 x 85 slots of partial sums, three heads."""
+    w = synth.Workload(f"bwd_db_L{L}", 36, L, 96, 3, "bf16", 5400 + L, 0, backward=True)
+    bias = synth.normal((3, L, L), 17 + L, 0.5) if use_bm else None
+    mask = None
+    if use_bm:
+        mask = np.where(synth.rng(19 + L).random((4, L, L)) < 0.2, -100.0, 0.0).astype(np.float32)
+        mask[:, np.arange(L), np.arange(L)] = 0.0
+    check_backward(oracle, w, bias, mask, f"L={L} bm={use_bm} dbias", want_dbias=True)
 
 
 @pytest.mark.parametrize("d", [64, 128, 256])
@@ -193,9 +207,9 @@ def test_unsupported_backward_cases_are_rejected():
     import torch
     import paper_2501_06480_amd as fwa
     from paper_2501_06480_amd import binding
-    q = torch.zeros((2, 144, 128), dtype=torch.bfloat16, device="cuda")
-    with pytest.raises(fwa.FwaError) as e:   # dBias exists only for windows of up to 64 tokens
-        fwa.fwa_backward(q, q.clone(), q.clone(), q.clone(), 4, 0.1, want_dbias=True)
+    q = torch.zeros((2, 144, 256), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(fwa.FwaError) as e:   # wide heads only for windows of up to 64 tokens
+        fwa.fwa_backward(q, q.clone(), q.clone(), q.clone(), 4, 0.1)
     assert e.value.code == binding.FWA_ERR_UNSUPPORTED
     q = torch.zeros((2, 49, 96), dtype=torch.float32, device="cuda")
     with pytest.raises(fwa.FwaError) as e:
