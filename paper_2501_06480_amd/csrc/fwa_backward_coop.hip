@@ -21,6 +21,7 @@
 // multiple of nW, so (bias[h] + mask[bw % nW]) * log2e is loaded once, into registers.
 #include "fwa_device.h"
 #include "fwa_internal.h"
+#include "fwa_softmax.h"
 
 namespace fwa {
 namespace {
@@ -149,36 +150,14 @@ __global__ void __launch_bounds__(64 * kCoopWavesPerTile * kCoopMaxHeads) bwd_bf
                 s[jb] = mfma_bf16(__builtin_bit_cast(bf16x8, lk[opd + 16 * jb * stride]), qop, zero);
                 dp[jb] = mfma_bf16(__builtin_bit_cast(bf16x8, lv[opd + 16 * jb * stride]), gop, zero);
             }
-#pragma unroll
-            for (int jb = 0; jb < NB; ++jb) {
-                if (BM) {
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) s[jb][r] = fmaf(s[jb][r], sl2, add[jb][r]);
-                } else {
-                    s[jb] *= sl2;
-                }
+            // softmax of the block's rows: s <- exp(score - rowmax), inv = 1 / rowsum
+            float inv;
+            if (BM) {
+                const AddendRegs<NB> addend = {add};
+                inv = softmax_block<NB, true>(s, sl2, addend, L, g);
+            } else {
+                inv = softmax_block<NB, false>(s, sl2, AddendNone{}, L, g);
             }
-#pragma unroll
-            for (int r = 0; r < 4; ++r)
-                if (16 * (NB - 1) + 4 * g + r >= L) s[NB - 1][r] = -INFINITY;
-            float m = s[0][0];
-#pragma unroll
-            for (int jb = 0; jb < NB; ++jb) {
-                m = fmaxf(fmaxf(m, s[jb][0]), s[jb][1]);
-                m = fmaxf(fmaxf(m, s[jb][2]), s[jb][3]);
-            }
-            m = max_over_g(m);
-            float sum = 0.f;
-#pragma unroll
-            for (int jb = 0; jb < NB; ++jb)
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const float e = __builtin_amdgcn_exp2f(s[jb][r] - m);
-                    s[jb][r] = e;
-                    sum += e;
-                }
-            sum = sum_over_g(sum);
-            const float inv = __builtin_amdgcn_rcpf(sum);
             float delta = 0.f;
 #pragma unroll
             for (int jb = 0; jb < NB; ++jb)

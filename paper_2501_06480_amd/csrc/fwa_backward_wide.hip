@@ -26,6 +26,7 @@
 // the same reduce kernel adds the slots.
 #include "fwa_device.h"
 #include "fwa_internal.h"
+#include "fwa_softmax.h"
 
 namespace fwa {
 namespace {
@@ -131,43 +132,18 @@ __global__ void __launch_bounds__(256) bwd_bf16_wide_kernel(BwdArgs p, uint32_t 
                 s[jb] = mfma_bf16(__builtin_bit_cast(bf16x8, sa[opd + 16 * jb * STRIDE + 4 * c]), qop[c], s[jb]);
                 dp[jb] = mfma_bf16(__builtin_bit_cast(bf16x8, sb[opd + 16 * jb * STRIDE + 4 * c]), gop[c], dp[jb]);
             }
+        // softmax of the block's rows: s <- exp(score - rowmax), inv = 1 / rowsum
+        float inv;
         if (BM) {
             const uint32_t ll = (uint32_t)L * L * 4u;
             const __amdgpu_buffer_rsrc_t rb = p.bias ? make_rsrc(p.bias + (size_t)h * L * L, ll) : make_rsrc(nullptr, 0);
             const __amdgpu_buffer_rsrc_t rm =
                 p.mask ? make_rsrc(p.mask + (size_t)(w % (uint32_t)p.nW) * L * L, ll) : make_rsrc(nullptr, 0);
-            const uint32_t off = (((uint32_t)(16 * qb + n)) * L + 4u * g) * 4u;
-#pragma unroll
-            for (int jb = 0; jb < NB; ++jb) {
-                const f32x4 add = (load_f32x4(rb, off + 16 * jb * 4u) + load_f32x4(rm, off + 16 * jb * 4u)) * kLog2e;
-#pragma unroll
-                for (int r = 0; r < 4; ++r) s[jb][r] = fmaf(s[jb][r], sl2, add[r]);
-            }
+            const AddendGlobal addend = {rb, rm, (((uint32_t)(16 * qb + n)) * L + 4u * g) * 4u};
+            inv = softmax_block<NB, true>(s, sl2, addend, L, g);
         } else {
-#pragma unroll
-            for (int jb = 0; jb < NB; ++jb) s[jb] *= sl2;
+            inv = softmax_block<NB, false>(s, sl2, AddendNone{}, L, g);
         }
-#pragma unroll
-        for (int r = 0; r < 4; ++r)
-            if (16 * (NB - 1) + 4 * g + r >= L) s[NB - 1][r] = -INFINITY;
-        float m = s[0][0];
-#pragma unroll
-        for (int jb = 0; jb < NB; ++jb) {
-            m = fmaxf(fmaxf(m, s[jb][0]), s[jb][1]);
-            m = fmaxf(fmaxf(m, s[jb][2]), s[jb][3]);
-        }
-        m = max_over_g(m);
-        float sum = 0.f;
-#pragma unroll
-        for (int jb = 0; jb < NB; ++jb)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const float e = __builtin_amdgcn_exp2f(s[jb][r] - m);
-                s[jb][r] = e;
-                sum += e;
-            }
-        sum = sum_over_g(sum);
-        const float inv = __builtin_amdgcn_rcpf(sum);
         float delta = 0.f;
 #pragma unroll
         for (int jb = 0; jb < NB; ++jb)

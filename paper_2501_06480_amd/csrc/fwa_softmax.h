@@ -1,5 +1,5 @@
 // Row softmax of one 16-query block in the "query on the lane" layout, shared by the
-// forward kernels.  Lane (g, n) holds s[jb][r] = <q_i, k_j> for query row i = i0 + n and
+// forward and backward kernels.  Lane (g, n) holds s[jb][r] = <q_i, k_j> for query row i = i0 + n and
 // key j = 16 jb + 4g + r; a row is spread over the 4 lanes that share n.
 #pragma once
 
