@@ -98,19 +98,20 @@ def time_other_workloads(torch, fwa, synth, dev):
 
     def run(name, w, backward, iters, want_dbias=True):
         shape = (w.N, w.L, w.C)
-        per_set = (7 if backward else 4) * w.N * w.L * w.C * 2
+        tdt, esz = (torch.float32, 4) if w.dtype == "f32" else (torch.bfloat16, 2)
+        per_set = (7 if backward else 4) * w.N * w.L * w.C * esz
         nsets = max(2, -(-2 * LLC_BYTES // per_set) + 1)
         g = torch.Generator(device=dev).manual_seed(w.seed)
-        sets = [[torch.randn(shape, device=dev, generator=g).to(torch.bfloat16) for _ in range(4 if backward else 3)]
+        sets = [[torch.randn(shape, device=dev, generator=g).to(tdt) for _ in range(4 if backward else 3)]
                 for _ in range(nsets)]
-        outs = [torch.empty(shape, device=dev, dtype=torch.bfloat16) for _ in range(nsets)]
+        outs = [torch.empty(shape, device=dev, dtype=tdt) for _ in range(nsets)]
         bias = mask = ws = None
         if w.use_bias:
             bias = fwa.fwa_bias_gather(torch.from_numpy(synth.bias_table(w.heads, w.k, w.seed)).to(dev), w.k)
         if w.shift:
             mask = torch.from_numpy(synth.shift_mask(w.map_hw, w.map_hw, w.k, w.shift)).to(dev)
         if backward:
-            need = fwa.fwa_backward_workspace_bytes(w.N, w.L, w.C, w.heads, 1, want_dbias)
+            need = fwa.fwa_backward_workspace_bytes(w.N, w.L, w.C, w.heads, 0 if w.dtype == "f32" else 1, want_dbias)
             ws = torch.empty(max(need, 16), dtype=torch.uint8, device=dev)
 
         def step(i):
@@ -131,7 +132,7 @@ def time_other_workloads(torch, fwa, synth, dev):
         torch.cuda.synchronize()
         us = e0.elapsed_time(e1) / iters * 1e3
         wh = w.N * w.heads
-        algo = (7 if backward else 4) * w.L * (w.C // w.heads) * 2 * wh
+        algo = (7 if backward else 4) * w.L * (w.C // w.heads) * esz * wh
         out.append({"workload": name, "us_per_call": round(us, 2), "window_heads_per_s": wh / us * 1e6,
                     "algorithmic_GBps": algo / us / 1e3, "frac_of_hbm_peak": algo / us / 1e3 / HBM_PEAK_GBPS})
 
@@ -187,6 +188,10 @@ def time_other_workloads(torch, fwa, synth, dev):
         pw = synth.Workload(f"paper_L64_d{d}", 4096, 64, 4 * d, 4, "bf16", 1100 + d, 8)
         run(f"paper_benchmark_shape_fwd (N=4096, L=64, 4 heads x {d})", pw, False, 50)
         run(f"paper_benchmark_shape_bwd (N=4096, L=64, 4 heads x {d}; dQ, dK, dV)", pw, True, 30, want_dbias=False)
+        # the same in the paper's own precision (fp32 data and arithmetic), half the windows
+        pf = synth.Workload(f"paper_L64_d{d}_f32", 2048, 64, 4 * d, 4, "f32", 1200 + d, 8)
+        run(f"paper_benchmark_shape_fwd_fp32 (N=2048, L=64, 4 heads x {d})", pf, False, 20)
+        run(f"paper_benchmark_shape_bwd_fp32 (N=2048, L=64, 4 heads x {d}; dQ, dK, dV)", pf, True, 10, want_dbias=False)
     return out
 
 

@@ -19,9 +19,9 @@
  *    (a hipStream_t passed as void*; NULL = the default stream) and returns.
  *  - Tensors are contiguous, row-major.  Q, K, V, O, dO, dQ, dK, dV are
  *    [N, L, C]; head h owns channels [h*d, (h+1)*d) with d = C / heads.
- *    Supported: d == 32 with 1 <= L <= 256; with FWA_BF16 also d == 64, 128,
- *    256 with 1 <= L <= 64 (the feature-dimension loop of paper eq. 5-6; the
- *    shapes of its Section 3.1 benchmark).  N >= 0 (N == 0 is a no-op).
+ *    Supported: d == 32 with 1 <= L <= 256; d == 64, 128, 256 with
+ *    1 <= L <= 64 (the feature-dimension loop of paper eq. 5-6; the shapes of
+ *    its Section 3.1 benchmark), in both dtypes.  N >= 0 (N == 0 is a no-op).
  *  - dtype is FWA_F32 (fp32 data, fp32 arithmetic) or FWA_BF16 (bf16 data,
  *    bf16 matrix-core products with fp32 accumulation, fp32 softmax, one final
  *    round-to-nearest-even to bf16).
@@ -83,8 +83,8 @@ int fwa_forward_strided(const void* q, const void* k, const void* v, void* o,
 
 /*
  * Backward pass (paper Algorithm 2).  Inputs are Q, K, V and dO only.
- * Supported: dtype FWA_BF16 in every shape the forward takes; fp32 data
- * returns FWA_ERR_UNSUPPORTED.
+ * Supported: FWA_BF16 in every shape the forward takes; FWA_F32 for
+ * L <= 64 without dbias (FWA_ERR_UNSUPPORTED otherwise).
  *   d_o        : in,  [N, L, C], dtype
  *   dq, dk, dv : out, [N, L, C], dtype, fully overwritten
  *   dbias      : NULL, or out [heads, L, L] fp32 = sum over all N windows of

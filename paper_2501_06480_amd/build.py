@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OUT = os.path.join(HERE, "libfwa.so")
 OBJ_DIR = os.path.join(HERE, "_build")
-SOURCES = ["fwa_api.hip", "fwa_forward.hip", "fwa_forward_staged.hip", "fwa_forward_wide.hip", "fwa_backward.hip",
+SOURCES = ["fwa_api.hip", "fwa_forward.hip", "fwa_forward_staged.hip", "fwa_forward_wide.hip", "fwa_f32_tile.hip", "fwa_backward.hip",
            "fwa_backward_coop.hip", "fwa_backward_large.hip", "fwa_backward_wide.hip", "fwa_bias.hip"]
 # packed fp32 VALU ops are switched off on purpose: the compiler must not form them
 # and matrix-core results go to ordinary VGPRs (no accumulator-register copies).

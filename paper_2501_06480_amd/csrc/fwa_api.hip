@@ -8,14 +8,13 @@ namespace {
 inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
 
 // Shape checks shared by forward, backward and the workspace query.
-// Head width 32 everywhere; the bf16 forward and backward also take 64, 128 and 256 for
-// L <= 64 (`wide_ok` = the call is one of those).
+// Head width 32 everywhere; 64, 128 and 256 for L <= 64 (`wide_ok`: every forward and backward call).
 int check_shape(int64_t N, int L, int C, int heads, int dtype, bool wide_ok) {
     if (N < 0 || L < 1 || C < 1 || heads < 1) return FWA_ERR_SHAPE;
     if (C % heads != 0) return FWA_ERR_SHAPE;
     if (dtype != FWA_F32 && dtype != FWA_BF16) return FWA_ERR_UNSUPPORTED;
     if (C / heads != fwa::kHeadDim &&
-        !(wide_ok && dtype == FWA_BF16 && fwa::forward_wide_supported(L, C / heads)))
+        !(wide_ok && fwa::forward_wide_supported(L, C / heads)))
         return FWA_ERR_UNSUPPORTED;
     if (L > fwa::kMaxL) return FWA_ERR_UNSUPPORTED;
     // one launch: the number of wave tasks (at most 4 per window-head) must fit a 32-bit grid
@@ -23,9 +22,10 @@ int check_shape(int64_t N, int L, int C, int heads, int dtype, bool wide_ok) {
     return FWA_OK;
 }
 
-// The backward covers bf16 data.
-int check_backward_support(int, int dtype, bool) {
-    if (dtype != FWA_BF16) return FWA_ERR_UNSUPPORTED;
+// The backward covers bf16 data in every shape of the forward, and fp32 data for windows of up to
+// 64 tokens without dBias.
+int check_backward_support(int L, int dtype, bool want_dbias) {
+    if (dtype != FWA_BF16 && (L > fwa::kMaxWideL || want_dbias)) return FWA_ERR_UNSUPPORTED;
     return FWA_OK;
 }
 
@@ -91,9 +91,9 @@ int fwa_forward_strided(const void* q, const void* k, const void* v, void* o, in
     a.N = N; a.L = L; a.C = C; a.heads = heads; a.nW = mask ? nW : 1; a.scale = scale;
     a.ldq = (int)ld_qkv; a.ldo = (int)ld_o;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    const hipError_t e = dtype != FWA_BF16            ? fwa::launch_forward_f32(a, st)
-                         : C / heads != fwa::kHeadDim ? fwa::launch_forward_bf16_wide(a, st)
-                                                      : fwa::launch_forward_bf16(a, st);
+    const bool wide = C / heads != fwa::kHeadDim;
+    const hipError_t e = dtype != FWA_BF16 ? (wide || L <= fwa::kMaxWideL ? fwa::launch_forward_f32_tile(a, st) : fwa::launch_forward_f32(a, st))
+                                           : (wide ? fwa::launch_forward_bf16_wide(a, st) : fwa::launch_forward_bf16(a, st));
     return e == hipSuccess ? FWA_OK : FWA_ERR_LAUNCH;
 }
 

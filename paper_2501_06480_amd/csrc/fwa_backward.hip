@@ -439,6 +439,5 @@ hipError_t launch_dbias_reduce(const BwdArgs& a, hipStream_t s, bool key_on_lane
     return hipGetLastError();
 }
 
-hipError_t launch_backward_f32(const BwdArgs&, hipStream_t) { return hipErrorNotSupported; }
 
 }  // namespace fwa

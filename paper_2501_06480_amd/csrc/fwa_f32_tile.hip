@@ -1,0 +1,394 @@
+// fp32 kernels for windows of up to 64 tokens and head widths 32, 64, 128, 256, forward and
+// backward (longer windows of width 32 have a forward kernel of their own in fwa_forward.hip).  True fp32 arithmetic throughout: v_mfma_f32_16x16x4_f32 products, v_exp_f32, IEEE
+// division.  These are the shapes and the precision of the paper's kernel benchmark
+// (section 3.1); they are written for correctness and reasonable speed, not tuned like the bf16
+// paths.
+//
+// One workgroup per (window, head), one wave per block of 16 rows.  The fp32 matrix instruction
+// takes one value per lane and k-slot group: lane (g, n) gives A[m = n][k = g] and B[k = g][n] and
+// receives D[4g + r][n].  A 16-byte LDS or global read of 4 consecutive channels therefore feeds
+// 4 successive instructions (k-slot g of step t standing for channel 16 c + 4g + t), which is how
+// row operands are read; operands with the contraction index on the rows of a slab (V^T, K^T,
+// dO^T, Q^T) are read element by element out of LDS.
+//
+// Backward: as for large bf16 windows the score tile is produced twice, in the two orientations
+// the outputs need, instead of being transposed: pass 1 ("query on the lane") gives the softmax
+// statistics and dQ with K, V parked in LDS; pass 2 ("key on the lane") gives dV and dK with Q, dO
+// parked in their place.  dBias is not produced in fp32.
+#include "fwa_device.h"
+#include "fwa_internal.h"
+
+namespace fwa {
+namespace {
+
+// slab row stride in floats: D + 4, an odd number of 16-byte units, so that 16-byte reads of 8
+// consecutive rows fall into different banks
+template <int D>
+struct F32Tile {
+    static constexpr int RS = D + 4;
+    static constexpr int TPR = D / 4;          // threads that move one row (16 bytes each)
+    static constexpr int RPP = 256 / TPR;      // rows per pass of the workgroup (TPR <= 64)
+    static constexpr int CH = D / 16;          // 16-channel chunks
+};
+
+// Copy rows [0, ROWS) x D floats of a tile into an LDS slab; rows beyond L arrive as zeros.
+template <int D, int ROWS>
+__device__ __forceinline__ void park_slab(float* slab, const __amdgpu_buffer_rsrc_t r, uint32_t row_bytes, int tid) {
+    using T = F32Tile<D>;
+    constexpr int PASSES = (ROWS + T::RPP - 1) / T::RPP;
+    const uint32_t srow = (uint32_t)tid / T::TPR, scol = (uint32_t)tid % T::TPR;
+    f32x4 v[PASSES];
+#pragma unroll
+    for (int t = 0; t < PASSES; ++t) v[t] = load_f32x4(r, (T::RPP * t + srow) * row_bytes + scol * 16u);
+#pragma unroll
+    for (int t = 0; t < PASSES; ++t) {
+        const uint32_t row = T::RPP * t + srow;
+        if (row < (uint32_t)ROWS) *reinterpret_cast<f32x4*>(slab + row * T::RS + 4 * scol) = v[t];
+    }
+}
+
+// acc[jb] += X[16 jb + n][:] . own[:] over all channels: X rows from an LDS slab (A operand),
+// `own` the 16 rows of this wave (B operand, in registers)
+template <int NB, int D>
+__device__ __forceinline__ void rows_times_own(f32x4 (&acc)[NB], const float* slab, const f32x4 (&own)[D / 16], int n, int g) {
+    using T = F32Tile<D>;
+#pragma unroll
+    for (int c = 0; c < T::CH; ++c)
+#pragma unroll
+        for (int jb = 0; jb < NB; ++jb) {
+            const f32x4 x = *reinterpret_cast<const f32x4*>(slab + (16 * jb + n) * T::RS + 16 * c + 4 * g);
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const float a = x[t], b = own[c][t];
+                acc[jb] = mfma_f32(a, b, acc[jb]);
+            }
+        }
+}
+
+// the 16 rows 16 blk + n of a tile as operands: channels 16 c + 4g .. + 3 per chunk
+template <int D>
+__device__ __forceinline__ void load_own_rows(f32x4 (&own)[D / 16], const __amdgpu_buffer_rsrc_t r, uint32_t row_bytes,
+                                              int blk, int n, int g) {
+    const uint32_t off = (uint32_t)(16 * blk + n) * row_bytes + 16u * g;
+#pragma unroll
+    for (int c = 0; c < D / 16; ++c) own[c] = load_f32x4(r, off + 64 * c);
+}
+
+// scores of a block of 16 query rows -> probabilities; returns nothing, leaves P in s and the
+// statistics in m (row max of the scaled scores, natural units) and sum
+template <int NB, bool BM>
+__device__ __forceinline__ void softmax_f32(f32x4 (&s)[NB], float scale, const __amdgpu_buffer_rsrc_t rb,
+                                            const __amdgpu_buffer_rsrc_t rm, uint32_t off_b, int L, int g, float& m,
+                                            float& sum) {
+    m = -INFINITY;
+#pragma unroll
+    for (int jb = 0; jb < NB; ++jb) {
+        f32x4 add = {0.f, 0.f, 0.f, 0.f};
+        if (BM) add = load_f32x4(rb, off_b + 16 * jb * 4u) + load_f32x4(rm, off_b + 16 * jb * 4u);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            float x = s[jb][r] * scale + add[r];
+            if (jb == NB - 1 && 16 * jb + 4 * g + r >= L) x = -INFINITY;
+            s[jb][r] = x;
+            m = fmaxf(m, x);
+        }
+    }
+    m = max_over_g(m);
+    sum = 0.f;
+#pragma unroll
+    for (int jb = 0; jb < NB; ++jb)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const float e = __builtin_amdgcn_exp2f((s[jb][r] - m) * kLog2e);
+            s[jb][r] = e;
+            sum += e;
+        }
+    sum = sum_over_g(sum);
+}
+
+// ------------------------------------------------------------------ forward
+template <int NB, int D, bool BM>
+__global__ void __launch_bounds__(256) fwd_f32_tile_kernel(FwdArgs p) {
+    using T = F32Tile<D>;
+    constexpr int ROWS = 16 * NB;
+    extern __shared__ __attribute__((aligned(16))) float ldsf[];  // [K, V][ROWS][RS]
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int n = lane & 15, g = lane >> 4;
+    const int qb = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const uint32_t w = blockIdx.x / (uint32_t)p.heads, h = blockIdx.x % (uint32_t)p.heads;
+    const int L = p.L;
+    const uint32_t row_bytes = (uint32_t)p.ldq * 4u, row_out = (uint32_t)p.ldo * 4u;
+    const size_t tile = ((size_t)w * L * p.ldq + (size_t)h * D) * 4u;
+    const uint32_t tile_bytes = (uint32_t)(L - 1) * row_bytes + 4u * D;
+    float* const lk = ldsf;
+    float* const lv = ldsf + ROWS * T::RS;
+
+    f32x4 qv[T::CH];
+    load_own_rows<D>(qv, make_rsrc((const char*)p.q + tile, tile_bytes), row_bytes, qb, n, g);
+    park_slab<D, ROWS>(lk, make_rsrc((const char*)p.k + tile, tile_bytes), row_bytes, tid);
+    park_slab<D, ROWS>(lv, make_rsrc((const char*)p.v + tile, tile_bytes), row_bytes, tid);
+    __syncthreads();
+    if (qb >= NB) return;  // no barrier follows
+
+    f32x4 s[NB];
+#pragma unroll
+    for (int jb = 0; jb < NB; ++jb) s[jb] = f32x4{0.f, 0.f, 0.f, 0.f};
+    rows_times_own<NB, D>(s, lk, qv, n, g);  // S[16 qb + n][16 jb + 4g + r]
+
+    __amdgpu_buffer_rsrc_t rb = make_rsrc(nullptr, 0), rm = make_rsrc(nullptr, 0);
+    if (BM) {
+        const uint32_t ll = (uint32_t)L * L * 4u;
+        if (p.bias) rb = make_rsrc(p.bias + (size_t)h * L * L, ll);
+        if (p.mask) rm = make_rsrc(p.mask + (size_t)(w % (uint32_t)p.nW) * L * L, ll);
+    }
+    float m, sum;
+    softmax_f32<NB, BM>(s, p.scale, rb, rm, (((uint32_t)(16 * qb + n)) * L + 4u * g) * 4u, L, g, m, sum);
+
+    // O^T = V^T P^T, 16 channels at a time: k-slot g of step (jb, r) stands for key 16 jb + 4g + r
+    const __amdgpu_buffer_rsrc_t ro =
+        make_rsrc((char*)p.o + ((size_t)w * L * p.ldo + (size_t)h * D) * 4u, (uint32_t)(L - 1) * row_out + 4u * D);
+    const uint32_t off_o = (uint32_t)(16 * qb + n) * row_out + 16u * g;
+#pragma unroll
+    for (int cb = 0; cb < T::CH; ++cb) {
+        f32x4 o = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int jb = 0; jb < NB; ++jb)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const float pv = s[jb][r];
+                o = mfma_f32(lv[(16 * jb + 4 * g + r) * T::RS + 16 * cb + n], pv, o);  // o[r'] = O[16 qb + n][16 cb + 4g + r']
+            }
+        store_f32x4(o / sum, ro, off_o + 64 * cb);
+    }
+}
+
+// ----------------------------------------------------------------- backward
+template <int NB, int D, bool BM>
+__global__ void __launch_bounds__(256) bwd_f32_tile_kernel(BwdArgs p) {
+    using T = F32Tile<D>;
+    constexpr int ROWS = 16 * NB;
+    extern __shared__ __attribute__((aligned(16))) float ldsf[];  // two slabs [ROWS][RS], then M[ROWS], delta[ROWS]
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int n = lane & 15, g = lane >> 4;
+    const int role = __builtin_amdgcn_readfirstlane(tid >> 6);  // query block in pass 1, key block in pass 2
+    const bool active = role < NB;
+    const uint32_t w = blockIdx.x / (uint32_t)p.heads, h = blockIdx.x % (uint32_t)p.heads;
+    const int L = p.L;
+    const uint32_t row_bytes = (uint32_t)p.ldq * 4u, row_g = (uint32_t)p.ldg * 4u, row_d = (uint32_t)p.ldd * 4u;
+    const size_t tile = ((size_t)w * L * p.ldq + (size_t)h * D) * 4u;
+    const size_t tile_g = ((size_t)w * L * p.ldg + (size_t)h * D) * 4u;
+    const size_t tile_d = ((size_t)w * L * p.ldd + (size_t)h * D) * 4u;
+    const uint32_t tile_bytes = (uint32_t)(L - 1) * row_bytes + 4u * D;
+    const uint32_t tile_bytes_g = (uint32_t)(L - 1) * row_g + 4u * D;
+    const uint32_t tile_bytes_d = (uint32_t)(L - 1) * row_d + 4u * D;
+    const __amdgpu_buffer_rsrc_t rq = make_rsrc((const char*)p.q + tile, tile_bytes);
+    const __amdgpu_buffer_rsrc_t rk = make_rsrc((const char*)p.k + tile, tile_bytes);
+    const __amdgpu_buffer_rsrc_t rv = make_rsrc((const char*)p.v + tile, tile_bytes);
+    const __amdgpu_buffer_rsrc_t rg = make_rsrc((const char*)p.d_o + tile_g, tile_bytes_g);
+    float* const sa = ldsf;                   // K, then Q
+    float* const sb = ldsf + ROWS * T::RS;    // V, then dO
+    float* const stM = ldsf + 2 * ROWS * T::RS;
+    float* const stD = stM + ROWS;
+    const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+
+    __amdgpu_buffer_rsrc_t rb = make_rsrc(nullptr, 0), rm = make_rsrc(nullptr, 0);
+    if (BM) {
+        const uint32_t ll = (uint32_t)L * L * 4u;
+        if (p.bias) rb = make_rsrc(p.bias + (size_t)h * L * L, ll);
+        if (p.mask) rm = make_rsrc(p.mask + (size_t)(w % (uint32_t)p.nW) * L * L, ll);
+    }
+
+    park_slab<D, ROWS>(sa, rk, row_bytes, tid);
+    park_slab<D, ROWS>(sb, rv, row_bytes, tid);
+    __syncthreads();
+
+    // ---------------- pass 1: query block `role` ----------------
+    if (active) {
+        const int qb = role;
+        f32x4 qv[T::CH], gv[T::CH];
+        load_own_rows<D>(qv, rq, row_bytes, qb, n, g);
+        load_own_rows<D>(gv, rg, row_g, qb, n, g);
+        f32x4 s[NB], dp[NB];
+#pragma unroll
+        for (int jb = 0; jb < NB; ++jb) s[jb] = dp[jb] = zero;
+        rows_times_own<NB, D>(s, sa, qv, n, g);   // <k_j, q_i>: query i = 16 qb + n, key j = 16 jb + 4g + r
+        rows_times_own<NB, D>(dp, sb, gv, n, g);  // <v_j, do_i>
+        float m, sum;
+        softmax_f32<NB, BM>(s, p.scale, rb, rm, (((uint32_t)(16 * qb + n)) * L + 4u * g) * 4u, L, g, m, sum);
+        float delta = 0.f;
+#pragma unroll
+        for (int jb = 0; jb < NB; ++jb)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                s[jb][r] = s[jb][r] / sum;  // P
+                delta = fmaf(s[jb][r], dp[jb][r], delta);
+            }
+        delta = sum_over_g(delta);
+        if (g == 0) {
+            stM[16 * qb + n] = m + logf(sum);  // p_ij = exp(score_ij - M_i)
+            stD[16 * qb + n] = delta;
+        }
+#pragma unroll
+        for (int jb = 0; jb < NB; ++jb)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) dp[jb][r] = s[jb][r] * (dp[jb][r] - delta);  // dS
+        // dQ^T = K^T dS^T, 16 channels at a time: k-slot g of step (jb, r) stands for key 16 jb + 4g + r
+        const __amdgpu_buffer_rsrc_t rdq = make_rsrc((char*)p.dq + tile_d, tile_bytes_d);
+        const uint32_t off_q = (uint32_t)(16 * qb + n) * row_d + 16u * g;
+#pragma unroll
+        for (int cb = 0; cb < T::CH; ++cb) {
+            f32x4 acc = zero;
+#pragma unroll
+            for (int jb = 0; jb < NB; ++jb)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const float ds = dp[jb][r];
+                    acc = mfma_f32(sa[(16 * jb + 4 * g + r) * T::RS + 16 * cb + n], ds, acc);
+                }
+            store_f32x4(acc * p.scale, rdq, off_q + 64 * cb);  // acc[r'] = dQ[16 qb + n][16 cb + 4g + r']
+        }
+    }
+    __syncthreads();  // K, V no longer needed; statistics complete
+    park_slab<D, ROWS>(sa, rq, row_bytes, tid);
+    park_slab<D, ROWS>(sb, rg, row_g, tid);
+    __syncthreads();
+
+    // ---------------- pass 2: key block `role` ----------------
+    if (active) {
+        const int jb = role;
+        f32x4 kv[T::CH], vv[T::CH];
+        load_own_rows<D>(kv, rk, row_bytes, jb, n, g);
+        load_own_rows<D>(vv, rv, row_bytes, jb, n, g);
+        const uint32_t jcol = 16u * jb + n;
+        const bool valid = jcol < (uint32_t)L;
+        f32x4 av[T::CH], ak[T::CH];  // dV, dK [16 jb + n][16 cb + 4g + r]
+#pragma unroll
+        for (int cb = 0; cb < T::CH; ++cb) av[cb] = ak[cb] = zero;
+#pragma unroll
+        for (int qb = 0; qb < NB; ++qb) {
+            // S = Q K^T and dP = dO V^T with the query on the slot: sc[r] = <q_i, k_j>, i = 16 qb + 4g + r, j = jcol
+            f32x4 sc = zero, dp = zero;
+#pragma unroll
+            for (int c = 0; c < T::CH; ++c) {
+                const f32x4 xq = *reinterpret_cast<const f32x4*>(sa + (16 * qb + n) * T::RS + 16 * c + 4 * g);
+                const f32x4 xg = *reinterpret_cast<const f32x4*>(sb + (16 * qb + n) * T::RS + 16 * c + 4 * g);
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    const float a = xq[t], b = kv[c][t], a2 = xg[t], b2 = vv[c][t];
+                    sc = mfma_f32(a, b, sc);
+                    dp = mfma_f32(a2, b2, dp);
+                }
+            }
+            const f32x4 M4 = *reinterpret_cast<const f32x4*>(stM + 16 * qb + 4 * g);
+            const f32x4 D4 = *reinterpret_cast<const f32x4*>(stD + 16 * qb + 4 * g);
+            f32x4 pr, ds;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                float x = sc[r] * p.scale;
+                if (BM) {
+                    const uint32_t off = ((uint32_t)(16 * qb + 4 * g + r) * L + jcol) * 4u;  // rows beyond L: outside, zero
+                    x += load_f32(rb, off) + load_f32(rm, off);
+                }
+                pr[r] = valid ? __builtin_amdgcn_exp2f((x - M4[r]) * kLog2e) : 0.f;
+                ds[r] = pr[r] * (dp[r] - D4[r]);
+            }
+            // dV^T += dO^T P, dK^T += Q^T dS: k-slot g of step r stands for query 16 qb + 4g + r
+#pragma unroll
+            for (int cb = 0; cb < T::CH; ++cb)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const float pp = pr[r], dd = ds[r];
+                    av[cb] = mfma_f32(sb[(16 * qb + 4 * g + r) * T::RS + 16 * cb + n], pp, av[cb]);
+                    ak[cb] = mfma_f32(sa[(16 * qb + 4 * g + r) * T::RS + 16 * cb + n], dd, ak[cb]);
+                }
+        }
+        const __amdgpu_buffer_rsrc_t rdv = make_rsrc((char*)p.dv + tile_d, tile_bytes_d);
+        const __amdgpu_buffer_rsrc_t rdk = make_rsrc((char*)p.dk + tile_d, tile_bytes_d);
+        const uint32_t off_k = (uint32_t)(16 * jb + n) * row_d + 16u * g;
+#pragma unroll
+        for (int cb = 0; cb < T::CH; ++cb) {
+            store_f32x4(av[cb], rdv, off_k + 64 * cb);
+            store_f32x4(ak[cb] * p.scale, rdk, off_k + 64 * cb);
+        }
+    }
+}
+
+template <int NB, int D>
+size_t f32_slab_bytes() {
+    return (size_t)2 * 16 * NB * (D + 4) * 4;
+}
+
+template <int NB, int D>
+hipError_t launch_fwd_nb(const FwdArgs& a, hipStream_t st) {
+    const unsigned grid = (unsigned)(a.N * a.heads);
+    const size_t lds = f32_slab_bytes<NB, D>();
+    const bool bm = a.bias || a.mask;
+    const void* fn = bm ? reinterpret_cast<const void*>(&fwd_f32_tile_kernel<NB, D, true>)
+                        : reinterpret_cast<const void*>(&fwd_f32_tile_kernel<NB, D, false>);
+    if (lds > 64 * 1024) {
+        const hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+    }
+    if (bm)
+        hipLaunchKernelGGL((fwd_f32_tile_kernel<NB, D, true>), dim3(grid), dim3(256), lds, st, a);
+    else
+        hipLaunchKernelGGL((fwd_f32_tile_kernel<NB, D, false>), dim3(grid), dim3(256), lds, st, a);
+    return hipGetLastError();
+}
+
+template <int NB, int D>
+hipError_t launch_bwd_nb(const BwdArgs& a, hipStream_t st) {
+    const unsigned grid = (unsigned)(a.N * a.heads);
+    const size_t lds = f32_slab_bytes<NB, D>() + (size_t)2 * 16 * NB * 4;
+    const bool bm = a.bias || a.mask;
+    const void* fn = bm ? reinterpret_cast<const void*>(&bwd_f32_tile_kernel<NB, D, true>)
+                        : reinterpret_cast<const void*>(&bwd_f32_tile_kernel<NB, D, false>);
+    if (lds > 64 * 1024) {
+        const hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+    }
+    if (bm)
+        hipLaunchKernelGGL((bwd_f32_tile_kernel<NB, D, true>), dim3(grid), dim3(256), lds, st, a);
+    else
+        hipLaunchKernelGGL((bwd_f32_tile_kernel<NB, D, false>), dim3(grid), dim3(256), lds, st, a);
+    return hipGetLastError();
+}
+
+#define FWA_F32_NB_SWITCH(FN, D, a, s)            \
+    switch (((a).L + 15) / 16) {                  \
+        case 1: return FN<1, D>(a, s);            \
+        case 2: return FN<2, D>(a, s);            \
+        case 3: return FN<3, D>(a, s);            \
+        case 4: return FN<4, D>(a, s);            \
+        default: return hipErrorInvalidValue;     \
+    }
+
+template <int D>
+hipError_t fwd_d(const FwdArgs& a, hipStream_t s) { FWA_F32_NB_SWITCH(launch_fwd_nb, D, a, s) }
+template <int D>
+hipError_t bwd_d(const BwdArgs& a, hipStream_t s) { FWA_F32_NB_SWITCH(launch_bwd_nb, D, a, s) }
+
+}  // namespace
+
+hipError_t launch_forward_f32_tile(const FwdArgs& a, hipStream_t s) {
+    switch (a.C / a.heads) {
+        case 32: return fwd_d<32>(a, s);
+        case 64: return fwd_d<64>(a, s);
+        case 128: return fwd_d<128>(a, s);
+        case 256: return fwd_d<256>(a, s);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+hipError_t launch_backward_f32(const BwdArgs& a, hipStream_t s) {
+    if (a.dbias != nullptr || a.L > kMaxWideL) return hipErrorNotSupported;
+    switch (a.C / a.heads) {
+        case 32: return bwd_d<32>(a, s);
+        case 64: return bwd_d<64>(a, s);
+        case 128: return bwd_d<128>(a, s);
+        case 256: return bwd_d<256>(a, s);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace fwa

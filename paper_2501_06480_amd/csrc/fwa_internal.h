@@ -59,6 +59,7 @@ struct BwdArgs {
 // Each returns a hipError_t from the launch (hipSuccess when enqueued).
 hipError_t launch_forward_bf16(const FwdArgs& a, hipStream_t s);
 hipError_t launch_forward_f32(const FwdArgs& a, hipStream_t s);
+hipError_t launch_forward_f32_tile(const FwdArgs& a, hipStream_t s);
 int staged_heads_per_block(int L, int heads);
 hipError_t launch_forward_bf16_staged(const FwdArgs& a, hipStream_t s);
 bool forward_wide_supported(int L, int head_dim);

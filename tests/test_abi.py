@@ -65,7 +65,7 @@ def test_forward_rejects_bad_arguments(lib):
     assert fwd(lib, C=100, heads=3) == b.FWA_ERR_SHAPE
     assert fwd(lib, C=48, heads=3) == b.FWA_ERR_UNSUPPORTED       # head dim 16
     assert fwd(lib, C=288, heads=3) == b.FWA_ERR_UNSUPPORTED      # head dim 96
-    assert fwd(lib, C=192, heads=3, dtype=0) == b.FWA_ERR_UNSUPPORTED   # head dim 64 in fp32
+    assert fwd(lib, C=192, heads=3, dtype=0, L=65) == b.FWA_ERR_UNSUPPORTED   # head dim 64 beyond one tile, fp32
     assert fwd(lib, C=192, heads=3, L=65) == b.FWA_ERR_UNSUPPORTED      # head dim 64 beyond one tile
     assert fwd(lib, L=257) == b.FWA_ERR_UNSUPPORTED
     assert fwd(lib, dtype=2) == b.FWA_ERR_UNSUPPORTED

@@ -166,6 +166,31 @@ def test_wide_heads_dbias_over_many_windows(oracle, d, L, N):
     check_backward(oracle, w, bias, mask, f"d={d} L={L} N={N} dbias", want_dbias=True)
 
 
+@pytest.mark.parametrize("d", [32, 64, 128, 256])
+@pytest.mark.parametrize("L", [64, 49, 17, 5])
+@pytest.mark.parametrize("use_bm", [False, True])
+def test_fp32_backward(oracle, d, L, use_bm):
+    """fp32 data, fp32 arithmetic: the precision of the paper's own kernel benchmark; 1e-5 max-abs."""
+    import torch
+    import paper_2501_06480_amd as fwa
+    heads = 2
+    w = synth.Workload(f"bwd_f32_d{d}_L{L}", 5, L, d * heads, heads, "f32", 8300 + d + L, 0, backward=True)
+    x = synth.draw(w)
+    bias = mask = None
+    if use_bm:
+        bias = synth.normal((heads, L, L), 83 + L, 0.5)
+        mask = np.where(synth.rng(89 + L + d).random((5, L, L)) < 0.2, -100.0, 0.0).astype(np.float32)
+        mask[:, np.arange(L), np.arange(L)] = 0.0
+    q, k, v, g = (to_device(x, w, n) for n in ("q", "k", "v", "d_o"))
+    dq, dk, dv, _ = fwa.fwa_backward(q, k, v, g, heads, w.scale, f32_device(bias), f32_device(mask))
+    torch.cuda.synchronize()
+    ref = oracle.backward(x["q"], x["k"], x["v"], x["d_o"], heads, w.scale, bias, mask)
+    errs = {nme: max_abs(to_f64(got), want) for nme, got, want in (("dq", dq, ref[0]), ("dk", dk, ref[1]), ("dv", dv, ref[2]))}
+    print(f"f32 d={d} L={L} bm={use_bm}: " + " ".join(f"{a}={b:.2e}" for a, b in errs.items()), flush=True)
+    for nme, e in errs.items():
+        assert e <= TOL["f32"], (nme, e)
+
+
 def test_backward_is_bit_reproducible():
     import torch
     import paper_2501_06480_amd as fwa
@@ -212,7 +237,11 @@ def test_unsupported_backward_cases_are_rejected():
         fwa.fwa_backward(q, q.clone(), q.clone(), q.clone(), 4, 0.1)
     assert e.value.code == binding.FWA_ERR_UNSUPPORTED
     q = torch.zeros((2, 49, 96), dtype=torch.float32, device="cuda")
-    with pytest.raises(fwa.FwaError) as e:
+    with pytest.raises(fwa.FwaError) as e:   # no dBias in fp32
+        fwa.fwa_backward(q, q.clone(), q.clone(), q.clone(), 3, 0.1, want_dbias=True)
+    assert e.value.code == binding.FWA_ERR_UNSUPPORTED
+    q = torch.zeros((2, 100, 96), dtype=torch.float32, device="cuda")
+    with pytest.raises(fwa.FwaError) as e:   # fp32 backward only for windows of up to 64 tokens
         fwa.fwa_backward(q, q.clone(), q.clone(), q.clone(), 3, 0.1)
     assert e.value.code == binding.FWA_ERR_UNSUPPORTED
 
