@@ -119,3 +119,21 @@ def test_binding_refuses_cpu_tensors():
     q = torch.zeros((2, 49, 96), dtype=torch.bfloat16)
     with pytest.raises((TypeError, RuntimeError, AssertionError)):
         fwa.fwa_forward(q, q, q, 3, 0.1)
+
+
+def test_strided_entry_points_check_their_strides(lib):
+    from paper_2501_06480_amd import binding as b
+    fwd = lambda ldq, ldo, dtype=1: lib.fwa_forward_strided(P, P + 0x1000, P + 0x2000, P + 0x3000, 4, 49, 96, 3, 0.1,
+                                                            ldq, ldo, None, None, 0, dtype, None)
+    assert fwd(95, 96) == b.FWA_ERR_SHAPE            # rows would overlap
+    assert fwd(288, 88) == b.FWA_ERR_SHAPE
+    assert fwd(100, 96) == b.FWA_ERR_ALIGN           # bf16 rows must stay 16-byte aligned: multiples of 8
+    assert fwd(98, 96, dtype=0) == b.FWA_ERR_ALIGN   # fp32: multiples of 4
+    assert fwd(1 << 21, 96) == b.FWA_ERR_UNSUPPORTED
+    bwd = lambda ldq, ldg, ldd: lib.fwa_backward_strided(P, P + 0x1000, P + 0x2000, P + 0x3000, P + 0x4000, P + 0x5000,
+                                                         P + 0x6000, None, 4, 49, 96, 3, 0.1, ldq, ldg, ldd, None, None,
+                                                         0, 1, None, 0, None)
+    assert bwd(288, 90, 288) == b.FWA_ERR_SHAPE
+    assert bwd(288, 96, 100) == b.FWA_ERR_ALIGN
+    assert bwd(95, 96, 96) == b.FWA_ERR_SHAPE
+
