@@ -66,6 +66,9 @@ class Oracle:
         lib.fwa_oracle_bias_gather.argtypes = [_dp, _dp, ctypes.c_int, ctypes.c_int]
         lib.fwa_oracle_bias_scatter.restype = ctypes.c_int
         lib.fwa_oracle_bias_scatter.argtypes = [_dp, _dp, ctypes.c_int, ctypes.c_int]
+        lib.fwa_oracle_mask_from_labels.restype = ctypes.c_int
+        lib.fwa_oracle_mask_from_labels.argtypes = [ctypes.POINTER(ctypes.c_int), _dp, ctypes.c_int, ctypes.c_int,
+                                                    ctypes.c_double]
         self._lib = lib
         self.threads_used = 0
 
@@ -152,6 +155,21 @@ class Oracle:
         return dtable
 
 
+    def mask_from_labels(self, labels, value=-100.0):
+        """[nW, L] integer region labels -> [nW, L, L] additive mask: 0 between tokens of
+        equal label, ``value`` elsewhere.  Feed the result to ``forward`` / ``backward``."""
+        labels = np.ascontiguousarray(labels, dtype=np.intc)
+        if labels.ndim != 2:
+            raise ValueError("labels must be [nW, L]")
+        nW, L = labels.shape
+        mask = np.empty((nW, L, L), dtype=np.float64)
+        rc = self._lib.fwa_oracle_mask_from_labels(labels.ctypes.data_as(ctypes.POINTER(ctypes.c_int)), _ptr(mask),
+                                                   nW, L, float(value))
+        if rc != 0:
+            raise ValueError(f"fwa_oracle_mask_from_labels failed with code {rc}")
+        return mask
+
+
 _default = None
 
 
@@ -177,6 +195,10 @@ def bias_gather(*a, **kw):
 
 def bias_scatter(*a, **kw):
     return load().bias_scatter(*a, **kw)
+
+
+def mask_from_labels(*a, **kw):
+    return load().mask_from_labels(*a, **kw)
 
 
 def threads_used() -> int:

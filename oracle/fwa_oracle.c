@@ -42,7 +42,9 @@
  * key/value permutation invariance, score-shift invariance, linearity in
  * V, the feature-chunk identity of eq. 5-6, the block-diagonal mask limit,
  * central finite differences and the adjoint identity for the backward,
- * and a float64 library expression as a third opinion.
+ * and a float64 library expression as a third opinion.  The label mask: a
+ * case written out by hand, the equivalence-class structure, and the dense
+ * shift mask of the input generator as a third opinion.
  */
 #include <math.h>
 #include <stdlib.h>
@@ -299,5 +301,22 @@ int fwa_oracle_bias_scatter(const double *dbias, double *dtable, int heads, int 
                 int dx = i % k - j % k + k - 1;
                 dtable[(size_t)h * T + dy * (2 * k - 1) + dx] += dbias[((size_t)h * L + i) * L + j];
             }
+    return FWA_ORACLE_OK;
+}
+
+/*
+ * The shift mask written out from per-token region labels (paper Section 2.1 only
+ * says that the shifted blocks mask attention between tokens that were not
+ * neighbours before the cyclic shift; this is the published Swin rule restated):
+ *   mask[w, i, j] = 0 when labels[w, i] == labels[w, j], else `value`.
+ *   labels: [nW, L] ints      mask: [nW, L, L]
+ */
+int fwa_oracle_mask_from_labels(const int *labels, double *mask, int nW, int L, double value)
+{
+    if (!labels || !mask || nW < 1 || L < 1) return FWA_ORACLE_BAD_ARG;
+    for (int w = 0; w < nW; ++w)
+        for (int i = 0; i < L; ++i)
+            for (int j = 0; j < L; ++j)
+                mask[((size_t)w * L + i) * L + j] = labels[w * L + i] == labels[w * L + j] ? 0.0 : value;
     return FWA_ORACLE_OK;
 }

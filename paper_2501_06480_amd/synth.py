@@ -76,6 +76,11 @@ def window_partition_2d(x: np.ndarray, k: int) -> np.ndarray:
     return x.reshape(H // k, k, W // k, k).transpose(0, 2, 1, 3).reshape(-1, k * k)
 
 
+def shift_labels(H: int, W: int, k: int, shift: int) -> np.ndarray:
+    """[nW, L] int32 region labels of the tokens of every window of an H x W map."""
+    return window_partition_2d(region_labels(H, W, k, shift), k).astype(np.int32)
+
+
 def shift_mask(H: int, W: int, k: int, shift: int, neg: float = -100.0) -> np.ndarray:
     """[nW, L, L] fp32 additive mask, 0 where labels agree, `neg` elsewhere."""
     lab = window_partition_2d(region_labels(H, W, k, shift), k)
@@ -120,7 +125,8 @@ def draw(w: Workload):
     Returns a dict with fp32 arrays ``q, k, v`` (and ``d_o`` for backward
     workloads) holding values already rounded to the workload dtype, the raw
     bf16 bit patterns under ``q_bits`` ... when dtype is bf16, ``table``
-    ([heads,(2k-1)^2] fp32 or None) and ``mask`` ([nW,L,L] fp32 or None).
+    ([heads,(2k-1)^2] fp32 or None), ``mask`` ([nW,L,L] fp32 or None) and
+    ``labels`` ([nW,L] int32 region labels the mask was made from, or None).
     """
     out = {}
     names = ["q", "k", "v"] + (["d_o"] if w.backward else [])
@@ -132,6 +138,7 @@ def draw(w: Workload):
         out[nm] = x
     out["table"] = bias_table(w.heads, w.k, w.seed * 16 + 8) if w.use_bias else None
     out["mask"] = shift_mask(w.map_hw, w.map_hw, w.k, w.shift) if w.shift else None
+    out["labels"] = shift_labels(w.map_hw, w.map_hw, w.k, w.shift) if w.shift else None
     return out
 
 

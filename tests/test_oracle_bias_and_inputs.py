@@ -98,6 +98,59 @@ def test_shift_mask_single_window_map():
     assert (m[0] == 0).sum() == 16 ** 2 + 12 ** 2 + 12 ** 2 + 9 ** 2
 
 
+def test_mask_from_labels_written_out_by_hand(oracle):
+    # two windows of 4 tokens; the second has three regions
+    lab = np.array([[5, 5, 5, 5], [0, 1, 0, 2]], dtype=np.int32)
+    m = oracle.mask_from_labels(lab, -7.5)
+    x = -7.5
+    want1 = np.array([[0, x, 0, x],
+                      [x, 0, x, x],
+                      [0, x, 0, x],
+                      [x, x, x, 0]], dtype=np.float64)
+    np.testing.assert_array_equal(m[0], np.zeros((4, 4)))
+    np.testing.assert_array_equal(m[1], want1)
+
+
+def test_mask_from_labels_properties(oracle):
+    g = np.random.default_rng(11)
+    lab = g.integers(0, 4, size=(5, 13)).astype(np.int32)
+    m = oracle.mask_from_labels(lab, -100.0)
+    assert m.shape == (5, 13, 13)
+    np.testing.assert_array_equal(m, m.transpose(0, 2, 1))            # an equivalence relation: symmetric,
+    assert (np.diagonal(m, axis1=1, axis2=2) == 0).all()               # reflexive,
+    for w in range(5):                                                 # and its classes are the label classes
+        for i in range(13):
+            np.testing.assert_array_equal(np.flatnonzero(m[w, i] == 0), np.flatnonzero(lab[w] == lab[w, i]))
+    # relabelling the regions changes nothing; a window only sees its own labels
+    np.testing.assert_array_equal(oracle.mask_from_labels(17 - 3 * lab, -100.0), m)
+    np.testing.assert_array_equal(oracle.mask_from_labels(lab[2:3], -100.0)[0], m[2])
+    # the value is taken as given (the oracle does not hard-wire -100)
+    np.testing.assert_array_equal(oracle.mask_from_labels(lab, 2.5), m * (2.5 / -100.0))
+
+
+@pytest.mark.parametrize("H,k,shift", [(56, 7, 3), (28, 7, 3), (7, 7, 3), (24, 12, 6)])
+def test_mask_from_labels_reproduces_the_shift_mask(oracle, H, k, shift):
+    # third opinion: the generator's dense mask, built by broadcasting, against the oracle's loops
+    lab = synth.shift_labels(H, H, k, shift)
+    assert lab.shape == ((H // k) ** 2, k * k) and lab.dtype == np.int32
+    np.testing.assert_array_equal(oracle.mask_from_labels(lab, -100.0), synth.shift_mask(H, H, k, shift))
+
+
+def test_masked_attention_is_attention_inside_each_region(oracle):
+    # With a large negative value, a token attends only inside its region: the output equals
+    # plain attention over the region's tokens alone (the block-diagonal limit, per label class).
+    g = np.random.default_rng(3)
+    L, C, heads = 9, 8, 2
+    q, k, v = (g.standard_normal((2, L, C)) for _ in range(3))
+    lab = np.array([[0, 0, 1, 0, 1, 1, 2, 0, 2], [3, 3, 3, 3, 3, 3, 3, 3, 3]], dtype=np.int32)
+    o = oracle.forward(q, k, v, heads, 0.5, mask=oracle.mask_from_labels(lab, -1e4))
+    for w in range(2):
+        for c in np.unique(lab[w]):
+            idx = np.flatnonzero(lab[w] == c)
+            sub = oracle.forward(q[w:w + 1, idx], k[w:w + 1, idx], v[w:w + 1, idx], heads, 0.5)
+            np.testing.assert_allclose(o[w, idx], sub[0], rtol=0, atol=1e-12)
+
+
 def test_workload_shapes_match_the_configs():
     assert (synth.config1().N, synth.config1().dtype) == (64, "f32")
     c2 = synth.config2()

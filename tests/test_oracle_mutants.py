@@ -44,6 +44,10 @@ MUTANTS = [
     ("dbias_scaled", "acc[e] += ds[e];", "acc[e] += scale * ds[e];", None),
     ("dbias_head_ignored", "partial + ((size_t)tid * heads + h) * LL", "partial + ((size_t)tid * heads) * LL", None),
     ("gather_offset_sign", "int dy = i / k - j / k + k - 1;", "int dy = j / k - i / k + k - 1;", None),
+    ("label_mask_inverted", "labels[w * L + i] == labels[w * L + j] ? 0.0 : value",
+     "labels[w * L + i] == labels[w * L + j] ? value : 0.0", None),
+    ("label_mask_window_ignored", "labels[w * L + i] == labels[w * L + j]", "labels[i] == labels[j]", None),
+    ("label_mask_value_hardwired", "labels[w * L + j] ? 0.0 : value", "labels[w * L + j] ? 0.0 : -100.0", None),
     ("gather_xy_swapped", "table[(size_t)h * T + dy * (2 * k - 1) + dx]", "table[(size_t)h * T + dx * (2 * k - 1) + dy]", None),
 ]
 
@@ -65,6 +69,7 @@ def _pins(o):
     yield lambda: G.test_gather_k2_written_out_by_hand(o)
     yield lambda: G.test_gather_depends_only_on_relative_offset(o, 3)
     yield lambda: G.test_scatter_is_the_adjoint_of_gather(o, 2)
+    yield lambda: G.test_mask_from_labels_written_out_by_hand(o)
 
 
 def _mutate(src, find, repl, occurrence):
