@@ -96,7 +96,7 @@ def time_other_workloads(torch, fwa, synth, dev):
     rotation rule as the headline (cycle larger than twice the last-level cache)."""
     out = []
 
-    def run(name, w, backward, iters, want_dbias=True):
+    def run(name, w, backward, iters, want_dbias=True, as_labels=False):
         shape = (w.N, w.L, w.C)
         tdt, esz = (torch.float32, 4) if w.dtype == "f32" else (torch.bfloat16, 2)
         per_set = (7 if backward else 4) * w.N * w.L * w.C * esz
@@ -105,10 +105,12 @@ def time_other_workloads(torch, fwa, synth, dev):
         sets = [[torch.randn(shape, device=dev, generator=g).to(tdt) for _ in range(4 if backward else 3)]
                 for _ in range(nsets)]
         outs = [torch.empty(shape, device=dev, dtype=tdt) for _ in range(nsets)]
-        bias = mask = ws = None
+        bias = mask = labels = ws = None
         if w.use_bias:
             bias = fwa.fwa_bias_gather(torch.from_numpy(synth.bias_table(w.heads, w.k, w.seed)).to(dev), w.k)
-        if w.shift:
+        if w.shift and as_labels:  # the mask as region labels, formed inside the kernels
+            labels = torch.from_numpy(synth.shift_labels(w.map_hw, w.map_hw, w.k, w.shift)).to(dev)
+        elif w.shift:
             mask = torch.from_numpy(synth.shift_mask(w.map_hw, w.map_hw, w.k, w.shift)).to(dev)
         if backward:
             need = fwa.fwa_backward_workspace_bytes(w.N, w.L, w.C, w.heads, 0 if w.dtype == "f32" else 1, want_dbias)
@@ -117,9 +119,10 @@ def time_other_workloads(torch, fwa, synth, dev):
         def step(i):
             t = sets[i % nsets]
             if backward:
-                fwa.fwa_backward(t[0], t[1], t[2], t[3], w.heads, w.scale, bias, mask, want_dbias=want_dbias, workspace=ws)
+                fwa.fwa_backward(t[0], t[1], t[2], t[3], w.heads, w.scale, bias, mask, want_dbias=want_dbias, workspace=ws,
+                                 labels=labels)
             else:
-                fwa.fwa_forward(t[0], t[1], t[2], w.heads, w.scale, bias, mask, out=outs[i % nsets])
+                fwa.fwa_forward(t[0], t[1], t[2], w.heads, w.scale, bias, mask, out=outs[i % nsets], labels=labels)
 
         for i in range(40):
             step(i)
@@ -173,6 +176,8 @@ def time_other_workloads(torch, fwa, synth, dev):
                         "algorithmic_GBps": algo / us / 1e3, "frac_of_hbm_peak": algo / us / 1e3 / HBM_PEAK_GBPS})
 
     run("swin_t_stage1_fwd_bias_shiftmask (N=8192, L=49, 3 heads)", synth.swin_t_stage(1, shifted=True), False, 400)
+    run("swin_t_stage1_fwd_bias_shiftlabels (N=8192, L=49, 3 heads; mask from region labels)",
+        synth.swin_t_stage(1, shifted=True), False, 400, as_labels=True)
     run_small("swin_t_stage3_fwd_bias (N=512, L=49, 12 heads)", synth.swin_t_stage(3))
     run_small("swin_t_stage4_fwd_bias (N=128, L=49, 24 heads)", synth.swin_t_stage(4))
     l144, l256 = synth.config4()
@@ -183,6 +188,11 @@ def time_other_workloads(torch, fwa, synth, dev):
     run("swin_t_stage3_bwd_bias_shiftmask_dbias (N=512, L=49, 12 heads)", s3, True, 200)
     run("window12_bwd_bias (N=1024, L=144, 4 heads; dQ, dK, dV)", l144, True, 30, want_dbias=False)
     run("window16_bwd_bias (N=1024, L=256, 4 heads; dQ, dK, dV)", l256, True, 20, want_dbias=False)
+    # shifted 16 x 16 windows of a 32 x 32 map: the dense mask against region labels
+    w16s = synth.Workload("window16_shift", 1024, 256, 128, 4, "bf16", 1300, 16, 32, True, 8, True)
+    for form, lab in (("shiftmask", False), ("shiftlabels", True)):
+        run(f"window16_fwd_bias_{form} (N=1024, L=256, 4 heads)", w16s, False, 50, as_labels=lab)
+        run(f"window16_bwd_bias_{form}_dbias (N=1024, L=256, 4 heads)", w16s, True, 20, as_labels=lab)
     # the shapes of the paper's own kernel benchmark (section 3.1): L = 64, 4 heads, width per head 64 and 256
     for d in (64, 256):
         pw = synth.Workload(f"paper_L64_d{d}", 4096, 64, 4 * d, 4, "bf16", 1100 + d, 8)

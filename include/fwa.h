@@ -112,6 +112,33 @@ int fwa_backward_strided(const void* q, const void* k, const void* v, const void
                          const float* bias, const float* mask, int nW,
                          int dtype, void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * Forward and backward with the shift mask given as region labels instead of a dense tile
+ * (paper Section 2.1: shifted blocks mask attention between tokens that were not neighbours
+ * before the cyclic shift; the labels name the regions of the shifted token map):
+ *   labels     : NULL (no mask), or in [nW, L] int32; the scores of window n receive
+ *                M[i][j] = labels[n % nW][i] == labels[n % nW][j] ? 0 : mask_value,
+ *                formed inside the kernels.  This reads L * 4 bytes per window position
+ *                instead of L * L * 4.  Requires nW >= 1 and N % nW == 0; 16-byte aligned.
+ *   mask_value : what a pair of tokens with different labels adds to its score (-100 in
+ *                the Swin Transformer); ignored when labels is NULL.
+ * Everything else (shapes, strides, dtype, workspace, error codes, supported ranges) is as in
+ * fwa_forward_strided / fwa_backward_strided, and the results are those of the same call with
+ * the dense mask written out from the labels.
+ */
+int fwa_forward_labels(const void* q, const void* k, const void* v, void* o,
+                       int64_t N, int L, int C, int heads, float scale,
+                       int64_t ld_qkv, int64_t ld_o,
+                       const float* bias, const int32_t* labels, float mask_value, int nW,
+                       int dtype, void* stream);
+
+int fwa_backward_labels(const void* q, const void* k, const void* v, const void* d_o,
+                        void* dq, void* dk, void* dv, float* dbias,
+                        int64_t N, int L, int C, int heads, float scale,
+                        int64_t ld_qkv, int64_t ld_do, int64_t ld_dqkv,
+                        const float* bias, const int32_t* labels, float mask_value, int nW,
+                        int dtype, void* workspace, size_t workspace_bytes, void* stream);
+
 /* Bytes of workspace fwa_backward needs for these arguments (0 if none).
  * Returns 0 for arguments fwa_backward would reject. */
 size_t fwa_backward_workspace_bytes(int64_t N, int L, int C, int heads, int dtype, int want_dbias);

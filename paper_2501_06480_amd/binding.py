@@ -27,7 +27,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libfwa.so")
 _lib = None
 
-EXPORTS = ("fwa_forward", "fwa_forward_strided", "fwa_backward", "fwa_backward_strided",
+EXPORTS = ("fwa_forward", "fwa_forward_strided", "fwa_forward_labels", "fwa_backward", "fwa_backward_strided",
+           "fwa_backward_labels",
            "fwa_backward_workspace_bytes", "fwa_bias_gather", "fwa_bias_scatter", "fwa_status_string")
 
 
@@ -56,6 +57,11 @@ def load_library():
     lib.fwa_forward.argtypes = [vp, vp, vp, vp, i64, ci, ci, ci, cf, vp, vp, ci, ci, vp]
     lib.fwa_forward_strided.restype = ci
     lib.fwa_forward_strided.argtypes = [vp, vp, vp, vp, i64, ci, ci, ci, cf, i64, i64, vp, vp, ci, ci, vp]
+    lib.fwa_forward_labels.restype = ci
+    lib.fwa_forward_labels.argtypes = [vp, vp, vp, vp, i64, ci, ci, ci, cf, i64, i64, vp, vp, cf, ci, ci, vp]
+    lib.fwa_backward_labels.restype = ci
+    lib.fwa_backward_labels.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i64, ci, ci, ci, cf, i64, i64, i64,
+                                        vp, vp, cf, ci, ci, vp, sz, vp]
     lib.fwa_backward.restype = ci
     lib.fwa_backward.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i64, ci, ci, ci, cf, vp, vp, ci, ci,
                                  vp, sz, vp]
@@ -153,9 +159,23 @@ class _on_device:
             self.ctx.__exit__(*exc)
 
 
-def fwa_forward(q, k, v, heads: int, scale: float, bias=None, mask=None, out=None, stream=None):
+def _labels_ptr(labels, mask, L: int):
+    """(device pointer, nW) of int32 region labels [nW, L]; they stand in for a dense mask."""
+    if mask is not None:
+        raise ValueError("give the mask either as a dense tensor or as labels, not both")
+    if not getattr(labels, "is_cuda", False):
+        raise TypeError("labels must be a GPU tensor (there is no CPU path)")
+    if labels.dtype != _torch().int32 or labels.dim() != 2 or labels.shape[1] != L or not labels.is_contiguous():
+        raise ValueError("labels must be a contiguous int32 tensor [nW, L]")
+    return labels.data_ptr(), int(labels.shape[0])
+
+
+def fwa_forward(q, k, v, heads: int, scale: float, bias=None, mask=None, out=None, stream=None, labels=None,
+                mask_value: float = -100.0):
     """O = softmax(scale*QK^T + B + M) V (paper Algorithm 1).  Tensors are [N, L, C] on the GPU;
-    q, k, v (and `out`) may be row-strided views, e.g. of a fused [N, L, 3, heads, d] tensor."""
+    q, k, v (and `out`) may be row-strided views, e.g. of a fused [N, L, 3, heads, d] tensor.
+    The mask is a dense [nW, L, L] fp32 tensor, or int32 region `labels` [nW, L] from which the
+    kernels form M[i][j] = 0 if labels agree else `mask_value`."""
     lib = _lib if _lib is not None else load_library()
     N, L, C = q.shape
     o = _torch().empty_like(q, memory_format=_torch().contiguous_format) if out is None else out
@@ -164,6 +184,19 @@ def fwa_forward(q, k, v, heads: int, scale: float, bias=None, mask=None, out=Non
         raise ValueError("bias must be [heads, L, L]")
     if mask is not None and tuple(mask.shape) != (nW, L, L):
         raise ValueError("mask must be [nW, L, L]")
+    if labels is not None:
+        lp, nW = _labels_ptr(labels, mask, L)
+        (qp, ld), (kp, ldk), (vp, ldv), (op, ldo) = (_row_ptr(q, "q"), _row_ptr(k, "k", q), _row_ptr(v, "v", q),
+                                                    _row_ptr(o, "out", q))
+        if not ld == ldk == ldv:
+            raise ValueError("q, k and v must share one row stride")
+        with _on_device(q.device):
+            rc = lib.fwa_forward_labels(qp, kp, vp, op, N, L, C, int(heads), float(scale), ld, ldo,
+                                        _dev_ptr(bias, "bias", f32=True), lp, float(mask_value), nW, _dtype_code(q),
+                                        _stream_handle(stream, q.device))
+        if rc != FWA_OK:
+            raise FwaError(rc, "fwa_forward_labels")
+        return o
     tail = (_dev_ptr(bias, "bias", f32=True), _dev_ptr(mask, "mask", f32=True), nW, _dtype_code(q),
             _stream_handle(stream, q.device))
     if q.is_contiguous() and k.is_contiguous() and v.is_contiguous() and o.is_contiguous():
@@ -189,10 +222,11 @@ def fwa_backward_workspace_bytes(N: int, L: int, C: int, heads: int, dtype: int,
 
 
 def fwa_backward(q, k, v, d_o, heads: int, scale: float, bias=None, mask=None, want_dbias: bool = False,
-                 workspace=None, stream=None, out=None):
+                 workspace=None, stream=None, out=None, labels=None, mask_value: float = -100.0):
     """(dQ, dK, dV, dBias) from Q, K, V, dO (paper Algorithm 2).  dBias is None unless asked for.
     q, k, v, d_o may be row-strided views; `out` = (dq, dk, dv) writes the gradients into given
-    tensors, e.g. the three views of a fused [N, L, 3, heads, d] gradient buffer."""
+    tensors, e.g. the three views of a fused [N, L, 3, heads, d] gradient buffer.  `labels` and
+    `mask_value` give the mask as region labels, as in ``fwa_forward``."""
     import torch
     lib = load_library()
     N, L, C = q.shape
@@ -213,6 +247,21 @@ def fwa_backward(q, k, v, d_o, heads: int, scale: float, bias=None, mask=None, w
     tail = (_dev_ptr(bias, "bias", f32=True), _dev_ptr(mask, "mask", f32=True), nW, _dtype_code(q),
             None if workspace is None else workspace.data_ptr(), ws_bytes, _stream_handle(stream, q.device))
     tensors = (q, k, v, d_o, dq, dk, dv)
+    if labels is not None:
+        lp, nW = _labels_ptr(labels, mask, L)
+        rows = [_row_ptr(t, nm, None if nm == "q" else q) for t, nm in zip(tensors, ("q", "k", "v", "d_o", "dq", "dk", "dv"))]
+        if not rows[0][1] == rows[1][1] == rows[2][1]:
+            raise ValueError("q, k and v must share one row stride")
+        if not rows[4][1] == rows[5][1] == rows[6][1]:
+            raise ValueError("dq, dk and dv must share one row stride")
+        args = tuple(r[0] for r in rows) + (None if dbias is None else dbias.data_ptr(), N, L, C, int(heads),
+                                            float(scale), rows[0][1], rows[3][1], rows[4][1],
+                                            _dev_ptr(bias, "bias", f32=True), lp, float(mask_value), nW) + tail[3:]
+        with _on_device(q.device):
+            rc = lib.fwa_backward_labels(*args)
+        if rc != FWA_OK:
+            raise FwaError(rc, "fwa_backward_labels")
+        return dq, dk, dv, dbias
     if all(t.is_contiguous() for t in tensors):
         ptrs = (_dev_ptr(q, "q"), _dev_ptr(k, "k", q), _dev_ptr(v, "v", q), _dev_ptr(d_o, "d_o", q),
                 _dev_ptr(dq, "dq", q), _dev_ptr(dk, "dk", q), _dev_ptr(dv, "dv", q))

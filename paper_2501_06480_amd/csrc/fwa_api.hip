@@ -45,11 +45,46 @@ int check_row_stride(int64_t ld, int C, int dtype) {
     return FWA_OK;
 }
 
-int check_mask(int64_t N, const float* mask, int nW) {
-    if (mask == nullptr) return FWA_OK;
+// The mask comes as a dense tile per window position or as region labels, never both.
+int check_mask(int64_t N, const void* mask, const void* labels, int nW) {
+    if (mask == nullptr && labels == nullptr) return FWA_OK;
     if (nW < 1 || N % nW != 0) return FWA_ERR_SHAPE;
     return FWA_OK;
 }
+
+int forward_impl(const void* q, const void* k, const void* v, void* o, int64_t N, int L, int C, int heads,
+                 float scale, int64_t ld_qkv, int64_t ld_o, const float* bias, const float* mask,
+                 const int32_t* labels, float mask_value, int nW, int dtype, void* stream) {
+    int rc = check_shape(N, L, C, heads, dtype, true);
+    if (rc != FWA_OK) return rc;
+    rc = check_mask(N, mask, labels, nW);
+    if (rc != FWA_OK) return rc;
+    rc = check_row_stride(ld_qkv, C, dtype);
+    if (rc != FWA_OK) return rc;
+    rc = check_row_stride(ld_o, C, dtype);
+    if (rc != FWA_OK) return rc;
+    if (N == 0) return FWA_OK;
+    if (!q || !k || !v || !o) return FWA_ERR_NULL;
+    if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(o) || misaligned(bias) || misaligned(mask) ||
+        misaligned(labels))
+        return FWA_ERR_ALIGN;
+    if (o == q || o == k || o == v) return FWA_ERR_ALIAS;
+    fwa::FwdArgs a;
+    a.q = q; a.k = k; a.v = v; a.o = o;
+    a.bias = bias; a.mask = mask; a.labels = labels; a.mask_value = mask_value;
+    a.N = N; a.L = L; a.C = C; a.heads = heads; a.nW = (mask || labels) ? nW : 1; a.scale = scale;
+    a.ldq = (int)ld_qkv; a.ldo = (int)ld_o;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const bool wide = C / heads != fwa::kHeadDim;
+    const hipError_t e = dtype != FWA_BF16 ? (wide || L <= fwa::kMaxWideL ? fwa::launch_forward_f32_tile(a, st) : fwa::launch_forward_f32(a, st))
+                                           : (wide ? fwa::launch_forward_bf16_wide(a, st) : fwa::launch_forward_bf16(a, st));
+    return e == hipSuccess ? FWA_OK : FWA_ERR_LAUNCH;
+}
+
+int backward_impl(const void* q, const void* k, const void* v, const void* d_o, void* dq, void* dk, void* dv,
+                  float* dbias, int64_t N, int L, int C, int heads, float scale, int64_t ld_qkv, int64_t ld_do,
+                  int64_t ld_dqkv, const float* bias, const float* mask, const int32_t* labels, float mask_value,
+                  int nW, int dtype, void* workspace, size_t workspace_bytes, void* stream);
 
 }  // namespace
 
@@ -72,29 +107,14 @@ const char* fwa_status_string(int code) {
 int fwa_forward_strided(const void* q, const void* k, const void* v, void* o, int64_t N, int L, int C, int heads,
                         float scale, int64_t ld_qkv, int64_t ld_o, const float* bias, const float* mask, int nW,
                         int dtype, void* stream) {
-    int rc = check_shape(N, L, C, heads, dtype, true);
-    if (rc != FWA_OK) return rc;
-    rc = check_mask(N, mask, nW);
-    if (rc != FWA_OK) return rc;
-    rc = check_row_stride(ld_qkv, C, dtype);
-    if (rc != FWA_OK) return rc;
-    rc = check_row_stride(ld_o, C, dtype);
-    if (rc != FWA_OK) return rc;
-    if (N == 0) return FWA_OK;
-    if (!q || !k || !v || !o) return FWA_ERR_NULL;
-    if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(o) || misaligned(bias) || misaligned(mask))
-        return FWA_ERR_ALIGN;
-    if (o == q || o == k || o == v) return FWA_ERR_ALIAS;
-    fwa::FwdArgs a;
-    a.q = q; a.k = k; a.v = v; a.o = o;
-    a.bias = bias; a.mask = mask;
-    a.N = N; a.L = L; a.C = C; a.heads = heads; a.nW = mask ? nW : 1; a.scale = scale;
-    a.ldq = (int)ld_qkv; a.ldo = (int)ld_o;
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    const bool wide = C / heads != fwa::kHeadDim;
-    const hipError_t e = dtype != FWA_BF16 ? (wide || L <= fwa::kMaxWideL ? fwa::launch_forward_f32_tile(a, st) : fwa::launch_forward_f32(a, st))
-                                           : (wide ? fwa::launch_forward_bf16_wide(a, st) : fwa::launch_forward_bf16(a, st));
-    return e == hipSuccess ? FWA_OK : FWA_ERR_LAUNCH;
+    return forward_impl(q, k, v, o, N, L, C, heads, scale, ld_qkv, ld_o, bias, mask, nullptr, 0.f, nW, dtype, stream);
+}
+
+int fwa_forward_labels(const void* q, const void* k, const void* v, void* o, int64_t N, int L, int C, int heads,
+                       float scale, int64_t ld_qkv, int64_t ld_o, const float* bias, const int32_t* labels,
+                       float mask_value, int nW, int dtype, void* stream) {
+    return forward_impl(q, k, v, o, N, L, C, heads, scale, ld_qkv, ld_o, bias, nullptr, labels, mask_value, nW, dtype,
+                        stream);
 }
 
 int fwa_forward(const void* q, const void* k, const void* v, void* o, int64_t N, int L, int C, int heads,
@@ -117,6 +137,26 @@ int fwa_backward_strided(const void* q, const void* k, const void* v, const void
                          float* dbias, int64_t N, int L, int C, int heads, float scale, int64_t ld_qkv,
                          int64_t ld_do, int64_t ld_dqkv, const float* bias, const float* mask, int nW, int dtype,
                          void* workspace, size_t workspace_bytes, void* stream) {
+    return backward_impl(q, k, v, d_o, dq, dk, dv, dbias, N, L, C, heads, scale, ld_qkv, ld_do, ld_dqkv, bias, mask,
+                         nullptr, 0.f, nW, dtype, workspace, workspace_bytes, stream);
+}
+
+int fwa_backward_labels(const void* q, const void* k, const void* v, const void* d_o, void* dq, void* dk, void* dv,
+                        float* dbias, int64_t N, int L, int C, int heads, float scale, int64_t ld_qkv,
+                        int64_t ld_do, int64_t ld_dqkv, const float* bias, const int32_t* labels, float mask_value,
+                        int nW, int dtype, void* workspace, size_t workspace_bytes, void* stream) {
+    return backward_impl(q, k, v, d_o, dq, dk, dv, dbias, N, L, C, heads, scale, ld_qkv, ld_do, ld_dqkv, bias, nullptr,
+                         labels, mask_value, nW, dtype, workspace, workspace_bytes, stream);
+}
+
+}  // extern "C"
+
+namespace {
+
+int backward_impl(const void* q, const void* k, const void* v, const void* d_o, void* dq, void* dk, void* dv,
+                  float* dbias, int64_t N, int L, int C, int heads, float scale, int64_t ld_qkv, int64_t ld_do,
+                  int64_t ld_dqkv, const float* bias, const float* mask, const int32_t* labels, float mask_value,
+                  int nW, int dtype, void* workspace, size_t workspace_bytes, void* stream) {
     int rc = check_shape(N, L, C, heads, dtype, true);
     if (rc != FWA_OK) return rc;
     rc = check_row_stride(ld_qkv, C, dtype);
@@ -127,7 +167,7 @@ int fwa_backward_strided(const void* q, const void* k, const void* v, const void
     if (rc != FWA_OK) return rc;
     rc = check_backward_support(L, dtype, dbias != nullptr);
     if (rc != FWA_OK) return rc;
-    rc = check_mask(N, mask, nW);
+    rc = check_mask(N, mask, labels, nW);
     if (rc != FWA_OK) return rc;
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (N == 0) {
@@ -140,7 +180,8 @@ int fwa_backward_strided(const void* q, const void* k, const void* v, const void
     }
     if (!q || !k || !v || !d_o || !dq || !dk || !dv) return FWA_ERR_NULL;
     if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(d_o) || misaligned(dq) || misaligned(dk) ||
-        misaligned(dv) || misaligned(dbias) || misaligned(bias) || misaligned(mask) || misaligned(workspace))
+        misaligned(dv) || misaligned(dbias) || misaligned(bias) || misaligned(mask) || misaligned(labels) ||
+        misaligned(workspace))
         return FWA_ERR_ALIGN;
     const void* ins[4] = {q, k, v, d_o};
     void* outs[3] = {dq, dk, dv};
@@ -161,15 +202,19 @@ int fwa_backward_strided(const void* q, const void* k, const void* v, const void
         a.stats = static_cast<float*>(workspace);
         a.partial = reinterpret_cast<float*>(static_cast<char*>(workspace) + large_stats_bytes(N, L, heads));
     }
-    a.bias = bias; a.mask = mask;
-    a.N = N; a.L = L; a.C = C; a.heads = heads; a.nW = mask ? nW : 1; a.scale = scale;
+    a.bias = bias; a.mask = mask; a.labels = labels; a.mask_value = mask_value;
+    a.N = N; a.L = L; a.C = C; a.heads = heads; a.nW = (mask || labels) ? nW : 1; a.scale = scale;
     a.slots = C / heads != fwa::kHeadDim ? fwa::backward_wide_slots(N, heads)
               : L > fwa::kMaxBackwardL   ? fwa::backward_large_slots(N, heads, L)
-                                         : fwa::backward_slots(N, heads, mask ? nW : 1);
+                                         : fwa::backward_slots(N, heads, a.nW);
     a.ldq = (int)ld_qkv; a.ldg = (int)ld_do; a.ldd = (int)ld_dqkv;
     const hipError_t e = dtype == FWA_BF16 ? fwa::launch_backward_bf16(a, st) : fwa::launch_backward_f32(a, st);
     return e == hipSuccess ? FWA_OK : FWA_ERR_LAUNCH;
 }
+
+}  // namespace
+
+extern "C" {
 
 int fwa_backward(const void* q, const void* k, const void* v, const void* d_o, void* dq, void* dk, void* dv,
                  float* dbias, int64_t N, int L, int C, int heads, float scale, const float* bias,

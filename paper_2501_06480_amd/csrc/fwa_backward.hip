@@ -34,6 +34,7 @@
 // slots in a fixed order, so the result is bit-reproducible.
 #include "fwa_device.h"
 #include "fwa_internal.h"
+#include "fwa_softmax.h"
 
 namespace fwa {
 namespace {
@@ -82,7 +83,6 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, 2) bwd_bf16_kernel(BwdArg
     const uint32_t off_row = (uint32_t)n * row_bytes + 16u * g;  // 16 B of row n (plus a block offset)
     const uint32_t off_row_g = (uint32_t)n * row_g + 16u * g, off_row_d = (uint32_t)n * row_d + 16u * g;
     const float sl2 = p.scale * kLog2e;
-    const uint32_t off_b = ((uint32_t)n * L + 4u * g) * 4u;      // B[n][4g] (plus block offsets)
     __amdgpu_buffer_rsrc_t rb = make_rsrc(nullptr, 0);
     if (BM && p.bias) rb = make_rsrc(p.bias + (size_t)h * L * L, (uint32_t)L * L * 4u);
 
@@ -130,8 +130,8 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, 2) bwd_bf16_kernel(BwdArg
         const __amdgpu_buffer_rsrc_t rdq = make_rsrc((char*)p.dq + tile_d, tile_bytes_d);
         const __amdgpu_buffer_rsrc_t rdk = make_rsrc((char*)p.dk + tile_d, tile_bytes_d);
         const __amdgpu_buffer_rsrc_t rdv = make_rsrc((char*)p.dv + tile_d, tile_bytes_d);
-        __amdgpu_buffer_rsrc_t rm = make_rsrc(nullptr, 0);
-        if (BM && p.mask) rm = make_rsrc(p.mask + (size_t)(w % p.nW) * L * L, (uint32_t)L * L * 4u);
+        MaskSrc msk = {make_rsrc(nullptr, 0), 0.f, false};
+        if (BM) msk = mask_of_window(p, (uint32_t)w);
 
         // Row operands (contraction over the 32 channels): lane (g, n) = X[16 b + n][8g .. 8g+7]
         bf16x8 krow[NB], vrow[NB], qrow[NB], grow[NB];
@@ -185,17 +185,17 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, 2) bwd_bf16_kernel(BwdArg
                 s[jb] = mfma_bf16(krow[jb], qrow[qb], zero);   // S[16 qb + n][16 jb + 4g + r]
                 dp[jb] = mfma_bf16(vrow[jb], grow[qb], zero);  // dP at the same positions
             }
+            if (BM) {
+                // 4 consecutive columns of one row: dword-aligned 16-byte loads, range-checked per dword
+                f32x4 add[NB];
+                addend_at(rb, msk, (uint32_t)(16 * qb + n), 4u * g, (uint32_t)L).fill(add, kLog2e);
 #pragma unroll
-            for (int jb = 0; jb < NB; ++jb) {
-                if (BM) {
-                    // 4 consecutive columns of one row: a dword-aligned 16-byte load, range-checked per dword
-                    const uint32_t off = off_b + ((uint32_t)(16 * qb) * L + 16 * jb) * 4u;
-                    const f32x4 add = (load_f32x4(rb, off) + load_f32x4(rm, off)) * kLog2e;
+                for (int jb = 0; jb < NB; ++jb)
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) s[jb][r] = fmaf(s[jb][r], sl2, add[r]);
-                } else {
-                    s[jb] *= sl2;
-                }
+                    for (int r = 0; r < 4; ++r) s[jb][r] = fmaf(s[jb][r], sl2, add[jb][r]);
+            } else {
+#pragma unroll
+                for (int jb = 0; jb < NB; ++jb) s[jb] *= sl2;
             }
 #pragma unroll
             for (int r = 0; r < 4; ++r)
@@ -378,7 +378,7 @@ hipError_t launch_bwd_nb(const BwdArgs& a, hipStream_t st) {
     gm.heads_per_block = (uint32_t)hpb;
     gm.slots = (uint32_t)a.slots;
     const unsigned grid = gm.slots * groups, block = 64u * (unsigned)hpb;
-    const bool bm = a.bias || a.mask, db = a.dbias != nullptr;
+    const bool bm = a.bias || has_mask(a), db = a.dbias != nullptr;
     hipError_t e;
     if (bm)
         e = db ? launch_one<NB, true, true>(a, gm, grid, block, st) : launch_one<NB, true, false>(a, gm, grid, block, st);
@@ -425,7 +425,7 @@ hipError_t launch_backward_bf16_single(const BwdArgs& a, hipStream_t s) {
 hipError_t launch_backward_bf16(const BwdArgs& a, hipStream_t s) {
     if (a.C / a.heads != kHeadDim) return launch_backward_bf16_wide(a, s);
     if (a.L > kMaxBackwardL) return launch_backward_bf16_large(a, s);
-    const bool coop = coop_slots(a.N, a.heads, a.mask ? a.nW : 1) > 0;
+    const bool coop = coop_slots(a.N, a.heads, mask_period(a)) > 0;
     const hipError_t e = coop ? launch_backward_bf16_coop(a, s) : launch_backward_bf16_single(a, s);
     if (e != hipSuccess || a.dbias == nullptr) return e;
     return launch_dbias_reduce(a, s);

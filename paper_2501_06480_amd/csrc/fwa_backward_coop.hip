@@ -117,12 +117,7 @@ __global__ void __launch_bounds__(64 * kCoopWavesPerTile * kCoopMaxHeads) bwd_bf
     if (BM && active) {
         const uint32_t ll = (uint32_t)L * L * 4u;
         const __amdgpu_buffer_rsrc_t rb = p.bias ? make_rsrc(p.bias + (size_t)h * L * L, ll) : make_rsrc(nullptr, 0);
-        const __amdgpu_buffer_rsrc_t rm =
-            p.mask ? make_rsrc(p.mask + (size_t)(bw % (uint32_t)p.nW) * L * L, ll) : make_rsrc(nullptr, 0);
-        const uint32_t off = (((uint32_t)(16 * role + n)) * L + 4u * g) * 4u;
-#pragma unroll
-        for (int jb = 0; jb < NB; ++jb)
-            add[jb] = (load_f32x4(rb, off + 16 * jb * 4u) + load_f32x4(rm, off + 16 * jb * 4u)) * kLog2e;
+        addend_at(rb, mask_of_window(p, bw), (uint32_t)(16 * role + n), 4u * g, (uint32_t)L).fill(add, kLog2e);
     }
     if (bw < (uint32_t)p.N) park();
 
@@ -294,7 +289,7 @@ hipError_t launch_coop_nb(const BwdArgs& a, int hpb, hipStream_t st) {
     gm.xcd_remap = (hpb % 2 == 1 && groups > 1) ? 1u : 0u;
     gm.xcd_q = grid / 8u;
     gm.xcd_r = grid % 8u;
-    const bool bm = a.bias || a.mask, db = a.dbias != nullptr;
+    const bool bm = a.bias || has_mask(a), db = a.dbias != nullptr;
     if (bm)
         return db ? launch_coop_one<NB, true, true>(a, gm, grid, block, lds, st)
                   : launch_coop_one<NB, true, false>(a, gm, grid, block, lds, st);

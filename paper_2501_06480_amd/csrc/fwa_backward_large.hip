@@ -31,6 +31,7 @@
 // with row-contiguous 16-byte loads into a private LDS patch and picks its values from there.
 #include "fwa_device.h"
 #include "fwa_internal.h"
+#include "fwa_softmax.h"
 
 namespace fwa {
 namespace {
@@ -47,10 +48,11 @@ __device__ __forceinline__ bf16x8 pair_operand(bf16x4 a, bf16x4 b) {
     return as_bf16x8(u32x4{ua.x, ua.y, ub.x, ub.y});
 }
 
-// HB / HM: a bias / a mask is present (the absent one costs neither loads nor registers)
-template <int NB, bool HB, bool HM>
+// HB: a bias is present; HM: no mask (0), a dense mask (1), or region labels from which the
+// mask values are formed in registers (2).  What is absent costs neither loads nor registers.
+template <int NB, bool HB, int HM>
 __global__ void __launch_bounds__(64 * large_waves(NB)) bwd_bf16_large_kernel(BwdArgs p, LargeGeom gm) {
-    constexpr bool BM = HB || HM;
+    constexpr bool BM = HB || HM != 0;
     constexpr int W = large_waves(NB);
     constexpr int NB2 = (NB + 1) / 2;
     constexpr int ROWS = 16 * NB;
@@ -122,8 +124,9 @@ __global__ void __launch_bounds__(64 * large_waves(NB)) bwd_bf16_large_kernel(Bw
             }
         }
         __syncthreads();
-        const __amdgpu_buffer_rsrc_t rm =
-            HM ? make_rsrc(p.mask + (size_t)(w % (uint32_t)p.nW) * L * L, ll) : make_rsrc(nullptr, 0);
+        // the labels of the window's tokens when the mask comes as labels
+        const __amdgpu_buffer_rsrc_t rl =
+            HM == 2 ? make_rsrc(p.labels + (size_t)(w % (uint32_t)p.nW) * L, (uint32_t)L * 4u) : make_rsrc(nullptr, 0);
 
         // ---------------- pass 1: query blocks wave, wave + W ----------------
         for (int qb = (int)wave; qb < NB; qb += W) {
@@ -136,17 +139,24 @@ __global__ void __launch_bounds__(64 * large_waves(NB)) bwd_bf16_large_kernel(Bw
             const uint32_t prow = (uint32_t)lane >> 4, pcol = 4u * ((uint32_t)lane & 15u);
             constexpr int CH = (NB + 3) / 4;
             f32x4 tb[2][4], tm[2][4];
+            i32x4 tk[2];  // with labels: those of a patch's 4 columns ...
+            int tq[4];    // ... and of the lane's 4 patch rows
             const uint32_t qrow = (uint32_t)(16 * qb) * L * 4u;  // < ll: the block starts inside the tile
             const __amdgpu_buffer_rsrc_t rbq = HB ? make_rsrc(p.bias + (size_t)h * L * L + (size_t)16 * qb * L, ll - qrow) : rb;
             const __amdgpu_buffer_rsrc_t rmq =
-                HM ? make_rsrc(p.mask + (size_t)(w % (uint32_t)p.nW) * L * L + (size_t)16 * qb * L, ll - qrow) : rm;
+                HM == 1 ? make_rsrc(p.mask + (size_t)(w % (uint32_t)p.nW) * L * L + (size_t)16 * qb * L, ll - qrow) : rb;
+            if (HM == 2) {
+#pragma unroll
+                for (int t = 0; t < 4; ++t) tq[t] = load_i32(rl, (uint32_t)(16 * qb + 4 * t + prow) * 4u);
+            }
             auto request_patch = [&](int ch, int slot) {
 #pragma unroll
                 for (int t = 0; t < 4; ++t) {
                     const uint32_t off = ((uint32_t)(4 * t + prow) * L + pcol) * 4u + 256u * ch;
                     if (HB) tb[slot][t] = load_f32x4(rbq, off);
-                    if (HM) tm[slot][t] = load_f32x4(rmq, off);
+                    if (HM == 1) tm[slot][t] = load_f32x4(rmq, off);
                 }
+                if (HM == 2) tk[slot] = load_i32x4(rl, (pcol + 64u * ch) * 4u);
             };
             if (BM) request_patch(0, 0);
             f32x4 s[NB];
@@ -160,9 +170,11 @@ __global__ void __launch_bounds__(64 * large_waves(NB)) bwd_bf16_large_kernel(Bw
                     if (ch + 1 < CH) request_patch(ch + 1, cur ^ 1);
                     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                    for (int t = 0; t < 4; ++t)
+                    for (int t = 0; t < 4; ++t) {
+                        const f32x4 mk = HM == 2 ? mask_of_labels(tq[t], tk[cur], p.mask_value) : tm[cur][t];
                         *reinterpret_cast<f32x4*>(patch + (4 * t + prow) * SG + pcol) =
-                            (HB && HM ? tb[cur][t] + tm[cur][t] : (HB ? tb[cur][t] : tm[cur][t])) * kLog2e;
+                            (HB && HM ? tb[cur][t] + mk : (HB ? tb[cur][t] : mk)) * kLog2e;
+                    }
 #pragma unroll
                     for (int b = 0; b < 4; ++b) {
                         const int jb = 4 * ch + b;
@@ -285,6 +297,8 @@ __global__ void __launch_bounds__(64 * large_waves(NB)) bwd_bf16_large_kernel(Bw
             for (int r = 0; r < 4; ++r) aoff[r] = ((uint32_t)(4 * g + r) * L + jcol) * 4u;
             bf16x8 oq[2][2], og[2][2], tg0[2], tg1[2], tx0[2], tx1[2];
             f32x4 oM[2][2], oD[2][2], ab[2][2], am[2][2];
+            i32x4 al[2][2];
+            const int lkey = HM == 2 ? load_i32(rl, jcol * 4u) : 0;
             auto fetch = [&](int qp, int slot) {
                 const bool two = 2 * qp + 1 < NB;
 #pragma unroll
@@ -311,12 +325,14 @@ __global__ void __launch_bounds__(64 * large_waves(NB)) bwd_bf16_large_kernel(Bw
                     const uint32_t qrow = (uint32_t)(16 * (2 * qp + u)) * L;
                     const __amdgpu_buffer_rsrc_t rbq = HB ? make_rsrc(p.bias + (size_t)h * L * L + qrow, ll - 4u * qrow) : rb;
                     const __amdgpu_buffer_rsrc_t rmq =
-                        HM ? make_rsrc(p.mask + (size_t)(w % (uint32_t)p.nW) * L * L + qrow, ll - 4u * qrow) : rm;
+                        HM == 1 ? make_rsrc(p.mask + (size_t)(w % (uint32_t)p.nW) * L * L + qrow, ll - 4u * qrow) : rb;
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
                         if (HB) ab[slot][u][r] = load_f32(rbq, aoff[r]);
-                        if (HM) am[slot][u][r] = load_f32(rmq, aoff[r]);
+                        if (HM == 1) am[slot][u][r] = load_f32(rmq, aoff[r]);
                     }
+                    // with labels: those of the 4 query rows, compared with the key's where the term is used
+                    if (HM == 2) al[slot][u] = load_i32x4(rl, (uint32_t)(16 * (2 * qp + u) + 4 * g) * 4u);
                 }
             };
             if (BM) fetch_add(0, 0);
@@ -345,7 +361,8 @@ __global__ void __launch_bounds__(64 * large_waves(NB)) bwd_bf16_large_kernel(Bw
                     for (int r = 0; r < 4; ++r) {
                         float x;
                         if (BM) {
-                            const float add = HB && HM ? ab[cur][u][r] + am[cur][u][r] : (HB ? ab[cur][u][r] : am[cur][u][r]);
+                            const float mk = HM == 2 ? (al[cur][u][r] == lkey ? 0.f : p.mask_value) : am[cur][u][r];
+                            const float add = HB && HM ? ab[cur][u][r] + mk : (HB ? ab[cur][u][r] : mk);
                             x = fmaf(sc[u][r], sl2, fmaf(add, kLog2e, -oM[cur][u][r]));
                         }
                         else
@@ -391,9 +408,9 @@ __global__ void __launch_bounds__(64 * large_waves(NB)) bwd_bf16_large_kernel(Bw
 // of one head for its whole life, holds dBias[all queries][its keys] in registers across the
 // windows bw, bw + G, ... and writes them out once, in register order, as one of G partial
 // sums per head (the reduce kernel adds the slots in a fixed order).
-template <int NB, bool HB, bool HM>
+template <int NB, bool HB, int HM>
 __global__ void __launch_bounds__(64 * large_waves(NB)) dbias_large_kernel(BwdArgs p, LargeGeom gm) {
-    constexpr bool BM = HB || HM;
+    constexpr bool BM = HB || HM != 0;
     constexpr int W = large_waves(NB);
     constexpr int JPW = (NB + W - 1) / W;  // key blocks per wave
     constexpr int NB2 = (NB + 1) / 2;
@@ -430,6 +447,8 @@ __global__ void __launch_bounds__(64 * large_waves(NB)) dbias_large_kernel(BwdAr
         for (int b = 0; b < NB; ++b) dbacc[a][b] = zero;
 
     for (uint32_t w = bw; w < (uint32_t)p.N; w += gm.G) {
+        const __amdgpu_buffer_rsrc_t rl =
+            HM == 2 ? make_rsrc(p.labels + (size_t)(w % (uint32_t)p.nW) * L, (uint32_t)L * 4u) : make_rsrc(nullptr, 0);
         {
             const size_t tile = ((size_t)w * L * p.ldq + (size_t)h * kHeadDim) * 2u;
             const size_t tile_g = ((size_t)w * L * p.ldg + (size_t)h * kHeadDim) * 2u;
@@ -478,6 +497,8 @@ __global__ void __launch_bounds__(64 * large_waves(NB)) dbias_large_kernel(BwdAr
                 for (int r = 0; r < 4; ++r) aoff[r] = ((uint32_t)(4 * g + r) * L + jcol) * 4u;
                 bf16x8 oq[2][2], og[2][2];
                 f32x4 oM[2][2], oD[2][2], ab[2][2], am[2][2];
+                i32x4 al[2][2];
+                const int lkey = HM == 2 ? load_i32(rl, jcol * 4u) : 0;
                 auto fetch = [&](int qp, int slot) {
 #pragma unroll
                     for (int u = 0; u < 2; ++u) {
@@ -492,13 +513,14 @@ __global__ void __launch_bounds__(64 * large_waves(NB)) dbias_large_kernel(BwdAr
                             const __amdgpu_buffer_rsrc_t rbq =
                                 HB ? make_rsrc(p.bias + (size_t)h * L * L + qrow, ll - 4u * qrow) : make_rsrc(nullptr, 0);
                             const __amdgpu_buffer_rsrc_t rmq =
-                                HM ? make_rsrc(p.mask + (size_t)(w % (uint32_t)p.nW) * L * L + qrow, ll - 4u * qrow)
-                                   : make_rsrc(nullptr, 0);
+                                HM == 1 ? make_rsrc(p.mask + (size_t)(w % (uint32_t)p.nW) * L * L + qrow, ll - 4u * qrow)
+                                        : make_rsrc(nullptr, 0);
 #pragma unroll
                             for (int r = 0; r < 4; ++r) {
                                 if (HB) ab[slot][u][r] = load_f32(rbq, aoff[r]);
-                                if (HM) am[slot][u][r] = load_f32(rmq, aoff[r]);
+                                if (HM == 1) am[slot][u][r] = load_f32(rmq, aoff[r]);
                             }
+                            if (HM == 2) al[slot][u] = load_i32x4(rl, (uint32_t)(16 * qb + 4 * g) * 4u);
                         }
                     }
                 };
@@ -517,7 +539,8 @@ __global__ void __launch_bounds__(64 * large_waves(NB)) dbias_large_kernel(BwdAr
                         for (int r = 0; r < 4; ++r) {
                             float x;
                             if (BM) {
-                                const float add = HB && HM ? ab[cur][u][r] + am[cur][u][r] : (HB ? ab[cur][u][r] : am[cur][u][r]);
+                                const float mk = HM == 2 ? (al[cur][u][r] == lkey ? 0.f : p.mask_value) : am[cur][u][r];
+                                const float add = HB && HM ? ab[cur][u][r] + mk : (HB ? ab[cur][u][r] : mk);
                                 x = fmaf(sc[r], sl2, fmaf(add, kLog2e, -oM[cur][u][r]));
                             } else {
                                 x = fmaf(sc[r], sl2, -oM[cur][u][r]);
@@ -546,7 +569,7 @@ __global__ void __launch_bounds__(64 * large_waves(NB)) dbias_large_kernel(BwdAr
     }
 }
 
-template <int NB, bool HB, bool HM>
+template <int NB, bool HB, int HM>
 hipError_t launch_dbias_large(const BwdArgs& a, hipStream_t st) {
     constexpr int W = large_waves(NB);
     const void* fn = reinterpret_cast<const void*>(&dbias_large_kernel<NB, HB, HM>);
@@ -566,9 +589,9 @@ hipError_t launch_dbias_large(const BwdArgs& a, hipStream_t st) {
     return hipGetLastError();
 }
 
-template <int NB, bool HB, bool HM>
+template <int NB, bool HB, int HM>
 hipError_t launch_large_one(const BwdArgs& a, hipStream_t st) {
-    constexpr bool BM = HB || HM;
+    constexpr bool BM = HB || HM != 0;
     constexpr int W = large_waves(NB);
     const void* fn = reinterpret_cast<const void*>(&bwd_bf16_large_kernel<NB, HB, HM>);
     const unsigned block = 64u * W;
@@ -598,7 +621,7 @@ hipError_t launch_large_one(const BwdArgs& a, hipStream_t st) {
     return hipGetLastError();
 }
 
-template <int NB, bool HB, bool HM>
+template <int NB, bool HB, int HM>
 hipError_t launch_large_both(const BwdArgs& a, hipStream_t st) {
     hipError_t e = launch_large_one<NB, HB, HM>(a, st);
     if (e != hipSuccess || a.dbias == nullptr) return e;
@@ -608,8 +631,12 @@ hipError_t launch_large_both(const BwdArgs& a, hipStream_t st) {
 
 template <int NB>
 hipError_t launch_large_nb(const BwdArgs& a, hipStream_t st) {
-    if (a.bias) return a.mask ? launch_large_both<NB, true, true>(a, st) : launch_large_both<NB, true, false>(a, st);
-    return a.mask ? launch_large_both<NB, false, true>(a, st) : launch_large_both<NB, false, false>(a, st);
+    if (a.bias) {
+        if (a.labels) return launch_large_both<NB, true, 2>(a, st);
+        return a.mask ? launch_large_both<NB, true, 1>(a, st) : launch_large_both<NB, true, 0>(a, st);
+    }
+    if (a.labels) return launch_large_both<NB, false, 2>(a, st);
+    return a.mask ? launch_large_both<NB, false, 1>(a, st) : launch_large_both<NB, false, 0>(a, st);
 }
 
 }  // namespace

@@ -137,9 +137,7 @@ __global__ void __launch_bounds__(256) bwd_bf16_wide_kernel(BwdArgs p, uint32_t 
         if (BM) {
             const uint32_t ll = (uint32_t)L * L * 4u;
             const __amdgpu_buffer_rsrc_t rb = p.bias ? make_rsrc(p.bias + (size_t)h * L * L, ll) : make_rsrc(nullptr, 0);
-            const __amdgpu_buffer_rsrc_t rm =
-                p.mask ? make_rsrc(p.mask + (size_t)(w % (uint32_t)p.nW) * L * L, ll) : make_rsrc(nullptr, 0);
-            const AddendGlobal addend = {rb, rm, (((uint32_t)(16 * qb + n)) * L + 4u * g) * 4u};
+            const AddendGlobal addend = addend_at(rb, mask_of_window(p, w), (uint32_t)(16 * qb + n), 4u * g, (uint32_t)L);
             inv = softmax_block<NB, true>(s, sl2, addend, L, g);
         } else {
             inv = softmax_block<NB, false>(s, sl2, AddendNone{}, L, g);
@@ -272,7 +270,7 @@ hipError_t launch_wide_one(const BwdArgs& a, unsigned G, size_t lds, hipStream_t
 template <int NB, int D>
 hipError_t launch_wide_nb(const BwdArgs& a, hipStream_t st) {
     const size_t lds = (size_t)2 * 16 * NB * (D / 8 + 1) * 16 + (size_t)4 * 16 * NB * 64 * 2;
-    const bool bm = a.bias || a.mask;
+    const bool bm = a.bias || has_mask(a);
     if (a.dbias == nullptr)  // one window per workgroup
         return bm ? launch_wide_one<NB, D, true, false>(a, (unsigned)a.N, lds, st)
                   : launch_wide_one<NB, D, false, false>(a, (unsigned)a.N, lds, st);

@@ -20,6 +20,7 @@ typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef int i32x4 __attribute__((ext_vector_type(4)));
 
 constexpr float kLog2e = 1.4426950408889634f;
 
@@ -59,6 +60,12 @@ __device__ __forceinline__ void store_f32x4(f32x4 v, __amdgpu_buffer_rsrc_t r, u
 }
 __device__ __forceinline__ float load_f32(__amdgpu_buffer_rsrc_t r, uint32_t voffset) {
     return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r, voffset, 0, 0));
+}
+__device__ __forceinline__ i32x4 load_i32x4(__amdgpu_buffer_rsrc_t r, uint32_t voffset) {
+    return __builtin_bit_cast(i32x4, __builtin_amdgcn_raw_buffer_load_b128(r, voffset, 0, 0));
+}
+__device__ __forceinline__ int load_i32(__amdgpu_buffer_rsrc_t r, uint32_t voffset) {
+    return (int)__builtin_amdgcn_raw_buffer_load_b32(r, voffset, 0, 0);
 }
 
 // Unsigned division by a runtime constant with a host-made multiplier

@@ -17,6 +17,7 @@
 // parked in their place.  dBias is not produced in fp32.
 #include "fwa_device.h"
 #include "fwa_internal.h"
+#include "fwa_softmax.h"
 
 namespace fwa {
 namespace {
@@ -77,17 +78,16 @@ __device__ __forceinline__ void load_own_rows(f32x4 (&own)[D / 16], const __amdg
 // scores of a block of 16 query rows -> probabilities; returns nothing, leaves P in s and the
 // statistics in m (row max of the scaled scores, natural units) and sum
 template <int NB, bool BM>
-__device__ __forceinline__ void softmax_f32(f32x4 (&s)[NB], float scale, const __amdgpu_buffer_rsrc_t rb,
-                                            const __amdgpu_buffer_rsrc_t rm, uint32_t off_b, int L, int g, float& m,
-                                            float& sum) {
+__device__ __forceinline__ void softmax_f32(f32x4 (&s)[NB], float scale, const AddendGlobal& addend, int L, int g,
+                                            float& m, float& sum) {
     m = -INFINITY;
+    f32x4 add[NB];
+    if (BM) addend.fill(add, 1.0f);
 #pragma unroll
     for (int jb = 0; jb < NB; ++jb) {
-        f32x4 add = {0.f, 0.f, 0.f, 0.f};
-        if (BM) add = load_f32x4(rb, off_b + 16 * jb * 4u) + load_f32x4(rm, off_b + 16 * jb * 4u);
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-            float x = s[jb][r] * scale + add[r];
+            float x = BM ? s[jb][r] * scale + add[jb][r] : s[jb][r] * scale;
             if (jb == NB - 1 && 16 * jb + 4 * g + r >= L) x = -INFINITY;
             s[jb][r] = x;
             m = fmaxf(m, x);
@@ -135,14 +135,14 @@ __global__ void __launch_bounds__(256) fwd_f32_tile_kernel(FwdArgs p) {
     for (int jb = 0; jb < NB; ++jb) s[jb] = f32x4{0.f, 0.f, 0.f, 0.f};
     rows_times_own<NB, D>(s, lk, qv, n, g);  // S[16 qb + n][16 jb + 4g + r]
 
-    __amdgpu_buffer_rsrc_t rb = make_rsrc(nullptr, 0), rm = make_rsrc(nullptr, 0);
+    __amdgpu_buffer_rsrc_t rb = make_rsrc(nullptr, 0);
+    MaskSrc msk = {make_rsrc(nullptr, 0), 0.f, false};
     if (BM) {
-        const uint32_t ll = (uint32_t)L * L * 4u;
-        if (p.bias) rb = make_rsrc(p.bias + (size_t)h * L * L, ll);
-        if (p.mask) rm = make_rsrc(p.mask + (size_t)(w % (uint32_t)p.nW) * L * L, ll);
+        if (p.bias) rb = make_rsrc(p.bias + (size_t)h * L * L, (uint32_t)L * L * 4u);
+        msk = mask_of_window(p, w);
     }
     float m, sum;
-    softmax_f32<NB, BM>(s, p.scale, rb, rm, (((uint32_t)(16 * qb + n)) * L + 4u * g) * 4u, L, g, m, sum);
+    softmax_f32<NB, BM>(s, p.scale, addend_at(rb, msk, (uint32_t)(16 * qb + n), 4u * g, (uint32_t)L), L, g, m, sum);
 
     // O^T = V^T P^T, 16 channels at a time: k-slot g of step (jb, r) stands for key 16 jb + 4g + r
     const __amdgpu_buffer_rsrc_t ro =
@@ -191,11 +191,11 @@ __global__ void __launch_bounds__(256) bwd_f32_tile_kernel(BwdArgs p) {
     float* const stD = stM + ROWS;
     const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
 
-    __amdgpu_buffer_rsrc_t rb = make_rsrc(nullptr, 0), rm = make_rsrc(nullptr, 0);
+    __amdgpu_buffer_rsrc_t rb = make_rsrc(nullptr, 0);
+    MaskSrc msk = {make_rsrc(nullptr, 0), 0.f, false};
     if (BM) {
-        const uint32_t ll = (uint32_t)L * L * 4u;
-        if (p.bias) rb = make_rsrc(p.bias + (size_t)h * L * L, ll);
-        if (p.mask) rm = make_rsrc(p.mask + (size_t)(w % (uint32_t)p.nW) * L * L, ll);
+        if (p.bias) rb = make_rsrc(p.bias + (size_t)h * L * L, (uint32_t)L * L * 4u);
+        msk = mask_of_window(p, w);
     }
 
     park_slab<D, ROWS>(sa, rk, row_bytes, tid);
@@ -214,7 +214,7 @@ __global__ void __launch_bounds__(256) bwd_f32_tile_kernel(BwdArgs p) {
         rows_times_own<NB, D>(s, sa, qv, n, g);   // <k_j, q_i>: query i = 16 qb + n, key j = 16 jb + 4g + r
         rows_times_own<NB, D>(dp, sb, gv, n, g);  // <v_j, do_i>
         float m, sum;
-        softmax_f32<NB, BM>(s, p.scale, rb, rm, (((uint32_t)(16 * qb + n)) * L + 4u * g) * 4u, L, g, m, sum);
+        softmax_f32<NB, BM>(s, p.scale, addend_at(rb, msk, (uint32_t)(16 * qb + n), 4u * g, (uint32_t)L), L, g, m, sum);
         float delta = 0.f;
 #pragma unroll
         for (int jb = 0; jb < NB; ++jb)
@@ -281,14 +281,12 @@ __global__ void __launch_bounds__(256) bwd_f32_tile_kernel(BwdArgs p) {
             }
             const f32x4 M4 = *reinterpret_cast<const f32x4*>(stM + 16 * qb + 4 * g);
             const f32x4 D4 = *reinterpret_cast<const f32x4*>(stD + 16 * qb + 4 * g);
-            f32x4 pr, ds;
+            f32x4 pr, ds, mk = zero;
+            if (BM) mk = mask_rows4(msk, (uint32_t)(16 * qb + 4 * g), jcol, (uint32_t)L);  // rows beyond L: outside, zero
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 float x = sc[r] * p.scale;
-                if (BM) {
-                    const uint32_t off = ((uint32_t)(16 * qb + 4 * g + r) * L + jcol) * 4u;  // rows beyond L: outside, zero
-                    x += load_f32(rb, off) + load_f32(rm, off);
-                }
+                if (BM) x += load_f32(rb, ((uint32_t)(16 * qb + 4 * g + r) * L + jcol) * 4u) + mk[r];
                 pr[r] = valid ? __builtin_amdgcn_exp2f((x - M4[r]) * kLog2e) : 0.f;
                 ds[r] = pr[r] * (dp[r] - D4[r]);
             }
@@ -322,7 +320,7 @@ template <int NB, int D>
 hipError_t launch_fwd_nb(const FwdArgs& a, hipStream_t st) {
     const unsigned grid = (unsigned)(a.N * a.heads);
     const size_t lds = f32_slab_bytes<NB, D>();
-    const bool bm = a.bias || a.mask;
+    const bool bm = a.bias || has_mask(a);
     const void* fn = bm ? reinterpret_cast<const void*>(&fwd_f32_tile_kernel<NB, D, true>)
                         : reinterpret_cast<const void*>(&fwd_f32_tile_kernel<NB, D, false>);
     if (lds > 64 * 1024) {
@@ -340,7 +338,7 @@ template <int NB, int D>
 hipError_t launch_bwd_nb(const BwdArgs& a, hipStream_t st) {
     const unsigned grid = (unsigned)(a.N * a.heads);
     const size_t lds = f32_slab_bytes<NB, D>() + (size_t)2 * 16 * NB * 4;
-    const bool bm = a.bias || a.mask;
+    const bool bm = a.bias || has_mask(a);
     const void* fn = bm ? reinterpret_cast<const void*>(&bwd_f32_tile_kernel<NB, D, true>)
                         : reinterpret_cast<const void*>(&bwd_f32_tile_kernel<NB, D, false>);
     if (lds > 64 * 1024) {

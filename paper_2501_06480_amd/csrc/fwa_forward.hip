@@ -123,13 +123,12 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) fwd_bf16_kernel(FwdArgs p
     }
 
     const float sl2 = p.scale * kLog2e;
-    __amdgpu_buffer_rsrc_t rb = make_rsrc(nullptr, 0), rm = make_rsrc(nullptr, 0);
+    __amdgpu_buffer_rsrc_t rb = make_rsrc(nullptr, 0);
+    MaskSrc msk = {make_rsrc(nullptr, 0), 0.f, false};
     if (BM) {
-        const uint32_t ll = (uint32_t)L * L * 4u;
-        if (p.bias) rb = make_rsrc(p.bias + (size_t)tc.h * L * L, ll);
-        if (p.mask) rm = make_rsrc(p.mask + (size_t)(tc.w % (uint32_t)p.nW) * L * L, ll);
+        if (p.bias) rb = make_rsrc(p.bias + (size_t)tc.h * L * L, (uint32_t)L * L * 4u);
+        msk = mask_of_window(p, tc.w);
     }
-    const uint32_t off_b = ((uint32_t)n * L + 4u * g) * 4u;  // B[n][4g] (plus block offsets)
 
 #pragma unroll
     for (int t = 0; t < QPW; ++t) {
@@ -142,7 +141,7 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) fwd_bf16_kernel(FwdArgs p
             const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
             s[jb] = mfma_bf16(kop[jb], qop[t], zero);  // s[jb][r] = S[16 qb + n][16 jb + 4g + r]
         }
-        const AddendGlobal addend = {rb, rm, off_b + (uint32_t)(16 * qb) * L * 4u};
+        const AddendGlobal addend = addend_at(rb, msk, (uint32_t)(16 * qb + n), 4u * g, (uint32_t)L);
         const float inv = softmax_block<NB, BM>(s, sl2, addend, L, g);
 
         f32x4 oe = {0.f, 0.f, 0.f, 0.f}, oo = {0.f, 0.f, 0.f, 0.f};
@@ -196,13 +195,12 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) fwd_f32_kernel(FwdArgs p,
             kop[jb][4 + c] = b[c];
         }
     }
-    __amdgpu_buffer_rsrc_t rb = make_rsrc(nullptr, 0), rm = make_rsrc(nullptr, 0);
+    __amdgpu_buffer_rsrc_t rb = make_rsrc(nullptr, 0);
+    MaskSrc msk = {make_rsrc(nullptr, 0), 0.f, false};
     if (BM) {
-        const uint32_t ll = (uint32_t)L * L * 4u;
-        if (p.bias) rb = make_rsrc(p.bias + (size_t)tc.h * L * L, ll);
-        if (p.mask) rm = make_rsrc(p.mask + (size_t)(tc.w % (uint32_t)p.nW) * L * L, ll);
+        if (p.bias) rb = make_rsrc(p.bias + (size_t)tc.h * L * L, (uint32_t)L * L * 4u);
+        msk = mask_of_window(p, tc.w);
     }
-    const uint32_t off_b = ((uint32_t)n * L + 4u * g) * 4u;
 
     for (int t = 0; t < QPW; ++t) {
         const int qb = tc.qs * QPW + t;
@@ -217,21 +215,17 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) fwd_f32_kernel(FwdArgs p,
                 qop[4 + c] = b[c];
             }
         }
-        f32x4 s[NB];
+        f32x4 s[NB], add[NB];
+        if (BM) addend_at(rb, msk, (uint32_t)(16 * qb + n), 4u * g, (uint32_t)L).fill(add, 1.0f);
         float m = -INFINITY;
 #pragma unroll
         for (int jb = 0; jb < NB; ++jb) {
             f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int kk = 0; kk < 8; ++kk) acc = mfma_f32(kop[jb][kk], qop[kk], acc);
-            f32x4 add = {0.f, 0.f, 0.f, 0.f};
-            if (BM) {
-                const uint32_t off = off_b + ((uint32_t)(16 * qb) * L + 16 * jb) * 4u;
-                add = load_f32x4(rb, off) + load_f32x4(rm, off);
-            }
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-                float x = acc[r] * p.scale + add[r];
+                float x = BM ? acc[r] * p.scale + add[jb][r] : acc[r] * p.scale;
                 if (jb == NB - 1 && 16 * jb + 4 * g + r >= L) x = -INFINITY;
                 acc[r] = x;
                 m = fmaxf(m, x);
@@ -296,7 +290,7 @@ template <int NB>
 hipError_t launch_bf16_nb(const FwdArgs& a, hipStream_t st) {
     unsigned grid, block;
     const FwdGeom gm = make_geom<NB>(a, &grid, &block);
-    if (a.bias || a.mask)
+    if (a.bias || has_mask(a))
         hipLaunchKernelGGL((fwd_bf16_kernel<NB, true>), dim3(grid), dim3(block), 0, st, a, gm);
     else
         hipLaunchKernelGGL((fwd_bf16_kernel<NB, false>), dim3(grid), dim3(block), 0, st, a, gm);
@@ -307,7 +301,7 @@ template <int NB>
 hipError_t launch_f32_nb(const FwdArgs& a, hipStream_t st) {
     unsigned grid, block;
     const FwdGeom gm = make_geom<NB>(a, &grid, &block);
-    if (a.bias || a.mask)
+    if (a.bias || has_mask(a))
         hipLaunchKernelGGL((fwd_f32_kernel<NB, true>), dim3(grid), dim3(block), 0, st, a, gm);
     else
         hipLaunchKernelGGL((fwd_f32_kernel<NB, false>), dim3(grid), dim3(block), 0, st, a, gm);

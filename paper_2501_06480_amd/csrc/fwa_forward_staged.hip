@@ -78,15 +78,8 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock * QS) fwd_bf16_staged_kern
         const uint32_t ll = (uint32_t)L * L * 4u;
         const uint32_t hh = h < (uint32_t)p.heads ? h : 0u;
         const __amdgpu_buffer_rsrc_t rb = p.bias ? make_rsrc(p.bias + (size_t)hh * L * L, ll) : make_rsrc(nullptr, 0);
-        const __amdgpu_buffer_rsrc_t rm =
-            p.mask ? make_rsrc(p.mask + (size_t)(w % (uint32_t)p.nW) * L * L, ll) : make_rsrc(nullptr, 0);
-        const uint32_t off_b = ((uint32_t)n * L + 4u * g) * 4u;
-#pragma unroll
-        for (int it = 0; it < NQ; ++it) {
-            const AddendGlobal src = {rb, rm, off_b + (uint32_t)(16 * (QS == 1 ? it : qs)) * L * 4u};
-#pragma unroll
-            for (int jb = 0; jb < NB; ++jb) add[it][jb] = src(jb);
-        }
+        const MaskSrc msk = mask_of_window(p, w);
+        fill_rows<NQ, NB>(add, rb, msk, (uint32_t)(16 * (QS == 1 ? 0 : qs) + n), 4u * g, (uint32_t)L, kLog2e);
     }
     uint4* const lk = lds;
     uint4* const lv = lds + ROWS * stride;
@@ -235,15 +228,8 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) fwd_bf16_persistent_kerne
     {
         const uint32_t ll = (uint32_t)L * L * 4u;
         const __amdgpu_buffer_rsrc_t rb = p.bias ? make_rsrc(p.bias + (size_t)h * L * L, ll) : make_rsrc(nullptr, 0);
-        const __amdgpu_buffer_rsrc_t rm =
-            p.mask ? make_rsrc(p.mask + (size_t)(bw % (uint32_t)p.nW) * L * L, ll) : make_rsrc(nullptr, 0);
-        const uint32_t off_b = ((uint32_t)n * L + 4u * g) * 4u;
-#pragma unroll
-        for (int qb = 0; qb < NB; ++qb) {
-            const AddendGlobal src = {rb, rm, off_b + (uint32_t)(16 * qb) * L * 4u};
-#pragma unroll
-            for (int jb = 0; jb < NB; ++jb) add[qb][jb] = src(jb);
-        }
+        const MaskSrc msk = mask_of_window(p, bw);
+        fill_rows<NB, NB>(add, rb, msk, (uint32_t)n, 4u * g, (uint32_t)L, kLog2e);
     }
 
     if (bw < (uint32_t)p.N) park();
@@ -381,13 +367,12 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) fwd_bf16_rowblock_kernel(
                                                 (uint32_t)(L - 1) * row_out + 2u * kHeadDim);
     const uint32_t off_row = (uint32_t)n * row_bytes + 16u * g;
     const float sl2 = p.scale * kLog2e;
-    __amdgpu_buffer_rsrc_t rb = make_rsrc(nullptr, 0), rm = make_rsrc(nullptr, 0);
+    __amdgpu_buffer_rsrc_t rb = make_rsrc(nullptr, 0);
+    MaskSrc msk = {make_rsrc(nullptr, 0), 0.f, false};
     if (BM) {
-        const uint32_t ll = (uint32_t)L * L * 4u;
-        if (p.bias) rb = make_rsrc(p.bias + (size_t)h * L * L, ll);
-        if (p.mask) rm = make_rsrc(p.mask + (size_t)(w % (uint32_t)p.nW) * L * L, ll);
+        if (p.bias) rb = make_rsrc(p.bias + (size_t)h * L * L, (uint32_t)L * L * 4u);
+        msk = mask_of_window(p, w);
     }
-    const uint32_t off_b = ((uint32_t)n * L + 4u * g) * 4u;
     const uint4* const lkh = lk + n * stride + 4 * hl + g;  // K[16 jb + n][8g..] at lkh[16 jb * stride]
     const uint16_t* const lvh = reinterpret_cast<const uint16_t*>(lv) + 32 * hl +
                                 (4 * g + (n >> 2)) * (stride * 8u) + 4 * (n & 3);
@@ -403,7 +388,7 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) fwd_bf16_rowblock_kernel(
             const bf16x8 kop = __builtin_bit_cast(bf16x8, lkh[16 * jb * stride]);
             s[jb] = mfma_bf16(kop, qop, zero);  // S[16 qb + n][16 jb + 4g + r]
         }
-        const AddendGlobal addend = {rb, rm, off_b + (uint32_t)(16 * qb) * L * 4u};
+        const AddendGlobal addend = addend_at(rb, msk, (uint32_t)(16 * qb + n), 4u * g, (uint32_t)L);
         const float inv = softmax_block<NB, BM>(s, sl2, addend, L, g);
         f32x4 o0 = {0.f, 0.f, 0.f, 0.f}, o1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -506,13 +491,9 @@ __global__ void __launch_bounds__(64 * rowpersist_waves(NB)) fwd_bf16_rowpersist
     {
         const uint32_t ll = (uint32_t)L * L * 4u;
         const __amdgpu_buffer_rsrc_t rb = p.bias ? make_rsrc(p.bias + (size_t)h * L * L, ll) : make_rsrc(nullptr, 0);
-        const __amdgpu_buffer_rsrc_t rm =
-            p.mask ? make_rsrc(p.mask + (size_t)(bw % (uint32_t)p.nW) * L * L, ll) : make_rsrc(nullptr, 0);
         // rows beyond L (and the whole block of an idle wave) fall outside the descriptors: zeros
-        const uint32_t off = active ? (((uint32_t)(16 * qb + n)) * L + 4u * g) * 4u : ll;
-#pragma unroll
-        for (int jb = 0; jb < NB; ++jb)
-            add[jb] = (load_f32x4(rb, off + 16 * jb * 4u) + load_f32x4(rm, off + 16 * jb * 4u)) * kLog2e;
+        addend_at(rb, mask_of_window(p, bw), active ? (uint32_t)(16 * qb + n) : (uint32_t)L, 4u * g, (uint32_t)L)
+            .fill(add, kLog2e);
     }
     if (bw < (uint32_t)p.N) park(0);
 
@@ -581,7 +562,7 @@ __global__ void __launch_bounds__(64 * rowpersist_waves(NB)) fwd_bf16_rowpersist
 template <int NB>
 long long rowpersist_slots(const FwdArgs& a) {
     const long long parts = NB <= 12 ? 1 : 2;
-    const long long nW = a.mask ? a.nW : 1;
+    const long long nW = mask_period(a);
     long long G = (256 / ((long long)a.heads * parts)) / nW * nW;
     if (G > a.N / 2) G = (a.N / 2) / nW * nW;
     return G >= nW && G > 0 ? G : 0;
@@ -619,7 +600,7 @@ hipError_t launch_rowblock_nb(const FwdArgs& a, hipStream_t st) {
     gm.xcd_q = grid / 8u;
     gm.xcd_r = grid % 8u;
     const size_t lds = (size_t)2 * 16 * NB * (4 * hpb + 1) * 16;
-    const bool bm = a.bias || a.mask;
+    const bool bm = a.bias || has_mask(a);
     if (bm) {  // without an additive term the walk over windows gains nothing (measured slower)
         const long long G = rowpersist_slots<NB>(a);
         if (G > 0) return launch_rowpersist_nb<NB>(a, G, st);
@@ -649,11 +630,11 @@ hipError_t launch_staged_nb(const FwdArgs& a, int hpb, hipStream_t st) {
     // Fewer window-heads than the chip holds waves (4 per SIMD): one wave per query block instead of
     // one per head, so that the call is not one long round of under-occupied CUs.
     const bool few_tiles = NB > 1 && a.N * a.heads <= 4096;
-    if (a.bias || a.mask) {
+    if (a.bias || has_mask(a)) {
         // Persistent walk over G window positions: a multiple of nW so that a workgroup always
         // sees the same mask tile, about 4 workgroups per CU (measured best of 2..8), at least 2
         // windows per workgroup, and enough workgroups to cover the chip; else one window each.
-        const long long nW = a.mask ? a.nW : 1;
+        const long long nW = mask_period(a);
         long long G = (4 * 256 / (long long)groups) / nW * nW;
         if (G > a.N / 2) G = (a.N / 2) / nW * nW;
         if (G >= nW && G > 0 && G * groups >= 512) {

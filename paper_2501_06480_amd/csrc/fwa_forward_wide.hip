@@ -87,9 +87,7 @@ __global__ void __launch_bounds__(256) fwd_bf16_wide_kernel(FwdArgs p) {
     if (BM) {
         const uint32_t ll = (uint32_t)L * L * 4u;
         const __amdgpu_buffer_rsrc_t rb = p.bias ? make_rsrc(p.bias + (size_t)h * L * L, ll) : make_rsrc(nullptr, 0);
-        const __amdgpu_buffer_rsrc_t rm =
-            p.mask ? make_rsrc(p.mask + (size_t)(w % (uint32_t)p.nW) * L * L, ll) : make_rsrc(nullptr, 0);
-        const AddendGlobal addend = {rb, rm, (((uint32_t)(16 * qb + n)) * L + 4u * g) * 4u};
+        const AddendGlobal addend = addend_at(rb, mask_of_window(p, w), (uint32_t)(16 * qb + n), 4u * g, (uint32_t)L);
         inv = softmax_block<NB, true>(s, sl2, addend, L, g);
     } else {
         inv = softmax_block<NB, false>(s, sl2, AddendNone{}, L, g);
@@ -119,7 +117,7 @@ template <int NB, int D>
 hipError_t launch_wide_nb(const FwdArgs& a, hipStream_t st) {
     const unsigned grid = (unsigned)(a.N * a.heads);
     const size_t lds = (size_t)2 * 16 * NB * (D / 8 + 1) * 16;
-    const bool bm = a.bias || a.mask;
+    const bool bm = a.bias || has_mask(a);
     const void* fn = bm ? reinterpret_cast<const void*>(&fwd_bf16_wide_kernel<NB, D, true>)
                         : reinterpret_cast<const void*>(&fwd_bf16_wide_kernel<NB, D, false>);
     if (lds > 64 * 1024) {

@@ -21,6 +21,8 @@ struct FwdArgs {
     void* o;
     const float* bias;   // [heads, L, L] or nullptr
     const float* mask;   // [nW, L, L] or nullptr
+    const int32_t* labels;  // [nW, L] region labels standing for the mask, or nullptr; never together with mask
+    float mask_value;       // what labels that differ add to a score
     long long N;
     int L;
     int C;
@@ -44,6 +46,8 @@ struct BwdArgs {
     float* stats;        // workspace [N, heads, 2, 16 * ceil(L / 16)] for the row statistics (L > 64 with dbias), or nullptr
     const float* bias;
     const float* mask;
+    const int32_t* labels;  // as in FwdArgs
+    float mask_value;
     long long N;
     int L;
     int C;
@@ -55,6 +59,12 @@ struct BwdArgs {
     int ldg;             // the same for d_o
     int ldd;             // the same for dq, dk, dv
 };
+
+// Whether the scores get a mask, in either form, and its period over the windows (1 without one).
+template <class Args>
+inline bool has_mask(const Args& a) { return a.mask != nullptr || a.labels != nullptr; }
+template <class Args>
+inline int mask_period(const Args& a) { return has_mask(a) ? a.nW : 1; }
 
 // Each returns a hipError_t from the launch (hipSuccess when enqueued).
 hipError_t launch_forward_bf16(const FwdArgs& a, hipStream_t s);

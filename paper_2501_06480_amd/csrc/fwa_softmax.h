@@ -7,25 +7,123 @@
 
 namespace fwa {
 
-// Where the additive term of the scores (bias + mask, in log2 units) comes from.
-// AddendGlobal: two buffer descriptors (absent tensor = null descriptor = zeros); every load
-// takes 4 consecutive columns of one row: 16 bytes, only dword aligned; the range check is per
-// dword, rows beyond L fall outside the descriptor and read as zero.
-struct AddendGlobal {
-    __amdgpu_buffer_rsrc_t rb, rm;
-    uint32_t off;  // byte offset of element [i0 + n][4g] of the tile
-    __device__ __forceinline__ f32x4 operator()(int jb) const {
-        return (load_f32x4(rb, off + 16 * jb * 4u) + load_f32x4(rm, off + 16 * jb * 4u)) * kLog2e;
-    }
+// The shift mask of one window comes in one of two forms: a dense fp32 tile [L, L], or the int32
+// region labels [L] of its tokens, from which M[i][j] = labels[i] == labels[j] ? 0 : value is formed
+// on the fly (L * 4 bytes per window instead of L * L * 4).  An absent mask is a dense one over a
+// null descriptor: every load returns zero.
+struct MaskSrc {
+    __amdgpu_buffer_rsrc_t r;
+    float value;  // what the scores of tokens with different labels receive; labels only
+    bool labels;
 };
+
+template <class Args>
+__device__ __forceinline__ MaskSrc mask_of_window(const Args& p, uint32_t w) {
+    const uint32_t L = (uint32_t)p.L;
+    if (p.labels) return MaskSrc{make_rsrc(p.labels + (size_t)(w % (uint32_t)p.nW) * L, L * 4u), p.mask_value, true};
+    if (p.mask) return MaskSrc{make_rsrc(p.mask + (size_t)(w % (uint32_t)p.nW) * L * L, L * L * 4u), 0.f, false};
+    return MaskSrc{make_rsrc(nullptr, 0), 0.f, false};
+}
+
+// Mask values of 4 consecutive columns of a row from the labels: lq = label of the row,
+// lk = labels of the columns.
+__device__ __forceinline__ f32x4 mask_of_labels(int lq, const i32x4& lk, float value) {
+    return f32x4{lk[0] == lq ? 0.f : value, lk[1] == lq ? 0.f : value, lk[2] == lq ? 0.f : value,
+                 lk[3] == lq ? 0.f : value};
+}
+
+// "Key on the lane": mask values M[i0 .. i0 + 3][j] for a lane that owns column j and 4 consecutive
+// rows (i0 a multiple of 4).  Dense tiles cost 4 dword loads, labels one dword and one 16-byte load.
+__device__ __forceinline__ f32x4 mask_rows4(const MaskSrc& m, uint32_t i0, uint32_t j, uint32_t L) {
+    if (m.labels) return mask_of_labels(load_i32(m.r, 4u * j), load_i32x4(m.r, 4u * i0), m.value);
+    const uint32_t off = (i0 * L + j) * 4u;
+    return f32x4{load_f32(m.r, off), load_f32(m.r, off + 4u * L), load_f32(m.r, off + 8u * L), load_f32(m.r, off + 12u * L)};
+}
+
+// Where the additive term of the scores (bias + mask) comes from.
+// AddendGlobal: the bias tile of the head and the mask of the window; every load takes 4
+// consecutive columns of the lane's row i: 16 bytes, only dword aligned; the range check is per
+// dword, rows beyond L fall outside the descriptors and read as zero (label 0 for the mask).
+struct AddendGlobal {
+    __amdgpu_buffer_rsrc_t rb;
+    MaskSrc m;
+    uint32_t off;     // byte offset of element [i][j0] of an [L, L] fp32 tile, j0 = 4g
+    uint32_t i4, j4;  // 4 i and 4 j0: byte offsets of the labels of the row and of its first column
+    template <int NB>
+    __device__ __forceinline__ void fill(f32x4 (&add)[NB], float mul) const;
+};
+// The addend of row i (beyond L: zeros), first column j0, of the given bias tile and mask.
+__device__ __forceinline__ AddendGlobal addend_at(__amdgpu_buffer_rsrc_t rb, const MaskSrc& m, uint32_t i, uint32_t j0,
+                                                  uint32_t L) {
+    return AddendGlobal{rb, m, (i * L + j0) * 4u, 4u * i, 4u * j0};
+}
+
+// add[t][jb] = (bias + mask)[i_t][j0 + 16 jb ..+3] * mul for the NQ rows described by `rows`
+// (same bias tile and mask).  Both forms of the mask issue the same loads, back to back and with
+// nothing waiting on them: 16 bytes per key block from the mask descriptor (tile values, or the
+// labels of the 4 columns) next to the bias loads, plus the row's own label.  Only the label form
+// then passes through a uniform branch that turns labels into mask values in place; a dense mask
+// skips it, so that the sums below can be scheduled as late as their consumer allows, as if there
+// were no branch at all.
+template <int NQ, int NB>
+__device__ __forceinline__ void fill_rows(f32x4 (&add)[NQ][NB], const AddendGlobal (&rows)[NQ], float mul) {
+    const MaskSrc& m = rows[0].m;
+    f32x4 mk[NQ][NB];
+    int lq[NQ];
+#pragma unroll
+    for (int t = 0; t < NQ; ++t) {
+        const uint32_t moff = m.labels ? rows[t].j4 : rows[t].off;
+#pragma unroll
+        for (int jb = 0; jb < NB; ++jb) {
+            add[t][jb] = load_f32x4(rows[t].rb, rows[t].off + 16 * jb * 4u);
+            mk[t][jb] = load_f32x4(m.r, moff + 16 * jb * 4u);
+        }
+        lq[t] = load_i32(m.r, rows[t].i4);  // dense: some element of the tile, unused
+    }
+    if (m.labels) {
+#pragma unroll
+        for (int t = 0; t < NQ; ++t)
+#pragma unroll
+            for (int jb = 0; jb < NB; ++jb)
+                mk[t][jb] = mask_of_labels(lq[t], __builtin_bit_cast(i32x4, mk[t][jb]), m.value);
+    }
+#pragma unroll
+    for (int t = 0; t < NQ; ++t)
+#pragma unroll
+        for (int jb = 0; jb < NB; ++jb) add[t][jb] = (add[t][jb] + mk[t][jb]) * mul;
+}
+// The rows i0, i0 + 16, ... of one bias tile and mask.
+template <int NQ, int NB>
+__device__ __forceinline__ void fill_rows(f32x4 (&add)[NQ][NB], __amdgpu_buffer_rsrc_t rb, const MaskSrc& m, uint32_t i0,
+                                          uint32_t j0, uint32_t L, float mul) {
+    AddendGlobal rows[NQ];
+#pragma unroll
+    for (int t = 0; t < NQ; ++t) rows[t] = addend_at(rb, m, i0 + 16 * t, j0, L);
+    fill_rows<NQ, NB>(add, rows, mul);
+}
+template <int NB>
+__device__ __forceinline__ void AddendGlobal::fill(f32x4 (&add)[NB], float mul) const {
+    f32x4 one[1][NB];
+    const AddendGlobal rows[1] = {*this};
+    fill_rows<1, NB>(one, rows, mul);
+#pragma unroll
+    for (int jb = 0; jb < NB; ++jb) add[jb] = one[0][jb];
+}
 // AddendRegs: the term is already in registers (one f32x4 per key block), times log2e.
 template <int NB>
 struct AddendRegs {
     const f32x4 (&a)[NB];
-    __device__ __forceinline__ f32x4 operator()(int jb) const { return a[jb]; }
+    __device__ __forceinline__ void fill(f32x4 (&add)[NB], float) const {
+#pragma unroll
+        for (int jb = 0; jb < NB; ++jb) add[jb] = a[jb];
+    }
 };
 struct AddendNone {
-    __device__ __forceinline__ f32x4 operator()(int) const { return f32x4{0.f, 0.f, 0.f, 0.f}; }
+    template <int NB>
+    __device__ __forceinline__ void fill(f32x4 (&add)[NB], float) const {
+#pragma unroll
+        for (int jb = 0; jb < NB; ++jb) add[jb] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
 };
 
 // On entry s holds the raw products.  On exit s holds exp(score - rowmax), not yet
@@ -36,12 +134,12 @@ __device__ __forceinline__ float softmax_block(f32x4 (&s)[NB], float sl2, const 
     float mul, mb;  // p = exp2(s * mul - mb)
     if (BM) {
         // Columns beyond L are overwritten with -inf below, whatever was fetched for them.
+        f32x4 add[NB];
+        addend.fill(add, kLog2e);
 #pragma unroll
-        for (int jb = 0; jb < NB; ++jb) {
-            const f32x4 add = addend(jb);
+        for (int jb = 0; jb < NB; ++jb)
 #pragma unroll
-            for (int r = 0; r < 4; ++r) s[jb][r] = fmaf(s[jb][r], sl2, add[r]);
-        }
+            for (int r = 0; r < 4; ++r) s[jb][r] = fmaf(s[jb][r], sl2, add[jb][r]);
 #pragma unroll
         for (int r = 0; r < 4; ++r)
             if (16 * (NB - 1) + 4 * g + r >= L) s[NB - 1][r] = -INFINITY;

@@ -137,3 +137,20 @@ def test_strided_entry_points_check_their_strides(lib):
     assert bwd(288, 96, 100) == b.FWA_ERR_ALIGN
     assert bwd(95, 96, 96) == b.FWA_ERR_SHAPE
 
+
+
+def test_label_entry_points_check_their_arguments(lib):
+    from paper_2501_06480_amd import binding as b
+    fwd = lambda N=4, labels=P + 0x9000, nW=2, ldq=96: lib.fwa_forward_labels(
+        P, P + 0x1000, P + 0x2000, P + 0x3000, N, 49, 96, 3, 0.1, ldq, 96, None, labels, -100.0, nW, 1, None)
+    assert fwd(nW=0) == b.FWA_ERR_SHAPE
+    assert fwd(nW=3) == b.FWA_ERR_SHAPE              # 4 % 3 != 0
+    assert fwd(labels=P + 0x9004) == b.FWA_ERR_ALIGN
+    assert fwd(ldq=95) == b.FWA_ERR_SHAPE
+    assert fwd(N=0, labels=None, nW=0) == b.FWA_OK   # empty batch, no mask: no-op
+    bwd = lambda labels=P + 0x9000, nW=2, dbias=None: lib.fwa_backward_labels(
+        P, P + 0x1000, P + 0x2000, P + 0x3000, P + 0x4000, P + 0x5000, P + 0x6000, dbias, 4, 49, 96, 3, 0.1,
+        96, 96, 96, None, labels, -100.0, nW, 1, None, 0, None)
+    assert bwd(nW=8) == b.FWA_ERR_SHAPE
+    assert bwd(labels=P + 0x9008) == b.FWA_ERR_ALIGN
+    assert bwd(dbias=P + 0x7000) == b.FWA_ERR_WORKSPACE

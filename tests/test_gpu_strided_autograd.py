@@ -80,25 +80,27 @@ def test_strided_dbias_and_stride_checks():
 
 
 @pytest.mark.parametrize("fused", [False, True])
-def test_autograd_wrappers_against_the_oracle(oracle, fused):
+@pytest.mark.parametrize("as_labels", [False, True])
+def test_autograd_wrappers_against_the_oracle(oracle, fused, as_labels):
     import torch
     from paper_2501_06480_amd import autograd
     w = synth.swin_t_stage(1, shifted=True, backward=True).with_N(128)
     x = synth.draw(w)
     bias64 = oracle.bias_gather(x["table"], w.k)
     bias = f32_device(bias64).requires_grad_(True)
-    mask = f32_device(x["mask"])
+    mask = None if as_labels else f32_device(x["mask"])
+    mask_args = {"labels": torch.from_numpy(x["labels"]).cuda()} if as_labels else {}
     g = to_device(x, w, "d_o")
     if fused:
         buf, _ = fused_views(x, w, ("q", "k", "v"), torch)
         buf.requires_grad_(True)
-        o = autograd.window_attention_qkv(buf, w.scale, bias, mask)
+        o = autograd.window_attention_qkv(buf, w.scale, bias, mask, **mask_args)
         o.backward(g)
         d = w.C // w.heads
         grads = [buf.grad[:, :, t].reshape(w.N, w.L, w.C) for t in range(3)]
     else:
         q, k, v = (to_device(x, w, n).requires_grad_(True) for n in ("q", "k", "v"))
-        o = autograd.window_attention(q, k, v, w.heads, w.scale, bias, mask)
+        o = autograd.window_attention(q, k, v, w.heads, w.scale, bias, mask, **mask_args)
         o.backward(g)
         grads = [q.grad, k.grad, v.grad]
     torch.cuda.synchronize()
