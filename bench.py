@@ -124,10 +124,14 @@ def time_other_workloads(torch, fwa, synth, dev):
             else:
                 fwa.fwa_forward(t[0], t[1], t[2], w.heads, w.scale, bias, mask, out=outs[i % nsets], labels=labels)
 
-        for i in range(40):
-            step(i)
+        t_warm = time.perf_counter()  # at least 0.3 s of warm-up: the clocks ramp up over the first launches
+        while True:
+            for i in range(40):
+                step(i)
+            torch.cuda.synchronize()
+            if time.perf_counter() - t_warm > 0.3:
+                break
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        torch.cuda.synchronize()
         e0.record()
         for i in range(iters):
             step(i)

@@ -427,132 +427,151 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) fwd_bf16_rowblock_kernel(
 // 16 rows sits in registers (NB float4 per lane), and the workgroup (W waves = W consecutive
 // query blocks of the head; the head is split over `parts` workgroups when NB > 12) walks the
 // windows bw, bw + G, ... with G a multiple of nW.  K and V of the head go through a double
-// buffered LDS slab, requested one window ahead; one barrier per window.  Workgroups that
+// buffered LDS slab and are requested two windows ahead (one window's slabs wait in registers
+// while the next one's are in flight: 4-5 % over one window ahead at L = 144 and 256); one
+// barrier per window.  Workgroups that
 // share 128-byte lines (the two heads of a pair, the parts of a head) are neighbours in the
 // logical block order, which is mapped so that neighbours run on the same XCD.
 struct RowPersistGeom {
-    uint32_t heads, parts, G;
+    uint32_t groups, parts, G;  // groups = heads / HPB
     uint32_t xcd_q, xcd_r;
 };
 
 constexpr int rowpersist_waves(int nb) { return nb <= 12 ? nb : (nb + 1) / 2; }
 
-template <int NB>
-__global__ void __launch_bounds__(64 * rowpersist_waves(NB)) fwd_bf16_rowpersist_kernel(FwdArgs p, RowPersistGeom gm) {
+// HPB heads per workgroup (HPB W waves): slab rows of HPB * 64 bytes, which are whole 128-byte
+// lines when HPB is even or the whole token row when HPB is the head count.  Used with HPB > 1
+// for L <= 64, where W <= 4.
+template <int NB, int HPB>
+__global__ void __launch_bounds__(64 * HPB * rowpersist_waves(NB)) fwd_bf16_rowpersist_kernel(FwdArgs p, RowPersistGeom gm) {
     constexpr int W = rowpersist_waves(NB);
     constexpr int NB2 = (NB + 1) / 2;
     constexpr int ROWS = 16 * NB;
     constexpr int PASSES = (ROWS + 16 * W - 1) / (16 * W);  // the workgroup moves 16 W slab rows per pass
-    constexpr uint32_t STRIDE = 5;                           // LDS row: 64 bytes of data + 16 of padding
+    constexpr uint32_t TPR = 4 * HPB;                        // threads per slab row, 16 bytes each
+    constexpr uint32_t STRIDE = TPR + 1;                     // LDS row: HPB * 64 bytes of data + 16 of padding
     extern __shared__ __attribute__((aligned(16))) uint4 lds[];  // [2 buffers][K, V][ROWS][STRIDE]
     const int tid = threadIdx.x, lane = tid & 63;
     const int n = lane & 15, g = lane >> 4;
     const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const uint32_t hl = wave / W, wq = wave % W;  // head inside the workgroup, query block inside the part
     const uint32_t lb = xcd_logical_block(blockIdx.x, gm.xcd_q, gm.xcd_r);
     const uint32_t part = lb % gm.parts, bh = lb / gm.parts;
-    const uint32_t h = bh % gm.heads, bw = bh / gm.heads;
-    const int qb = (int)(part * W + wave);
+    const uint32_t grp = bh % gm.groups, bw = bh / gm.groups;
+    const uint32_t h = grp * HPB + hl;
+    const int qb = (int)(part * W + wq);
     const bool active = qb < NB;
     const int L = p.L;
     const uint32_t row_bytes = (uint32_t)p.ldq * 2u, row_out = (uint32_t)p.ldo * 2u;
     const float sl2 = p.scale * kLog2e;
 
-    const uint32_t srow = (uint32_t)tid >> 2, scol = (uint32_t)tid & 3u;  // slab movement: thread -> (row, 16 B column)
-    const uint32_t tile_bytes = (uint32_t)(L - 1) * row_bytes + 2u * kHeadDim;
-    const uint32_t off_row = (uint32_t)(16 * qb + n) * row_bytes + 16u * g;
-    u32x4 pk[PASSES], pv[PASSES], qnext = {0u, 0u, 0u, 0u};
-    auto request = [&](uint32_t w) {
-        const size_t tile = ((size_t)w * L * p.ldq + (size_t)h * kHeadDim) * 2u;
+    const uint32_t srow = (uint32_t)tid / TPR, scol = (uint32_t)tid % TPR;  // slab movement: thread -> (row, 16 B column)
+    const uint32_t tile_bytes = (uint32_t)(L - 1) * row_bytes + 2u * kHeadDim * HPB;
+    const uint32_t off_row = (uint32_t)(16 * qb + n) * row_bytes + 64u * hl + 16u * g;
+    // Two register sets of slab data: while window w is computed out of LDS, the slabs of w + step
+    // sit in one set (requested an iteration ago, parked at the end of this one) and those of
+    // w + 2 step are requested into the other, so that two windows are in flight per workgroup.
+    struct Slab {
+        u32x4 k[PASSES], v[PASSES], q;
+    };
+    Slab sa, sb;
+    sa.q = sb.q = u32x4{0u, 0u, 0u, 0u};
+    auto request = [&](Slab& d, uint32_t w) {
+        const size_t tile = ((size_t)w * L * p.ldq + (size_t)grp * HPB * kHeadDim) * 2u;
         const __amdgpu_buffer_rsrc_t rk = make_rsrc((const char*)p.k + tile, tile_bytes);
         const __amdgpu_buffer_rsrc_t rv = make_rsrc((const char*)p.v + tile, tile_bytes);
 #pragma unroll
         for (int t = 0; t < PASSES; ++t) {
             const uint32_t off = (16 * W * t + srow) * row_bytes + scol * 16u;  // rows beyond L arrive as zeros
-            pk[t] = __builtin_amdgcn_raw_buffer_load_b128(rk, off, 0, 0);
-            pv[t] = __builtin_amdgcn_raw_buffer_load_b128(rv, off, 0, 0);
+            d.k[t] = __builtin_amdgcn_raw_buffer_load_b128(rk, off, 0, 0);
+            d.v[t] = __builtin_amdgcn_raw_buffer_load_b128(rv, off, 0, 0);
         }
         if (active)
-            qnext = __builtin_amdgcn_raw_buffer_load_b128(make_rsrc((const char*)p.q + tile, tile_bytes), off_row, 0, 0);
+            d.q = __builtin_amdgcn_raw_buffer_load_b128(make_rsrc((const char*)p.q + tile, tile_bytes), off_row, 0, 0);
     };
-    auto park = [&](uint32_t b) {
+    auto park = [&](const Slab& d, uint32_t b) {
         uint4* const dk = lds + b * (2 * ROWS * STRIDE);
         uint4* const dv = dk + ROWS * STRIDE;
 #pragma unroll
         for (int t = 0; t < PASSES; ++t) {
             const uint32_t row = 16 * W * t + srow;
             if (row < (uint32_t)ROWS) {
-                dk[row * STRIDE + scol] = __builtin_bit_cast(uint4, pk[t]);
-                dv[row * STRIDE + scol] = __builtin_bit_cast(uint4, pv[t]);
+                dk[row * STRIDE + scol] = __builtin_bit_cast(uint4, d.k[t]);
+                dv[row * STRIDE + scol] = __builtin_bit_cast(uint4, d.v[t]);
             }
         }
     };
-    if (bw < (uint32_t)p.N) request(bw);  // in flight while the additive term is fetched
+    // The windows of this workgroup: w0, w0 + step, ... below `end`
+    uint32_t w0 = bw, step = gm.G, end = (uint32_t)p.N;
+    if (w0 < end) request(sa, w0);  // in flight while the additive term is fetched
+    if (w0 + step < end) request(sb, w0 + step);
     f32x4 add[NB];
     {
         const uint32_t ll = (uint32_t)L * L * 4u;
         const __amdgpu_buffer_rsrc_t rb = p.bias ? make_rsrc(p.bias + (size_t)h * L * L, ll) : make_rsrc(nullptr, 0);
         // rows beyond L (and the whole block of an idle wave) fall outside the descriptors: zeros
-        addend_at(rb, mask_of_window(p, bw), active ? (uint32_t)(16 * qb + n) : (uint32_t)L, 4u * g, (uint32_t)L)
+        addend_at(rb, mask_of_window(p, w0), active ? (uint32_t)(16 * qb + n) : (uint32_t)L, 4u * g, (uint32_t)L)
             .fill(add, kLog2e);
     }
-    if (bw < (uint32_t)p.N) park(0);
+    if (w0 < end) park(sa, 0);
 
-    // Per window: request the next slabs, one barrier, compute from buffer `buf`, store, then park
-    // the next slabs in the other buffer.  That buffer was last read in the previous iteration,
-    // which every wave has left before any wave passes this iteration's barrier; and parking after
-    // the stores means the wait in front of it counts the stores out instead of waiting for them.
-    uint32_t buf = 0;
-    for (uint32_t w = bw; w < (uint32_t)p.N; w += gm.G, buf ^= 1u) {
-        const bool has_next = w + gm.G < (uint32_t)p.N;
+    // One window: K, V of window w are in LDS buffer `buf`, its Q rows in cur.q; nxt holds window
+    // w + step.  Request w + 2 step into cur, one barrier, compute, store, then park nxt in the
+    // other buffer.  That buffer was last read in the previous iteration, which every wave has left
+    // before any wave passes this iteration's barrier; and parking after the stores means the wait
+    // in front of it counts the stores and the younger loads out instead of waiting for them.
+    auto window = [&](uint32_t w, Slab& cur, const Slab& nxt, uint32_t buf) {
+        const bool has_next = w + step < end;
         uint4* const lk = lds + buf * (2 * ROWS * STRIDE);
         uint4* const lv = lk + ROWS * STRIDE;
-        const bf16x8 qop = as_bf16x8(qnext);
-        if (has_next) request(w + gm.G);  // in flight while this window is computed
+        const bf16x8 qop = as_bf16x8(cur.q);
+        if (w + 2 * step < end) request(cur, w + 2 * step);
         __syncthreads();
-        if (!active) {
-            if (has_next) park(buf ^ 1u);
-            continue;
-        }
-
-        const uint4* const lkh = lk + n * STRIDE + g;  // K[16 jb + n][8g..] at lkh[16 jb * STRIDE]
-        const uint16_t* const lvh =
-            reinterpret_cast<const uint16_t*>(lv) + (4 * g + (n >> 2)) * (STRIDE * 8u) + 4 * (n & 3);
-        f32x4 s[NB];
+        if (active) {
+            const uint4* const lkh = lk + n * STRIDE + 4 * hl + g;  // K[16 jb + n][8g..] of head hl at lkh[16 jb * STRIDE]
+            const uint16_t* const lvh =
+                reinterpret_cast<const uint16_t*>(lv) + 32 * hl + (4 * g + (n >> 2)) * (STRIDE * 8u) + 4 * (n & 3);
+            f32x4 s[NB];
 #pragma unroll
-        for (int jb = 0; jb < NB; ++jb) {
-            const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
-            s[jb] = mfma_bf16(__builtin_bit_cast(bf16x8, lkh[16 * jb * STRIDE]), qop, zero);  // S[16 qb + n][16 jb + 4g + r]
-        }
-        const AddendRegs<NB> addend = {add};
-        const float inv = softmax_block<NB, true>(s, sl2, addend, L, g);
-        f32x4 o0 = {0.f, 0.f, 0.f, 0.f}, o1 = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int kp = 0; kp < NB2; ++kp) {
-            const bf16x8 pop = prob_operand<NB>(s, kp);
-#pragma unroll
-            for (int c = 0; c < 2; ++c) {
-                const uint2 a = lds_read_tr(lvh + (32 * kp) * (STRIDE * 8u) + 16 * c);
-                uint2 b = {0u, 0u};
-                if (2 * kp + 1 < NB) b = lds_read_tr(lvh + (32 * kp + 16) * (STRIDE * 8u) + 16 * c);
-                const u32x4 v = {a.x, a.y, b.x, b.y};
-                if (c == 0)
-                    o0 = mfma_bf16(as_bf16x8(v), pop, o0);  // o0[r] = O[16 qb + n][4g + r]
-                else
-                    o1 = mfma_bf16(as_bf16x8(v), pop, o1);  // o1[r] = O[16 qb + n][16 + 4g + r]
+            for (int jb = 0; jb < NB; ++jb) {
+                const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+                s[jb] = mfma_bf16(__builtin_bit_cast(bf16x8, lkh[16 * jb * STRIDE]), qop, zero);  // S[16 qb + n][16 jb + 4g + r]
             }
+            const AddendRegs<NB> addend = {add};
+            const float inv = softmax_block<NB, true>(s, sl2, addend, L, g);
+            f32x4 o0 = {0.f, 0.f, 0.f, 0.f}, o1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int kp = 0; kp < NB2; ++kp) {
+                const bf16x8 pop = prob_operand<NB>(s, kp);
+#pragma unroll
+                for (int c = 0; c < 2; ++c) {
+                    const uint2 a = lds_read_tr(lvh + (32 * kp) * (STRIDE * 8u) + 16 * c);
+                    uint2 b = {0u, 0u};
+                    if (2 * kp + 1 < NB) b = lds_read_tr(lvh + (32 * kp + 16) * (STRIDE * 8u) + 16 * c);
+                    const u32x4 v = {a.x, a.y, b.x, b.y};
+                    if (c == 0)
+                        o0 = mfma_bf16(as_bf16x8(v), pop, o0);  // o0[r] = O[16 qb + n][4g + r]
+                    else
+                        o1 = mfma_bf16(as_bf16x8(v), pop, o1);  // o1[r] = O[16 qb + n][16 + 4g + r]
+                }
+            }
+            typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+            u32x2 lo, hi;
+            lo.x = pack_bf16(o0[0] * inv, o0[1] * inv);
+            lo.y = pack_bf16(o0[2] * inv, o0[3] * inv);
+            hi.x = pack_bf16(o1[0] * inv, o1[1] * inv);
+            hi.y = pack_bf16(o1[2] * inv, o1[3] * inv);
+            const size_t tile = ((size_t)w * L * p.ldo + (size_t)h * kHeadDim) * 2u;
+            const __amdgpu_buffer_rsrc_t ro = make_rsrc((char*)p.o + tile, (uint32_t)(L - 1) * row_out + 2u * kHeadDim);
+            const uint32_t off_o = (uint32_t)(16 * qb + n) * row_out + 8u * g;
+            __builtin_amdgcn_raw_buffer_store_b64(lo, ro, off_o, 0, 0);
+            __builtin_amdgcn_raw_buffer_store_b64(hi, ro, off_o + 32, 0, 0);
         }
-        typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-        u32x2 lo, hi;
-        lo.x = pack_bf16(o0[0] * inv, o0[1] * inv);
-        lo.y = pack_bf16(o0[2] * inv, o0[3] * inv);
-        hi.x = pack_bf16(o1[0] * inv, o1[1] * inv);
-        hi.y = pack_bf16(o1[2] * inv, o1[3] * inv);
-        const size_t tile = ((size_t)w * L * p.ldo + (size_t)h * kHeadDim) * 2u;
-        const __amdgpu_buffer_rsrc_t ro = make_rsrc((char*)p.o + tile, (uint32_t)(L - 1) * row_out + 2u * kHeadDim);
-        const uint32_t off_o = (uint32_t)(16 * qb + n) * row_out + 8u * g;
-        __builtin_amdgcn_raw_buffer_store_b64(lo, ro, off_o, 0, 0);
-        __builtin_amdgcn_raw_buffer_store_b64(hi, ro, off_o + 32, 0, 0);
-        if (has_next) park(buf ^ 1u);
+        if (has_next) park(nxt, buf ^ 1u);
+    };
+    for (uint32_t w = w0; w < end; w += 2 * step) {
+        window(w, sa, sb, 0u);
+        if (w + step < end) window(w + step, sb, sa, 1u);
     }
 }
 
@@ -568,23 +587,28 @@ long long rowpersist_slots(const FwdArgs& a) {
     return G >= nW && G > 0 ? G : 0;
 }
 
-template <int NB>
-hipError_t launch_rowpersist_nb(const FwdArgs& a, long long G, hipStream_t st) {
+template <int NB, int HPB>
+hipError_t launch_rowpersist_hpb(const FwdArgs& a, long long G, hipStream_t st) {
     RowPersistGeom gm;
-    gm.heads = (uint32_t)a.heads;
+    gm.groups = (uint32_t)(a.heads / HPB);
     gm.parts = NB <= 12 ? 1u : 2u;
     gm.G = (uint32_t)G;
-    const unsigned grid = gm.G * gm.heads * gm.parts, block = 64u * (unsigned)rowpersist_waves(NB);
+    const unsigned grid = gm.G * gm.groups * gm.parts, block = 64u * (unsigned)(HPB * rowpersist_waves(NB));
     gm.xcd_q = grid / 8u;
     gm.xcd_r = grid % 8u;
-    const size_t lds = (size_t)2 * 2 * 16 * NB * 5 * 16;
+    const size_t lds = (size_t)2 * 2 * 16 * NB * (4 * HPB + 1) * 16;
     if (lds > 64 * 1024) {
-        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&fwd_bf16_rowpersist_kernel<NB>),
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&fwd_bf16_rowpersist_kernel<NB, HPB>),
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL((fwd_bf16_rowpersist_kernel<NB>), dim3(grid), dim3(block), lds, st, a, gm);
+    hipLaunchKernelGGL((fwd_bf16_rowpersist_kernel<NB, HPB>), dim3(grid), dim3(block), lds, st, a, gm);
     return hipGetLastError();
+}
+
+template <int NB>
+hipError_t launch_rowpersist_nb(const FwdArgs& a, long long G, hipStream_t st) {
+    return launch_rowpersist_hpb<NB, 1>(a, G, st);
 }
 
 template <int NB>
@@ -635,6 +659,20 @@ hipError_t launch_staged_nb(const FwdArgs& a, int hpb, hipStream_t st) {
         // sees the same mask tile, about 4 workgroups per CU (measured best of 2..8), at least 2
         // windows per workgroup, and enough workgroups to cover the chip; else one window each.
         const long long nW = mask_period(a);
+        // All heads of a window in one workgroup (2..4 heads): one wave per head and query block, one
+        // workgroup per CU, two windows in flight per workgroup (measured 3 % faster on Swin-T stage 1
+        // than one wave per head, and slower than it with more than one workgroup per CU).
+        if (groups == 1 && hpb > 1) {
+            long long G1 = 256 / nW * nW;
+            if (G1 > a.N / 2) G1 = (a.N / 2) / nW * nW;
+            if (G1 >= nW && G1 >= 128) {
+                switch (hpb) {
+                    case 2: return launch_rowpersist_hpb<NB, 2>(a, G1, st);
+                    case 3: return launch_rowpersist_hpb<NB, 3>(a, G1, st);
+                    default: return launch_rowpersist_hpb<NB, 4>(a, G1, st);
+                }
+            }
+        }
         long long G = (4 * 256 / (long long)groups) / nW * nW;
         if (G > a.N / 2) G = (a.N / 2) / nW * nW;
         if (G >= nW && G > 0 && G * groups >= 512) {

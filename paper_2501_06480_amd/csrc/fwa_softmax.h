@@ -129,7 +129,9 @@ struct AddendNone {
 // On entry s holds the raw products.  On exit s holds exp(score - rowmax), not yet
 // normalised; the return value is 1 / rowsum.  Scores are scale * s + addend (BM) or
 // scale * s (no bias/mask), and columns j >= L are excluded.
-template <int NB, bool BM, class Addend>
+// KT < 4 promises L <= 16 (NB - 1) + KT: of the last key block only the components r < KT can be
+// real columns (e.g. KT = 1 for L = 49), the others are set to zero without any arithmetic.
+template <int NB, bool BM, class Addend, int KT = 4>
 __device__ __forceinline__ float softmax_block(f32x4 (&s)[NB], float sl2, const Addend& addend, int L, int g) {
     float mul, mb;  // p = exp2(s * mul - mb)
     if (BM) {
@@ -139,16 +141,15 @@ __device__ __forceinline__ float softmax_block(f32x4 (&s)[NB], float sl2, const 
 #pragma unroll
         for (int jb = 0; jb < NB; ++jb)
 #pragma unroll
-            for (int r = 0; r < 4; ++r) s[jb][r] = fmaf(s[jb][r], sl2, add[jb][r]);
+            for (int r = 0; r < (jb == NB - 1 ? KT : 4); ++r) s[jb][r] = fmaf(s[jb][r], sl2, add[jb][r]);
 #pragma unroll
-        for (int r = 0; r < 4; ++r)
+        for (int r = 0; r < KT; ++r)
             if (16 * (NB - 1) + 4 * g + r >= L) s[NB - 1][r] = -INFINITY;
         float m = s[0][0];
 #pragma unroll
-        for (int jb = 0; jb < NB; ++jb) {
-            m = fmaxf(fmaxf(m, s[jb][0]), s[jb][1]);
-            m = fmaxf(fmaxf(m, s[jb][2]), s[jb][3]);
-        }
+        for (int jb = 0; jb < NB; ++jb)
+#pragma unroll
+            for (int r = 0; r < (jb == NB - 1 ? KT : 4); ++r) m = fmaxf(m, s[jb][r]);
         mul = 1.0f;
         mb = max_over_g(m);
     } else {
@@ -157,22 +158,20 @@ __device__ __forceinline__ float softmax_block(f32x4 (&s)[NB], float sl2, const 
         // sl2 * max(s); a negative scale uses the minimum instead.
         const float pad = sl2 >= 0.f ? -INFINITY : INFINITY;
 #pragma unroll
-        for (int r = 0; r < 4; ++r)
+        for (int r = 0; r < KT; ++r)
             if (16 * (NB - 1) + 4 * g + r >= L) s[NB - 1][r] = pad;
         float m = s[0][0];
         if (sl2 >= 0.f) {
 #pragma unroll
-            for (int jb = 0; jb < NB; ++jb) {
-                m = fmaxf(fmaxf(m, s[jb][0]), s[jb][1]);
-                m = fmaxf(fmaxf(m, s[jb][2]), s[jb][3]);
-            }
+            for (int jb = 0; jb < NB; ++jb)
+#pragma unroll
+                for (int r = 0; r < (jb == NB - 1 ? KT : 4); ++r) m = fmaxf(m, s[jb][r]);
             m = max_over_g(m);
         } else {
 #pragma unroll
-            for (int jb = 0; jb < NB; ++jb) {
-                m = fminf(fminf(m, s[jb][0]), s[jb][1]);
-                m = fminf(fminf(m, s[jb][2]), s[jb][3]);
-            }
+            for (int jb = 0; jb < NB; ++jb)
+#pragma unroll
+                for (int r = 0; r < (jb == NB - 1 ? KT : 4); ++r) m = fminf(m, s[jb][r]);
             m = -max_over_g(-m);
         }
         mul = sl2;
@@ -183,6 +182,10 @@ __device__ __forceinline__ float softmax_block(f32x4 (&s)[NB], float sl2, const 
     for (int jb = 0; jb < NB; ++jb)
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
+            if (jb == NB - 1 && r >= KT) {
+                s[jb][r] = 0.f;
+                continue;
+            }
             const float e = __builtin_amdgcn_exp2f(fmaf(s[jb][r], mul, -mb));
             s[jb][r] = e;
             sum += e;
