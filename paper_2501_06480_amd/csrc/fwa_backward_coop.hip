@@ -37,7 +37,9 @@ struct CoopGeom {
     uint32_t xcd_remap, xcd_q, xcd_r;
 };
 
-template <int NB, bool BM, bool DB>
+// KT < 4 promises that only the first KT of a lane's 4 columns in the last key block can be real
+// (L <= 16 (NB - 1) + KT, e.g. KT = 1 for L = 49): the others are zero without any arithmetic.
+template <int NB, bool BM, bool DB, int KT>
 __global__ void __launch_bounds__(64 * kCoopWavesPerTile * kCoopMaxHeads) bwd_bf16_coop_kernel(BwdArgs p, CoopGeom gm) {
     constexpr int NB2 = (NB + 1) / 2;
     constexpr int ROWS = 16 * NB;
@@ -149,15 +151,15 @@ __global__ void __launch_bounds__(64 * kCoopWavesPerTile * kCoopMaxHeads) bwd_bf
             float inv;
             if (BM) {
                 const AddendRegs<NB> addend = {add};
-                inv = softmax_block<NB, true>(s, sl2, addend, L, g);
+                inv = softmax_block<NB, true, AddendRegs<NB>, KT>(s, sl2, addend, L, g);
             } else {
-                inv = softmax_block<NB, false>(s, sl2, AddendNone{}, L, g);
+                inv = softmax_block<NB, false, AddendNone, KT>(s, sl2, AddendNone{}, L, g);
             }
             float delta = 0.f;
 #pragma unroll
             for (int jb = 0; jb < NB; ++jb)
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
+                for (int r = 0; r < (jb == NB - 1 ? KT : 4); ++r) {
                     s[jb][r] *= inv;  // P
                     delta = fmaf(s[jb][r], dp[jb][r], delta);
                 }
@@ -165,7 +167,8 @@ __global__ void __launch_bounds__(64 * kCoopWavesPerTile * kCoopMaxHeads) bwd_bf
 #pragma unroll
             for (int jb = 0; jb < NB; ++jb) {
 #pragma unroll
-                for (int r = 0; r < 4; ++r) dp[jb][r] = s[jb][r] * (dp[jb][r] - delta);  // dS
+                for (int r = 0; r < 4; ++r)
+                    dp[jb][r] = (jb == NB - 1 && r >= KT) ? 0.f : s[jb][r] * (dp[jb][r] - delta);  // dS
                 if (DB) dbacc[jb] += dp[jb];
             }
             // hi + lo bf16 parts of P and dS: rows of this block into the LDS tiles for phase B
@@ -264,16 +267,24 @@ __global__ void __launch_bounds__(64 * kCoopWavesPerTile * kCoopMaxHeads) bwd_bf
     }
 }
 
-template <int NB, bool BM, bool DB>
-hipError_t launch_coop_one(const BwdArgs& a, const CoopGeom& gm, unsigned grid, unsigned block, size_t lds,
-                           hipStream_t st) {
+template <int NB, bool BM, bool DB, int KT>
+hipError_t launch_coop_kt(const BwdArgs& a, const CoopGeom& gm, unsigned grid, unsigned block, size_t lds,
+                          hipStream_t st) {
     if (lds > 64 * 1024) {
-        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&bwd_bf16_coop_kernel<NB, BM, DB>),
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&bwd_bf16_coop_kernel<NB, BM, DB, KT>),
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL((bwd_bf16_coop_kernel<NB, BM, DB>), dim3(grid), dim3(block), lds, st, a, gm);
+    hipLaunchKernelGGL((bwd_bf16_coop_kernel<NB, BM, DB, KT>), dim3(grid), dim3(block), lds, st, a, gm);
     return hipGetLastError();
+}
+
+template <int NB, bool BM, bool DB>
+hipError_t launch_coop_one(const BwdArgs& a, const CoopGeom& gm, unsigned grid, unsigned block, size_t lds,
+                           hipStream_t st) {
+    // a single column in the last key block (L = 16 (NB - 1) + 1: the 7 x 7 window): the trimmed variant
+    if (a.L == 16 * (NB - 1) + 1 && NB > 1) return launch_coop_kt<NB, BM, DB, 1>(a, gm, grid, block, lds, st);
+    return launch_coop_kt<NB, BM, DB, 4>(a, gm, grid, block, lds, st);
 }
 
 template <int NB>
