@@ -20,8 +20,9 @@
 // Q and dO are therefore read twice from global memory (the second time from L2), which is the
 // paper's own count for its Algorithm 2.
 //
-// A workgroup walks the windows bw, bw + G, ... of its head (G = N, one window each, unless dBias
-// is wanted).  dBias rows of a wave's query block are summed in registers across its windows and
+// A workgroup walks the windows bw, bw + G, ... of its head (G = N, one window each, for widths 64
+// and 128 without dBias; one workgroup per CU at width 256); the K, V slabs and the Q, dO operand
+// rows of the next window are requested during phase B of the current one.  dBias rows of a wave's query block are summed in registers across its windows and
 // leave as per-workgroup partial sums in register order, like those of the kernel for width 32;
 // the same reduce kernel adds the slots.
 #include "fwa_device.h"
@@ -73,16 +74,18 @@ __global__ void __launch_bounds__(256) bwd_bf16_wide_kernel(BwdArgs p, uint32_t 
 #pragma unroll
     for (int jb = 0; jb < NB; ++jb) dbacc[jb] = zero;
 
-    for (uint32_t w = bw; w < (uint32_t)p.N; w += G) {
-    const size_t tile = ((size_t)w * L * p.ldq + (size_t)h * D) * 2u;
-    const size_t tile_g = ((size_t)w * L * p.ldg + (size_t)h * D) * 2u;
-    const size_t tile_d = ((size_t)w * L * p.ldd + (size_t)h * D) * 2u;
-    const __amdgpu_buffer_rsrc_t rq = make_rsrc((const char*)p.q + tile, tile_bytes);
-    const __amdgpu_buffer_rsrc_t rg = make_rsrc((const char*)p.d_o + tile_g, tile_bytes_g);
-
-    // own Q and dO rows as operands: lane (g, n) takes channels 32 c + 8g .. + 7 of row 16 role + n
+    // Requested one window ahead, during phase B of the window before: the K and V slabs (in
+    // registers until the slab area is free) and the wave's own Q and dO rows as operands:
+    // lane (g, n) takes channels 32 c + 8g .. + 7 of row 16 role + n.
+    u32x4 sk[PASSES], sv[PASSES];
     bf16x8 qop[CH], gop[CH];
-    {
+    auto request = [&](uint32_t w) {
+        const size_t tile = ((size_t)w * L * p.ldq + (size_t)h * D) * 2u;
+        const size_t tile_g = ((size_t)w * L * p.ldg + (size_t)h * D) * 2u;
+        const __amdgpu_buffer_rsrc_t rq = make_rsrc((const char*)p.q + tile, tile_bytes);
+        const __amdgpu_buffer_rsrc_t rg = make_rsrc((const char*)p.d_o + tile_g, tile_bytes_g);
+        const __amdgpu_buffer_rsrc_t rk = make_rsrc((const char*)p.k + tile, tile_bytes);
+        const __amdgpu_buffer_rsrc_t rv = make_rsrc((const char*)p.v + tile, tile_bytes);
         const uint32_t off = (uint32_t)(16 * role + n) * row_bytes + 16u * g;
         const uint32_t off_g = (uint32_t)(16 * role + n) * row_g + 16u * g;
 #pragma unroll
@@ -90,24 +93,28 @@ __global__ void __launch_bounds__(256) bwd_bf16_wide_kernel(BwdArgs p, uint32_t 
             qop[c] = as_bf16x8(__builtin_amdgcn_raw_buffer_load_b128(rq, off + 64 * c, 0, 0));
             gop[c] = as_bf16x8(__builtin_amdgcn_raw_buffer_load_b128(rg, off_g + 64 * c, 0, 0));
         }
-    }
-    {
-        const __amdgpu_buffer_rsrc_t rk = make_rsrc((const char*)p.k + tile, tile_bytes);
-        const __amdgpu_buffer_rsrc_t rv = make_rsrc((const char*)p.v + tile, tile_bytes);
-        u32x4 sk[PASSES], sv[PASSES];
 #pragma unroll
         for (int t = 0; t < PASSES; ++t) {
-            const uint32_t off = (RPP * t + srow) * row_bytes + scol * 16u;
-            sk[t] = __builtin_amdgcn_raw_buffer_load_b128(rk, off, 0, 0);
-            sv[t] = __builtin_amdgcn_raw_buffer_load_b128(rv, off, 0, 0);
+            const uint32_t o = (RPP * t + srow) * row_bytes + scol * 16u;
+            sk[t] = __builtin_amdgcn_raw_buffer_load_b128(rk, o, 0, 0);
+            sv[t] = __builtin_amdgcn_raw_buffer_load_b128(rv, o, 0, 0);
         }
+    };
+    if (bw < (uint32_t)p.N) request(bw);
+
+    for (uint32_t w = bw; w < (uint32_t)p.N; w += G) {
+    const bool has_next = w + G < (uint32_t)p.N;
+    const size_t tile = ((size_t)w * L * p.ldq + (size_t)h * D) * 2u;
+    const size_t tile_g = ((size_t)w * L * p.ldg + (size_t)h * D) * 2u;
+    const size_t tile_d = ((size_t)w * L * p.ldd + (size_t)h * D) * 2u;
+    const __amdgpu_buffer_rsrc_t rq = make_rsrc((const char*)p.q + tile, tile_bytes);
+    const __amdgpu_buffer_rsrc_t rg = make_rsrc((const char*)p.d_o + tile_g, tile_bytes_g);
 #pragma unroll
-        for (int t = 0; t < PASSES; ++t) {
-            const uint32_t row = RPP * t + srow;
-            if (row < (uint32_t)ROWS) {
-                sa[row * STRIDE + scol] = __builtin_bit_cast(uint4, sk[t]);
-                sb[row * STRIDE + scol] = __builtin_bit_cast(uint4, sv[t]);
-            }
+    for (int t = 0; t < PASSES; ++t) {
+        const uint32_t row = RPP * t + srow;
+        if (row < (uint32_t)ROWS) {
+            sa[row * STRIDE + scol] = __builtin_bit_cast(uint4, sk[t]);
+            sb[row * STRIDE + scol] = __builtin_bit_cast(uint4, sv[t]);
         }
     }
     // the Q and dO slabs for phase B, in flight during phase A
@@ -206,6 +213,7 @@ __global__ void __launch_bounds__(256) bwd_bf16_wide_kernel(BwdArgs p, uint32_t 
         }
     }
     __syncthreads();
+    if (has_next) request(w + G);  // in flight during phase B
 
     // ---------------- phase B: key block `role` ----------------
     if (active) {
@@ -245,7 +253,7 @@ __global__ void __launch_bounds__(256) bwd_bf16_wide_kernel(BwdArgs p, uint32_t 
             __builtin_amdgcn_raw_buffer_store_b64(vk, rdk, off_half + 16 * jb * row_d + 32 * cb, 0, 0);
         }
     }
-    if (w + G < (uint32_t)p.N) __syncthreads();  // slabs and tiles are rewritten for the next window
+    if (has_next) __syncthreads();  // slabs and tiles are rewritten for the next window
     }
 
     if (DB && active) {
@@ -271,9 +279,15 @@ template <int NB, int D>
 hipError_t launch_wide_nb(const BwdArgs& a, hipStream_t st) {
     const size_t lds = (size_t)2 * 16 * NB * (D / 8 + 1) * 16 + (size_t)4 * 16 * NB * 64 * 2;
     const bool bm = a.bias || has_mask(a);
-    if (a.dbias == nullptr)  // one window per workgroup
-        return bm ? launch_wide_one<NB, D, true, false>(a, (unsigned)a.N, lds, st)
-                  : launch_wide_one<NB, D, false, false>(a, (unsigned)a.N, lds, st);
+    if (a.dbias == nullptr) {
+        // Width 256 (100 KB of LDS: one workgroup per CU): as many window positions as workgroups stay
+        // resident, 5 % faster than one window per workgroup; narrower heads (2-3 workgroups per
+        // CU) are 5-8 % faster with one window each.
+        long long G0 = a.N;
+        if (D == 256 && a.N > 256 / a.heads) G0 = 256 / a.heads > 0 ? 256 / a.heads : 1;
+        return bm ? launch_wide_one<NB, D, true, false>(a, (unsigned)G0, lds, st)
+                  : launch_wide_one<NB, D, false, false>(a, (unsigned)G0, lds, st);
+    }
     const unsigned G = (unsigned)a.slots;
     const hipError_t e = bm ? launch_wide_one<NB, D, true, true>(a, G, lds, st)
                             : launch_wide_one<NB, D, false, true>(a, G, lds, st);
