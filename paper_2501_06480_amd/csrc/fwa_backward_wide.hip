@@ -21,8 +21,8 @@
 // paper's own count for its Algorithm 2.
 //
 // A workgroup walks the windows bw, bw + G, ... of its head (G = N, one window each, for widths 64
-// and 128 without dBias; one workgroup per CU at width 256); the K, V slabs and the Q, dO operand
-// rows of the next window are requested during phase B of the current one.  dBias rows of a wave's query block are summed in registers across its windows and
+// and 128 without dBias; one workgroup per CU at width 256); the K, V slabs of the next window are
+// requested during phase B of the current one.  dBias rows of a wave's query block are summed in registers across its windows and
 // leave as per-workgroup partial sums in register order, like those of the kernel for width 32;
 // the same reduce kernel adds the slots.
 #include "fwa_device.h"
@@ -74,25 +74,13 @@ __global__ void __launch_bounds__(256) bwd_bf16_wide_kernel(BwdArgs p, uint32_t 
 #pragma unroll
     for (int jb = 0; jb < NB; ++jb) dbacc[jb] = zero;
 
-    // Requested one window ahead, during phase B of the window before: the K and V slabs (in
-    // registers until the slab area is free) and the wave's own Q and dO rows as operands:
-    // lane (g, n) takes channels 32 c + 8g .. + 7 of row 16 role + n.
+    // The K and V slabs are requested one window ahead, during phase B of the window before, and
+    // wait in registers until the slab area is free.
     u32x4 sk[PASSES], sv[PASSES];
-    bf16x8 qop[CH], gop[CH];
     auto request = [&](uint32_t w) {
         const size_t tile = ((size_t)w * L * p.ldq + (size_t)h * D) * 2u;
-        const size_t tile_g = ((size_t)w * L * p.ldg + (size_t)h * D) * 2u;
-        const __amdgpu_buffer_rsrc_t rq = make_rsrc((const char*)p.q + tile, tile_bytes);
-        const __amdgpu_buffer_rsrc_t rg = make_rsrc((const char*)p.d_o + tile_g, tile_bytes_g);
         const __amdgpu_buffer_rsrc_t rk = make_rsrc((const char*)p.k + tile, tile_bytes);
         const __amdgpu_buffer_rsrc_t rv = make_rsrc((const char*)p.v + tile, tile_bytes);
-        const uint32_t off = (uint32_t)(16 * role + n) * row_bytes + 16u * g;
-        const uint32_t off_g = (uint32_t)(16 * role + n) * row_g + 16u * g;
-#pragma unroll
-        for (int c = 0; c < CH; ++c) {
-            qop[c] = as_bf16x8(__builtin_amdgcn_raw_buffer_load_b128(rq, off + 64 * c, 0, 0));
-            gop[c] = as_bf16x8(__builtin_amdgcn_raw_buffer_load_b128(rg, off_g + 64 * c, 0, 0));
-        }
 #pragma unroll
         for (int t = 0; t < PASSES; ++t) {
             const uint32_t o = (RPP * t + srow) * row_bytes + scol * 16u;
@@ -109,6 +97,18 @@ __global__ void __launch_bounds__(256) bwd_bf16_wide_kernel(BwdArgs p, uint32_t 
     const size_t tile_d = ((size_t)w * L * p.ldd + (size_t)h * D) * 2u;
     const __amdgpu_buffer_rsrc_t rq = make_rsrc((const char*)p.q + tile, tile_bytes);
     const __amdgpu_buffer_rsrc_t rg = make_rsrc((const char*)p.d_o + tile_g, tile_bytes_g);
+    // own Q and dO rows as operands: lane (g, n) takes channels 32 c + 8g .. + 7 of row 16 role + n.
+    // The slab loads below read the same lines a moment later, out of L2.
+    bf16x8 qop[CH], gop[CH];
+    {
+        const uint32_t off = (uint32_t)(16 * role + n) * row_bytes + 16u * g;
+        const uint32_t off_g = (uint32_t)(16 * role + n) * row_g + 16u * g;
+#pragma unroll
+        for (int c = 0; c < CH; ++c) {
+            qop[c] = as_bf16x8(__builtin_amdgcn_raw_buffer_load_b128(rq, off + 64 * c, 0, 0));
+            gop[c] = as_bf16x8(__builtin_amdgcn_raw_buffer_load_b128(rg, off_g + 64 * c, 0, 0));
+        }
+    }
 #pragma unroll
     for (int t = 0; t < PASSES; ++t) {
         const uint32_t row = RPP * t + srow;
