@@ -11,14 +11,13 @@
 //   phase A, wave <-> query block      : own Q, dO rows straight from global memory as operands;
 //                                        softmax, delta, dS; dQ; P and dS as hi + lo bf16 into
 //                                        swizzled LDS tiles
-//   LDS, second half                   : the Q, dO slabs take the place of K, V (requested from
-//                                        global memory before phase A, parked after it)
+//   LDS, second half                   : the Q, dO slabs take the place of K, V, written by the
+//                                        waves from the operand registers of phase A
 //   phase B, wave <-> key block        : dV^T = dO^T P, dK^T = Q^T dS with P, dS (key on the lane)
 //                                        and dO^T, Q^T (channel on the lane) through the
 //                                        transposing read
 //
-// Q and dO are therefore read twice from global memory (the second time from L2), which is the
-// paper's own count for its Algorithm 2.
+// Every input is read from global memory once.
 //
 // A workgroup walks the windows bw, bw + G, ... of its head (G = N, one window each, for widths 64
 // and 128 without dBias; one workgroup per CU at width 256); the K, V slabs of the next window are
@@ -97,8 +96,7 @@ __global__ void __launch_bounds__(256) bwd_bf16_wide_kernel(BwdArgs p, uint32_t 
     const size_t tile_d = ((size_t)w * L * p.ldd + (size_t)h * D) * 2u;
     const __amdgpu_buffer_rsrc_t rq = make_rsrc((const char*)p.q + tile, tile_bytes);
     const __amdgpu_buffer_rsrc_t rg = make_rsrc((const char*)p.d_o + tile_g, tile_bytes_g);
-    // own Q and dO rows as operands: lane (g, n) takes channels 32 c + 8g .. + 7 of row 16 role + n.
-    // The slab loads below read the same lines a moment later, out of L2.
+    // own Q and dO rows as operands: lane (g, n) takes channels 32 c + 8g .. + 7 of row 16 role + n
     bf16x8 qop[CH], gop[CH];
     {
         const uint32_t off = (uint32_t)(16 * role + n) * row_bytes + 16u * g;
@@ -116,13 +114,6 @@ __global__ void __launch_bounds__(256) bwd_bf16_wide_kernel(BwdArgs p, uint32_t 
             sa[row * STRIDE + scol] = __builtin_bit_cast(uint4, sk[t]);
             sb[row * STRIDE + scol] = __builtin_bit_cast(uint4, sv[t]);
         }
-    }
-    // the Q and dO slabs for phase B, in flight during phase A
-    u32x4 sq[PASSES], sg[PASSES];
-#pragma unroll
-    for (int t = 0; t < PASSES; ++t) {
-        sq[t] = __builtin_amdgcn_raw_buffer_load_b128(rq, (RPP * t + srow) * row_bytes + scol * 16u, 0, 0);
-        sg[t] = __builtin_amdgcn_raw_buffer_load_b128(rg, (RPP * t + srow) * row_g + scol * 16u, 0, 0);
     }
     __syncthreads();
 
@@ -204,12 +195,13 @@ __global__ void __launch_bounds__(256) bwd_bf16_wide_kernel(BwdArgs p, uint32_t 
         }
     }
     __syncthreads();  // K, V no longer needed; tiles complete
+    // The Q and dO slabs of phase B take their place: the four waves hold all rows between them,
+    // as the operands of phase A, and put them down themselves (no second read of Q and dO).
+    if (active) {
 #pragma unroll
-    for (int t = 0; t < PASSES; ++t) {
-        const uint32_t row = RPP * t + srow;
-        if (row < (uint32_t)ROWS) {
-            sa[row * STRIDE + scol] = __builtin_bit_cast(uint4, sq[t]);
-            sb[row * STRIDE + scol] = __builtin_bit_cast(uint4, sg[t]);
+        for (int c = 0; c < CH; ++c) {
+            sa[opd + 16 * role * STRIDE + 4 * c] = __builtin_bit_cast(uint4, qop[c]);
+            sb[opd + 16 * role * STRIDE + 4 * c] = __builtin_bit_cast(uint4, gop[c]);
         }
     }
     __syncthreads();
