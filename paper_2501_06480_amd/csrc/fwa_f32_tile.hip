@@ -203,9 +203,9 @@ __global__ void __launch_bounds__(256) bwd_f32_tile_kernel(BwdArgs p) {
     __syncthreads();
 
     // ---------------- pass 1: query block `role` ----------------
+    f32x4 qv[T::CH], gv[T::CH];  // own Q and dO rows in pass 1; own K and V rows in pass 2 (see below)
     if (active) {
         const int qb = role;
-        f32x4 qv[T::CH], gv[T::CH];
         load_own_rows<D>(qv, rq, row_bytes, qb, n, g);
         load_own_rows<D>(gv, rg, row_g, qb, n, g);
         f32x4 s[NB], dp[NB];
@@ -248,17 +248,30 @@ __global__ void __launch_bounds__(256) bwd_f32_tile_kernel(BwdArgs p) {
             store_f32x4(acc * p.scale, rdq, off_q + 64 * cb);  // acc[r'] = dQ[16 qb + n][16 cb + 4g + r']
         }
     }
-    __syncthreads();  // K, V no longer needed; statistics complete
-    park_slab<D, ROWS>(sa, rq, row_bytes, tid);
-    park_slab<D, ROWS>(sb, rg, row_g, tid);
+    __syncthreads();  // K, V no longer needed as whole slabs; statistics complete
+    // Pass 2 wants the Q and dO slabs in LDS and the wave's own K and V rows in registers: exactly
+    // the other way round.  Between them the waves hold every row of Q and dO, and each wave is now
+    // the only reader of its own 16 rows of the K and V slabs, so it swaps them in place: nothing
+    // is read from global memory a second time.
+    if (active) {
+#pragma unroll
+        for (int c = 0; c < T::CH; ++c) {
+            f32x4* const pk = reinterpret_cast<f32x4*>(sa + (16 * role + n) * T::RS + 16 * c + 4 * g);
+            f32x4* const pv = reinterpret_cast<f32x4*>(sb + (16 * role + n) * T::RS + 16 * c + 4 * g);
+            const f32x4 krow = *pk, vrow = *pv;
+            *pk = qv[c];
+            *pv = gv[c];
+            qv[c] = krow;
+            gv[c] = vrow;
+        }
+    }
     __syncthreads();
 
     // ---------------- pass 2: key block `role` ----------------
     if (active) {
         const int jb = role;
-        f32x4 kv[T::CH], vv[T::CH];
-        load_own_rows<D>(kv, rk, row_bytes, jb, n, g);
-        load_own_rows<D>(vv, rv, row_bytes, jb, n, g);
+        const f32x4 (&kv)[T::CH] = qv;
+        const f32x4 (&vv)[T::CH] = gv;
         const uint32_t jcol = 16u * jb + n;
         const bool valid = jcol < (uint32_t)L;
         f32x4 av[T::CH], ak[T::CH];  // dV, dK [16 jb + n][16 cb + 4g + r]
