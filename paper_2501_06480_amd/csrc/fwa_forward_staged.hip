@@ -673,9 +673,14 @@ hipError_t launch_staged_nb(const FwdArgs& a, int hpb, hipStream_t st) {
                 }
             }
         }
-        long long G = (4 * 256 / (long long)groups) / nW * nW;
+        // as many workgroups as stay resident: the registers of the kernel allow 8 / 12 / 20 / 32 waves per
+        // CU at NB = 4 / 3 / 2 / 1 (a second round of workgroups would double the time of a small call)
+        const long long waves_per_cu = NB == 4 ? 8 : (NB == 3 ? 12 : (NB == 2 ? 20 : 32));
+        long long per_cu = waves_per_cu / hpb;
+        if (per_cu > 4) per_cu = 4;
+        long long G = (per_cu * 256 / (long long)groups) / nW * nW;
         if (G > a.N / 2) G = (a.N / 2) / nW * nW;
-        if (G >= nW && G > 0 && G * groups >= 512) {
+        if (!few_tiles && G >= nW && G > 0 && G * groups >= 256) {
             hipLaunchKernelGGL((fwd_bf16_persistent_kernel<NB>), dim3((unsigned)(G * groups)), dim3(block), lds, st,
                                a, gm, (uint32_t)G);
             return hipGetLastError();
