@@ -96,7 +96,7 @@ def time_other_workloads(torch, fwa, synth, dev):
     rotation rule as the headline (cycle larger than twice the last-level cache)."""
     out = []
 
-    def run(name, w, backward, iters, want_dbias=True, as_labels=False):
+    def run(name, w, backward, iters, want_dbias=True, as_labels=False, bias_bf16=False):
         shape = (w.N, w.L, w.C)
         tdt, esz = (torch.float32, 4) if w.dtype == "f32" else (torch.bfloat16, 2)
         per_set = (7 if backward else 4) * w.N * w.L * w.C * esz
@@ -108,6 +108,8 @@ def time_other_workloads(torch, fwa, synth, dev):
         bias = mask = labels = ws = None
         if w.use_bias:
             bias = fwa.fwa_bias_gather(torch.from_numpy(synth.bias_table(w.heads, w.k, w.seed)).to(dev), w.k)
+            if bias_bf16:
+                bias = bias.to(torch.bfloat16)
         if w.shift and as_labels:  # the mask as region labels, formed inside the kernels
             labels = torch.from_numpy(synth.shift_labels(w.map_hw, w.map_hw, w.k, w.shift)).to(dev)
         elif w.shift:
@@ -194,9 +196,10 @@ def time_other_workloads(torch, fwa, synth, dev):
     run("window16_bwd_bias (N=1024, L=256, 4 heads; dQ, dK, dV)", l256, True, 20, want_dbias=False)
     # shifted 16 x 16 windows of a 32 x 32 map: the dense mask against region labels
     w16s = synth.Workload("window16_shift", 1024, 256, 128, 4, "bf16", 1300, 16, 32, True, 8, True)
-    for form, lab in (("shiftmask", False), ("shiftlabels", True)):
-        run(f"window16_fwd_bias_{form} (N=1024, L=256, 4 heads)", w16s, False, 50, as_labels=lab)
-        run(f"window16_bwd_bias_{form}_dbias (N=1024, L=256, 4 heads)", w16s, True, 20, as_labels=lab)
+    for form, lab, b16 in (("bias_shiftmask", False, False), ("bias_shiftlabels", True, False),
+                           ("bf16bias_shiftlabels", True, True)):
+        run(f"window16_fwd_{form} (N=1024, L=256, 4 heads)", w16s, False, 50, as_labels=lab, bias_bf16=b16)
+        run(f"window16_bwd_{form}_dbias (N=1024, L=256, 4 heads)", w16s, True, 20, as_labels=lab, bias_bf16=b16)
     # the shapes of the paper's own kernel benchmark (section 3.1): L = 64, 4 heads, width per head 64 and 256
     for d in (64, 256):
         pw = synth.Workload(f"paper_L64_d{d}", 4096, 64, 4 * d, 4, "bf16", 1100 + d, 8)

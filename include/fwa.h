@@ -113,7 +113,8 @@ int fwa_backward_strided(const void* q, const void* k, const void* v, const void
                          int dtype, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
- * Forward and backward with the shift mask given as region labels instead of a dense tile
+ * Forward and backward with the shift mask given as region labels instead of a dense tile,
+ * and optionally a bf16 bias
  * (paper Section 2.1: shifted blocks mask attention between tokens that were not neighbours
  * before the cyclic shift; the labels name the regions of the shifted token map):
  *   labels     : NULL (no mask), or in [nW, L] int32; the scores of window n receive
@@ -122,6 +123,9 @@ int fwa_backward_strided(const void* q, const void* k, const void* v, const void
  *                instead of L * L * 4.  Requires nW >= 1 and N % nW == 0; 16-byte aligned.
  *   mask_value : what a pair of tokens with different labels adds to its score (-100 in
  *                the Swin Transformer); ignored when labels is NULL.
+ *   bias       : NULL, or in [heads, L, L] of type bias_dtype: FWA_F32 as everywhere else, or
+ *                FWA_BF16 (half the bytes; the values are used as they are, i.e. the result is
+ *                that of the fp32 call on the same values).  dbias stays fp32.
  * Everything else (shapes, strides, dtype, workspace, error codes, supported ranges) is as in
  * fwa_forward_strided / fwa_backward_strided, and the results are those of the same call with
  * the dense mask written out from the labels.
@@ -129,14 +133,14 @@ int fwa_backward_strided(const void* q, const void* k, const void* v, const void
 int fwa_forward_labels(const void* q, const void* k, const void* v, void* o,
                        int64_t N, int L, int C, int heads, float scale,
                        int64_t ld_qkv, int64_t ld_o,
-                       const float* bias, const int32_t* labels, float mask_value, int nW,
+                       const void* bias, int bias_dtype, const int32_t* labels, float mask_value, int nW,
                        int dtype, void* stream);
 
 int fwa_backward_labels(const void* q, const void* k, const void* v, const void* d_o,
                         void* dq, void* dk, void* dv, float* dbias,
                         int64_t N, int L, int C, int heads, float scale,
                         int64_t ld_qkv, int64_t ld_do, int64_t ld_dqkv,
-                        const float* bias, const int32_t* labels, float mask_value, int nW,
+                        const void* bias, int bias_dtype, const int32_t* labels, float mask_value, int nW,
                         int dtype, void* workspace, size_t workspace_bytes, void* stream);
 
 /* Bytes of workspace fwa_backward needs for these arguments (0 if none).

@@ -58,10 +58,10 @@ def load_library():
     lib.fwa_forward_strided.restype = ci
     lib.fwa_forward_strided.argtypes = [vp, vp, vp, vp, i64, ci, ci, ci, cf, i64, i64, vp, vp, ci, ci, vp]
     lib.fwa_forward_labels.restype = ci
-    lib.fwa_forward_labels.argtypes = [vp, vp, vp, vp, i64, ci, ci, ci, cf, i64, i64, vp, vp, cf, ci, ci, vp]
+    lib.fwa_forward_labels.argtypes = [vp, vp, vp, vp, i64, ci, ci, ci, cf, i64, i64, vp, ci, vp, cf, ci, ci, vp]
     lib.fwa_backward_labels.restype = ci
     lib.fwa_backward_labels.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i64, ci, ci, ci, cf, i64, i64, i64,
-                                        vp, vp, cf, ci, ci, vp, sz, vp]
+                                        vp, ci, vp, cf, ci, ci, vp, sz, vp]
     lib.fwa_backward.restype = ci
     lib.fwa_backward.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i64, ci, ci, ci, cf, vp, vp, ci, ci,
                                  vp, sz, vp]
@@ -159,6 +159,17 @@ class _on_device:
             self.ctx.__exit__(*exc)
 
 
+def _bias_ptr(bias, heads: int, L: int):
+    """(device pointer, dtype code) of a [heads, L, L] bias, fp32 or bf16."""
+    if bias is None:
+        return None, FWA_F32
+    if tuple(bias.shape) != (heads, L, L):
+        raise ValueError("bias must be [heads, L, L]")
+    if bias.dtype == _torch().bfloat16:
+        return _dev_ptr(bias, "bias"), FWA_BF16
+    return _dev_ptr(bias, "bias", f32=True), FWA_F32
+
+
 def _labels_ptr(labels, mask, L: int):
     """(device pointer, nW) of int32 region labels [nW, L]; they stand in for a dense mask."""
     if mask is not None:
@@ -180,25 +191,25 @@ def fwa_forward(q, k, v, heads: int, scale: float, bias=None, mask=None, out=Non
     N, L, C = q.shape
     o = _torch().empty_like(q, memory_format=_torch().contiguous_format) if out is None else out
     nW = 0 if mask is None else int(mask.shape[0])
-    if bias is not None and tuple(bias.shape) != (heads, L, L):
-        raise ValueError("bias must be [heads, L, L]")
+    bp, bias_code = _bias_ptr(bias, heads, L)
     if mask is not None and tuple(mask.shape) != (nW, L, L):
         raise ValueError("mask must be [nW, L, L]")
-    if labels is not None:
-        lp, nW = _labels_ptr(labels, mask, L)
+    if bias_code == FWA_BF16 and mask is not None:
+        raise ValueError("a bf16 bias goes with a mask given as labels (or with no mask), not with a dense mask")
+    if labels is not None or bias_code == FWA_BF16:
+        lp, nW = _labels_ptr(labels, mask, L) if labels is not None else (None, 0)
         (qp, ld), (kp, ldk), (vp, ldv), (op, ldo) = (_row_ptr(q, "q"), _row_ptr(k, "k", q), _row_ptr(v, "v", q),
                                                     _row_ptr(o, "out", q))
         if not ld == ldk == ldv:
             raise ValueError("q, k and v must share one row stride")
         with _on_device(q.device):
             rc = lib.fwa_forward_labels(qp, kp, vp, op, N, L, C, int(heads), float(scale), ld, ldo,
-                                        _dev_ptr(bias, "bias", f32=True), lp, float(mask_value), nW, _dtype_code(q),
+                                        bp, bias_code, lp, float(mask_value), nW, _dtype_code(q),
                                         _stream_handle(stream, q.device))
         if rc != FWA_OK:
             raise FwaError(rc, "fwa_forward_labels")
         return o
-    tail = (_dev_ptr(bias, "bias", f32=True), _dev_ptr(mask, "mask", f32=True), nW, _dtype_code(q),
-            _stream_handle(stream, q.device))
+    tail = (bp, _dev_ptr(mask, "mask", f32=True), nW, _dtype_code(q), _stream_handle(stream, q.device))
     if q.is_contiguous() and k.is_contiguous() and v.is_contiguous() and o.is_contiguous():
         args = (_dev_ptr(q, "q"), _dev_ptr(k, "k", q), _dev_ptr(v, "v", q), _dev_ptr(o, "out", q), N, L, C,
                 int(heads), float(scale)) + tail
@@ -236,19 +247,20 @@ def fwa_backward(q, k, v, d_o, heads: int, scale: float, bias=None, mask=None, w
         dq, dk, dv = out
     dbias = torch.empty((heads, L, L), dtype=torch.float32, device=q.device) if want_dbias else None
     nW = 0 if mask is None else int(mask.shape[0])
-    if bias is not None and tuple(bias.shape) != (heads, L, L):
-        raise ValueError("bias must be [heads, L, L]")
+    bp, bias_code = _bias_ptr(bias, heads, L)
     if mask is not None and tuple(mask.shape) != (nW, L, L):
         raise ValueError("mask must be [nW, L, L]")
+    if bias_code == FWA_BF16 and mask is not None:
+        raise ValueError("a bf16 bias goes with a mask given as labels (or with no mask), not with a dense mask")
     need = fwa_backward_workspace_bytes(N, L, C, heads, _dtype_code(q), want_dbias)
     if workspace is None and need:
         workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
-    tail = (_dev_ptr(bias, "bias", f32=True), _dev_ptr(mask, "mask", f32=True), nW, _dtype_code(q),
+    tail = (bp, _dev_ptr(mask, "mask", f32=True), nW, _dtype_code(q),
             None if workspace is None else workspace.data_ptr(), ws_bytes, _stream_handle(stream, q.device))
     tensors = (q, k, v, d_o, dq, dk, dv)
-    if labels is not None:
-        lp, nW = _labels_ptr(labels, mask, L)
+    if labels is not None or bias_code == FWA_BF16:
+        lp, nW = _labels_ptr(labels, mask, L) if labels is not None else (None, 0)
         rows = [_row_ptr(t, nm, None if nm == "q" else q) for t, nm in zip(tensors, ("q", "k", "v", "d_o", "dq", "dk", "dv"))]
         if not rows[0][1] == rows[1][1] == rows[2][1]:
             raise ValueError("q, k and v must share one row stride")
@@ -256,7 +268,7 @@ def fwa_backward(q, k, v, d_o, heads: int, scale: float, bias=None, mask=None, w
             raise ValueError("dq, dk and dv must share one row stride")
         args = tuple(r[0] for r in rows) + (None if dbias is None else dbias.data_ptr(), N, L, C, int(heads),
                                             float(scale), rows[0][1], rows[3][1], rows[4][1],
-                                            _dev_ptr(bias, "bias", f32=True), lp, float(mask_value), nW) + tail[3:]
+                                            bp, bias_code, lp, float(mask_value), nW) + tail[3:]
         with _on_device(q.device):
             rc = lib.fwa_backward_labels(*args)
         if rc != FWA_OK:

@@ -53,10 +53,11 @@ int check_mask(int64_t N, const void* mask, const void* labels, int nW) {
 }
 
 int forward_impl(const void* q, const void* k, const void* v, void* o, int64_t N, int L, int C, int heads,
-                 float scale, int64_t ld_qkv, int64_t ld_o, const float* bias, const float* mask,
+                 float scale, int64_t ld_qkv, int64_t ld_o, const void* bias, int bias_dtype, const float* mask,
                  const int32_t* labels, float mask_value, int nW, int dtype, void* stream) {
     int rc = check_shape(N, L, C, heads, dtype, true);
     if (rc != FWA_OK) return rc;
+    if (bias && bias_dtype != FWA_F32 && bias_dtype != FWA_BF16) return FWA_ERR_UNSUPPORTED;
     rc = check_mask(N, mask, labels, nW);
     if (rc != FWA_OK) return rc;
     rc = check_row_stride(ld_qkv, C, dtype);
@@ -71,7 +72,8 @@ int forward_impl(const void* q, const void* k, const void* v, void* o, int64_t N
     if (o == q || o == k || o == v) return FWA_ERR_ALIAS;
     fwa::FwdArgs a;
     a.q = q; a.k = k; a.v = v; a.o = o;
-    a.bias = bias; a.mask = mask; a.labels = labels; a.mask_value = mask_value;
+    a.bias = bias; a.bias_bf16 = bias && bias_dtype == FWA_BF16;
+    a.mask = mask; a.labels = labels; a.mask_value = mask_value;
     a.N = N; a.L = L; a.C = C; a.heads = heads; a.nW = (mask || labels) ? nW : 1; a.scale = scale;
     a.ldq = (int)ld_qkv; a.ldo = (int)ld_o;
     hipStream_t st = static_cast<hipStream_t>(stream);
@@ -83,8 +85,8 @@ int forward_impl(const void* q, const void* k, const void* v, void* o, int64_t N
 
 int backward_impl(const void* q, const void* k, const void* v, const void* d_o, void* dq, void* dk, void* dv,
                   float* dbias, int64_t N, int L, int C, int heads, float scale, int64_t ld_qkv, int64_t ld_do,
-                  int64_t ld_dqkv, const float* bias, const float* mask, const int32_t* labels, float mask_value,
-                  int nW, int dtype, void* workspace, size_t workspace_bytes, void* stream);
+                  int64_t ld_dqkv, const void* bias, int bias_dtype, const float* mask, const int32_t* labels,
+                  float mask_value, int nW, int dtype, void* workspace, size_t workspace_bytes, void* stream);
 
 }  // namespace
 
@@ -107,14 +109,15 @@ const char* fwa_status_string(int code) {
 int fwa_forward_strided(const void* q, const void* k, const void* v, void* o, int64_t N, int L, int C, int heads,
                         float scale, int64_t ld_qkv, int64_t ld_o, const float* bias, const float* mask, int nW,
                         int dtype, void* stream) {
-    return forward_impl(q, k, v, o, N, L, C, heads, scale, ld_qkv, ld_o, bias, mask, nullptr, 0.f, nW, dtype, stream);
+    return forward_impl(q, k, v, o, N, L, C, heads, scale, ld_qkv, ld_o, bias, FWA_F32, mask, nullptr, 0.f, nW, dtype,
+                        stream);
 }
 
 int fwa_forward_labels(const void* q, const void* k, const void* v, void* o, int64_t N, int L, int C, int heads,
-                       float scale, int64_t ld_qkv, int64_t ld_o, const float* bias, const int32_t* labels,
-                       float mask_value, int nW, int dtype, void* stream) {
-    return forward_impl(q, k, v, o, N, L, C, heads, scale, ld_qkv, ld_o, bias, nullptr, labels, mask_value, nW, dtype,
-                        stream);
+                       float scale, int64_t ld_qkv, int64_t ld_o, const void* bias, int bias_dtype,
+                       const int32_t* labels, float mask_value, int nW, int dtype, void* stream) {
+    return forward_impl(q, k, v, o, N, L, C, heads, scale, ld_qkv, ld_o, bias, bias_dtype, nullptr, labels, mask_value,
+                        nW, dtype, stream);
 }
 
 int fwa_forward(const void* q, const void* k, const void* v, void* o, int64_t N, int L, int C, int heads,
@@ -137,16 +140,16 @@ int fwa_backward_strided(const void* q, const void* k, const void* v, const void
                          float* dbias, int64_t N, int L, int C, int heads, float scale, int64_t ld_qkv,
                          int64_t ld_do, int64_t ld_dqkv, const float* bias, const float* mask, int nW, int dtype,
                          void* workspace, size_t workspace_bytes, void* stream) {
-    return backward_impl(q, k, v, d_o, dq, dk, dv, dbias, N, L, C, heads, scale, ld_qkv, ld_do, ld_dqkv, bias, mask,
-                         nullptr, 0.f, nW, dtype, workspace, workspace_bytes, stream);
+    return backward_impl(q, k, v, d_o, dq, dk, dv, dbias, N, L, C, heads, scale, ld_qkv, ld_do, ld_dqkv, bias, FWA_F32,
+                         mask, nullptr, 0.f, nW, dtype, workspace, workspace_bytes, stream);
 }
 
 int fwa_backward_labels(const void* q, const void* k, const void* v, const void* d_o, void* dq, void* dk, void* dv,
                         float* dbias, int64_t N, int L, int C, int heads, float scale, int64_t ld_qkv,
-                        int64_t ld_do, int64_t ld_dqkv, const float* bias, const int32_t* labels, float mask_value,
-                        int nW, int dtype, void* workspace, size_t workspace_bytes, void* stream) {
-    return backward_impl(q, k, v, d_o, dq, dk, dv, dbias, N, L, C, heads, scale, ld_qkv, ld_do, ld_dqkv, bias, nullptr,
-                         labels, mask_value, nW, dtype, workspace, workspace_bytes, stream);
+                        int64_t ld_do, int64_t ld_dqkv, const void* bias, int bias_dtype, const int32_t* labels,
+                        float mask_value, int nW, int dtype, void* workspace, size_t workspace_bytes, void* stream) {
+    return backward_impl(q, k, v, d_o, dq, dk, dv, dbias, N, L, C, heads, scale, ld_qkv, ld_do, ld_dqkv, bias, bias_dtype,
+                         nullptr, labels, mask_value, nW, dtype, workspace, workspace_bytes, stream);
 }
 
 }  // extern "C"
@@ -155,10 +158,11 @@ namespace {
 
 int backward_impl(const void* q, const void* k, const void* v, const void* d_o, void* dq, void* dk, void* dv,
                   float* dbias, int64_t N, int L, int C, int heads, float scale, int64_t ld_qkv, int64_t ld_do,
-                  int64_t ld_dqkv, const float* bias, const float* mask, const int32_t* labels, float mask_value,
-                  int nW, int dtype, void* workspace, size_t workspace_bytes, void* stream) {
+                  int64_t ld_dqkv, const void* bias, int bias_dtype, const float* mask, const int32_t* labels,
+                  float mask_value, int nW, int dtype, void* workspace, size_t workspace_bytes, void* stream) {
     int rc = check_shape(N, L, C, heads, dtype, true);
     if (rc != FWA_OK) return rc;
+    if (bias && bias_dtype != FWA_F32 && bias_dtype != FWA_BF16) return FWA_ERR_UNSUPPORTED;
     rc = check_row_stride(ld_qkv, C, dtype);
     if (rc != FWA_OK) return rc;
     rc = check_row_stride(ld_do, C, dtype);
@@ -202,12 +206,17 @@ int backward_impl(const void* q, const void* k, const void* v, const void* d_o, 
         a.stats = static_cast<float*>(workspace);
         a.partial = reinterpret_cast<float*>(static_cast<char*>(workspace) + large_stats_bytes(N, L, heads));
     }
-    a.bias = bias; a.mask = mask; a.labels = labels; a.mask_value = mask_value;
+    a.bias = bias; a.bias_bf16 = bias && bias_dtype == FWA_BF16;
+    a.mask = mask; a.labels = labels; a.mask_value = mask_value;
     a.N = N; a.L = L; a.C = C; a.heads = heads; a.nW = (mask || labels) ? nW : 1; a.scale = scale;
     a.slots = C / heads != fwa::kHeadDim ? fwa::backward_wide_slots(N, heads)
               : L > fwa::kMaxBackwardL   ? fwa::backward_large_slots(N, heads, L)
                                          : fwa::backward_slots(N, heads, a.nW);
     a.ldq = (int)ld_qkv; a.ldg = (int)ld_do; a.ldd = (int)ld_dqkv;
+    // the one-wave-per-tile kernel (mask periods too long for the cooperative one) takes fp32 biases only
+    if (a.bias_bf16 && dtype == FWA_BF16 && C / heads == fwa::kHeadDim && L <= fwa::kMaxBackwardL &&
+        fwa::coop_slots(N, heads, a.nW) == 0)
+        return FWA_ERR_UNSUPPORTED;
     const hipError_t e = dtype == FWA_BF16 ? fwa::launch_backward_bf16(a, st) : fwa::launch_backward_f32(a, st);
     return e == hipSuccess ? FWA_OK : FWA_ERR_LAUNCH;
 }

@@ -83,8 +83,8 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, 2) bwd_bf16_kernel(BwdArg
     const uint32_t off_row = (uint32_t)n * row_bytes + 16u * g;  // 16 B of row n (plus a block offset)
     const uint32_t off_row_g = (uint32_t)n * row_g + 16u * g, off_row_d = (uint32_t)n * row_d + 16u * g;
     const float sl2 = p.scale * kLog2e;
-    __amdgpu_buffer_rsrc_t rb = make_rsrc(nullptr, 0);
-    if (BM && p.bias) rb = make_rsrc(p.bias + (size_t)h * L * L, (uint32_t)L * L * 4u);
+    BiasSrc rb = no_bias();
+    if (BM) rb = bias_of_head(p, h);
 
     // identity B operand: slot e of lane (g, n) is 1.0 iff 4g + e == n
     uint2 idu;
@@ -188,7 +188,7 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, 2) bwd_bf16_kernel(BwdArg
             if (BM) {
                 // 4 consecutive columns of one row: dword-aligned 16-byte loads, range-checked per dword
                 f32x4 add[NB];
-                addend_at(rb, msk, (uint32_t)(16 * qb + n), 4u * g, (uint32_t)L).fill(add, kLog2e);
+                addend_at(rb, msk, (uint32_t)(16 * qb + n), 4u * g, (uint32_t)L).template fill<NB, false>(add, kLog2e);  // fp32 bias only: this kernel has no register to spare
 #pragma unroll
                 for (int jb = 0; jb < NB; ++jb)
 #pragma unroll

@@ -117,8 +117,7 @@ __global__ void __launch_bounds__(64 * kCoopWavesPerTile * kCoopMaxHeads) bwd_bf
     // additive score term of this wave's query rows, in registers (see the file comment)
     f32x4 add[NB];
     if (BM && active) {
-        const uint32_t ll = (uint32_t)L * L * 4u;
-        const __amdgpu_buffer_rsrc_t rb = p.bias ? make_rsrc(p.bias + (size_t)h * L * L, ll) : make_rsrc(nullptr, 0);
+        const BiasSrc rb = bias_of_head(p, h);
         addend_at(rb, mask_of_window(p, bw), (uint32_t)(16 * role + n), 4u * g, (uint32_t)L).fill(add, kLog2e);
     }
     if (bw < (uint32_t)p.N) park();

@@ -48,11 +48,12 @@ __device__ __forceinline__ bf16x8 pair_operand(bf16x4 a, bf16x4 b) {
     return as_bf16x8(u32x4{ua.x, ua.y, ub.x, ub.y});
 }
 
-// HB: a bias is present; HM: no mask (0), a dense mask (1), or region labels from which the
-// mask values are formed in registers (2).  What is absent costs neither loads nor registers.
-template <int NB, bool HB, int HM>
+// HB: no bias (0), an fp32 bias (1) or a bf16 bias (2); HM: no mask (0), a dense mask (1), or region
+// labels from which the mask values are formed in registers (2).  What is absent costs neither
+// loads nor registers.
+template <int NB, int HB, int HM>
 __global__ void __launch_bounds__(64 * large_waves(NB)) bwd_bf16_large_kernel(BwdArgs p, LargeGeom gm) {
-    constexpr bool BM = HB || HM != 0;
+    constexpr bool BM = HB != 0 || HM != 0;
     constexpr int W = large_waves(NB);
     constexpr int NB2 = (NB + 1) / 2;
     constexpr int ROWS = 16 * NB;
@@ -82,8 +83,14 @@ __global__ void __launch_bounds__(64 * large_waves(NB)) bwd_bf16_large_kernel(Bw
     float* const patch = stD + ROWS + wave * (16 * SG);
 
     const uint32_t ll = (uint32_t)L * L * 4u;
+    const float* const bias32 = static_cast<const float*>(p.bias);
     const __amdgpu_buffer_rsrc_t rb =
-        HB ? make_rsrc(p.bias + (size_t)h * L * L, ll) : make_rsrc(nullptr, 0);
+        HB == 1 ? make_rsrc(bias32 + (size_t)h * L * L, ll) : make_rsrc(nullptr, 0);
+    // a bf16 bias is addressed from the (dword aligned) start of the whole tensor: a head's tile may
+    // begin at an odd element
+    const __amdgpu_buffer_rsrc_t rbt =
+        HB == 2 ? make_rsrc(p.bias, ((uint32_t)p.heads * L * L * 2u + 3u) & ~3u) : make_rsrc(nullptr, 0);  // whole dwords
+    const uint32_t hbase = h * (uint32_t)L * (uint32_t)L;
 
     const uint32_t srow = (uint32_t)tid >> 2, scol = (uint32_t)tid & 3u;  // slab movement: (row, 16 B column)
     const uint32_t tile_bytes = (uint32_t)(L - 1) * row_bytes + 2u * kHeadDim;
@@ -142,7 +149,7 @@ __global__ void __launch_bounds__(64 * large_waves(NB)) bwd_bf16_large_kernel(Bw
             i32x4 tk[2];  // with labels: those of a patch's 4 columns ...
             int tq[4];    // ... and of the lane's 4 patch rows
             const uint32_t qrow = (uint32_t)(16 * qb) * L * 4u;  // < ll: the block starts inside the tile
-            const __amdgpu_buffer_rsrc_t rbq = HB ? make_rsrc(p.bias + (size_t)h * L * L + (size_t)16 * qb * L, ll - qrow) : rb;
+            const __amdgpu_buffer_rsrc_t rbq = HB == 1 ? make_rsrc(bias32 + (size_t)h * L * L + (size_t)16 * qb * L, ll - qrow) : rb;
             const __amdgpu_buffer_rsrc_t rmq =
                 HM == 1 ? make_rsrc(p.mask + (size_t)(w % (uint32_t)p.nW) * L * L + (size_t)16 * qb * L, ll - qrow) : rb;
             if (HM == 2) {
@@ -153,7 +160,9 @@ __global__ void __launch_bounds__(64 * large_waves(NB)) bwd_bf16_large_kernel(Bw
 #pragma unroll
                 for (int t = 0; t < 4; ++t) {
                     const uint32_t off = ((uint32_t)(4 * t + prow) * L + pcol) * 4u + 256u * ch;
-                    if (HB) tb[slot][t] = load_f32x4(rbq, off);
+                    if (HB == 1) tb[slot][t] = load_f32x4(rbq, off);
+                    // bf16: 16 bytes from the dword that holds the first of the 4 elements
+                    if (HB == 2) tb[slot][t] = load_f32x4(rbt, (2u * (hbase + (uint32_t)(16 * qb) * L) + (off >> 1)) & ~3u);
                     if (HM == 1) tm[slot][t] = load_f32x4(rmq, off);
                 }
                 if (HM == 2) tk[slot] = load_i32x4(rl, (pcol + 64u * ch) * 4u);
@@ -172,8 +181,11 @@ __global__ void __launch_bounds__(64 * large_waves(NB)) bwd_bf16_large_kernel(Bw
 #pragma unroll
                     for (int t = 0; t < 4; ++t) {
                         const f32x4 mk = HM == 2 ? mask_of_labels(tq[t], tk[cur], p.mask_value) : tm[cur][t];
+                        // the columns pcol + 64 ch are even: the quad starts on an odd element iff its row does
+                        const f32x4 bq = HB == 2 ? bf16_quad(tb[cur][t], ((hbase + (uint32_t)(16 * qb + 4 * t + prow) * L) & 1u) != 0)
+                                                 : tb[cur][t];
                         *reinterpret_cast<f32x4*>(patch + (4 * t + prow) * SG + pcol) =
-                            (HB && HM ? tb[cur][t] + mk : (HB ? tb[cur][t] : mk)) * kLog2e;
+                            (HB && HM ? bq + mk : (HB ? bq : mk)) * kLog2e;
                     }
 #pragma unroll
                     for (int b = 0; b < 4; ++b) {
@@ -295,6 +307,11 @@ __global__ void __launch_bounds__(64 * large_waves(NB)) bwd_bf16_large_kernel(Bw
             uint32_t aoff[4];
 #pragma unroll
             for (int r = 0; r < 4; ++r) aoff[r] = ((uint32_t)(4 * g + r) * L + jcol) * 4u;
+            // bf16 bias: the descriptor of a query block starts at an even element of the tensor
+            // (a dword), the parity of the head's first element goes into the lane offsets
+            uint32_t aoff16[4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) aoff16[r] = (aoff[r] >> 1) + 2u * (hbase & 1u);
             bf16x8 oq[2][2], og[2][2], tg0[2], tg1[2], tx0[2], tx1[2];
             f32x4 oM[2][2], oD[2][2], ab[2][2], am[2][2];
             i32x4 al[2][2];
@@ -323,12 +340,16 @@ __global__ void __launch_bounds__(64 * large_waves(NB)) bwd_bf16_large_kernel(Bw
                 for (int u = 0; u < 2; ++u) {
                     if (u == 1 && 2 * qp + 1 >= NB) break;
                     const uint32_t qrow = (uint32_t)(16 * (2 * qp + u)) * L;
-                    const __amdgpu_buffer_rsrc_t rbq = HB ? make_rsrc(p.bias + (size_t)h * L * L + qrow, ll - 4u * qrow) : rb;
+                    const __amdgpu_buffer_rsrc_t rbq = HB == 1 ? make_rsrc(bias32 + (size_t)h * L * L + qrow, ll - 4u * qrow) : rb;
+                    const uint32_t e0 = (hbase + qrow) & ~1u;
+                    const __amdgpu_buffer_rsrc_t rbq16 =
+                        HB == 2 ? make_rsrc(static_cast<const char*>(p.bias) + 2u * (size_t)e0, ((uint32_t)p.heads * L * L - e0) * 2u) : rb;
                     const __amdgpu_buffer_rsrc_t rmq =
                         HM == 1 ? make_rsrc(p.mask + (size_t)(w % (uint32_t)p.nW) * L * L + qrow, ll - 4u * qrow) : rb;
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
-                        if (HB) ab[slot][u][r] = load_f32(rbq, aoff[r]);
+                        if (HB == 1) ab[slot][u][r] = load_f32(rbq, aoff[r]);
+                        if (HB == 2) ab[slot][u][r] = load_u16_bits(rbq16, aoff16[r]);  // raw; widened where it is used
                         if (HM == 1) am[slot][u][r] = load_f32(rmq, aoff[r]);
                     }
                     // with labels: those of the 4 query rows, compared with the key's where the term is used
@@ -362,7 +383,9 @@ __global__ void __launch_bounds__(64 * large_waves(NB)) bwd_bf16_large_kernel(Bw
                         float x;
                         if (BM) {
                             const float mk = HM == 2 ? (al[cur][u][r] == lkey ? 0.f : p.mask_value) : am[cur][u][r];
-                            const float add = HB && HM ? ab[cur][u][r] + mk : (HB ? ab[cur][u][r] : mk);
+                            const float braw = ab[cur][u][r];
+                            const float bv = HB == 2 ? widen_bf16_bits(braw) : braw;
+                            const float add = HB && HM ? bv + mk : (HB ? bv : mk);
                             x = fmaf(sc[u][r], sl2, fmaf(add, kLog2e, -oM[cur][u][r]));
                         }
                         else
@@ -408,9 +431,9 @@ __global__ void __launch_bounds__(64 * large_waves(NB)) bwd_bf16_large_kernel(Bw
 // of one head for its whole life, holds dBias[all queries][its keys] in registers across the
 // windows bw, bw + G, ... and writes them out once, in register order, as one of G partial
 // sums per head (the reduce kernel adds the slots in a fixed order).
-template <int NB, bool HB, int HM>
+template <int NB, int HB, int HM>
 __global__ void __launch_bounds__(64 * large_waves(NB)) dbias_large_kernel(BwdArgs p, LargeGeom gm) {
-    constexpr bool BM = HB || HM != 0;
+    constexpr bool BM = HB != 0 || HM != 0;
     constexpr int W = large_waves(NB);
     constexpr int JPW = (NB + W - 1) / W;  // key blocks per wave
     constexpr int NB2 = (NB + 1) / 2;
@@ -495,6 +518,10 @@ __global__ void __launch_bounds__(64 * large_waves(NB)) dbias_large_kernel(BwdAr
                 uint32_t aoff[4];
 #pragma unroll
                 for (int r = 0; r < 4; ++r) aoff[r] = ((uint32_t)(4 * g + r) * L + jcol) * 4u;
+                const uint32_t hbase = h * (uint32_t)L * (uint32_t)L;
+                uint32_t aoff16[4];  // bf16 bias: see the main kernel
+#pragma unroll
+                for (int r = 0; r < 4; ++r) aoff16[r] = (aoff[r] >> 1) + 2u * (hbase & 1u);
                 bf16x8 oq[2][2], og[2][2];
                 f32x4 oM[2][2], oD[2][2], ab[2][2], am[2][2];
                 i32x4 al[2][2];
@@ -511,13 +538,19 @@ __global__ void __launch_bounds__(64 * large_waves(NB)) dbias_large_kernel(BwdAr
                         if (BM) {
                             const uint32_t qrow = (uint32_t)(16 * qb) * L;
                             const __amdgpu_buffer_rsrc_t rbq =
-                                HB ? make_rsrc(p.bias + (size_t)h * L * L + qrow, ll - 4u * qrow) : make_rsrc(nullptr, 0);
+                                HB == 1 ? make_rsrc(static_cast<const float*>(p.bias) + (size_t)h * L * L + qrow, ll - 4u * qrow)
+                                        : make_rsrc(nullptr, 0);
+                            const uint32_t e0 = (hbase + qrow) & ~1u;
+                            const __amdgpu_buffer_rsrc_t rbq16 =
+                                HB == 2 ? make_rsrc(static_cast<const char*>(p.bias) + 2u * (size_t)e0, ((uint32_t)p.heads * L * L - e0) * 2u)
+                                        : make_rsrc(nullptr, 0);
                             const __amdgpu_buffer_rsrc_t rmq =
                                 HM == 1 ? make_rsrc(p.mask + (size_t)(w % (uint32_t)p.nW) * L * L + qrow, ll - 4u * qrow)
                                         : make_rsrc(nullptr, 0);
 #pragma unroll
                             for (int r = 0; r < 4; ++r) {
-                                if (HB) ab[slot][u][r] = load_f32(rbq, aoff[r]);
+                                if (HB == 1) ab[slot][u][r] = load_f32(rbq, aoff[r]);
+                                if (HB == 2) ab[slot][u][r] = load_u16_bits(rbq16, aoff16[r]);
                                 if (HM == 1) am[slot][u][r] = load_f32(rmq, aoff[r]);
                             }
                             if (HM == 2) al[slot][u] = load_i32x4(rl, (uint32_t)(16 * qb + 4 * g) * 4u);
@@ -540,7 +573,9 @@ __global__ void __launch_bounds__(64 * large_waves(NB)) dbias_large_kernel(BwdAr
                             float x;
                             if (BM) {
                                 const float mk = HM == 2 ? (al[cur][u][r] == lkey ? 0.f : p.mask_value) : am[cur][u][r];
-                                const float add = HB && HM ? ab[cur][u][r] + mk : (HB ? ab[cur][u][r] : mk);
+                                const float braw = ab[cur][u][r];
+                                const float bv = HB == 2 ? widen_bf16_bits(braw) : braw;
+                                const float add = HB && HM ? bv + mk : (HB ? bv : mk);
                                 x = fmaf(sc[r], sl2, fmaf(add, kLog2e, -oM[cur][u][r]));
                             } else {
                                 x = fmaf(sc[r], sl2, -oM[cur][u][r]);
@@ -569,7 +604,7 @@ __global__ void __launch_bounds__(64 * large_waves(NB)) dbias_large_kernel(BwdAr
     }
 }
 
-template <int NB, bool HB, int HM>
+template <int NB, int HB, int HM>
 hipError_t launch_dbias_large(const BwdArgs& a, hipStream_t st) {
     constexpr int W = large_waves(NB);
     const void* fn = reinterpret_cast<const void*>(&dbias_large_kernel<NB, HB, HM>);
@@ -589,9 +624,9 @@ hipError_t launch_dbias_large(const BwdArgs& a, hipStream_t st) {
     return hipGetLastError();
 }
 
-template <int NB, bool HB, int HM>
+template <int NB, int HB, int HM>
 hipError_t launch_large_one(const BwdArgs& a, hipStream_t st) {
-    constexpr bool BM = HB || HM != 0;
+    constexpr bool BM = HB != 0 || HM != 0;
     constexpr int W = large_waves(NB);
     const void* fn = reinterpret_cast<const void*>(&bwd_bf16_large_kernel<NB, HB, HM>);
     const unsigned block = 64u * W;
@@ -621,7 +656,7 @@ hipError_t launch_large_one(const BwdArgs& a, hipStream_t st) {
     return hipGetLastError();
 }
 
-template <int NB, bool HB, int HM>
+template <int NB, int HB, int HM>
 hipError_t launch_large_both(const BwdArgs& a, hipStream_t st) {
     hipError_t e = launch_large_one<NB, HB, HM>(a, st);
     if (e != hipSuccess || a.dbias == nullptr) return e;
@@ -631,12 +666,16 @@ hipError_t launch_large_both(const BwdArgs& a, hipStream_t st) {
 
 template <int NB>
 hipError_t launch_large_nb(const BwdArgs& a, hipStream_t st) {
-    if (a.bias) {
-        if (a.labels) return launch_large_both<NB, true, 2>(a, st);
-        return a.mask ? launch_large_both<NB, true, 1>(a, st) : launch_large_both<NB, true, 0>(a, st);
+    if (a.bias && a.bias_bf16) {
+        if (a.labels) return launch_large_both<NB, 2, 2>(a, st);
+        return a.mask ? launch_large_both<NB, 2, 1>(a, st) : launch_large_both<NB, 2, 0>(a, st);
     }
-    if (a.labels) return launch_large_both<NB, false, 2>(a, st);
-    return a.mask ? launch_large_both<NB, false, 1>(a, st) : launch_large_both<NB, false, 0>(a, st);
+    if (a.bias) {
+        if (a.labels) return launch_large_both<NB, 1, 2>(a, st);
+        return a.mask ? launch_large_both<NB, 1, 1>(a, st) : launch_large_both<NB, 1, 0>(a, st);
+    }
+    if (a.labels) return launch_large_both<NB, 0, 2>(a, st);
+    return a.mask ? launch_large_both<NB, 0, 1>(a, st) : launch_large_both<NB, 0, 0>(a, st);
 }
 
 }  // namespace

@@ -133,8 +133,7 @@ __global__ void __launch_bounds__(256) bwd_bf16_wide_kernel(BwdArgs p, uint32_t 
         // softmax of the block's rows: s <- exp(score - rowmax), inv = 1 / rowsum
         float inv;
         if (BM) {
-            const uint32_t ll = (uint32_t)L * L * 4u;
-            const __amdgpu_buffer_rsrc_t rb = p.bias ? make_rsrc(p.bias + (size_t)h * L * L, ll) : make_rsrc(nullptr, 0);
+            const BiasSrc rb = bias_of_head(p, h);
             const AddendGlobal addend = addend_at(rb, mask_of_window(p, w), (uint32_t)(16 * qb + n), 4u * g, (uint32_t)L);
             inv = softmax_block<NB, true>(s, sl2, addend, L, g);
         } else {

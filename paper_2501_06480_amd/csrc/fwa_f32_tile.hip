@@ -135,10 +135,10 @@ __global__ void __launch_bounds__(256) fwd_f32_tile_kernel(FwdArgs p) {
     for (int jb = 0; jb < NB; ++jb) s[jb] = f32x4{0.f, 0.f, 0.f, 0.f};
     rows_times_own<NB, D>(s, lk, qv, n, g);  // S[16 qb + n][16 jb + 4g + r]
 
-    __amdgpu_buffer_rsrc_t rb = make_rsrc(nullptr, 0);
+    BiasSrc rb = no_bias();
     MaskSrc msk = {make_rsrc(nullptr, 0), 0.f, false};
     if (BM) {
-        if (p.bias) rb = make_rsrc(p.bias + (size_t)h * L * L, (uint32_t)L * L * 4u);
+        rb = bias_of_head(p, h);
         msk = mask_of_window(p, w);
     }
     float m, sum;
@@ -191,10 +191,10 @@ __global__ void __launch_bounds__(256) bwd_f32_tile_kernel(BwdArgs p) {
     float* const stD = stM + ROWS;
     const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
 
-    __amdgpu_buffer_rsrc_t rb = make_rsrc(nullptr, 0);
+    BiasSrc rb = no_bias();
     MaskSrc msk = {make_rsrc(nullptr, 0), 0.f, false};
     if (BM) {
-        if (p.bias) rb = make_rsrc(p.bias + (size_t)h * L * L, (uint32_t)L * L * 4u);
+        rb = bias_of_head(p, h);
         msk = mask_of_window(p, w);
     }
 
@@ -299,7 +299,7 @@ __global__ void __launch_bounds__(256) bwd_f32_tile_kernel(BwdArgs p) {
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 float x = sc[r] * p.scale;
-                if (BM) x += load_f32(rb, ((uint32_t)(16 * qb + 4 * g + r) * L + jcol) * 4u) + mk[r];
+                if (BM) x += bias_elem(rb, (uint32_t)(16 * qb + 4 * g + r) * L + jcol) + mk[r];
                 pr[r] = valid ? __builtin_amdgcn_exp2f((x - M4[r]) * kLog2e) : 0.f;
                 ds[r] = pr[r] * (dp[r] - D4[r]);
             }

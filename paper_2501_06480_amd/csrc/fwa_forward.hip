@@ -123,10 +123,10 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) fwd_bf16_kernel(FwdArgs p
     }
 
     const float sl2 = p.scale * kLog2e;
-    __amdgpu_buffer_rsrc_t rb = make_rsrc(nullptr, 0);
+    BiasSrc rb = no_bias();
     MaskSrc msk = {make_rsrc(nullptr, 0), 0.f, false};
     if (BM) {
-        if (p.bias) rb = make_rsrc(p.bias + (size_t)tc.h * L * L, (uint32_t)L * L * 4u);
+        rb = bias_of_head(p, tc.h);
         msk = mask_of_window(p, tc.w);
     }
 
@@ -195,10 +195,10 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) fwd_f32_kernel(FwdArgs p,
             kop[jb][4 + c] = b[c];
         }
     }
-    __amdgpu_buffer_rsrc_t rb = make_rsrc(nullptr, 0);
+    BiasSrc rb = no_bias();
     MaskSrc msk = {make_rsrc(nullptr, 0), 0.f, false};
     if (BM) {
-        if (p.bias) rb = make_rsrc(p.bias + (size_t)tc.h * L * L, (uint32_t)L * L * 4u);
+        rb = bias_of_head(p, tc.h);
         msk = mask_of_window(p, tc.w);
     }
 

@@ -75,9 +75,8 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock * QS) fwd_bf16_staged_kern
     constexpr int NQ = QS == 1 ? NB : 1;  // query blocks of this wave: all, or block qs alone
     f32x4 add[NQ][NB];
     if (BM) {
-        const uint32_t ll = (uint32_t)L * L * 4u;
         const uint32_t hh = h < (uint32_t)p.heads ? h : 0u;
-        const __amdgpu_buffer_rsrc_t rb = p.bias ? make_rsrc(p.bias + (size_t)hh * L * L, ll) : make_rsrc(nullptr, 0);
+        const BiasSrc rb = bias_of_head(p, hh);
         const MaskSrc msk = mask_of_window(p, w);
         fill_rows<NQ, NB>(add, rb, msk, (uint32_t)(16 * (QS == 1 ? 0 : qs) + n), 4u * g, (uint32_t)L, kLog2e);
     }
@@ -226,8 +225,7 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) fwd_bf16_persistent_kerne
     // the additive term of this wave's head and this workgroup's mask tile, in score layout
     f32x4 add[NB][NB];
     {
-        const uint32_t ll = (uint32_t)L * L * 4u;
-        const __amdgpu_buffer_rsrc_t rb = p.bias ? make_rsrc(p.bias + (size_t)h * L * L, ll) : make_rsrc(nullptr, 0);
+        const BiasSrc rb = bias_of_head(p, h);
         const MaskSrc msk = mask_of_window(p, bw);
         fill_rows<NB, NB>(add, rb, msk, (uint32_t)n, 4u * g, (uint32_t)L, kLog2e);
     }
@@ -367,10 +365,10 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) fwd_bf16_rowblock_kernel(
                                                 (uint32_t)(L - 1) * row_out + 2u * kHeadDim);
     const uint32_t off_row = (uint32_t)n * row_bytes + 16u * g;
     const float sl2 = p.scale * kLog2e;
-    __amdgpu_buffer_rsrc_t rb = make_rsrc(nullptr, 0);
+    BiasSrc rb = no_bias();
     MaskSrc msk = {make_rsrc(nullptr, 0), 0.f, false};
     if (BM) {
-        if (p.bias) rb = make_rsrc(p.bias + (size_t)h * L * L, (uint32_t)L * L * 4u);
+        rb = bias_of_head(p, h);
         msk = mask_of_window(p, w);
     }
     const uint4* const lkh = lk + n * stride + 4 * hl + g;  // K[16 jb + n][8g..] at lkh[16 jb * stride]
@@ -507,8 +505,7 @@ __global__ void __launch_bounds__(64 * HPB * rowpersist_waves(NB)) fwd_bf16_rowp
     if (w0 + step < end) request(sb, w0 + step);
     f32x4 add[NB];
     {
-        const uint32_t ll = (uint32_t)L * L * 4u;
-        const __amdgpu_buffer_rsrc_t rb = p.bias ? make_rsrc(p.bias + (size_t)h * L * L, ll) : make_rsrc(nullptr, 0);
+        const BiasSrc rb = bias_of_head(p, h);
         // rows beyond L (and the whole block of an idle wave) fall outside the descriptors: zeros
         addend_at(rb, mask_of_window(p, w0), active ? (uint32_t)(16 * qb + n) : (uint32_t)L, 4u * g, (uint32_t)L)
             .fill(add, kLog2e);

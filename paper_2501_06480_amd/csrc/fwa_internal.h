@@ -19,7 +19,8 @@ struct FwdArgs {
     const void* k;
     const void* v;
     void* o;
-    const float* bias;   // [heads, L, L] or nullptr
+    const void* bias;    // [heads, L, L], fp32 or (bias_bf16) bf16, or nullptr
+    int bias_bf16;
     const float* mask;   // [nW, L, L] or nullptr
     const int32_t* labels;  // [nW, L] region labels standing for the mask, or nullptr; never together with mask
     float mask_value;       // what labels that differ add to a score
@@ -44,7 +45,8 @@ struct BwdArgs {
     float* dbias;        // [heads, L, L] or nullptr
     float* partial;      // workspace for per-slot dS sums, or nullptr
     float* stats;        // workspace [N, heads, 2, 16 * ceil(L / 16)] for the row statistics (L > 64 with dbias), or nullptr
-    const float* bias;
+    const void* bias;    // as in FwdArgs
+    int bias_bf16;
     const float* mask;
     const int32_t* labels;  // as in FwdArgs
     float mask_value;

@@ -40,20 +40,56 @@ __device__ __forceinline__ f32x4 mask_rows4(const MaskSrc& m, uint32_t i0, uint3
     return f32x4{load_f32(m.r, off), load_f32(m.r, off + 4u * L), load_f32(m.r, off + 8u * L), load_f32(m.r, off + 12u * L)};
 }
 
+// The bias tile of a head: fp32 through a descriptor over the head's [L, L] tile (rows beyond L read
+// as zero), or bf16 through a descriptor over the whole [heads, L, L] tensor with the head's first
+// element in `hbase` (a head's tile may start at an odd element, i.e. not on a dword, so loads are
+// addressed from the tensor's aligned base; rows beyond L then read the next head's values, which
+// are discarded like every padded row).  An absent bias is an fp32 one over a null descriptor.
+struct BiasSrc {
+    __amdgpu_buffer_rsrc_t r;
+    uint32_t hbase;
+    bool bf16;
+};
+__device__ __forceinline__ BiasSrc no_bias() { return BiasSrc{make_rsrc(nullptr, 0), 0u, false}; }
+template <class Args>
+__device__ __forceinline__ BiasSrc bias_of_head(const Args& p, uint32_t h) {
+    const uint32_t L = (uint32_t)p.L;
+    if (!p.bias) return no_bias();
+    // size rounded up to whole dwords: with an odd element count the last dword holds the last element and
+    // two bytes past the tensor, which lie in the same (aligned) dword and hence in the same page
+    if (p.bias_bf16) return BiasSrc{make_rsrc(p.bias, ((uint32_t)p.heads * L * L * 2u + 3u) & ~3u), h * L * L, true};
+    return BiasSrc{make_rsrc(static_cast<const float*>(p.bias) + (size_t)h * L * L, L * L * 4u), 0u, false};
+}
+// One element of the tile (idx = i L + j) and four consecutive ones out of a 16-byte load that
+// started at the dword holding element idx (bf16: `odd` = idx is odd, the quad then starts in the
+// upper half of the first dword).
+__device__ __forceinline__ float bias_elem(const BiasSrc& b, uint32_t idx) {
+    if (b.bf16) return load_bf16(b.r, 2u * (b.hbase + idx));
+    return load_f32(b.r, 4u * idx);
+}
+__device__ __forceinline__ f32x4 bf16_quad(const f32x4& raw, bool odd) {
+    const u32x4 r = __builtin_bit_cast(u32x4, raw);
+    const uint32_t sh = odd ? 16u : 0u;
+    const uint32_t lo = __builtin_amdgcn_alignbit(r.y, r.x, sh), hi = __builtin_amdgcn_alignbit(r.z, r.y, sh);
+    const u32x4 e = {lo << 16, lo & 0xffff0000u, hi << 16, hi & 0xffff0000u};
+    return __builtin_bit_cast(f32x4, e);
+}
+
 // Where the additive term of the scores (bias + mask) comes from.
 // AddendGlobal: the bias tile of the head and the mask of the window; every load takes 4
 // consecutive columns of the lane's row i: 16 bytes, only dword aligned; the range check is per
 // dword, rows beyond L fall outside the descriptors and read as zero (label 0 for the mask).
 struct AddendGlobal {
-    __amdgpu_buffer_rsrc_t rb;
+    BiasSrc rb;
     MaskSrc m;
     uint32_t off;     // byte offset of element [i][j0] of an [L, L] fp32 tile, j0 = 4g
     uint32_t i4, j4;  // 4 i and 4 j0: byte offsets of the labels of the row and of its first column
-    template <int NB>
+    // BF16_BIAS = false promises an fp32 (or absent) bias and leaves the bf16 path out of the code
+    template <int NB, bool BF16_BIAS = true>
     __device__ __forceinline__ void fill(f32x4 (&add)[NB], float mul) const;
 };
 // The addend of row i (beyond L: zeros), first column j0, of the given bias tile and mask.
-__device__ __forceinline__ AddendGlobal addend_at(__amdgpu_buffer_rsrc_t rb, const MaskSrc& m, uint32_t i, uint32_t j0,
+__device__ __forceinline__ AddendGlobal addend_at(const BiasSrc& rb, const MaskSrc& m, uint32_t i, uint32_t j0,
                                                   uint32_t L) {
     return AddendGlobal{rb, m, (i * L + j0) * 4u, 4u * i, 4u * j0};
 }
@@ -65,20 +101,33 @@ __device__ __forceinline__ AddendGlobal addend_at(__amdgpu_buffer_rsrc_t rb, con
 // then passes through a uniform branch that turns labels into mask values in place; a dense mask
 // skips it, so that the sums below can be scheduled as late as their consumer allows, as if there
 // were no branch at all.
-template <int NQ, int NB>
+template <int NQ, int NB, bool BF16_BIAS = true>
 __device__ __forceinline__ void fill_rows(f32x4 (&add)[NQ][NB], const AddendGlobal (&rows)[NQ], float mul) {
     const MaskSrc& m = rows[0].m;
+    const BiasSrc& b = rows[0].rb;
+    const bool bbf = BF16_BIAS && b.bf16;
     f32x4 mk[NQ][NB];
     int lq[NQ];
 #pragma unroll
     for (int t = 0; t < NQ; ++t) {
         const uint32_t moff = m.labels ? rows[t].j4 : rows[t].off;
+        // bf16 bias: the dword that holds element hbase + i L + j0, then 32 bytes per key block
+        const uint32_t boff = bbf ? ((2u * b.hbase + (rows[t].off >> 1)) & ~3u) : rows[t].off;
+        const uint32_t bstep = bbf ? 32u : 64u;
 #pragma unroll
         for (int jb = 0; jb < NB; ++jb) {
-            add[t][jb] = load_f32x4(rows[t].rb, rows[t].off + 16 * jb * 4u);
+            add[t][jb] = load_f32x4(b.r, boff + bstep * jb);
             mk[t][jb] = load_f32x4(m.r, moff + 16 * jb * 4u);
         }
         lq[t] = load_i32(m.r, rows[t].i4);  // dense: some element of the tile, unused
+    }
+    if (bbf) {  // uniform, like the label branch below: fp32 biases skip it
+#pragma unroll
+        for (int t = 0; t < NQ; ++t) {
+            const bool odd = ((b.hbase + (rows[t].off >> 2)) & 1u) != 0;
+#pragma unroll
+            for (int jb = 0; jb < NB; ++jb) add[t][jb] = bf16_quad(add[t][jb], odd);
+        }
     }
     if (m.labels) {
 #pragma unroll
@@ -94,18 +143,18 @@ __device__ __forceinline__ void fill_rows(f32x4 (&add)[NQ][NB], const AddendGlob
 }
 // The rows i0, i0 + 16, ... of one bias tile and mask.
 template <int NQ, int NB>
-__device__ __forceinline__ void fill_rows(f32x4 (&add)[NQ][NB], __amdgpu_buffer_rsrc_t rb, const MaskSrc& m, uint32_t i0,
+__device__ __forceinline__ void fill_rows(f32x4 (&add)[NQ][NB], const BiasSrc& rb, const MaskSrc& m, uint32_t i0,
                                           uint32_t j0, uint32_t L, float mul) {
     AddendGlobal rows[NQ];
 #pragma unroll
     for (int t = 0; t < NQ; ++t) rows[t] = addend_at(rb, m, i0 + 16 * t, j0, L);
     fill_rows<NQ, NB>(add, rows, mul);
 }
-template <int NB>
+template <int NB, bool BF16_BIAS>
 __device__ __forceinline__ void AddendGlobal::fill(f32x4 (&add)[NB], float mul) const {
     f32x4 one[1][NB];
     const AddendGlobal rows[1] = {*this};
-    fill_rows<1, NB>(one, rows, mul);
+    fill_rows<1, NB, BF16_BIAS>(one, rows, mul);
 #pragma unroll
     for (int jb = 0; jb < NB; ++jb) add[jb] = one[0][jb];
 }

@@ -141,16 +141,21 @@ def test_strided_entry_points_check_their_strides(lib):
 
 def test_label_entry_points_check_their_arguments(lib):
     from paper_2501_06480_amd import binding as b
-    fwd = lambda N=4, labels=P + 0x9000, nW=2, ldq=96: lib.fwa_forward_labels(
-        P, P + 0x1000, P + 0x2000, P + 0x3000, N, 49, 96, 3, 0.1, ldq, 96, None, labels, -100.0, nW, 1, None)
+    fwd = lambda N=4, labels=P + 0x9000, nW=2, ldq=96, bias=None, bias_dtype=0: lib.fwa_forward_labels(
+        P, P + 0x1000, P + 0x2000, P + 0x3000, N, 49, 96, 3, 0.1, ldq, 96, bias, bias_dtype, labels, -100.0, nW, 1, None)
     assert fwd(nW=0) == b.FWA_ERR_SHAPE
     assert fwd(nW=3) == b.FWA_ERR_SHAPE              # 4 % 3 != 0
     assert fwd(labels=P + 0x9004) == b.FWA_ERR_ALIGN
     assert fwd(ldq=95) == b.FWA_ERR_SHAPE
     assert fwd(N=0, labels=None, nW=0) == b.FWA_OK   # empty batch, no mask: no-op
-    bwd = lambda labels=P + 0x9000, nW=2, dbias=None: lib.fwa_backward_labels(
-        P, P + 0x1000, P + 0x2000, P + 0x3000, P + 0x4000, P + 0x5000, P + 0x6000, dbias, 4, 49, 96, 3, 0.1,
-        96, 96, 96, None, labels, -100.0, nW, 1, None, 0, None)
+    assert fwd(bias=P + 0x7000, bias_dtype=2) == b.FWA_ERR_UNSUPPORTED   # bias is fp32 or bf16
+    assert fwd(bias=P + 0x7002, bias_dtype=1) == b.FWA_ERR_ALIGN
+    bwd = lambda labels=P + 0x9000, nW=2, dbias=None, bias=None, bias_dtype=0, N=4, heads=3: lib.fwa_backward_labels(
+        P, P + 0x1000, P + 0x2000, P + 0x3000, P + 0x4000, P + 0x5000, P + 0x6000, dbias, N, 49, 32 * heads, heads, 0.1,
+        32 * heads, 32 * heads, 32 * heads, bias, bias_dtype, labels, -100.0, nW, 1, None, 0, None)
     assert bwd(nW=8) == b.FWA_ERR_SHAPE
     assert bwd(labels=P + 0x9008) == b.FWA_ERR_ALIGN
     assert bwd(dbias=P + 0x7000) == b.FWA_ERR_WORKSPACE
+    assert bwd(bias=P + 0x7000, bias_dtype=3) == b.FWA_ERR_UNSUPPORTED
+    # a mask period too long for the cooperative kernel leaves the one-wave kernel, which takes fp32 biases only
+    assert bwd(bias=P + 0x7000, bias_dtype=1, N=64, nW=64, heads=24) == b.FWA_ERR_UNSUPPORTED

@@ -206,3 +206,85 @@ def test_label_arguments_are_checked():
     with pytest.raises(ValueError):
         fwa.fwa_forward(q, q.clone(), q.clone(), 3, 0.1, mask=torch.zeros((3, 49, 49), device="cuda"),
                         labels=lab[:3].contiguous())
+
+
+# ---------------------------------------------------------------------------------- bf16 bias
+def bf16_exact(a):
+    """fp32 array whose values are exactly representable in bf16, and the same as a bf16 device tensor."""
+    import torch
+    vals, bits = synth.bf16_round(a.astype(np.float32))
+    return vals, torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).cuda()
+
+
+BF16_BIAS = [
+    # name, N, L, C, heads, dtype, nW (0 = no mask), backward, dbias
+    ("fwd_persistent_s1", 256, 49, 96, 3, "bf16", 64, False, False),
+    ("fwd_one_wave_per_head_s3", 512, 49, 384, 12, "bf16", 4, False, False),
+    ("fwd_staged_few_windows", 6, 49, 96, 3, "bf16", 3, False, False),
+    ("fwd_direct_five_heads", 12, 49, 160, 5, "bf16", 4, False, False),
+    ("fwd_odd_heads_odd_L_no_mask", 9, 37, 96, 3, "bf16", 0, False, False),
+    ("fwd_rowpersist_L144", 64, 144, 96, 3, "bf16", 4, False, False),
+    ("fwd_rowblock_L201", 2, 201, 96, 3, "bf16", 1, False, False),
+    ("fwd_wide_d64", 12, 64, 256, 4, "bf16", 4, False, False),
+    ("fwd_f32_tile_L49", 12, 49, 96, 3, "f32", 4, False, False),
+    ("fwd_f32_L145", 4, 145, 96, 3, "f32", 2, False, False),
+    ("bwd_coop_s1", 256, 49, 96, 3, "bf16", 64, True, True),
+    ("bwd_coop_s3", 32, 49, 384, 12, "bf16", 4, True, True),
+    ("bwd_large_L143_odd", 12, 143, 96, 3, "bf16", 4, True, True),
+    ("bwd_large_L256", 8, 256, 64, 2, "bf16", 4, True, True),
+    ("bwd_large_L81_no_mask", 6, 81, 96, 3, "bf16", 0, True, False),
+    ("bwd_wide_d128_L49", 6, 49, 384, 3, "bf16", 3, True, True),
+    ("bwd_f32_L49", 12, 49, 96, 3, "f32", 4, True, False),
+]
+
+
+@pytest.mark.parametrize("name,N,L,C,heads,dtype,nW,backward,dbias", BF16_BIAS, ids=[c[0] for c in BF16_BIAS])
+def test_bf16_bias(oracle, name, N, L, C, heads, dtype, nW, backward, dbias):
+    """A bf16 bias gives the bits of the fp32 call on the same values, and matches the oracle."""
+    import torch
+    import paper_2501_06480_amd as fwa
+    w = workload("b16_" + name, N, L, C, heads, dtype, 7800 + L, backward=backward)
+    x = synth.draw(w)
+    bias, bias_dev = bf16_exact(synth.normal((heads, L, L), 7900 + L, 0.5))
+    labels = random_labels(nW, L, 7950 + L) if nW else None
+    kw = {"labels": torch.from_numpy(labels).cuda(), "mask_value": VALUE} if nW else {}
+    mask64 = oracle.mask_from_labels(labels, VALUE) if nW else None
+    q, k, v = (to_device(x, w, n) for n in ("q", "k", "v"))
+    bits = torch.int16 if dtype == "bf16" else torch.int32
+    if not backward:
+        o = fwa.fwa_forward(q, k, v, heads, w.scale, bias_dev, **kw)
+        o32 = fwa.fwa_forward(q, k, v, heads, w.scale, f32_device(bias), **kw)
+        torch.cuda.synchronize()
+        assert torch.equal(o.view(bits), o32.view(bits)), name
+        ref = oracle.forward(x["q"], x["k"], x["v"], heads, w.scale, bias, mask64)
+        err = max_abs(to_f64(o), ref)
+        print(f"{w.name}: bf16 bias, err={err:.2e}", flush=True)
+        assert err <= TOL[dtype], (name, err)
+        return
+    g = to_device(x, w, "d_o")
+    got = fwa.fwa_backward(q, k, v, g, heads, w.scale, bias_dev, want_dbias=dbias, **kw)
+    got32 = fwa.fwa_backward(q, k, v, g, heads, w.scale, f32_device(bias), want_dbias=dbias, **kw)
+    torch.cuda.synchronize()
+    for nm, a, b in zip(("dq", "dk", "dv"), got[:3], got32[:3]):
+        assert torch.equal(a.view(bits), b.view(bits)), (name, nm)
+    if dbias:
+        assert torch.equal(got[3].view(torch.int32), got32[3].view(torch.int32)), (name, "dbias")
+    ref = oracle.backward(x["q"], x["k"], x["v"], x["d_o"], heads, w.scale, bias, mask64, want_dbias=dbias)
+    for nm, t, want in zip(("dq", "dk", "dv"), got[:3], ref[:3]):
+        if dtype == "bf16":
+            check_bf16_output(to_f64(t), want, f"{w.name} {nm}")
+        else:
+            assert max_abs(to_f64(t), want) <= TOL["f32"], (name, nm)
+    if dbias:
+        assert max_abs(to_f64(got[3]), ref[3]) <= TOL["bf16"]
+
+
+def test_bf16_bias_argument_rules():
+    import torch
+    import paper_2501_06480_amd as fwa
+    q = torch.zeros((4, 49, 96), dtype=torch.bfloat16, device="cuda")
+    bias = torch.zeros((3, 49, 49), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(ValueError):   # a dense mask goes with an fp32 bias
+        fwa.fwa_forward(q, q.clone(), q.clone(), 3, 0.1, bias, torch.zeros((2, 49, 49), device="cuda"))
+    with pytest.raises(ValueError):
+        fwa.fwa_forward(q, q.clone(), q.clone(), 3, 0.1, bias[:2])
