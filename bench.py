@@ -225,7 +225,8 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (the workload is data-parallel "
-              "over windows; see DESIGN.md). Run with --gpus 1.", file=sys.stderr)
+              "over windows: each GPU would take a contiguous range of them, with one all-reduce of dBias). "
+              "Run with --gpus 1.", file=sys.stderr)
         sys.exit(2)
 
     import torch
