@@ -317,7 +317,19 @@ dbias_reduce_kernel(const f32x4* __restrict__ partial, float* __restrict__ dbias
     const size_t padded = (size_t)heads * nb * nb * 64;  // float4 per slot
     const size_t f = (size_t)blockIdx.x * 16 + x;        // < padded: the grid is padded / 16
     f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-    for (int s = y; s < slots; s += kReduceRows) acc += partial[(size_t)s * padded + f];
+    // 8 loads in flight per thread (one at a time leaves the kernel waiting on L2 latency); the
+    // additions keep the index order
+    for (int s = y; s < slots; s += 8 * kReduceRows) {
+        f32x4 v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int su = s + u * kReduceRows;
+            v[u] = su < slots ? partial[(size_t)su * padded + f] : f32x4{0.f, 0.f, 0.f, 0.f};
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            if (s + u * kReduceRows < slots) acc += v[u];
+    }
     part[y][x] = acc;
     __syncthreads();
     if (y == 0) {
