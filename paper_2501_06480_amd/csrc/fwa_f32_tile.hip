@@ -32,20 +32,33 @@ struct F32Tile {
     static constexpr int CH = D / 16;          // 16-channel chunks
 };
 
-// Copy rows [0, ROWS) x D floats of a tile into an LDS slab; rows beyond L arrive as zeros.
+// Rows [0, ROWS) x D floats of a tile on their way into an LDS slab: requested into registers, then
+// parked; rows beyond L arrive as zeros.
+template <int D, int ROWS>
+struct SlabInFlight {
+    using T = F32Tile<D>;
+    static constexpr int PASSES = (ROWS + T::RPP - 1) / T::RPP;
+    f32x4 v[PASSES];
+    __device__ __forceinline__ void request(const __amdgpu_buffer_rsrc_t r, uint32_t row_bytes, int tid) {
+        const uint32_t srow = (uint32_t)tid / T::TPR, scol = (uint32_t)tid % T::TPR;
+#pragma unroll
+        for (int t = 0; t < PASSES; ++t) v[t] = load_f32x4(r, (T::RPP * t + srow) * row_bytes + scol * 16u);
+    }
+    __device__ __forceinline__ void park(float* slab, int tid) const {
+        const uint32_t srow = (uint32_t)tid / T::TPR, scol = (uint32_t)tid % T::TPR;
+#pragma unroll
+        for (int t = 0; t < PASSES; ++t) {
+            const uint32_t row = T::RPP * t + srow;
+            if (row < (uint32_t)ROWS) *reinterpret_cast<f32x4*>(slab + row * T::RS + 4 * scol) = v[t];
+        }
+    }
+};
+
 template <int D, int ROWS>
 __device__ __forceinline__ void park_slab(float* slab, const __amdgpu_buffer_rsrc_t r, uint32_t row_bytes, int tid) {
-    using T = F32Tile<D>;
-    constexpr int PASSES = (ROWS + T::RPP - 1) / T::RPP;
-    const uint32_t srow = (uint32_t)tid / T::TPR, scol = (uint32_t)tid % T::TPR;
-    f32x4 v[PASSES];
-#pragma unroll
-    for (int t = 0; t < PASSES; ++t) v[t] = load_f32x4(r, (T::RPP * t + srow) * row_bytes + scol * 16u);
-#pragma unroll
-    for (int t = 0; t < PASSES; ++t) {
-        const uint32_t row = T::RPP * t + srow;
-        if (row < (uint32_t)ROWS) *reinterpret_cast<f32x4*>(slab + row * T::RS + 4 * scol) = v[t];
-    }
+    SlabInFlight<D, ROWS> x;
+    x.request(r, row_bytes, tid);
+    x.park(slab, tid);
 }
 
 // acc[jb] += X[16 jb + n][:] . own[:] over all channels: X rows from an LDS slab (A operand),
@@ -111,7 +124,7 @@ template <int NB, int D, bool BM>
 __global__ void __launch_bounds__(256) fwd_f32_tile_kernel(FwdArgs p) {
     using T = F32Tile<D>;
     constexpr int ROWS = 16 * NB;
-    extern __shared__ __attribute__((aligned(16))) float ldsf[];  // [K, V][ROWS][RS]
+    extern __shared__ __attribute__((aligned(16))) float ldsf[];  // one slab [ROWS][RS]: K, then V
     const int tid = threadIdx.x, lane = tid & 63;
     const int n = lane & 15, g = lane >> 4;
     const int qb = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -120,29 +133,39 @@ __global__ void __launch_bounds__(256) fwd_f32_tile_kernel(FwdArgs p) {
     const uint32_t row_bytes = (uint32_t)p.ldq * 4u, row_out = (uint32_t)p.ldo * 4u;
     const size_t tile = ((size_t)w * L * p.ldq + (size_t)h * D) * 4u;
     const uint32_t tile_bytes = (uint32_t)(L - 1) * row_bytes + 4u * D;
-    float* const lk = ldsf;
-    float* const lv = ldsf + ROWS * T::RS;
+    const bool active = qb < NB;  // the other waves only move slab rows
 
+    // K and V take turns in one slab: V waits in registers while the scores are made from K.  Half
+    // the LDS of two slabs means twice the workgroups per CU, so that one of them computes while
+    // another one loads (at width 256 a two-slab workgroup had the CU to itself).
     f32x4 qv[T::CH];
+    SlabInFlight<D, ROWS> kin, vin;
+    kin.request(make_rsrc((const char*)p.k + tile, tile_bytes), row_bytes, tid);
     load_own_rows<D>(qv, make_rsrc((const char*)p.q + tile, tile_bytes), row_bytes, qb, n, g);
-    park_slab<D, ROWS>(lk, make_rsrc((const char*)p.k + tile, tile_bytes), row_bytes, tid);
-    park_slab<D, ROWS>(lv, make_rsrc((const char*)p.v + tile, tile_bytes), row_bytes, tid);
+    kin.park(ldsf, tid);
+    vin.request(make_rsrc((const char*)p.v + tile, tile_bytes), row_bytes, tid);
     __syncthreads();
-    if (qb >= NB) return;  // no barrier follows
 
     f32x4 s[NB];
+    float m = 0.f, sum = 1.f;
+    if (active) {
 #pragma unroll
-    for (int jb = 0; jb < NB; ++jb) s[jb] = f32x4{0.f, 0.f, 0.f, 0.f};
-    rows_times_own<NB, D>(s, lk, qv, n, g);  // S[16 qb + n][16 jb + 4g + r]
-
-    BiasSrc rb = no_bias();
-    MaskSrc msk = {make_rsrc(nullptr, 0), 0.f, false};
-    if (BM) {
-        rb = bias_of_head(p, h);
-        msk = mask_of_window(p, w);
+        for (int jb = 0; jb < NB; ++jb) s[jb] = f32x4{0.f, 0.f, 0.f, 0.f};
+        rows_times_own<NB, D>(s, ldsf, qv, n, g);  // S[16 qb + n][16 jb + 4g + r]
     }
-    float m, sum;
-    softmax_f32<NB, BM>(s, p.scale, addend_at(rb, msk, (uint32_t)(16 * qb + n), 4u * g, (uint32_t)L), L, g, m, sum);
+    __syncthreads();  // every wave has read its K rows
+    vin.park(ldsf, tid);
+    if (active) {
+        BiasSrc rb = no_bias();
+        MaskSrc msk = {make_rsrc(nullptr, 0), 0.f, false};
+        if (BM) {
+            rb = bias_of_head(p, h);
+            msk = mask_of_window(p, w);
+        }
+        softmax_f32<NB, BM>(s, p.scale, addend_at(rb, msk, (uint32_t)(16 * qb + n), 4u * g, (uint32_t)L), L, g, m, sum);
+    }
+    __syncthreads();  // V is in place
+    if (!active) return;  // no barrier follows
 
     // O^T = V^T P^T, 16 channels at a time: k-slot g of step (jb, r) stands for key 16 jb + 4g + r
     const __amdgpu_buffer_rsrc_t ro =
@@ -156,7 +179,7 @@ __global__ void __launch_bounds__(256) fwd_f32_tile_kernel(FwdArgs p) {
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 const float pv = s[jb][r];
-                o = mfma_f32(lv[(16 * jb + 4 * g + r) * T::RS + 16 * cb + n], pv, o);  // o[r'] = O[16 qb + n][16 cb + 4g + r']
+                o = mfma_f32(ldsf[(16 * jb + 4 * g + r) * T::RS + 16 * cb + n], pv, o);  // o[r'] = O[16 qb + n][16 cb + 4g + r']
             }
         store_f32x4(o / sum, ro, off_o + 64 * cb);
     }
@@ -332,7 +355,7 @@ size_t f32_slab_bytes() {
 template <int NB, int D>
 hipError_t launch_fwd_nb(const FwdArgs& a, hipStream_t st) {
     const unsigned grid = (unsigned)(a.N * a.heads);
-    const size_t lds = f32_slab_bytes<NB, D>();
+    const size_t lds = f32_slab_bytes<NB, D>() / 2;  // K and V take turns in one slab
     const bool bm = a.bias || has_mask(a);
     const void* fn = bm ? reinterpret_cast<const void*>(&fwd_f32_tile_kernel<NB, D, true>)
                         : reinterpret_cast<const void*>(&fwd_f32_tile_kernel<NB, D, false>);
