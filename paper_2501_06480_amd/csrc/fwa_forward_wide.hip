@@ -5,8 +5,8 @@
 // is accumulated over D / 32 chunks of 32 channels (one matrix-core k-step each), and the output
 // is produced in D / 16 blocks of 16 channels.  One workgroup per (window, head), one wave per
 // 16-query block.  The head's K and V rows (D * 2 bytes each: whole 128-byte lines) go to LDS
-// with coalesced 16-byte loads; a wave reads its own Q rows straight from global memory as
-// operands, one 16-byte load per chunk, all requested before the slabs are parked.  Register
+// with coalesced 16-byte loads, one after the other through the same slab; a wave reads its own
+// Q rows straight from global memory as operands, one 16-byte load per chunk.  Register
 // layouts are those of the other forward kernels ("query on the lane"): S^T = K Q^T chunk by
 // chunk into the same accumulators, softmax across the 4 lanes that share a query, and
 // O^T = V^T P^T channel block by channel block with V^T from the transposing LDS read.
@@ -28,18 +28,28 @@ __global__ void __launch_bounds__(256) fwd_bf16_wide_kernel(FwdArgs p) {
     constexpr int TPR = D / 8;               // threads that move one slab row
     constexpr int RPP = 256 / TPR;           // rows per pass of the workgroup
     constexpr int PASSES = (ROWS + RPP - 1) / RPP;
-    extern __shared__ __attribute__((aligned(16))) uint4 lds[];  // [K, V][ROWS][STRIDE]
+    extern __shared__ __attribute__((aligned(16))) uint4 lds[];  // one slab [ROWS][STRIDE]: K, then V
     const int tid = threadIdx.x, lane = tid & 63;
     const int n = lane & 15, g = lane >> 4;
     const int qb = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const bool active = qb < NB;  // the other waves only move slab rows
     const uint32_t w = blockIdx.x / (uint32_t)p.heads, h = blockIdx.x % (uint32_t)p.heads;
     const int L = p.L;
     const uint32_t row_bytes = (uint32_t)p.ldq * 2u, row_out = (uint32_t)p.ldo * 2u;  // token rows: ldq / ldo elements apart
     const size_t tile = ((size_t)w * L * p.ldq + (size_t)h * D) * 2u;
     const uint32_t tile_bytes = (uint32_t)(L - 1) * row_bytes + 2u * D;  // rows beyond L read as zero
-    uint4* const lk = lds;
-    uint4* const lv = lds + ROWS * STRIDE;
 
+    // K and V take turns in one slab: V is requested once K is parked, waits in registers while the
+    // scores are made, and is parked behind a barrier.  Half the LDS of two slabs means twice the
+    // workgroups per CU at widths 128 and 256, where LDS is what limits them.
+    const uint32_t srow = (uint32_t)tid / TPR, scol = (uint32_t)tid % TPR;
+    u32x4 slab[PASSES];
+    {
+        const __amdgpu_buffer_rsrc_t rk = make_rsrc((const char*)p.k + tile, tile_bytes);
+#pragma unroll
+        for (int t = 0; t < PASSES; ++t)
+            slab[t] = __builtin_amdgcn_raw_buffer_load_b128(rk, (RPP * t + srow) * row_bytes + scol * 16u, 0, 0);
+    }
     // Q rows of this wave's block as operands: lane (g, n) takes channels 32 c + 8g .. + 7 of row n
     bf16x8 qop[CH];
     {
@@ -48,55 +58,56 @@ __global__ void __launch_bounds__(256) fwd_bf16_wide_kernel(FwdArgs p) {
 #pragma unroll
         for (int c = 0; c < CH; ++c) qop[c] = as_bf16x8(__builtin_amdgcn_raw_buffer_load_b128(rq, off + 64 * c, 0, 0));
     }
-    {
-        const uint32_t srow = (uint32_t)tid / TPR, scol = (uint32_t)tid % TPR;
-        const __amdgpu_buffer_rsrc_t rk = make_rsrc((const char*)p.k + tile, tile_bytes);
-        const __amdgpu_buffer_rsrc_t rv = make_rsrc((const char*)p.v + tile, tile_bytes);
-        u32x4 sk[PASSES], sv[PASSES];
-#pragma unroll
-        for (int t = 0; t < PASSES; ++t) {
-            const uint32_t off = (RPP * t + srow) * row_bytes + scol * 16u;
-            sk[t] = __builtin_amdgcn_raw_buffer_load_b128(rk, off, 0, 0);
-            sv[t] = __builtin_amdgcn_raw_buffer_load_b128(rv, off, 0, 0);
-        }
+    auto park = [&]() {
 #pragma unroll
         for (int t = 0; t < PASSES; ++t) {
             const uint32_t row = RPP * t + srow;
-            if (row < (uint32_t)ROWS) {
-                lk[row * STRIDE + scol] = __builtin_bit_cast(uint4, sk[t]);
-                lv[row * STRIDE + scol] = __builtin_bit_cast(uint4, sv[t]);
-            }
+            if (row < (uint32_t)ROWS) lds[row * STRIDE + scol] = __builtin_bit_cast(uint4, slab[t]);
         }
+    };
+    park();
+    {
+        const __amdgpu_buffer_rsrc_t rv = make_rsrc((const char*)p.v + tile, tile_bytes);
+#pragma unroll
+        for (int t = 0; t < PASSES; ++t)
+            slab[t] = __builtin_amdgcn_raw_buffer_load_b128(rv, (RPP * t + srow) * row_bytes + scol * 16u, 0, 0);
     }
     __syncthreads();
-    if (qb >= NB) return;  // no barrier follows
 
     // scores: S[16 qb + n][16 jb + 4g + r], accumulated over the chunks
     f32x4 s[NB];
 #pragma unroll
     for (int jb = 0; jb < NB; ++jb) s[jb] = f32x4{0.f, 0.f, 0.f, 0.f};
-    const uint4* const lkh = lk + n * STRIDE + g;  // K[16 jb + n][32 c + 8g ..] at lkh[16 jb STRIDE + 4 c]
+    if (active) {
+        const uint4* const lkh = lds + n * STRIDE + g;  // K[16 jb + n][32 c + 8g ..] at lkh[16 jb STRIDE + 4 c]
 #pragma unroll
-    for (int c = 0; c < CH; ++c)
+        for (int c = 0; c < CH; ++c)
 #pragma unroll
-        for (int jb = 0; jb < NB; ++jb)
-            s[jb] = mfma_bf16(__builtin_bit_cast(bf16x8, lkh[16 * jb * STRIDE + 4 * c]), qop[c], s[jb]);
+            for (int jb = 0; jb < NB; ++jb)
+                s[jb] = mfma_bf16(__builtin_bit_cast(bf16x8, lkh[16 * jb * STRIDE + 4 * c]), qop[c], s[jb]);
+    }
+    __syncthreads();  // every wave has read its K operands
+    park();
 
     const float sl2 = p.scale * kLog2e;
-    float inv;
-    if (BM) {
-        const BiasSrc rb = bias_of_head(p, h);
-        const AddendGlobal addend = addend_at(rb, mask_of_window(p, w), (uint32_t)(16 * qb + n), 4u * g, (uint32_t)L);
-        inv = softmax_block<NB, true>(s, sl2, addend, L, g);
-    } else {
-        inv = softmax_block<NB, false>(s, sl2, AddendNone{}, L, g);
+    float inv = 1.f;
+    if (active) {
+        if (BM) {
+            const BiasSrc rb = bias_of_head(p, h);
+            const AddendGlobal addend = addend_at(rb, mask_of_window(p, w), (uint32_t)(16 * qb + n), 4u * g, (uint32_t)L);
+            inv = softmax_block<NB, true>(s, sl2, addend, L, g);
+        } else {
+            inv = softmax_block<NB, false>(s, sl2, AddendNone{}, L, g);
+        }
     }
+    __syncthreads();  // V is in place
+    if (!active) return;  // no barrier follows
     bf16x8 pop[NB2];
 #pragma unroll
     for (int kp = 0; kp < NB2; ++kp) pop[kp] = prob_operand<NB>(s, kp);
 
     // O^T = V^T P^T, 16 channels at a time: o[r] = O[16 qb + n][16 cb + 4g + r]
-    const uint16_t* const lvh = reinterpret_cast<const uint16_t*>(lv) + (4 * g + (n >> 2)) * SROW + 4 * (n & 3);
+    const uint16_t* const lvh = reinterpret_cast<const uint16_t*>(lds) + (4 * g + (n >> 2)) * SROW + 4 * (n & 3);
     const __amdgpu_buffer_rsrc_t ro = make_rsrc((char*)p.o + ((size_t)w * L * p.ldo + (size_t)h * D) * 2u,
                                                 (uint32_t)(L - 1) * row_out + 2u * D);
     const uint32_t off_o = (uint32_t)(16 * qb + n) * row_out + 8u * g;
@@ -115,7 +126,7 @@ __global__ void __launch_bounds__(256) fwd_bf16_wide_kernel(FwdArgs p) {
 template <int NB, int D>
 hipError_t launch_wide_nb(const FwdArgs& a, hipStream_t st) {
     const unsigned grid = (unsigned)(a.N * a.heads);
-    const size_t lds = (size_t)2 * 16 * NB * (D / 8 + 1) * 16;
+    const size_t lds = (size_t)16 * NB * (D / 8 + 1) * 16;  // one slab: K, then V
     const bool bm = a.bias || has_mask(a);
     const void* fn = bm ? reinterpret_cast<const void*>(&fwd_bf16_wide_kernel<NB, D, true>)
                         : reinterpret_cast<const void*>(&fwd_bf16_wide_kernel<NB, D, false>);
