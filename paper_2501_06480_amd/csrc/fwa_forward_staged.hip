@@ -301,8 +301,8 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) fwd_bf16_persistent_kerne
 // ---------------------------------------------------------------------------
 // Row-blocked forward for 64 < L <= 256 (paper Discussion: such windows do not fit its
 // on-chip tile; here K and V of the head stay on chip and the queries are walked in blocks
-// of 16).  The workgroup parks the K and V slabs of its heads in LDS once; two waves share
-// each head and take alternate 16-query blocks.  Per block a wave reads its K operands
+// of 16).  The workgroup parks the K and V slabs of its heads in LDS once; QW waves share
+// each head and take every QW-th 16-query block.  Per block a wave reads its K operands
 // (ds_read_b128) and V operands (transposing reads) from LDS, keeps the 16 x L score block
 // in registers, and loads Q / stores O for its own rows directly.
 struct RowBlockGeom {
@@ -312,16 +312,17 @@ struct RowBlockGeom {
     uint32_t xcd_remap, xcd_q, xcd_r;
 };
 
-template <int NB, bool BM>
-__global__ void __launch_bounds__(64 * kWavesPerBlock) fwd_bf16_rowblock_kernel(FwdArgs p, RowBlockGeom gm) {
+template <int NB, bool BM, int QW>
+__global__ void __launch_bounds__(64 * 2 * QW) fwd_bf16_rowblock_kernel(FwdArgs p, RowBlockGeom gm) {
     constexpr int NB2 = (NB + 1) / 2;
     constexpr int ROWS = 16 * NB;
-    constexpr int PASSES = (ROWS + 31) / 32;  // the workgroup moves 32 slab rows per pass
+    constexpr int RPP = 16 * QW;                       // slab rows the workgroup moves per pass
+    constexpr int PASSES = (ROWS + RPP - 1) / RPP;
     extern __shared__ __attribute__((aligned(16))) uint4 lds[];  // [2][ROWS][stride]: K, V
     const int tid = threadIdx.x, lane = tid & 63;
     const int n = lane & 15, g = lane >> 4;
     const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const uint32_t hl = wave >> 1, qs = wave & 1u;
+    const uint32_t hl = wave / QW, qs = wave % QW;
     const uint32_t lb = gm.xcd_remap ? xcd_logical_block(blockIdx.x, gm.xcd_q, gm.xcd_r) : blockIdx.x;
     const uint32_t w = fastdiv(lb, gm.groups);
     const uint32_t hg = lb - w * gm.groups.d;
@@ -334,7 +335,7 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) fwd_bf16_rowblock_kernel(
     uint4* const lk = lds;
     uint4* const lv = lds + ROWS * stride;
     {
-        const uint32_t rip = fastdiv((uint32_t)tid, gm.lanes_per_row);  // 0..31
+        const uint32_t rip = fastdiv((uint32_t)tid, gm.lanes_per_row);  // 0..RPP-1
         const uint32_t col = (uint32_t)tid - rip * gm.lanes_per_row.d;
         const size_t slab = ((size_t)w * L * p.ldq + (size_t)hg * hpb * kHeadDim) * 2u;
         const uint32_t slab_bytes = (uint32_t)(L - 1) * row_bytes + hpb * 2u * kHeadDim;
@@ -343,13 +344,13 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) fwd_bf16_rowblock_kernel(
         u32x4 sk[PASSES], sv[PASSES];
 #pragma unroll
         for (int t = 0; t < PASSES; ++t) {
-            const uint32_t off = (32 * t + rip) * row_bytes + col * 16u;  // rows beyond L arrive as zeros
+            const uint32_t off = (RPP * t + rip) * row_bytes + col * 16u;  // rows beyond L arrive as zeros
             sk[t] = __builtin_amdgcn_raw_buffer_load_b128(rk, off, 0, 0);
             sv[t] = __builtin_amdgcn_raw_buffer_load_b128(rv, off, 0, 0);
         }
 #pragma unroll
         for (int t = 0; t < PASSES; ++t) {
-            const uint32_t row = 32 * t + rip;
+            const uint32_t row = RPP * t + rip;
             if (row < (uint32_t)ROWS) {
                 lk[row * stride + col] = __builtin_bit_cast(uint4, sk[t]);
                 lv[row * stride + col] = __builtin_bit_cast(uint4, sv[t]);
@@ -376,9 +377,9 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) fwd_bf16_rowblock_kernel(
                                 (4 * g + (n >> 2)) * (stride * 8u) + 4 * (n & 3);
 
     u32x4 qnext = __builtin_amdgcn_raw_buffer_load_b128(rq, off_row + 16 * qs * row_bytes, 0, 0);
-    for (int qb = qs; qb < NB; qb += 2) {
+    for (int qb = qs; qb < NB; qb += QW) {
         const bf16x8 qop = as_bf16x8(qnext);
-        if (qb + 2 < NB) qnext = __builtin_amdgcn_raw_buffer_load_b128(rq, off_row + 16 * (qb + 2) * row_bytes, 0, 0);
+        if (qb + QW < NB) qnext = __builtin_amdgcn_raw_buffer_load_b128(rq, off_row + 16 * (qb + QW) * row_bytes, 0, 0);
         f32x4 s[NB];
 #pragma unroll
         for (int jb = 0; jb < NB; ++jb) {
@@ -608,6 +609,23 @@ hipError_t launch_rowpersist_nb(const FwdArgs& a, long long G, hipStream_t st) {
     return launch_rowpersist_hpb<NB, 1>(a, G, st);
 }
 
+template <int NB, int QW>
+hipError_t launch_rowblock_qw(const FwdArgs& a, const RowBlockGeom& gm, unsigned grid, int hpb, size_t lds, bool bm,
+                              hipStream_t st) {
+    const unsigned block = 64u * (unsigned)(QW * hpb);
+    const void* fn = bm ? reinterpret_cast<const void*>(&fwd_bf16_rowblock_kernel<NB, true, QW>)
+                        : reinterpret_cast<const void*>(&fwd_bf16_rowblock_kernel<NB, false, QW>);
+    if (lds > 64 * 1024) {
+        const hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+    }
+    if (bm)
+        hipLaunchKernelGGL((fwd_bf16_rowblock_kernel<NB, true, QW>), dim3(grid), dim3(block), lds, st, a, gm);
+    else
+        hipLaunchKernelGGL((fwd_bf16_rowblock_kernel<NB, false, QW>), dim3(grid), dim3(block), lds, st, a, gm);
+    return hipGetLastError();
+}
+
 template <int NB>
 hipError_t launch_rowblock_nb(const FwdArgs& a, hipStream_t st) {
     RowBlockGeom gm;
@@ -616,7 +634,7 @@ hipError_t launch_rowblock_nb(const FwdArgs& a, hipStream_t st) {
     gm.groups = make_fastdiv(groups);
     gm.lanes_per_row = make_fastdiv(4u * (uint32_t)hpb);
     gm.heads_per_block = (uint32_t)hpb;
-    const unsigned grid = (unsigned)(a.N * groups), block = 128u * (unsigned)hpb;
+    const unsigned grid = (unsigned)(a.N * groups);
     gm.xcd_remap = (hpb == 1 && groups > 1) ? 1u : 0u;  // 64 B slabs: keep line-sharing heads on one L2
     gm.xcd_q = grid / 8u;
     gm.xcd_r = grid % 8u;
@@ -626,17 +644,10 @@ hipError_t launch_rowblock_nb(const FwdArgs& a, hipStream_t st) {
         const long long G = rowpersist_slots<NB>(a);
         if (G > 0) return launch_rowpersist_nb<NB>(a, G, st);
     }
-    const void* fn = bm ? reinterpret_cast<const void*>(&fwd_bf16_rowblock_kernel<NB, true>)
-                        : reinterpret_cast<const void*>(&fwd_bf16_rowblock_kernel<NB, false>);
-    if (lds > 64 * 1024) {
-        const hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-    }
-    if (bm)
-        hipLaunchKernelGGL((fwd_bf16_rowblock_kernel<NB, true>), dim3(grid), dim3(block), lds, st, a, gm);
-    else
-        hipLaunchKernelGGL((fwd_bf16_rowblock_kernel<NB, false>), dim3(grid), dim3(block), lds, st, a, gm);
-    return hipGetLastError();
+    // waves per head: 2 with two heads per workgroup (3 or 4 measured 3-20 % slower at L = 144..256), 4
+    // with one (an odd head count: 10 % faster than 2)
+    if (hpb == 1) return launch_rowblock_qw<NB, 4>(a, gm, grid, hpb, lds, bm, st);
+    return launch_rowblock_qw<NB, 2>(a, gm, grid, hpb, lds, bm, st);
 }
 
 template <int NB>
