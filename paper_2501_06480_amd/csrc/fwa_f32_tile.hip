@@ -347,6 +347,146 @@ __global__ void __launch_bounds__(256) bwd_f32_tile_kernel(BwdArgs p) {
     }
 }
 
+// Backward for widths 32 and 64: P and dS of a query block go through LDS tiles instead of being
+// made a second time.  The fp32 matrix instruction takes single values, so any orientation can be
+// read out of a row-major tile: pass 1 leaves P[i][j] and dS[i][j] (16-byte writes of a lane's 4
+// consecutive keys), pass 2 reads them with the query on the slot and the key on the lane.  Pass 2
+// then needs no K, V rows and no statistics, only the Q and dO slabs, which the waves write from the
+// operand registers of pass 1.  10 instead of 14 L^2 D flops per tile on the unit that bounds these
+// kernels; the two tiles (34 KB) do not fit beside the slabs of width 256, and at width 128 they
+// would leave one workgroup per CU.
+constexpr int kTileStrideF32 = 68;  // floats per tile row: rows 4 apart fall 16 banks apart
+template <int NB, int D, bool BM>
+__global__ void __launch_bounds__(256) bwd_f32_exchange_kernel(BwdArgs p) {
+    using T = F32Tile<D>;
+    constexpr int ROWS = 16 * NB;
+    constexpr int TS = kTileStrideF32;
+    extern __shared__ __attribute__((aligned(16))) float ldsf[];  // two slabs [ROWS][RS], then P, dS tiles [ROWS][TS]
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int n = lane & 15, g = lane >> 4;
+    const int role = __builtin_amdgcn_readfirstlane(tid >> 6);  // query block in pass 1, key block in pass 2
+    const bool active = role < NB;
+    const uint32_t w = blockIdx.x / (uint32_t)p.heads, h = blockIdx.x % (uint32_t)p.heads;
+    const int L = p.L;
+    const uint32_t row_bytes = (uint32_t)p.ldq * 4u, row_g = (uint32_t)p.ldg * 4u, row_d = (uint32_t)p.ldd * 4u;
+    const size_t tile = ((size_t)w * L * p.ldq + (size_t)h * D) * 4u;
+    const size_t tile_g = ((size_t)w * L * p.ldg + (size_t)h * D) * 4u;
+    const size_t tile_d = ((size_t)w * L * p.ldd + (size_t)h * D) * 4u;
+    const uint32_t tile_bytes = (uint32_t)(L - 1) * row_bytes + 4u * D;
+    const uint32_t tile_bytes_g = (uint32_t)(L - 1) * row_g + 4u * D;
+    const uint32_t tile_bytes_d = (uint32_t)(L - 1) * row_d + 4u * D;
+    const __amdgpu_buffer_rsrc_t rq = make_rsrc((const char*)p.q + tile, tile_bytes);
+    const __amdgpu_buffer_rsrc_t rk = make_rsrc((const char*)p.k + tile, tile_bytes);
+    const __amdgpu_buffer_rsrc_t rv = make_rsrc((const char*)p.v + tile, tile_bytes);
+    const __amdgpu_buffer_rsrc_t rg = make_rsrc((const char*)p.d_o + tile_g, tile_bytes_g);
+    float* const sa = ldsf;                   // K, then Q
+    float* const sb = ldsf + ROWS * T::RS;    // V, then dO
+    float* const tp = ldsf + 2 * ROWS * T::RS;
+    float* const td = tp + ROWS * TS;
+    const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+
+    f32x4 qv[T::CH], gv[T::CH];  // own Q and dO rows (rows beyond L arrive as zeros)
+    load_own_rows<D>(qv, rq, row_bytes, role, n, g);
+    load_own_rows<D>(gv, rg, row_g, role, n, g);
+    park_slab<D, ROWS>(sa, rk, row_bytes, tid);
+    park_slab<D, ROWS>(sb, rv, row_bytes, tid);
+    __syncthreads();
+
+    // ---------------- pass 1: query block `role` ----------------
+    if (active) {
+        const int qb = role;
+        BiasSrc rb = no_bias();
+        MaskSrc msk = {make_rsrc(nullptr, 0), 0.f, false};
+        if (BM) {
+            rb = bias_of_head(p, h);
+            msk = mask_of_window(p, w);
+        }
+        f32x4 s[NB], dp[NB];
+#pragma unroll
+        for (int jb = 0; jb < NB; ++jb) s[jb] = dp[jb] = zero;
+        rows_times_own<NB, D>(s, sa, qv, n, g);   // <k_j, q_i>: query i = 16 qb + n, key j = 16 jb + 4g + r
+        rows_times_own<NB, D>(dp, sb, gv, n, g);  // <v_j, do_i>
+        float m, sum;
+        softmax_f32<NB, BM>(s, p.scale, addend_at(rb, msk, (uint32_t)(16 * qb + n), 4u * g, (uint32_t)L), L, g, m, sum);
+        float delta = 0.f;
+#pragma unroll
+        for (int jb = 0; jb < NB; ++jb)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                s[jb][r] = s[jb][r] / sum;  // P
+                delta = fmaf(s[jb][r], dp[jb][r], delta);
+            }
+        delta = sum_over_g(delta);
+#pragma unroll
+        for (int jb = 0; jb < NB; ++jb) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) dp[jb][r] = s[jb][r] * (dp[jb][r] - delta);  // dS
+            *reinterpret_cast<f32x4*>(tp + (16 * qb + n) * TS + 16 * jb + 4 * g) = s[jb];
+            *reinterpret_cast<f32x4*>(td + (16 * qb + n) * TS + 16 * jb + 4 * g) = dp[jb];
+        }
+        // dQ^T = K^T dS^T, 16 channels at a time: k-slot g of step (jb, r) stands for key 16 jb + 4g + r
+        const __amdgpu_buffer_rsrc_t rdq = make_rsrc((char*)p.dq + tile_d, tile_bytes_d);
+        const uint32_t off_q = (uint32_t)(16 * qb + n) * row_d + 16u * g;
+#pragma unroll
+        for (int cb = 0; cb < T::CH; ++cb) {
+            f32x4 acc = zero;
+#pragma unroll
+            for (int jb = 0; jb < NB; ++jb)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const float ds = dp[jb][r];
+                    acc = mfma_f32(sa[(16 * jb + 4 * g + r) * T::RS + 16 * cb + n], ds, acc);
+                }
+            store_f32x4(acc * p.scale, rdq, off_q + 64 * cb);  // acc[r'] = dQ[16 qb + n][16 cb + 4g + r']
+        }
+    }
+    __syncthreads();  // K, V no longer needed; the tiles are complete
+    // the Q and dO slabs take the place of K and V, written from the operand registers
+    if (active) {
+#pragma unroll
+        for (int c = 0; c < T::CH; ++c) {
+            *reinterpret_cast<f32x4*>(sa + (16 * role + n) * T::RS + 16 * c + 4 * g) = qv[c];
+            *reinterpret_cast<f32x4*>(sb + (16 * role + n) * T::RS + 16 * c + 4 * g) = gv[c];
+        }
+    }
+    __syncthreads();
+
+    // ---------------- pass 2: key block `role` ----------------
+    if (active) {
+        const int jb = role;
+        f32x4 av[T::CH], ak[T::CH];  // dV, dK [16 jb + n][16 cb + 4g + r]
+#pragma unroll
+        for (int cb = 0; cb < T::CH; ++cb) av[cb] = ak[cb] = zero;
+#pragma unroll
+        for (int qb = 0; qb < NB; ++qb) {
+            // P and dS with the query on the slot: pr[r] = P[16 qb + 4g + r][16 jb + n]
+            f32x4 pr, ds;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                pr[r] = tp[(16 * qb + 4 * g + r) * TS + 16 * jb + n];
+                ds[r] = td[(16 * qb + 4 * g + r) * TS + 16 * jb + n];
+            }
+            // dV^T += dO^T P, dK^T += Q^T dS: k-slot g of step r stands for query 16 qb + 4g + r
+#pragma unroll
+            for (int cb = 0; cb < T::CH; ++cb)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const float pp = pr[r], dd = ds[r];
+                    av[cb] = mfma_f32(sb[(16 * qb + 4 * g + r) * T::RS + 16 * cb + n], pp, av[cb]);
+                    ak[cb] = mfma_f32(sa[(16 * qb + 4 * g + r) * T::RS + 16 * cb + n], dd, ak[cb]);
+                }
+        }
+        const __amdgpu_buffer_rsrc_t rdv = make_rsrc((char*)p.dv + tile_d, tile_bytes_d);
+        const __amdgpu_buffer_rsrc_t rdk = make_rsrc((char*)p.dk + tile_d, tile_bytes_d);
+        const uint32_t off_k = (uint32_t)(16 * jb + n) * row_d + 16u * g;
+#pragma unroll
+        for (int cb = 0; cb < T::CH; ++cb) {
+            store_f32x4(av[cb], rdv, off_k + 64 * cb);
+            store_f32x4(ak[cb] * p.scale, rdk, off_k + 64 * cb);
+        }
+    }
+}
+
 template <int NB, int D>
 size_t f32_slab_bytes() {
     return (size_t)2 * 16 * NB * (D + 4) * 4;
@@ -373,19 +513,34 @@ hipError_t launch_fwd_nb(const FwdArgs& a, hipStream_t st) {
 template <int NB, int D>
 hipError_t launch_bwd_nb(const BwdArgs& a, hipStream_t st) {
     const unsigned grid = (unsigned)(a.N * a.heads);
-    const size_t lds = f32_slab_bytes<NB, D>() + (size_t)2 * 16 * NB * 4;
     const bool bm = a.bias || has_mask(a);
-    const void* fn = bm ? reinterpret_cast<const void*>(&bwd_f32_tile_kernel<NB, D, true>)
-                        : reinterpret_cast<const void*>(&bwd_f32_tile_kernel<NB, D, false>);
-    if (lds > 64 * 1024) {
-        const hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
+    if constexpr (D <= 64) {  // P and dS exchanged through LDS tiles
+        const size_t lds = f32_slab_bytes<NB, D>() + (size_t)2 * 16 * NB * kTileStrideF32 * 4;
+        const void* fn = bm ? reinterpret_cast<const void*>(&bwd_f32_exchange_kernel<NB, D, true>)
+                            : reinterpret_cast<const void*>(&bwd_f32_exchange_kernel<NB, D, false>);
+        if (lds > 64 * 1024) {
+            const hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) return e;
+        }
+        if (bm)
+            hipLaunchKernelGGL((bwd_f32_exchange_kernel<NB, D, true>), dim3(grid), dim3(256), lds, st, a);
+        else
+            hipLaunchKernelGGL((bwd_f32_exchange_kernel<NB, D, false>), dim3(grid), dim3(256), lds, st, a);
+        return hipGetLastError();
+    } else {
+        const size_t lds = f32_slab_bytes<NB, D>() + (size_t)2 * 16 * NB * 4;
+        const void* fn = bm ? reinterpret_cast<const void*>(&bwd_f32_tile_kernel<NB, D, true>)
+                            : reinterpret_cast<const void*>(&bwd_f32_tile_kernel<NB, D, false>);
+        if (lds > 64 * 1024) {
+            const hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) return e;
+        }
+        if (bm)
+            hipLaunchKernelGGL((bwd_f32_tile_kernel<NB, D, true>), dim3(grid), dim3(256), lds, st, a);
+        else
+            hipLaunchKernelGGL((bwd_f32_tile_kernel<NB, D, false>), dim3(grid), dim3(256), lds, st, a);
+        return hipGetLastError();
     }
-    if (bm)
-        hipLaunchKernelGGL((bwd_f32_tile_kernel<NB, D, true>), dim3(grid), dim3(256), lds, st, a);
-    else
-        hipLaunchKernelGGL((bwd_f32_tile_kernel<NB, D, false>), dim3(grid), dim3(256), lds, st, a);
-    return hipGetLastError();
 }
 
 #define FWA_F32_NB_SWITCH(FN, D, a, s)            \
