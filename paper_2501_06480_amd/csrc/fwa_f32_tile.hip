@@ -1,8 +1,7 @@
 // fp32 kernels for windows of up to 64 tokens and head widths 32, 64, 128, 256, forward and
-// backward (longer windows of width 32 have a forward kernel of their own in fwa_forward.hip).  True fp32 arithmetic throughout: v_mfma_f32_16x16x4_f32 products, v_exp_f32, IEEE
-// division.  These are the shapes and the precision of the paper's kernel benchmark
-// (section 3.1); they are written for correctness and reasonable speed, not tuned like the bf16
-// paths.
+// backward (longer windows of width 32 have a forward kernel of their own in fwa_forward.hip).
+// True fp32 arithmetic throughout: v_mfma_f32_16x16x4_f32 products, v_exp_f32, IEEE division.
+// These are the shapes and the precision of the paper's kernel benchmark (section 3.1).
 //
 // One workgroup per (window, head), one wave per block of 16 rows.  The fp32 matrix instruction
 // takes one value per lane and k-slot group: lane (g, n) gives A[m = n][k = g] and B[k = g][n] and
@@ -11,10 +10,8 @@
 // row operands are read; operands with the contraction index on the rows of a slab (V^T, K^T,
 // dO^T, Q^T) are read element by element out of LDS.
 //
-// Backward: as for large bf16 windows the score tile is produced twice, in the two orientations
-// the outputs need, instead of being transposed: pass 1 ("query on the lane") gives the softmax
-// statistics and dQ with K, V parked in LDS; pass 2 ("key on the lane") gives dV and dK with Q, dO
-// parked in their place.  dBias is not produced in fp32.
+// Backward: pass 1 with K, V parked gives P, dS and dQ; dV and dK follow from P resp. dS exchanged
+// through an LDS tile and the dO resp. Q slab (see the kernel).  dBias is not produced in fp32.
 #include "fwa_device.h"
 #include "fwa_internal.h"
 #include "fwa_softmax.h"
@@ -186,185 +183,27 @@ __global__ void __launch_bounds__(256) fwd_f32_tile_kernel(FwdArgs p) {
 }
 
 // ----------------------------------------------------------------- backward
+// Pass 1 ("query on the lane", K and V parked in the two slabs): S, softmax, dP, delta, dS, dQ.
+// P and dS are not made a second time for dV and dK: the fp32 matrix instruction takes single
+// values, so any orientation can be read out of a row-major tile.  dV and dK are made one after the
+// other, each from one slab and one tile, and the tile lives where a dead slab was (a tile row, 68
+// floats, is not longer than a slab row except at width 32, where the slab area is sized by the
+// tile): dO -> slab B and P -> tile in slab A, dV; then Q -> slab B and dS -> tile in slab A, dK.
+// The waves write those slabs and tiles from the registers of pass 1, so every input is read from
+// global memory once, and the matrix cores do 10 L^2 D flops per tile (making S and dP again in
+// the second orientation, as the large-window bf16 kernel must, costs 14 and was 15-30 % slower).
+constexpr int kTileStrideF32 = 68;  // floats per tile row: rows 4 apart fall 16 banks apart
 template <int NB, int D, bool BM>
 __global__ void __launch_bounds__(256) bwd_f32_tile_kernel(BwdArgs p) {
     using T = F32Tile<D>;
     constexpr int ROWS = 16 * NB;
-    extern __shared__ __attribute__((aligned(16))) float ldsf[];  // two slabs [ROWS][RS], then M[ROWS], delta[ROWS]
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int n = lane & 15, g = lane >> 4;
-    const int role = __builtin_amdgcn_readfirstlane(tid >> 6);  // query block in pass 1, key block in pass 2
-    const bool active = role < NB;
-    const uint32_t w = blockIdx.x / (uint32_t)p.heads, h = blockIdx.x % (uint32_t)p.heads;
-    const int L = p.L;
-    const uint32_t row_bytes = (uint32_t)p.ldq * 4u, row_g = (uint32_t)p.ldg * 4u, row_d = (uint32_t)p.ldd * 4u;
-    const size_t tile = ((size_t)w * L * p.ldq + (size_t)h * D) * 4u;
-    const size_t tile_g = ((size_t)w * L * p.ldg + (size_t)h * D) * 4u;
-    const size_t tile_d = ((size_t)w * L * p.ldd + (size_t)h * D) * 4u;
-    const uint32_t tile_bytes = (uint32_t)(L - 1) * row_bytes + 4u * D;
-    const uint32_t tile_bytes_g = (uint32_t)(L - 1) * row_g + 4u * D;
-    const uint32_t tile_bytes_d = (uint32_t)(L - 1) * row_d + 4u * D;
-    const __amdgpu_buffer_rsrc_t rq = make_rsrc((const char*)p.q + tile, tile_bytes);
-    const __amdgpu_buffer_rsrc_t rk = make_rsrc((const char*)p.k + tile, tile_bytes);
-    const __amdgpu_buffer_rsrc_t rv = make_rsrc((const char*)p.v + tile, tile_bytes);
-    const __amdgpu_buffer_rsrc_t rg = make_rsrc((const char*)p.d_o + tile_g, tile_bytes_g);
-    float* const sa = ldsf;                   // K, then Q
-    float* const sb = ldsf + ROWS * T::RS;    // V, then dO
-    float* const stM = ldsf + 2 * ROWS * T::RS;
-    float* const stD = stM + ROWS;
-    const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
-
-    BiasSrc rb = no_bias();
-    MaskSrc msk = {make_rsrc(nullptr, 0), 0.f, false};
-    if (BM) {
-        rb = bias_of_head(p, h);
-        msk = mask_of_window(p, w);
-    }
-
-    park_slab<D, ROWS>(sa, rk, row_bytes, tid);
-    park_slab<D, ROWS>(sb, rv, row_bytes, tid);
-    __syncthreads();
-
-    // ---------------- pass 1: query block `role` ----------------
-    f32x4 qv[T::CH], gv[T::CH];  // own Q and dO rows in pass 1; own K and V rows in pass 2 (see below)
-    if (active) {
-        const int qb = role;
-        load_own_rows<D>(qv, rq, row_bytes, qb, n, g);
-        load_own_rows<D>(gv, rg, row_g, qb, n, g);
-        f32x4 s[NB], dp[NB];
-#pragma unroll
-        for (int jb = 0; jb < NB; ++jb) s[jb] = dp[jb] = zero;
-        rows_times_own<NB, D>(s, sa, qv, n, g);   // <k_j, q_i>: query i = 16 qb + n, key j = 16 jb + 4g + r
-        rows_times_own<NB, D>(dp, sb, gv, n, g);  // <v_j, do_i>
-        float m, sum;
-        softmax_f32<NB, BM>(s, p.scale, addend_at(rb, msk, (uint32_t)(16 * qb + n), 4u * g, (uint32_t)L), L, g, m, sum);
-        float delta = 0.f;
-#pragma unroll
-        for (int jb = 0; jb < NB; ++jb)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                s[jb][r] = s[jb][r] / sum;  // P
-                delta = fmaf(s[jb][r], dp[jb][r], delta);
-            }
-        delta = sum_over_g(delta);
-        if (g == 0) {
-            stM[16 * qb + n] = m + logf(sum);  // p_ij = exp(score_ij - M_i)
-            stD[16 * qb + n] = delta;
-        }
-#pragma unroll
-        for (int jb = 0; jb < NB; ++jb)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) dp[jb][r] = s[jb][r] * (dp[jb][r] - delta);  // dS
-        // dQ^T = K^T dS^T, 16 channels at a time: k-slot g of step (jb, r) stands for key 16 jb + 4g + r
-        const __amdgpu_buffer_rsrc_t rdq = make_rsrc((char*)p.dq + tile_d, tile_bytes_d);
-        const uint32_t off_q = (uint32_t)(16 * qb + n) * row_d + 16u * g;
-#pragma unroll
-        for (int cb = 0; cb < T::CH; ++cb) {
-            f32x4 acc = zero;
-#pragma unroll
-            for (int jb = 0; jb < NB; ++jb)
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const float ds = dp[jb][r];
-                    acc = mfma_f32(sa[(16 * jb + 4 * g + r) * T::RS + 16 * cb + n], ds, acc);
-                }
-            store_f32x4(acc * p.scale, rdq, off_q + 64 * cb);  // acc[r'] = dQ[16 qb + n][16 cb + 4g + r']
-        }
-    }
-    __syncthreads();  // K, V no longer needed as whole slabs; statistics complete
-    // Pass 2 wants the Q and dO slabs in LDS and the wave's own K and V rows in registers: exactly
-    // the other way round.  Between them the waves hold every row of Q and dO, and each wave is now
-    // the only reader of its own 16 rows of the K and V slabs, so it swaps them in place: nothing
-    // is read from global memory a second time.
-    if (active) {
-#pragma unroll
-        for (int c = 0; c < T::CH; ++c) {
-            f32x4* const pk = reinterpret_cast<f32x4*>(sa + (16 * role + n) * T::RS + 16 * c + 4 * g);
-            f32x4* const pv = reinterpret_cast<f32x4*>(sb + (16 * role + n) * T::RS + 16 * c + 4 * g);
-            const f32x4 krow = *pk, vrow = *pv;
-            *pk = qv[c];
-            *pv = gv[c];
-            qv[c] = krow;
-            gv[c] = vrow;
-        }
-    }
-    __syncthreads();
-
-    // ---------------- pass 2: key block `role` ----------------
-    if (active) {
-        const int jb = role;
-        const f32x4 (&kv)[T::CH] = qv;
-        const f32x4 (&vv)[T::CH] = gv;
-        const uint32_t jcol = 16u * jb + n;
-        const bool valid = jcol < (uint32_t)L;
-        f32x4 av[T::CH], ak[T::CH];  // dV, dK [16 jb + n][16 cb + 4g + r]
-#pragma unroll
-        for (int cb = 0; cb < T::CH; ++cb) av[cb] = ak[cb] = zero;
-#pragma unroll
-        for (int qb = 0; qb < NB; ++qb) {
-            // S = Q K^T and dP = dO V^T with the query on the slot: sc[r] = <q_i, k_j>, i = 16 qb + 4g + r, j = jcol
-            f32x4 sc = zero, dp = zero;
-#pragma unroll
-            for (int c = 0; c < T::CH; ++c) {
-                const f32x4 xq = *reinterpret_cast<const f32x4*>(sa + (16 * qb + n) * T::RS + 16 * c + 4 * g);
-                const f32x4 xg = *reinterpret_cast<const f32x4*>(sb + (16 * qb + n) * T::RS + 16 * c + 4 * g);
-#pragma unroll
-                for (int t = 0; t < 4; ++t) {
-                    const float a = xq[t], b = kv[c][t], a2 = xg[t], b2 = vv[c][t];
-                    sc = mfma_f32(a, b, sc);
-                    dp = mfma_f32(a2, b2, dp);
-                }
-            }
-            const f32x4 M4 = *reinterpret_cast<const f32x4*>(stM + 16 * qb + 4 * g);
-            const f32x4 D4 = *reinterpret_cast<const f32x4*>(stD + 16 * qb + 4 * g);
-            f32x4 pr, ds, mk = zero;
-            if (BM) mk = mask_rows4(msk, (uint32_t)(16 * qb + 4 * g), jcol, (uint32_t)L);  // rows beyond L: outside, zero
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                float x = sc[r] * p.scale;
-                if (BM) x += bias_elem(rb, (uint32_t)(16 * qb + 4 * g + r) * L + jcol) + mk[r];
-                pr[r] = valid ? __builtin_amdgcn_exp2f((x - M4[r]) * kLog2e) : 0.f;
-                ds[r] = pr[r] * (dp[r] - D4[r]);
-            }
-            // dV^T += dO^T P, dK^T += Q^T dS: k-slot g of step r stands for query 16 qb + 4g + r
-#pragma unroll
-            for (int cb = 0; cb < T::CH; ++cb)
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const float pp = pr[r], dd = ds[r];
-                    av[cb] = mfma_f32(sb[(16 * qb + 4 * g + r) * T::RS + 16 * cb + n], pp, av[cb]);
-                    ak[cb] = mfma_f32(sa[(16 * qb + 4 * g + r) * T::RS + 16 * cb + n], dd, ak[cb]);
-                }
-        }
-        const __amdgpu_buffer_rsrc_t rdv = make_rsrc((char*)p.dv + tile_d, tile_bytes_d);
-        const __amdgpu_buffer_rsrc_t rdk = make_rsrc((char*)p.dk + tile_d, tile_bytes_d);
-        const uint32_t off_k = (uint32_t)(16 * jb + n) * row_d + 16u * g;
-#pragma unroll
-        for (int cb = 0; cb < T::CH; ++cb) {
-            store_f32x4(av[cb], rdv, off_k + 64 * cb);
-            store_f32x4(ak[cb] * p.scale, rdk, off_k + 64 * cb);
-        }
-    }
-}
-
-// Backward for widths 32 and 64: P and dS of a query block go through LDS tiles instead of being
-// made a second time.  The fp32 matrix instruction takes single values, so any orientation can be
-// read out of a row-major tile: pass 1 leaves P[i][j] and dS[i][j] (16-byte writes of a lane's 4
-// consecutive keys), pass 2 reads them with the query on the slot and the key on the lane.  Pass 2
-// then needs no K, V rows and no statistics, only the Q and dO slabs, which the waves write from the
-// operand registers of pass 1.  10 instead of 14 L^2 D flops per tile on the unit that bounds these
-// kernels; the two tiles (34 KB) do not fit beside the slabs of width 256, and at width 128 they
-// would leave one workgroup per CU.
-constexpr int kTileStrideF32 = 68;  // floats per tile row: rows 4 apart fall 16 banks apart
-template <int NB, int D, bool BM>
-__global__ void __launch_bounds__(256) bwd_f32_exchange_kernel(BwdArgs p) {
-    using T = F32Tile<D>;
-    constexpr int ROWS = 16 * NB;
     constexpr int TS = kTileStrideF32;
-    extern __shared__ __attribute__((aligned(16))) float ldsf[];  // two slabs [ROWS][RS], then P, dS tiles [ROWS][TS]
+    static_assert(TS <= T::RS || D == 32, "a tile must fit into a slab");
+    extern __shared__ __attribute__((aligned(16))) float ldsf[];  // two slabs [ROWS][max(RS, TS)]
+    constexpr int SLAB = ROWS * (T::RS > TS ? T::RS : TS);
     const int tid = threadIdx.x, lane = tid & 63;
     const int n = lane & 15, g = lane >> 4;
-    const int role = __builtin_amdgcn_readfirstlane(tid >> 6);  // query block in pass 1, key block in pass 2
+    const int role = __builtin_amdgcn_readfirstlane(tid >> 6);  // query block in pass 1, key block afterwards
     const bool active = role < NB;
     const uint32_t w = blockIdx.x / (uint32_t)p.heads, h = blockIdx.x % (uint32_t)p.heads;
     const int L = p.L;
@@ -379,10 +218,8 @@ __global__ void __launch_bounds__(256) bwd_f32_exchange_kernel(BwdArgs p) {
     const __amdgpu_buffer_rsrc_t rk = make_rsrc((const char*)p.k + tile, tile_bytes);
     const __amdgpu_buffer_rsrc_t rv = make_rsrc((const char*)p.v + tile, tile_bytes);
     const __amdgpu_buffer_rsrc_t rg = make_rsrc((const char*)p.d_o + tile_g, tile_bytes_g);
-    float* const sa = ldsf;                   // K, then Q
-    float* const sb = ldsf + ROWS * T::RS;    // V, then dO
-    float* const tp = ldsf + 2 * ROWS * T::RS;
-    float* const td = tp + ROWS * TS;
+    float* const sa = ldsf;         // K, then the P tile, then the dS tile
+    float* const sb = ldsf + SLAB;  // V, then dO, then Q
     const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
 
     f32x4 qv[T::CH], gv[T::CH];  // own Q and dO rows (rows beyond L arrive as zeros)
@@ -393,6 +230,7 @@ __global__ void __launch_bounds__(256) bwd_f32_exchange_kernel(BwdArgs p) {
     __syncthreads();
 
     // ---------------- pass 1: query block `role` ----------------
+    f32x4 s[NB], dp[NB];
     if (active) {
         const int qb = role;
         BiasSrc rb = no_bias();
@@ -401,7 +239,6 @@ __global__ void __launch_bounds__(256) bwd_f32_exchange_kernel(BwdArgs p) {
             rb = bias_of_head(p, h);
             msk = mask_of_window(p, w);
         }
-        f32x4 s[NB], dp[NB];
 #pragma unroll
         for (int jb = 0; jb < NB; ++jb) s[jb] = dp[jb] = zero;
         rows_times_own<NB, D>(s, sa, qv, n, g);   // <k_j, q_i>: query i = 16 qb + n, key j = 16 jb + 4g + r
@@ -418,12 +255,9 @@ __global__ void __launch_bounds__(256) bwd_f32_exchange_kernel(BwdArgs p) {
             }
         delta = sum_over_g(delta);
 #pragma unroll
-        for (int jb = 0; jb < NB; ++jb) {
+        for (int jb = 0; jb < NB; ++jb)
 #pragma unroll
             for (int r = 0; r < 4; ++r) dp[jb][r] = s[jb][r] * (dp[jb][r] - delta);  // dS
-            *reinterpret_cast<f32x4*>(tp + (16 * qb + n) * TS + 16 * jb + 4 * g) = s[jb];
-            *reinterpret_cast<f32x4*>(td + (16 * qb + n) * TS + 16 * jb + 4 * g) = dp[jb];
-        }
         // dQ^T = K^T dS^T, 16 channels at a time: k-slot g of step (jb, r) stands for key 16 jb + 4g + r
         const __amdgpu_buffer_rsrc_t rdq = make_rsrc((char*)p.dq + tile_d, tile_bytes_d);
         const uint32_t off_q = (uint32_t)(16 * qb + n) * row_d + 16u * g;
@@ -440,51 +274,42 @@ __global__ void __launch_bounds__(256) bwd_f32_exchange_kernel(BwdArgs p) {
             store_f32x4(acc * p.scale, rdq, off_q + 64 * cb);  // acc[r'] = dQ[16 qb + n][16 cb + 4g + r']
         }
     }
-    __syncthreads();  // K, V no longer needed; the tiles are complete
-    // the Q and dO slabs take the place of K and V, written from the operand registers
-    if (active) {
+    const uint32_t off_k = (uint32_t)(16 * role + n) * row_d + 16u * g;
+    // out[16 role + n][:] = sum over queries of tile[query][16 role + n] * slab B[query][:], times `mul`
+    auto contract_and_store = [&](const __amdgpu_buffer_rsrc_t dst, float mul) {
+        f32x4 acc[T::CH];
 #pragma unroll
-        for (int c = 0; c < T::CH; ++c) {
-            *reinterpret_cast<f32x4*>(sa + (16 * role + n) * T::RS + 16 * c + 4 * g) = qv[c];
-            *reinterpret_cast<f32x4*>(sb + (16 * role + n) * T::RS + 16 * c + 4 * g) = gv[c];
-        }
-    }
-    __syncthreads();
-
-    // ---------------- pass 2: key block `role` ----------------
-    if (active) {
-        const int jb = role;
-        f32x4 av[T::CH], ak[T::CH];  // dV, dK [16 jb + n][16 cb + 4g + r]
-#pragma unroll
-        for (int cb = 0; cb < T::CH; ++cb) av[cb] = ak[cb] = zero;
+        for (int cb = 0; cb < T::CH; ++cb) acc[cb] = zero;
 #pragma unroll
         for (int qb = 0; qb < NB; ++qb) {
-            // P and dS with the query on the slot: pr[r] = P[16 qb + 4g + r][16 jb + n]
-            f32x4 pr, ds;
+            f32x4 t;  // the tile with the query on the slot: t[r] = tile[16 qb + 4g + r][16 role + n]
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                pr[r] = tp[(16 * qb + 4 * g + r) * TS + 16 * jb + n];
-                ds[r] = td[(16 * qb + 4 * g + r) * TS + 16 * jb + n];
-            }
-            // dV^T += dO^T P, dK^T += Q^T dS: k-slot g of step r stands for query 16 qb + 4g + r
+            for (int r = 0; r < 4; ++r) t[r] = sa[(16 * qb + 4 * g + r) * TS + 16 * role + n];
 #pragma unroll
             for (int cb = 0; cb < T::CH; ++cb)
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
-                    const float pp = pr[r], dd = ds[r];
-                    av[cb] = mfma_f32(sb[(16 * qb + 4 * g + r) * T::RS + 16 * cb + n], pp, av[cb]);
-                    ak[cb] = mfma_f32(sa[(16 * qb + 4 * g + r) * T::RS + 16 * cb + n], dd, ak[cb]);
+                    const float tv = t[r];
+                    acc[cb] = mfma_f32(sb[(16 * qb + 4 * g + r) * T::RS + 16 * cb + n], tv, acc[cb]);
                 }
         }
-        const __amdgpu_buffer_rsrc_t rdv = make_rsrc((char*)p.dv + tile_d, tile_bytes_d);
-        const __amdgpu_buffer_rsrc_t rdk = make_rsrc((char*)p.dk + tile_d, tile_bytes_d);
-        const uint32_t off_k = (uint32_t)(16 * jb + n) * row_d + 16u * g;
 #pragma unroll
-        for (int cb = 0; cb < T::CH; ++cb) {
-            store_f32x4(av[cb], rdv, off_k + 64 * cb);
-            store_f32x4(ak[cb] * p.scale, rdk, off_k + 64 * cb);
-        }
-    }
+        for (int cb = 0; cb < T::CH; ++cb) store_f32x4(acc[cb] * mul, dst, off_k + 64 * cb);
+    };
+    auto place = [&](const f32x4 (&rows)[T::CH], const f32x4 (&tile_rows)[NB]) {
+#pragma unroll
+        for (int c = 0; c < T::CH; ++c) *reinterpret_cast<f32x4*>(sb + (16 * role + n) * T::RS + 16 * c + 4 * g) = rows[c];
+#pragma unroll
+        for (int jb = 0; jb < NB; ++jb) *reinterpret_cast<f32x4*>(sa + (16 * role + n) * TS + 16 * jb + 4 * g) = tile_rows[jb];
+    };
+    __syncthreads();  // K, V no longer needed
+    if (active) place(gv, s);  // dO rows and P rows of this wave's query block
+    __syncthreads();
+    if (active) contract_and_store(make_rsrc((char*)p.dv + tile_d, tile_bytes_d), 1.0f);  // dV^T = dO^T P
+    __syncthreads();  // dO and P no longer needed
+    if (active) place(qv, dp);  // Q rows and dS rows
+    __syncthreads();
+    if (active) contract_and_store(make_rsrc((char*)p.dk + tile_d, tile_bytes_d), p.scale);  // dK^T = Q^T dS
 }
 
 template <int NB, int D>
@@ -514,33 +339,19 @@ template <int NB, int D>
 hipError_t launch_bwd_nb(const BwdArgs& a, hipStream_t st) {
     const unsigned grid = (unsigned)(a.N * a.heads);
     const bool bm = a.bias || has_mask(a);
-    if constexpr (D <= 64) {  // P and dS exchanged through LDS tiles
-        const size_t lds = f32_slab_bytes<NB, D>() + (size_t)2 * 16 * NB * kTileStrideF32 * 4;
-        const void* fn = bm ? reinterpret_cast<const void*>(&bwd_f32_exchange_kernel<NB, D, true>)
-                            : reinterpret_cast<const void*>(&bwd_f32_exchange_kernel<NB, D, false>);
-        if (lds > 64 * 1024) {
-            const hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-            if (e != hipSuccess) return e;
-        }
-        if (bm)
-            hipLaunchKernelGGL((bwd_f32_exchange_kernel<NB, D, true>), dim3(grid), dim3(256), lds, st, a);
-        else
-            hipLaunchKernelGGL((bwd_f32_exchange_kernel<NB, D, false>), dim3(grid), dim3(256), lds, st, a);
-        return hipGetLastError();
-    } else {
-        const size_t lds = f32_slab_bytes<NB, D>() + (size_t)2 * 16 * NB * 4;
-        const void* fn = bm ? reinterpret_cast<const void*>(&bwd_f32_tile_kernel<NB, D, true>)
-                            : reinterpret_cast<const void*>(&bwd_f32_tile_kernel<NB, D, false>);
-        if (lds > 64 * 1024) {
-            const hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-            if (e != hipSuccess) return e;
-        }
-        if (bm)
-            hipLaunchKernelGGL((bwd_f32_tile_kernel<NB, D, true>), dim3(grid), dim3(256), lds, st, a);
-        else
-            hipLaunchKernelGGL((bwd_f32_tile_kernel<NB, D, false>), dim3(grid), dim3(256), lds, st, a);
-        return hipGetLastError();
+    constexpr size_t rs = (D + 4) > kTileStrideF32 ? (D + 4) : kTileStrideF32;  // a slab also holds a tile
+    const size_t lds = (size_t)2 * 16 * NB * rs * 4;
+    const void* fn = bm ? reinterpret_cast<const void*>(&bwd_f32_tile_kernel<NB, D, true>)
+                        : reinterpret_cast<const void*>(&bwd_f32_tile_kernel<NB, D, false>);
+    if (lds > 64 * 1024) {
+        const hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
     }
+    if (bm)
+        hipLaunchKernelGGL((bwd_f32_tile_kernel<NB, D, true>), dim3(grid), dim3(256), lds, st, a);
+    else
+        hipLaunchKernelGGL((bwd_f32_tile_kernel<NB, D, false>), dim3(grid), dim3(256), lds, st, a);
+    return hipGetLastError();
 }
 
 #define FWA_F32_NB_SWITCH(FN, D, a, s)            \
