@@ -90,10 +90,11 @@ int fwa_forward_strided(const void* q, const void* k, const void* v, void* o,
  *   dbias      : NULL, or out [heads, L, L] fp32 = sum over all N windows of
  *                dS; overwritten, not accumulated.  The mask gets no gradient.
  *   workspace  : device scratch of at least fwa_backward_workspace_bytes(...)
- *                bytes, 16-byte aligned; may be NULL when that size is 0 (it is
- *                0 unless dbias is wanted: it holds per-workgroup partial sums
- *                of dbias and, for L > 64, the softmax statistics of every
- *                row).  Contents on entry are ignored and undefined on exit.
+ *                bytes, 16-byte aligned.  It holds per-workgroup partial sums
+ *                of dbias and, for L > 64, the softmax statistics of every row
+ *                and the fp32 copy of a bf16 bias (fwa_backward_labels).  It
+ *                may be NULL when dbias is NULL, unless L > 64 and the bias is
+ *                bf16.  Contents on entry are ignored and undefined on exit.
  * Results are bit-reproducible from run to run for fixed arguments.
  */
 int fwa_backward(const void* q, const void* k, const void* v, const void* d_o,
@@ -143,8 +144,10 @@ int fwa_backward_labels(const void* q, const void* k, const void* v, const void*
                         const void* bias, int bias_dtype, const int32_t* labels, float mask_value, int nW,
                         int dtype, void* workspace, size_t workspace_bytes, void* stream);
 
-/* Bytes of workspace fwa_backward needs for these arguments (0 if none).
- * Returns 0 for arguments fwa_backward would reject. */
+/* Bytes of workspace that suffice for any backward call with these arguments
+ * (0 if none is needed; for L > 64 the size includes room for the fp32 copy of
+ * a bf16 bias whether or not one will be passed).  Returns 0 for arguments
+ * fwa_backward would reject. */
 size_t fwa_backward_workspace_bytes(int64_t N, int L, int C, int heads, int dtype, int want_dbias);
 
 /*

@@ -253,7 +253,8 @@ def fwa_backward(q, k, v, d_o, heads: int, scale: float, bias=None, mask=None, w
     if bias_code == FWA_BF16 and mask is not None:
         raise ValueError("a bf16 bias goes with a mask given as labels (or with no mask), not with a dense mask")
     need = fwa_backward_workspace_bytes(N, L, C, heads, _dtype_code(q), want_dbias)
-    if workspace is None and need:
+    # needed for dBias, and above 64 tokens for the fp32 copy the library makes of a bf16 bias
+    if workspace is None and need and (want_dbias or (bias_code == FWA_BF16 and L > 64)):
         workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     tail = (bp, _dev_ptr(mask, "mask", f32=True), nW, _dtype_code(q),

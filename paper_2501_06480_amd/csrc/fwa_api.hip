@@ -35,6 +35,13 @@ size_t large_stats_bytes(int64_t N, int L, int heads) {
     return (size_t)N * heads * 2 * 16 * nb * sizeof(float);
 }
 
+// fp32 copy of a bf16 bias for the large-window backward, which reads the bias once per window and
+// query block (a copy made once per call costs less than widening it at every use): [heads, L, L]
+// floats, rounded up to 256 bytes
+size_t large_bias_copy_bytes(int L, int heads) {
+    return (((size_t)heads * L * L * sizeof(float)) + 255) & ~(size_t)255;
+}
+
 // Row stride of a strided tensor, in elements: at least C, rows 16-byte aligned, and small enough
 // that the byte offsets inside one window fit 32 bits with room to spare.
 int check_row_stride(int64_t ld, int C, int dtype) {
@@ -128,11 +135,17 @@ int fwa_forward(const void* q, const void* k, const void* v, void* o, int64_t N,
 size_t fwa_backward_workspace_bytes(int64_t N, int L, int C, int heads, int dtype, int want_dbias) {
     if (check_shape(N, L, C, heads, dtype, true) != FWA_OK || check_backward_support(L, dtype, want_dbias != 0) != FWA_OK)
         return 0;
-    if (!want_dbias || N == 0) return 0;
+    if (N == 0) return 0;
     // the slot count depends on the mask period; this is its upper bound over all periods
     const size_t nb = (size_t)(L + 15) / 16;  // partial sums are kept per 16 x 16 block, padded
-    if (L > fwa::kMaxBackwardL)
-        return large_stats_bytes(N, L, heads) + (size_t)fwa::backward_large_slots(N, heads, L) * heads * nb * nb * 256 * sizeof(float);
+    if (L > fwa::kMaxBackwardL) {
+        // room for the fp32 copy of a bf16 bias whether or not the call will pass one
+        const size_t copy = large_bias_copy_bytes(L, heads);
+        if (!want_dbias) return copy;
+        return copy + large_stats_bytes(N, L, heads) +
+               (size_t)fwa::backward_large_slots(N, heads, L) * heads * nb * nb * 256 * sizeof(float);
+    }
+    if (!want_dbias) return 0;
     return (size_t)fwa::backward_max_slots(N, heads) * heads * nb * nb * 256 * sizeof(float);
 }
 
@@ -195,16 +208,30 @@ int backward_impl(const void* q, const void* k, const void* v, const void* d_o, 
         for (int b = a + 1; b < 3; ++b)
             if (outs[a] == outs[b]) return FWA_ERR_ALIAS;
     }
-    const size_t need = fwa_backward_workspace_bytes(N, L, C, heads, dtype, dbias != nullptr);
+    // workspace: [fp32 copy of a bf16 bias (large windows only)] [row statistics (large windows
+    // with dBias)] [partial sums of dBias]; a call needs the parts it uses
+    const bool large = L > fwa::kMaxBackwardL;
+    const bool copy_bias = large && bias && bias_dtype == FWA_BF16;
+    const size_t full = fwa_backward_workspace_bytes(N, L, C, heads, dtype, dbias != nullptr);
+    const size_t copy_room = large ? large_bias_copy_bytes(L, heads) : 0;
+    const size_t need = (dbias ? full - copy_room : 0) + (copy_bias ? copy_room : 0);
     if (need > 0 && (workspace == nullptr || workspace_bytes < need)) return FWA_ERR_WORKSPACE;
+    char* ws = static_cast<char*>(workspace);
+    if (copy_bias) {
+        if (fwa::launch_widen_bf16(bias, reinterpret_cast<float*>(ws), (size_t)heads * L * L, st) != hipSuccess)
+            return FWA_ERR_LAUNCH;
+        bias = ws;
+        bias_dtype = FWA_F32;
+        ws += copy_room;
+    }
     fwa::BwdArgs a;
     a.q = q; a.k = k; a.v = v; a.d_o = d_o;
     a.dq = dq; a.dk = dk; a.dv = dv; a.dbias = dbias;
-    a.partial = dbias ? static_cast<float*>(workspace) : nullptr;
+    a.partial = dbias ? reinterpret_cast<float*>(ws) : nullptr;
     a.stats = nullptr;
-    if (dbias && L > fwa::kMaxBackwardL) {  // workspace = [row statistics][partial sums]
-        a.stats = static_cast<float*>(workspace);
-        a.partial = reinterpret_cast<float*>(static_cast<char*>(workspace) + large_stats_bytes(N, L, heads));
+    if (dbias && large) {  // [row statistics][partial sums]
+        a.stats = reinterpret_cast<float*>(ws);
+        a.partial = reinterpret_cast<float*>(ws + large_stats_bytes(N, L, heads));
     }
     a.bias = bias; a.bias_bf16 = bias && bias_dtype == FWA_BF16;
     a.mask = mask; a.labels = labels; a.mask_value = mask_value;

@@ -48,7 +48,7 @@ __device__ __forceinline__ bf16x8 pair_operand(bf16x4 a, bf16x4 b) {
     return as_bf16x8(u32x4{ua.x, ua.y, ub.x, ub.y});
 }
 
-// HB: no bias (0), an fp32 bias (1) or a bf16 bias (2); HM: no mask (0), a dense mask (1), or region
+// HB: no bias (0) or an fp32 bias (1; a bf16 bias arrives as an fp32 copy made once per call); HM: no mask (0), a dense mask (1), or region
 // labels from which the mask values are formed in registers (2).  What is absent costs neither
 // loads nor registers.
 template <int NB, int HB, int HM>
@@ -86,11 +86,6 @@ __global__ void __launch_bounds__(64 * large_waves(NB)) bwd_bf16_large_kernel(Bw
     const float* const bias32 = static_cast<const float*>(p.bias);
     const __amdgpu_buffer_rsrc_t rb =
         HB == 1 ? make_rsrc(bias32 + (size_t)h * L * L, ll) : make_rsrc(nullptr, 0);
-    // a bf16 bias is addressed from the (dword aligned) start of the whole tensor: a head's tile may
-    // begin at an odd element
-    const __amdgpu_buffer_rsrc_t rbt =
-        HB == 2 ? make_rsrc(p.bias, ((uint32_t)p.heads * L * L * 2u + 3u) & ~3u) : make_rsrc(nullptr, 0);  // whole dwords
-    const uint32_t hbase = h * (uint32_t)L * (uint32_t)L;
 
     const uint32_t srow = (uint32_t)tid >> 2, scol = (uint32_t)tid & 3u;  // slab movement: (row, 16 B column)
     const uint32_t tile_bytes = (uint32_t)(L - 1) * row_bytes + 2u * kHeadDim;
@@ -161,8 +156,6 @@ __global__ void __launch_bounds__(64 * large_waves(NB)) bwd_bf16_large_kernel(Bw
                 for (int t = 0; t < 4; ++t) {
                     const uint32_t off = ((uint32_t)(4 * t + prow) * L + pcol) * 4u + 256u * ch;
                     if (HB == 1) tb[slot][t] = load_f32x4(rbq, off);
-                    // bf16: 16 bytes from the dword that holds the first of the 4 elements
-                    if (HB == 2) tb[slot][t] = load_f32x4(rbt, (2u * (hbase + (uint32_t)(16 * qb) * L) + (off >> 1)) & ~3u);
                     if (HM == 1) tm[slot][t] = load_f32x4(rmq, off);
                 }
                 if (HM == 2) tk[slot] = load_i32x4(rl, (pcol + 64u * ch) * 4u);
@@ -181,9 +174,7 @@ __global__ void __launch_bounds__(64 * large_waves(NB)) bwd_bf16_large_kernel(Bw
 #pragma unroll
                     for (int t = 0; t < 4; ++t) {
                         const f32x4 mk = HM == 2 ? mask_of_labels(tq[t], tk[cur], p.mask_value) : tm[cur][t];
-                        // the columns pcol + 64 ch are even: the quad starts on an odd element iff its row does
-                        const f32x4 bq = HB == 2 ? bf16_quad(tb[cur][t], ((hbase + (uint32_t)(16 * qb + 4 * t + prow) * L) & 1u) != 0)
-                                                 : tb[cur][t];
+                        const f32x4 bq = tb[cur][t];
                         *reinterpret_cast<f32x4*>(patch + (4 * t + prow) * SG + pcol) =
                             (HB && HM ? bq + mk : (HB ? bq : mk)) * kLog2e;
                     }
@@ -307,11 +298,6 @@ __global__ void __launch_bounds__(64 * large_waves(NB)) bwd_bf16_large_kernel(Bw
             uint32_t aoff[4];
 #pragma unroll
             for (int r = 0; r < 4; ++r) aoff[r] = ((uint32_t)(4 * g + r) * L + jcol) * 4u;
-            // bf16 bias: the descriptor of a query block starts at an even element of the tensor
-            // (a dword), the parity of the head's first element goes into the lane offsets
-            uint32_t aoff16[4];
-#pragma unroll
-            for (int r = 0; r < 4; ++r) aoff16[r] = (aoff[r] >> 1) + 2u * (hbase & 1u);
             bf16x8 oq[2][2], og[2][2], tg0[2], tg1[2], tx0[2], tx1[2];
             f32x4 oM[2][2], oD[2][2], ab[2][2], am[2][2];
             i32x4 al[2][2];
@@ -341,15 +327,11 @@ __global__ void __launch_bounds__(64 * large_waves(NB)) bwd_bf16_large_kernel(Bw
                     if (u == 1 && 2 * qp + 1 >= NB) break;
                     const uint32_t qrow = (uint32_t)(16 * (2 * qp + u)) * L;
                     const __amdgpu_buffer_rsrc_t rbq = HB == 1 ? make_rsrc(bias32 + (size_t)h * L * L + qrow, ll - 4u * qrow) : rb;
-                    const uint32_t e0 = (hbase + qrow) & ~1u;
-                    const __amdgpu_buffer_rsrc_t rbq16 =
-                        HB == 2 ? make_rsrc(static_cast<const char*>(p.bias) + 2u * (size_t)e0, ((uint32_t)p.heads * L * L - e0) * 2u) : rb;
                     const __amdgpu_buffer_rsrc_t rmq =
                         HM == 1 ? make_rsrc(p.mask + (size_t)(w % (uint32_t)p.nW) * L * L + qrow, ll - 4u * qrow) : rb;
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
                         if (HB == 1) ab[slot][u][r] = load_f32(rbq, aoff[r]);
-                        if (HB == 2) ab[slot][u][r] = load_u16_bits(rbq16, aoff16[r]);  // raw; widened where it is used
                         if (HM == 1) am[slot][u][r] = load_f32(rmq, aoff[r]);
                     }
                     // with labels: those of the 4 query rows, compared with the key's where the term is used
@@ -383,8 +365,7 @@ __global__ void __launch_bounds__(64 * large_waves(NB)) bwd_bf16_large_kernel(Bw
                         float x;
                         if (BM) {
                             const float mk = HM == 2 ? (al[cur][u][r] == lkey ? 0.f : p.mask_value) : am[cur][u][r];
-                            const float braw = ab[cur][u][r];
-                            const float bv = HB == 2 ? widen_bf16_bits(braw) : braw;
+                            const float bv = ab[cur][u][r];
                             const float add = HB && HM ? bv + mk : (HB ? bv : mk);
                             x = fmaf(sc[u][r], sl2, fmaf(add, kLog2e, -oM[cur][u][r]));
                         }
@@ -518,10 +499,6 @@ __global__ void __launch_bounds__(64 * large_waves(NB)) dbias_large_kernel(BwdAr
                 uint32_t aoff[4];
 #pragma unroll
                 for (int r = 0; r < 4; ++r) aoff[r] = ((uint32_t)(4 * g + r) * L + jcol) * 4u;
-                const uint32_t hbase = h * (uint32_t)L * (uint32_t)L;
-                uint32_t aoff16[4];  // bf16 bias: see the main kernel
-#pragma unroll
-                for (int r = 0; r < 4; ++r) aoff16[r] = (aoff[r] >> 1) + 2u * (hbase & 1u);
                 bf16x8 oq[2][2], og[2][2];
                 f32x4 oM[2][2], oD[2][2], ab[2][2], am[2][2];
                 i32x4 al[2][2];
@@ -540,17 +517,12 @@ __global__ void __launch_bounds__(64 * large_waves(NB)) dbias_large_kernel(BwdAr
                             const __amdgpu_buffer_rsrc_t rbq =
                                 HB == 1 ? make_rsrc(static_cast<const float*>(p.bias) + (size_t)h * L * L + qrow, ll - 4u * qrow)
                                         : make_rsrc(nullptr, 0);
-                            const uint32_t e0 = (hbase + qrow) & ~1u;
-                            const __amdgpu_buffer_rsrc_t rbq16 =
-                                HB == 2 ? make_rsrc(static_cast<const char*>(p.bias) + 2u * (size_t)e0, ((uint32_t)p.heads * L * L - e0) * 2u)
-                                        : make_rsrc(nullptr, 0);
                             const __amdgpu_buffer_rsrc_t rmq =
                                 HM == 1 ? make_rsrc(p.mask + (size_t)(w % (uint32_t)p.nW) * L * L + qrow, ll - 4u * qrow)
                                         : make_rsrc(nullptr, 0);
 #pragma unroll
                             for (int r = 0; r < 4; ++r) {
                                 if (HB == 1) ab[slot][u][r] = load_f32(rbq, aoff[r]);
-                                if (HB == 2) ab[slot][u][r] = load_u16_bits(rbq16, aoff16[r]);
                                 if (HM == 1) am[slot][u][r] = load_f32(rmq, aoff[r]);
                             }
                             if (HM == 2) al[slot][u] = load_i32x4(rl, (uint32_t)(16 * qb + 4 * g) * 4u);
@@ -573,8 +545,7 @@ __global__ void __launch_bounds__(64 * large_waves(NB)) dbias_large_kernel(BwdAr
                             float x;
                             if (BM) {
                                 const float mk = HM == 2 ? (al[cur][u][r] == lkey ? 0.f : p.mask_value) : am[cur][u][r];
-                                const float braw = ab[cur][u][r];
-                                const float bv = HB == 2 ? widen_bf16_bits(braw) : braw;
+                                const float bv = ab[cur][u][r];
                                 const float add = HB && HM ? bv + mk : (HB ? bv : mk);
                                 x = fmaf(sc[r], sl2, fmaf(add, kLog2e, -oM[cur][u][r]));
                             } else {
@@ -666,10 +637,7 @@ hipError_t launch_large_both(const BwdArgs& a, hipStream_t st) {
 
 template <int NB>
 hipError_t launch_large_nb(const BwdArgs& a, hipStream_t st) {
-    if (a.bias && a.bias_bf16) {
-        if (a.labels) return launch_large_both<NB, 2, 2>(a, st);
-        return a.mask ? launch_large_both<NB, 2, 1>(a, st) : launch_large_both<NB, 2, 0>(a, st);
-    }
+    if (a.bias && a.bias_bf16) return hipErrorInvalidValue;  // the caller hands over an fp32 copy
     if (a.bias) {
         if (a.labels) return launch_large_both<NB, 1, 2>(a, st);
         return a.mask ? launch_large_both<NB, 1, 1>(a, st) : launch_large_both<NB, 1, 0>(a, st);

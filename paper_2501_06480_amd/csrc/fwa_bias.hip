@@ -46,7 +46,20 @@ __global__ void zero_f32_kernel(float* __restrict__ dst, size_t count) {
         dst[e] = 0.f;
 }
 
+// bf16 -> fp32 (exact: the 16 bits become the upper half of the word)
+__global__ void widen_bf16_kernel(const uint16_t* __restrict__ src, float* __restrict__ dst, size_t count) {
+    for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < count; e += (size_t)gridDim.x * blockDim.x)
+        dst[e] = __builtin_bit_cast(float, (uint32_t)src[e] << 16);
+}
+
 }  // namespace
+
+hipError_t launch_widen_bf16(const void* src, float* dst, size_t count, hipStream_t s) {
+    const size_t blocks = (count + 255) / 256;
+    hipLaunchKernelGGL(widen_bf16_kernel, dim3((unsigned)(blocks > 1024 ? 1024 : blocks)), dim3(256), 0, s,
+                       static_cast<const uint16_t*>(src), dst, count);
+    return hipGetLastError();
+}
 
 // A fill kernel rather than a memset node, so that callers may capture it in a graph.
 hipError_t launch_zero_f32(float* dst, size_t count, hipStream_t s) {

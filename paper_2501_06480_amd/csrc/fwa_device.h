@@ -65,14 +65,6 @@ __device__ __forceinline__ float load_f32(__amdgpu_buffer_rsrc_t r, uint32_t vof
 __device__ __forceinline__ float load_bf16(__amdgpu_buffer_rsrc_t r, uint32_t voffset) {
     return __builtin_bit_cast(float, (uint32_t)(uint16_t)__builtin_amdgcn_raw_buffer_load_b16(r, voffset, 0, 0) << 16);
 }
-// the same in two steps, for loads that are issued well ahead of their use: the 16 bits as they
-// come (in the low half of a register, carried in a float variable), widened to fp32 later
-__device__ __forceinline__ float load_u16_bits(__amdgpu_buffer_rsrc_t r, uint32_t voffset) {
-    return __builtin_bit_cast(float, (uint32_t)(uint16_t)__builtin_amdgcn_raw_buffer_load_b16(r, voffset, 0, 0));
-}
-__device__ __forceinline__ float widen_bf16_bits(float bits) {
-    return __builtin_bit_cast(float, __builtin_bit_cast(uint32_t, bits) << 16);
-}
 __device__ __forceinline__ i32x4 load_i32x4(__amdgpu_buffer_rsrc_t r, uint32_t voffset) {
     return __builtin_bit_cast(i32x4, __builtin_amdgcn_raw_buffer_load_b128(r, voffset, 0, 0));
 }

@@ -89,6 +89,7 @@ int backward_wide_slots(long long N, int heads);
 hipError_t launch_dbias_reduce(const BwdArgs& a, hipStream_t s, bool key_on_lane = false);
 int backward_large_slots(long long N, int heads, int L);
 hipError_t launch_zero_f32(float* dst, size_t count, hipStream_t s);
+hipError_t launch_widen_bf16(const void* src, float* dst, size_t count, hipStream_t s);
 hipError_t launch_bias_gather(const float* table, float* bias, int heads, int k, hipStream_t s);
 hipError_t launch_bias_scatter(const float* dbias, float* dtable, int heads, int k, hipStream_t s);
 

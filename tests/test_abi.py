@@ -159,3 +159,20 @@ def test_label_entry_points_check_their_arguments(lib):
     assert bwd(bias=P + 0x7000, bias_dtype=3) == b.FWA_ERR_UNSUPPORTED
     # a mask period too long for the cooperative kernel leaves the one-wave kernel, which takes fp32 biases only
     assert bwd(bias=P + 0x7000, bias_dtype=1, N=64, nW=64, heads=24) == b.FWA_ERR_UNSUPPORTED
+
+
+def test_large_window_backward_needs_a_workspace_for_a_bf16_bias(lib):
+    """Above 64 tokens the backward works on an fp32 copy of a bf16 bias, which lives in the workspace:
+    the size query always leaves room for it, and a call that passes a bf16 bias without a workspace
+    is turned away before anything is launched."""
+    from paper_2501_06480_amd import binding as b
+    L, heads = 144, 4
+    room = (heads * L * L * 4 + 255) // 256 * 256
+    assert lib.fwa_backward_workspace_bytes(16, L, 32 * heads, heads, 1, 0) == room
+    assert lib.fwa_backward_workspace_bytes(16, L, 32 * heads, heads, 1, 1) > room
+    assert lib.fwa_backward_workspace_bytes(16, 64, 32 * heads, heads, 1, 0) == 0
+    bwd = lambda bias_dtype, ws=None, ws_bytes=0: lib.fwa_backward_labels(
+        P, P + 0x1000, P + 0x2000, P + 0x3000, P + 0x4000, P + 0x5000, P + 0x6000, None, 16, L, 32 * heads, heads, 0.1,
+        32 * heads, 32 * heads, 32 * heads, P + 0x7000, bias_dtype, None, -100.0, 0, 1, ws, ws_bytes, None)
+    assert bwd(1) == b.FWA_ERR_WORKSPACE
+    assert bwd(1, P + 0x8000, room - 1) == b.FWA_ERR_WORKSPACE
