@@ -388,23 +388,26 @@ __global__ void __launch_bounds__(64 * 2 * QW) fwd_bf16_rowblock_kernel(FwdArgs 
             s[jb] = mfma_bf16(kop, qop, zero);  // S[16 qb + n][16 jb + 4g + r]
         }
         const AddendGlobal addend = addend_at(rb, msk, (uint32_t)(16 * qb + n), 4u * g, (uint32_t)L);
-        const float inv = softmax_block<NB, BM>(s, sl2, addend, L, g);
+        float mul, sum = 0.f;
+        const float mb = softmax_scale_max<NB, BM>(s, sl2, addend, L, g, mul);
         f32x4 o0 = {0.f, 0.f, 0.f, 0.f}, o1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int kp = 0; kp < NB2; ++kp) {
-            const bf16x8 pop = prob_operand<NB>(s, kp);
+            // the V operands of this pair of key blocks are requested before its exponentials
+            u32x4 v[2];
 #pragma unroll
             for (int c = 0; c < 2; ++c) {
                 const uint2 a = lds_read_tr(lvh + (32 * kp) * (stride * 8u) + 16 * c);
                 uint2 b = {0u, 0u};
                 if (2 * kp + 1 < NB) b = lds_read_tr(lvh + (32 * kp + 16) * (stride * 8u) + 16 * c);
-                const u32x4 v = {a.x, a.y, b.x, b.y};
-                if (c == 0)
-                    o0 = mfma_bf16(as_bf16x8(v), pop, o0);  // o0[r] = O[16 qb + n][4g + r]
-                else
-                    o1 = mfma_bf16(as_bf16x8(v), pop, o1);  // o1[r] = O[16 qb + n][16 + 4g + r]
+                v[c] = u32x4{a.x, a.y, b.x, b.y};
             }
+            softmax_exp_pair<NB>(s, kp, mul, mb, sum);
+            const bf16x8 pop = prob_operand<NB>(s, kp);
+            o0 = mfma_bf16(as_bf16x8(v[0]), pop, o0);  // o0[r] = O[16 qb + n][4g + r]
+            o1 = mfma_bf16(as_bf16x8(v[1]), pop, o1);  // o1[r] = O[16 qb + n][16 + 4g + r]
         }
+        const float inv = __builtin_amdgcn_rcpf(sum_over_g(sum));
         typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
         u32x2 lo, hi;
         lo.x = pack_bf16(o0[0] * inv, o0[1] * inv);
@@ -536,23 +539,26 @@ __global__ void __launch_bounds__(64 * HPB * rowpersist_waves(NB)) fwd_bf16_rowp
                 s[jb] = mfma_bf16(__builtin_bit_cast(bf16x8, lkh[16 * jb * STRIDE]), qop, zero);  // S[16 qb + n][16 jb + 4g + r]
             }
             const AddendRegs<NB> addend = {add};
-            const float inv = softmax_block<NB, true>(s, sl2, addend, L, g);
+            float mul, sum = 0.f;
+            const float mb = softmax_scale_max<NB, true>(s, sl2, addend, L, g, mul);
             f32x4 o0 = {0.f, 0.f, 0.f, 0.f}, o1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int kp = 0; kp < NB2; ++kp) {
-                const bf16x8 pop = prob_operand<NB>(s, kp);
+                // the V operands of this pair of key blocks are requested before its exponentials
+                u32x4 v[2];
 #pragma unroll
                 for (int c = 0; c < 2; ++c) {
                     const uint2 a = lds_read_tr(lvh + (32 * kp) * (STRIDE * 8u) + 16 * c);
                     uint2 b = {0u, 0u};
                     if (2 * kp + 1 < NB) b = lds_read_tr(lvh + (32 * kp + 16) * (STRIDE * 8u) + 16 * c);
-                    const u32x4 v = {a.x, a.y, b.x, b.y};
-                    if (c == 0)
-                        o0 = mfma_bf16(as_bf16x8(v), pop, o0);  // o0[r] = O[16 qb + n][4g + r]
-                    else
-                        o1 = mfma_bf16(as_bf16x8(v), pop, o1);  // o1[r] = O[16 qb + n][16 + 4g + r]
+                    v[c] = u32x4{a.x, a.y, b.x, b.y};
                 }
+                softmax_exp_pair<NB>(s, kp, mul, mb, sum);
+                const bf16x8 pop = prob_operand<NB>(s, kp);
+                o0 = mfma_bf16(as_bf16x8(v[0]), pop, o0);  // o0[r] = O[16 qb + n][4g + r]
+                o1 = mfma_bf16(as_bf16x8(v[1]), pop, o1);  // o1[r] = O[16 qb + n][16 + 4g + r]
             }
+            const float inv = __builtin_amdgcn_rcpf(sum_over_g(sum));
             typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
             u32x2 lo, hi;
             lo.x = pack_bf16(o0[0] * inv, o0[1] * inv);

@@ -243,6 +243,68 @@ __device__ __forceinline__ float softmax_block(f32x4 (&s)[NB], float sl2, const 
     return __builtin_amdgcn_rcpf(sum);
 }
 
+// The first half of softmax_block on its own: scores scaled (with an additive term) and padded, the
+// row maximum reduced.  Afterwards p = exp2(s * mul - mb), which softmax_exp_pair applies to two key
+// blocks at a time, so that a kernel can issue the loads of the matching V operands first and let
+// their latency pass behind the exponentials instead of in front of every matrix instruction.
+template <int NB, bool BM, class Addend>
+__device__ __forceinline__ float softmax_scale_max(f32x4 (&s)[NB], float sl2, const Addend& addend, int L, int g, float& mul) {
+    if (BM) {
+        f32x4 add[NB];
+        addend.fill(add, kLog2e);
+#pragma unroll
+        for (int jb = 0; jb < NB; ++jb)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) s[jb][r] = fmaf(s[jb][r], sl2, add[jb][r]);
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+            if (16 * (NB - 1) + 4 * g + r >= L) s[NB - 1][r] = -INFINITY;
+        float m = s[0][0];
+#pragma unroll
+        for (int jb = 0; jb < NB; ++jb)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) m = fmaxf(m, s[jb][r]);
+        mul = 1.0f;
+        return max_over_g(m);
+    }
+    const float pad = sl2 >= 0.f ? -INFINITY : INFINITY;
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+        if (16 * (NB - 1) + 4 * g + r >= L) s[NB - 1][r] = pad;
+    float m = s[0][0];
+    if (sl2 >= 0.f) {
+#pragma unroll
+        for (int jb = 0; jb < NB; ++jb)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) m = fmaxf(m, s[jb][r]);
+        m = max_over_g(m);
+    } else {
+#pragma unroll
+        for (int jb = 0; jb < NB; ++jb)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) m = fminf(m, s[jb][r]);
+        m = -max_over_g(-m);
+    }
+    mul = sl2;
+    return m * sl2;
+}
+
+// exponentials of key blocks 2 kp and 2 kp + 1, added to the lane's partial row sum
+template <int NB>
+__device__ __forceinline__ void softmax_exp_pair(f32x4 (&s)[NB], int kp, float mul, float mb, float& sum) {
+#pragma unroll
+    for (int b = 0; b < 2; ++b) {
+        const int jb = 2 * kp + b;
+        if (jb >= NB) break;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const float e = __builtin_amdgcn_exp2f(fmaf(s[jb][r], mul, -mb));
+            s[jb][r] = e;
+            sum += e;
+        }
+    }
+}
+
 // The probabilities of key blocks 2 kp and 2 kp + 1 of a lane as one bf16 operand
 // (k-slots 0..3 = keys 4g..4g+3 of the first block, 4..7 = the same keys of the second).
 template <int NB>
