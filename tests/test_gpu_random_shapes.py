@@ -19,8 +19,10 @@ N_CASES = 240
 ELEMENTS = 2_000_000          # cap on N*L*C per tensor: the oracle stays within a second or two per case
 
 
-def draw_case(i):
-    """The i-th combination (a pure function of i)."""
+def draw_case(i, long_period=False):
+    """The i-th combination (a pure function of i).  long_period: mask periods of 16 to 512 windows, which
+    decide how many windows a persistent workgroup may walk and, beyond the slot count of the cooperative
+    backward, send the call to the one-wave-per-tile kernel."""
     r = synth.rng(424200 + i)
     dtype = "f32" if r.random() < 0.25 else "bf16"
     wide = r.random() < 0.3
@@ -32,11 +34,11 @@ def draw_case(i):
         d = 32
         L = int(r.integers(1, 65)) if r.random() < 0.6 else int(r.integers(65, 257))
         heads = int(r.integers(1, 13))
-    nW = int(r.choice([1, 1, 2, 3, 4, 6]))
+    nW = int(r.choice([16, 64, 256, 512])) if long_period else int(r.choice([1, 1, 2, 3, 4, 6]))
     most = max(1, ELEMENTS // (L * heads * d * nW))
     mult = int(np.exp(r.uniform(0.4, 1.0) * np.log(most + 0.5)))   # skewed towards many windows
     N = nW * max(1, min(mult, most))
-    mask_kind = str(r.choice(["none", "dense", "labels"]))
+    mask_kind = str(r.choice(["dense", "labels"] if long_period else ["none", "dense", "labels"]))
     bias_kind = str(r.choice(["none", "f32", "bf16"]))
     if bias_kind == "bf16" and mask_kind == "dense":   # a bf16 bias comes with labels or with no mask
         mask_kind = "labels"
@@ -51,7 +53,7 @@ def case_id(c):
             f"b{c['bias']}-m{c['mask']}{'-strided' if c['strided'] else ''}{'-dB' if c['want_dbias'] else ''}")
 
 
-CASES = [draw_case(i) for i in range(N_CASES)]
+CASES = [draw_case(i) for i in range(N_CASES)] + [draw_case(N_CASES + i, long_period=True) for i in range(48)]
 
 
 def fused(tensors, torch):
