@@ -201,6 +201,18 @@ def time_other_workloads(torch, fwa, synth, dev):
         run(f"window16_fwd_{form} (N=1024, L=256, 4 heads)", w16s, False, 50, as_labels=lab, bias_bf16=b16)
         run(f"window16_bwd_{form}_dbias (N=1024, L=256, 4 heads)", w16s, True, 20, as_labels=lab, bias_bf16=b16)
     # the shapes of the paper's own kernel benchmark (section 3.1): L = 64, 4 heads, width per head 64 and 256
+    paper_shapes(run)
+    # stage 1 on the token map of an 896 x 896 input (224 x 224 tokens: 1024 windows per image, batch 8): a mask
+    # period that no workgroup stride over the windows is a multiple of; the mask as region labels
+    hr = synth.Workload("stage1_map224", 8192, 49, 96, 3, "bf16", 1400, 7, 224, True, 3, True)
+    run("swin_t_stage1_fwd_bias_shiftlabels, 1024 windows per image (N=8192, L=49, 3 heads)", hr, False, 200, as_labels=True)
+    run("swin_t_stage1_bwd_bias_shiftlabels_dbias, 1024 windows per image (N=8192, L=49, 3 heads)", hr, True, 100,
+        as_labels=True)
+    return out
+
+
+def paper_shapes(run):
+    from paper_2501_06480_amd import synth
     for d in (64, 256):
         pw = synth.Workload(f"paper_L64_d{d}", 4096, 64, 4 * d, 4, "bf16", 1100 + d, 8)
         run(f"paper_benchmark_shape_fwd (N=4096, L=64, 4 heads x {d})", pw, False, 50)
@@ -209,7 +221,6 @@ def time_other_workloads(torch, fwa, synth, dev):
         pf = synth.Workload(f"paper_L64_d{d}_f32", 2048, 64, 4 * d, 4, "f32", 1200 + d, 8)
         run(f"paper_benchmark_shape_fwd_fp32 (N=2048, L=64, 4 heads x {d})", pf, False, 20)
         run(f"paper_benchmark_shape_bwd_fp32 (N=2048, L=64, 4 heads x {d}; dQ, dK, dV)", pf, True, 10, want_dbias=False)
-    return out
 
 
 def main():

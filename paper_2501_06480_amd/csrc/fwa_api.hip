@@ -236,13 +236,17 @@ int backward_impl(const void* q, const void* k, const void* v, const void* d_o, 
     a.bias = bias; a.bias_bf16 = bias && bias_dtype == FWA_BF16;
     a.mask = mask; a.labels = labels; a.mask_value = mask_value;
     a.N = N; a.L = L; a.C = C; a.heads = heads; a.nW = (mask || labels) ? nW : 1; a.scale = scale;
+    // A mask period that no slot count of the cooperative kernel is a multiple of: with the mask as
+    // labels the kernel forms each window's mask itself and its workgroups walk the windows as if
+    // there were no period; with a dense mask the one-wave-per-tile kernel takes the call.
+    const bool small = dtype == FWA_BF16 && C / heads == fwa::kHeadDim && L <= fwa::kMaxBackwardL;
+    a.per_window = small && labels && fwa::coop_slots(N, heads, a.nW) == 0 && fwa::coop_slots(N, heads, 1) > 0;
     a.slots = C / heads != fwa::kHeadDim ? fwa::backward_wide_slots(N, heads)
               : L > fwa::kMaxBackwardL   ? fwa::backward_large_slots(N, heads, L)
-                                         : fwa::backward_slots(N, heads, a.nW);
+                                         : fwa::backward_slots(N, heads, a.per_window ? 1 : a.nW);
     a.ldq = (int)ld_qkv; a.ldg = (int)ld_do; a.ldd = (int)ld_dqkv;
-    // the one-wave-per-tile kernel (mask periods too long for the cooperative one) takes fp32 biases only
-    if (a.bias_bf16 && dtype == FWA_BF16 && C / heads == fwa::kHeadDim && L <= fwa::kMaxBackwardL &&
-        fwa::coop_slots(N, heads, a.nW) == 0)
+    // the one-wave-per-tile kernel takes fp32 biases only
+    if (a.bias_bf16 && small && !a.per_window && fwa::coop_slots(N, heads, a.nW) == 0)
         return FWA_ERR_UNSUPPORTED;
     const hipError_t e = dtype == FWA_BF16 ? fwa::launch_backward_bf16(a, st) : fwa::launch_backward_f32(a, st);
     return e == hipSuccess ? FWA_OK : FWA_ERR_LAUNCH;

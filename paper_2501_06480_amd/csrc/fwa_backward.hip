@@ -437,7 +437,7 @@ hipError_t launch_backward_bf16_single(const BwdArgs& a, hipStream_t s) {
 hipError_t launch_backward_bf16(const BwdArgs& a, hipStream_t s) {
     if (a.C / a.heads != kHeadDim) return launch_backward_bf16_wide(a, s);
     if (a.L > kMaxBackwardL) return launch_backward_bf16_large(a, s);
-    const bool coop = coop_slots(a.N, a.heads, mask_period(a)) > 0;
+    const bool coop = a.per_window || coop_slots(a.N, a.heads, mask_period(a)) > 0;
     const hipError_t e = coop ? launch_backward_bf16_coop(a, s) : launch_backward_bf16_single(a, s);
     if (e != hipSuccess || a.dbias == nullptr) return e;
     return launch_dbias_reduce(a, s);

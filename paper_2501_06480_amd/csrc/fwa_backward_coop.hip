@@ -39,7 +39,10 @@ struct CoopGeom {
 
 // KT < 4 promises that only the first KT of a lane's 4 columns in the last key block can be real
 // (L <= 16 (NB - 1) + KT, e.g. KT = 1 for L = 49): the others are zero without any arithmetic.
-template <int NB, bool BM, bool DB, int KT>
+// PW ("per window"): the mask comes as labels whose period G is no multiple of.  The registers then
+// hold bias * log2e alone; the labels of a window travel with its slabs into LDS and phase A forms
+// the mask per score (AddendRegsLabels).
+template <int NB, bool BM, bool DB, int KT, bool PW>
 __global__ void __launch_bounds__(64 * kCoopWavesPerTile * kCoopMaxHeads) bwd_bf16_coop_kernel(BwdArgs p, CoopGeom gm) {
     constexpr int NB2 = (NB + 1) / 2;
     constexpr int ROWS = 16 * NB;
@@ -74,6 +77,8 @@ __global__ void __launch_bounds__(64 * kCoopWavesPerTile * kCoopMaxHeads) bwd_bf
     // different units, i.e. every bank once.
     constexpr uint32_t XS = 64, XT = ROWS * XS;
     uint16_t* const ex = reinterpret_cast<uint16_t*>(lds + 4 * ROWS * stride) + (size_t)hl * (4 * XT);
+    // PW: the labels of the window in LDS, behind the tiles of all heads
+    int* const llab = reinterpret_cast<int*>(reinterpret_cast<uint16_t*>(lds + 4 * ROWS * stride) + (size_t)hpb * (4 * XT));
     const uint32_t srow = stride * 8u;  // slab row stride in bf16 elements
     // transposing-read base of this lane inside a slab (channel on the lane) and inside a tile
     const uint32_t trs = (4u * g + (n >> 2)) * srow + 32u * hl + 4u * (n & 3);
@@ -96,6 +101,7 @@ __global__ void __launch_bounds__(64 * kCoopWavesPerTile * kCoopMaxHeads) bwd_bf
     const uint32_t goff_g = rip * row_g + col * 16u;
     const uint32_t loff = rip * stride + col;
     u32x4 pk, pv, pq, pg;
+    i32x4 plab;  // PW: labels 4 tid .. 4 tid + 3 of the requested window (0 beyond L)
     auto request = [&](uint32_t w) {
         const size_t slab = ((size_t)w * L * p.ldq + (size_t)hg * hpb * kHeadDim) * 2u;
         const size_t slab_g = ((size_t)w * L * p.ldg + (size_t)hg * hpb * kHeadDim) * 2u;
@@ -104,6 +110,7 @@ __global__ void __launch_bounds__(64 * kCoopWavesPerTile * kCoopMaxHeads) bwd_bf
         pv = __builtin_amdgcn_raw_buffer_load_b128(make_rsrc((const char*)p.v + slab, slab_bytes), goff, 0, 0);
         pq = __builtin_amdgcn_raw_buffer_load_b128(make_rsrc((const char*)p.q + slab, slab_bytes), goff, 0, 0);
         pg = __builtin_amdgcn_raw_buffer_load_b128(make_rsrc((const char*)p.d_o + slab_g, slab_bytes_g), goff_g, 0, 0);
+        if (PW) plab = load_i32x4(make_rsrc(p.labels + (size_t)(w % (uint32_t)p.nW) * L, (uint32_t)L * 4u), (uint32_t)tid * 16u);
     };
     auto park = [&]() {
         if (rip < (uint32_t)ROWS) {
@@ -112,14 +119,17 @@ __global__ void __launch_bounds__(64 * kCoopWavesPerTile * kCoopMaxHeads) bwd_bf
             lq[loff] = __builtin_bit_cast(uint4, pq);
             lg[loff] = __builtin_bit_cast(uint4, pg);
         }
+        if (PW && tid < ROWS / 4) reinterpret_cast<i32x4*>(llab)[tid] = plab;
     };
     if (bw < (uint32_t)p.N) request(bw);  // in flight while the additive term is fetched
     // additive score term of this wave's query rows, in registers (see the file comment)
     f32x4 add[NB];
     if (BM && active) {
         const BiasSrc rb = bias_of_head(p, h);
-        addend_at(rb, mask_of_window(p, bw), (uint32_t)(16 * role + n), 4u * g, (uint32_t)L).fill(add, kLog2e);
+        const MaskSrc msk = PW ? MaskSrc{make_rsrc(nullptr, 0), 0.f, false} : mask_of_window(p, bw);
+        addend_at(rb, msk, (uint32_t)(16 * role + n), 4u * g, (uint32_t)L).fill(add, kLog2e);
     }
+    const float mv = p.mask_value * kLog2e;
     if (bw < (uint32_t)p.N) park();
 
     const uint32_t tile_bytes = (uint32_t)(L - 1) * row_d + 2u * kHeadDim;  // of an output tile
@@ -148,7 +158,10 @@ __global__ void __launch_bounds__(64 * kCoopWavesPerTile * kCoopMaxHeads) bwd_bf
             }
             // softmax of the block's rows: s <- exp(score - rowmax), inv = 1 / rowsum
             float inv;
-            if (BM) {
+            if (BM && PW) {
+                const AddendRegsLabels<NB> addend = {add, llab, llab[16 * qb + n], mv, g};
+                inv = softmax_block<NB, true, AddendRegsLabels<NB>, KT>(s, sl2, addend, L, g);
+            } else if (BM) {
                 const AddendRegs<NB> addend = {add};
                 inv = softmax_block<NB, true, AddendRegs<NB>, KT>(s, sl2, addend, L, g);
             } else {
@@ -266,16 +279,26 @@ __global__ void __launch_bounds__(64 * kCoopWavesPerTile * kCoopMaxHeads) bwd_bf
     }
 }
 
-template <int NB, bool BM, bool DB, int KT>
-hipError_t launch_coop_kt(const BwdArgs& a, const CoopGeom& gm, unsigned grid, unsigned block, size_t lds,
+template <int NB, bool BM, bool DB, int KT, bool PW>
+hipError_t launch_coop_pw(const BwdArgs& a, const CoopGeom& gm, unsigned grid, unsigned block, size_t lds,
                           hipStream_t st) {
+    if (PW) lds += (size_t)16 * NB * 4;  // the window's labels
     if (lds > 64 * 1024) {
-        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&bwd_bf16_coop_kernel<NB, BM, DB, KT>),
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&bwd_bf16_coop_kernel<NB, BM, DB, KT, PW>),
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL((bwd_bf16_coop_kernel<NB, BM, DB, KT>), dim3(grid), dim3(block), lds, st, a, gm);
+    hipLaunchKernelGGL((bwd_bf16_coop_kernel<NB, BM, DB, KT, PW>), dim3(grid), dim3(block), lds, st, a, gm);
     return hipGetLastError();
+}
+
+template <int NB, bool BM, bool DB, int KT>
+hipError_t launch_coop_kt(const BwdArgs& a, const CoopGeom& gm, unsigned grid, unsigned block, size_t lds,
+                          hipStream_t st) {
+    if constexpr (BM) {
+        if (a.per_window) return launch_coop_pw<NB, true, DB, KT, true>(a, gm, grid, block, lds, st);
+    }
+    return launch_coop_pw<NB, BM, DB, KT, false>(a, gm, grid, block, lds, st);
 }
 
 template <int NB, bool BM, bool DB>

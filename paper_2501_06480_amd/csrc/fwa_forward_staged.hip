@@ -171,11 +171,14 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock * QS) fwd_bf16_staged_kern
 // (bias[h] + mask[bw % nW]) * log2e ONCE, straight into the registers of the score layout, and
 // the per-window work is that of the bias-free kernel plus one fused multiply-add per score.
 // The slab of the next window is requested before the current one is computed.
-template <int NB>
+// PW: the mask comes as labels whose period does not divide G; the bias alone stays in registers,
+// the labels of a window travel with its slab and the mask is formed per score (see
+// AddendRegsLabels).
+template <int NB, bool PW>
 __global__ void __launch_bounds__(64 * kWavesPerBlock) fwd_bf16_persistent_kernel(FwdArgs p, StagedGeom gm, uint32_t G) {
     constexpr int NB2 = (NB + 1) / 2;
     constexpr int ROWS = 16 * NB;
-    extern __shared__ __attribute__((aligned(16))) uint4 lds[];  // [3][ROWS][stride]: K, V, Q (then O)
+    extern __shared__ __attribute__((aligned(16))) uint4 lds[];  // [3][ROWS][stride]: K, V, Q (then O); then (PW) [ROWS] labels
     const int tid = threadIdx.x, lane = tid & 63;
     const int n = lane & 15, g = lane >> 4;
     const uint32_t hl = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -197,10 +200,12 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) fwd_bf16_persistent_kerne
     uint4* const lk = lds;
     uint4* const lv = lds + ROWS * stride;
     uint4* const lq = lds + 2 * ROWS * stride;
+    int* const llab = reinterpret_cast<int*>(lds + 3 * ROWS * stride);
     const uint16_t* const lvh = reinterpret_cast<const uint16_t*>(lv) + 32 * hl +
                                 (4 * g + (n >> 2)) * (stride * 8u) + 4 * (n & 3);
 
     u32x4 sk[NB], sv[NB], sq[NB];
+    i32x4 slab_labels;  // PW: labels 4 tid .. 4 tid + 3 of the requested window (0 beyond L)
     auto request = [&](uint32_t w) {
         const size_t slab = ((size_t)w * L * p.ldq + (size_t)hg * hpb * kHeadDim) * 2u;
         const __amdgpu_buffer_rsrc_t rq = make_rsrc((const char*)p.q + slab, slab_bytes);
@@ -212,6 +217,8 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) fwd_bf16_persistent_kerne
             sq[t] = __builtin_amdgcn_raw_buffer_load_b128(rq, goff + 16 * t * row_bytes, 0, 0);
             sv[t] = __builtin_amdgcn_raw_buffer_load_b128(rv, goff + 16 * t * row_bytes, 0, 0);
         }
+        if (PW)
+            slab_labels = load_i32x4(make_rsrc(p.labels + (size_t)(w % (uint32_t)p.nW) * L, (uint32_t)L * 4u), (uint32_t)tid * 16u);
     };
     auto park = [&]() {
 #pragma unroll
@@ -220,15 +227,17 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) fwd_bf16_persistent_kerne
             lq[loff + 16 * t * stride] = __builtin_bit_cast(uint4, sq[t]);
             lv[loff + 16 * t * stride] = __builtin_bit_cast(uint4, sv[t]);
         }
+        if (PW && tid < ROWS / 4) reinterpret_cast<i32x4*>(llab)[tid] = slab_labels;
     };
     if (bw < (uint32_t)p.N) request(bw);  // in flight while the additive term is fetched
     // the additive term of this wave's head and this workgroup's mask tile, in score layout
     f32x4 add[NB][NB];
     {
         const BiasSrc rb = bias_of_head(p, h);
-        const MaskSrc msk = mask_of_window(p, bw);
+        const MaskSrc msk = PW ? MaskSrc{make_rsrc(nullptr, 0), 0.f, false} : mask_of_window(p, bw);
         fill_rows<NB, NB>(add, rb, msk, (uint32_t)n, 4u * g, (uint32_t)L, kLog2e);
     }
+    const float mv = p.mask_value * kLog2e;
 
     if (bw < (uint32_t)p.N) park();
 
@@ -255,6 +264,9 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) fwd_bf16_persistent_kerne
                 const u32x4 v = {a.x, a.y, b.x, b.y};
                 vop[kp][c] = as_bf16x8(v);
             }
+        int tq[NB];  // PW: labels of this lane's query rows
+#pragma unroll
+        for (int b = 0; b < NB; ++b) tq[b] = PW ? llab[16 * b + n] : 0;
         if (has_next) request(w + G);  // in flight while this window is computed
 
 #pragma unroll
@@ -265,8 +277,14 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) fwd_bf16_persistent_kerne
                 const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
                 s[jb] = mfma_bf16(kop[jb], qop[qb], zero);
             }
-            const AddendRegs<NB> addend = {add[qb]};
-            const float inv = softmax_block<NB, true>(s, sl2, addend, L, g);
+            float inv;
+            if (PW) {
+                const AddendRegsLabels<NB> addend = {add[qb], llab, tq[qb], mv, g};
+                inv = softmax_block<NB, true>(s, sl2, addend, L, g);
+            } else {
+                const AddendRegs<NB> addend = {add[qb]};
+                inv = softmax_block<NB, true>(s, sl2, addend, L, g);
+            }
             f32x4 o0 = {0.f, 0.f, 0.f, 0.f}, o1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int kp = 0; kp < NB2; ++kp) {
@@ -444,7 +462,12 @@ constexpr int rowpersist_waves(int nb) { return nb <= 12 ? nb : (nb + 1) / 2; }
 // HPB heads per workgroup (HPB W waves): slab rows of HPB * 64 bytes, which are whole 128-byte
 // lines when HPB is even or the whole token row when HPB is the head count.  Used with HPB > 1
 // for L <= 64, where W <= 4.
-template <int NB, int HPB>
+//
+// PW ("per window"): the mask comes as labels and its period does not divide G, so that a workgroup
+// meets a different mask tile at every window.  Then only the bias stays in registers; the labels
+// of a window travel with its slabs (requested two windows ahead, parked in LDS beside them) and
+// the mask is formed per score.
+template <int NB, int HPB, bool PW>
 __global__ void __launch_bounds__(64 * HPB * rowpersist_waves(NB)) fwd_bf16_rowpersist_kernel(FwdArgs p, RowPersistGeom gm) {
     constexpr int W = rowpersist_waves(NB);
     constexpr int NB2 = (NB + 1) / 2;
@@ -452,11 +475,12 @@ __global__ void __launch_bounds__(64 * HPB * rowpersist_waves(NB)) fwd_bf16_rowp
     constexpr int PASSES = (ROWS + 16 * W - 1) / (16 * W);  // the workgroup moves 16 W slab rows per pass
     constexpr uint32_t TPR = 4 * HPB;                        // threads per slab row, 16 bytes each
     constexpr uint32_t STRIDE = TPR + 1;                     // LDS row: HPB * 64 bytes of data + 16 of padding
-    extern __shared__ __attribute__((aligned(16))) uint4 lds[];  // [2 buffers][K, V][ROWS][STRIDE]
+    extern __shared__ __attribute__((aligned(16))) uint4 lds[];  // [2 buffers][K, V][ROWS][STRIDE], then (PW) [2][ROWS] labels
     const int tid = threadIdx.x, lane = tid & 63;
     const int n = lane & 15, g = lane >> 4;
     const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const uint32_t hl = wave / W, wq = wave % W;  // head inside the workgroup, query block inside the part
+    int* const llab = reinterpret_cast<int*>(lds + 2 * (2 * ROWS * STRIDE));
     const uint32_t lb = xcd_logical_block(blockIdx.x, gm.xcd_q, gm.xcd_r);
     const uint32_t part = lb % gm.parts, bh = lb / gm.parts;
     const uint32_t grp = bh % gm.groups, bw = bh / gm.groups;
@@ -475,6 +499,7 @@ __global__ void __launch_bounds__(64 * HPB * rowpersist_waves(NB)) fwd_bf16_rowp
     // w + 2 step are requested into the other, so that two windows are in flight per workgroup.
     struct Slab {
         u32x4 k[PASSES], v[PASSES], q;
+        i32x4 lab;  // PW: labels 4 tid .. 4 tid + 3 of the window
     };
     Slab sa, sb;
     sa.q = sb.q = u32x4{0u, 0u, 0u, 0u};
@@ -490,6 +515,8 @@ __global__ void __launch_bounds__(64 * HPB * rowpersist_waves(NB)) fwd_bf16_rowp
         }
         if (active)
             d.q = __builtin_amdgcn_raw_buffer_load_b128(make_rsrc((const char*)p.q + tile, tile_bytes), off_row, 0, 0);
+        if (PW)  // tokens beyond L lie outside the descriptor: label 0, discarded with their rows and columns
+            d.lab = load_i32x4(make_rsrc(p.labels + (size_t)(w % (uint32_t)p.nW) * L, (uint32_t)L * 4u), (uint32_t)tid * 16u);
     };
     auto park = [&](const Slab& d, uint32_t b) {
         uint4* const dk = lds + b * (2 * ROWS * STRIDE);
@@ -502,6 +529,7 @@ __global__ void __launch_bounds__(64 * HPB * rowpersist_waves(NB)) fwd_bf16_rowp
                 dv[row * STRIDE + scol] = __builtin_bit_cast(uint4, d.v[t]);
             }
         }
+        if (PW && tid < ROWS / 4) reinterpret_cast<i32x4*>(llab + b * ROWS)[tid] = d.lab;
     };
     // The windows of this workgroup: w0, w0 + step, ... below `end`
     uint32_t w0 = bw, step = gm.G, end = (uint32_t)p.N;
@@ -511,9 +539,10 @@ __global__ void __launch_bounds__(64 * HPB * rowpersist_waves(NB)) fwd_bf16_rowp
     {
         const BiasSrc rb = bias_of_head(p, h);
         // rows beyond L (and the whole block of an idle wave) fall outside the descriptors: zeros
-        addend_at(rb, mask_of_window(p, w0), active ? (uint32_t)(16 * qb + n) : (uint32_t)L, 4u * g, (uint32_t)L)
-            .fill(add, kLog2e);
+        const MaskSrc msk = PW ? MaskSrc{make_rsrc(nullptr, 0), 0.f, false} : mask_of_window(p, w0);
+        addend_at(rb, msk, active ? (uint32_t)(16 * qb + n) : (uint32_t)L, 4u * g, (uint32_t)L).fill(add, kLog2e);
     }
+    const float mv = p.mask_value * kLog2e;
     if (w0 < end) park(sa, 0);
 
     // One window: K, V of window w are in LDS buffer `buf`, its Q rows in cur.q; nxt holds window
@@ -538,9 +567,15 @@ __global__ void __launch_bounds__(64 * HPB * rowpersist_waves(NB)) fwd_bf16_rowp
                 const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
                 s[jb] = mfma_bf16(__builtin_bit_cast(bf16x8, lkh[16 * jb * STRIDE]), qop, zero);  // S[16 qb + n][16 jb + 4g + r]
             }
-            const AddendRegs<NB> addend = {add};
-            float mul, sum = 0.f;
-            const float mb = softmax_scale_max<NB, true>(s, sl2, addend, L, g, mul);
+            float mul, sum = 0.f, mb;
+            if (PW) {
+                const int* const lab = llab + buf * ROWS;
+                const AddendRegsLabels<NB> addend = {add, lab, lab[16 * qb + n], mv, g};
+                mb = softmax_scale_max<NB, true>(s, sl2, addend, L, g, mul);
+            } else {
+                const AddendRegs<NB> addend = {add};
+                mb = softmax_scale_max<NB, true>(s, sl2, addend, L, g, mul);
+            }
             f32x4 o0 = {0.f, 0.f, 0.f, 0.f}, o1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int kp = 0; kp < NB2; ++kp) {
@@ -583,16 +618,24 @@ __global__ void __launch_bounds__(64 * HPB * rowpersist_waves(NB)) fwd_bf16_rowp
 // workgroup per CU, a multiple of the mask period, at least two windows per workgroup);
 // 0 = use the plain row-blocked kernel.
 template <int NB>
-long long rowpersist_slots(const FwdArgs& a) {
+long long rowpersist_slots(const FwdArgs& a, bool& pw) {
     const long long parts = NB <= 12 ? 1 : 2;
     const long long nW = mask_period(a);
-    long long G = (256 / ((long long)a.heads * parts)) / nW * nW;
+    const long long most = 256 / ((long long)a.heads * parts);
+    long long G = most / nW * nW;
     if (G > a.N / 2) G = (a.N / 2) / nW * nW;
-    return G >= nW && G > 0 ? G : 0;
+    pw = false;
+    if (G >= nW && G > 0) return G;
+    // no multiple of the mask period fits: with the mask as labels the workgroups walk the windows
+    // all the same and form the mask of each window from its labels
+    if (a.labels == nullptr) return 0;
+    pw = true;
+    G = most < a.N / 2 ? most : a.N / 2;
+    return G > 0 ? G : 0;
 }
 
-template <int NB, int HPB>
-hipError_t launch_rowpersist_hpb(const FwdArgs& a, long long G, hipStream_t st) {
+template <int NB, int HPB, bool PW>
+hipError_t launch_rowpersist_pw(const FwdArgs& a, long long G, hipStream_t st) {
     RowPersistGeom gm;
     gm.groups = (uint32_t)(a.heads / HPB);
     gm.parts = NB <= 12 ? 1u : 2u;
@@ -600,35 +643,31 @@ hipError_t launch_rowpersist_hpb(const FwdArgs& a, long long G, hipStream_t st) 
     const unsigned grid = gm.G * gm.groups * gm.parts, block = 64u * (unsigned)(HPB * rowpersist_waves(NB));
     gm.xcd_q = grid / 8u;
     gm.xcd_r = grid % 8u;
-    const size_t lds = (size_t)2 * 2 * 16 * NB * (4 * HPB + 1) * 16;
+    const size_t lds = (size_t)2 * 2 * 16 * NB * (4 * HPB + 1) * 16 + (PW ? (size_t)2 * 16 * NB * 4 : 0);
     if (lds > 64 * 1024) {
-        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&fwd_bf16_rowpersist_kernel<NB, HPB>),
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&fwd_bf16_rowpersist_kernel<NB, HPB, PW>),
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL((fwd_bf16_rowpersist_kernel<NB, HPB>), dim3(grid), dim3(block), lds, st, a, gm);
+    hipLaunchKernelGGL((fwd_bf16_rowpersist_kernel<NB, HPB, PW>), dim3(grid), dim3(block), lds, st, a, gm);
     return hipGetLastError();
 }
 
-template <int NB>
-hipError_t launch_rowpersist_nb(const FwdArgs& a, long long G, hipStream_t st) {
-    return launch_rowpersist_hpb<NB, 1>(a, G, st);
+// pw: the mask comes as labels whose period does not divide G (see the kernel)
+template <int NB, int HPB>
+hipError_t launch_rowpersist_hpb(const FwdArgs& a, long long G, hipStream_t st, bool pw = false) {
+    return pw ? launch_rowpersist_pw<NB, HPB, true>(a, G, st) : launch_rowpersist_pw<NB, HPB, false>(a, G, st);
 }
 
-template <int NB, int QW>
-hipError_t launch_rowblock_qw(const FwdArgs& a, const RowBlockGeom& gm, unsigned grid, int hpb, size_t lds, bool bm,
-                              hipStream_t st) {
+template <int NB, bool BM, int QW>
+hipError_t launch_rowblock_qw(const FwdArgs& a, const RowBlockGeom& gm, unsigned grid, int hpb, size_t lds, hipStream_t st) {
     const unsigned block = 64u * (unsigned)(QW * hpb);
-    const void* fn = bm ? reinterpret_cast<const void*>(&fwd_bf16_rowblock_kernel<NB, true, QW>)
-                        : reinterpret_cast<const void*>(&fwd_bf16_rowblock_kernel<NB, false, QW>);
     if (lds > 64 * 1024) {
-        const hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&fwd_bf16_rowblock_kernel<NB, BM, QW>),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
-    if (bm)
-        hipLaunchKernelGGL((fwd_bf16_rowblock_kernel<NB, true, QW>), dim3(grid), dim3(block), lds, st, a, gm);
-    else
-        hipLaunchKernelGGL((fwd_bf16_rowblock_kernel<NB, false, QW>), dim3(grid), dim3(block), lds, st, a, gm);
+    hipLaunchKernelGGL((fwd_bf16_rowblock_kernel<NB, BM, QW>), dim3(grid), dim3(block), lds, st, a, gm);
     return hipGetLastError();
 }
 
@@ -647,13 +686,16 @@ hipError_t launch_rowblock_nb(const FwdArgs& a, hipStream_t st) {
     const size_t lds = (size_t)2 * 16 * NB * (4 * hpb + 1) * 16;
     const bool bm = a.bias || has_mask(a);
     if (bm) {  // without an additive term the walk over windows gains nothing (measured slower)
-        const long long G = rowpersist_slots<NB>(a);
-        if (G > 0) return launch_rowpersist_nb<NB>(a, G, st);
+        bool pw;
+        const long long G = rowpersist_slots<NB>(a, pw);
+        if (G > 0) return launch_rowpersist_hpb<NB, 1>(a, G, st, pw);
     }
     // waves per head: 2 with two heads per workgroup (3 or 4 measured 3-20 % slower at L = 144..256), 4
-    // with one (an odd head count: 10 % faster than 2)
-    if (hpb == 1) return launch_rowblock_qw<NB, 4>(a, gm, grid, hpb, lds, bm, st);
-    return launch_rowblock_qw<NB, 2>(a, gm, grid, hpb, lds, bm, st);
+    // with one (an odd head count: 10 % faster than 2; not with an additive term, whose registers
+    // need the whole file of a SIMD that holds one wave of the workgroup)
+    if (bm) return launch_rowblock_qw<NB, true, 2>(a, gm, grid, hpb, lds, st);
+    if (hpb == 1) return launch_rowblock_qw<NB, false, 4>(a, gm, grid, hpb, lds, st);
+    return launch_rowblock_qw<NB, false, 2>(a, gm, grid, hpb, lds, st);
 }
 
 template <int NB>
@@ -679,11 +721,17 @@ hipError_t launch_staged_nb(const FwdArgs& a, int hpb, hipStream_t st) {
         if (groups == 1 && hpb > 1) {
             long long G1 = 256 / nW * nW;
             if (G1 > a.N / 2) G1 = (a.N / 2) / nW * nW;
-            if (G1 >= nW && G1 >= 128) {
+            bool pw = false;
+            if (!(G1 >= nW && G1 >= 128) && a.labels != nullptr && a.N >= 256) {
+                // no multiple of the mask period fits: per-window masks from the labels
+                G1 = a.N / 2 < 256 ? a.N / 2 : 256;
+                pw = true;
+            }
+            if (pw || (G1 >= nW && G1 >= 128)) {
                 switch (hpb) {
-                    case 2: return launch_rowpersist_hpb<NB, 2>(a, G1, st);
-                    case 3: return launch_rowpersist_hpb<NB, 3>(a, G1, st);
-                    default: return launch_rowpersist_hpb<NB, 4>(a, G1, st);
+                    case 2: return launch_rowpersist_hpb<NB, 2>(a, G1, st, pw);
+                    case 3: return launch_rowpersist_hpb<NB, 3>(a, G1, st, pw);
+                    default: return launch_rowpersist_hpb<NB, 4>(a, G1, st, pw);
                 }
             }
         }
@@ -692,11 +740,19 @@ hipError_t launch_staged_nb(const FwdArgs& a, int hpb, hipStream_t st) {
         const long long waves_per_cu = NB == 4 ? 8 : (NB == 3 ? 12 : (NB == 2 ? 20 : 32));
         long long per_cu = waves_per_cu / hpb;
         if (per_cu > 4) per_cu = 4;
-        long long G = (per_cu * 256 / (long long)groups) / nW * nW;
+        const long long most = per_cu * 256 / (long long)groups;
+        long long G = most / nW * nW;
         if (G > a.N / 2) G = (a.N / 2) / nW * nW;
         if (!few_tiles && G >= nW && G > 0 && G * groups >= 256) {
-            hipLaunchKernelGGL((fwd_bf16_persistent_kernel<NB>), dim3((unsigned)(G * groups)), dim3(block), lds, st,
+            hipLaunchKernelGGL((fwd_bf16_persistent_kernel<NB, false>), dim3((unsigned)(G * groups)), dim3(block), lds, st,
                                a, gm, (uint32_t)G);
+            return hipGetLastError();
+        }
+        // no multiple of the mask period fits: with the mask as labels, per-window masks from the labels
+        G = most < a.N / 2 ? most : a.N / 2;
+        if (!few_tiles && a.labels != nullptr && G * groups >= 256) {
+            hipLaunchKernelGGL((fwd_bf16_persistent_kernel<NB, true>), dim3((unsigned)(G * groups)), dim3(block),
+                               lds + (size_t)16 * NB * 4, st, a, gm, (uint32_t)G);
             return hipGetLastError();
         }
         if (few_tiles)

@@ -57,6 +57,8 @@ struct BwdArgs {
     int nW;
     float scale;
     int slots;           // number of partial-sum slots per head in `partial`
+    int per_window;      // cooperative kernel for L <= 64: the mask is formed per window from the labels (a period
+                         // that no slot count is a multiple of); only the bias stays in registers
     int ldq;             // elements between consecutive token rows of q, k, v (C when contiguous)
     int ldg;             // the same for d_o
     int ldd;             // the same for dq, dk, dv

@@ -167,6 +167,36 @@ struct AddendRegs {
         for (int jb = 0; jb < NB; ++jb) add[jb] = a[jb];
     }
 };
+// AddendRegsLabels: the bias (times log2e) in registers as above, the mask formed per score from the
+// labels of the current window, which the kernel has staged in LDS: 0 where the label of the lane's
+// query row equals that of the key, `mv` (mask value times log2e) elsewhere.  For persistent kernels
+// whose workgroups cannot keep one mask tile for life (a mask period that does not divide their
+// stride over the windows): the bias still stays in registers.  Keys beyond L read whatever the
+// staging left there; their columns are overwritten with -inf afterwards.
+template <int NB>
+struct AddendRegsLabels {
+    const f32x4 (&a)[NB];
+    const int* lab;  // LDS: labels of tokens 0 .. 16 NB - 1 of the window
+    int tq;          // label of the lane's query row
+    float mv;
+    int g;
+    // the term of key block jb (one block at a time keeps the labels out of the register file)
+    __device__ __forceinline__ f32x4 block(int jb) const {
+        const i32x4 tk = *reinterpret_cast<const i32x4*>(lab + 16 * jb + 4 * g);
+        f32x4 t;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) t[r] = a[jb][r] + (tk[r] == tq ? 0.f : mv);
+        return t;
+    }
+    __device__ __forceinline__ void fill(f32x4 (&add)[NB], float) const {
+#pragma unroll
+        for (int jb = 0; jb < NB; ++jb) add[jb] = block(jb);
+    }
+};
+template <class A>
+struct addend_per_block { static constexpr bool value = false; };
+template <int NB>
+struct addend_per_block<AddendRegsLabels<NB>> { static constexpr bool value = true; };
 struct AddendNone {
     template <int NB>
     __device__ __forceinline__ void fill(f32x4 (&add)[NB], float) const {
@@ -250,12 +280,21 @@ __device__ __forceinline__ float softmax_block(f32x4 (&s)[NB], float sl2, const 
 template <int NB, bool BM, class Addend>
 __device__ __forceinline__ float softmax_scale_max(f32x4 (&s)[NB], float sl2, const Addend& addend, int L, int g, float& mul) {
     if (BM) {
-        f32x4 add[NB];
-        addend.fill(add, kLog2e);
+        if constexpr (addend_per_block<Addend>::value) {
 #pragma unroll
-        for (int jb = 0; jb < NB; ++jb)
+            for (int jb = 0; jb < NB; ++jb) {
+                const f32x4 t = addend.block(jb);
 #pragma unroll
-            for (int r = 0; r < 4; ++r) s[jb][r] = fmaf(s[jb][r], sl2, add[jb][r]);
+                for (int r = 0; r < 4; ++r) s[jb][r] = fmaf(s[jb][r], sl2, t[r]);
+            }
+        } else {
+            f32x4 add[NB];
+            addend.fill(add, kLog2e);
+#pragma unroll
+            for (int jb = 0; jb < NB; ++jb)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) s[jb][r] = fmaf(s[jb][r], sl2, add[jb][r]);
+        }
 #pragma unroll
         for (int r = 0; r < 4; ++r)
             if (16 * (NB - 1) + 4 * g + r >= L) s[NB - 1][r] = -INFINITY;

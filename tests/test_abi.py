@@ -157,8 +157,6 @@ def test_label_entry_points_check_their_arguments(lib):
     assert bwd(labels=P + 0x9008) == b.FWA_ERR_ALIGN
     assert bwd(dbias=P + 0x7000) == b.FWA_ERR_WORKSPACE
     assert bwd(bias=P + 0x7000, bias_dtype=3) == b.FWA_ERR_UNSUPPORTED
-    # a mask period too long for the cooperative kernel leaves the one-wave kernel, which takes fp32 biases only
-    assert bwd(bias=P + 0x7000, bias_dtype=1, N=64, nW=64, heads=24) == b.FWA_ERR_UNSUPPORTED
 
 
 def test_large_window_backward_needs_a_workspace_for_a_bf16_bias(lib):

@@ -53,7 +53,7 @@ def check_forward(oracle, w, nW, use_bias, seed, value=VALUE):
     assert err <= TOL[w.dtype], (w.name, err)
 
 
-def check_backward(oracle, w, nW, use_bias, seed, want_dbias, value=VALUE):
+def check_backward(oracle, w, nW, use_bias, seed, want_dbias, value=VALUE, bitwise=True):
     import torch
     import paper_2501_06480_amd as fwa
     x = synth.draw(w)
@@ -68,9 +68,15 @@ def check_backward(oracle, w, nW, use_bias, seed, want_dbias, value=VALUE):
     torch.cuda.synchronize()
     bits = torch.int16 if w.dtype == "bf16" else torch.int32
     for name, a, b in zip(("dq", "dk", "dv"), got[:3], dense[:3]):
-        assert torch.equal(a.view(bits), b.view(bits)), (w.name, name)
+        if bitwise:
+            assert torch.equal(a.view(bits), b.view(bits)), (w.name, name)
+        else:  # another kernel takes the dense form: the same numbers up to a rounding of the output
+            assert max_abs(to_f64(a), to_f64(b)) <= 2.0 ** -7 * max(1.0, float(b.float().abs().max())), (w.name, name)
     if want_dbias:
-        assert torch.equal(got[3].view(torch.int32), dense[3].view(torch.int32)), (w.name, "dbias")
+        if bitwise:
+            assert torch.equal(got[3].view(torch.int32), dense[3].view(torch.int32)), (w.name, "dbias")
+        else:
+            assert max_abs(to_f64(got[3]), to_f64(dense[3])) <= 1e-3 * max(1.0, float(dense[3].abs().max())), (w.name, "dbias")
     ref = oracle.backward(x["q"], x["k"], x["v"], x["d_o"], w.heads, w.scale, bias,
                           oracle.mask_from_labels(labels, value), want_dbias=want_dbias)
     errs = {}
@@ -131,7 +137,11 @@ BWD = [
     ("coop_s1", 256, 49, 96, 3, "bf16", 64, True),
     ("coop_s3", 32, 49, 384, 12, "bf16", 4, True),
     ("coop_no_dbias", 128, 49, 96, 3, "bf16", 16, False),
-    ("single_wave_kernel", 64, 49, 768, 24, "bf16", 64, True),  # mask period too long for the cooperative kernel
+    # a mask period too long for the cooperative kernel: labels keep it (per-window masks), the dense form
+    # goes to the one-wave kernel
+    ("period_beyond_the_slots", 64, 49, 768, 24, "bf16", 64, True),
+    ("period_beyond_the_slots_3_heads", 1024, 49, 96, 3, "bf16", 512, True),
+    ("period_beyond_the_slots_L25", 1536, 25, 64, 2, "bf16", 768, False),
     ("ragged_L23", 12, 23, 64, 2, "bf16", 4, True),
     ("large_L144", 16, 144, 96, 3, "bf16", 4, True),
     ("large_L144_no_dbias", 8, 144, 64, 2, "bf16", 2, False),
@@ -148,7 +158,7 @@ BWD = [
 @pytest.mark.parametrize("use_bias", [True, False])
 def test_backward(oracle, name, N, L, C, heads, dtype, nW, dbias, use_bias):
     check_backward(oracle, workload("lab_" + name, N, L, C, heads, dtype, 7500 + L, backward=True), nW, use_bias,
-                   7600 + L, dbias)
+                   7600 + L, dbias, bitwise=not name.startswith("period_beyond"))
 
 
 def test_swin_labels_reproduce_the_shift_mask_results(oracle):
@@ -288,3 +298,46 @@ def test_bf16_bias_argument_rules():
         fwa.fwa_forward(q, q.clone(), q.clone(), 3, 0.1, bias, torch.zeros((2, 49, 49), device="cuda"))
     with pytest.raises(ValueError):
         fwa.fwa_forward(q, q.clone(), q.clone(), 3, 0.1, bias[:2])
+
+
+# Mask periods that no workgroup stride over the windows can be a multiple of (more windows per image
+# than the chip holds workgroups, as on the token maps of detection and segmentation inputs).  With
+# the mask as labels the persistent kernels keep only the bias in registers and form each window's
+# mask from its labels, so the arithmetic differs in rounding order from the dense-mask call, which
+# takes another kernel: both are held to the oracle, not to each other bit for bit.
+# name, N, L, C, heads, nW
+LONG_PERIOD_FWD = [
+    ("all_heads_3", 1024, 49, 96, 3, 512),       # one workgroup per window position, three heads
+    ("all_heads_2_L25", 1024, 25, 64, 2, 1024),
+    ("all_heads_4_L64", 768, 64, 128, 4, 384),
+    ("wave_per_head_6", 1024, 49, 192, 6, 512),  # two heads per workgroup, one wave each
+    ("wave_per_head_12", 1024, 49, 384, 12, 512),
+    ("ragged_L37_8_heads", 1536, 37, 256, 8, 768),
+    ("rows_L144", 512, 144, 128, 4, 256),
+    ("rows_L256_two_parts", 256, 256, 64, 2, 128),
+    ("rows_L100_3_heads", 768, 100, 96, 3, 384),
+]
+
+
+@pytest.mark.parametrize("name,N,L,C,heads,nW", LONG_PERIOD_FWD, ids=[c[0] for c in LONG_PERIOD_FWD])
+@pytest.mark.parametrize("use_bias", [True, False])
+def test_forward_long_mask_periods(oracle, name, N, L, C, heads, nW, use_bias):
+    import torch
+    import paper_2501_06480_amd as fwa
+    w = workload("longp_" + name, N, L, C, heads, "bf16", 7700 + L + heads)
+    x = synth.draw(w)
+    labels = random_labels(nW, L, 7800 + L + heads)
+    bias = synth.normal((heads, L, L), 7900 + L, 0.5) if use_bias else None
+    q, k, v = (to_device(x, w, n) for n in ("q", "k", "v"))
+    o = fwa.fwa_forward(q, k, v, heads, w.scale, f32_device(bias), labels=torch.from_numpy(labels).cuda(), mask_value=VALUE)
+    o_dense = fwa.fwa_forward(q, k, v, heads, w.scale, f32_device(bias), f32_device(dense_of(labels, VALUE)))
+    torch.cuda.synchronize()
+    ref = oracle.forward(x["q"], x["k"], x["v"], heads, w.scale, bias, oracle.mask_from_labels(labels, VALUE))
+    got = to_f64(o)
+    assert np.isfinite(got).all()
+    err, err_dense = max_abs(got, ref), max_abs(to_f64(o_dense), ref)
+    # the two calls differ by a rounding of the additive term: at most one bf16 step of the output apart
+    apart = max_abs(got, to_f64(o_dense))
+    print(f"{w.name}: nW={nW} bias={use_bias} err={err:.2e} (dense-mask call {err_dense:.2e}, apart {apart:.2e})", flush=True)
+    assert err <= TOL["bf16"] and err_dense <= TOL["bf16"], (w.name, err, err_dense)
+    assert apart <= 2.0 ** -7 * max(1.0, np.abs(ref).max()), (w.name, apart)

@@ -21,8 +21,8 @@ ELEMENTS = 2_000_000          # cap on N*L*C per tensor: the oracle stays within
 
 def draw_case(i, long_period=False):
     """The i-th combination (a pure function of i).  long_period: mask periods of 16 to 512 windows, which
-    decide how many windows a persistent workgroup may walk and, beyond the slot count of the cooperative
-    backward, send the call to the one-wave-per-tile kernel."""
+    decide how many windows a persistent workgroup may walk; beyond the slot counts, labels make the
+    kernels form each window's mask themselves and dense masks go to the kernels without a walk."""
     r = synth.rng(424200 + i)
     dtype = "f32" if r.random() < 0.25 else "bf16"
     wide = r.random() < 0.3
@@ -121,17 +121,8 @@ def test_random_combination(oracle, c):
     # ---- backward
     g = to_device(x, w, "d_o")
     want_dbias = c["want_dbias"]
-    try:
-        dq, dk, dv, db = fwa.fwa_backward(q, k, v, g, heads, w.scale, bias_dev, mask_dev, want_dbias=want_dbias,
-                                          labels=labels_dev)
-    except fwa.FwaError as e:
-        # the one documented gap: a bf16 bias where the one-wave-per-tile backward runs (width 32,
-        # L <= 64, too few windows for a cooperative slot per mask period)
-        assert c["bias"] == "bf16" and d == 32 and L <= 64 and "unsupported" in str(e), (case_id(c), str(e))
-        print("  backward: bf16 bias rejected for the one-wave kernel; repeating with the same values in fp32", flush=True)
-        bias_dev = torch.from_numpy(bias64.astype(np.float32)).cuda()
-        dq, dk, dv, db = fwa.fwa_backward(q, k, v, g, heads, w.scale, bias_dev, mask_dev, want_dbias=want_dbias,
-                                          labels=labels_dev)
+    dq, dk, dv, db = fwa.fwa_backward(q, k, v, g, heads, w.scale, bias_dev, mask_dev, want_dbias=want_dbias,
+                                      labels=labels_dev)
     torch.cuda.synchronize()
     ref = oracle.backward(x["q"], x["k"], x["v"], x["d_o"], heads, w.scale, bias64, mask64, want_dbias=want_dbias)
     errs = {}
