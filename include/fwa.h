@@ -129,7 +129,10 @@ int fwa_backward_strided(const void* q, const void* k, const void* v, const void
  *                that of the fp32 call on the same values).  dbias stays fp32.
  * Everything else (shapes, strides, dtype, workspace, error codes, supported ranges) is as in
  * fwa_forward_strided / fwa_backward_strided, and the results are those of the same call with
- * the dense mask written out from the labels.
+ * the dense mask written out from the labels: bit for bit while nW is small enough for a
+ * workgroup to keep one mask tile for life (nW <= 256 / heads-per-workgroup, roughly), and to
+ * within a rounding of the additive term beyond, where the dense form falls back to slower
+ * kernels and this form does not (each window's mask is formed from its labels).
  */
 int fwa_forward_labels(const void* q, const void* k, const void* v, void* o,
                        int64_t N, int L, int C, int heads, float scale,
