@@ -101,7 +101,7 @@ __global__ void __launch_bounds__(64 * kCoopWavesPerTile * kCoopMaxHeads) bwd_bf
     const uint32_t goff_g = rip * row_g + col * 16u;
     const uint32_t loff = rip * stride + col;
     u32x4 pk, pv, pq, pg;
-    i32x4 plab;  // PW: labels 4 tid .. 4 tid + 3 of the requested window (0 beyond L)
+    i32x4 plab = {0, 0, 0, 0};  // PW: labels 4 tid .. 4 tid + 3 of the requested window (0 beyond L)
     auto request = [&](uint32_t w) {
         const size_t slab = ((size_t)w * L * p.ldq + (size_t)hg * hpb * kHeadDim) * 2u;
         const size_t slab_g = ((size_t)w * L * p.ldg + (size_t)hg * hpb * kHeadDim) * 2u;
@@ -110,7 +110,7 @@ __global__ void __launch_bounds__(64 * kCoopWavesPerTile * kCoopMaxHeads) bwd_bf
         pv = __builtin_amdgcn_raw_buffer_load_b128(make_rsrc((const char*)p.v + slab, slab_bytes), goff, 0, 0);
         pq = __builtin_amdgcn_raw_buffer_load_b128(make_rsrc((const char*)p.q + slab, slab_bytes), goff, 0, 0);
         pg = __builtin_amdgcn_raw_buffer_load_b128(make_rsrc((const char*)p.d_o + slab_g, slab_bytes_g), goff_g, 0, 0);
-        if (PW) plab = load_i32x4(make_rsrc(p.labels + (size_t)(w % (uint32_t)p.nW) * L, (uint32_t)L * 4u), (uint32_t)tid * 16u);
+        if (PW && wv == 0) plab = load_i32x4(make_rsrc(p.labels + (size_t)(w % (uint32_t)p.nW) * L, (uint32_t)L * 4u), (uint32_t)tid * 16u);
     };
     auto park = [&]() {
         if (rip < (uint32_t)ROWS) {

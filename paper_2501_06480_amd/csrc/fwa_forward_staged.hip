@@ -205,7 +205,7 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) fwd_bf16_persistent_kerne
                                 (4 * g + (n >> 2)) * (stride * 8u) + 4 * (n & 3);
 
     u32x4 sk[NB], sv[NB], sq[NB];
-    i32x4 slab_labels;  // PW: labels 4 tid .. 4 tid + 3 of the requested window (0 beyond L)
+    i32x4 slab_labels = {0, 0, 0, 0};  // PW: labels 4 tid .. 4 tid + 3 of the requested window (0 beyond L)
     auto request = [&](uint32_t w) {
         const size_t slab = ((size_t)w * L * p.ldq + (size_t)hg * hpb * kHeadDim) * 2u;
         const __amdgpu_buffer_rsrc_t rq = make_rsrc((const char*)p.q + slab, slab_bytes);
@@ -217,7 +217,7 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) fwd_bf16_persistent_kerne
             sq[t] = __builtin_amdgcn_raw_buffer_load_b128(rq, goff + 16 * t * row_bytes, 0, 0);
             sv[t] = __builtin_amdgcn_raw_buffer_load_b128(rv, goff + 16 * t * row_bytes, 0, 0);
         }
-        if (PW)
+        if (PW && hl == 0)  // one wave fetches them
             slab_labels = load_i32x4(make_rsrc(p.labels + (size_t)(w % (uint32_t)p.nW) * L, (uint32_t)L * 4u), (uint32_t)tid * 16u);
     };
     auto park = [&]() {
@@ -503,6 +503,7 @@ __global__ void __launch_bounds__(64 * HPB * rowpersist_waves(NB)) fwd_bf16_rowp
     };
     Slab sa, sb;
     sa.q = sb.q = u32x4{0u, 0u, 0u, 0u};
+    sa.lab = sb.lab = i32x4{0, 0, 0, 0};
     auto request = [&](Slab& d, uint32_t w) {
         const size_t tile = ((size_t)w * L * p.ldq + (size_t)grp * HPB * kHeadDim) * 2u;
         const __amdgpu_buffer_rsrc_t rk = make_rsrc((const char*)p.k + tile, tile_bytes);
@@ -515,7 +516,7 @@ __global__ void __launch_bounds__(64 * HPB * rowpersist_waves(NB)) fwd_bf16_rowp
         }
         if (active)
             d.q = __builtin_amdgcn_raw_buffer_load_b128(make_rsrc((const char*)p.q + tile, tile_bytes), off_row, 0, 0);
-        if (PW)  // tokens beyond L lie outside the descriptor: label 0, discarded with their rows and columns
+        if (PW && wave == 0)  // one wave fetches them; tokens beyond L lie outside the descriptor: label 0
             d.lab = load_i32x4(make_rsrc(p.labels + (size_t)(w % (uint32_t)p.nW) * L, (uint32_t)L * 4u), (uint32_t)tid * 16u);
     };
     auto park = [&](const Slab& d, uint32_t b) {
