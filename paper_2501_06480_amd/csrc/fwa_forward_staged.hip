@@ -27,8 +27,8 @@ struct StagedGeom {
     uint32_t heads_per_block;
 };
 
-// QS = waves per head: 1 (a wave walks all query blocks of its head) or 4 (one wave per query
-// block: a quarter of the work per wave, for calls with too few tiles to fill the chip otherwise).
+// QS = waves per head: 1 (a wave walks all query blocks of its head), 2 or 4 (a wave takes every
+// QS-th query block: less work per wave, for calls with too few tiles to fill the chip otherwise).
 template <int NB, bool BM, int QS>
 __global__ void __launch_bounds__(64 * kWavesPerBlock * QS) fwd_bf16_staged_kernel(FwdArgs p, StagedGeom gm) {
     constexpr int NB2 = (NB + 1) / 2;
@@ -72,13 +72,16 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock * QS) fwd_bf16_staged_kern
     }
     // The additive term of this wave's query blocks, requested right behind the slab so that its
     // trip to L2 overlaps the slab's trip to HBM instead of following the score products.
-    constexpr int NQ = QS == 1 ? NB : 1;  // query blocks of this wave: all, or block qs alone
+    constexpr int NQ = (NB + QS - 1) / QS;  // query blocks of this wave: qs, qs + QS, ...
     f32x4 add[NQ][NB];
     if (BM) {
         const uint32_t hh = h < (uint32_t)p.heads ? h : 0u;
         const BiasSrc rb = bias_of_head(p, hh);
         const MaskSrc msk = mask_of_window(p, w);
-        fill_rows<NQ, NB>(add, rb, msk, (uint32_t)(16 * (QS == 1 ? 0 : qs) + n), 4u * g, (uint32_t)L, kLog2e);
+        AddendGlobal rows[NQ];  // blocks beyond the last one: rows outside the tile, zeros
+#pragma unroll
+        for (int t = 0; t < NQ; ++t) rows[t] = addend_at(rb, msk, (uint32_t)(16 * (qs + QS * t) + n), 4u * g, (uint32_t)L);
+        fill_rows<NQ, NB>(add, rows, kLog2e);
     }
     uint4* const lk = lds;
     uint4* const lv = lds + ROWS * stride;
@@ -98,8 +101,8 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock * QS) fwd_bf16_staged_kern
 #pragma unroll
     for (int b = 0; b < NB; ++b) kop[b] = __builtin_bit_cast(bf16x8, lk[(16 * b + n) * stride + 4 * hl + g]);
 #pragma unroll
-    for (int b = 0; b < NQ; ++b)
-        qop[b] = __builtin_bit_cast(bf16x8, lq[(16 * (QS == 1 ? b : qs) + n) * stride + 4 * hl + g]);
+    for (int b = 0; b < NQ; ++b)  // a block beyond the last one reads inside the slab area and is never used
+        qop[b] = __builtin_bit_cast(bf16x8, lq[((16 * (qs + QS * b)) % ROWS + n) * stride + 4 * hl + g]);
     // V: A operands of O^T per pair of key blocks, channels 0..15 and 16..31.
     // lane r of a row points at V[i0 + (r >> 2)][j0 + 4 (r & 3)], i0 = first key of the 4 the lane row owns
     bf16x8 vop[NB2][2];
@@ -122,7 +125,7 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock * QS) fwd_bf16_staged_kern
 
 #pragma unroll
     for (int it = 0; it < NQ; ++it) {
-        const int qb = QS == 1 ? it : qs;
+        const int qb = qs + QS * it;
         if (16 * qb >= L) break;  // uniform
         f32x4 s[NB];
 #pragma unroll
@@ -711,6 +714,11 @@ hipError_t launch_staged_nb(const FwdArgs& a, int hpb, hipStream_t st) {
     // Fewer window-heads than the chip holds waves (4 per SIMD): one wave per query block instead of
     // one per head, so that the call is not one long round of under-occupied CUs.
     const bool few_tiles = NB > 1 && a.N * a.heads <= 4096;
+    // Without bias and mask: four waves per head while they all fit the chip at once (32 waves per CU),
+    // else two, since a second round of workgroups costs such a call more than the longer life of a
+    // wave (9 % at Swin-T stage 4).  With an additive term two waves per head need 113 VGPRs, which
+    // allows no more workgroups per CU than four do, and are 5 % slower.
+    const bool two_waves = NB > 2 && a.N * a.heads > 2048;
     if (a.bias || has_mask(a)) {
         // Persistent walk over G window positions: a multiple of nW so that a workgroup always
         // sees the same mask tile, about 4 workgroups per CU (measured best of 2..8), at least 2
@@ -760,6 +768,8 @@ hipError_t launch_staged_nb(const FwdArgs& a, int hpb, hipStream_t st) {
             hipLaunchKernelGGL((fwd_bf16_staged_kernel<NB, true, 4>), dim3(grid), dim3(4 * block), lds, st, a, gm);
         else
             hipLaunchKernelGGL((fwd_bf16_staged_kernel<NB, true, 1>), dim3(grid), dim3(block), lds, st, a, gm);
+    } else if (few_tiles && two_waves) {
+        hipLaunchKernelGGL((fwd_bf16_staged_kernel<NB, false, 2>), dim3(grid), dim3(2 * block), lds, st, a, gm);
     } else if (few_tiles) {
         hipLaunchKernelGGL((fwd_bf16_staged_kernel<NB, false, 4>), dim3(grid), dim3(4 * block), lds, st, a, gm);
     } else {
