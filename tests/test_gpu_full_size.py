@@ -101,3 +101,35 @@ def test_backward_large_windows_full_size(oracle, which):
     for a, b in zip((dq, dk, dv), lab[:3]):
         assert torch.equal(a.view(torch.int16), b.view(torch.int16))
     assert torch.equal(lab[3].view(torch.int32), torch.from_numpy(db.astype(np.float32)).cuda().view(torch.int32))
+
+
+def test_stage1_on_a_large_token_map_full_size(oracle):
+    """bench.py's long-mask-period workload (stage 1 on a 224 x 224 token map: 1024 windows per image, batch 8,
+    the mask as labels), forward and backward with dBias, on sampled windows; dBias through its row sums."""
+    import torch
+    import paper_2501_06480_amd as fwa
+    w = synth.Workload("stage1_map224", 8192, 49, 96, 3, "bf16", 1400, 7, 224, True, 3, True)
+    x = synth.draw(w)
+    assert x["labels"].shape == (1024, 49)
+    bias64 = oracle.bias_gather(x["table"], w.k)
+    q, k, v, g = (to_device(x, w, n) for n in ("q", "k", "v", "d_o"))
+    lab = torch.from_numpy(x["labels"]).cuda()
+    o = fwa.fwa_forward(q, k, v, w.heads, w.scale, f32_device(bias64), labels=lab)
+    dq, dk, dv, db = fwa.fwa_backward(q, k, v, g, w.heads, w.scale, f32_device(bias64), labels=lab, want_dbias=True)
+    torch.cuda.synchronize()
+    pick = sample_windows(w.N, 1400, 100)
+    m = mask_of_sample(x["mask"], pick)
+    want = oracle.forward(x["q"][pick], x["k"][pick], x["v"][pick], w.heads, w.scale, bias64, m)
+    err = max_abs(to_f64(o)[pick], want)
+    print(f"stage 1 on a 224 x 224 map, {len(pick)} sampled windows: forward err={err:.3e}", flush=True)
+    assert err <= TOL["bf16"]
+    ref = oracle.backward(x["q"][pick], x["k"][pick], x["v"][pick], x["d_o"][pick], w.heads, w.scale, bias64, m,
+                          want_dbias=False)
+    for name, a, b in zip(("dq", "dk", "dv"), (dq, dk, dv), ref[:3]):
+        a = to_f64(a)
+        assert np.isfinite(a).all(), name
+        check_bf16_output(a[pick], b, f"stage 1 on a 224 x 224 map {name}")
+    db = to_f64(db)
+    assert np.isfinite(db).all()
+    rows, size = np.abs(db.sum(axis=2)), np.abs(db).sum(axis=2)
+    assert (rows <= 1e-4 * size + 1e-3).all(), float(rows.max())
