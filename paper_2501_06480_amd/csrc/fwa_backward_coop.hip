@@ -260,15 +260,24 @@ __global__ void __launch_bounds__(64 * kCoopWavesPerTile * kCoopMaxHeads) bwd_bf
             const u32x2 vb = {pack_bf16(v1[0], v1[1]), pack_bf16(v1[2], v1[3])};
             const u32x2 ka = {pack_bf16(k0[0] * p.scale, k0[1] * p.scale), pack_bf16(k0[2] * p.scale, k0[3] * p.scale)};
             const u32x2 kb = {pack_bf16(k1[0] * p.scale, k1[1] * p.scale), pack_bf16(k1[2] * p.scale, k1[3] * p.scale)};
-            const __amdgpu_buffer_rsrc_t rdv = make_rsrc((char*)p.dv + tile, tile_bytes);
-            const __amdgpu_buffer_rsrc_t rdk = make_rsrc((char*)p.dk + tile, tile_bytes);
-            __builtin_amdgcn_raw_buffer_store_b64(va, rdv, off_half + 16 * jb * row_d, 0, 0);
-            __builtin_amdgcn_raw_buffer_store_b64(vb, rdv, off_half + 32 + 16 * jb * row_d, 0, 0);
-            __builtin_amdgcn_raw_buffer_store_b64(ka, rdk, off_half + 16 * jb * row_d, 0, 0);
-            __builtin_amdgcn_raw_buffer_store_b64(kb, rdk, off_half + 32 + 16 * jb * row_d, 0, 0);
+            // The rows leave through the K and V slabs, which nothing reads in phase B (only this wave
+            // touches its head's 64-byte slice of its 16 rows), and from there as whole rows.
+            u32x2* const rowv = reinterpret_cast<u32x2*>(lv + (16 * jb + n) * stride + 4 * hl);
+            u32x2* const rowk = reinterpret_cast<u32x2*>(lk + (16 * jb + n) * stride + 4 * hl);
+            rowv[g] = va;
+            rowv[4 + g] = vb;
+            rowk[g] = ka;
+            rowk[4 + g] = kb;
         }
-        __syncthreads();  // slabs and exchange area are rewritten by the next window
-        if (has_next) park();
+        __syncthreads();  // dK, dV rows complete; slabs and exchange area are rewritten by the next window
+        if (rip < (uint32_t)ROWS) {  // 16 bytes per lane, whole rows; rows beyond L are dropped by the range check
+            const size_t slab_d = ((size_t)w * L * p.ldd + (size_t)hg * hpb * kHeadDim) * 2u;
+            const uint32_t slab_bytes_d = (uint32_t)(L - 1) * row_d + hpb * 2u * kHeadDim;
+            const uint32_t goff_d = rip * row_d + col * 16u;
+            __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, lk[loff]), make_rsrc((char*)p.dk + slab_d, slab_bytes_d), goff_d, 0, 0);
+            __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, lv[loff]), make_rsrc((char*)p.dv + slab_d, slab_bytes_d), goff_d, 0, 0);
+        }
+        if (has_next) park();  // each thread overwrites the slab cells it has just read out
     }
 
     if (DB && active) {
