@@ -484,6 +484,7 @@ __global__ void __launch_bounds__(64 * HPB * rowpersist_waves(NB)) fwd_bf16_rowp
     const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const uint32_t hl = wave / W, wq = wave % W;  // head inside the workgroup, query block inside the part
     int* const llab = reinterpret_cast<int*>(lds + 2 * (2 * ROWS * STRIDE));
+    uint4* const oscratch = lds + 2 * (2 * ROWS * STRIDE) + (2 * ROWS) / 4;  // behind the labels: 1 KB per wave
     const uint32_t lb = xcd_logical_block(blockIdx.x, gm.xcd_q, gm.xcd_r);
     const uint32_t part = lb % gm.parts, bh = lb / gm.parts;
     const uint32_t grp = bh % gm.groups, bw = bh / gm.groups;
@@ -606,9 +607,25 @@ __global__ void __launch_bounds__(64 * HPB * rowpersist_waves(NB)) fwd_bf16_rowp
             hi.y = pack_bf16(o1[2] * inv, o1[3] * inv);
             const size_t tile = ((size_t)w * L * p.ldo + (size_t)h * kHeadDim) * 2u;
             const __amdgpu_buffer_rsrc_t ro = make_rsrc((char*)p.o + tile, (uint32_t)(L - 1) * row_out + 2u * kHeadDim);
-            const uint32_t off_o = (uint32_t)(16 * qb + n) * row_out + 8u * g;
-            __builtin_amdgcn_raw_buffer_store_b64(lo, ro, off_o, 0, 0);
-            __builtin_amdgcn_raw_buffer_store_b64(hi, ro, off_o + 32, 0, 0);
+            if constexpr (HPB > 1) {  // three or four heads fill the rows between them: direct stores are faster
+                const uint32_t off_o = (uint32_t)(16 * qb + n) * row_out + 8u * g;
+                __builtin_amdgcn_raw_buffer_store_b64(lo, ro, off_o, 0, 0);
+                __builtin_amdgcn_raw_buffer_store_b64(hi, ro, off_o + 32, 0, 0);
+            } else {
+            // One head per workgroup: through 1 KB of LDS of this wave's own, written in accumulator order
+            // and read back 16 bytes per lane, so that one store covers the wave's 16 rows x 64 bytes
+            // instead of two stores of 32-byte pieces (43 -> 41 us at L = 144).
+            uint4* const mine = oscratch + 64 * wave;
+            u32x2* const rowo = reinterpret_cast<u32x2*>(mine + 4 * n);
+            rowo[g] = lo;
+            rowo[4 + g] = hi;
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            const u32x4 rows = __builtin_bit_cast(u32x4, mine[lane]);
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_raw_buffer_store_b128(rows, ro, (uint32_t)(16 * qb + (lane >> 2)) * row_out + 16u * (uint32_t)(lane & 3), 0, 0);
+            }
         }
         if (has_next) park(nxt, buf ^ 1u);
     };
@@ -647,7 +664,8 @@ hipError_t launch_rowpersist_pw(const FwdArgs& a, long long G, hipStream_t st) {
     const unsigned grid = gm.G * gm.groups * gm.parts, block = 64u * (unsigned)(HPB * rowpersist_waves(NB));
     gm.xcd_q = grid / 8u;
     gm.xcd_r = grid % 8u;
-    const size_t lds = (size_t)2 * 2 * 16 * NB * (4 * HPB + 1) * 16 + (PW ? (size_t)2 * 16 * NB * 4 : 0);
+    // slabs, labels, and (one head per workgroup) 1 KB per wave for the output rows
+    const size_t lds = (size_t)2 * 2 * 16 * NB * (4 * HPB + 1) * 16 + (size_t)2 * 16 * NB * 4 + (HPB == 1 ? (size_t)(block / 64) * 1024 : 0);
     if (lds > 64 * 1024) {
         const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&fwd_bf16_rowpersist_kernel<NB, HPB, PW>),
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
