@@ -110,8 +110,8 @@ __global__ void __launch_bounds__(256) fwd_bf16_wide_kernel(FwdArgs p) {
     const uint16_t* const lvh = reinterpret_cast<const uint16_t*>(lds) + (4 * g + (n >> 2)) * SROW + 4 * (n & 3);
     const __amdgpu_buffer_rsrc_t ro = make_rsrc((char*)p.o + ((size_t)w * L * p.ldo + (size_t)h * D) * 2u,
                                                 (uint32_t)(L - 1) * row_out + 2u * D);
-    const uint32_t off_o = (uint32_t)(16 * qb + n) * row_out + 8u * g;
     typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+    char* const mine = reinterpret_cast<char*>(lds + ROWS * STRIDE) + qb * (16 * 144);  // behind the slab
 #pragma unroll
     for (int cb = 0; cb < CB; ++cb) {
         f32x4 o = {0.f, 0.f, 0.f, 0.f};
@@ -119,14 +119,29 @@ __global__ void __launch_bounds__(256) fwd_bf16_wide_kernel(FwdArgs p) {
         for (int kp = 0; kp < NB2; ++kp)
             o = mfma_bf16(operand_tr(lvh + (32 * kp) * SROW + 16 * cb, 16 * SROW, 2 * kp + 1 < NB), pop[kp], o);
         const u32x2 v = {pack_bf16(o[0] * inv, o[1] * inv), pack_bf16(o[2] * inv, o[3] * inv)};
-        __builtin_amdgcn_raw_buffer_store_b64(v, ro, off_o + 32 * cb, 0, 0);
+        // Four channel blocks (64 channels, a 128-byte line per row) are gathered in LDS cells of this wave's
+        // own -- rows 144 bytes apart -- and leave as two 16-byte-per-lane stores of 8 whole lines each,
+        // instead of four stores of 32-byte pieces.
+        *reinterpret_cast<u32x2*>(mine + n * 144 + (cb & 3) * 32 + g * 8) = v;
+        if ((cb & 3) == 3) {
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                const uint32_t r = (uint32_t)(8 * i + (lane >> 3)), c = (uint32_t)(lane & 7);
+                const u32x4 rows = *reinterpret_cast<const u32x4*>(mine + r * 144 + c * 16);
+                __builtin_amdgcn_raw_buffer_store_b128(rows, ro, (uint32_t)(16 * qb + r) * row_out + 128u * (uint32_t)(cb >> 2) + 16u * c, 0, 0);
+            }
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+        }
     }
 }
 
 template <int NB, int D>
 hipError_t launch_wide_nb(const FwdArgs& a, hipStream_t st) {
     const unsigned grid = (unsigned)(a.N * a.heads);
-    const size_t lds = (size_t)16 * NB * (D / 8 + 1) * 16;  // one slab: K, then V
+    const size_t lds = (size_t)16 * NB * (D / 8 + 1) * 16 + (size_t)4 * 16 * 144;  // one slab (K, then V); output cells of the waves
     const bool bm = a.bias || has_mask(a);
     const void* fn = bm ? reinterpret_cast<const void*>(&fwd_bf16_wide_kernel<NB, D, true>)
                         : reinterpret_cast<const void*>(&fwd_bf16_wide_kernel<NB, D, false>);
