@@ -68,7 +68,24 @@ __global__ void __launch_bounds__(256) bwd_bf16_wide_kernel(BwdArgs p, uint32_t 
     const uint32_t srow = (uint32_t)tid / TPR, scol = (uint32_t)tid % TPR;  // slab movement: (row, 16 B column)
     const uint32_t opd = (uint32_t)n * STRIDE + g;                   // row operand: slab[opd + 16 b STRIDE + 4 c]
     const uint32_t trs = (4u * g + (n >> 2)) * SROW + 4u * (n & 3);  // transposing-read base inside a slab
-    const uint32_t off_half = (uint32_t)n * row_d + 8u * g;          // channels 4g..4g+3 of output row n
+    // The output rows of a wave leave through 16 x 144 bytes of LDS of its own, four 16-channel blocks
+    // (a 128-byte line per row) at a time: written in accumulator order, read back 16 bytes per lane,
+    // two stores of 8 whole lines each instead of four stores of 32-byte pieces (12 % at width 128,
+    // 8-11 % at width 64 although the 9 KB cost it one of its three workgroups per CU).
+    char* const mine = reinterpret_cast<char*>(ex + 4 * XT) + role * (16 * 144);
+    auto gather = [&](const u32x2 v, int cb) { *reinterpret_cast<u32x2*>(mine + n * 144 + (cb & 3) * 32 + g * 8) = v; };
+    auto flush = [&](const __amdgpu_buffer_rsrc_t dst, int blk, int cb) {
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const uint32_t r = (uint32_t)(8 * i + (lane >> 3)), c = (uint32_t)(lane & 7);
+            const u32x4 rows = *reinterpret_cast<const u32x4*>(mine + r * 144 + c * 16);
+            __builtin_amdgcn_raw_buffer_store_b128(rows, dst, (uint32_t)(16 * blk + r) * row_d + 128u * (uint32_t)(cb >> 2) + 16u * c, 0, 0);
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+    };
     f32x4 dbacc[NB];
 #pragma unroll
     for (int jb = 0; jb < NB; ++jb) dbacc[jb] = zero;
@@ -190,7 +207,8 @@ __global__ void __launch_bounds__(256) bwd_bf16_wide_kernel(BwdArgs p, uint32_t 
                 acc = mfma_bf16(kt, dl[kp], acc);
             }
             const u32x2 v = {pack_bf16(acc[0] * p.scale, acc[1] * p.scale), pack_bf16(acc[2] * p.scale, acc[3] * p.scale)};
-            __builtin_amdgcn_raw_buffer_store_b64(v, rdq, off_half + 16 * qb * row_d + 32 * cb, 0, 0);
+            gather(v, cb);
+            if ((cb & 3) == 3) flush(rdq, qb, cb);
         }
     }
     __syncthreads();  // K, V no longer needed; tiles complete
@@ -225,6 +243,7 @@ __global__ void __launch_bounds__(256) bwd_bf16_wide_kernel(BwdArgs p, uint32_t 
         const uint16_t* lg16 = reinterpret_cast<const uint16_t*>(sb) + trs;
         const __amdgpu_buffer_rsrc_t rdv = make_rsrc((char*)p.dv + tile_d, tile_bytes_d);
         const __amdgpu_buffer_rsrc_t rdk = make_rsrc((char*)p.dk + tile_d, tile_bytes_d);
+        u32x2 kwait[4];
 #pragma unroll
         for (int cb = 0; cb < CB; ++cb) {
             f32x4 av = zero, ak = zero;  // dV, dK [16 jb + n][16 cb + 4g + r]
@@ -240,8 +259,15 @@ __global__ void __launch_bounds__(256) bwd_bf16_wide_kernel(BwdArgs p, uint32_t 
             }
             const u32x2 vv = {pack_bf16(av[0], av[1]), pack_bf16(av[2], av[3])};
             const u32x2 vk = {pack_bf16(ak[0] * p.scale, ak[1] * p.scale), pack_bf16(ak[2] * p.scale, ak[3] * p.scale)};
-            __builtin_amdgcn_raw_buffer_store_b64(vv, rdv, off_half + 16 * jb * row_d + 32 * cb, 0, 0);
-            __builtin_amdgcn_raw_buffer_store_b64(vk, rdk, off_half + 16 * jb * row_d + 32 * cb, 0, 0);
+            // dV through the cells block by block; dK waits in registers and follows
+            gather(vv, cb);
+            kwait[cb & 3] = vk;
+            if ((cb & 3) == 3) {
+                flush(rdv, jb, cb);
+#pragma unroll
+                for (int t = 0; t < 4; ++t) gather(kwait[t], t);
+                flush(rdk, jb, cb);
+            }
         }
     }
     if (has_next) __syncthreads();  // slabs and tiles are rewritten for the next window
@@ -268,7 +294,7 @@ hipError_t launch_wide_one(const BwdArgs& a, unsigned G, size_t lds, hipStream_t
 
 template <int NB, int D>
 hipError_t launch_wide_nb(const BwdArgs& a, hipStream_t st) {
-    const size_t lds = (size_t)2 * 16 * NB * (D / 8 + 1) * 16 + (size_t)4 * 16 * NB * 64 * 2;
+    const size_t lds = (size_t)2 * 16 * NB * (D / 8 + 1) * 16 + (size_t)4 * 16 * NB * 64 * 2 + (size_t)4 * 16 * 144;
     const bool bm = a.bias || has_mask(a);
     if (a.dbias == nullptr) {
         // Width 256 (100 KB of LDS: one workgroup per CU): as many window positions as workgroups stay
