@@ -93,7 +93,22 @@ __global__ void __launch_bounds__(64 * large_waves(NB)) bwd_bf16_large_kernel(Bw
     const uint32_t opd = (uint32_t)n * STRIDE + g;                   // row operand of block b: slab[opd + 16 b STRIDE]
     const uint32_t tile_bytes_g = (uint32_t)(L - 1) * row_g + 2u * kHeadDim;
     const uint32_t tile_bytes_d = (uint32_t)(L - 1) * row_d + 2u * kHeadDim;
-    const uint32_t off_half = (uint32_t)n * row_d + 8u * g;          // channels 4g..4g+3 of output row n (+32 B: 16+4g..)
+    typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+    // 16 output rows of this wave (64 bytes each: channels 0..15 in `lo`, 16..31 in `hi`, accumulator
+    // order) leave through the wave's patch area, free whenever a block's results are ready: written
+    // there, read back 16 bytes per lane, one store of 64-byte row pieces instead of two of 32.
+    auto store_rows = [&](const u32x2_t lo, const u32x2_t hi, const __amdgpu_buffer_rsrc_t dst, int blk) {
+        char* const cell = reinterpret_cast<char*>(patch);
+        *reinterpret_cast<u32x2_t*>(cell + n * 80 + g * 8) = lo;
+        *reinterpret_cast<u32x2_t*>(cell + n * 80 + 32 + g * 8) = hi;
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        const uint32_t r = (uint32_t)(lane >> 2), c = (uint32_t)(lane & 3);
+        const u32x4 rows = *reinterpret_cast<const u32x4*>(cell + r * 80 + c * 16);
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_raw_buffer_store_b128(rows, dst, (uint32_t)(16 * blk + r) * row_d + 16u * c, 0, 0);
+    };
     typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
     for (uint32_t w = bw; w < (uint32_t)p.N; w += gm.G) {
@@ -278,9 +293,7 @@ __global__ void __launch_bounds__(64 * large_waves(NB)) bwd_bf16_large_kernel(Bw
             }
             const u32x2 lo2 = {pack_bf16(q0[0] * p.scale, q0[1] * p.scale), pack_bf16(q0[2] * p.scale, q0[3] * p.scale)};
             const u32x2 hi2 = {pack_bf16(q1[0] * p.scale, q1[1] * p.scale), pack_bf16(q1[2] * p.scale, q1[3] * p.scale)};
-            const __amdgpu_buffer_rsrc_t rdq = make_rsrc((char*)p.dq + tile_d, tile_bytes_d);
-            __builtin_amdgcn_raw_buffer_store_b64(lo2, rdq, off_half + 16 * qb * row_d, 0, 0);
-            __builtin_amdgcn_raw_buffer_store_b64(hi2, rdq, off_half + 32 + 16 * qb * row_d, 0, 0);
+            store_rows(lo2, hi2, make_rsrc((char*)p.dq + tile_d, tile_bytes_d), qb);
         }
         __syncthreads();
 
@@ -393,12 +406,8 @@ __global__ void __launch_bounds__(64 * large_waves(NB)) bwd_bf16_large_kernel(Bw
             const u32x2 vb = {pack_bf16(v1[0], v1[1]), pack_bf16(v1[2], v1[3])};
             const u32x2 ka = {pack_bf16(k0[0] * p.scale, k0[1] * p.scale), pack_bf16(k0[2] * p.scale, k0[3] * p.scale)};
             const u32x2 kb = {pack_bf16(k1[0] * p.scale, k1[1] * p.scale), pack_bf16(k1[2] * p.scale, k1[3] * p.scale)};
-            const __amdgpu_buffer_rsrc_t rdv = make_rsrc((char*)p.dv + tile_d, tile_bytes_d);
-            const __amdgpu_buffer_rsrc_t rdk = make_rsrc((char*)p.dk + tile_d, tile_bytes_d);
-            __builtin_amdgcn_raw_buffer_store_b64(va, rdv, off_half + 16 * jb * row_d, 0, 0);
-            __builtin_amdgcn_raw_buffer_store_b64(vb, rdv, off_half + 32 + 16 * jb * row_d, 0, 0);
-            __builtin_amdgcn_raw_buffer_store_b64(ka, rdk, off_half + 16 * jb * row_d, 0, 0);
-            __builtin_amdgcn_raw_buffer_store_b64(kb, rdk, off_half + 32 + 16 * jb * row_d, 0, 0);
+            store_rows(va, vb, make_rsrc((char*)p.dv + tile_d, tile_bytes_d), jb);
+            store_rows(ka, kb, make_rsrc((char*)p.dk + tile_d, tile_bytes_d), jb);
         }
         __syncthreads();  // the slabs are rewritten for the next window
     }
@@ -597,11 +606,10 @@ hipError_t launch_dbias_large(const BwdArgs& a, hipStream_t st) {
 
 template <int NB, int HB, int HM>
 hipError_t launch_large_one(const BwdArgs& a, hipStream_t st) {
-    constexpr bool BM = HB != 0 || HM != 0;
     constexpr int W = large_waves(NB);
     const void* fn = reinterpret_cast<const void*>(&bwd_bf16_large_kernel<NB, HB, HM>);
     const unsigned block = 64u * W;
-    const size_t lds = (size_t)4 * 16 * NB * 5 * 16 + (size_t)2 * 16 * NB * 4 + (BM ? (size_t)W * 16 * 68 * 4 : 0);
+    const size_t lds = (size_t)4 * 16 * NB * 5 * 16 + (size_t)2 * 16 * NB * 4 + (size_t)W * 16 * 68 * 4;  // slabs, statistics, one patch per wave
     // Workgroups one CU holds (LDS and registers decide), asked once per kernel.
     static int per_cu = 0;
     if (per_cu == 0) {
