@@ -342,17 +342,23 @@ hipError_t launch_coop_nb(const BwdArgs& a, int hpb, hipStream_t st) {
 }  // namespace
 
 // Heads per workgroup of the cooperative kernel: all of them when the row has at most 3 (the
-// slab is then whole rows: full 128-byte lines in and out); otherwise one, three 4-wave
-// workgroups per CU that run their phases independently of each other.  With one head per
-// workgroup the 64-byte halves of a line are fetched by two workgroups (measured x1.4 fetch
-// traffic even with both on one XCD), yet over the Swin-T stages with 6, 12 and 24 heads it is
-// 3-4 % faster than groups of 2 or 3 heads, which fit only one workgroup per CU.
-int coop_heads_per_block(int heads) { return heads <= kCoopMaxHeads ? heads : 1; }
+// slab is then whole rows: full 128-byte lines in and out).  Beyond that, groups of 2 (whole
+// lines) or 3 heads with one workgroup per CU, or single heads with three 4-wave workgroups per
+// CU that run their phases independently but fetch and store 64-byte halves of lines.  Measured,
+// backward with dBias: 4, 8, 16, 32 heads in pairs are 16-18 % faster than singly (Swin-B stages
+// 1-4); 6 and 12 heads in threes 14 % and 8 % faster at 8192 and 2048 windows (Swin-L stages 1, 2)
+// but 2-5 % slower at 512 and 128 windows (Swin-T stages 3, 4), where a workgroup meets too few
+// windows to make up for its longer set-up: threes from 16 windows per workgroup on.
+int coop_heads_per_block(int heads, long long N) {
+    if (heads <= kCoopMaxHeads) return heads;
+    if (heads % 3 == 0) return N * heads >= 16LL * 768 ? 3 : 1;  // windows per workgroup = N / (256 / (heads / 3))
+    return heads % 2 == 0 ? 2 : 1;
+}
 
 // Window positions walked in parallel: about one workgroup per CU (LDS allows no more), a
 // multiple of nW so that every workgroup keeps one mask tile; 0 = the kernel does not apply.
 int coop_slots(long long N, int heads, int nW) {
-    const int hpb = coop_heads_per_block(heads);
+    const int hpb = coop_heads_per_block(heads, N);
     if (hpb == 0 || nW < 1) return 0;
     const int groups = heads / hpb;
     const int per_cu = hpb == 3 ? 1 : (hpb == 2 ? 1 : 3);
@@ -363,7 +369,7 @@ int coop_slots(long long N, int heads, int nW) {
 }
 
 hipError_t launch_backward_bf16_coop(const BwdArgs& a, hipStream_t s) {
-    const int hpb = coop_heads_per_block(a.heads);
+    const int hpb = coop_heads_per_block(a.heads, a.N);
     switch ((a.L + 15) / 16) {
         case 1: return launch_coop_nb<1>(a, hpb, s);
         case 2: return launch_coop_nb<2>(a, hpb, s);
