@@ -742,6 +742,18 @@ hipError_t launch_staged_nb(const FwdArgs& a, int hpb, hipStream_t st) {
         // sees the same mask tile, about 4 workgroups per CU (measured best of 2..8), at least 2
         // windows per workgroup, and enough workgroups to cover the chip; else one window each.
         const long long nW = mask_period(a);
+        // A small call with an additive term whose workgroups of four waves per head would not all be
+        // resident at once (Swin-T stage 4: 24 heads x 128 windows): groups of 3 (or 2) heads in the
+        // row-persistent kernel instead, one workgroup per CU walking a few windows with the term in
+        // registers (13.1 against 14.2 us there, 16.5 against 17.0 us with 32 heads).
+        if (few_tiles && two_waves && a.heads > 4 && (a.heads % 3 == 0 || a.heads % 2 == 0)) {
+            const int k = a.heads % 3 == 0 ? 3 : 2;
+            const long long grp = a.heads / k;
+            long long G1 = (256 / grp) / nW * nW;
+            if (G1 > a.N / 2) G1 = (a.N / 2) / nW * nW;
+            if (G1 >= nW && G1 > 0 && G1 * grp >= 128)
+                return k == 3 ? launch_rowpersist_hpb<NB, 3>(a, G1, st, false) : launch_rowpersist_hpb<NB, 2>(a, G1, st, false);
+        }
         // All heads of a window in one workgroup (2..4 heads): one wave per head and query block, one
         // workgroup per CU, two windows in flight per workgroup (measured 3 % faster on Swin-T stage 1
         // than one wave per head, and slower than it with more than one workgroup per CU).
