@@ -348,10 +348,13 @@ hipError_t launch_coop_nb(const BwdArgs& a, int hpb, hipStream_t st) {
 // backward with dBias: 4, 8, 16, 32 heads in pairs are 16-18 % faster than singly (Swin-B stages
 // 1-4); 6 and 12 heads in threes 14 % and 8 % faster at 8192 and 2048 windows (Swin-L stages 1, 2)
 // but 2-5 % slower at 512 and 128 windows (Swin-T stages 3, 4), where a workgroup meets too few
-// windows to make up for its longer set-up: threes from 16 windows per workgroup on.
+// windows to make up for its longer set-up: threes from 16 windows per workgroup on.  With 48
+// heads (Swin-L stage 4, 128 windows) threes are 8 % faster already at 8 windows per workgroup
+// (24 heads at 256 windows: no difference either way).
 int coop_heads_per_block(int heads, long long N) {
     if (heads <= kCoopMaxHeads) return heads;
-    if (heads % 3 == 0) return N * heads >= 16LL * 768 ? 3 : 1;  // windows per workgroup = N / (256 / (heads / 3))
+    if (heads % 3 == 0)   // windows per workgroup = N / (256 / (heads / 3))
+        return (N * heads >= 16LL * 768 || (heads >= 48 && N * heads >= 8LL * 768)) ? 3 : 1;
     return heads % 2 == 0 ? 2 : 1;
 }
 

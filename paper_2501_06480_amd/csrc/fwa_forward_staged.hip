@@ -756,8 +756,10 @@ hipError_t launch_staged_nb(const FwdArgs& a, int hpb, hipStream_t st) {
         }
         // All heads of a window in one workgroup (2..4 heads): one wave per head and query block, one
         // workgroup per CU, two windows in flight per workgroup (measured 3 % faster on Swin-T stage 1
-        // than one wave per head, and slower than it with more than one workgroup per CU).
-        if (groups == 1 && hpb > 1) {
+        // than one wave per head, and slower than it with more than one workgroup per CU).  Not for 4
+        // heads beyond the small calls: there two 4-wave workgroups per CU of the kernel below are
+        // 5-8 % faster than one of 16 waves (82.6 against 86.8 us at 8192 windows, 43.2 against 46.8 at 4096).
+        if (groups == 1 && hpb > 1 && (hpb < 4 || few_tiles)) {
             long long G1 = 256 / nW * nW;
             if (G1 > a.N / 2) G1 = (a.N / 2) / nW * nW;
             bool pw = false;

