@@ -42,6 +42,10 @@ struct LargeGeom {
 };
 
 constexpr int large_waves(int nb) { return nb <= 10 ? 4 : 8; }
+// The dBias kernel: 16 waves from L = 161 on, one key block each, so that its accumulator is 64 registers
+// and a SIMD holds four waves (8 waves of two key blocks each, two per SIMD: 4-7 % slower at L = 196 and 256);
+// up to L = 160 four waves (eight: 2-6 % slower).
+constexpr int dbias_waves(int nb) { return nb <= 10 ? 4 : 16; }
 
 __device__ __forceinline__ bf16x8 pair_operand(bf16x4 a, bf16x4 b) {
     const uint2 ua = __builtin_bit_cast(uint2, a), ub = __builtin_bit_cast(uint2, b);
@@ -422,9 +426,9 @@ __global__ void __launch_bounds__(64 * large_waves(NB)) bwd_bf16_large_kernel(Bw
 // windows bw, bw + G, ... and writes them out once, in register order, as one of G partial
 // sums per head (the reduce kernel adds the slots in a fixed order).
 template <int NB, int HB, int HM>
-__global__ void __launch_bounds__(64 * large_waves(NB)) dbias_large_kernel(BwdArgs p, LargeGeom gm) {
+__global__ void __launch_bounds__(64 * dbias_waves(NB)) dbias_large_kernel(BwdArgs p, LargeGeom gm) {
     constexpr bool BM = HB != 0 || HM != 0;
-    constexpr int W = large_waves(NB);
+    constexpr int W = dbias_waves(NB);
     constexpr int JPW = (NB + W - 1) / W;  // key blocks per wave
     constexpr int NB2 = (NB + 1) / 2;
     constexpr int ROWS = 16 * NB;
@@ -512,41 +516,46 @@ __global__ void __launch_bounds__(64 * large_waves(NB)) dbias_large_kernel(BwdAr
                 f32x4 oM[2][2], oD[2][2], ab[2][2], am[2][2];
                 i32x4 al[2][2];
                 const int lkey = HM == 2 ? load_i32(rl, jcol * 4u) : 0;
-                auto fetch = [&](int qp, int slot) {
+                auto fetch_one = [&](int qb, int slot, int u) {
+                    oq[slot][u] = __builtin_bit_cast(bf16x8, lq[opd + 16 * qb * STRIDE]);
+                    og[slot][u] = __builtin_bit_cast(bf16x8, lg[opd + 16 * qb * STRIDE]);
+                    oM[slot][u] = *reinterpret_cast<const f32x4*>(stM + 16 * qb + 4 * g);
+                    oD[slot][u] = *reinterpret_cast<const f32x4*>(stD + 16 * qb + 4 * g);
+                    if (BM) {
+                        const uint32_t qrow = (uint32_t)(16 * qb) * L;
+                        const __amdgpu_buffer_rsrc_t rbq =
+                            HB == 1 ? make_rsrc(static_cast<const float*>(p.bias) + (size_t)h * L * L + qrow, ll - 4u * qrow)
+                                    : make_rsrc(nullptr, 0);
+                        const __amdgpu_buffer_rsrc_t rmq =
+                            HM == 1 ? make_rsrc(p.mask + (size_t)(w % (uint32_t)p.nW) * L * L + qrow, ll - 4u * qrow)
+                                    : make_rsrc(nullptr, 0);
 #pragma unroll
-                    for (int u = 0; u < 2; ++u) {
-                        if (u == 1 && 2 * qp + 1 >= NB) break;
-                        const int qb = 2 * qp + u;
-                        oq[slot][u] = __builtin_bit_cast(bf16x8, lq[opd + 16 * qb * STRIDE]);
-                        og[slot][u] = __builtin_bit_cast(bf16x8, lg[opd + 16 * qb * STRIDE]);
-                        oM[slot][u] = *reinterpret_cast<const f32x4*>(stM + 16 * qb + 4 * g);
-                        oD[slot][u] = *reinterpret_cast<const f32x4*>(stD + 16 * qb + 4 * g);
-                        if (BM) {
-                            const uint32_t qrow = (uint32_t)(16 * qb) * L;
-                            const __amdgpu_buffer_rsrc_t rbq =
-                                HB == 1 ? make_rsrc(static_cast<const float*>(p.bias) + (size_t)h * L * L + qrow, ll - 4u * qrow)
-                                        : make_rsrc(nullptr, 0);
-                            const __amdgpu_buffer_rsrc_t rmq =
-                                HM == 1 ? make_rsrc(p.mask + (size_t)(w % (uint32_t)p.nW) * L * L + qrow, ll - 4u * qrow)
-                                        : make_rsrc(nullptr, 0);
-#pragma unroll
-                            for (int r = 0; r < 4; ++r) {
-                                if (HB == 1) ab[slot][u][r] = load_f32(rbq, aoff[r]);
-                                if (HM == 1) am[slot][u][r] = load_f32(rmq, aoff[r]);
-                            }
-                            if (HM == 2) al[slot][u] = load_i32x4(rl, (uint32_t)(16 * qb + 4 * g) * 4u);
+                        for (int r = 0; r < 4; ++r) {
+                            if (HB == 1) ab[slot][u][r] = load_f32(rbq, aoff[r]);
+                            if (HM == 1) am[slot][u][r] = load_f32(rmq, aoff[r]);
                         }
+                        if (HM == 2) al[slot][u] = load_i32x4(rl, (uint32_t)(16 * qb + 4 * g) * 4u);
                     }
                 };
-                fetch(0, 0);
+                auto fetch = [&](int qp, int slot) {
+                    fetch_one(2 * qp, slot, 0);
+                    if (2 * qp + 1 < NB) fetch_one(2 * qp + 1, slot, 1);
+                };
+                // operands of the next pair of query blocks on their way during the arithmetic of this one;
+                // not where the SIMD holds four waves that cover for one another and have 128 registers
+                // each: there one block at a time
+                constexpr bool AHEAD = W < 16;
+                if (AHEAD) fetch(0, 0);
 #pragma unroll
                 for (int qp = 0; qp < NB2; ++qp) {
-                    const int cur = qp & 1;
-                    if (qp + 1 < NB2) fetch(qp + 1, cur ^ 1);
+                    const int cur = AHEAD ? (qp & 1) : 0;
+                    if (AHEAD && qp + 1 < NB2) fetch(qp + 1, cur ^ 1);
                     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                    for (int u = 0; u < 2; ++u) {
-                        if (u == 1 && 2 * qp + 1 >= NB) break;
+                    for (int v = 0; v < 2; ++v) {
+                        if (v == 1 && 2 * qp + 1 >= NB) break;
+                        if (!AHEAD) fetch_one(2 * qp + v, 0, 0);
+                        const int u = AHEAD ? v : 0;
                         const f32x4 sc = mfma_bf16(oq[cur][u], kop, zero);  // <q_i, k_j>, i = 16 qb + 4g + r, j = jcol
                         const f32x4 dp = mfma_bf16(og[cur][u], vop, zero);
 #pragma unroll
@@ -561,7 +570,7 @@ __global__ void __launch_bounds__(64 * large_waves(NB)) dbias_large_kernel(BwdAr
                                 x = fmaf(sc[r], sl2, -oM[cur][u][r]);
                             }
                             const float pr = valid ? __builtin_amdgcn_exp2f(x) : 0.f;
-                            dbacc[a][2 * qp + u][r] += pr * (dp[r] - oD[cur][u][r]);
+                            dbacc[a][2 * qp + v][r] += pr * (dp[r] - oD[cur][u][r]);
                         }
                     }
                     __builtin_amdgcn_sched_barrier(0);
@@ -586,7 +595,7 @@ __global__ void __launch_bounds__(64 * large_waves(NB)) dbias_large_kernel(BwdAr
 
 template <int NB, int HB, int HM>
 hipError_t launch_dbias_large(const BwdArgs& a, hipStream_t st) {
-    constexpr int W = large_waves(NB);
+    constexpr int W = dbias_waves(NB);
     const void* fn = reinterpret_cast<const void*>(&dbias_large_kernel<NB, HB, HM>);
     const unsigned block = 64u * W;
     const size_t lds = (size_t)4 * 16 * NB * 5 * 16 + (size_t)2 * 16 * NB * 4;
