@@ -42,10 +42,12 @@ struct LargeGeom {
 };
 
 constexpr int large_waves(int nb) { return nb <= 10 ? 4 : 8; }
-// The dBias kernel: 16 waves from L = 161 on, one key block each, so that its accumulator is 64 registers
-// and a SIMD holds four waves (8 waves of two key blocks each, two per SIMD: 4-7 % slower at L = 196 and 256);
-// up to L = 160 four waves (eight: 2-6 % slower).
-constexpr int dbias_waves(int nb) { return nb <= 10 ? 4 : 16; }
+// The dBias kernel: one key block per wave, so that the accumulator is at most 64 registers and a SIMD holds
+// four waves -- one workgroup of 16 waves per CU from L = 161 on (8 waves of two key blocks each, two per
+// SIMD: 4-7 % slower over the call at L = 196 and 256), two workgroups of up to 8 waves per CU up to L = 128
+// (four waves of two key blocks: 4-5 % slower at L = 81 and 100).  L = 129..160 would need 18 or 20 waves
+// per CU for its two workgroups and keeps four waves of three key blocks (9 waves: 2 % slower, 5: 6 %).
+constexpr int dbias_waves(int nb) { return nb <= 8 ? nb : (nb <= 10 ? 4 : 16); }
 
 __device__ __forceinline__ bf16x8 pair_operand(bf16x4 a, bf16x4 b) {
     const uint2 ua = __builtin_bit_cast(uint2, a), ub = __builtin_bit_cast(uint2, b);
@@ -542,9 +544,9 @@ __global__ void __launch_bounds__(64 * dbias_waves(NB)) dbias_large_kernel(BwdAr
                     if (2 * qp + 1 < NB) fetch_one(2 * qp + 1, slot, 1);
                 };
                 // operands of the next pair of query blocks on their way during the arithmetic of this one;
-                // not where the SIMD holds four waves that cover for one another and have 128 registers
-                // each: there one block at a time
-                constexpr bool AHEAD = W < 16;
+                // not where a wave has one key block and the SIMD holds four waves that cover for one
+                // another, with 128 registers each: there one block at a time
+                constexpr bool AHEAD = JPW > 1;
                 if (AHEAD) fetch(0, 0);
 #pragma unroll
                 for (int qp = 0; qp < NB2; ++qp) {
