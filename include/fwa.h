@@ -25,10 +25,21 @@
  *  - dtype is FWA_F32 (fp32 data, fp32 arithmetic) or FWA_BF16 (bf16 data,
  *    bf16 matrix-core products with fp32 accumulation, fp32 softmax, one final
  *    round-to-nearest-even to bf16).
- *  - bias, mask, dbias are always fp32.
- *  - Base pointers must be 16-byte aligned.  Outputs must not alias inputs.
+ *  - mask and dbias are always fp32; bias is fp32, or bf16 through the
+ *    *_labels entry points (bias_dtype).
+ *  - Base pointers must be 16-byte aligned.  No output may share a byte with an
+ *    input or with another output (FWA_ERR_ALIAS).  For row-strided tensors of
+ *    one stride -- the q/k/v or dq/dk/dv views of one fused buffer -- the test is
+ *    exact: rows may interleave.  Tensors of different strides whose address
+ *    extents intersect are rejected even if their rows happen not to touch.
  *  - The return value is FWA_OK or an error code; on error nothing has been
- *    launched.  No global state; calls are thread-safe.
+ *    launched.
+ *  - Calls are thread-safe.  The only state the library keeps is per kernel and
+ *    device, behind atomics: whether the runtime has been told that the kernel
+ *    may use more than 64 KB of LDS (hipFuncSetAttribute), how many of its
+ *    workgroups fit a compute unit, and the device's compute-unit count.  These
+ *    are asked on the first call that needs them, so a caller that records calls
+ *    into a HIP graph makes one call of the same shape outside the capture first.
  */
 #ifndef FWA_H
 #define FWA_H
@@ -50,7 +61,7 @@ enum {
     FWA_ERR_ALIGN = 4,       /* a base pointer is not 16-byte aligned               */
     FWA_ERR_WORKSPACE = 5,   /* workspace missing or smaller than required          */
     FWA_ERR_LAUNCH = 6,      /* the HIP runtime refused the launch                  */
-    FWA_ERR_ALIAS = 7        /* an output pointer equals another argument           */
+    FWA_ERR_ALIAS = 7        /* an output shares memory with another argument       */
 };
 
 /*

@@ -18,7 +18,7 @@ from . import binding
 def _check_dbias_supported(q, heads, bias):
     if bias is not None and bias.requires_grad:
         N, L, C = q.shape
-        if binding.fwa_backward_workspace_bytes(max(N, 1), L, C, heads, binding.FWA_BF16, True) == 0 and N > 0:
+        if binding.fwa_backward_workspace_bytes(max(N, 1), L, C, heads, binding._dtype_code(q), True) == 0 and N > 0:
             raise NotImplementedError("the gradient of the bias is not available for this shape and dtype")
 
 

@@ -143,6 +143,28 @@ def _stream_handle(stream, device) -> int:
     return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
 
 
+class _alloc_on:
+    """Allocate from torch's caching allocator as work of `stream`: a block handed out under
+    another stream could be given to other work while the kernels enqueued on `stream` still use
+    it.  `stream` = None (the current stream) needs nothing."""
+
+    def __init__(self, stream, device):
+        torch = _torch()
+        if stream is None:
+            self.ctx = None
+        else:
+            ts = stream if hasattr(stream, "cuda_stream") else torch.cuda.ExternalStream(int(stream), device=device)
+            self.ctx = torch.cuda.stream(ts)
+
+    def __enter__(self):
+        if self.ctx is not None:
+            self.ctx.__enter__()
+
+    def __exit__(self, *exc):
+        if self.ctx is not None:
+            self.ctx.__exit__(*exc)
+
+
 class _on_device:
     """Make `device` current for the duration of the call, only if it is not already."""
 
@@ -189,7 +211,11 @@ def fwa_forward(q, k, v, heads: int, scale: float, bias=None, mask=None, out=Non
     kernels form M[i][j] = 0 if labels agree else `mask_value`."""
     lib = _lib if _lib is not None else load_library()
     N, L, C = q.shape
-    o = _torch().empty_like(q, memory_format=_torch().contiguous_format) if out is None else out
+    if out is None:
+        with _alloc_on(stream, q.device):
+            o = _torch().empty_like(q, memory_format=_torch().contiguous_format)
+    else:
+        o = out
     nW = 0 if mask is None else int(mask.shape[0])
     bp, bias_code = _bias_ptr(bias, heads, L)
     if mask is not None and tuple(mask.shape) != (nW, L, L):
@@ -241,11 +267,12 @@ def fwa_backward(q, k, v, d_o, heads: int, scale: float, bias=None, mask=None, w
     import torch
     lib = load_library()
     N, L, C = q.shape
-    if out is None:
-        dq, dk, dv = (torch.empty_like(q, memory_format=torch.contiguous_format) for _ in range(3))
-    else:
-        dq, dk, dv = out
-    dbias = torch.empty((heads, L, L), dtype=torch.float32, device=q.device) if want_dbias else None
+    with _alloc_on(stream, q.device):
+        if out is None:
+            dq, dk, dv = (torch.empty_like(q, memory_format=torch.contiguous_format) for _ in range(3))
+        else:
+            dq, dk, dv = out
+        dbias = torch.empty((heads, L, L), dtype=torch.float32, device=q.device) if want_dbias else None
     nW = 0 if mask is None else int(mask.shape[0])
     bp, bias_code = _bias_ptr(bias, heads, L)
     if mask is not None and tuple(mask.shape) != (nW, L, L):
@@ -255,7 +282,8 @@ def fwa_backward(q, k, v, d_o, heads: int, scale: float, bias=None, mask=None, w
     need = fwa_backward_workspace_bytes(N, L, C, heads, _dtype_code(q), want_dbias)
     # needed for dBias, and above 64 tokens for the fp32 copy the library makes of a bf16 bias
     if workspace is None and need and (want_dbias or (bias_code == FWA_BF16 and L > 64)):
-        workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+        with _alloc_on(stream, q.device):
+            workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     tail = (bp, _dev_ptr(mask, "mask", f32=True), nW, _dtype_code(q),
             None if workspace is None else workspace.data_ptr(), ws_bytes, _stream_handle(stream, q.device))

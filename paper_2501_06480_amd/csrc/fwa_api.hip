@@ -3,6 +3,62 @@
 #include "../../include/fwa.h"
 #include "fwa_internal.h"
 
+namespace fwa {
+
+namespace {
+constexpr int kDeviceSlots = 64;
+std::atomic<int> g_cu_count[kDeviceSlots];  // 0 = not asked yet
+
+// kernel -> devices on which its dynamic-LDS limit has been lifted: an open-addressing table that
+// only ever grows (a few hundred kernels exist), filled with compare-and-swap
+constexpr unsigned kKernelSlots = 4096;
+std::atomic<const void*> g_lds_kernel[kKernelSlots];
+std::atomic<uint64_t> g_lds_devices[kKernelSlots];
+}  // namespace
+
+int cu_count() {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0) {
+        (void)hipGetLastError();  // no device: not an error the next call should see
+        return 256;
+    }
+    std::atomic<int>& slot = g_cu_count[dev % kDeviceSlots];
+    int n = slot.load(std::memory_order_relaxed);
+    if (n > 0) return n;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1) {
+        (void)hipGetLastError();
+        return 256;
+    }
+    slot.store(n, std::memory_order_relaxed);
+    return n;
+}
+
+hipError_t allow_lds(const void* fn, size_t lds_bytes) {
+    if (lds_bytes <= 64 * 1024) return hipSuccess;
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    const uint64_t bit = (uint64_t)1 << (dev & 63);
+    unsigned i = (unsigned)((reinterpret_cast<uintptr_t>(fn) >> 4) * 2654435761u) % kKernelSlots;
+    for (unsigned probes = 0; probes < kKernelSlots; ++probes, i = (i + 1) % kKernelSlots) {
+        const void* key = g_lds_kernel[i].load(std::memory_order_acquire);
+        if (key == nullptr) {
+            const void* expected = nullptr;
+            if (g_lds_kernel[i].compare_exchange_strong(expected, fn, std::memory_order_acq_rel)) key = fn;
+            else key = expected;
+        }
+        if (key != fn) continue;
+        if (g_lds_devices[i].load(std::memory_order_acquire) & bit) return hipSuccess;
+        e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e == hipSuccess) g_lds_devices[i].fetch_or(bit, std::memory_order_release);
+        return e;
+    }
+    // table full (cannot happen with this library's kernel count): ask every time
+    return hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+}
+
+}  // namespace fwa
+
 namespace {
 
 inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
@@ -52,6 +108,27 @@ int check_row_stride(int64_t ld, int C, int dtype) {
     return FWA_OK;
 }
 
+// A row-strided [N, L, C] tensor as the bytes it touches: rows of `width` bytes every `ld` bytes.
+struct Span {
+    uintptr_t base;
+    uint64_t ld, width, rows;
+    uintptr_t end() const { return base + (rows - 1) * ld + width; }
+};
+Span span_of(const void* p, int64_t N, int L, int C, int64_t ld, int dtype) {
+    const uint64_t e = dtype == FWA_BF16 ? 2 : 4;
+    return Span{reinterpret_cast<uintptr_t>(p), (uint64_t)ld * e, (uint64_t)C * e, (uint64_t)N * (uint64_t)L};
+}
+// Whether two such tensors share a byte.  Tensors whose extents are disjoint do not.  With equal row
+// strides (the views of one fused [N, L, 3, heads, d] buffer) the test is exact: rows interleave
+// without touching iff the bases differ, modulo the stride, by at least a row width either way.
+// Extents that intersect under different strides are reported as overlapping (conservative).
+bool overlaps(const Span& a, const Span& b) {
+    if (a.end() <= b.base || b.end() <= a.base) return false;
+    if (a.ld != b.ld) return true;
+    const uint64_t d = (a.base >= b.base ? a.base - b.base : b.base - a.base) % a.ld;
+    return d < a.width || a.ld - d < a.width;
+}
+
 // The mask comes as a dense tile per window position or as region labels, never both.
 int check_mask(int64_t N, const void* mask, const void* labels, int nW) {
     if (mask == nullptr && labels == nullptr) return FWA_OK;
@@ -76,7 +153,12 @@ int forward_impl(const void* q, const void* k, const void* v, void* o, int64_t N
     if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(o) || misaligned(bias) || misaligned(mask) ||
         misaligned(labels))
         return FWA_ERR_ALIGN;
-    if (o == q || o == k || o == v) return FWA_ERR_ALIAS;
+    {
+        const Span so = span_of(o, N, L, C, ld_o, dtype);
+        const void* ins[3] = {q, k, v};
+        for (const void* in : ins)
+            if (overlaps(so, span_of(in, N, L, C, ld_qkv, dtype))) return FWA_ERR_ALIAS;
+    }
     fwa::FwdArgs a;
     a.q = q; a.k = k; a.v = v; a.o = o;
     a.bias = bias; a.bias_bf16 = bias && bias_dtype == FWA_BF16;
@@ -200,22 +282,51 @@ int backward_impl(const void* q, const void* k, const void* v, const void* d_o, 
         misaligned(dv) || misaligned(dbias) || misaligned(bias) || misaligned(mask) || misaligned(labels) ||
         misaligned(workspace))
         return FWA_ERR_ALIGN;
-    const void* ins[4] = {q, k, v, d_o};
-    void* outs[3] = {dq, dk, dv};
-    for (int a = 0; a < 3; ++a) {
-        for (int b = 0; b < 4; ++b)
-            if (outs[a] == ins[b]) return FWA_ERR_ALIAS;
-        for (int b = a + 1; b < 3; ++b)
-            if (outs[a] == outs[b]) return FWA_ERR_ALIAS;
+    {
+        const Span ins[4] = {span_of(q, N, L, C, ld_qkv, dtype), span_of(k, N, L, C, ld_qkv, dtype),
+                             span_of(v, N, L, C, ld_qkv, dtype), span_of(d_o, N, L, C, ld_do, dtype)};
+        const Span outs[3] = {span_of(dq, N, L, C, ld_dqkv, dtype), span_of(dk, N, L, C, ld_dqkv, dtype),
+                              span_of(dv, N, L, C, ld_dqkv, dtype)};
+        for (int a = 0; a < 3; ++a) {
+            for (int b = 0; b < 4; ++b)
+                if (overlaps(outs[a], ins[b])) return FWA_ERR_ALIAS;
+            for (int b = a + 1; b < 3; ++b)
+                if (overlaps(outs[a], outs[b])) return FWA_ERR_ALIAS;
+        }
+        if (dbias) {  // one contiguous row of heads * L * L floats
+            const uint64_t bytes = (uint64_t)heads * L * L * sizeof(float);
+            const Span sd = Span{reinterpret_cast<uintptr_t>(dbias), bytes, bytes, 1};
+            for (int b = 0; b < 4; ++b)
+                if (overlaps(sd, ins[b])) return FWA_ERR_ALIAS;
+            for (int b = 0; b < 3; ++b)
+                if (overlaps(sd, outs[b])) return FWA_ERR_ALIAS;
+            const uint64_t bias_bytes = bias_dtype == FWA_BF16 ? bytes / 2 : bytes;
+            if (bias && overlaps(sd, Span{reinterpret_cast<uintptr_t>(bias), bias_bytes, bias_bytes, 1})) return FWA_ERR_ALIAS;
+        }
     }
+    fwa::BwdArgs a;
+    a.q = q; a.k = k; a.v = v; a.d_o = d_o;
+    a.dq = dq; a.dk = dk; a.dv = dv; a.dbias = dbias;
+    a.mask = mask; a.labels = labels; a.mask_value = mask_value;
+    a.N = N; a.L = L; a.C = C; a.heads = heads; a.nW = (mask || labels) ? nW : 1; a.scale = scale;
+    // A mask period that no slot count of the cooperative kernel is a multiple of: with the mask as
+    // labels the kernel forms each window's mask itself and its workgroups walk the windows as if
+    // there were no period; with a dense mask the one-wave-per-tile kernel takes the call.
+    const bool large = L > fwa::kMaxBackwardL;
+    const bool small = dtype == FWA_BF16 && C / heads == fwa::kHeadDim && !large;
+    a.per_window = small && labels && fwa::coop_slots(N, heads, a.nW) == 0 && fwa::coop_slots(N, heads, 1) > 0;
+    a.slots = C / heads != fwa::kHeadDim ? fwa::backward_wide_slots(N, heads)
+              : large                    ? fwa::backward_large_slots(N, heads, L)
+                                         : fwa::backward_slots(N, heads, a.per_window ? 1 : a.nW);
     // workspace: [fp32 copy of a bf16 bias (large windows only)] [row statistics (large windows
     // with dBias)] [partial sums of dBias]; a call needs the parts it uses
-    const bool large = L > fwa::kMaxBackwardL;
     const bool copy_bias = large && bias && bias_dtype == FWA_BF16;
-    const size_t full = fwa_backward_workspace_bytes(N, L, C, heads, dtype, dbias != nullptr);
     const size_t copy_room = large ? large_bias_copy_bytes(L, heads) : 0;
-    const size_t need = (dbias ? full - copy_room : 0) + (copy_bias ? copy_room : 0);
-    if (need > 0 && (workspace == nullptr || workspace_bytes < need)) return FWA_ERR_WORKSPACE;
+    {
+        const size_t full = fwa_backward_workspace_bytes(N, L, C, heads, dtype, dbias != nullptr);
+        const size_t need = (dbias ? full - copy_room : 0) + (copy_bias ? copy_room : 0);
+        if (need > 0 && (workspace == nullptr || workspace_bytes < need)) return FWA_ERR_WORKSPACE;
+    }
     char* ws = static_cast<char*>(workspace);
     if (copy_bias) {
         if (fwa::launch_widen_bf16(bias, reinterpret_cast<float*>(ws), (size_t)heads * L * L, st) != hipSuccess)
@@ -224,9 +335,6 @@ int backward_impl(const void* q, const void* k, const void* v, const void* d_o, 
         bias_dtype = FWA_F32;
         ws += copy_room;
     }
-    fwa::BwdArgs a;
-    a.q = q; a.k = k; a.v = v; a.d_o = d_o;
-    a.dq = dq; a.dk = dk; a.dv = dv; a.dbias = dbias;
     a.partial = dbias ? reinterpret_cast<float*>(ws) : nullptr;
     a.stats = nullptr;
     if (dbias && large) {  // [row statistics][partial sums]
@@ -234,16 +342,6 @@ int backward_impl(const void* q, const void* k, const void* v, const void* d_o, 
         a.partial = reinterpret_cast<float*>(ws + large_stats_bytes(N, L, heads));
     }
     a.bias = bias; a.bias_bf16 = bias && bias_dtype == FWA_BF16;
-    a.mask = mask; a.labels = labels; a.mask_value = mask_value;
-    a.N = N; a.L = L; a.C = C; a.heads = heads; a.nW = (mask || labels) ? nW : 1; a.scale = scale;
-    // A mask period that no slot count of the cooperative kernel is a multiple of: with the mask as
-    // labels the kernel forms each window's mask itself and its workgroups walk the windows as if
-    // there were no period; with a dense mask the one-wave-per-tile kernel takes the call.
-    const bool small = dtype == FWA_BF16 && C / heads == fwa::kHeadDim && L <= fwa::kMaxBackwardL;
-    a.per_window = small && labels && fwa::coop_slots(N, heads, a.nW) == 0 && fwa::coop_slots(N, heads, 1) > 0;
-    a.slots = C / heads != fwa::kHeadDim ? fwa::backward_wide_slots(N, heads)
-              : L > fwa::kMaxBackwardL   ? fwa::backward_large_slots(N, heads, L)
-                                         : fwa::backward_slots(N, heads, a.per_window ? 1 : a.nW);
     a.ldq = (int)ld_qkv; a.ldg = (int)ld_do; a.ldd = (int)ld_dqkv;
     // the one-wave-per-tile kernel takes fp32 biases only
     if (a.bias_bf16 && small && !a.per_window && fwa::coop_slots(N, heads, a.nW) == 0)

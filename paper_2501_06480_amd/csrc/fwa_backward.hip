@@ -369,8 +369,8 @@ hipError_t launch_one(const BwdArgs& a, const BwdGeom& gm, unsigned grid, unsign
     const size_t lds = (size_t)(block / 64) * per_wave;
     const void* fn = pf ? reinterpret_cast<const void*>(&bwd_bf16_kernel<NB, BM, DB, true>)
                         : reinterpret_cast<const void*>(&bwd_bf16_kernel<NB, BM, DB, false>);
-    if (lds > 64 * 1024) {
-        const hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    {
+        const hipError_t e = allow_lds(fn, lds);
         if (e != hipSuccess) return e;
     }
     if (pf)
@@ -407,7 +407,7 @@ hipError_t launch_bwd_nb(const BwdArgs& a, hipStream_t st) {
 static int single_slots(long long N, int heads) {
     const int hpb = heads < kWavesPerBlock ? heads : kWavesPerBlock;
     const int groups = (heads + hpb - 1) / hpb;
-    long long slots = (256 * 8 / hpb + groups - 1) / groups;  // ~8 waves per CU over 256 CUs
+    long long slots = (cu_count() * 8 / hpb + groups - 1) / groups;  // ~8 waves per CU
     if (slots > N) slots = N;
     if (slots < 1) slots = 1;
     return (int)slots;

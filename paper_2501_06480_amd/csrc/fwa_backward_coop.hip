@@ -292,9 +292,8 @@ template <int NB, bool BM, bool DB, int KT, bool PW>
 hipError_t launch_coop_pw(const BwdArgs& a, const CoopGeom& gm, unsigned grid, unsigned block, size_t lds,
                           hipStream_t st) {
     if (PW) lds += (size_t)16 * NB * 4;  // the window's labels
-    if (lds > 64 * 1024) {
-        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&bwd_bf16_coop_kernel<NB, BM, DB, KT, PW>),
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    {
+        const hipError_t e = allow_lds(reinterpret_cast<const void*>(&bwd_bf16_coop_kernel<NB, BM, DB, KT, PW>), lds);
         if (e != hipSuccess) return e;
     }
     hipLaunchKernelGGL((bwd_bf16_coop_kernel<NB, BM, DB, KT, PW>), dim3(grid), dim3(block), lds, st, a, gm);
@@ -353,8 +352,8 @@ hipError_t launch_coop_nb(const BwdArgs& a, int hpb, hipStream_t st) {
 // (24 heads at 256 windows: no difference either way).
 int coop_heads_per_block(int heads, long long N) {
     if (heads <= kCoopMaxHeads) return heads;
-    if (heads % 3 == 0)   // windows per workgroup = N / (256 / (heads / 3))
-        return (N * heads >= 16LL * 768 || (heads >= 48 && N * heads >= 8LL * 768)) ? 3 : 1;
+    if (heads % 3 == 0)   // windows per workgroup = N / (compute units / (heads / 3))
+        return (N * heads >= 16LL * 3 * cu_count() || (heads >= 48 && N * heads >= 8LL * 3 * cu_count())) ? 3 : 1;
     return heads % 2 == 0 ? 2 : 1;
 }
 
@@ -365,7 +364,7 @@ int coop_slots(long long N, int heads, int nW) {
     if (hpb == 0 || nW < 1) return 0;
     const int groups = heads / hpb;
     const int per_cu = hpb == 3 ? 1 : (hpb == 2 ? 1 : 3);
-    long long G = (256LL * per_cu / groups) / nW * nW;
+    long long G = ((long long)cu_count() * per_cu / groups) / nW * nW;
     if (G > N) G = N / nW * nW;
     if (G < nW || G <= 0) return 0;
     return (int)G;

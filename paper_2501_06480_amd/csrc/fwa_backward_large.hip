@@ -601,8 +601,8 @@ hipError_t launch_dbias_large(const BwdArgs& a, hipStream_t st) {
     const void* fn = reinterpret_cast<const void*>(&dbias_large_kernel<NB, HB, HM>);
     const unsigned block = 64u * W;
     const size_t lds = (size_t)4 * 16 * NB * 5 * 16 + (size_t)2 * 16 * NB * 4;
-    if (lds > 64 * 1024) {
-        const hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    {
+        const hipError_t e = allow_lds(fn, lds);
         if (e != hipSuccess) return e;
     }
     LargeGeom gm;
@@ -621,21 +621,24 @@ hipError_t launch_large_one(const BwdArgs& a, hipStream_t st) {
     const void* fn = reinterpret_cast<const void*>(&bwd_bf16_large_kernel<NB, HB, HM>);
     const unsigned block = 64u * W;
     const size_t lds = (size_t)4 * 16 * NB * 5 * 16 + (size_t)2 * 16 * NB * 4 + (size_t)W * 16 * 68 * 4;  // slabs, statistics, one patch per wave
-    // Workgroups one CU holds (LDS and registers decide), asked once per kernel.
-    static int per_cu = 0;
+    // Workgroups one CU holds (LDS and registers decide), asked once per kernel; threads racing
+    // through the first call ask twice and store the same figure.
+    static std::atomic<int> per_cu_once{0};
+    {
+        const hipError_t e = allow_lds(fn, lds);
+        if (e != hipSuccess) return e;
+    }
+    int per_cu = per_cu_once.load(std::memory_order_relaxed);
     if (per_cu == 0) {
-        if (lds > 64 * 1024) {
-            const hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-            if (e != hipSuccess) return e;
-        }
         int nblk = 0;
         const hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nblk, fn, (int)block, lds);
         if (e != hipSuccess) return e;
         per_cu = nblk < 1 ? 1 : nblk;
+        per_cu_once.store(per_cu, std::memory_order_relaxed);
     }
     LargeGeom gm;
     gm.heads = (uint32_t)a.heads;
-    long long G = 256LL * per_cu / a.heads;  // one resident workgroup per slot and head
+    long long G = (long long)cu_count() * per_cu / a.heads;  // one resident workgroup per slot and head
     if (G < 1) G = 1;
     if (G > a.N) G = a.N;
     gm.G = (uint32_t)G;
@@ -670,7 +673,7 @@ hipError_t launch_large_nb(const BwdArgs& a, hipStream_t st) {
 // Slots of dBias partial sums for large windows: one resident workgroup of the dBias kernel per CU
 // when its slabs fill most of the LDS (more than 10 blocks of 16 rows), two otherwise
 int backward_large_slots(long long N, int heads, int L) {
-    long long G = (L > 160 ? 256 : 512) / heads;
+    long long G = (L > 160 ? 1 : 2) * cu_count() / heads;
     if (G < 1) G = 1;
     return (int)(G > N ? N : G);
 }

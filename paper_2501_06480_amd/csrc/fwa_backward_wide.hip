@@ -283,9 +283,8 @@ __global__ void __launch_bounds__(256) bwd_bf16_wide_kernel(BwdArgs p, uint32_t 
 
 template <int NB, int D, bool BM, bool DB>
 hipError_t launch_wide_one(const BwdArgs& a, unsigned G, size_t lds, hipStream_t st) {
-    if (lds > 64 * 1024) {
-        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&bwd_bf16_wide_kernel<NB, D, BM, DB>),
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    {
+        const hipError_t e = allow_lds(reinterpret_cast<const void*>(&bwd_bf16_wide_kernel<NB, D, BM, DB>), lds);
         if (e != hipSuccess) return e;
     }
     hipLaunchKernelGGL((bwd_bf16_wide_kernel<NB, D, BM, DB>), dim3(G * (unsigned)a.heads), dim3(256), lds, st, a, G);
@@ -301,7 +300,8 @@ hipError_t launch_wide_nb(const BwdArgs& a, hipStream_t st) {
         // resident, 5 % faster than one window per workgroup; narrower heads (2-3 workgroups per
         // CU) are 5-8 % faster with one window each.
         long long G0 = a.N;
-        if (D == 256 && a.N > 256 / a.heads) G0 = 256 / a.heads > 0 ? 256 / a.heads : 1;
+        const long long per_head = cu_count() / a.heads;
+        if (D == 256 && a.N > per_head) G0 = per_head > 0 ? per_head : 1;
         return bm ? launch_wide_one<NB, D, true, false>(a, (unsigned)G0, lds, st)
                   : launch_wide_one<NB, D, false, false>(a, (unsigned)G0, lds, st);
     }
@@ -327,7 +327,7 @@ hipError_t launch_wide_d(const BwdArgs& a, hipStream_t s) {
 // Window positions walked in parallel (= dBias slots) when dBias is wanted: two or three resident
 // workgroups per CU; never more than the single-wave kernel's count, which sizes the workspace.
 int backward_wide_slots(long long N, int heads) {
-    long long G = 512 / heads;
+    long long G = 2 * cu_count() / heads;
     if (G < 1) G = 1;
     return (int)(G > N ? N : G);
 }

@@ -324,8 +324,8 @@ hipError_t launch_fwd_nb(const FwdArgs& a, hipStream_t st) {
     const bool bm = a.bias || has_mask(a);
     const void* fn = bm ? reinterpret_cast<const void*>(&fwd_f32_tile_kernel<NB, D, true>)
                         : reinterpret_cast<const void*>(&fwd_f32_tile_kernel<NB, D, false>);
-    if (lds > 64 * 1024) {
-        const hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    {
+        const hipError_t e = allow_lds(fn, lds);
         if (e != hipSuccess) return e;
     }
     if (bm)
@@ -343,8 +343,8 @@ hipError_t launch_bwd_nb(const BwdArgs& a, hipStream_t st) {
     const size_t lds = (size_t)2 * 16 * NB * rs * 4;
     const void* fn = bm ? reinterpret_cast<const void*>(&bwd_f32_tile_kernel<NB, D, true>)
                         : reinterpret_cast<const void*>(&bwd_f32_tile_kernel<NB, D, false>);
-    if (lds > 64 * 1024) {
-        const hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    {
+        const hipError_t e = allow_lds(fn, lds);
         if (e != hipSuccess) return e;
     }
     if (bm)

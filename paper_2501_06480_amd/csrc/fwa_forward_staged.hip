@@ -642,7 +642,7 @@ template <int NB>
 long long rowpersist_slots(const FwdArgs& a, bool& pw) {
     const long long parts = NB <= 12 ? 1 : 2;
     const long long nW = mask_period(a);
-    const long long most = 256 / ((long long)a.heads * parts);
+    const long long most = cu_count() / ((long long)a.heads * parts);
     long long G = most / nW * nW;
     if (G > a.N / 2) G = (a.N / 2) / nW * nW;
     pw = false;
@@ -666,9 +666,8 @@ hipError_t launch_rowpersist_pw(const FwdArgs& a, long long G, hipStream_t st) {
     gm.xcd_r = grid % 8u;
     // slabs, labels, and (one head per workgroup) 1 KB per wave for the output rows
     const size_t lds = (size_t)2 * 2 * 16 * NB * (4 * HPB + 1) * 16 + (size_t)2 * 16 * NB * 4 + (HPB == 1 ? (size_t)(block / 64) * 1024 : 0);
-    if (lds > 64 * 1024) {
-        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&fwd_bf16_rowpersist_kernel<NB, HPB, PW>),
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    {
+        const hipError_t e = allow_lds(reinterpret_cast<const void*>(&fwd_bf16_rowpersist_kernel<NB, HPB, PW>), lds);
         if (e != hipSuccess) return e;
     }
     hipLaunchKernelGGL((fwd_bf16_rowpersist_kernel<NB, HPB, PW>), dim3(grid), dim3(block), lds, st, a, gm);
@@ -684,9 +683,8 @@ hipError_t launch_rowpersist_hpb(const FwdArgs& a, long long G, hipStream_t st, 
 template <int NB, bool BM, int QW>
 hipError_t launch_rowblock_qw(const FwdArgs& a, const RowBlockGeom& gm, unsigned grid, int hpb, size_t lds, hipStream_t st) {
     const unsigned block = 64u * (unsigned)(QW * hpb);
-    if (lds > 64 * 1024) {
-        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&fwd_bf16_rowblock_kernel<NB, BM, QW>),
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    {
+        const hipError_t e = allow_lds(reinterpret_cast<const void*>(&fwd_bf16_rowblock_kernel<NB, BM, QW>), lds);
         if (e != hipSuccess) return e;
     }
     hipLaunchKernelGGL((fwd_bf16_rowblock_kernel<NB, BM, QW>), dim3(grid), dim3(block), lds, st, a, gm);
@@ -731,12 +729,12 @@ hipError_t launch_staged_nb(const FwdArgs& a, int hpb, hipStream_t st) {
     const size_t lds = (size_t)3 * 16 * NB * (4 * hpb + 1) * 16;
     // Fewer window-heads than the chip holds waves (4 per SIMD): one wave per query block instead of
     // one per head, so that the call is not one long round of under-occupied CUs.
-    const bool few_tiles = NB > 1 && a.N * a.heads <= 4096;
+    const bool few_tiles = NB > 1 && a.N * a.heads <= 16LL * cu_count();
     // Without bias and mask: four waves per head while they all fit the chip at once (32 waves per CU),
     // else two, since a second round of workgroups costs such a call more than the longer life of a
     // wave (9 % at Swin-T stage 4).  With an additive term two waves per head need 113 VGPRs, which
     // allows no more workgroups per CU than four do, and are 5 % slower.
-    const bool two_waves = NB > 2 && a.N * a.heads > 2048;
+    const bool two_waves = NB > 2 && a.N * a.heads > 8LL * cu_count();
     if (a.bias || has_mask(a)) {
         // Persistent walk over G window positions: a multiple of nW so that a workgroup always
         // sees the same mask tile, about 4 workgroups per CU (measured best of 2..8), at least 2
@@ -749,9 +747,9 @@ hipError_t launch_staged_nb(const FwdArgs& a, int hpb, hipStream_t st) {
         if (few_tiles && two_waves && a.heads > 4 && (a.heads % 3 == 0 || a.heads % 2 == 0)) {
             const int k = a.heads % 3 == 0 ? 3 : 2;
             const long long grp = a.heads / k;
-            long long G1 = (256 / grp) / nW * nW;
+            long long G1 = (cu_count() / grp) / nW * nW;
             if (G1 > a.N / 2) G1 = (a.N / 2) / nW * nW;
-            if (G1 >= nW && G1 > 0 && G1 * grp >= 128)
+            if (G1 >= nW && G1 > 0 && G1 * grp >= cu_count() / 2)
                 return k == 3 ? launch_rowpersist_hpb<NB, 3>(a, G1, st, false) : launch_rowpersist_hpb<NB, 2>(a, G1, st, false);
         }
         // All heads of a window in one workgroup (2..4 heads): one wave per head and query block, one
@@ -760,15 +758,16 @@ hipError_t launch_staged_nb(const FwdArgs& a, int hpb, hipStream_t st) {
         // heads beyond the small calls: there two 4-wave workgroups per CU of the kernel below are
         // 5-8 % faster than one of 16 waves (82.6 against 86.8 us at 8192 windows, 43.2 against 46.8 at 4096).
         if (groups == 1 && hpb > 1 && (hpb < 4 || few_tiles)) {
-            long long G1 = 256 / nW * nW;
+            const long long cus = cu_count();
+            long long G1 = cus / nW * nW;
             if (G1 > a.N / 2) G1 = (a.N / 2) / nW * nW;
             bool pw = false;
-            if (!(G1 >= nW && G1 >= 128) && a.labels != nullptr && a.N >= 256) {
+            if (!(G1 >= nW && G1 >= cus / 2) && a.labels != nullptr && a.N >= cus) {
                 // no multiple of the mask period fits: per-window masks from the labels
-                G1 = a.N / 2 < 256 ? a.N / 2 : 256;
+                G1 = a.N / 2 < cus ? a.N / 2 : cus;
                 pw = true;
             }
-            if (pw || (G1 >= nW && G1 >= 128)) {
+            if (pw || (G1 >= nW && G1 >= cus / 2)) {
                 switch (hpb) {
                     case 2: return launch_rowpersist_hpb<NB, 2>(a, G1, st, pw);
                     case 3: return launch_rowpersist_hpb<NB, 3>(a, G1, st, pw);
@@ -781,17 +780,17 @@ hipError_t launch_staged_nb(const FwdArgs& a, int hpb, hipStream_t st) {
         const long long waves_per_cu = NB == 4 ? 8 : (NB == 3 ? 12 : (NB == 2 ? 20 : 32));
         long long per_cu = waves_per_cu / hpb;
         if (per_cu > 4) per_cu = 4;
-        const long long most = per_cu * 256 / (long long)groups;
+        const long long most = per_cu * cu_count() / (long long)groups;
         long long G = most / nW * nW;
         if (G > a.N / 2) G = (a.N / 2) / nW * nW;
-        if (!few_tiles && G >= nW && G > 0 && G * groups >= 256) {
+        if (!few_tiles && G >= nW && G > 0 && G * groups >= cu_count()) {
             hipLaunchKernelGGL((fwd_bf16_persistent_kernel<NB, false>), dim3((unsigned)(G * groups)), dim3(block), lds, st,
                                a, gm, (uint32_t)G);
             return hipGetLastError();
         }
         // no multiple of the mask period fits: with the mask as labels, per-window masks from the labels
         G = most < a.N / 2 ? most : a.N / 2;
-        if (!few_tiles && a.labels != nullptr && G * groups >= 256) {
+        if (!few_tiles && a.labels != nullptr && G * groups >= cu_count()) {
             hipLaunchKernelGGL((fwd_bf16_persistent_kernel<NB, true>), dim3((unsigned)(G * groups)), dim3(block),
                                lds + (size_t)16 * NB * 4, st, a, gm, (uint32_t)G);
             return hipGetLastError();

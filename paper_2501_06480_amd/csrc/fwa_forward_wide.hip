@@ -145,8 +145,8 @@ hipError_t launch_wide_nb(const FwdArgs& a, hipStream_t st) {
     const bool bm = a.bias || has_mask(a);
     const void* fn = bm ? reinterpret_cast<const void*>(&fwd_bf16_wide_kernel<NB, D, true>)
                         : reinterpret_cast<const void*>(&fwd_bf16_wide_kernel<NB, D, false>);
-    if (lds > 64 * 1024) {
-        const hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    {
+        const hipError_t e = allow_lds(fn, lds);
         if (e != hipSuccess) return e;
     }
     if (bm)

@@ -6,6 +6,8 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <atomic>
+
 namespace fwa {
 
 constexpr int kHeadDim = 32;   // head width of every path but the wide-head kernels
@@ -69,6 +71,16 @@ template <class Args>
 inline bool has_mask(const Args& a) { return a.mask != nullptr || a.labels != nullptr; }
 template <class Args>
 inline int mask_period(const Args& a) { return has_mask(a) ? a.nW : 1; }
+
+// Compute units of the current device, asked from the runtime once per device (256 on MI355X; the
+// same figure stands in when no device answers, e.g. a workspace-size query on a machine without a
+// GPU).  Workgroup counts of the persistent kernels and dBias slot counts are derived from it.
+int cu_count();
+
+// Lifts the 64 KB limit on dynamic LDS for kernel `fn` on the current device (to the 160 KB of a
+// compute unit), once per kernel and device; a no-op for requests of at most 64 KB.  Lock-free: two
+// threads racing through a kernel's first call merely ask the runtime twice.
+hipError_t allow_lds(const void* fn, size_t lds_bytes);
 
 // Each returns a hipError_t from the launch (hipSuccess when enqueued).
 hipError_t launch_forward_bf16(const FwdArgs& a, hipStream_t s);

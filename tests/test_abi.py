@@ -42,15 +42,15 @@ def test_status_strings(lib):
     assert lib.fwa_status_string(99).decode() == "unknown status code"
 
 
-P = 0x10000  # a fake, 16-byte aligned, non-NULL "device pointer"; never dereferenced on error paths
+P = 0x10000000  # a fake, 16-byte aligned, non-NULL "device pointer"; never dereferenced on error paths
 
 
-def fwd(lib, q=P, k=P + 0x1000, v=P + 0x2000, o=P + 0x3000, N=4, L=49, C=96, heads=3, scale=0.1, bias=None,
+def fwd(lib, q=P, k=P + 0x1000000, v=P + 0x2000000, o=P + 0x3000000, N=4, L=49, C=96, heads=3, scale=0.1, bias=None,
         mask=None, nW=0, dtype=1):
     return lib.fwa_forward(q, k, v, o, N, L, C, heads, scale, bias, mask, nW, dtype, None)
 
 
-def bwd(lib, q=P, k=P + 0x1000, v=P + 0x2000, g=P + 0x3000, dq=P + 0x4000, dk=P + 0x5000, dv=P + 0x6000,
+def bwd(lib, q=P, k=P + 0x1000000, v=P + 0x2000000, g=P + 0x3000000, dq=P + 0x4000000, dk=P + 0x5000000, dv=P + 0x6000000,
         dbias=None, N=4, L=49, C=96, heads=3, scale=0.1, bias=None, mask=None, nW=0, dtype=1, ws=None,
         ws_bytes=0):
     return lib.fwa_backward(q, k, v, g, dq, dk, dv, dbias, N, L, C, heads, scale, bias, mask, nW, dtype, ws,
@@ -69,8 +69,8 @@ def test_forward_rejects_bad_arguments(lib):
     assert fwd(lib, C=192, heads=3, L=65) == b.FWA_ERR_UNSUPPORTED      # head dim 64 beyond one tile
     assert fwd(lib, L=257) == b.FWA_ERR_UNSUPPORTED
     assert fwd(lib, dtype=2) == b.FWA_ERR_UNSUPPORTED
-    assert fwd(lib, mask=P + 0x9000, nW=0) == b.FWA_ERR_SHAPE
-    assert fwd(lib, mask=P + 0x9000, nW=3) == b.FWA_ERR_SHAPE     # 4 % 3 != 0
+    assert fwd(lib, mask=P + 0x9000000, nW=0) == b.FWA_ERR_SHAPE
+    assert fwd(lib, mask=P + 0x9000000, nW=3) == b.FWA_ERR_SHAPE     # 4 % 3 != 0
     assert fwd(lib, q=None) == b.FWA_ERR_NULL
     assert fwd(lib, o=None) == b.FWA_ERR_NULL
     assert fwd(lib, k=P + 8) == b.FWA_ERR_ALIGN
@@ -89,12 +89,12 @@ def test_backward_rejects_bad_arguments(lib):
     assert bwd(lib, dv=None) == b.FWA_ERR_NULL
     assert bwd(lib, dq=P + 2) == b.FWA_ERR_ALIGN
     assert bwd(lib, dq=P) == b.FWA_ERR_ALIAS
-    assert bwd(lib, dk=P + 0x4000) == b.FWA_ERR_ALIAS              # dk == dq
-    assert bwd(lib, mask=P + 0x9000, nW=8) == b.FWA_ERR_SHAPE
+    assert bwd(lib, dk=P + 0x4000000) == b.FWA_ERR_ALIAS              # dk == dq
+    assert bwd(lib, mask=P + 0x9000000, nW=8) == b.FWA_ERR_SHAPE
     need = lib.fwa_backward_workspace_bytes(4, 49, 96, 3, 1, 1)
     assert need >= 3 * 64 * 64 * 4
-    assert bwd(lib, dbias=P + 0x7000) == b.FWA_ERR_WORKSPACE
-    assert bwd(lib, dbias=P + 0x7000, ws=P + 0x8000, ws_bytes=need - 1) == b.FWA_ERR_WORKSPACE
+    assert bwd(lib, dbias=P + 0x7000000) == b.FWA_ERR_WORKSPACE
+    assert bwd(lib, dbias=P + 0x7000000, ws=P + 0x8000000, ws_bytes=need - 1) == b.FWA_ERR_WORKSPACE
     assert lib.fwa_backward_workspace_bytes(4, 49, 96, 3, 1, 0) == 0
     assert lib.fwa_backward_workspace_bytes(4, 49, 100, 3, 1, 1) == 0
     assert lib.fwa_backward_workspace_bytes(0, 49, 96, 3, 1, 1) == 0
@@ -103,14 +103,14 @@ def test_backward_rejects_bad_arguments(lib):
 
 def test_bias_helpers_reject_bad_arguments(lib):
     from paper_2501_06480_amd import binding as b
-    assert lib.fwa_bias_gather(P, P + 0x1000, 0, 7, None) == b.FWA_ERR_SHAPE
-    assert lib.fwa_bias_gather(P, P + 0x1000, 3, 0, None) == b.FWA_ERR_SHAPE
-    assert lib.fwa_bias_gather(P, P + 0x1000, 3, 17, None) == b.FWA_ERR_UNSUPPORTED
+    assert lib.fwa_bias_gather(P, P + 0x1000000, 0, 7, None) == b.FWA_ERR_SHAPE
+    assert lib.fwa_bias_gather(P, P + 0x1000000, 3, 0, None) == b.FWA_ERR_SHAPE
+    assert lib.fwa_bias_gather(P, P + 0x1000000, 3, 17, None) == b.FWA_ERR_UNSUPPORTED
     assert lib.fwa_bias_gather(None, P, 3, 7, None) == b.FWA_ERR_NULL
     assert lib.fwa_bias_gather(P, P + 4, 3, 7, None) == b.FWA_ERR_ALIGN
     assert lib.fwa_bias_gather(P, P, 3, 7, None) == b.FWA_ERR_ALIAS
     assert lib.fwa_bias_scatter(P, None, 3, 7, None) == b.FWA_ERR_NULL
-    assert lib.fwa_bias_scatter(P, P + 0x1000, 3, 20, None) == b.FWA_ERR_UNSUPPORTED
+    assert lib.fwa_bias_scatter(P, P + 0x1000000, 3, 20, None) == b.FWA_ERR_UNSUPPORTED
 
 
 def test_binding_refuses_cpu_tensors():
@@ -123,15 +123,15 @@ def test_binding_refuses_cpu_tensors():
 
 def test_strided_entry_points_check_their_strides(lib):
     from paper_2501_06480_amd import binding as b
-    fwd = lambda ldq, ldo, dtype=1: lib.fwa_forward_strided(P, P + 0x1000, P + 0x2000, P + 0x3000, 4, 49, 96, 3, 0.1,
+    fwd = lambda ldq, ldo, dtype=1: lib.fwa_forward_strided(P, P + 0x1000000, P + 0x2000000, P + 0x3000000, 4, 49, 96, 3, 0.1,
                                                             ldq, ldo, None, None, 0, dtype, None)
     assert fwd(95, 96) == b.FWA_ERR_SHAPE            # rows would overlap
     assert fwd(288, 88) == b.FWA_ERR_SHAPE
     assert fwd(100, 96) == b.FWA_ERR_ALIGN           # bf16 rows must stay 16-byte aligned: multiples of 8
     assert fwd(98, 96, dtype=0) == b.FWA_ERR_ALIGN   # fp32: multiples of 4
     assert fwd(1 << 21, 96) == b.FWA_ERR_UNSUPPORTED
-    bwd = lambda ldq, ldg, ldd: lib.fwa_backward_strided(P, P + 0x1000, P + 0x2000, P + 0x3000, P + 0x4000, P + 0x5000,
-                                                         P + 0x6000, None, 4, 49, 96, 3, 0.1, ldq, ldg, ldd, None, None,
+    bwd = lambda ldq, ldg, ldd: lib.fwa_backward_strided(P, P + 0x1000000, P + 0x2000000, P + 0x3000000, P + 0x4000000, P + 0x5000000,
+                                                         P + 0x6000000, None, 4, 49, 96, 3, 0.1, ldq, ldg, ldd, None, None,
                                                          0, 1, None, 0, None)
     assert bwd(288, 90, 288) == b.FWA_ERR_SHAPE
     assert bwd(288, 96, 100) == b.FWA_ERR_ALIGN
@@ -141,22 +141,22 @@ def test_strided_entry_points_check_their_strides(lib):
 
 def test_label_entry_points_check_their_arguments(lib):
     from paper_2501_06480_amd import binding as b
-    fwd = lambda N=4, labels=P + 0x9000, nW=2, ldq=96, bias=None, bias_dtype=0: lib.fwa_forward_labels(
-        P, P + 0x1000, P + 0x2000, P + 0x3000, N, 49, 96, 3, 0.1, ldq, 96, bias, bias_dtype, labels, -100.0, nW, 1, None)
+    fwd = lambda N=4, labels=P + 0x9000000, nW=2, ldq=96, bias=None, bias_dtype=0: lib.fwa_forward_labels(
+        P, P + 0x1000000, P + 0x2000000, P + 0x3000000, N, 49, 96, 3, 0.1, ldq, 96, bias, bias_dtype, labels, -100.0, nW, 1, None)
     assert fwd(nW=0) == b.FWA_ERR_SHAPE
     assert fwd(nW=3) == b.FWA_ERR_SHAPE              # 4 % 3 != 0
-    assert fwd(labels=P + 0x9004) == b.FWA_ERR_ALIGN
+    assert fwd(labels=P + 0x9000004) == b.FWA_ERR_ALIGN
     assert fwd(ldq=95) == b.FWA_ERR_SHAPE
     assert fwd(N=0, labels=None, nW=0) == b.FWA_OK   # empty batch, no mask: no-op
-    assert fwd(bias=P + 0x7000, bias_dtype=2) == b.FWA_ERR_UNSUPPORTED   # bias is fp32 or bf16
-    assert fwd(bias=P + 0x7002, bias_dtype=1) == b.FWA_ERR_ALIGN
-    bwd = lambda labels=P + 0x9000, nW=2, dbias=None, bias=None, bias_dtype=0, N=4, heads=3: lib.fwa_backward_labels(
-        P, P + 0x1000, P + 0x2000, P + 0x3000, P + 0x4000, P + 0x5000, P + 0x6000, dbias, N, 49, 32 * heads, heads, 0.1,
+    assert fwd(bias=P + 0x7000000, bias_dtype=2) == b.FWA_ERR_UNSUPPORTED   # bias is fp32 or bf16
+    assert fwd(bias=P + 0x7000002, bias_dtype=1) == b.FWA_ERR_ALIGN
+    bwd = lambda labels=P + 0x9000000, nW=2, dbias=None, bias=None, bias_dtype=0, N=4, heads=3: lib.fwa_backward_labels(
+        P, P + 0x1000000, P + 0x2000000, P + 0x3000000, P + 0x4000000, P + 0x5000000, P + 0x6000000, dbias, N, 49, 32 * heads, heads, 0.1,
         32 * heads, 32 * heads, 32 * heads, bias, bias_dtype, labels, -100.0, nW, 1, None, 0, None)
     assert bwd(nW=8) == b.FWA_ERR_SHAPE
-    assert bwd(labels=P + 0x9008) == b.FWA_ERR_ALIGN
-    assert bwd(dbias=P + 0x7000) == b.FWA_ERR_WORKSPACE
-    assert bwd(bias=P + 0x7000, bias_dtype=3) == b.FWA_ERR_UNSUPPORTED
+    assert bwd(labels=P + 0x9000008) == b.FWA_ERR_ALIGN
+    assert bwd(dbias=P + 0x7000000) == b.FWA_ERR_WORKSPACE
+    assert bwd(bias=P + 0x7000000, bias_dtype=3) == b.FWA_ERR_UNSUPPORTED
 
 
 def test_large_window_backward_needs_a_workspace_for_a_bf16_bias(lib):
@@ -170,7 +170,35 @@ def test_large_window_backward_needs_a_workspace_for_a_bf16_bias(lib):
     assert lib.fwa_backward_workspace_bytes(16, L, 32 * heads, heads, 1, 1) > room
     assert lib.fwa_backward_workspace_bytes(16, 64, 32 * heads, heads, 1, 0) == 0
     bwd = lambda bias_dtype, ws=None, ws_bytes=0: lib.fwa_backward_labels(
-        P, P + 0x1000, P + 0x2000, P + 0x3000, P + 0x4000, P + 0x5000, P + 0x6000, None, 16, L, 32 * heads, heads, 0.1,
-        32 * heads, 32 * heads, 32 * heads, P + 0x7000, bias_dtype, None, -100.0, 0, 1, ws, ws_bytes, None)
+        P, P + 0x1000000, P + 0x2000000, P + 0x3000000, P + 0x4000000, P + 0x5000000, P + 0x6000000, None, 16, L, 32 * heads, heads, 0.1,
+        32 * heads, 32 * heads, 32 * heads, P + 0x7000000, bias_dtype, None, -100.0, 0, 1, ws, ws_bytes, None)
     assert bwd(1) == b.FWA_ERR_WORKSPACE
-    assert bwd(1, P + 0x8000, room - 1) == b.FWA_ERR_WORKSPACE
+    assert bwd(1, P + 0x8000000, room - 1) == b.FWA_ERR_WORKSPACE
+
+
+def test_overlapping_tensors_are_rejected_and_interleaved_views_are_not(lib):
+    """An output may not share a byte with an input or another output: not only equal pointers but
+    any overlap of the byte ranges is turned away, while the views of one fused [N, L, 3, heads, d]
+    buffer (equal row strides, rows interleaved) pass."""
+    from paper_2501_06480_amd import binding as b
+    N, L, C, heads = 4, 49, 96, 3
+    nbytes = N * L * C * 2
+    assert fwd(lib, o=P + nbytes - 16) == b.FWA_ERR_ALIAS           # o starts inside q's last row
+    assert fwd(lib, o=P + 0x1000000 - nbytes + 32) == b.FWA_ERR_ALIAS   # o's tail reaches into k
+    assert bwd(lib, dq=P + 0x3000000 + 64) == b.FWA_ERR_ALIAS        # dq inside d_o
+    assert bwd(lib, dv=P + 0x5000000 + nbytes - 16) == b.FWA_ERR_ALIAS   # dv starts in dk's last row
+    assert bwd(lib, dbias=P + 0x4000000 + 1024, ws=P + 0x8000000, ws_bytes=1 << 30) == b.FWA_ERR_ALIAS  # dbias inside dq
+    # fused buffers: q, k, v at base, base + C, base + 2C with row stride 3C, and the same for dq, dk, dv.
+    # The call gets past the alias check and is stopped by the next one (dbias without a workspace).
+    e = 2
+    strided = lambda dq, dk, dv, ldd=3 * C: lib.fwa_backward_strided(
+        P, P + C * e, P + 2 * C * e, P + 0x3000000, dq, dk, dv, P + 0x7000000, N, L, C, heads, 0.1, 3 * C, C, ldd,
+        None, None, 0, 1, None, 0, None)
+    G = P + 0x4000000
+    assert strided(G, G + C * e, G + 2 * C * e) == b.FWA_ERR_WORKSPACE
+    assert strided(G, G + C * e - 16, G + 2 * C * e) == b.FWA_ERR_ALIAS      # dk's rows start inside dq's rows
+    assert strided(G, G + C * e, G + 3 * C * e - 16) == b.FWA_ERR_ALIAS      # dv's rows run into the next row of dq
+    assert strided(P + 3 * C * e * 2, G + C * e, G + 2 * C * e) == b.FWA_ERR_ALIAS  # dq on top of q, two rows down
+    # different strides with intersecting extents: rejected (conservative)
+    assert strided(P + 16, G + C * e, G + 2 * C * e, ldd=4 * C) == b.FWA_ERR_ALIAS
+
