@@ -234,7 +234,14 @@ __device__ __forceinline__ float softmax_block(f32x4 (&s)[NB], float sl2, const 
     } else {
         // No bias: keep the raw products and fold the scale into the exponent,
         // p = exp2(s*sl2 - max(s*sl2)).  For sl2 >= 0 the maximum of the scaled scores is
-        // sl2 * max(s); a negative scale uses the minimum instead.
+        // sl2 * max(s); a negative scale uses the minimum instead.  A zero scale makes every
+        // score zero: the products are replaced by zeros and the multiplier by one (an infinite
+        // pad times a zero multiplier would be NaN); the branch is uniform.
+        const bool flat = sl2 == 0.f;
+        if (flat) {
+#pragma unroll
+            for (int jb = 0; jb < NB; ++jb) s[jb] = f32x4{0.f, 0.f, 0.f, 0.f};
+        }
         const float pad = sl2 >= 0.f ? -INFINITY : INFINITY;
 #pragma unroll
         for (int r = 0; r < KT; ++r)
@@ -253,8 +260,8 @@ __device__ __forceinline__ float softmax_block(f32x4 (&s)[NB], float sl2, const 
                 for (int r = 0; r < (jb == NB - 1 ? KT : 4); ++r) m = fminf(m, s[jb][r]);
             m = -max_over_g(-m);
         }
-        mul = sl2;
-        mb = m * sl2;
+        mul = flat ? 1.0f : sl2;
+        mb = m * mul;
     }
     float sum = 0.f;
 #pragma unroll
@@ -306,6 +313,12 @@ __device__ __forceinline__ float softmax_scale_max(f32x4 (&s)[NB], float sl2, co
         mul = 1.0f;
         return max_over_g(m);
     }
+    // a zero scale: all scores are zero (see softmax_block)
+    const bool flat = sl2 == 0.f;
+    if (flat) {
+#pragma unroll
+        for (int jb = 0; jb < NB; ++jb) s[jb] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
     const float pad = sl2 >= 0.f ? -INFINITY : INFINITY;
 #pragma unroll
     for (int r = 0; r < 4; ++r)
@@ -324,8 +337,8 @@ __device__ __forceinline__ float softmax_scale_max(f32x4 (&s)[NB], float sl2, co
             for (int r = 0; r < 4; ++r) m = fminf(m, s[jb][r]);
         m = -max_over_g(-m);
     }
-    mul = sl2;
-    return m * sl2;
+    mul = flat ? 1.0f : sl2;
+    return m * mul;
 }
 
 // exponentials of key blocks 2 kp and 2 kp + 1, added to the lane's partial row sum
