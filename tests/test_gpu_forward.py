@@ -314,9 +314,9 @@ def test_empty_batch_is_a_no_op():
     assert fwa.fwa_forward(q, q.clone(), q.clone(), 3, 0.1).shape == (0, 49, 96)
 
 
-def test_full_size_stage1_sampled_windows(oracle):
-    """Config 2 at its full size, in the launch configuration the benchmark times;
-    the oracle recomputes a sample of windows one by one."""
+def test_full_size_stage1_every_window(oracle):
+    """Config 2 at its full size, in the launch configuration the benchmark times: every window of
+    the output against the oracle."""
     import torch
     w = synth.config2()
     x = synth.draw(w)
@@ -324,13 +324,7 @@ def test_full_size_stage1_sampled_windows(oracle):
     torch.cuda.synchronize()
     got = to_f64(o)
     assert np.isfinite(got).all()
-    pick = np.unique(np.concatenate([[0, 1, 2, 3, w.N - 4, w.N - 3, w.N - 2, w.N - 1],
-                                     synth.rng(99).integers(0, w.N, 120)]))
-    want = oracle.forward(x["q"][pick], x["k"][pick], x["v"][pick], w.heads, w.scale)
-    err = max_abs(got[pick], want)
-    print(f"config 2 full size, {len(pick)} sampled windows: max-abs err={err:.3e}", flush=True)
+    want = oracle.forward(x["q"], x["k"], x["v"], w.heads, w.scale)
+    err = max_abs(got, want)
+    print(f"config 2 full size, all {w.N} windows: max|ref|={np.abs(want).max():.3f} max-abs err={err:.3e}", flush=True)
     assert err <= TOL["bf16"]
-    # a property that holds at any size: every output row lies in the convex hull of V's rows
-    vmax = x["v"].reshape(w.N, w.L, w.C).max(axis=1, keepdims=True)
-    vmin = x["v"].reshape(w.N, w.L, w.C).min(axis=1, keepdims=True)
-    assert (got <= vmax + 2e-2).all() and (got >= vmin - 2e-2).all()
