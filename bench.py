@@ -34,7 +34,13 @@ LLC_BYTES = 256 * 2 ** 20       # Infinity Cache
 # kernel of known size; figures and commands in profiles/fwd_bf16_staged_kernel_swin_t_stage1.md):
 # 232.7 MB read + 77.1 MB written.
 MEASURED_TRAFFIC_BYTES = 309.8e6
-EVENT_GROUP = 100
+# Matrix-core busy fraction of the same kernel on the same workload, from the SQ counters in the same
+# file (SQ_VALU_MFMA_BUSY_CYCLES over SIMDs x active cycles).  tests/test_bench_constants.py holds both
+# constants to the figures in that file.
+MEASURED_MFMA_BUSY_FRAC = 0.084
+PROFILE_FILE = "profiles/fwd_bf16_staged_kernel_swin_t_stage1.md"
+EVENT_GROUP = 100               # launches between two HIP events, at most
+PREWARM_SECONDS = 0.3           # un-timed launches in front of the warm-up: the clocks ramp up over the first ones
 
 
 def ensure_built():
@@ -67,6 +73,29 @@ def cpu_baseline(workload):
             "cores": cores, "kind": "oracle",
             "sample": f"whole batch ({workload.N} windows x {workload.heads} heads, fp64) x {reps} passes, "
                       f"{dt:.2f} s wall = {dt * cores:.0f} core-seconds"}
+
+
+def device_info(torch, dev):
+    """What the runtime reports for the device, next to the published peaks the fractions are taken against."""
+    p = torch.cuda.get_device_properties(dev)
+    khz = getattr(p, "clock_rate", None)
+    mem_khz = bus_bits = None
+    try:  # the HIP runtime torch has already loaded; attribute numbers of hipDeviceAttribute_t (hip_runtime_api.h)
+        import ctypes
+        hip = ctypes.CDLL("libamdhip64.so")
+        def attr(which):
+            v = ctypes.c_int(0)
+            return v.value if hip.hipDeviceGetAttribute(ctypes.byref(v), which, dev.index or 0) == 0 else None
+        khz = khz or attr(5)                   # hipDeviceAttributeClockRate, kHz
+        mem_khz, bus_bits = attr(60), attr(59)  # hipDeviceAttributeMemoryClockRate (kHz), ...MemoryBusWidth (bits)
+    except OSError:
+        pass
+    return {"name": p.name, "arch": getattr(p, "gcnArchName", None), "compute_units": p.multi_processor_count,
+            "max_clock_mhz": None if not khz else khz / 1e3,
+            "memory_clock_mhz": None if not mem_khz else mem_khz / 1e3, "memory_bus_bits": bus_bits,
+            "hbm_bytes": p.total_memory,
+            "published_peaks": {"hbm_GBps": HBM_PEAK_GBPS, "bf16_mfma_dense_TFLOPs": 2500.0,
+                                "compute_units": 256, "clock_mhz": 2400}}
 
 
 def copy_ceiling(torch, sets, iters=60):
@@ -265,12 +294,27 @@ def main():
         q, k, v, o = sets[i % nsets]
         fwa.fwa_forward(q, k, v, w.heads, w.scale, out=o)
 
+    # Whatever --warmup says, the device first gets PREWARM_SECONDS of the same launches: a fresh
+    # process starts at idle clocks, and a short timed region (the default K, W of a driver run are
+    # a millisecond of work) would otherwise measure the ramp.
+    t_warm, i = time.perf_counter(), 0
+    while True:
+        for _ in range(50):
+            step(i)
+            i += 1
+        torch.cuda.synchronize()
+        if time.perf_counter() - t_warm >= PREWARM_SECONDS:
+            break
+    prewarm_steps = i
     for i in range(args.warmup):
         step(i)
-    # HIP events on the launch stream bracket groups of EVENT_GROUP launches (an event between
-    # every two kernels would itself put a bubble between them); the kernel's average duration is
-    # the summed event time over the whole timed region divided by the number of launches.
-    bounds = list(range(0, args.steps, EVENT_GROUP)) + [args.steps]
+    # HIP events on the launch stream bracket groups of launches (an event between every two kernels
+    # would itself put a bubble between them): at most EVENT_GROUP per group, at least 4 groups when
+    # the run is long enough for groups of 5.  The kernel's average duration is the summed event time
+    # over the whole timed region divided by the number of launches; median and minimum are over the
+    # groups' per-launch times.
+    group = max(1, min(EVENT_GROUP, max(5, args.steps // 20)))
+    bounds = list(range(0, args.steps, group)) + [args.steps]
     marks = [torch.cuda.Event(enable_timing=True) for _ in bounds]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -281,7 +325,9 @@ def main():
     marks[-1].record()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
+    group_ms = [marks[gi].elapsed_time(marks[gi + 1]) / (bounds[gi + 1] - bounds[gi]) for gi in range(len(bounds) - 1)]
     kernel_ms = sum(marks[gi].elapsed_time(marks[gi + 1]) for gi in range(len(bounds) - 1)) / args.steps
+    kernel_ms_median, kernel_ms_min = sorted(group_ms)[len(group_ms) // 2], min(group_ms)
     assert all(torch.isfinite(s[3].float()).all().item() for s in sets)
 
     if args.calibrate_copy:
@@ -307,7 +353,14 @@ def main():
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS, "traffic": MEASURED_TRAFFIC_BYTES,
                      "kernel": "fwd_bf16_staged_kernel<4,false,1>", "kernel_ms": kernel_ms,
-                     "algorithmic_bytes_per_launch": algo_bytes},
+                     "kernel_ms_median": kernel_ms_median, "kernel_ms_min": kernel_ms_min,
+                     "event_groups": len(group_ms), "launches_per_group": group,
+                     "frac_at_median": algo_bytes / (kernel_ms_median * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+                     "frac_at_min": algo_bytes / (kernel_ms_min * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+                     "algorithmic_bytes_per_launch": algo_bytes,
+                     "mfma_busy_frac": MEASURED_MFMA_BUSY_FRAC, "counters_from": PROFILE_FILE},
+        "prewarm": {"seconds": PREWARM_SECONDS, "steps": prewarm_steps},
+        "device": device_info(torch, dev),
     }
     line["copy_ceiling"] = copy_ceiling(torch, sets)
     line["paper_context"] = ("paper (one RTX 4090, Triton, fp32): forward up to 300 % faster than Swin's window "
