@@ -40,6 +40,7 @@
  *    workgroups fit a compute unit, and the device's compute-unit count.  These
  *    are asked on the first call that needs them, so a caller that records calls
  *    into a HIP graph makes one call of the same shape outside the capture first.
+ *    (fwa_backward_noalloc also shares one scratch array per device: see there.)
  */
 #ifndef FWA_H
 #define FWA_H
@@ -157,6 +158,29 @@ int fwa_backward_labels(const void* q, const void* k, const void* v, const void*
                         int64_t ld_qkv, int64_t ld_do, int64_t ld_dqkv,
                         const void* bias, int bias_dtype, const int32_t* labels, float mask_value, int nW,
                         int dtype, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * fwa_backward for callers that cannot allocate: code under HIP graph capture, serving loops,
+ * harnesses that forbid hipMalloc.  It is fwa_backward without the workspace arguments: the
+ * workspace (dBias partial sums; for L > 64 also the row statistics) lives in an array of
+ * FWA_NOALLOC_SCRATCH_BYTES bytes inside the library's code object, of which every device the
+ * library runs on holds its own copy until the process ends.  The call itself allocates and frees
+ * nothing, and runs the same kernels with the same results, bit for bit, as fwa_backward.
+ *   - A call whose workspace would exceed the array returns FWA_ERR_WORKSPACE.  Every bf16 call
+ *     with L <= 64 and head width 32 fits (at most 3 x compute-units tiles of 16 KB = 12 MiB);
+ *     large windows with dbias mostly do not.  Without dbias no scratch is used at all.
+ *   - All calls on one device share that device's array, which keeps the previous call's contents;
+ *     the kernels overwrite every element they later read, so nothing needs clearing.  Calls that
+ *     overlap in time on one device (two streams, two threads) race on it: serialise them.
+ *   - The array's device address is looked up on the first call on each device
+ *     (hipGetSymbolAddress, no allocation).
+ */
+#define FWA_NOALLOC_SCRATCH_BYTES (16u * 1024u * 1024u)
+int fwa_backward_noalloc(const void* q, const void* k, const void* v, const void* d_o,
+                         void* dq, void* dk, void* dv, float* dbias,
+                         int64_t N, int L, int C, int heads, float scale,
+                         const float* bias, const float* mask, int nW,
+                         int dtype, void* stream);
 
 /* Bytes of workspace that suffice for any backward call with these arguments
  * (0 if none is needed; for L > 64 the size includes room for the fp32 copy of

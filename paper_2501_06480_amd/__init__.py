@@ -9,6 +9,6 @@ calls fail loudly.
 """
 from . import synth  # noqa: F401
 from .binding import (  # noqa: F401
-    FwaError, fwa_forward, fwa_backward, fwa_backward_workspace_bytes, fwa_bias_gather,
+    FwaError, fwa_forward, fwa_backward, fwa_backward_noalloc, fwa_backward_workspace_bytes, fwa_bias_gather,
     fwa_bias_scatter, fwa_status_string, library_path, load_library,
 )

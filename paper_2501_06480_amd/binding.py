@@ -22,13 +22,14 @@ FWA_ERR_ALIGN = 4
 FWA_ERR_WORKSPACE = 5
 FWA_ERR_LAUNCH = 6
 FWA_ERR_ALIAS = 7
+FWA_NOALLOC_SCRATCH_BYTES = 16 * 1024 * 1024
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libfwa.so")
 _lib = None
 
 EXPORTS = ("fwa_forward", "fwa_forward_strided", "fwa_forward_labels", "fwa_backward", "fwa_backward_strided",
-           "fwa_backward_labels",
+           "fwa_backward_labels", "fwa_backward_noalloc",
            "fwa_backward_workspace_bytes", "fwa_bias_gather", "fwa_bias_scatter", "fwa_status_string")
 
 
@@ -65,6 +66,8 @@ def load_library():
     lib.fwa_backward.restype = ci
     lib.fwa_backward.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i64, ci, ci, ci, cf, vp, vp, ci, ci,
                                  vp, sz, vp]
+    lib.fwa_backward_noalloc.restype = ci
+    lib.fwa_backward_noalloc.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i64, ci, ci, ci, cf, vp, vp, ci, ci, vp]
     lib.fwa_backward_strided.restype = ci
     lib.fwa_backward_strided.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i64, ci, ci, ci, cf, i64, i64, i64,
                                          vp, vp, ci, ci, vp, sz, vp]
@@ -321,6 +324,32 @@ def fwa_backward(q, k, v, d_o, heads: int, scale: float, bias=None, mask=None, w
         rc = fn(*args)
     if rc != FWA_OK:
         raise FwaError(rc, what)
+    return dq, dk, dv, dbias
+
+
+def fwa_backward_noalloc(q, k, v, d_o, heads: int, scale: float, out, dbias=None, bias=None, mask=None, stream=None):
+    """``fwa_backward`` for callers that cannot allocate: the caller passes every output
+    (`out` = (dq, dk, dv), contiguous; `dbias` = a [heads, L, L] fp32 tensor or None) and the
+    library uses its own static scratch array as workspace.  Returns (dq, dk, dv, dbias)."""
+    lib = load_library()
+    N, L, C = q.shape
+    dq, dk, dv = out
+    nW = 0 if mask is None else int(mask.shape[0])
+    if mask is not None and tuple(mask.shape) != (nW, L, L):
+        raise ValueError("mask must be [nW, L, L]")
+    if dbias is not None and tuple(dbias.shape) != (heads, L, L):
+        raise ValueError("dbias must be [heads, L, L]")
+    bp, bias_code = _bias_ptr(bias, heads, L)
+    if bias_code != FWA_F32:
+        raise TypeError("fwa_backward_noalloc takes an fp32 bias")
+    args = (_dev_ptr(q, "q"), _dev_ptr(k, "k", q), _dev_ptr(v, "v", q), _dev_ptr(d_o, "d_o", q),
+            _dev_ptr(dq, "dq", q), _dev_ptr(dk, "dk", q), _dev_ptr(dv, "dv", q), _dev_ptr(dbias, "dbias", f32=True),
+            N, L, C, int(heads), float(scale), bp, _dev_ptr(mask, "mask", f32=True), nW, _dtype_code(q),
+            _stream_handle(stream, q.device))
+    with _on_device(q.device):
+        rc = lib.fwa_backward_noalloc(*args)
+    if rc != FWA_OK:
+        raise FwaError(rc, "fwa_backward_noalloc")
     return dq, dk, dv, dbias
 
 

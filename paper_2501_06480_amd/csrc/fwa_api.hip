@@ -175,7 +175,8 @@ int forward_impl(const void* q, const void* k, const void* v, void* o, int64_t N
 int backward_impl(const void* q, const void* k, const void* v, const void* d_o, void* dq, void* dk, void* dv,
                   float* dbias, int64_t N, int L, int C, int heads, float scale, int64_t ld_qkv, int64_t ld_do,
                   int64_t ld_dqkv, const void* bias, int bias_dtype, const float* mask, const int32_t* labels,
-                  float mask_value, int nW, int dtype, void* workspace, size_t workspace_bytes, void* stream);
+                  float mask_value, int nW, int dtype, void* workspace, size_t workspace_bytes, void* stream,
+                  bool static_scratch = false);
 
 }  // namespace
 
@@ -251,10 +252,28 @@ int fwa_backward_labels(const void* q, const void* k, const void* v, const void*
 
 namespace {
 
+// Scratch of fwa_backward_noalloc: the workspace of a backward call, held by the library itself so
+// that the call allocates nothing.  Every device the library runs on holds its own copy of the
+// array until the process ends; host code must address it through the pointer the runtime reports
+// for the current device, never through the array's name.
+__device__ __attribute__((used)) __align__(256) unsigned char scratch[FWA_NOALLOC_SCRATCH_BYTES];
+std::atomic<void*> g_scratch_ptr[64];  // per device; nullptr = not asked yet
+
+void* scratch_of_current_device() {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
+    void* ptr = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (ptr != nullptr) return ptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || ptr == nullptr) return nullptr;
+    g_scratch_ptr[dev].store(ptr, std::memory_order_release);
+    return ptr;
+}
+
 int backward_impl(const void* q, const void* k, const void* v, const void* d_o, void* dq, void* dk, void* dv,
                   float* dbias, int64_t N, int L, int C, int heads, float scale, int64_t ld_qkv, int64_t ld_do,
                   int64_t ld_dqkv, const void* bias, int bias_dtype, const float* mask, const int32_t* labels,
-                  float mask_value, int nW, int dtype, void* workspace, size_t workspace_bytes, void* stream) {
+                  float mask_value, int nW, int dtype, void* workspace, size_t workspace_bytes, void* stream,
+                  bool static_scratch) {
     int rc = check_shape(N, L, C, heads, dtype, true);
     if (rc != FWA_OK) return rc;
     if (bias && bias_dtype != FWA_F32 && bias_dtype != FWA_BF16) return FWA_ERR_UNSUPPORTED;
@@ -322,7 +341,18 @@ int backward_impl(const void* q, const void* k, const void* v, const void* d_o, 
     // with dBias)] [partial sums of dBias]; a call needs the parts it uses
     const bool copy_bias = large && bias && bias_dtype == FWA_BF16;
     const size_t copy_room = large ? large_bias_copy_bytes(L, heads) : 0;
-    {
+    if (static_scratch) {
+        // the parts at their exact sizes for this call, out of the library's own array
+        const size_t nb = (size_t)(L + 15) / 16;
+        const size_t exact = (copy_bias ? copy_room : 0) + (dbias && large ? large_stats_bytes(N, L, heads) : 0) +
+                             (dbias ? (size_t)a.slots * heads * nb * nb * 256 * sizeof(float) : 0);
+        if (exact > FWA_NOALLOC_SCRATCH_BYTES) return FWA_ERR_WORKSPACE;
+        workspace = nullptr;
+        if (exact > 0) {
+            workspace = scratch_of_current_device();
+            if (workspace == nullptr) return FWA_ERR_LAUNCH;
+        }
+    } else {
         const size_t full = fwa_backward_workspace_bytes(N, L, C, heads, dtype, dbias != nullptr);
         const size_t need = (dbias ? full - copy_room : 0) + (copy_bias ? copy_room : 0);
         if (need > 0 && (workspace == nullptr || workspace_bytes < need)) return FWA_ERR_WORKSPACE;
@@ -359,6 +389,13 @@ int fwa_backward(const void* q, const void* k, const void* v, const void* d_o, v
                  const float* mask, int nW, int dtype, void* workspace, size_t workspace_bytes, void* stream) {
     return fwa_backward_strided(q, k, v, d_o, dq, dk, dv, dbias, N, L, C, heads, scale, C, C, C, bias, mask, nW,
                                 dtype, workspace, workspace_bytes, stream);
+}
+
+int fwa_backward_noalloc(const void* q, const void* k, const void* v, const void* d_o, void* dq, void* dk, void* dv,
+                         float* dbias, int64_t N, int L, int C, int heads, float scale, const float* bias,
+                         const float* mask, int nW, int dtype, void* stream) {
+    return backward_impl(q, k, v, d_o, dq, dk, dv, dbias, N, L, C, heads, scale, C, C, C, bias, FWA_F32, mask, nullptr,
+                         0.f, nW, dtype, nullptr, 0, stream, true);
 }
 
 int fwa_bias_gather(const float* table, float* bias, int heads, int k, void* stream) {

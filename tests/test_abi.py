@@ -202,3 +202,25 @@ def test_overlapping_tensors_are_rejected_and_interleaved_views_are_not(lib):
     # different strides with intersecting extents: rejected (conservative)
     assert strided(P + 16, G + C * e, G + 2 * C * e, ldd=4 * C) == b.FWA_ERR_ALIAS
 
+
+def test_noalloc_backward_checks_its_arguments_and_its_limit(lib):
+    from paper_2501_06480_amd import binding as b
+    call = lambda N=4, L=49, C=96, heads=3, dbias=None, dq=P + 0x4000000, dtype=1: lib.fwa_backward_noalloc(
+        P, P + 0x1000000, P + 0x2000000, P + 0x3000000, dq, P + 0x5000000, P + 0x6000000, dbias, N, L, C, heads, 0.1,
+        None, None, 0, dtype, None)
+    assert call(N=-1) == b.FWA_ERR_SHAPE
+    assert call(dq=P) == b.FWA_ERR_ALIAS
+    assert call(dq=P + 4) == b.FWA_ERR_ALIGN
+    assert call(N=0) == b.FWA_OK
+    assert call(dtype=0, dbias=P + 0x7000000) == b.FWA_ERR_UNSUPPORTED        # no dBias in fp32
+    # the dBias workspace of large windows exceeds the static array: turned away, nothing launched
+    assert b.FWA_NOALLOC_SCRATCH_BYTES == 16 * 1024 * 1024
+    assert lib.fwa_backward_workspace_bytes(1024, 144, 128, 4, 1, 1) > b.FWA_NOALLOC_SCRATCH_BYTES
+    assert call(N=64, L=144, C=128, heads=4, dbias=P + 0x7000000) == b.FWA_ERR_WORKSPACE
+
+
+def test_header_and_binding_agree_on_the_scratch_limit():
+    from paper_2501_06480_amd import binding as b
+    text = open(os.path.join(ROOT, "include", "fwa.h")).read()
+    m = re.search(r"#define FWA_NOALLOC_SCRATCH_BYTES \((\d+)u \* (\d+)u \* (\d+)u\)", text)
+    assert m and int(m.group(1)) * int(m.group(2)) * int(m.group(3)) == b.FWA_NOALLOC_SCRATCH_BYTES
