@@ -33,6 +33,8 @@
 #include "fwa_internal.h"
 #include "fwa_softmax.h"
 
+#include <type_traits>
+
 namespace fwa {
 namespace {
 
@@ -42,13 +44,6 @@ struct LargeGeom {
 };
 
 constexpr int large_waves(int nb) { return nb <= 10 ? 4 : 8; }
-// The dBias kernel: one key block per wave, so that the accumulator is at most 64 registers and a SIMD holds
-// four waves -- one workgroup of 16 waves per CU from L = 161 on (8 waves of two key blocks each, two per
-// SIMD: 4-7 % slower over the call at L = 196 and 256), two workgroups of up to 8 waves per CU up to L = 128
-// (four waves of two key blocks: 4-5 % slower at L = 81 and 100).  L = 129..160 would need 18 or 20 waves
-// per CU for its two workgroups and keeps four waves of three key blocks (9 waves: 2 % slower, 5: 6 %).
-constexpr int dbias_waves(int nb) { return nb <= 8 ? nb : (nb <= 10 ? 4 : 16); }
-
 __device__ __forceinline__ bf16x8 pair_operand(bf16x4 a, bf16x4 b) {
     const uint2 ua = __builtin_bit_cast(uint2, a), ub = __builtin_bit_cast(uint2, b);
     return as_bf16x8(u32x4{ua.x, ua.y, ub.x, ub.y});
@@ -57,7 +52,9 @@ __device__ __forceinline__ bf16x8 pair_operand(bf16x4 a, bf16x4 b) {
 // HB: no bias (0) or an fp32 bias (1; a bf16 bias arrives as an fp32 copy made once per call); HM: no mask (0), a dense mask (1), or region
 // labels from which the mask values are formed in registers (2).  What is absent costs neither
 // loads nor registers.
-template <int NB, int HB, int HM>
+// P2 = false: pass 1 only (dQ, and the row statistics to the workspace); dK, dV and dBias are then
+// left to bwd_bf16_large_keys_kernel.
+template <int NB, int HB, int HM, bool P2>
 __global__ void __launch_bounds__(64 * large_waves(NB)) bwd_bf16_large_kernel(BwdArgs p, LargeGeom gm) {
     constexpr bool BM = HB != 0 || HM != 0;
     constexpr int W = large_waves(NB);
@@ -235,6 +232,8 @@ __global__ void __launch_bounds__(64 * large_waves(NB)) bwd_bf16_large_kernel(Bw
                 }
             sum = sum_over_g(sum);
             const float inv = __builtin_amdgcn_rcpf(sum);
+            // s keeps exp(score - max), not normalised: P = s * inv enters delta here and dQ at the very
+            // end (one factor per output element instead of one per score)
             float delta = 0.f;
 #pragma unroll
             for (int jb = 0; jb < NB; ++jb) {
@@ -243,8 +242,6 @@ __global__ void __launch_bounds__(64 * large_waves(NB)) bwd_bf16_large_kernel(Bw
                 for (int r = 0; r < 4; ++r) delta = fmaf(s[jb][r], dp[r], delta);
             }
             delta = sum_over_g(delta) * inv;
-#pragma unroll
-            for (int jb = 0; jb < NB; ++jb) s[jb] *= inv;  // P
             if (g == 0) {
                 const float Mi = m + __builtin_amdgcn_logf(sum);  // p_ij = exp2(score_ij - M_i)
                 stM[16 * qb + n] = Mi;
@@ -297,345 +294,447 @@ __global__ void __launch_bounds__(64 * large_waves(NB)) bwd_bf16_large_kernel(Bw
                 q1 = mfma_bf16(tk1[cur], dl, q1);
                 __builtin_amdgcn_sched_barrier(0);
             }
-            const u32x2 lo2 = {pack_bf16(q0[0] * p.scale, q0[1] * p.scale), pack_bf16(q0[2] * p.scale, q0[3] * p.scale)};
-            const u32x2 hi2 = {pack_bf16(q1[0] * p.scale, q1[1] * p.scale), pack_bf16(q1[2] * p.scale, q1[3] * p.scale)};
+            const float qs = p.scale * inv;  // the lane's query row: dQ_i = scale / sum_i * (the products above)
+            const u32x2 lo2 = {pack_bf16(q0[0] * qs, q0[1] * qs), pack_bf16(q0[2] * qs, q0[3] * qs)};
+            const u32x2 hi2 = {pack_bf16(q1[0] * qs, q1[1] * qs), pack_bf16(q1[2] * qs, q1[3] * qs)};
             store_rows(lo2, hi2, make_rsrc((char*)p.dq + tile_d, tile_bytes_d), qb);
         }
         __syncthreads();
 
-        // ---------------- pass 2: key blocks wave, wave + W ----------------
-        for (int jb = (int)wave; jb < NB; jb += W) {
-            const bf16x8 kop = __builtin_bit_cast(bf16x8, lk[opd + 16 * jb * STRIDE]);
-            const bf16x8 vop = __builtin_bit_cast(bf16x8, lv[opd + 16 * jb * STRIDE]);
-            const uint32_t jcol = 16u * jb + n;
-            const bool valid = jcol < (uint32_t)L;
-            f32x4 v0 = zero, v1 = zero, k0 = zero, k1 = zero;  // dV, dK [16 jb + n][4g + r] and [..][16 + 4g + r]
+        // ---------------- pass 2: key blocks wave, wave + W, ..., two at a time ----------------
+        // A wave that owns two key blocks works on both at once: every operand it fetches for a query
+        // block (Q and dO rows, their transposes, the statistics) then serves two key blocks, which
+        // halves the LDS traffic of this pass, and the two blocks are independent chains of work.
+        auto pass2 = [&](auto nk_tag, const int jb0) {
+            constexpr int NK = decltype(nk_tag)::value;  // key blocks jb0 (and jb0 + W)
+            bf16x8 kop[NK], vop[NK];
+            f32x4 v0[NK], v1[NK], k0[NK], k1[NK];  // dV, dK [16 jb + n][4g + r] and [..][16 + 4g + r]
+            int lkey[NK];
+#pragma unroll
+            for (int t = 0; t < NK; ++t) {
+                const int jb = jb0 + t * W;
+                kop[t] = __builtin_bit_cast(bf16x8, lk[opd + 16 * jb * STRIDE]);
+                vop[t] = __builtin_bit_cast(bf16x8, lv[opd + 16 * jb * STRIDE]);
+                v0[t] = v1[t] = k0[t] = k1[t] = zero;
+                lkey[t] = HM == 2 ? load_i32(rl, (uint32_t)(16 * jb + n) * 4u) : 0;
+            }
+            // A key beyond L (a lane of the last key block) is not masked out: what it computes -- from
+            // zero rows of K and V, possibly an overflow -- stays in its own column of every product,
+            // i.e. in rows of dV and dK beyond L, which the stores drop.
             const uint16_t* lg16 = reinterpret_cast<const uint16_t*>(lg) + trs;
             const uint16_t* lq16 = reinterpret_cast<const uint16_t*>(lq) + trs;
-            // Operands (LDS) and additive terms (L2) of a pair of query blocks are fetched one pair ahead;
-            // the scheduling barriers keep the compiler from hoisting more than that.
-            uint32_t aoff[4];
+            uint32_t aoff[4];  // additive term of query 4g + r and key 16 jb0 + n; key block t: + 64 W t bytes
 #pragma unroll
-            for (int r = 0; r < 4; ++r) aoff[r] = ((uint32_t)(4 * g + r) * L + jcol) * 4u;
-            bf16x8 oq[2][2], og[2][2], tg0[2], tg1[2], tx0[2], tx1[2];
-            f32x4 oM[2][2], oD[2][2], ab[2][2], am[2][2];
-            i32x4 al[2][2];
-            const int lkey = HM == 2 ? load_i32(rl, jcol * 4u) : 0;
-            auto fetch = [&](int qp, int slot) {
-                const bool two = 2 * qp + 1 < NB;
+            for (int r = 0; r < 4; ++r) aoff[r] = ((uint32_t)(4 * g + r) * L + 16u * jb0 + n) * 4u;
+            // Row operands, statistics (LDS) and additive terms (L2) are fetched one query block ahead of
+            // their use, the transposed operands one pair of query blocks ahead; the scheduling barriers
+            // keep the compiler from hoisting more than that.
+            bf16x8 oq[2], og[2], tg0[2], tg1[2], tx0[2], tx1[2];
+            f32x4 oM[2], oD[2], ab[2][NK], am[2][NK];
+            i32x4 al[2];
+            auto fetch_q = [&](int qb, int slot) {
+                oq[slot] = __builtin_bit_cast(bf16x8, lq[opd + 16 * qb * STRIDE]);
+                og[slot] = __builtin_bit_cast(bf16x8, lg[opd + 16 * qb * STRIDE]);
+                oM[slot] = *reinterpret_cast<const f32x4*>(stM + 16 * qb + 4 * g);
+                oD[slot] = *reinterpret_cast<const f32x4*>(stD + 16 * qb + 4 * g);
+                if (BM) {
+                    // rows beyond L lie outside the descriptors (which start at the first row of the query
+                    // block, so that the 4 lane offsets serve every block)
+                    const uint32_t qrow = (uint32_t)(16 * qb) * L;
+                    const __amdgpu_buffer_rsrc_t rbq = HB == 1 ? make_rsrc(bias32 + (size_t)h * L * L + qrow, ll - 4u * qrow) : rb;
+                    const __amdgpu_buffer_rsrc_t rmq =
+                        HM == 1 ? make_rsrc(p.mask + (size_t)(w % (uint32_t)p.nW) * L * L + qrow, ll - 4u * qrow) : rb;
 #pragma unroll
-                for (int u = 0; u < 2; ++u) {
-                    if (u == 1 && !two) break;
-                    const int qb = 2 * qp + u;
-                    oq[slot][u] = __builtin_bit_cast(bf16x8, lq[opd + 16 * qb * STRIDE]);
-                    og[slot][u] = __builtin_bit_cast(bf16x8, lg[opd + 16 * qb * STRIDE]);
-                    oM[slot][u] = *reinterpret_cast<const f32x4*>(stM + 16 * qb + 4 * g);
-                    oD[slot][u] = *reinterpret_cast<const f32x4*>(stD + 16 * qb + 4 * g);
+                    for (int t = 0; t < NK; ++t)
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) {
+                            if (HB == 1) ab[slot][t][r] = load_f32(rbq, aoff[r] + 64u * W * t);
+                            if (HM == 1) am[slot][t][r] = load_f32(rmq, aoff[r] + 64u * W * t);
+                        }
+                    // with labels: those of the 4 query rows, compared with the key's where the term is used
+                    if (HM == 2) al[slot] = load_i32x4(rl, (uint32_t)(16 * qb + 4 * g) * 4u);
                 }
-                // dO^T and Q^T of the 32 queries (channel on the lane)
+            };
+            auto fetch_t = [&](int qp, int slot) {  // dO^T and Q^T of the 32 queries (channel on the lane)
+                const bool two = 2 * qp + 1 < NB;
                 tg0[slot] = operand_tr(lg16 + (32 * qp) * SROW, 16 * SROW, two);
                 tg1[slot] = operand_tr(lg16 + (32 * qp) * SROW + 16, 16 * SROW, two);
                 tx0[slot] = operand_tr(lq16 + (32 * qp) * SROW, 16 * SROW, two);
                 tx1[slot] = operand_tr(lq16 + (32 * qp) * SROW + 16, 16 * SROW, two);
             };
-            auto fetch_add = [&](int qp, int slot) {
-                // rows beyond L lie outside the descriptors (which start at the first row of the query
-                // block, so that the 4 lane offsets serve every block); a key beyond L gets p = 0 below
-#pragma unroll
-                for (int u = 0; u < 2; ++u) {
-                    if (u == 1 && 2 * qp + 1 >= NB) break;
-                    const uint32_t qrow = (uint32_t)(16 * (2 * qp + u)) * L;
-                    const __amdgpu_buffer_rsrc_t rbq = HB == 1 ? make_rsrc(bias32 + (size_t)h * L * L + qrow, ll - 4u * qrow) : rb;
-                    const __amdgpu_buffer_rsrc_t rmq =
-                        HM == 1 ? make_rsrc(p.mask + (size_t)(w % (uint32_t)p.nW) * L * L + qrow, ll - 4u * qrow) : rb;
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        if (HB == 1) ab[slot][u][r] = load_f32(rbq, aoff[r]);
-                        if (HM == 1) am[slot][u][r] = load_f32(rmq, aoff[r]);
-                    }
-                    // with labels: those of the 4 query rows, compared with the key's where the term is used
-                    if (HM == 2) al[slot][u] = load_i32x4(rl, (uint32_t)(16 * (2 * qp + u) + 4 * g) * 4u);
-                }
-            };
-            if (BM) fetch_add(0, 0);
-            fetch(0, 0);
+            fetch_q(0, 0);
+            fetch_t(0, 0);
 #pragma unroll
             for (int qp = 0; qp < NB2; ++qp) {
                 const bool two = 2 * qp + 1 < NB;
-                const int cur = qp & 1;
-                if (BM && qp + 1 < NB2) fetch_add(qp + 1, cur ^ 1);
-                if (qp + 1 < NB2) fetch(qp + 1, cur ^ 1);
-                __builtin_amdgcn_sched_barrier(0);
-                bf16x4 ph[2], pl[2], sh[2], sl[2];
-                ph[1] = pl[1] = sh[1] = sl[1] = as_bf16x4(uint2{0u, 0u});
-                f32x4 sc[2], dp[2];
+                const int tcur = qp & 1;
+                if (qp + 1 < NB2) fetch_t(qp + 1, tcur ^ 1);
+                bf16x4 ph[NK][2], pl[NK][2], sh[NK][2], sl[NK][2];
+#pragma unroll
+                for (int t = 0; t < NK; ++t) ph[t][1] = pl[t][1] = sh[t][1] = sl[t][1] = as_bf16x4(uint2{0u, 0u});
 #pragma unroll
                 for (int u = 0; u < 2; ++u) {
                     if (u == 1 && !two) break;
-                    sc[u] = mfma_bf16(oq[cur][u], kop, zero);  // sc[r] = <q_i, k_j>, i = 16 qb + 4g + r, j = jcol
-                    dp[u] = mfma_bf16(og[cur][u], vop, zero);
+                    const int qb = 2 * qp + u, cur = qb & 1;
+                    if (qb + 1 < NB) fetch_q(qb + 1, cur ^ 1);
+                    __builtin_amdgcn_sched_barrier(0);
+                    f32x4 sc[NK], dp[NK];
+#pragma unroll
+                    for (int t = 0; t < NK; ++t) {
+                        sc[t] = mfma_bf16(oq[cur], kop[t], zero);  // sc[r] = <q_i, k_j>, i = 16 qb + 4g + r, j = 16 jb + n
+                        dp[t] = mfma_bf16(og[cur], vop[t], zero);
+                    }
+#pragma unroll
+                    for (int t = 0; t < NK; ++t) {
+                        f32x4 pr, ds;
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) {
+                            float x;
+                            if (BM) {
+                                const float mk = HM == 2 ? (al[cur][r] == lkey[t] ? 0.f : p.mask_value) : am[cur][t][r];
+                                const float bv = ab[cur][t][r];
+                                const float add = HB && HM ? bv + mk : (HB ? bv : mk);
+                                x = fmaf(sc[t][r], sl2, fmaf(add, kLog2e, -oM[cur][r]));
+                            } else {
+                                x = fmaf(sc[t][r], sl2, -oM[cur][r]);
+                            }
+                            pr[r] = __builtin_amdgcn_exp2f(x);
+                            ds[r] = pr[r] * (dp[t][r] - oD[cur][r]);
+                        }
+                        split_hi_lo(pr, ph[t][u], pl[t][u]);
+                        split_hi_lo(ds, sh[t][u], sl[t][u]);
+                    }
                 }
 #pragma unroll
+                for (int t = 0; t < NK; ++t) {
+                    const bf16x8 PH = pair_operand(ph[t][0], ph[t][1]), PL = pair_operand(pl[t][0], pl[t][1]);
+                    const bf16x8 SH = pair_operand(sh[t][0], sh[t][1]), SL = pair_operand(sl[t][0], sl[t][1]);
+                    v0[t] = mfma_bf16(tg0[tcur], PH, v0[t]);
+                    v1[t] = mfma_bf16(tg1[tcur], PH, v1[t]);
+                    k0[t] = mfma_bf16(tx0[tcur], SH, k0[t]);
+                    k1[t] = mfma_bf16(tx1[tcur], SH, k1[t]);
+                    v0[t] = mfma_bf16(tg0[tcur], PL, v0[t]);
+                    v1[t] = mfma_bf16(tg1[tcur], PL, v1[t]);
+                    k0[t] = mfma_bf16(tx0[tcur], SL, k0[t]);
+                    k1[t] = mfma_bf16(tx1[tcur], SL, k1[t]);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+#pragma unroll
+            for (int t = 0; t < NK; ++t) {
+                const int jb = jb0 + t * W;
+                const u32x2 va = {pack_bf16(v0[t][0], v0[t][1]), pack_bf16(v0[t][2], v0[t][3])};
+                const u32x2 vb = {pack_bf16(v1[t][0], v1[t][1]), pack_bf16(v1[t][2], v1[t][3])};
+                const u32x2 ka = {pack_bf16(k0[t][0] * p.scale, k0[t][1] * p.scale), pack_bf16(k0[t][2] * p.scale, k0[t][3] * p.scale)};
+                const u32x2 kb = {pack_bf16(k1[t][0] * p.scale, k1[t][1] * p.scale), pack_bf16(k1[t][2] * p.scale, k1[t][3] * p.scale)};
+                store_rows(va, vb, make_rsrc((char*)p.dv + tile_d, tile_bytes_d), jb);
+                store_rows(ka, kb, make_rsrc((char*)p.dk + tile_d, tile_bytes_d), jb);
+            }
+        };
+        for (int jb0 = (int)wave; P2 && jb0 < NB; jb0 += 2 * W) {
+            if (jb0 + W < NB)
+                pass2(std::integral_constant<int, 2>{}, jb0);
+            else
+                pass2(std::integral_constant<int, 1>{}, jb0);
+        }
+        __syncthreads();  // the slabs are rewritten for the next window
+    }
+}
+
+// dK, dV and dBias for 64 < L <= 256 when dBias is wanted.  The dBias accumulator is L x L fp32 per
+// head (256 KB at L = 256): half of a CU's register file, which the two passes of the kernel above
+// need themselves.  So a call with dBias runs that kernel with pass 1 only (dQ; the row statistics
+// M_i, delta_i go to the workspace, 8 bytes per query) and this one for pass 2: a wave owns ONE key
+// block of one head for its whole life -- the key blocks of a head are spread over one workgroup
+// (up to 8 blocks) or two (9 to 16) -- produces S and dP block by block in the "key on the lane"
+// orientation, P = exp2(score - M_i), dS = P (dP - delta_i), feeds both back into the matrix cores
+// for its dV and dK rows exactly as pass 2 above, and adds dS into dBias[all queries][its keys],
+// held in registers (at most 64) across the windows bw, bw + G, ...  The sums are written out once,
+// in register order, as one of G partial sums per head; the reduce kernel adds the slots in a fixed
+// order.  Only Q and dO (all rows) go through LDS; the wave takes the K and V rows of its key block
+// straight from global memory.
+// The key blocks of a head are spread over workgroups of at most 4 waves (one wave per SIMD), of which a CU
+// holds two: while one loads or waits at a barrier the other computes.
+constexpr int keys_parts(int nb) { return (nb + 3) / 4; }
+constexpr int keys_waves(int nb) { return (nb + keys_parts(nb) - 1) / keys_parts(nb); }
+
+template <int NB, int HB, int HM>
+__global__ void __launch_bounds__(64 * keys_waves(NB), 2) bwd_bf16_large_keys_kernel(BwdArgs p, LargeGeom gm) {
+    constexpr bool BM = HB != 0 || HM != 0;
+    constexpr int PARTS = keys_parts(NB);
+    constexpr int W = keys_waves(NB);
+    constexpr int NB2 = (NB + 1) / 2;
+    constexpr int ROWS = 16 * NB;
+    constexpr int PASSES = (ROWS + 16 * W - 1) / (16 * W);
+    constexpr uint32_t STRIDE = 5;         // slab row: 64 bytes of data + 16 of padding
+    constexpr uint32_t SROW = STRIDE * 8;  // the same in bf16 elements
+    extern __shared__ __attribute__((aligned(16))) uint4 lds[];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int n = lane & 15, g = lane >> 4;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    // the parts of a head and the heads of a window are neighbours in the logical order: one XCD
+    const uint32_t lb = xcd_logical_block(blockIdx.x, gm.xcd_q, gm.xcd_r);
+    const uint32_t part = lb % PARTS, h = (lb / PARTS) % gm.heads, bw = lb / (PARTS * gm.heads);
+    const int jb = (int)(part * W + wave);  // this wave's key block
+    const bool active = jb < NB;            // wave-uniform
+    const int L = p.L;
+    const uint32_t row_bytes = (uint32_t)p.ldq * 2u, row_g = (uint32_t)p.ldg * 2u, row_d = (uint32_t)p.ldd * 2u;
+    const float sl2 = p.scale * kLog2e;
+    const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+
+    // LDS: slabs [Q][dO], each [ROWS][STRIDE] uint4; M[ROWS], delta[ROWS]; 16 rows x 80 bytes per wave for its output rows
+    constexpr uint32_t SET = 2 * ROWS * STRIDE + ROWS / 2;  // in uint4
+    char* const cell = reinterpret_cast<char*>(lds + SET) + wave * (16 * 80);
+
+    const uint32_t ll = (uint32_t)L * L * 4u;
+    const float* const bias32 = static_cast<const float*>(p.bias);
+    const uint32_t srow = (uint32_t)tid >> 2, scol = (uint32_t)tid & 3u;
+    const uint32_t tile_bytes = (uint32_t)(L - 1) * row_bytes + 2u * kHeadDim;
+    const uint32_t tile_bytes_g = (uint32_t)(L - 1) * row_g + 2u * kHeadDim;
+    const uint32_t tile_bytes_d = (uint32_t)(L - 1) * row_d + 2u * kHeadDim;
+    const uint32_t trs = (4u * g + (n >> 2)) * SROW + 4u * (n & 3);
+    const uint32_t opd = (uint32_t)n * STRIDE + g;
+    typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+    auto store_rows = [&](const u32x2 lo, const u32x2 hi, const __amdgpu_buffer_rsrc_t dst) {
+        *reinterpret_cast<u32x2*>(cell + n * 80 + g * 8) = lo;
+        *reinterpret_cast<u32x2*>(cell + n * 80 + 32 + g * 8) = hi;
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        const uint32_t r = (uint32_t)(lane >> 2), c = (uint32_t)(lane & 3);
+        const u32x4 rows = *reinterpret_cast<const u32x4*>(cell + r * 80 + c * 16);
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_raw_buffer_store_b128(rows, dst, (uint32_t)(16 * jb + r) * row_d + 16u * c, 0, 0);
+    };
+
+    f32x4 dbacc[NB];  // dS summed over the windows: queries 16 qb + 4g + r, key 16 jb + n
+#pragma unroll
+    for (int qb = 0; qb < NB; ++qb) dbacc[qb] = zero;
+    uint32_t aoff[4];  // additive term of query 4g + r (of a query block) and this lane's key
+#pragma unroll
+    for (int r = 0; r < 4; ++r) aoff[r] = ((uint32_t)(4 * g + r) * L + 16u * jb + n) * 4u;
+
+    // The Q and dO slabs, the statistics and the wave's own K and V rows of a window are requested a whole
+    // window ahead: into registers at the top of an iteration, from there into LDS at its end, between two
+    // barriers.
+    constexpr int PASSES_ = PASSES;
+    constexpr int SPASSES = (ROWS / 2 + 64 * W - 1) / (64 * W);
+    u32x4 pq[PASSES_], pg[PASSES_], st4[SPASSES], pk, pv;
+    auto request = [&](uint32_t w) {
+        const size_t tile = ((size_t)w * L * p.ldq + (size_t)h * kHeadDim) * 2u;
+        const size_t tile_g = ((size_t)w * L * p.ldg + (size_t)h * kHeadDim) * 2u;
+        const __amdgpu_buffer_rsrc_t rk = make_rsrc((const char*)p.k + tile, tile_bytes);
+        const __amdgpu_buffer_rsrc_t rv = make_rsrc((const char*)p.v + tile, tile_bytes);
+        const __amdgpu_buffer_rsrc_t rq = make_rsrc((const char*)p.q + tile, tile_bytes);
+        const __amdgpu_buffer_rsrc_t rg = make_rsrc((const char*)p.d_o + tile_g, tile_bytes_g);
+        const __amdgpu_buffer_rsrc_t rs =
+            make_rsrc(p.stats + ((size_t)w * p.heads + h) * (2 * ROWS), (uint32_t)(2 * ROWS * 4));
+#pragma unroll
+        for (int t = 0; t < PASSES; ++t) {  // rows beyond L arrive as zeros
+            pq[t] = __builtin_amdgcn_raw_buffer_load_b128(rq, (16 * W * t + srow) * row_bytes + scol * 16u, 0, 0);
+            pg[t] = __builtin_amdgcn_raw_buffer_load_b128(rg, (16 * W * t + srow) * row_g + scol * 16u, 0, 0);
+        }
+        // 2 ROWS floats of statistics: 16 bytes per thread
+#pragma unroll
+        for (int t = 0; t < SPASSES; ++t) st4[t] = __builtin_amdgcn_raw_buffer_load_b128(rs, (uint32_t)(tid + 64 * W * t) * 16u, 0, 0);
+        // the wave's own K and V rows as operands: row 16 jb + n, channels 8g .. 8g + 7
+        pk = __builtin_amdgcn_raw_buffer_load_b128(rk, (uint32_t)(16 * jb + n) * row_bytes + 16u * g, 0, 0);
+        pv = __builtin_amdgcn_raw_buffer_load_b128(rv, (uint32_t)(16 * jb + n) * row_bytes + 16u * g, 0, 0);
+    };
+    auto park = [&]() {
+        uint4* const sq = lds;
+        uint4* const sg = sq + ROWS * STRIDE;
+#pragma unroll
+        for (int t = 0; t < PASSES; ++t) {
+            const uint32_t row = 16 * W * t + srow;
+            if (row < (uint32_t)ROWS) {
+                sq[row * STRIDE + scol] = __builtin_bit_cast(uint4, pq[t]);
+                sg[row * STRIDE + scol] = __builtin_bit_cast(uint4, pg[t]);
+            }
+        }
+#pragma unroll
+        for (int t = 0; t < SPASSES; ++t)
+            if (tid + 64 * W * t < ROWS / 2) sq[2 * ROWS * STRIDE + tid + 64 * W * t] = __builtin_bit_cast(uint4, st4[t]);
+    };
+    if (bw < (uint32_t)p.N) {
+        request(bw);
+        park();
+    }
+    __syncthreads();
+    const uint4* const lq = lds;
+    const uint4* const lg = lq + ROWS * STRIDE;
+    const float* const stM = reinterpret_cast<const float*>(lq + 2 * ROWS * STRIDE);
+    const float* const stD = stM + ROWS;
+    const uint16_t* const lg16 = reinterpret_cast<const uint16_t*>(lg) + trs;
+    const uint16_t* const lq16 = reinterpret_cast<const uint16_t*>(lq) + trs;
+
+    for (uint32_t w = bw; w < (uint32_t)p.N; w += gm.G) {
+        const size_t tile_d = ((size_t)w * L * p.ldd + (size_t)h * kHeadDim) * 2u;
+        const __amdgpu_buffer_rsrc_t rl =
+            HM == 2 ? make_rsrc(p.labels + (size_t)(w % (uint32_t)p.nW) * L, (uint32_t)L * 4u) : make_rsrc(nullptr, 0);
+        const bf16x8 kop = as_bf16x8(pk), vop = as_bf16x8(pv);
+        const bool has_next = w + gm.G < (uint32_t)p.N;
+        if (has_next) request(w + gm.G);  // in flight while this window is computed
+
+        if (active) {
+            const int lkey = HM == 2 ? load_i32(rl, (uint32_t)(16 * jb + n) * 4u) : 0;
+            f32x4 v0 = zero, v1 = zero, k0 = zero, k1 = zero;  // dV, dK [16 jb + n][4g + r] and [..][16 + 4g + r]
+            // operands of a query block one block ahead of their use, transposed operands one pair ahead
+            bf16x8 oq[2], og[2], tg0[2], tg1[2], tx0[2], tx1[2];
+            f32x4 oM[2], oD[2], ab[2], am[2];
+            i32x4 al[2];
+            auto fetch_q = [&](int qb, int slot) {
+                oq[slot] = __builtin_bit_cast(bf16x8, lq[opd + 16 * qb * STRIDE]);
+                og[slot] = __builtin_bit_cast(bf16x8, lg[opd + 16 * qb * STRIDE]);
+                oM[slot] = *reinterpret_cast<const f32x4*>(stM + 16 * qb + 4 * g);
+                oD[slot] = *reinterpret_cast<const f32x4*>(stD + 16 * qb + 4 * g);
+                if (BM) {
+                    // descriptors start at the first row of the query block, so that the 4 lane offsets
+                    // serve every block; rows beyond L lie outside them
+                    const uint32_t qrow = (uint32_t)(16 * qb) * L;
+                    const __amdgpu_buffer_rsrc_t rbq =
+                        HB == 1 ? make_rsrc(bias32 + (size_t)h * L * L + qrow, ll - 4u * qrow) : make_rsrc(nullptr, 0);
+                    const __amdgpu_buffer_rsrc_t rmq =
+                        HM == 1 ? make_rsrc(p.mask + (size_t)(w % (uint32_t)p.nW) * L * L + qrow, ll - 4u * qrow)
+                                : make_rsrc(nullptr, 0);
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        if (HB == 1) ab[slot][r] = load_f32(rbq, aoff[r]);
+                        if (HM == 1) am[slot][r] = load_f32(rmq, aoff[r]);
+                    }
+                    if (HM == 2) al[slot] = load_i32x4(rl, (uint32_t)(16 * qb + 4 * g) * 4u);
+                }
+            };
+            auto fetch_t = [&](int qp, int slot) {  // dO^T and Q^T of the 32 queries (channel on the lane)
+                const bool two = 2 * qp + 1 < NB;
+                tg0[slot] = operand_tr(lg16 + (32 * qp) * SROW, 16 * SROW, two);
+                tg1[slot] = operand_tr(lg16 + (32 * qp) * SROW + 16, 16 * SROW, two);
+                tx0[slot] = operand_tr(lq16 + (32 * qp) * SROW, 16 * SROW, two);
+                tx1[slot] = operand_tr(lq16 + (32 * qp) * SROW + 16, 16 * SROW, two);
+            };
+            fetch_q(0, 0);
+            fetch_t(0, 0);
+#pragma unroll
+            for (int qp = 0; qp < NB2; ++qp) {
+                const bool two = 2 * qp + 1 < NB;
+                const int tcur = qp & 1;
+                if (qp + 1 < NB2) fetch_t(qp + 1, tcur ^ 1);
+                bf16x4 ph[2], pl[2], sh[2], sl[2];
+                ph[1] = pl[1] = sh[1] = sl[1] = as_bf16x4(uint2{0u, 0u});
+#pragma unroll
                 for (int u = 0; u < 2; ++u) {
                     if (u == 1 && !two) break;
+                    const int qb = 2 * qp + u, cur = qb & 1;
+                    if (qb + 1 < NB) fetch_q(qb + 1, cur ^ 1);
+                    __builtin_amdgcn_sched_barrier(0);
+                    const f32x4 sc = mfma_bf16(oq[cur], kop, zero);  // <q_i, k_j>, i = 16 qb + 4g + r, j = 16 jb + n
+                    const f32x4 dp = mfma_bf16(og[cur], vop, zero);
                     f32x4 pr, ds;
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
                         float x;
                         if (BM) {
-                            const float mk = HM == 2 ? (al[cur][u][r] == lkey ? 0.f : p.mask_value) : am[cur][u][r];
-                            const float bv = ab[cur][u][r];
+                            const float mk = HM == 2 ? (al[cur][r] == lkey ? 0.f : p.mask_value) : am[cur][r];
+                            const float bv = ab[cur][r];
                             const float add = HB && HM ? bv + mk : (HB ? bv : mk);
-                            x = fmaf(sc[u][r], sl2, fmaf(add, kLog2e, -oM[cur][u][r]));
+                            x = fmaf(sc[r], sl2, fmaf(add, kLog2e, -oM[cur][r]));
+                        } else {
+                            x = fmaf(sc[r], sl2, -oM[cur][r]);
                         }
-                        else
-                            x = fmaf(sc[u][r], sl2, -oM[cur][u][r]);
-                        pr[r] = valid ? __builtin_amdgcn_exp2f(x) : 0.f;
-                        ds[r] = pr[r] * (dp[u][r] - oD[cur][u][r]);
+                        // a key beyond L is not masked out: its column of every product lands in rows of dV, dK
+                        // and columns of dBias beyond L, which the stores and the reduce kernel drop
+                        pr[r] = __builtin_amdgcn_exp2f(x);
+                        ds[r] = pr[r] * (dp[r] - oD[cur][r]);
                     }
+                    dbacc[qb] += ds;
                     split_hi_lo(pr, ph[u], pl[u]);
                     split_hi_lo(ds, sh[u], sl[u]);
                 }
                 const bf16x8 PH = pair_operand(ph[0], ph[1]), PL = pair_operand(pl[0], pl[1]);
                 const bf16x8 SH = pair_operand(sh[0], sh[1]), SL = pair_operand(sl[0], sl[1]);
-                v0 = mfma_bf16(tg0[cur], PH, v0);
-                v1 = mfma_bf16(tg1[cur], PH, v1);
-                k0 = mfma_bf16(tx0[cur], SH, k0);
-                k1 = mfma_bf16(tx1[cur], SH, k1);
-                v0 = mfma_bf16(tg0[cur], PL, v0);
-                v1 = mfma_bf16(tg1[cur], PL, v1);
-                k0 = mfma_bf16(tx0[cur], SL, k0);
-                k1 = mfma_bf16(tx1[cur], SL, k1);
+                v0 = mfma_bf16(tg0[tcur], PH, v0);
+                v1 = mfma_bf16(tg1[tcur], PH, v1);
+                k0 = mfma_bf16(tx0[tcur], SH, k0);
+                k1 = mfma_bf16(tx1[tcur], SH, k1);
+                v0 = mfma_bf16(tg0[tcur], PL, v0);
+                v1 = mfma_bf16(tg1[tcur], PL, v1);
+                k0 = mfma_bf16(tx0[tcur], SL, k0);
+                k1 = mfma_bf16(tx1[tcur], SL, k1);
                 __builtin_amdgcn_sched_barrier(0);
             }
             const u32x2 va = {pack_bf16(v0[0], v0[1]), pack_bf16(v0[2], v0[3])};
             const u32x2 vb = {pack_bf16(v1[0], v1[1]), pack_bf16(v1[2], v1[3])};
             const u32x2 ka = {pack_bf16(k0[0] * p.scale, k0[1] * p.scale), pack_bf16(k0[2] * p.scale, k0[3] * p.scale)};
             const u32x2 kb = {pack_bf16(k1[0] * p.scale, k1[1] * p.scale), pack_bf16(k1[2] * p.scale, k1[3] * p.scale)};
-            store_rows(va, vb, make_rsrc((char*)p.dv + tile_d, tile_bytes_d), jb);
-            store_rows(ka, kb, make_rsrc((char*)p.dk + tile_d, tile_bytes_d), jb);
+            store_rows(va, vb, make_rsrc((char*)p.dv + tile_d, tile_bytes_d));
+            store_rows(ka, kb, make_rsrc((char*)p.dk + tile_d, tile_bytes_d));
         }
-        __syncthreads();  // the slabs are rewritten for the next window
-    }
-}
-
-// dBias for 64 < L <= 256.  Its accumulator is L x L fp32 per head (256 KB at L = 256): half of
-// a CU's register file, which the two passes above need themselves.  So it has a kernel of its
-// own that redoes pass 2 only -- S and dP block by block in the "key on the lane" orientation,
-// P = exp2(score - M_i), dS = P (dP - delta_i) with M_i, delta_i as the main kernel left them in
-// global memory -- and keeps nothing but the sums: a wave owns key blocks jb = wave, wave + W, ...
-// of one head for its whole life, holds dBias[all queries][its keys] in registers across the
-// windows bw, bw + G, ... and writes them out once, in register order, as one of G partial
-// sums per head (the reduce kernel adds the slots in a fixed order).
-template <int NB, int HB, int HM>
-__global__ void __launch_bounds__(64 * dbias_waves(NB)) dbias_large_kernel(BwdArgs p, LargeGeom gm) {
-    constexpr bool BM = HB != 0 || HM != 0;
-    constexpr int W = dbias_waves(NB);
-    constexpr int JPW = (NB + W - 1) / W;  // key blocks per wave
-    constexpr int NB2 = (NB + 1) / 2;
-    constexpr int ROWS = 16 * NB;
-    constexpr int PASSES = (ROWS + 16 * W - 1) / (16 * W);
-    constexpr uint32_t STRIDE = 5;
-    extern __shared__ __attribute__((aligned(16))) uint4 lds[];
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int n = lane & 15, g = lane >> 4;
-    const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const uint32_t lb = xcd_logical_block(blockIdx.x, gm.xcd_q, gm.xcd_r);
-    const uint32_t h = lb % gm.heads, bw = lb / gm.heads;
-    const int L = p.L;
-    const uint32_t row_bytes = (uint32_t)p.ldq * 2u, row_g = (uint32_t)p.ldg * 2u;
-    const float sl2 = p.scale * kLog2e;
-    const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
-
-    uint4* const lk = lds;
-    uint4* const lv = lds + ROWS * STRIDE;
-    uint4* const lq = lds + 2 * ROWS * STRIDE;
-    uint4* const lg = lds + 3 * ROWS * STRIDE;
-    float* const stM = reinterpret_cast<float*>(lds + 4 * ROWS * STRIDE);  // M[ROWS] then delta[ROWS]
-
-    const uint32_t ll = (uint32_t)L * L * 4u;
-    const uint32_t srow = (uint32_t)tid >> 2, scol = (uint32_t)tid & 3u;
-    const uint32_t tile_bytes = (uint32_t)(L - 1) * row_bytes + 2u * kHeadDim;
-    const uint32_t tile_bytes_g = (uint32_t)(L - 1) * row_g + 2u * kHeadDim;
-    const uint32_t opd = (uint32_t)n * STRIDE + g;
-
-    f32x4 dbacc[JPW][NB];
-#pragma unroll
-    for (int a = 0; a < JPW; ++a)
-#pragma unroll
-        for (int b = 0; b < NB; ++b) dbacc[a][b] = zero;
-
-    for (uint32_t w = bw; w < (uint32_t)p.N; w += gm.G) {
-        const __amdgpu_buffer_rsrc_t rl =
-            HM == 2 ? make_rsrc(p.labels + (size_t)(w % (uint32_t)p.nW) * L, (uint32_t)L * 4u) : make_rsrc(nullptr, 0);
-        {
-            const size_t tile = ((size_t)w * L * p.ldq + (size_t)h * kHeadDim) * 2u;
-            const size_t tile_g = ((size_t)w * L * p.ldg + (size_t)h * kHeadDim) * 2u;
-            const __amdgpu_buffer_rsrc_t rk = make_rsrc((const char*)p.k + tile, tile_bytes);
-            const __amdgpu_buffer_rsrc_t rv = make_rsrc((const char*)p.v + tile, tile_bytes);
-            const __amdgpu_buffer_rsrc_t rq = make_rsrc((const char*)p.q + tile, tile_bytes);
-            const __amdgpu_buffer_rsrc_t rg = make_rsrc((const char*)p.d_o + tile_g, tile_bytes_g);
-            const __amdgpu_buffer_rsrc_t rs =
-                make_rsrc(p.stats + ((size_t)w * p.heads + h) * (2 * ROWS), (uint32_t)(2 * ROWS * 4));
-            u32x4 pk[PASSES], pv[PASSES], pq[PASSES], pg[PASSES];
-#pragma unroll
-            for (int t = 0; t < PASSES; ++t) {
-                const uint32_t off = (16 * W * t + srow) * row_bytes + scol * 16u;  // rows beyond L arrive as zeros
-                pk[t] = __builtin_amdgcn_raw_buffer_load_b128(rk, off, 0, 0);
-                pv[t] = __builtin_amdgcn_raw_buffer_load_b128(rv, off, 0, 0);
-                pq[t] = __builtin_amdgcn_raw_buffer_load_b128(rq, off, 0, 0);
-                pg[t] = __builtin_amdgcn_raw_buffer_load_b128(rg, (16 * W * t + srow) * row_g + scol * 16u, 0, 0);
-            }
-            // 2 ROWS floats of statistics: 16 bytes per thread, the first ROWS / 2 threads
-            const u32x4 st4 = __builtin_amdgcn_raw_buffer_load_b128(rs, (uint32_t)tid * 16u, 0, 0);
-#pragma unroll
-            for (int t = 0; t < PASSES; ++t) {
-                const uint32_t row = 16 * W * t + srow;
-                if (row < (uint32_t)ROWS) {
-                    lk[row * STRIDE + scol] = __builtin_bit_cast(uint4, pk[t]);
-                    lv[row * STRIDE + scol] = __builtin_bit_cast(uint4, pv[t]);
-                    lq[row * STRIDE + scol] = __builtin_bit_cast(uint4, pq[t]);
-                    lg[row * STRIDE + scol] = __builtin_bit_cast(uint4, pg[t]);
-                }
-            }
-            if (tid < ROWS / 2) reinterpret_cast<uint4*>(stM)[tid] = __builtin_bit_cast(uint4, st4);
-        }
+        __syncthreads();  // every wave is done with the slabs
+        if (has_next) park();
         __syncthreads();
-        const float* const stD = stM + ROWS;
-
-#pragma unroll
-        for (int a = 0; a < JPW; ++a) {
-            const int jb = (int)wave + a * W;
-            if (jb < NB) {
-                const bf16x8 kop = __builtin_bit_cast(bf16x8, lk[opd + 16 * jb * STRIDE]);
-                const bf16x8 vop = __builtin_bit_cast(bf16x8, lv[opd + 16 * jb * STRIDE]);
-                const uint32_t jcol = 16u * jb + n;
-                const bool valid = jcol < (uint32_t)L;
-                uint32_t aoff[4];
-#pragma unroll
-                for (int r = 0; r < 4; ++r) aoff[r] = ((uint32_t)(4 * g + r) * L + jcol) * 4u;
-                bf16x8 oq[2][2], og[2][2];
-                f32x4 oM[2][2], oD[2][2], ab[2][2], am[2][2];
-                i32x4 al[2][2];
-                const int lkey = HM == 2 ? load_i32(rl, jcol * 4u) : 0;
-                auto fetch_one = [&](int qb, int slot, int u) {
-                    oq[slot][u] = __builtin_bit_cast(bf16x8, lq[opd + 16 * qb * STRIDE]);
-                    og[slot][u] = __builtin_bit_cast(bf16x8, lg[opd + 16 * qb * STRIDE]);
-                    oM[slot][u] = *reinterpret_cast<const f32x4*>(stM + 16 * qb + 4 * g);
-                    oD[slot][u] = *reinterpret_cast<const f32x4*>(stD + 16 * qb + 4 * g);
-                    if (BM) {
-                        const uint32_t qrow = (uint32_t)(16 * qb) * L;
-                        const __amdgpu_buffer_rsrc_t rbq =
-                            HB == 1 ? make_rsrc(static_cast<const float*>(p.bias) + (size_t)h * L * L + qrow, ll - 4u * qrow)
-                                    : make_rsrc(nullptr, 0);
-                        const __amdgpu_buffer_rsrc_t rmq =
-                            HM == 1 ? make_rsrc(p.mask + (size_t)(w % (uint32_t)p.nW) * L * L + qrow, ll - 4u * qrow)
-                                    : make_rsrc(nullptr, 0);
-#pragma unroll
-                        for (int r = 0; r < 4; ++r) {
-                            if (HB == 1) ab[slot][u][r] = load_f32(rbq, aoff[r]);
-                            if (HM == 1) am[slot][u][r] = load_f32(rmq, aoff[r]);
-                        }
-                        if (HM == 2) al[slot][u] = load_i32x4(rl, (uint32_t)(16 * qb + 4 * g) * 4u);
-                    }
-                };
-                auto fetch = [&](int qp, int slot) {
-                    fetch_one(2 * qp, slot, 0);
-                    if (2 * qp + 1 < NB) fetch_one(2 * qp + 1, slot, 1);
-                };
-                // operands of the next pair of query blocks on their way during the arithmetic of this one;
-                // not where a wave has one key block and the SIMD holds four waves that cover for one
-                // another, with 128 registers each: there one block at a time
-                constexpr bool AHEAD = JPW > 1;
-                if (AHEAD) fetch(0, 0);
-#pragma unroll
-                for (int qp = 0; qp < NB2; ++qp) {
-                    const int cur = AHEAD ? (qp & 1) : 0;
-                    if (AHEAD && qp + 1 < NB2) fetch(qp + 1, cur ^ 1);
-                    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-                    for (int v = 0; v < 2; ++v) {
-                        if (v == 1 && 2 * qp + 1 >= NB) break;
-                        if (!AHEAD) fetch_one(2 * qp + v, 0, 0);
-                        const int u = AHEAD ? v : 0;
-                        const f32x4 sc = mfma_bf16(oq[cur][u], kop, zero);  // <q_i, k_j>, i = 16 qb + 4g + r, j = jcol
-                        const f32x4 dp = mfma_bf16(og[cur][u], vop, zero);
-#pragma unroll
-                        for (int r = 0; r < 4; ++r) {
-                            float x;
-                            if (BM) {
-                                const float mk = HM == 2 ? (al[cur][u][r] == lkey ? 0.f : p.mask_value) : am[cur][u][r];
-                                const float bv = ab[cur][u][r];
-                                const float add = HB && HM ? bv + mk : (HB ? bv : mk);
-                                x = fmaf(sc[r], sl2, fmaf(add, kLog2e, -oM[cur][u][r]));
-                            } else {
-                                x = fmaf(sc[r], sl2, -oM[cur][u][r]);
-                            }
-                            const float pr = valid ? __builtin_amdgcn_exp2f(x) : 0.f;
-                            dbacc[a][2 * qp + v][r] += pr * (dp[r] - oD[cur][u][r]);
-                        }
-                    }
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-            }
-        }
-        __syncthreads();  // the slabs are rewritten for the next window
     }
 
     // partial sums in register order: [slot][head][jb][qb][lane] float4, element r of lane (g, n) being
     // dS summed over windows for query 16 qb + 4g + r and key 16 jb + n
-    f32x4* dst = reinterpret_cast<f32x4*>(p.partial) + ((size_t)bw * p.heads + h) * (NB * NB * 64) + lane;
+    if (active) {
+        f32x4* dst = reinterpret_cast<f32x4*>(p.partial) + ((size_t)bw * p.heads + h) * (NB * NB * 64) + lane;
 #pragma unroll
-    for (int a = 0; a < JPW; ++a) {
-        const int jb = (int)wave + a * W;
-        if (jb < NB) {
-#pragma unroll
-            for (int qb = 0; qb < NB; ++qb) dst[(jb * NB + qb) * 64] = dbacc[a][qb];
-        }
+        for (int qb = 0; qb < NB; ++qb) dst[(jb * NB + qb) * 64] = dbacc[qb];
     }
 }
 
-template <int NB, int HB, int HM>
-hipError_t launch_dbias_large(const BwdArgs& a, hipStream_t st) {
-    constexpr int W = dbias_waves(NB);
-    const void* fn = reinterpret_cast<const void*>(&dbias_large_kernel<NB, HB, HM>);
-    const unsigned block = 64u * W;
-    const size_t lds = (size_t)4 * 16 * NB * 5 * 16 + (size_t)2 * 16 * NB * 4;
-    {
-        const hipError_t e = allow_lds(fn, lds);
-        if (e != hipSuccess) return e;
+// Workgroups of `fn` one CU holds (LDS and registers decide), asked once per kernel; threads racing
+// through the first call ask twice and store the same figure.
+hipError_t workgroups_per_cu(const void* fn, unsigned block, size_t lds, std::atomic<int>& once, int& per_cu) {
+    const hipError_t e = allow_lds(fn, lds);
+    if (e != hipSuccess) return e;
+    per_cu = once.load(std::memory_order_relaxed);
+    if (per_cu == 0) {
+        int nblk = 0;
+        const hipError_t q = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nblk, fn, (int)block, lds);
+        if (q != hipSuccess) return q;
+        per_cu = nblk < 1 ? 1 : nblk;
+        once.store(per_cu, std::memory_order_relaxed);
     }
+    return hipSuccess;
+}
+
+// dK, dV and the dBias partial sums; `slots` receives the number of partial sums per head
+template <int NB, int HB, int HM>
+hipError_t launch_large_keys(const BwdArgs& a, hipStream_t st, int& slots) {
+    constexpr int W = keys_waves(NB), HALVES = keys_parts(NB);
+    const void* fn = reinterpret_cast<const void*>(&bwd_bf16_large_keys_kernel<NB, HB, HM>);
+    const unsigned block = 64u * W;
+    const size_t lds = (size_t)2 * 16 * NB * 5 * 16 + (size_t)2 * 16 * NB * 4 + (size_t)W * 16 * 80;  // slabs, statistics, the waves' output cells
+    static std::atomic<int> once{0};
+    int per_cu = 1;
+    const hipError_t e = workgroups_per_cu(fn, block, lds, once, per_cu);
+    if (e != hipSuccess) return e;
     LargeGeom gm;
     gm.heads = (uint32_t)a.heads;
-    gm.G = (uint32_t)a.slots;
-    const unsigned grid = gm.G * gm.heads;
+    long long G = (long long)cu_count() * per_cu / ((long long)a.heads * HALVES);  // resident workgroups only
+    if (G > a.slots) G = a.slots;  // the workspace holds a.slots partial sums per head
+    if (G > a.N) G = a.N;
+    if (G < 1) G = 1;
+    gm.G = (uint32_t)G;
+    slots = (int)G;
+    const unsigned grid = gm.G * gm.heads * HALVES;
     gm.xcd_q = grid / 8u;
     gm.xcd_r = grid % 8u;
-    hipLaunchKernelGGL((dbias_large_kernel<NB, HB, HM>), dim3(grid), dim3(block), lds, st, a, gm);
+    hipLaunchKernelGGL((bwd_bf16_large_keys_kernel<NB, HB, HM>), dim3(grid), dim3(block), lds, st, a, gm);
     return hipGetLastError();
 }
 
-template <int NB, int HB, int HM>
+template <int NB, int HB, int HM, bool P2>
 hipError_t launch_large_one(const BwdArgs& a, hipStream_t st) {
     constexpr int W = large_waves(NB);
-    const void* fn = reinterpret_cast<const void*>(&bwd_bf16_large_kernel<NB, HB, HM>);
+    const void* fn = reinterpret_cast<const void*>(&bwd_bf16_large_kernel<NB, HB, HM, P2>);
     const unsigned block = 64u * W;
     const size_t lds = (size_t)4 * 16 * NB * 5 * 16 + (size_t)2 * 16 * NB * 4 + (size_t)W * 16 * 68 * 4;  // slabs, statistics, one patch per wave
-    // Workgroups one CU holds (LDS and registers decide), asked once per kernel; threads racing
-    // through the first call ask twice and store the same figure.
-    static std::atomic<int> per_cu_once{0};
-    {
-        const hipError_t e = allow_lds(fn, lds);
-        if (e != hipSuccess) return e;
-    }
-    int per_cu = per_cu_once.load(std::memory_order_relaxed);
-    if (per_cu == 0) {
-        int nblk = 0;
-        const hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nblk, fn, (int)block, lds);
-        if (e != hipSuccess) return e;
-        per_cu = nblk < 1 ? 1 : nblk;
-        per_cu_once.store(per_cu, std::memory_order_relaxed);
-    }
+    static std::atomic<int> once{0};
+    int per_cu = 1;
+    const hipError_t e = workgroups_per_cu(fn, block, lds, once, per_cu);
+    if (e != hipSuccess) return e;
     LargeGeom gm;
     gm.heads = (uint32_t)a.heads;
     long long G = (long long)cu_count() * per_cu / a.heads;  // one resident workgroup per slot and head
@@ -645,16 +744,23 @@ hipError_t launch_large_one(const BwdArgs& a, hipStream_t st) {
     const unsigned grid = gm.G * gm.heads;
     gm.xcd_q = grid / 8u;
     gm.xcd_r = grid % 8u;
-    hipLaunchKernelGGL((bwd_bf16_large_kernel<NB, HB, HM>), dim3(grid), dim3(block), lds, st, a, gm);
+    hipLaunchKernelGGL((bwd_bf16_large_kernel<NB, HB, HM, P2>), dim3(grid), dim3(block), lds, st, a, gm);
     return hipGetLastError();
 }
 
+// Without dBias one kernel does both passes.  With it: pass 1 (dQ, statistics), then the keys kernel
+// (dK, dV, dBias partial sums), then the reduction of the partial sums.
 template <int NB, int HB, int HM>
 hipError_t launch_large_both(const BwdArgs& a, hipStream_t st) {
-    hipError_t e = launch_large_one<NB, HB, HM>(a, st);
-    if (e != hipSuccess || a.dbias == nullptr) return e;
-    e = launch_dbias_large<NB, HB, HM>(a, st);
-    return e != hipSuccess ? e : launch_dbias_reduce(a, st, true);
+    if (a.dbias == nullptr) return launch_large_one<NB, HB, HM, true>(a, st);
+    hipError_t e = launch_large_one<NB, HB, HM, false>(a, st);
+    if (e != hipSuccess) return e;
+    int slots = a.slots;
+    e = launch_large_keys<NB, HB, HM>(a, st, slots);
+    if (e != hipSuccess) return e;
+    BwdArgs r = a;
+    r.slots = slots;
+    return launch_dbias_reduce(r, st, true);
 }
 
 template <int NB>
