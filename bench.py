@@ -127,7 +127,7 @@ def time_other_workloads(torch, fwa, synth, dev):
 
     def run(name, w, backward, iters, want_dbias=True, as_labels=False, bias_bf16=False):
         shape = (w.N, w.L, w.C)
-        tdt, esz = (torch.float32, 4) if w.dtype == "f32" else (torch.bfloat16, 2)
+        tdt, esz = {"f32": (torch.float32, 4), "bf16": (torch.bfloat16, 2), "f16": (torch.float16, 2)}[w.dtype]
         per_set = (7 if backward else 4) * w.N * w.L * w.C * esz
         nsets = max(2, -(-2 * LLC_BYTES // per_set) + 1)
         g = torch.Generator(device=dev).manual_seed(w.seed)
@@ -144,7 +144,7 @@ def time_other_workloads(torch, fwa, synth, dev):
         elif w.shift:
             mask = torch.from_numpy(synth.shift_mask(w.map_hw, w.map_hw, w.k, w.shift)).to(dev)
         if backward:
-            need = fwa.fwa_backward_workspace_bytes(w.N, w.L, w.C, w.heads, 0 if w.dtype == "f32" else 1, want_dbias)
+            need = fwa.fwa_backward_workspace_bytes(w.N, w.L, w.C, w.heads, {"f32": 0, "bf16": 1, "f16": 2}[w.dtype], want_dbias)
             ws = torch.empty(max(need, 16), dtype=torch.uint8, device=dev)
 
         def step(i):
@@ -246,6 +246,10 @@ def paper_shapes(run):
         pw = synth.Workload(f"paper_L64_d{d}", 4096, 64, 4 * d, 4, "bf16", 1100 + d, 8)
         run(f"paper_benchmark_shape_fwd (N=4096, L=64, 4 heads x {d})", pw, False, 50)
         run(f"paper_benchmark_shape_bwd (N=4096, L=64, 4 heads x {d}; dQ, dK, dV)", pw, True, 30, want_dbias=False)
+        # IEEE half data, the precision of the paper's comparison with flash-attention (section 3.3)
+        ph = synth.Workload(f"paper_L64_d{d}_f16", 4096, 64, 4 * d, 4, "f16", 1150 + d, 8)
+        run(f"paper_benchmark_shape_fwd_fp16 (N=4096, L=64, 4 heads x {d})", ph, False, 50)
+        run(f"paper_benchmark_shape_bwd_fp16 (N=4096, L=64, 4 heads x {d}; dQ, dK, dV)", ph, True, 30, want_dbias=False)
         # the same in the paper's own precision (fp32 data and arithmetic), half the windows
         pf = synth.Workload(f"paper_L64_d{d}_f32", 2048, 64, 4 * d, 4, "f32", 1200 + d, 8)
         run(f"paper_benchmark_shape_fwd_fp32 (N=2048, L=64, 4 heads x {d})", pf, False, 20)

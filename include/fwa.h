@@ -22,9 +22,13 @@
  *    Supported: d == 32 with 1 <= L <= 256; d == 64, 128, 256 with
  *    1 <= L <= 64 (the feature-dimension loop of paper eq. 5-6; the shapes of
  *    its Section 3.1 benchmark), in both dtypes.  N >= 0 (N == 0 is a no-op).
- *  - dtype is FWA_F32 (fp32 data, fp32 arithmetic) or FWA_BF16 (bf16 data,
+ *  - dtype is FWA_F32 (fp32 data, fp32 arithmetic), FWA_BF16 (bf16 data,
  *    bf16 matrix-core products with fp32 accumulation, fp32 softmax, one final
- *    round-to-nearest-even to bf16).
+ *    round-to-nearest-even to bf16) or FWA_F16 (IEEE half data, handled like
+ *    bf16 with half products; head widths 64, 128 and 256 only, i.e. the
+ *    shapes and the precision of the paper's Section 3 comparisons;
+ *    FWA_ERR_UNSUPPORTED at head width 32).  With half data every intermediate
+ *    that enters a matrix product -- P, dS -- must stay inside the half range.
  *  - mask and dbias are always fp32; bias is fp32, or bf16 through the
  *    *_labels entry points (bias_dtype).
  *  - Base pointers must be 16-byte aligned.  No output may share a byte with an
@@ -52,7 +56,7 @@
 extern "C" {
 #endif
 
-enum { FWA_F32 = 0, FWA_BF16 = 1 };
+enum { FWA_F32 = 0, FWA_BF16 = 1, FWA_F16 = 2 };
 
 enum {
     FWA_OK = 0,
@@ -95,8 +99,8 @@ int fwa_forward_strided(const void* q, const void* k, const void* v, void* o,
 
 /*
  * Backward pass (paper Algorithm 2).  Inputs are Q, K, V and dO only.
- * Supported: FWA_BF16 in every shape the forward takes; FWA_F32 for
- * L <= 64 without dbias (FWA_ERR_UNSUPPORTED otherwise).
+ * Supported: FWA_BF16 and FWA_F16 in every shape the forward takes them;
+ * FWA_F32 for L <= 64 without dbias (FWA_ERR_UNSUPPORTED otherwise).
  *   d_o        : in,  [N, L, C], dtype
  *   dq, dk, dv : out, [N, L, C], dtype, fully overwritten
  *   dbias      : NULL, or out [heads, L, L] fp32 = sum over all N windows of

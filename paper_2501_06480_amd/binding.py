@@ -13,6 +13,7 @@ from typing import Optional
 
 FWA_F32 = 0
 FWA_BF16 = 1
+FWA_F16 = 2
 
 FWA_OK = 0
 FWA_ERR_NULL = 1
@@ -93,6 +94,8 @@ def _dtype_code(t) -> int:
         return FWA_F32
     if t.dtype == torch.bfloat16:
         return FWA_BF16
+    if t.dtype == torch.float16:
+        return FWA_F16
     raise TypeError(f"unsupported tensor dtype {t.dtype}")
 
 

@@ -68,10 +68,12 @@ inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) &
 int check_shape(int64_t N, int L, int C, int heads, int dtype, bool wide_ok) {
     if (N < 0 || L < 1 || C < 1 || heads < 1) return FWA_ERR_SHAPE;
     if (C % heads != 0) return FWA_ERR_SHAPE;
-    if (dtype != FWA_F32 && dtype != FWA_BF16) return FWA_ERR_UNSUPPORTED;
+    if (dtype != FWA_F32 && dtype != FWA_BF16 && dtype != FWA_F16) return FWA_ERR_UNSUPPORTED;
     if (C / heads != fwa::kHeadDim &&
         !(wide_ok && fwa::forward_wide_supported(L, C / heads)))
         return FWA_ERR_UNSUPPORTED;
+    // half data: the wide-head kernels only (head widths 64, 128, 256 at L <= 64)
+    if (dtype == FWA_F16 && C / heads == fwa::kHeadDim) return FWA_ERR_UNSUPPORTED;
     if (L > fwa::kMaxL) return FWA_ERR_UNSUPPORTED;
     // one launch: the number of wave tasks (at most 4 per window-head) must fit a 32-bit grid
     if ((double)N * heads * 4.0 > 2.0e9) return FWA_ERR_UNSUPPORTED;
@@ -81,7 +83,7 @@ int check_shape(int64_t N, int L, int C, int heads, int dtype, bool wide_ok) {
 // The backward covers bf16 data in every shape of the forward, and fp32 data for windows of up to
 // 64 tokens without dBias.
 int check_backward_support(int L, int dtype, bool want_dbias) {
-    if (dtype != FWA_BF16 && (L > fwa::kMaxWideL || want_dbias)) return FWA_ERR_UNSUPPORTED;
+    if (dtype == FWA_F32 && (L > fwa::kMaxWideL || want_dbias)) return FWA_ERR_UNSUPPORTED;
     return FWA_OK;
 }
 
@@ -101,7 +103,7 @@ size_t large_bias_copy_bytes(int L, int heads) {
 // Row stride of a strided tensor, in elements: at least C, rows 16-byte aligned, and small enough
 // that the byte offsets inside one window fit 32 bits with room to spare.
 int check_row_stride(int64_t ld, int C, int dtype) {
-    const int64_t per16 = dtype == FWA_BF16 ? 8 : 4;
+    const int64_t per16 = dtype == FWA_F32 ? 4 : 8;
     if (ld < C) return FWA_ERR_SHAPE;
     if (ld % per16 != 0) return FWA_ERR_ALIGN;
     if (ld > (int64_t)1 << 20) return FWA_ERR_UNSUPPORTED;
@@ -115,7 +117,7 @@ struct Span {
     uintptr_t end() const { return base + (rows - 1) * ld + width; }
 };
 Span span_of(const void* p, int64_t N, int L, int C, int64_t ld, int dtype) {
-    const uint64_t e = dtype == FWA_BF16 ? 2 : 4;
+    const uint64_t e = dtype == FWA_F32 ? 4 : 2;
     return Span{reinterpret_cast<uintptr_t>(p), (uint64_t)ld * e, (uint64_t)C * e, (uint64_t)N * (uint64_t)L};
 }
 // Whether two such tensors share a byte.  Tensors whose extents are disjoint do not.  With equal row
@@ -164,10 +166,10 @@ int forward_impl(const void* q, const void* k, const void* v, void* o, int64_t N
     a.bias = bias; a.bias_bf16 = bias && bias_dtype == FWA_BF16;
     a.mask = mask; a.labels = labels; a.mask_value = mask_value;
     a.N = N; a.L = L; a.C = C; a.heads = heads; a.nW = (mask || labels) ? nW : 1; a.scale = scale;
-    a.ldq = (int)ld_qkv; a.ldo = (int)ld_o;
+    a.ldq = (int)ld_qkv; a.ldo = (int)ld_o; a.f16 = dtype == FWA_F16;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const bool wide = C / heads != fwa::kHeadDim;
-    const hipError_t e = dtype != FWA_BF16 ? (wide || L <= fwa::kMaxWideL ? fwa::launch_forward_f32_tile(a, st) : fwa::launch_forward_f32(a, st))
+    const hipError_t e = dtype == FWA_F32 ? (wide || L <= fwa::kMaxWideL ? fwa::launch_forward_f32_tile(a, st) : fwa::launch_forward_f32(a, st))
                                            : (wide ? fwa::launch_forward_bf16_wide(a, st) : fwa::launch_forward_bf16(a, st));
     return e == hipSuccess ? FWA_OK : FWA_ERR_LAUNCH;
 }
@@ -372,11 +374,11 @@ int backward_impl(const void* q, const void* k, const void* v, const void* d_o, 
         a.partial = reinterpret_cast<float*>(ws + large_stats_bytes(N, L, heads));
     }
     a.bias = bias; a.bias_bf16 = bias && bias_dtype == FWA_BF16;
-    a.ldq = (int)ld_qkv; a.ldg = (int)ld_do; a.ldd = (int)ld_dqkv;
+    a.ldq = (int)ld_qkv; a.ldg = (int)ld_do; a.ldd = (int)ld_dqkv; a.f16 = dtype == FWA_F16;
     // the one-wave-per-tile kernel takes fp32 biases only
     if (a.bias_bf16 && small && !a.per_window && fwa::coop_slots(N, heads, a.nW) == 0)
         return FWA_ERR_UNSUPPORTED;
-    const hipError_t e = dtype == FWA_BF16 ? fwa::launch_backward_bf16(a, st) : fwa::launch_backward_f32(a, st);
+    const hipError_t e = dtype != FWA_F32 ? fwa::launch_backward_bf16(a, st) : fwa::launch_backward_f32(a, st);
     return e == hipSuccess ? FWA_OK : FWA_ERR_LAUNCH;
 }
 

@@ -31,7 +31,11 @@
 namespace fwa {
 namespace {
 
-template <int NB, int D, bool BM, bool DB>
+// F16: the data are IEEE half instead of bf16.  P and dS then enter the matrix cores as single half
+// operands (11 significant bits, against 16 for the hi + lo bf16 pairs: products stay within 3e-4
+// relative, far inside the 1e-2 bound), so the lo tiles, their LDS traffic and the second product of
+// each pair are absent.  |dS| must stay inside the half range (65504), as everything in half data must.
+template <int NB, int D, bool BM, bool DB, bool F16>
 __global__ void __launch_bounds__(256) bwd_bf16_wide_kernel(BwdArgs p, uint32_t G) {
     constexpr int NB2 = (NB + 1) / 2;
     constexpr int ROWS = 16 * NB;
@@ -43,6 +47,7 @@ __global__ void __launch_bounds__(256) bwd_bf16_wide_kernel(BwdArgs p, uint32_t 
     constexpr int RPP = 256 / TPR;           // rows per pass of the workgroup
     constexpr int PASSES = (ROWS + RPP - 1) / RPP;
     constexpr uint32_t XS = 64, XT = ROWS * XS;  // P / dS tiles: [ROWS][64] bf16, units swizzled (see below)
+    constexpr int NT = F16 ? 2 : 4;              // tiles: P, dS (half) or P_hi, P_lo, dS_hi, dS_lo (bf16)
     extern __shared__ __attribute__((aligned(16))) uint4 lds[];
     const int tid = threadIdx.x, lane = tid & 63;
     const int n = lane & 15, g = lane >> 4;
@@ -72,7 +77,7 @@ __global__ void __launch_bounds__(256) bwd_bf16_wide_kernel(BwdArgs p, uint32_t 
     // (a 128-byte line per row) at a time: written in accumulator order, read back 16 bytes per lane,
     // two stores of 8 whole lines each instead of four stores of 32-byte pieces (12 % at width 128,
     // 8-11 % at width 64 although the 9 KB cost it one of its three workgroups per CU).
-    char* const mine = reinterpret_cast<char*>(ex + 4 * XT) + role * (16 * 144);
+    char* const mine = reinterpret_cast<char*>(ex + NT * XT) + role * (16 * 144);
     auto gather = [&](const u32x2 v, int cb) { *reinterpret_cast<u32x2*>(mine + n * 144 + (cb & 3) * 32 + g * 8) = v; };
     auto flush = [&](const __amdgpu_buffer_rsrc_t dst, int blk, int cb) {
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
@@ -144,8 +149,8 @@ __global__ void __launch_bounds__(256) bwd_bf16_wide_kernel(BwdArgs p, uint32_t 
         for (int c = 0; c < CH; ++c)
 #pragma unroll
             for (int jb = 0; jb < NB; ++jb) {
-                s[jb] = mfma_bf16(__builtin_bit_cast(bf16x8, sa[opd + 16 * jb * STRIDE + 4 * c]), qop[c], s[jb]);
-                dp[jb] = mfma_bf16(__builtin_bit_cast(bf16x8, sb[opd + 16 * jb * STRIDE + 4 * c]), gop[c], dp[jb]);
+                s[jb] = mfma_e<F16>(__builtin_bit_cast(bf16x8, sa[opd + 16 * jb * STRIDE + 4 * c]), qop[c], s[jb]);
+                dp[jb] = mfma_e<F16>(__builtin_bit_cast(bf16x8, sb[opd + 16 * jb * STRIDE + 4 * c]), gop[c], dp[jb]);
             }
         // softmax of the block's rows: s <- exp(score - rowmax), inv = 1 / rowsum
         float inv;
@@ -171,14 +176,23 @@ __global__ void __launch_bounds__(256) bwd_bf16_wide_kernel(BwdArgs p, uint32_t 
 #pragma unroll
             for (int r = 0; r < 4; ++r) dp[jb][r] = s[jb][r] * (dp[jb][r] - delta);  // dS
             if (DB) dbacc[jb] += dp[jb];
-            bf16x4 p_hi, p_lo;
-            split_hi_lo(s[jb], p_hi, p_lo);
-            split_hi_lo(dp[jb], ds_hi[jb], ds_lo[jb]);
             uint16_t* cell = ex + (16 * qb + n) * XS + ((jb ^ (n & 3)) << 4) + ((g ^ ((n >> 2) & 3)) << 2);
-            *reinterpret_cast<uint2*>(cell + 0 * XT) = __builtin_bit_cast(uint2, p_hi);
-            *reinterpret_cast<uint2*>(cell + 1 * XT) = __builtin_bit_cast(uint2, p_lo);
-            *reinterpret_cast<uint2*>(cell + 2 * XT) = __builtin_bit_cast(uint2, ds_hi[jb]);
-            *reinterpret_cast<uint2*>(cell + 3 * XT) = __builtin_bit_cast(uint2, ds_lo[jb]);
+            if constexpr (F16) {
+                const uint2 ph = {pack_e<true>(s[jb][0], s[jb][1]), pack_e<true>(s[jb][2], s[jb][3])};
+                const uint2 dh = {pack_e<true>(dp[jb][0], dp[jb][1]), pack_e<true>(dp[jb][2], dp[jb][3])};
+                ds_hi[jb] = as_bf16x4(dh);
+                ds_lo[jb] = as_bf16x4(uint2{0u, 0u});
+                *reinterpret_cast<uint2*>(cell + 0 * XT) = ph;
+                *reinterpret_cast<uint2*>(cell + 1 * XT) = dh;
+            } else {
+                bf16x4 p_hi, p_lo;
+                split_hi_lo(s[jb], p_hi, p_lo);
+                split_hi_lo(dp[jb], ds_hi[jb], ds_lo[jb]);
+                *reinterpret_cast<uint2*>(cell + 0 * XT) = __builtin_bit_cast(uint2, p_hi);
+                *reinterpret_cast<uint2*>(cell + 1 * XT) = __builtin_bit_cast(uint2, p_lo);
+                *reinterpret_cast<uint2*>(cell + 2 * XT) = __builtin_bit_cast(uint2, ds_hi[jb]);
+                *reinterpret_cast<uint2*>(cell + 3 * XT) = __builtin_bit_cast(uint2, ds_lo[jb]);
+            }
         }
         // dS of pairs of key blocks as operands (keys on the k-slots)
         bf16x8 dh[NB2], dl[NB2];
@@ -203,10 +217,10 @@ __global__ void __launch_bounds__(256) bwd_bf16_wide_kernel(BwdArgs p, uint32_t 
 #pragma unroll
             for (int kp = 0; kp < NB2; ++kp) {
                 const bf16x8 kt = operand_tr(lk16 + (32 * kp) * SROW + 16 * cb, 16 * SROW, 2 * kp + 1 < NB);
-                acc = mfma_bf16(kt, dh[kp], acc);
-                acc = mfma_bf16(kt, dl[kp], acc);
+                acc = mfma_e<F16>(kt, dh[kp], acc);
+                if constexpr (!F16) acc = mfma_bf16(kt, dl[kp], acc);
             }
-            const u32x2 v = {pack_bf16(acc[0] * p.scale, acc[1] * p.scale), pack_bf16(acc[2] * p.scale, acc[3] * p.scale)};
+            const u32x2 v = {pack_e<F16>(acc[0] * p.scale, acc[1] * p.scale), pack_e<F16>(acc[2] * p.scale, acc[3] * p.scale)};
             gather(v, cb);
             if ((cb & 3) == 3) flush(rdq, qb, cb);
         }
@@ -235,9 +249,11 @@ __global__ void __launch_bounds__(256) bwd_bf16_wide_kernel(BwdArgs p, uint32_t 
         for (int qp = 0; qp < NB2; ++qp) {
             const bool two = 2 * qp + 1 < NB;
             ph[qp] = operand_tr(xt + 0 * XT + (32 * qp) * XS, 16 * XS, two);
-            pl[qp] = operand_tr(xt + 1 * XT + (32 * qp) * XS, 16 * XS, two);
-            sh[qp] = operand_tr(xt + 2 * XT + (32 * qp) * XS, 16 * XS, two);
-            sl[qp] = operand_tr(xt + 3 * XT + (32 * qp) * XS, 16 * XS, two);
+            sh[qp] = operand_tr(xt + (F16 ? 1 : 2) * XT + (32 * qp) * XS, 16 * XS, two);
+            if constexpr (!F16) {
+                pl[qp] = operand_tr(xt + 1 * XT + (32 * qp) * XS, 16 * XS, two);
+                sl[qp] = operand_tr(xt + 3 * XT + (32 * qp) * XS, 16 * XS, two);
+            }
         }
         const uint16_t* lq16 = reinterpret_cast<const uint16_t*>(sa) + trs;
         const uint16_t* lg16 = reinterpret_cast<const uint16_t*>(sb) + trs;
@@ -252,13 +268,15 @@ __global__ void __launch_bounds__(256) bwd_bf16_wide_kernel(BwdArgs p, uint32_t 
                 const bool two = 2 * qp + 1 < NB;
                 const bf16x8 gt = operand_tr(lg16 + (32 * qp) * SROW + 16 * cb, 16 * SROW, two);
                 const bf16x8 qt = operand_tr(lq16 + (32 * qp) * SROW + 16 * cb, 16 * SROW, two);
-                av = mfma_bf16(gt, ph[qp], av);
-                ak = mfma_bf16(qt, sh[qp], ak);
-                av = mfma_bf16(gt, pl[qp], av);
-                ak = mfma_bf16(qt, sl[qp], ak);
+                av = mfma_e<F16>(gt, ph[qp], av);
+                ak = mfma_e<F16>(qt, sh[qp], ak);
+                if constexpr (!F16) {
+                    av = mfma_bf16(gt, pl[qp], av);
+                    ak = mfma_bf16(qt, sl[qp], ak);
+                }
             }
-            const u32x2 vv = {pack_bf16(av[0], av[1]), pack_bf16(av[2], av[3])};
-            const u32x2 vk = {pack_bf16(ak[0] * p.scale, ak[1] * p.scale), pack_bf16(ak[2] * p.scale, ak[3] * p.scale)};
+            const u32x2 vv = {pack_e<F16>(av[0], av[1]), pack_e<F16>(av[2], av[3])};
+            const u32x2 vk = {pack_e<F16>(ak[0] * p.scale, ak[1] * p.scale), pack_e<F16>(ak[2] * p.scale, ak[3] * p.scale)};
             // dV through the cells block by block; dK waits in registers and follows
             gather(vv, cb);
             kwait[cb & 3] = vk;
@@ -281,19 +299,18 @@ __global__ void __launch_bounds__(256) bwd_bf16_wide_kernel(BwdArgs p, uint32_t 
     }
 }
 
-template <int NB, int D, bool BM, bool DB>
-hipError_t launch_wide_one(const BwdArgs& a, unsigned G, size_t lds, hipStream_t st) {
-    {
-        const hipError_t e = allow_lds(reinterpret_cast<const void*>(&bwd_bf16_wide_kernel<NB, D, BM, DB>), lds);
-        if (e != hipSuccess) return e;
-    }
-    hipLaunchKernelGGL((bwd_bf16_wide_kernel<NB, D, BM, DB>), dim3(G * (unsigned)a.heads), dim3(256), lds, st, a, G);
+template <int NB, int D, bool BM, bool DB, bool F16>
+hipError_t launch_wide_one(const BwdArgs& a, unsigned G, hipStream_t st) {
+    // K, V (then Q, dO) slabs; the P / dS tiles (two for half data, four hi / lo tiles for bf16); output cells
+    const size_t lds = (size_t)2 * 16 * NB * (D / 8 + 1) * 16 + (size_t)(F16 ? 2 : 4) * 16 * NB * 64 * 2 + (size_t)4 * 16 * 144;
+    const hipError_t e = allow_lds(reinterpret_cast<const void*>(&bwd_bf16_wide_kernel<NB, D, BM, DB, F16>), lds);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL((bwd_bf16_wide_kernel<NB, D, BM, DB, F16>), dim3(G * (unsigned)a.heads), dim3(256), lds, st, a, G);
     return hipGetLastError();
 }
 
-template <int NB, int D>
+template <int NB, int D, bool F16>
 hipError_t launch_wide_nb(const BwdArgs& a, hipStream_t st) {
-    const size_t lds = (size_t)2 * 16 * NB * (D / 8 + 1) * 16 + (size_t)4 * 16 * NB * 64 * 2 + (size_t)4 * 16 * 144;
     const bool bm = a.bias || has_mask(a);
     if (a.dbias == nullptr) {
         // Width 256 (100 KB of LDS: one workgroup per CU): as many window positions as workgroups stay
@@ -302,22 +319,22 @@ hipError_t launch_wide_nb(const BwdArgs& a, hipStream_t st) {
         long long G0 = a.N;
         const long long per_head = cu_count() / a.heads;
         if (D == 256 && a.N > per_head) G0 = per_head > 0 ? per_head : 1;
-        return bm ? launch_wide_one<NB, D, true, false>(a, (unsigned)G0, lds, st)
-                  : launch_wide_one<NB, D, false, false>(a, (unsigned)G0, lds, st);
+        return bm ? launch_wide_one<NB, D, true, false, F16>(a, (unsigned)G0, st)
+                  : launch_wide_one<NB, D, false, false, F16>(a, (unsigned)G0, st);
     }
     const unsigned G = (unsigned)a.slots;
-    const hipError_t e = bm ? launch_wide_one<NB, D, true, true>(a, G, lds, st)
-                            : launch_wide_one<NB, D, false, true>(a, G, lds, st);
+    const hipError_t e = bm ? launch_wide_one<NB, D, true, true, F16>(a, G, st)
+                            : launch_wide_one<NB, D, false, true, F16>(a, G, st);
     return e != hipSuccess ? e : launch_dbias_reduce(a, st);
 }
 
 template <int D>
 hipError_t launch_wide_d(const BwdArgs& a, hipStream_t s) {
     switch ((a.L + 15) / 16) {
-        case 1: return launch_wide_nb<1, D>(a, s);
-        case 2: return launch_wide_nb<2, D>(a, s);
-        case 3: return launch_wide_nb<3, D>(a, s);
-        case 4: return launch_wide_nb<4, D>(a, s);
+        case 1: return a.f16 ? launch_wide_nb<1, D, true>(a, s) : launch_wide_nb<1, D, false>(a, s);
+        case 2: return a.f16 ? launch_wide_nb<2, D, true>(a, s) : launch_wide_nb<2, D, false>(a, s);
+        case 3: return a.f16 ? launch_wide_nb<3, D, true>(a, s) : launch_wide_nb<3, D, false>(a, s);
+        case 4: return a.f16 ? launch_wide_nb<4, D, true>(a, s) : launch_wide_nb<4, D, false>(a, s);
         default: return hipErrorInvalidValue;
     }
 }

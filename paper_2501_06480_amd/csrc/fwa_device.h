@@ -38,6 +38,28 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(t, bf16x2));
 }
 
+// The 16-bit operand types share one carrier: kernels that take bf16 or IEEE half data (template flag F16)
+// keep their operands in the bf16 vector types as raw bits and pick the matrix instruction and the
+// conversion here.  Half products have 11 significant bits in each operand, bf16 products 8.
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+template <bool F16>
+__device__ __forceinline__ f32x4 mfma_e(bf16x8 a, bf16x8 b, f32x4 c) {
+    if constexpr (F16)
+        return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+    else
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+}
+// two fp32 -> a packed pair of the 16-bit type (lo = a, hi = b), round to nearest even
+template <bool F16>
+__device__ __forceinline__ uint32_t pack_e(float a, float b) {
+    f32x2 t = {a, b};
+    if constexpr (F16)
+        return __builtin_bit_cast(uint32_t, __builtin_convertvector(t, f16x2));
+    else
+        return __builtin_bit_cast(uint32_t, __builtin_convertvector(t, bf16x2));
+}
+
 __device__ __forceinline__ bf16x8 as_bf16x8(uint4 u) { return __builtin_bit_cast(bf16x8, u); }
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 u) { return __builtin_bit_cast(bf16x8, u); }
 

@@ -17,7 +17,9 @@
 namespace fwa {
 namespace {
 
-template <int NB, int D, bool BM>
+// F16: the data are IEEE half instead of bf16 (the precision the paper's Section 3.3 comparison runs in);
+// same bytes, same layouts, the other matrix instruction and conversion.
+template <int NB, int D, bool BM, bool F16>
 __global__ void __launch_bounds__(256) fwd_bf16_wide_kernel(FwdArgs p) {
     constexpr int NB2 = (NB + 1) / 2;
     constexpr int ROWS = 16 * NB;
@@ -84,7 +86,7 @@ __global__ void __launch_bounds__(256) fwd_bf16_wide_kernel(FwdArgs p) {
         for (int c = 0; c < CH; ++c)
 #pragma unroll
             for (int jb = 0; jb < NB; ++jb)
-                s[jb] = mfma_bf16(__builtin_bit_cast(bf16x8, lkh[16 * jb * STRIDE + 4 * c]), qop[c], s[jb]);
+                s[jb] = mfma_e<F16>(__builtin_bit_cast(bf16x8, lkh[16 * jb * STRIDE + 4 * c]), qop[c], s[jb]);
     }
     __syncthreads();  // every wave has read its K operands
     park();
@@ -104,7 +106,7 @@ __global__ void __launch_bounds__(256) fwd_bf16_wide_kernel(FwdArgs p) {
     if (!active) return;  // no barrier follows
     bf16x8 pop[NB2];
 #pragma unroll
-    for (int kp = 0; kp < NB2; ++kp) pop[kp] = prob_operand<NB>(s, kp);
+    for (int kp = 0; kp < NB2; ++kp) pop[kp] = prob_operand<NB, F16>(s, kp);
 
     // O^T = V^T P^T, 16 channels at a time: o[r] = O[16 qb + n][16 cb + 4g + r]
     const uint16_t* const lvh = reinterpret_cast<const uint16_t*>(lds) + (4 * g + (n >> 2)) * SROW + 4 * (n & 3);
@@ -117,8 +119,8 @@ __global__ void __launch_bounds__(256) fwd_bf16_wide_kernel(FwdArgs p) {
         f32x4 o = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int kp = 0; kp < NB2; ++kp)
-            o = mfma_bf16(operand_tr(lvh + (32 * kp) * SROW + 16 * cb, 16 * SROW, 2 * kp + 1 < NB), pop[kp], o);
-        const u32x2 v = {pack_bf16(o[0] * inv, o[1] * inv), pack_bf16(o[2] * inv, o[3] * inv)};
+            o = mfma_e<F16>(operand_tr(lvh + (32 * kp) * SROW + 16 * cb, 16 * SROW, 2 * kp + 1 < NB), pop[kp], o);
+        const u32x2 v = {pack_e<F16>(o[0] * inv, o[1] * inv), pack_e<F16>(o[2] * inv, o[3] * inv)};
         // Four channel blocks (64 channels, a 128-byte line per row) are gathered in LDS cells of this wave's
         // own -- rows 144 bytes apart -- and leave as two 16-byte-per-lane stores of 8 whole lines each,
         // instead of four stores of 32-byte pieces.
@@ -138,22 +140,21 @@ __global__ void __launch_bounds__(256) fwd_bf16_wide_kernel(FwdArgs p) {
     }
 }
 
-template <int NB, int D>
-hipError_t launch_wide_nb(const FwdArgs& a, hipStream_t st) {
+template <int NB, int D, bool BM, bool F16>
+hipError_t launch_wide_one(const FwdArgs& a, hipStream_t st) {
     const unsigned grid = (unsigned)(a.N * a.heads);
     const size_t lds = (size_t)16 * NB * (D / 8 + 1) * 16 + (size_t)4 * 16 * 144;  // one slab (K, then V); output cells of the waves
-    const bool bm = a.bias || has_mask(a);
-    const void* fn = bm ? reinterpret_cast<const void*>(&fwd_bf16_wide_kernel<NB, D, true>)
-                        : reinterpret_cast<const void*>(&fwd_bf16_wide_kernel<NB, D, false>);
-    {
-        const hipError_t e = allow_lds(fn, lds);
-        if (e != hipSuccess) return e;
-    }
-    if (bm)
-        hipLaunchKernelGGL((fwd_bf16_wide_kernel<NB, D, true>), dim3(grid), dim3(256), lds, st, a);
-    else
-        hipLaunchKernelGGL((fwd_bf16_wide_kernel<NB, D, false>), dim3(grid), dim3(256), lds, st, a);
+    const hipError_t e = allow_lds(reinterpret_cast<const void*>(&fwd_bf16_wide_kernel<NB, D, BM, F16>), lds);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL((fwd_bf16_wide_kernel<NB, D, BM, F16>), dim3(grid), dim3(256), lds, st, a);
     return hipGetLastError();
+}
+
+template <int NB, int D>
+hipError_t launch_wide_nb(const FwdArgs& a, hipStream_t st) {
+    const bool bm = a.bias || has_mask(a);
+    if (a.f16) return bm ? launch_wide_one<NB, D, true, true>(a, st) : launch_wide_one<NB, D, false, true>(a, st);
+    return bm ? launch_wide_one<NB, D, true, false>(a, st) : launch_wide_one<NB, D, false, false>(a, st);
 }
 
 template <int D>

@@ -34,6 +34,7 @@ struct FwdArgs {
     float scale;
     int ldq;             // elements between consecutive token rows of q, k, v (C when contiguous)
     int ldo;             // the same for o
+    int f16;             // the 16-bit data are IEEE half, not bf16 (wide-head kernels only)
 };
 
 struct BwdArgs {
@@ -64,6 +65,7 @@ struct BwdArgs {
     int ldq;             // elements between consecutive token rows of q, k, v (C when contiguous)
     int ldg;             // the same for d_o
     int ldd;             // the same for dq, dk, dv
+    int f16;             // the 16-bit data are IEEE half, not bf16 (wide-head kernels only)
 };
 
 // Whether the scores get a mask, in either form, and its period over the windows (1 without one).

@@ -357,16 +357,16 @@ __device__ __forceinline__ void softmax_exp_pair(f32x4 (&s)[NB], int kp, float m
     }
 }
 
-// The probabilities of key blocks 2 kp and 2 kp + 1 of a lane as one bf16 operand
+// The probabilities of key blocks 2 kp and 2 kp + 1 of a lane as one 16-bit operand (bf16, or half with F16)
 // (k-slots 0..3 = keys 4g..4g+3 of the first block, 4..7 = the same keys of the second).
-template <int NB>
+template <int NB, bool F16 = false>
 __device__ __forceinline__ bf16x8 prob_operand(const f32x4 (&s)[NB], int kp) {
     u32x4 a;
-    a.x = pack_bf16(s[2 * kp][0], s[2 * kp][1]);
-    a.y = pack_bf16(s[2 * kp][2], s[2 * kp][3]);
+    a.x = pack_e<F16>(s[2 * kp][0], s[2 * kp][1]);
+    a.y = pack_e<F16>(s[2 * kp][2], s[2 * kp][3]);
     const int j1 = 2 * kp + 1 < NB ? 2 * kp + 1 : 0;  // odd NB: the last pair has no second block
-    a.z = 2 * kp + 1 < NB ? pack_bf16(s[j1][0], s[j1][1]) : 0u;
-    a.w = 2 * kp + 1 < NB ? pack_bf16(s[j1][2], s[j1][3]) : 0u;
+    a.z = 2 * kp + 1 < NB ? pack_e<F16>(s[j1][0], s[j1][1]) : 0u;
+    a.w = 2 * kp + 1 < NB ? pack_e<F16>(s[j1][2], s[j1][3]) : 0u;
     return as_bf16x8(a);
 }
 

@@ -96,7 +96,7 @@ class Workload:
     L: int
     C: int
     heads: int
-    dtype: str                      # "f32" or "bf16"
+    dtype: str                      # "f32", "bf16" or "f16"
     seed: int
     k: int                          # window side, L == k*k
     map_hw: int = 0                 # token-map side (H == W); 0 = not tied to a map
@@ -135,6 +135,8 @@ def draw(w: Workload):
         if w.dtype == "bf16":
             x, bits = bf16_round(x)
             out[nm + "_bits"] = bits
+        elif w.dtype == "f16":
+            x = x.astype(np.float16).astype(np.float32)   # rounded once to IEEE half, nearest even
         out[nm] = x
     out["table"] = bias_table(w.heads, w.k, w.seed * 16 + 8) if w.use_bias else None
     out["mask"] = shift_mask(w.map_hw, w.map_hw, w.k, w.shift) if w.shift else None

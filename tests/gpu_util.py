@@ -2,7 +2,7 @@
 import numpy as np
 
 # Tolerances of the benchmark spec: max-abs error against the fp64 oracle.
-TOL = {"f32": 1e-5, "bf16": 1e-2}
+TOL = {"f32": 1e-5, "bf16": 1e-2, "f16": 1e-2}
 
 
 def to_device(x, w, name):
@@ -10,6 +10,8 @@ def to_device(x, w, name):
     import torch
     if w.dtype == "bf16":
         return torch.from_numpy(x[name + "_bits"].view(np.int16)).view(torch.bfloat16).cuda()
+    if w.dtype == "f16":  # the drawn values are already rounded to half: the cast is exact
+        return torch.from_numpy(x[name]).cuda().half()
     return torch.from_numpy(x[name]).cuda()
 
 

@@ -68,7 +68,8 @@ def test_forward_rejects_bad_arguments(lib):
     assert fwd(lib, C=192, heads=3, dtype=0, L=65) == b.FWA_ERR_UNSUPPORTED   # head dim 64 beyond one tile, fp32
     assert fwd(lib, C=192, heads=3, L=65) == b.FWA_ERR_UNSUPPORTED      # head dim 64 beyond one tile
     assert fwd(lib, L=257) == b.FWA_ERR_UNSUPPORTED
-    assert fwd(lib, dtype=2) == b.FWA_ERR_UNSUPPORTED
+    assert fwd(lib, dtype=2) == b.FWA_ERR_UNSUPPORTED            # half data at head width 32
+    assert fwd(lib, dtype=3) == b.FWA_ERR_UNSUPPORTED
     assert fwd(lib, mask=P + 0x9000000, nW=0) == b.FWA_ERR_SHAPE
     assert fwd(lib, mask=P + 0x9000000, nW=3) == b.FWA_ERR_SHAPE     # 4 % 3 != 0
     assert fwd(lib, q=None) == b.FWA_ERR_NULL
