@@ -54,15 +54,20 @@ def check_bf16_output(got, want, what):
 
 
 def check_forward_arithmetic_bound(got, want, spread, what):
-    """Element-wise bound of the bf16 forward derived from its arithmetic, for shapes where the flat
-    1e-2 of the benchmark workloads need not hold (few keys per row and |V| up to 4-5): the output
-    is rounded once (half a bf16 ulp of the result) and the un-normalised probabilities enter the
-    matrix core rounded to bf16 (unit roundoff 2^-8; the largest one, exp(0) = 1, exactly), so the
-    error of an element is at most half_ulp(|o|) + 2^-8 * sum_j p_ij |v_j| plus fp32 rounding noise.
-    `spread` is that sum: the oracle's forward on |V|."""
+    """The bf16 forward on shapes where the flat 1e-2 of the benchmark workloads cannot hold for every
+    element (few keys per row and |V| up to 4-5).  Every element is held to the flat 1e-2 unless the
+    bound derived from the arithmetic is larger for THAT element, and then to that bound: the output is
+    rounded once (half a bf16 ulp of the result) and the un-normalised probabilities enter the matrix
+    core rounded to bf16 (unit roundoff 2^-8; the largest one, exp(0) = 1, exactly), so the error of an
+    element is at most half_ulp(|o|) + 2^-8 * sum_j p_ij |v_j| plus fp32 rounding noise.  `spread` is
+    that sum: the oracle's forward on |V|.  Prints how many elements needed more than the flat figure."""
     err = np.abs(got - want)
     half_ulp = 2.0 ** (np.floor(np.log2(np.maximum(np.maximum(np.abs(want), np.abs(got)), 2.0 ** -20))) - 8)
-    bound = half_ulp + 2.0 ** -8 * spread + 1e-4
+    bound = np.maximum(half_ulp + 2.0 ** -8 * spread + 1e-4, TOL["bf16"])
     worst = float((err - bound).max())
     assert worst <= 0.0, (what, worst, float(err.max()))
+    beyond = int((err > TOL["bf16"]).sum())
+    if beyond:
+        print(f"{what}: {beyond} of {err.size} elements beyond the flat 1e-2 (max {err.max():.3e}), "
+              f"each within its own arithmetic bound", flush=True)
     return float(err.max())

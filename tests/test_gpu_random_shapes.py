@@ -138,8 +138,7 @@ def test_random_combination(oracle, c):
         a = to_f64(db)
         assert np.isfinite(a).all()
         errs["dbias"] = max_abs(a, ref[3])
-        # a sum over N windows of terms each good to the bf16 bound of the operands: relative to its size
-        assert errs["dbias"] <= TOL["bf16"] * max(1.0, np.abs(ref[3]).max() / 4.0), ("dbias", errs["dbias"])
+        assert errs["dbias"] <= TOL["bf16"], ("dbias", errs["dbias"], float(np.abs(ref[3]).max()))
     else:
         assert db is None
     print("  backward " + " ".join(f"{n}={e:.2e}" for n, e in errs.items()), flush=True)
