@@ -75,7 +75,9 @@ int check_shape(int64_t N, int L, int C, int heads, int dtype, bool wide_ok) {
     // half data: the wide-head kernels only (head widths 64, 128, 256 at L <= 64)
     if (dtype == FWA_F16 && C / heads == fwa::kHeadDim) return FWA_ERR_UNSUPPORTED;
     if (L > fwa::kMaxL) return FWA_ERR_UNSUPPORTED;
-    // one launch: the number of wave tasks (at most 4 per window-head) must fit a 32-bit grid
+    // one launch: the number of wave tasks (at most 4 per window-head) must fit a 32-bit grid.  The other grids
+    // are bounded through the row stride: C <= 2^20 elements (check_row_stride) means at most 2^15 heads of
+    // width 32, so the dBias reduction's heads * 16 * 16 * 4 workgroups stay below 2^25.
     if ((double)N * heads * 4.0 > 2.0e9) return FWA_ERR_UNSUPPORTED;
     return FWA_OK;
 }
