@@ -214,6 +214,16 @@ __device__ __forceinline__ bf16x4 identity_operand(int g, int n) {
     return as_bf16x4(u);
 }
 
+// A operand of the K=32 matrix op that is all ones: times the probability operand of a pair of key blocks it
+// returns, in every component of every lane (g, n), the sum over the pair's 32 keys of the (rounded)
+// probabilities of query n.  Accumulated over the pairs this is the row sum the output is divided by -- the sum of
+// the very weights the output was formed with -- at the price of one matrix instruction per pair instead of one
+// addition per score and the reduction over the four lanes of a row.
+__device__ __forceinline__ bf16x8 ones_operand() {
+    const u32x4 s = {0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u};
+    return as_bf16x8(s);
+}
+
 // B operand of the K=32 matrix op that picks every second channel: slot e of lane (g, n)
 // stands for channel 8g + e; the product rows x selector puts channel 2n + parity of each
 // row into column n, i.e. returns lane (g', n') <- X[row 4g' + r][channel 2n' + parity].

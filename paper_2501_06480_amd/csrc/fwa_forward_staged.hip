@@ -411,7 +411,7 @@ __global__ void __launch_bounds__(64 * 2 * QW) fwd_bf16_rowblock_kernel(FwdArgs 
         const AddendGlobal addend = addend_at(rb, msk, (uint32_t)(16 * qb + n), 4u * g, (uint32_t)L);
         float mul, sum = 0.f;
         const float mb = softmax_scale_max<NB, BM>(s, sl2, addend, L, g, mul);
-        f32x4 o0 = {0.f, 0.f, 0.f, 0.f}, o1 = {0.f, 0.f, 0.f, 0.f};
+        f32x4 o0 = {0.f, 0.f, 0.f, 0.f}, o1 = {0.f, 0.f, 0.f, 0.f}, osum = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int kp = 0; kp < NB2; ++kp) {
             // the V operands of this pair of key blocks are requested before its exponentials
@@ -423,12 +423,13 @@ __global__ void __launch_bounds__(64 * 2 * QW) fwd_bf16_rowblock_kernel(FwdArgs 
                 if (2 * kp + 1 < NB) b = lds_read_tr(lvh + (32 * kp + 16) * (stride * 8u) + 16 * c);
                 v[c] = u32x4{a.x, a.y, b.x, b.y};
             }
-            softmax_exp_pair<NB>(s, kp, mul, mb, sum);
+            softmax_exp_pair<NB, false>(s, kp, mul, mb, sum);
             const bf16x8 pop = prob_operand<NB>(s, kp);
             o0 = mfma_bf16(as_bf16x8(v[0]), pop, o0);  // o0[r] = O[16 qb + n][4g + r]
             o1 = mfma_bf16(as_bf16x8(v[1]), pop, o1);  // o1[r] = O[16 qb + n][16 + 4g + r]
+            osum = mfma_bf16(ones_operand(), pop, osum);  // every component: the row sum of query 16 qb + n
         }
-        const float inv = __builtin_amdgcn_rcpf(sum_over_g(sum));
+        const float inv = __builtin_amdgcn_rcpf(osum[0]);
         typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
         u32x2 lo, hi;
         lo.x = pack_bf16(o0[0] * inv, o0[1] * inv);
@@ -581,7 +582,7 @@ __global__ void __launch_bounds__(64 * HPB * rowpersist_waves(NB)) fwd_bf16_rowp
                 const AddendRegs<NB> addend = {add};
                 mb = softmax_scale_max<NB, true>(s, sl2, addend, L, g, mul);
             }
-            f32x4 o0 = {0.f, 0.f, 0.f, 0.f}, o1 = {0.f, 0.f, 0.f, 0.f};
+            f32x4 o0 = {0.f, 0.f, 0.f, 0.f}, o1 = {0.f, 0.f, 0.f, 0.f}, osum = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int kp = 0; kp < NB2; ++kp) {
                 // the V operands of this pair of key blocks are requested before its exponentials
@@ -593,12 +594,13 @@ __global__ void __launch_bounds__(64 * HPB * rowpersist_waves(NB)) fwd_bf16_rowp
                     if (2 * kp + 1 < NB) b = lds_read_tr(lvh + (32 * kp + 16) * (STRIDE * 8u) + 16 * c);
                     v[c] = u32x4{a.x, a.y, b.x, b.y};
                 }
-                softmax_exp_pair<NB>(s, kp, mul, mb, sum);
+                softmax_exp_pair<NB, false>(s, kp, mul, mb, sum);
                 const bf16x8 pop = prob_operand<NB>(s, kp);
                 o0 = mfma_bf16(as_bf16x8(v[0]), pop, o0);  // o0[r] = O[16 qb + n][4g + r]
                 o1 = mfma_bf16(as_bf16x8(v[1]), pop, o1);  // o1[r] = O[16 qb + n][16 + 4g + r]
+                osum = mfma_bf16(ones_operand(), pop, osum);  // every component: the row sum of query 16 qb + n
             }
-            const float inv = __builtin_amdgcn_rcpf(sum_over_g(sum));
+            const float inv = __builtin_amdgcn_rcpf(osum[0]);
             typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
             u32x2 lo, hi;
             lo.x = pack_bf16(o0[0] * inv, o0[1] * inv);
@@ -635,14 +637,39 @@ __global__ void __launch_bounds__(64 * HPB * rowpersist_waves(NB)) fwd_bf16_rowp
     }
 }
 
-// Window positions walked in parallel by the persistent row-blocked kernel (about one
-// workgroup per CU, a multiple of the mask period, at least two windows per workgroup);
-// 0 = use the plain row-blocked kernel.
+// LDS of one workgroup of the persistent row-blocked kernel: slabs, labels, and (one head per workgroup) 1 KB per
+// wave for the output rows
+template <int NB, int HPB>
+constexpr size_t rowpersist_lds() {
+    return (size_t)2 * 2 * 16 * NB * (4 * HPB + 1) * 16 + (size_t)2 * 16 * NB * 4 +
+           (HPB == 1 ? (size_t)rowpersist_waves(NB) * 1024 : 0);
+}
+
+// Workgroups of the one-head variant a CU holds at once (registers and LDS decide), asked once per kernel.
+template <int NB, bool PW>
+int rowpersist_per_cu() {
+    static std::atomic<int> once{0};
+    int per_cu = once.load(std::memory_order_relaxed);
+    if (per_cu == 0) {
+        const void* fn = reinterpret_cast<const void*>(&fwd_bf16_rowpersist_kernel<NB, 1, PW>);
+        int nblk = 0;
+        if (allow_lds(fn, rowpersist_lds<NB, 1>()) != hipSuccess ||
+            hipOccupancyMaxActiveBlocksPerMultiprocessor(&nblk, fn, 64 * rowpersist_waves(NB), rowpersist_lds<NB, 1>()) != hipSuccess)
+            nblk = 1;
+        per_cu = nblk < 1 ? 1 : (nblk > 2 ? 2 : nblk);  // a third one measured no faster
+        once.store(per_cu, std::memory_order_relaxed);
+    }
+    return per_cu;
+}
+
+// Window positions walked in parallel by the persistent row-blocked kernel (as many workgroups as
+// the chip holds at once, two per CU at most: 3-9 % over one per CU where two fit, L <= 128; a
+// multiple of the mask period, at least two windows per workgroup); 0 = use the plain row-blocked kernel.
 template <int NB>
 long long rowpersist_slots(const FwdArgs& a, bool& pw) {
     const long long parts = NB <= 12 ? 1 : 2;
     const long long nW = mask_period(a);
-    const long long most = cu_count() / ((long long)a.heads * parts);
+    long long most = (long long)cu_count() * rowpersist_per_cu<NB, false>() / ((long long)a.heads * parts);
     long long G = most / nW * nW;
     if (G > a.N / 2) G = (a.N / 2) / nW * nW;
     pw = false;
@@ -651,6 +678,7 @@ long long rowpersist_slots(const FwdArgs& a, bool& pw) {
     // all the same and form the mask of each window from its labels
     if (a.labels == nullptr) return 0;
     pw = true;
+    most = (long long)cu_count() * rowpersist_per_cu<NB, true>() / ((long long)a.heads * parts);
     G = most < a.N / 2 ? most : a.N / 2;
     return G > 0 ? G : 0;
 }
@@ -664,8 +692,7 @@ hipError_t launch_rowpersist_pw(const FwdArgs& a, long long G, hipStream_t st) {
     const unsigned grid = gm.G * gm.groups * gm.parts, block = 64u * (unsigned)(HPB * rowpersist_waves(NB));
     gm.xcd_q = grid / 8u;
     gm.xcd_r = grid % 8u;
-    // slabs, labels, and (one head per workgroup) 1 KB per wave for the output rows
-    const size_t lds = (size_t)2 * 2 * 16 * NB * (4 * HPB + 1) * 16 + (size_t)2 * 16 * NB * 4 + (HPB == 1 ? (size_t)(block / 64) * 1024 : 0);
+    const size_t lds = rowpersist_lds<NB, HPB>();
     {
         const hipError_t e = allow_lds(reinterpret_cast<const void*>(&fwd_bf16_rowpersist_kernel<NB, HPB, PW>), lds);
         if (e != hipSuccess) return e;

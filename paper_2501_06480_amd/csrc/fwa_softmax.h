@@ -341,8 +341,9 @@ __device__ __forceinline__ float softmax_scale_max(f32x4 (&s)[NB], float sl2, co
     return m * mul;
 }
 
-// exponentials of key blocks 2 kp and 2 kp + 1, added to the lane's partial row sum
-template <int NB>
+// exponentials of key blocks 2 kp and 2 kp + 1, added to the lane's partial row sum (SUM = false: not
+// added; the caller takes the row sum from the matrix core, see ones_operand)
+template <int NB, bool SUM = true>
 __device__ __forceinline__ void softmax_exp_pair(f32x4 (&s)[NB], int kp, float mul, float mb, float& sum) {
 #pragma unroll
     for (int b = 0; b < 2; ++b) {
@@ -352,7 +353,7 @@ __device__ __forceinline__ void softmax_exp_pair(f32x4 (&s)[NB], int kp, float m
         for (int r = 0; r < 4; ++r) {
             const float e = __builtin_amdgcn_exp2f(fmaf(s[jb][r], mul, -mb));
             s[jb][r] = e;
-            sum += e;
+            if (SUM) sum += e;
         }
     }
 }
