@@ -21,7 +21,8 @@
  *    [N, L, C]; head h owns channels [h*d, (h+1)*d) with d = C / heads.
  *    Supported: d == 32 with 1 <= L <= 256; d == 64, 128, 256 with
  *    1 <= L <= 64 (the feature-dimension loop of paper eq. 5-6; the shapes of
- *    its Section 3.1 benchmark), in both dtypes.  N >= 0 (N == 0 is a no-op).
+ *    its Section 3.1 benchmark), in fp32 and bf16 (half: the wider heads only,
+ *    see dtype).  N >= 0 (N == 0 is a no-op).
  *  - dtype is FWA_F32 (fp32 data, fp32 arithmetic), FWA_BF16 (bf16 data,
  *    bf16 matrix-core products with fp32 accumulation, fp32 softmax, one final
  *    round-to-nearest-even to bf16) or FWA_F16 (IEEE half data, handled like
