@@ -499,16 +499,22 @@ __global__ void __launch_bounds__(64 * HPB * rowpersist_waves(NB)) fwd_bf16_rowp
     const uint32_t srow = (uint32_t)tid / TPR, scol = (uint32_t)tid % TPR;  // slab movement: thread -> (row, 16 B column)
     const uint32_t tile_bytes = (uint32_t)(L - 1) * row_bytes + 2u * kHeadDim * HPB;
     const uint32_t off_row = (uint32_t)(16 * qb + n) * row_bytes + 64u * hl + 16u * g;
-    // Two register sets of slab data: while window w is computed out of LDS, the slabs of w + step
-    // sit in one set (requested an iteration ago, parked at the end of this one) and those of
-    // w + 2 step are requested into the other, so that two windows are in flight per workgroup.
+    // Register sets of slab data: while window w is computed out of LDS, the slabs of w + step
+    // sit in one set (requested earlier, parked at the end of this iteration) and those of
+    // w + 2 step are requested into the other, so that two windows are in flight per workgroup
+    // (with a third set: w + 2 step is in flight already and w + 3 step is requested).
     struct Slab {
         u32x4 k[PASSES], v[PASSES], q;
         i32x4 lab;  // PW: labels 4 tid .. 4 tid + 3 of the window
     };
-    Slab sa, sb;
-    sa.q = sb.q = u32x4{0u, 0u, 0u, 0u};
-    sa.lab = sb.lab = i32x4{0, 0, 0, 0};
+    // three windows ahead at NB > 12, whose 8 waves per workgroup may use 256 registers per lane (a third set of
+    // slab registers; 3-4 % at L = 196 and 256).  At 64 < L <= 192 the set would cost the second workgroup per
+    // CU or spill, and with several heads per workgroup (L <= 64) it measured no gain.
+    constexpr bool D3 = HPB == 1 && NB > 12;
+    constexpr uint32_t AHEAD = D3 ? 3u : 2u;
+    Slab sa, sb, sc;
+    sa.q = sb.q = sc.q = u32x4{0u, 0u, 0u, 0u};
+    sa.lab = sb.lab = sc.lab = i32x4{0, 0, 0, 0};
     auto request = [&](Slab& d, uint32_t w) {
         const size_t tile = ((size_t)w * L * p.ldq + (size_t)grp * HPB * kHeadDim) * 2u;
         const __amdgpu_buffer_rsrc_t rk = make_rsrc((const char*)p.k + tile, tile_bytes);
@@ -541,6 +547,7 @@ __global__ void __launch_bounds__(64 * HPB * rowpersist_waves(NB)) fwd_bf16_rowp
     uint32_t w0 = bw, step = gm.G, end = (uint32_t)p.N;
     if (w0 < end) request(sa, w0);  // in flight while the additive term is fetched
     if (w0 + step < end) request(sb, w0 + step);
+    if (D3 && w0 + 2 * step < end) request(sc, w0 + 2 * step);
     f32x4 add[NB];
     {
         const BiasSrc rb = bias_of_head(p, h);
@@ -561,7 +568,7 @@ __global__ void __launch_bounds__(64 * HPB * rowpersist_waves(NB)) fwd_bf16_rowp
         uint4* const lk = lds + buf * (2 * ROWS * STRIDE);
         uint4* const lv = lk + ROWS * STRIDE;
         const bf16x8 qop = as_bf16x8(cur.q);
-        if (w + 2 * step < end) request(cur, w + 2 * step);
+        if (w + AHEAD * step < end) request(cur, w + AHEAD * step);
         __syncthreads();
         if (active) {
             const uint4* const lkh = lk + n * STRIDE + 4 * hl + g;  // K[16 jb + n][8g..] of head hl at lkh[16 jb * STRIDE]
@@ -631,9 +638,23 @@ __global__ void __launch_bounds__(64 * HPB * rowpersist_waves(NB)) fwd_bf16_rowp
         }
         if (has_next) park(nxt, buf ^ 1u);
     };
-    for (uint32_t w = w0; w < end; w += 2 * step) {
-        window(w, sa, sb, 0u);
-        if (w + step < end) window(w + step, sb, sa, 1u);
+    if (D3) {
+        uint32_t buf = 0u;
+        for (uint32_t w = w0; w < end;) {
+            window(w, sa, sb, buf);
+            w += step, buf ^= 1u;
+            if (w >= end) break;
+            window(w, sb, sc, buf);
+            w += step, buf ^= 1u;
+            if (w >= end) break;
+            window(w, sc, sa, buf);
+            w += step, buf ^= 1u;
+        }
+    } else {
+        for (uint32_t w = w0; w < end; w += 2 * step) {
+            window(w, sa, sb, 0u);
+            if (w + step < end) window(w + step, sb, sa, 1u);
+        }
     }
 }
 
