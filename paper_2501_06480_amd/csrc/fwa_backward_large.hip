@@ -44,6 +44,10 @@ struct LargeGeom {
 };
 
 constexpr int large_waves(int nb) { return nb <= 10 ? 4 : 8; }
+// Slab rows of the kernel below in 16-byte units: 64 bytes of data and no padding.  Row-operand and transposing
+// reads run at the same rate as with 16 bytes of padding (measured), and the smaller workgroup lets a CU hold a third
+// one where registers allow (pass 1 alone at L = 100: 294 -> 261 us with dBias).
+constexpr uint32_t kLargeStride = 4;
 __device__ __forceinline__ bf16x8 pair_operand(bf16x4 a, bf16x4 b) {
     const uint2 ua = __builtin_bit_cast(uint2, a), ub = __builtin_bit_cast(uint2, b);
     return as_bf16x8(u32x4{ua.x, ua.y, ub.x, ub.y});
@@ -61,7 +65,7 @@ __global__ void __launch_bounds__(64 * large_waves(NB)) bwd_bf16_large_kernel(Bw
     constexpr int NB2 = (NB + 1) / 2;
     constexpr int ROWS = 16 * NB;
     constexpr int PASSES = (ROWS + 16 * W - 1) / (16 * W);  // the workgroup moves 16 W slab rows per pass
-    constexpr uint32_t STRIDE = 5;                           // slab row: 64 bytes of data + 16 of padding
+    constexpr uint32_t STRIDE = kLargeStride;                // slab row in 16-byte units
     constexpr uint32_t SROW = STRIDE * 8;                    // the same in bf16 elements
     constexpr uint32_t SG = 68;                              // patch row: 64 floats + 4 of padding
     extern __shared__ __attribute__((aligned(16))) uint4 lds[];
@@ -730,7 +734,7 @@ hipError_t launch_large_one(const BwdArgs& a, hipStream_t st) {
     constexpr int W = large_waves(NB);
     const void* fn = reinterpret_cast<const void*>(&bwd_bf16_large_kernel<NB, HB, HM, P2>);
     const unsigned block = 64u * W;
-    const size_t lds = (size_t)4 * 16 * NB * 5 * 16 + (size_t)2 * 16 * NB * 4 + (size_t)W * 16 * 68 * 4;  // slabs, statistics, one patch per wave
+    const size_t lds = (size_t)4 * 16 * NB * kLargeStride * 16 + (size_t)2 * 16 * NB * 4 + (size_t)W * 16 * 68 * 4;  // slabs, statistics, one patch per wave
     static std::atomic<int> once{0};
     int per_cu = 1;
     const hipError_t e = workgroups_per_cu(fn, block, lds, once, per_cu);
