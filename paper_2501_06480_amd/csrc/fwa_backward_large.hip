@@ -118,36 +118,52 @@ __global__ void __launch_bounds__(64 * large_waves(NB)) bwd_bf16_large_kernel(Bw
     };
     typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
-    for (uint32_t w = bw; w < (uint32_t)p.N; w += gm.G) {
+    // The slabs of the next window are requested into registers by every wave right before its last stores of the
+    // current one -- the big temporaries of the passes are dead by then --, so that their way through memory
+    // overlaps with those stores and with the wait for the slowest wave; they are parked between the two barriers
+    // that separate the windows.
+    u32x4 pk[PASSES], pv[PASSES], pq[PASSES], pg[PASSES];
+    auto request = [&](uint32_t w) {
         const size_t tile = ((size_t)w * L * p.ldq + (size_t)h * kHeadDim) * 2u;
         const size_t tile_g = ((size_t)w * L * p.ldg + (size_t)h * kHeadDim) * 2u;
-        const size_t tile_d = ((size_t)w * L * p.ldd + (size_t)h * kHeadDim) * 2u;
-        {
-            const __amdgpu_buffer_rsrc_t rk = make_rsrc((const char*)p.k + tile, tile_bytes);
-            const __amdgpu_buffer_rsrc_t rv = make_rsrc((const char*)p.v + tile, tile_bytes);
-            const __amdgpu_buffer_rsrc_t rq = make_rsrc((const char*)p.q + tile, tile_bytes);
-            const __amdgpu_buffer_rsrc_t rg = make_rsrc((const char*)p.d_o + tile_g, tile_bytes_g);
-            u32x4 pk[PASSES], pv[PASSES], pq[PASSES], pg[PASSES];
+        const __amdgpu_buffer_rsrc_t rk = make_rsrc((const char*)p.k + tile, tile_bytes);
+        const __amdgpu_buffer_rsrc_t rv = make_rsrc((const char*)p.v + tile, tile_bytes);
+        const __amdgpu_buffer_rsrc_t rq = make_rsrc((const char*)p.q + tile, tile_bytes);
+        const __amdgpu_buffer_rsrc_t rg = make_rsrc((const char*)p.d_o + tile_g, tile_bytes_g);
 #pragma unroll
-            for (int t = 0; t < PASSES; ++t) {
-                const uint32_t off = (16 * W * t + srow) * row_bytes + scol * 16u;  // rows beyond L arrive as zeros
-                pk[t] = __builtin_amdgcn_raw_buffer_load_b128(rk, off, 0, 0);
-                pv[t] = __builtin_amdgcn_raw_buffer_load_b128(rv, off, 0, 0);
-                pq[t] = __builtin_amdgcn_raw_buffer_load_b128(rq, off, 0, 0);
-                pg[t] = __builtin_amdgcn_raw_buffer_load_b128(rg, (16 * W * t + srow) * row_g + scol * 16u, 0, 0);
-            }
+        for (int t = 0; t < PASSES; ++t) {
+            const uint32_t off = (16 * W * t + srow) * row_bytes + scol * 16u;  // rows beyond L arrive as zeros
+            pk[t] = __builtin_amdgcn_raw_buffer_load_b128(rk, off, 0, 0);
+            pv[t] = __builtin_amdgcn_raw_buffer_load_b128(rv, off, 0, 0);
+            pq[t] = __builtin_amdgcn_raw_buffer_load_b128(rq, off, 0, 0);
+            pg[t] = __builtin_amdgcn_raw_buffer_load_b128(rg, (16 * W * t + srow) * row_g + scol * 16u, 0, 0);
+        }
+    };
+    auto park = [&]() {
 #pragma unroll
-            for (int t = 0; t < PASSES; ++t) {
-                const uint32_t row = 16 * W * t + srow;
-                if (row < (uint32_t)ROWS) {
-                    lk[row * STRIDE + scol] = __builtin_bit_cast(uint4, pk[t]);
-                    lv[row * STRIDE + scol] = __builtin_bit_cast(uint4, pv[t]);
-                    lq[row * STRIDE + scol] = __builtin_bit_cast(uint4, pq[t]);
-                    lg[row * STRIDE + scol] = __builtin_bit_cast(uint4, pg[t]);
-                }
+        for (int t = 0; t < PASSES; ++t) {
+            const uint32_t row = 16 * W * t + srow;
+            if (row < (uint32_t)ROWS) {
+                lk[row * STRIDE + scol] = __builtin_bit_cast(uint4, pk[t]);
+                lv[row * STRIDE + scol] = __builtin_bit_cast(uint4, pv[t]);
+                lq[row * STRIDE + scol] = __builtin_bit_cast(uint4, pq[t]);
+                lg[row * STRIDE + scol] = __builtin_bit_cast(uint4, pg[t]);
             }
         }
-        __syncthreads();
+    };
+    if (bw < (uint32_t)p.N) {
+        request(bw);
+        park();
+    }
+
+    for (uint32_t w = bw; w < (uint32_t)p.N; w += gm.G) {
+        const size_t tile_d = ((size_t)w * L * p.ldd + (size_t)h * kHeadDim) * 2u;
+        const bool has_next = w + gm.G < (uint32_t)p.N;
+        __syncthreads();  // the slabs are in place
+        // dead until the request at the end of this window: said so, or the compiler carries the old values
+        // through both passes on behalf of the path on which no request happens
+#pragma unroll
+        for (int t = 0; t < PASSES; ++t) pk[t] = pv[t] = pq[t] = pg[t] = u32x4{0u, 0u, 0u, 0u};
         // the labels of the window's tokens when the mask comes as labels
         const __amdgpu_buffer_rsrc_t rl =
             HM == 2 ? make_rsrc(p.labels + (size_t)(w % (uint32_t)p.nW) * L, (uint32_t)L * 4u) : make_rsrc(nullptr, 0);
@@ -301,6 +317,7 @@ __global__ void __launch_bounds__(64 * large_waves(NB)) bwd_bf16_large_kernel(Bw
             const float qs = p.scale * inv;  // the lane's query row: dQ_i = scale / sum_i * (the products above)
             const u32x2 lo2 = {pack_bf16(q0[0] * qs, q0[1] * qs), pack_bf16(q0[2] * qs, q0[3] * qs)};
             const u32x2 hi2 = {pack_bf16(q1[0] * qs, q1[1] * qs), pack_bf16(q1[2] * qs, q1[3] * qs)};
+            if (!P2 && has_next && qb + W >= NB) request(w + gm.G);  // the wave's last block of this window
             store_rows(lo2, hi2, make_rsrc((char*)p.dq + tile_d, tile_bytes_d), qb);
         }
         __syncthreads();
@@ -424,6 +441,9 @@ __global__ void __launch_bounds__(64 * large_waves(NB)) bwd_bf16_large_kernel(Bw
                 }
                 __builtin_amdgcn_sched_barrier(0);
             }
+            // The wave's last key blocks of this window (with 8 waves it comes through here once per window;
+            // with 4, up to twice, and asks after the loop below instead).
+            if (W == 8 && has_next) request(w + gm.G);
 #pragma unroll
             for (int t = 0; t < NK; ++t) {
                 const int jb = jb0 + t * W;
@@ -441,7 +461,9 @@ __global__ void __launch_bounds__(64 * large_waves(NB)) bwd_bf16_large_kernel(Bw
             else
                 pass2(std::integral_constant<int, 1>{}, jb0);
         }
-        __syncthreads();  // the slabs are rewritten for the next window
+        if (P2 && W == 4 && has_next) request(w + gm.G);
+        if (P2) __syncthreads();  // every wave has left the slabs (without pass 2: the barrier after pass 1)
+        if (has_next) park();
     }
 }
 
