@@ -540,9 +540,9 @@ __global__ void __launch_bounds__(64 * keys_waves(NB), 2) bwd_bf16_large_keys_ke
 #pragma unroll
     for (int r = 0; r < 4; ++r) aoff[r] = ((uint32_t)(4 * g + r) * L + 16u * jb + n) * 4u;
 
-    // The Q and dO slabs, the statistics and the wave's own K and V rows of a window are requested a whole
-    // window ahead: into registers at the top of an iteration, from there into LDS at its end, between two
-    // barriers.
+    // The Q and dO slabs, the statistics and the wave's own K and V rows of the next window are requested into
+    // registers at the end of an iteration, in front of its stores, and go from there into LDS between the two
+    // barriers that separate the windows.
     constexpr int PASSES_ = PASSES;
     constexpr int SPASSES = (ROWS / 2 + 64 * W - 1) / (64 * W);
     u32x4 pq[PASSES_], pg[PASSES_], st4[SPASSES], pk, pv;
@@ -600,7 +600,7 @@ __global__ void __launch_bounds__(64 * keys_waves(NB), 2) bwd_bf16_large_keys_ke
             HM == 2 ? make_rsrc(p.labels + (size_t)(w % (uint32_t)p.nW) * L, (uint32_t)L * 4u) : make_rsrc(nullptr, 0);
         const bf16x8 kop = as_bf16x8(pk), vop = as_bf16x8(pv);
         const bool has_next = w + gm.G < (uint32_t)p.N;
-        if (has_next) request(w + gm.G);  // in flight while this window is computed
+        u32x2 va = {0u, 0u}, vb = {0u, 0u}, ka = {0u, 0u}, kb = {0u, 0u};  // the wave's 16 rows of dV and dK, packed
 
         if (active) {
             const int lkey = HM == 2 ? load_i32(rl, (uint32_t)(16 * jb + n) * 4u) : 0;
@@ -688,10 +688,16 @@ __global__ void __launch_bounds__(64 * keys_waves(NB), 2) bwd_bf16_large_keys_ke
                 k1 = mfma_bf16(tx1[tcur], SL, k1);
                 __builtin_amdgcn_sched_barrier(0);
             }
-            const u32x2 va = {pack_bf16(v0[0], v0[1]), pack_bf16(v0[2], v0[3])};
-            const u32x2 vb = {pack_bf16(v1[0], v1[1]), pack_bf16(v1[2], v1[3])};
-            const u32x2 ka = {pack_bf16(k0[0] * p.scale, k0[1] * p.scale), pack_bf16(k0[2] * p.scale, k0[3] * p.scale)};
-            const u32x2 kb = {pack_bf16(k1[0] * p.scale, k1[1] * p.scale), pack_bf16(k1[2] * p.scale, k1[3] * p.scale)};
+            va = u32x2{pack_bf16(v0[0], v0[1]), pack_bf16(v0[2], v0[3])};
+            vb = u32x2{pack_bf16(v1[0], v1[1]), pack_bf16(v1[2], v1[3])};
+            ka = u32x2{pack_bf16(k0[0] * p.scale, k0[1] * p.scale), pack_bf16(k0[2] * p.scale, k0[3] * p.scale)};
+            kb = u32x2{pack_bf16(k1[0] * p.scale, k1[1] * p.scale), pack_bf16(k1[2] * p.scale, k1[3] * p.scale)};
+        }
+        // The next window is requested here, behind the last loads of this one's additive term and in front of
+        // its stores: memory operations of a wave complete in the order issued, so a request at the top of the
+        // window would hold up every small load behind it.
+        if (has_next) request(w + gm.G);
+        if (active) {
             store_rows(va, vb, make_rsrc((char*)p.dv + tile_d, tile_bytes_d));
             store_rows(ka, kb, make_rsrc((char*)p.dk + tile_d, tile_bytes_d));
         }
