@@ -568,8 +568,8 @@ __global__ void __launch_bounds__(64 * HPB * rowpersist_waves(NB)) fwd_bf16_rowp
         uint4* const lk = lds + buf * (2 * ROWS * STRIDE);
         uint4* const lv = lk + ROWS * STRIDE;
         const bf16x8 qop = as_bf16x8(cur.q);
-        if (w + AHEAD * step < end) request(cur, w + AHEAD * step);
         __syncthreads();
+        if (w + AHEAD * step < end) request(cur, w + AHEAD * step);
         if (active) {
             const uint4* const lkh = lk + n * STRIDE + 4 * hl + g;  // K[16 jb + n][8g..] of head hl at lkh[16 jb * STRIDE]
             const uint16_t* const lvh =
