@@ -149,6 +149,8 @@ __global__ void __launch_bounds__(64 * kCoopWavesPerTile * kCoopMaxHeads) bwd_bf
         if (has_next) request(w + gm.G);  // in flight while this window is computed
 
         const size_t tile = ((size_t)w * L * p.ldd + (size_t)h * kHeadDim) * 2u;
+        typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+        u32x2 dq_lo = {0u, 0u}, dq_hi = {0u, 0u};
         // ---------------- phase A: query block `role` ----------------
         if (active) {
             const int qb = role;
@@ -222,16 +224,17 @@ __global__ void __launch_bounds__(64 * kCoopWavesPerTile * kCoopMaxHeads) bwd_bf
                 q0 = mfma_bf16(k0, dl, q0);
                 q1 = mfma_bf16(k1, dl, q1);
             }
-            typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-            const u32x2 lo2 = {pack_bf16(q0[0] * p.scale, q0[1] * p.scale), pack_bf16(q0[2] * p.scale, q0[3] * p.scale)};
-            const u32x2 hi2 = {pack_bf16(q1[0] * p.scale, q1[1] * p.scale), pack_bf16(q1[2] * p.scale, q1[3] * p.scale)};
-            const __amdgpu_buffer_rsrc_t rdq = make_rsrc((char*)p.dq + tile, tile_bytes);
-            __builtin_amdgcn_raw_buffer_store_b64(lo2, rdq, off_half + 16 * qb * row_d, 0, 0);
-            __builtin_amdgcn_raw_buffer_store_b64(hi2, rdq, off_half + 32 + 16 * qb * row_d, 0, 0);
+            dq_lo = u32x2{pack_bf16(q0[0] * p.scale, q0[1] * p.scale), pack_bf16(q0[2] * p.scale, q0[3] * p.scale)};
+            dq_hi = u32x2{pack_bf16(q1[0] * p.scale, q1[1] * p.scale), pack_bf16(q1[2] * p.scale, q1[3] * p.scale)};
         }
         __syncthreads();
         // ---------------- phase B: key block `role` ----------------
         if (active) {
+            {   // the dQ rows of phase A leave behind the barrier
+                const __amdgpu_buffer_rsrc_t rdq = make_rsrc((char*)p.dq + tile, tile_bytes);
+                __builtin_amdgcn_raw_buffer_store_b64(dq_lo, rdq, off_half + 16 * role * row_d, 0, 0);
+                __builtin_amdgcn_raw_buffer_store_b64(dq_hi, rdq, off_half + 32 + 16 * role * row_d, 0, 0);
+            }
             const int jb = role;
             f32x4 v0 = zero, v1 = zero, k0 = zero, k1 = zero;  // dV, dK [16 jb + n][4g + r] and [..][16 + 4g + r]
             const uint16_t* lg16 = reinterpret_cast<const uint16_t*>(lg) + trs;
